@@ -1,0 +1,174 @@
+"""ctypes front end of the CPU oracle (test infrastructure only).
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg import this
+package.  It compiles `ss_oracle.c` with gcc on first use (or when the source
+is newer than the library) and exposes the four calls on NumPy arrays.
+Nothing here touches the HIP library.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ss_oracle.c")
+_LIB = os.path.join(_HERE, "libss_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc; returns the library path."""
+    stale = (not os.path.exists(_LIB)
+             or os.path.getmtime(_LIB) < os.path.getmtime(_SRC))
+    if force or stale:
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.run(
+            ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-ffp-contract=off",
+             "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"],
+            check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        for name in ("oracle_embbag_forward", "oracle_embbag_backward_update",
+                     "oracle_detect_stale", "oracle_filter_batch"):
+            getattr(_lib, name).restype = C.c_int
+    return _lib
+
+
+def _ptr_array(arrays: Optional[Sequence[Optional[np.ndarray]]], n: int):
+    """void*[n] holding the data pointers of `arrays` (None -> NULL)."""
+    arr = (C.c_void_p * n)()
+    if arrays is not None:
+        assert len(arrays) == n
+        for i, a in enumerate(arrays):
+            arr[i] = None if a is None else a.ctypes.data
+    return arr
+
+
+def _check(a: np.ndarray, dtype, name: str):
+    if a.dtype != dtype or not a.flags["C_CONTIGUOUS"]:
+        raise TypeError(f"{name}: need C-contiguous {np.dtype(dtype)}")
+
+
+def _check_rc(rc: int, what: str):
+    if rc == -1:
+        raise IndexError(f"{what}: index out of range")
+    if rc != 0:
+        raise RuntimeError(f"{what}: oracle returned {rc}")
+
+
+def embbag_forward(weights: Sequence[np.ndarray], idx: np.ndarray,
+                   n_valid: Optional[int] = None) -> np.ndarray:
+    """weights: T arrays [R, D] fp32; idx int32 [T, Bcap, L] -> [T, Bcap, D].
+
+    Rows j >= n_valid of the result are zero.
+    """
+    T = len(weights)
+    R, D = weights[0].shape
+    _check(idx, np.int32, "idx")
+    assert idx.shape[0] == T and idx.ndim == 3
+    Bcap, L = idx.shape[1], idx.shape[2]
+    if n_valid is None:
+        n_valid = Bcap
+    for w in weights:
+        _check(w, np.float32, "weights")
+        assert w.shape == (R, D)
+    out = np.zeros((T, Bcap, D), dtype=np.float32)
+    rc = _load().oracle_embbag_forward(
+        C.c_int(T), C.c_int64(R), C.c_int(D), _ptr_array(weights, T),
+        C.c_void_p(idx.ctypes.data), C.c_int(Bcap), C.c_int(L),
+        C.c_int(n_valid), C.c_void_p(out.ctypes.data))
+    _check_rc(rc, "embbag_forward")
+    return out
+
+
+def embbag_backward_update(weights: Sequence[np.ndarray],
+                           stale_bits: Optional[Sequence[Optional[np.ndarray]]],
+                           idx: np.ndarray, grad: np.ndarray, lr: float,
+                           n_valid: Optional[int] = None) -> None:
+    """Updates `weights` in place; stale_bits: T uint32 arrays or None."""
+    T = len(weights)
+    R, D = weights[0].shape
+    _check(idx, np.int32, "idx")
+    _check(grad, np.float32, "grad")
+    Bcap, L = idx.shape[1], idx.shape[2]
+    assert idx.shape[0] == T and grad.shape == (T, Bcap, D)
+    if n_valid is None:
+        n_valid = Bcap
+    for w in weights:
+        _check(w, np.float32, "weights")
+        assert w.shape == (R, D)
+    if stale_bits is not None:
+        for b in stale_bits:
+            if b is not None:
+                _check(b, np.uint32, "stale_bits")
+                assert b.size >= (R + 31) // 32
+    bits = _ptr_array(stale_bits, T) if stale_bits is not None else None
+    rc = _load().oracle_embbag_backward_update(
+        C.c_int(T), C.c_int64(R), C.c_int(D), _ptr_array(weights, T), bits,
+        C.c_void_p(idx.ctypes.data), C.c_int(Bcap), C.c_int(L),
+        C.c_int(n_valid), C.c_void_p(grad.ctypes.data), C.c_float(lr))
+    _check_rc(rc, "embbag_backward_update")
+
+
+def detect_stale(weights: Sequence[np.ndarray],
+                 stale_bits: Sequence[np.ndarray],
+                 hot_ids: Sequence[np.ndarray], snapshot: Sequence[np.ndarray],
+                 threshold: float, refresh: bool = True):
+    """ORs new stale bits into `stale_bits`, refreshes `snapshot` in place.
+
+    Returns (stale_hot uint8 [T, H], drift fp64 [T, H], stale_count uint32 [T]).
+    """
+    T = len(weights)
+    R, D = weights[0].shape
+    H = hot_ids[0].shape[0]
+    for t in range(T):
+        _check(weights[t], np.float32, "weights")
+        _check(stale_bits[t], np.uint32, "stale_bits")
+        _check(hot_ids[t], np.int32, "hot_ids")
+        _check(snapshot[t], np.float32, "snapshot")
+        assert snapshot[t].shape == (H, D) and hot_ids[t].shape == (H,)
+        assert stale_bits[t].size >= (R + 31) // 32
+    stale_hot = np.zeros((T, H), dtype=np.uint8)
+    drift = np.zeros((T, H), dtype=np.float64)
+    count = np.zeros(T, dtype=np.uint32)
+    rc = _load().oracle_detect_stale(
+        C.c_int(T), C.c_int64(R), C.c_int(D), _ptr_array(weights, T),
+        _ptr_array(stale_bits, T), _ptr_array(hot_ids, T), C.c_int(H),
+        _ptr_array(snapshot, T), C.c_float(threshold), C.c_int(int(refresh)),
+        _ptr_array([stale_hot[t] for t in range(T)], T),
+        _ptr_array([drift[t] for t in range(T)], T),
+        C.c_void_p(count.ctypes.data))
+    _check_rc(rc, "detect_stale")
+    return stale_hot, drift, count
+
+
+def filter_batch(rows: int, stale_bits: Optional[Sequence[Optional[np.ndarray]]],
+                 idx: np.ndarray, alpha: int):
+    """Returns (skip_mask uint8 [B], kept_ids int32 [n_kept], idx_c [T, B, L]).
+
+    idx_c rows j >= n_kept are zero.
+    """
+    _check(idx, np.int32, "idx")
+    T, B, L = idx.shape
+    skip = np.zeros(B, dtype=np.uint8)
+    kept = np.zeros(B, dtype=np.int32)
+    n_kept = C.c_int32(0)
+    idx_c = np.zeros_like(idx)
+    bits = _ptr_array(stale_bits, T) if stale_bits is not None else None
+    rc = _load().oracle_filter_batch(
+        C.c_int(T), C.c_int64(rows), bits, C.c_void_p(idx.ctypes.data),
+        C.c_int(B), C.c_int(L), C.c_int(alpha), C.c_void_p(skip.ctypes.data),
+        C.c_void_p(kept.ctypes.data), C.byref(n_kept),
+        C.c_void_p(idx_c.ctypes.data))
+    _check_rc(rc, "filter_batch")
+    return skip, kept[:n_kept.value].copy(), idx_c

@@ -1,0 +1,227 @@
+/*
+ * CPU oracle for the embedding-table side of a Slipstream training step.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file defines what the GPU library must
+ * compute; it is slow on purpose (scalar loops, fp64 accumulation, one table
+ * and one lookup at a time) so that it can be checked against the paper by
+ * eye.  Only the tests, the smoke check and the benchmark's CPU-baseline leg
+ * may call it.  It shares no code, header or table with the HIP library.
+ *
+ * Every function works on HOST memory.  Tables are fp32, row-major [R][D].
+ * A stale bitmap holds one bit per row: row r is bit (r & 31) of 32-bit word
+ * (r >> 5).  Lookup indices are int32 [T][B][L].
+ *
+ * Parity pins (tests that tie each function to something other than itself):
+ *   forward          - brute force, gather identity for L = 1, library
+ *                      embedding-bag sum, m copies of a row = m * row
+ *   backward_update  - dense scatter-add SGD (textbook), closed forms for
+ *                      duplicates, frozen stale rows
+ *   detect_stale     - closed-form Euclidean norms with exact ties,
+ *                      threshold 0 / infinity, monotone bitmap
+ *   filter_batch     - brute force, alpha = 0 drops everything (the first
+ *                      column of the paper's alpha table), partition identity
+ *   general alpha between 1 and T*L-1: the paper's own drop percentages need
+ *   its datasets, so for those values parity is pinned by brute force only.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+static int bit_is_set(const uint32_t *bits, int64_t r)
+{
+    if (!bits)
+        return 0;
+    return (int)((bits[r >> 5] >> (r & 31)) & 1u);
+}
+
+/*
+ * Pooled lookup (section 2.1: every sparse feature yields one vector per
+ * table; the multi-hot workload fixes the pooling to a sum):
+ *     out[t][j][:] = sum_{l < L} W_t[ idx[t][j][l] ][:]        j < n_valid
+ * A row that occurs m times in a bag is added m times.  Sums are taken in
+ * fp64 and rounded once.  Returns 0, or -1 on an out-of-range index.
+ */
+int oracle_embbag_forward(int T, int64_t R, int D, float *const *W,
+                          const int32_t *idx, int Bcap, int L, int n_valid,
+                          float *out)
+{
+    for (int t = 0; t < T; ++t) {
+        for (int j = 0; j < n_valid; ++j) {
+            for (int d = 0; d < D; ++d) {
+                double s = 0.0;
+                for (int l = 0; l < L; ++l) {
+                    int64_t r = idx[((int64_t)t * Bcap + j) * L + l];
+                    if (r < 0 || r >= R)
+                        return -1;
+                    s += (double)W[t][r * D + d];
+                }
+                out[((int64_t)t * Bcap + j) * D + d] = (float)s;
+            }
+        }
+    }
+    return 0;
+}
+
+/*
+ * Sparse SGD that leaves stale rows alone (abstract and section 3.6: stale
+ * embeddings are found on the fly and their updates are skipped).
+ *
+ * With sum pooling the gradient of bag (t, j) flows unchanged to each of its
+ * L lookups, so for every row r of table t that was looked up at least once
+ *     acc[r][:] = sum over lookups (j, l) with idx[t][j][l] == r of g[t][j][:]
+ * and, when r's stale bit is clear,
+ *     W_t[r][:] <- W_t[r][:] - lr * acc[r][:]
+ * (fp64 throughout, one rounding to fp32).  Rows whose bit is set are neither
+ * read nor written.  Bitmaps are not modified.
+ */
+int oracle_embbag_backward_update(int T, int64_t R, int D, float *const *W,
+                                  uint32_t *const *stale_bits,
+                                  const int32_t *idx, int Bcap, int L,
+                                  int n_valid, const float *grad, float lr)
+{
+    int64_t nnz = (int64_t)n_valid * L;
+    if (nnz == 0)
+        return 0;
+    /* slot[r] = position of row r's accumulator, or -1 */
+    int32_t *slot = (int32_t *)malloc((size_t)R * sizeof(int32_t));
+    int64_t *rows = (int64_t *)malloc((size_t)nnz * sizeof(int64_t));
+    double *acc = (double *)malloc((size_t)nnz * D * sizeof(double));
+    if (!slot || !rows || !acc) {
+        free(slot); free(rows); free(acc);
+        return -2;
+    }
+    memset(slot, 0xff, (size_t)R * sizeof(int32_t));
+    int rc = 0;
+    for (int t = 0; t < T && rc == 0; ++t) {
+        const uint32_t *bits = stale_bits ? stale_bits[t] : NULL;
+        int64_t n_touched = 0;
+        for (int j = 0; j < n_valid && rc == 0; ++j) {
+            const float *g = grad + ((int64_t)t * Bcap + j) * D;
+            for (int l = 0; l < L; ++l) {
+                int64_t r = idx[((int64_t)t * Bcap + j) * L + l];
+                if (r < 0 || r >= R) { rc = -1; break; }
+                if (slot[r] < 0) {
+                    slot[r] = (int32_t)n_touched;
+                    rows[n_touched] = r;
+                    for (int d = 0; d < D; ++d)
+                        acc[n_touched * D + d] = 0.0;
+                    ++n_touched;
+                }
+                double *a = acc + (int64_t)slot[r] * D;
+                for (int d = 0; d < D; ++d)
+                    a[d] += (double)g[d];
+            }
+        }
+        for (int64_t k = 0; k < n_touched; ++k) {
+            int64_t r = rows[k];
+            slot[r] = -1;
+            if (rc != 0 || bit_is_set(bits, r))
+                continue;
+            float *w = W[t] + r * D;
+            for (int d = 0; d < D; ++d)
+                w[d] = (float)((double)w[d] - (double)lr * acc[k * D + d]);
+        }
+    }
+    free(slot); free(rows); free(acc);
+    return rc;
+}
+
+/*
+ * Drift test of hot rows against their last snapshot (Eq. 1 and Eq. 5: a hot
+ * row is "varying" when the Euclidean distance between two consecutive
+ * snapshots of it exceeds T, and stale otherwise).
+ *
+ * For hot slot h of table t, r = hot_ids[t][h]:
+ *     drift = || W_t[r][:] - S_t[h][:] ||_2                       (fp64)
+ *     stale = (T > 0) and (drift <= T)
+ * Readings where the paper is silent: equality counts as stale ("> T" is
+ * varying); T = 0 switches detection off so that a zero threshold means plain
+ * training; a stale bit, once set, is never cleared (skipped "for the
+ * remaining training process", section 1), so the bitmap is OR-ed; a NaN
+ * drift compares false and leaves the row varying.
+ * If refresh != 0 the snapshot row is then overwritten with the current row.
+ * stale_hot[t][h] (0/1), drift[t][h] and stale_count[t] (rows flagged by this
+ * call, whether or not their bit was already set) are optional outputs.
+ */
+int oracle_detect_stale(int T, int64_t R, int D, float *const *W,
+                        uint32_t *const *stale_bits, int32_t *const *hot_ids,
+                        int H, float *const *snapshot, float threshold,
+                        int refresh, uint8_t *const *stale_hot,
+                        double *const *drift, uint32_t *stale_count)
+{
+    double thr = (double)threshold;
+    for (int t = 0; t < T; ++t) {
+        uint32_t count = 0;
+        for (int h = 0; h < H; ++h) {
+            int64_t r = hot_ids[t][h];
+            if (r < 0 || r >= R)
+                return -1;
+            const float *w = W[t] + r * D;
+            float *s = snapshot[t] + (int64_t)h * D;
+            double d2 = 0.0;
+            for (int d = 0; d < D; ++d) {
+                double e = (double)w[d] - (double)s[d];
+                d2 += e * e;
+            }
+            double dist = sqrt(d2);
+            int stale = (thr > 0.0) && (dist <= thr);
+            if (stale) {
+                stale_bits[t][r >> 5] |= (1u << (r & 31));
+                ++count;
+            }
+            if (stale_hot && stale_hot[t])
+                stale_hot[t][h] = (uint8_t)stale;
+            if (drift && drift[t])
+                drift[t][h] = dist;
+            if (refresh)
+                memcpy(s, w, (size_t)D * sizeof(float));
+        }
+        if (stale_count)
+            stale_count[t] = count;
+    }
+    return 0;
+}
+
+/*
+ * Input classifier (section 3.4, Eq. 6-8): an input is dropped when the
+ * number of stale embeddings it accesses reaches alpha; the rest are kept, in
+ * their original order.
+ *     c_b    = #{ (t, l) : stale_t[ idx[t][b][l] ] }
+ *     skip_b = (c_b >= alpha)
+ * alpha = T*L drops the inputs whose every lookup is stale; alpha <= 0 drops
+ * every input (the alpha = 0 column of the paper's alpha table reads 100 %).
+ * Outputs: skip_mask[B]; kept_ids[0..n_kept) ascending; *n_kept;
+ * idx_c[t][j][:] = idx[t][kept_ids[j]][:] with the same [T][B][L] strides
+ * (entries j >= n_kept are left as they were).
+ */
+int oracle_filter_batch(int T, int64_t R, uint32_t *const *stale_bits,
+                        const int32_t *idx, int B, int L, int alpha,
+                        uint8_t *skip_mask, int32_t *kept_ids, int32_t *n_kept,
+                        int32_t *idx_c)
+{
+    int32_t nk = 0;
+    for (int b = 0; b < B; ++b) {
+        int c = 0;
+        for (int t = 0; t < T; ++t) {
+            const uint32_t *bits = stale_bits ? stale_bits[t] : NULL;
+            for (int l = 0; l < L; ++l) {
+                int64_t r = idx[((int64_t)t * B + b) * L + l];
+                if (r < 0 || r >= R)
+                    return -1;
+                c += bit_is_set(bits, r);
+            }
+        }
+        int skip = (c >= alpha);
+        skip_mask[b] = (uint8_t)skip;
+        if (!skip)
+            kept_ids[nk++] = b;
+    }
+    for (int t = 0; t < T; ++t)
+        for (int32_t j = 0; j < nk; ++j)
+            for (int l = 0; l < L; ++l)
+                idx_c[((int64_t)t * B + j) * L + l] =
+                    idx[((int64_t)t * B + kept_ids[j]) * L + l];
+    *n_kept = nk;
+    return 0;
+}

@@ -1,0 +1,26 @@
+"""MI355X-native embedding hot path of a Slipstream training step.
+
+`workload` draws the seeded synthetic inputs.  `binding` (imported on first
+use of any `ss_*` name) loads libslipstream.so, the HIP library behind the
+C ABI declared in include/slipstream.h, and raises if it is missing: there
+is no CPU fallback.
+"""
+from . import workload  # noqa: F401
+
+_BINDING_NAMES = (
+    "Tables", "ss_embbag_forward", "ss_embbag_backward_update",
+    "ss_detect_stale", "ss_filter_batch", "ss_filter_batch_workspace_bytes",
+    "ss_backward_workspace_bytes", "ss_last_error", "SlipstreamError",
+    "EmbeddingStep", "lib_path",
+)
+
+
+def __getattr__(name):
+    if name in _BINDING_NAMES or name in ("binding", "step"):
+        import importlib
+        if name == "step" or name == "EmbeddingStep":
+            mod = importlib.import_module(".step", __name__)
+            return mod if name == "step" else mod.EmbeddingStep
+        mod = importlib.import_module(".binding", __name__)
+        return mod if name == "binding" else getattr(mod, name)
+    raise AttributeError(name)

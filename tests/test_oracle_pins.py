@@ -1,0 +1,391 @@
+"""Pins of the CPU oracle: each function is tied to something other than
+itself (brute force, a textbook/library routine, a closed form, a value the
+paper prints, an invariant), so that a wrong sign, index, term or operand
+order in oracle/ss_oracle.c fails here.  CPU only.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle.protocol import OracleRun
+from paper_2404_04270_amd import workload as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rand_tables(rng, T, R, D):
+    return [rng.uniform(-0.05, 0.05, (R, D)).astype(np.float32) for _ in range(T)]
+
+
+def set_bits(R, rows):
+    b = np.zeros((R + 31) // 32, dtype=np.uint32)
+    for r in rows:
+        b[r >> 5] |= np.uint32(1 << (r & 31))
+    return b
+
+
+# --------------------------------------------------------------- forward
+def test_forward_brute_force_tiny():
+    rng = np.random.default_rng(0)
+    T, R, D, B, L = 3, 7, 4, 5, 3
+    W = rand_tables(rng, T, R, D)
+    idx = rng.integers(0, R, (T, B, L)).astype(np.int32)
+    out = oracle.embbag_forward(W, idx)
+    for t in range(T):
+        for j in range(B):
+            for d in range(D):
+                s = 0.0
+                for l in range(L):
+                    s += float(W[t][idx[t, j, l], d])
+                assert out[t, j, d] == np.float32(s)
+
+
+def test_forward_one_hot_is_a_gather_bit_exact():
+    rng = np.random.default_rng(1)
+    T, R, D, B = 4, 100, 16, 33
+    W = rand_tables(rng, T, R, D)
+    idx = rng.integers(0, R, (T, B, 1)).astype(np.int32)
+    out = oracle.embbag_forward(W, idx)
+    for t in range(T):
+        assert np.array_equal(out[t], W[t][idx[t, :, 0]])
+
+
+def test_forward_matches_library_embedding_bag():
+    rng = np.random.default_rng(2)
+    T, R, D, B, L = 2, 50, 12, 17, 5
+    W = rand_tables(rng, T, R, D)
+    idx = rng.integers(0, R, (T, B, L)).astype(np.int32)
+    out = oracle.embbag_forward(W, idx)
+    for t in range(T):
+        ref = torch.nn.functional.embedding_bag(
+            torch.from_numpy(idx[t].astype(np.int64)),
+            torch.from_numpy(W[t]).double(), mode="sum").numpy()
+        assert np.array_equal(out[t], ref.astype(np.float32))
+        ref2 = W[t].astype(np.float64)[idx[t]].sum(axis=1)
+        np.testing.assert_allclose(out[t], ref2, rtol=1e-7, atol=0)
+
+
+def test_forward_duplicates_count_each_time():
+    rng = np.random.default_rng(3)
+    R, D, m = 9, 8, 4
+    W = rand_tables(rng, 1, R, D)
+    idx = np.full((1, 2, m), 5, dtype=np.int32)
+    idx[0, 1, :] = [2, 2, 7, 2]
+    out = oracle.embbag_forward(W, idx)
+    assert np.array_equal(out[0, 0], np.float32(m) * W[0][5])   # 4x is exact
+    np.testing.assert_allclose(
+        out[0, 1], 3.0 * W[0][2].astype(np.float64) + W[0][7], rtol=1e-7)
+
+
+def test_forward_n_valid_and_range_check():
+    rng = np.random.default_rng(4)
+    W = rand_tables(rng, 2, 10, 4)
+    idx = rng.integers(0, 10, (2, 6, 2)).astype(np.int32)
+    out = oracle.embbag_forward(W, idx, n_valid=4)
+    full = oracle.embbag_forward(W, idx)
+    assert np.array_equal(out[:, :4], full[:, :4])
+    assert not out[:, 4:].any()
+    idx[1, 0, 0] = 10
+    with pytest.raises(IndexError):
+        oracle.embbag_forward(W, idx)
+
+
+# -------------------------------------------------------------- backward
+def dense_sgd(W, idx, grad, lr):
+    """Textbook: W -= lr * scatter_add(grad) with a dense gradient (fp64)."""
+    T, B, L = idx.shape
+    out = []
+    for t in range(T):
+        G = np.zeros(W[t].shape, dtype=np.float64)
+        np.add.at(G, idx[t].reshape(-1),
+                  np.repeat(grad[t].astype(np.float64), L, axis=0))
+        out.append((W[t].astype(np.float64)
+                    - float(np.float32(lr)) * G).astype(np.float32))
+    return out
+
+
+def test_backward_no_bitmap_is_plain_sgd():
+    rng = np.random.default_rng(10)
+    T, R, D, B, L = 3, 40, 8, 64, 3
+    W = rand_tables(rng, T, R, D)
+    idx = (rng.zipf(1.5, (T, B, L)) % R).astype(np.int32)
+    grad = rng.normal(0, 0.01, (T, B, D)).astype(np.float32)
+    ref = dense_sgd(W, idx, grad, 0.01)
+    oracle.embbag_backward_update(W, None, idx, grad, 0.01)
+    for t in range(T):
+        assert np.array_equal(W[t], ref[t])
+    # zero bitmaps behave like no bitmap
+    W2 = rand_tables(np.random.default_rng(10), T, R, D)
+    bits = [np.zeros((R + 31) // 32, np.uint32) for _ in range(T)]
+    oracle.embbag_backward_update(W2, bits, idx, grad, 0.01)
+    for t in range(T):
+        assert np.array_equal(W2[t], ref[t])
+
+
+def test_backward_matches_torch_sgd_on_embedding_bag():
+    rng = np.random.default_rng(11)
+    R, D, B, L = 30, 6, 20, 4
+    W = rand_tables(rng, 1, R, D)
+    idx = rng.integers(0, R, (1, B, L)).astype(np.int32)
+    grad = rng.normal(0, 0.01, (1, B, D)).astype(np.float32)
+    emb = torch.nn.EmbeddingBag(R, D, mode="sum", dtype=torch.float64)
+    with torch.no_grad():
+        emb.weight.copy_(torch.from_numpy(W[0]).double())
+    opt = torch.optim.SGD(emb.parameters(), lr=float(np.float32(0.01)))
+    out = emb(torch.from_numpy(idx[0].astype(np.int64)))
+    out.backward(torch.from_numpy(grad[0]).double())
+    opt.step()
+    oracle.embbag_backward_update(W, None, idx, grad, 0.01)
+    np.testing.assert_allclose(W[0], emb.weight.detach().numpy(),
+                               rtol=1e-6, atol=1e-9)
+
+
+def test_backward_duplicate_closed_forms():
+    R, D = 6, 4
+    W = [np.ones((R, D), dtype=np.float32)]
+    # bag 0 holds row 3 four times; bags 1, 2 hold row 1 once each
+    idx = np.array([[[3, 3, 3, 3], [1, 0, 0, 0], [1, 2, 2, 2]]], dtype=np.int32)
+    g = np.zeros((1, 3, D), dtype=np.float32)
+    g[0, 0] = [0.25, -0.5, 1.0, 2.0]
+    g[0, 1] = [1.0, 1.0, 1.0, 1.0]
+    g[0, 2] = [0.5, 0.5, -0.5, 0.0]
+    lr = 0.5
+    oracle.embbag_backward_update(W, None, idx, g, lr)
+    assert np.array_equal(W[0][3], 1.0 - lr * 4 * g[0, 0])          # m * g
+    assert np.array_equal(W[0][1], 1.0 - lr * (g[0, 1] + g[0, 2]))  # sum of g
+    assert np.array_equal(W[0][0], 1.0 - lr * 3 * g[0, 1])
+    assert np.array_equal(W[0][2], 1.0 - lr * 3 * g[0, 2])
+    assert np.array_equal(W[0][4], np.ones(D, np.float32))          # untouched
+    assert np.array_equal(W[0][5], np.ones(D, np.float32))
+
+
+def test_backward_stale_rows_frozen_and_untouched_rows_identical():
+    rng = np.random.default_rng(12)
+    T, R, D, B, L = 2, 64, 8, 50, 2
+    W = rand_tables(rng, T, R, D)
+    W0 = [w.copy() for w in W]
+    idx = rng.integers(0, 40, (T, B, L)).astype(np.int32)   # rows >= 40 untouched
+    grad = rng.normal(0, 0.01, (T, B, D)).astype(np.float32)
+    stale = [[0, 5, 31, 32, 33], [7, 39]]
+    bits = [set_bits(R, s) for s in stale]
+    bits0 = [b.copy() for b in bits]
+    ref = dense_sgd(W0, idx, grad, 0.01)
+    oracle.embbag_backward_update(W, bits, idx, grad, 0.01)
+    for t in range(T):
+        assert np.array_equal(bits[t], bits0[t])
+        for r in range(R):
+            if r in stale[t] or r >= 40:
+                assert np.array_equal(W[t][r], W0[t][r])
+            else:
+                assert np.array_equal(W[t][r], ref[t][r])
+    # every bit set: whole tables identical
+    W = [w.copy() for w in W0]
+    allbits = [np.full((R + 31) // 32, 0xFFFFFFFF, np.uint32) for _ in range(T)]
+    oracle.embbag_backward_update(W, allbits, idx, grad, 0.01)
+    for t in range(T):
+        assert np.array_equal(W[t], W0[t])
+
+
+def test_backward_n_valid_ignores_tail():
+    rng = np.random.default_rng(13)
+    W = rand_tables(rng, 1, 20, 4)
+    W0 = [W[0].copy()]
+    idx = rng.integers(0, 20, (1, 8, 2)).astype(np.int32)
+    grad = rng.normal(0, 0.01, (1, 8, 4)).astype(np.float32)
+    oracle.embbag_backward_update(W, None, idx, grad, 0.01, n_valid=5)
+    ref = dense_sgd(W0, idx[:, :5], grad[:, :5], 0.01)
+    assert np.array_equal(W[0], ref[0])
+
+
+# ---------------------------------------------------------------- detect
+@pytest.mark.parametrize("D,a", [(16, 2.0 ** -12), (64, 2.0 ** -13), (4, 2.0 ** -10)])
+def test_detect_closed_form_uniform_shift_and_tie(D, a):
+    # W = S + a*1  =>  drift = a*sqrt(D); exact in binary for D a power of 4
+    R, H = 50, 6
+    rng = np.random.default_rng(20)
+    S = [np.round(rng.uniform(-1, 1, (H, D)) * 256).astype(np.float32) / 256]
+    hot = [np.array([1, 5, 9, 31, 32, 40], dtype=np.int32)]
+    W = [np.zeros((R, D), dtype=np.float32)]
+    W[0][hot[0]] = S[0] + np.float32(a)
+    drift_exact = a * math.sqrt(D)
+    for thr, expect in [(drift_exact, 1), (np.nextafter(np.float32(drift_exact), np.float32(0)), 0),
+                        (np.nextafter(np.float32(drift_exact), np.float32(1)), 1)]:
+        bits = [np.zeros(2, np.uint32)]
+        snap = [S[0].copy()]
+        sh, dr, cnt = oracle.detect_stale(W, bits, hot, snap, float(thr), refresh=False)
+        assert np.all(dr[0] == drift_exact)
+        assert np.all(sh[0] == expect) and cnt[0] == expect * H
+        assert np.array_equal(bits[0], set_bits(R, hot[0]) if expect else np.zeros(2, np.uint32))
+        assert np.array_equal(snap[0], S[0])          # refresh off
+
+
+def test_detect_single_coordinate_and_pythagoras():
+    R, D = 10, 8
+    W = [np.zeros((R, D), np.float32)]
+    hot = [np.array([2, 4, 6], dtype=np.int32)]
+    S = [np.zeros((3, D), np.float32)]
+    W[0][2, 5] = -0.375                 # |c|
+    W[0][4, 0], W[0][4, 7] = 3.0, -4.0  # 3-4-5
+    bits = [np.zeros(1, np.uint32)]
+    sh, dr, cnt = oracle.detect_stale(W, bits, hot, S, 1.0, refresh=True)
+    assert list(dr[0]) == [0.375, 5.0, 0.0]
+    assert list(sh[0]) == [1, 0, 1] and cnt[0] == 2
+    assert bits[0][0] == (1 << 2) | (1 << 6)
+    assert np.array_equal(S[0], W[0][hot[0]])         # refreshed bit-exactly
+
+
+def test_detect_threshold_zero_infinity_nan_and_monotone():
+    rng = np.random.default_rng(21)
+    T, R, D, H = 2, 100, 16, 10
+    W = rand_tables(rng, T, R, D)
+    hot = [np.sort(rng.choice(R, H, replace=False)).astype(np.int32) for _ in range(T)]
+    snap = [W[t][hot[t]].copy() for t in range(T)]
+    snap[0][3] += 1e-3
+    pre = set_bits(R, [int(hot[0][3])])                  # already stale, large drift now
+    bits = [pre.copy(), np.zeros(4, np.uint32)]
+    # T = 0: detection off even for zero-drift rows
+    sh, dr, cnt = oracle.detect_stale(W, bits, hot, [s.copy() for s in snap], 0.0, refresh=False)
+    assert not sh.any() and not cnt.any()
+    assert np.array_equal(bits[0], pre) and not bits[1].any()
+    # T = inf: every hot row, only hot rows; earlier bits survive (OR)
+    sh, dr, cnt = oracle.detect_stale(W, bits, hot, [s.copy() for s in snap], math.inf, refresh=False)
+    assert sh.all() and list(cnt) == [H, H]
+    for t in range(T):
+        assert np.array_equal(bits[t], set_bits(R, hot[t]))
+    # finite T: bitmap only grows; NaN drift stays varying
+    bits = [pre.copy(), np.zeros(4, np.uint32)]
+    W[1][hot[1][0], 0] = np.nan
+    sh, dr, cnt = oracle.detect_stale(W, bits, hot, snap, 1e-4, refresh=False)
+    assert sh[0, 3] == 0 and (bits[0] & pre).any()       # bit kept though varying now
+    assert sh[1, 0] == 0 and math.isnan(dr[1, 0])
+    assert sh[0].sum() == H - 1 and sh[1].sum() == H - 1
+
+
+# ---------------------------------------------------------------- filter
+def brute_filter(idx, stale_sets, alpha):
+    T, B, L = idx.shape
+    skip = []
+    for b in range(B):
+        c = sum(1 for t in range(T) for l in range(L) if int(idx[t, b, l]) in stale_sets[t])
+        skip.append(c >= alpha)
+    return skip
+
+
+@pytest.mark.parametrize("alpha", [0, 1, 2, 3, 6, 7])
+def test_filter_brute_force(alpha):
+    rng = np.random.default_rng(30)
+    T, R, B, L = 3, 40, 25, 2
+    idx = rng.integers(0, R, (T, B, L)).astype(np.int32)
+    stale_sets = [set(rng.choice(R, 20, replace=False).tolist()) for _ in range(T)]
+    bits = [set_bits(R, s) for s in stale_sets]
+    skip, kept, idx_c = oracle.filter_batch(R, bits, idx, alpha)
+    ref = brute_filter(idx, stale_sets, alpha)
+    assert skip.tolist() == [int(x) for x in ref]
+    assert kept.tolist() == [b for b in range(B) if not ref[b]]
+    assert np.array_equal(idx_c[:, :len(kept)], idx[:, kept])
+    # partition identity (Eq. 8): kept and skipped are disjoint and cover the batch
+    assert sorted(kept.tolist() + [b for b in range(B) if skip[b]]) == list(range(B))
+    if alpha > T * L:
+        assert len(kept) == B
+
+
+def test_filter_alpha_zero_drops_everything_as_in_the_paper_table():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "alpha_zero_drop.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 4
+    rng = np.random.default_rng(31)
+    for model, n_sparse, pct in rows:
+        T, B, R = int(n_sparse), 200, 64
+        idx = rng.integers(0, R, (T, B, 1)).astype(np.int32)
+        for bits in (None, [set_bits(R, range(0, R, 3)) for _ in range(T)]):
+            skip, kept, _ = oracle.filter_batch(R, bits, idx, 0)
+            assert 100.0 * skip.mean() == float(pct), model
+            assert len(kept) == 0
+
+
+def test_filter_every_lookup_rule_equals_hot_membership():
+    # all hot rows stale  =>  skipped samples == samples whose lookups are all hot
+    cfg = wl.CONFIGS[1].scaled(rows=500, batch=300, num_tables=2, bag=2, zipf_alpha=1.6)
+    w = wl.Workload(cfg)
+    idx = w.indices(0, 1)[0]
+    hot = wl.hot_set(w.indices(0, 4), cfg.rows, 25)
+    bits = [set_bits(cfg.rows, hot[t].tolist()) for t in range(2)]
+    skip, kept, _ = oracle.filter_batch(cfg.rows, bits, idx, 2 * 2)
+    member = np.ones(cfg.batch, bool)
+    for t in range(2):
+        member &= np.isin(idx[t], hot[t]).all(axis=1)
+    assert np.array_equal(skip.astype(bool), member)
+    assert 0 < member.sum() < cfg.batch
+
+
+# -------------------------------------------------------------- protocol
+def small_cfg():
+    return wl.CONFIGS[1].scaled(rows=300, batch=64, num_tables=3, iters=45,
+                                snapshot_every=10, zipf_alpha=1.3)
+
+
+def run_protocol(cfg, threshold):
+    w = wl.Workload(cfg)
+    idx = w.indices(0, cfg.iters)
+    hot = wl.hot_set(idx, cfg.rows, 12)
+    W = [w.weights(t) for t in range(cfg.num_tables)]
+    run = OracleRun(W, hot, cfg.lr, threshold, cfg.snapshot_every)
+    logs = [run.step(idx[it], w.grads(it)) for it in range(cfg.iters)]
+    return run, logs, idx, hot, w
+
+
+def test_protocol_threshold_zero_is_plain_sgd():
+    cfg = small_cfg()
+    run, logs, idx, hot, w = run_protocol(cfg, 0.0)
+    W = [w.weights(t) for t in range(cfg.num_tables)]
+    for it in range(cfg.iters):
+        W = dense_sgd(W, idx[it], w.grads(it), cfg.lr)
+    for t in range(cfg.num_tables):
+        assert np.array_equal(run.W[t], W[t])
+        assert not run.bits[t].any()
+    assert all(l["n_kept"] == cfg.batch for l in logs)
+
+
+def test_protocol_threshold_infinity_freezes_hot_rows_after_first_detect():
+    cfg = small_cfg()
+    run, logs, idx, hot, w = run_protocol(cfg, math.inf)
+    K = cfg.snapshot_every
+    # replay plain SGD up to the first detect (end of iteration 2K-1) ...
+    W = [w.weights(t) for t in range(cfg.num_tables)]
+    for it in range(2 * K):
+        W = dense_sgd(W, idx[it], w.grads(it), cfg.lr)
+    for t in range(cfg.num_tables):
+        # ... from then on hot rows never move
+        assert np.array_equal(run.W[t][hot[t]], W[t][hot[t]])
+        assert np.array_equal(run.bits[t], set_bits(cfg.rows, hot[t].tolist()))
+    # and samples whose lookups are all hot are skipped afterwards
+    for it in range(2 * K, cfg.iters):
+        member = np.ones(cfg.batch, bool)
+        for t in range(cfg.num_tables):
+            member &= np.isin(idx[it, t, :, 0], hot[t])
+        assert np.array_equal(logs[it]["skip"].astype(bool), member)
+    assert all(l["n_kept"] == cfg.batch for l in logs[:2 * K])
+    assert [l["detected"] for l in logs].count(True) == cfg.iters // K - 1
+
+
+def test_protocol_stale_set_is_monotone_and_cold_rows_follow_sgd():
+    cfg = small_cfg()
+    w = wl.Workload(cfg)
+    idx = w.indices(0, cfg.iters)
+    hot = wl.hot_set(idx, cfg.rows, 12)
+    W = [w.weights(t) for t in range(cfg.num_tables)]
+    run = OracleRun(W, hot, cfg.lr, 3e-4, cfg.snapshot_every)
+    prev = [b.copy() for b in run.bits]
+    for it in range(cfg.iters):
+        run.step(idx[it], w.grads(it))
+        for t in range(cfg.num_tables):
+            assert np.array_equal(run.bits[t] & prev[t], prev[t])
+            prev[t] = run.bits[t].copy()
+    for t in range(cfg.num_tables):
+        nonhot = np.setdiff1d(np.flatnonzero(
+            np.unpackbits(run.bits[t].view(np.uint8), bitorder="little")), hot[t])
+        assert nonhot.size == 0          # only hot rows can ever be flagged
