@@ -1,0 +1,171 @@
+#!/usr/bin/env python3
+"""Throughput of the embedding hot path on one MI355X.
+
+A step = filter_batch -> forward -> backward_update over one batch of seeded
+Zipf lookups, plus detect_stale on the iterations where the snapshot period
+ends.  Inputs are resident in HBM before the timed region starts.  Prints one
+JSON line (see the design doc for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--threshold", type=float, default=None,
+                    help="drift threshold T (default: the config's; inf freezes all hot rows)")
+    ap.add_argument("--ring", type=int, default=16, help="distinct batches cycled through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    return ap.parse_args()
+
+
+def unique_rows_per_batch(idx_ring):
+    """Mean over the ring of sum over tables of #distinct rows in a batch."""
+    tot = 0
+    for k in range(idx_ring.shape[0]):
+        for t in range(idx_ring.shape[1]):
+            tot += np.unique(idx_ring[k, t]).size
+    return tot / idx_ring.shape[0]
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
+              "(no collectives or sharding are part of it)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2404_04270_amd import binding as B
+    from paper_2404_04270_amd import workload as wl
+    from paper_2404_04270_amd.step import EmbeddingStep
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    cfg = wl.CONFIGS[args.config]
+    thr = cfg.threshold if args.threshold is None else args.threshold
+    T, R, D, Bn, L = cfg.num_tables, cfg.rows, cfg.dim, cfg.batch, cfg.bag
+    w = wl.Workload(cfg)
+
+    t0 = time.time()
+    idx_ring = w.indices(0, args.ring)                          # [ring, T, B, L]
+    hot = wl.hot_set(idx_ring, R, cfg.hot_rows)
+    weights = [w.weights_device(t, dev) for t in range(T)]
+    idx_d = torch.from_numpy(idx_ring).to(dev)
+    n_grads = 4
+    grads = [torch.from_numpy(w.grads(k)).to(dev) for k in range(n_grads)]
+    step = EmbeddingStep(weights, [torch.from_numpy(h).to(dev) for h in hot],
+                         Bn, L, cfg.lr, thr, cfg.snapshot_every, diagnostics=False)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    def run(n, start_it):
+        for k in range(n):
+            it = start_it + k
+            step.filter_forward(idx_d[it % args.ring])
+            step.backward(grads[it % n_grads])
+
+    run(args.warmup, 0)
+    torch.cuda.synchronize()
+    kept_before = 0
+    t1 = time.perf_counter()
+    run(args.steps, args.warmup)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t1
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = Bn * args.steps / elapsed
+    n_kept_last = int(step.n_kept.item())
+    stale_rows = int(sum(int(torch.count_nonzero(b).item()) for b in step.bits))
+
+    # per-kernel durations: same steps again, each launch bracketed by events
+    B.ss_profile_enable(True)
+    run(args.steps, args.warmup + args.steps)
+    torch.cuda.synchronize()
+    B.ss_profile_enable(False)
+    prof = B.ss_profile_report()
+    kern = {k: {"launches": n, "avg_us": 1e3 * ms / n, "total_ms": ms}
+            for k, (n, ms) in prof.items()}
+
+    # algorithmic bytes per launch (all tables are in one launch)
+    U = unique_rows_per_batch(idx_ring)          # distinct rows per batch, all tables
+    nnz = T * Bn * L
+    kept_frac = n_kept_last / Bn
+    row_b = D * 4
+    alg = {
+        "forward_kernel": U * row_b + nnz * 4 + T * Bn * row_b * kept_frac,
+        "apply_kernel": T * Bn * row_b * kept_frac + nnz * 4 + 2 * U * row_b,
+    }
+    dom = max((k for k in kern if k in alg), key=lambda k: kern[k]["total_ms"])
+    achieved = alg[dom] / (kern[dom]["avg_us"] * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                "traffic": None, "algorithmic_bytes_per_launch": alg[dom],
+                "avg_kernel_us": kern[dom]["avg_us"]}
+    step_bytes = alg["forward_kernel"] + alg["apply_kernel"]
+
+    out = {
+        "metric": "train samples/s through embedding fwd+update+stale-skip; achieved HBM GB/s",
+        "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "tables": T, "rows": R, "dim": D, "batch": Bn,
+                   "bag": L, "zipf_alpha": cfg.zipf_alpha, "threshold": thr,
+                   "snapshot_every": cfg.snapshot_every, "ring": args.ring},
+        "roofline": roofline,
+        "whole_step": {"algorithmic_bytes": step_bytes,
+                       "achieved_GBs": step_bytes / (ms_per_step * 1e-3) / 1e9,
+                       "frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "skip_fraction": 1.0 - kept_frac, "stale_rows": stale_rows,
+        "kernels": kern, "setup_s": setup_s,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, w, idx_ring, hot, thr, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+def cpu_baseline(cfg, w, idx_ring, hot, thr, budget_s):
+    """The oracle as it stands, on this machine's host cores (one thread)."""
+    from oracle.protocol import OracleRun
+    W = [w.weights(t) if cfg.table_bytes <= 8e9 else None for t in range(cfg.num_tables)]
+    if W[0] is None:
+        rng = np.random.default_rng(cfg.seed)
+        W = []
+        for t in range(cfg.num_tables):
+            a = np.empty((cfg.rows, cfg.dim), dtype=np.float32)
+            a[:] = rng.uniform(-cfg.init_bound, cfg.init_bound, cfg.dim).astype(np.float32)
+            W.append(a)
+    run = OracleRun(W, hot, cfg.lr, thr, cfg.snapshot_every)
+    g = [w.grads(k) for k in range(2)]
+    run.step(idx_ring[0], g[0])                       # warm-up (page faults)
+    t0 = time.perf_counter()
+    n = 0
+    while True:
+        run.step(idx_ring[(n + 1) % idx_ring.shape[0]], g[n % 2])
+        n += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or n >= 2000:
+            break
+    return {"value": cfg.batch * n / el, "unit": "samples/s", "cores": 1,
+            "kind": "oracle",
+            "sample": "%d iterations of the same workload after 1 warm-up, "
+                      "single thread, %.1f s" % (n, el)}
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,169 @@
+/*
+ * libslipstream - embedding-table side of a Slipstream training step on one
+ * AMD MI355X (gfx950).  C ABI; every kernel behind it is hand-written HIP.
+ *
+ * The paper (arXiv 2404.04270) trains recommendation models whose embedding
+ * tables E (m rows x d columns, section 2.4.1) dominate memory traffic.  It
+ * keeps periodic snapshots of the frequently accessed ("hot") rows, marks a hot
+ * row stale once the Euclidean distance between two consecutive snapshots of it
+ * no longer exceeds a threshold T (Eq. 1, Eq. 5), stops updating stale rows and
+ * drops the inputs that only reach stale rows (Eq. 6-8).  The four calls below
+ * are the pieces of one training iteration that touch the tables.
+ *
+ * Conventions common to all calls
+ *   - Return value: SS_OK or an SS_ERR_* code; ss_last_error() gives the text
+ *     of the calling thread's last error.  On an error nothing was enqueued.
+ *   - Arguments are validated on the host.  Row indices are NOT range-checked
+ *     on the device: an index outside [0, rows) is undefined behaviour.
+ *   - Every pointer marked "device" is device memory owned by the caller; the
+ *     library allocates nothing, keeps no state between calls and never
+ *     synchronises with the host.  Work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL is the default stream) and the
+ *     buffers must stay alive until that work has finished.
+ *   - The ss_tables struct itself lives in HOST memory and is only read.
+ *   - Tables are fp32, row-major [rows][dim], 16-byte aligned, dim % 4 == 0.
+ *   - A stale bitmap has one bit per row: row r is bit (r & 31) of 32-bit
+ *     word (r >> 5); ceil(rows / 32) words per table.
+ *   - Lookup indices are int32 [T][B][L]: table-major, then sample, then the
+ *     L lookups of that sample's bag (L = 1 for one-hot features).
+ */
+#ifndef SLIPSTREAM_H
+#define SLIPSTREAM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    SS_OK = 0,
+    SS_ERR_INVALID_ARG = 1,
+    SS_ERR_UNSUPPORTED = 2,
+    SS_ERR_WORKSPACE = 3, /* workspace missing, misaligned or too small */
+    SS_ERR_HIP = 4        /* a HIP runtime call or kernel launch failed */
+};
+
+/* Text of the calling thread's last error ("" if none).  Static storage. */
+const char *ss_last_error(void);
+
+typedef struct {
+    int32_t num_tables;    /* T >= 1 */
+    int32_t dim;           /* d: floats per row, multiple of 4, <= 1024 */
+    int64_t rows;          /* m: rows of every table, 1 <= rows < 2^31 */
+    float **weights;       /* device array of T device pointers, each [rows][dim] */
+    uint32_t **stale_bits; /* device array of T device pointers to bitmaps, or
+                              NULL when no row of any table is stale */
+} ss_tables;
+
+/*
+ * Input classifier (section 3.4, Eq. 6-8; alpha as in the notation table and
+ * the alpha ablation).  For sample b let c_b be the number of its T*L lookups
+ * that hit a row whose stale bit is set.  The sample is skipped iff
+ * c_b >= alpha.  alpha = T*L skips the samples whose every lookup is stale;
+ * alpha <= 0 skips every sample; alpha > T*L skips none.
+ *
+ *   idx        device, int32 [T][B][L], read only
+ *   skip_mask  device, uint8 [B]: 1 = skipped
+ *   kept_ids   device, int32 [B]: the kept sample numbers in ascending order
+ *              in entries [0, n_kept); the rest is left untouched
+ *   n_kept     device, one int32
+ *   idx_c      device, int32 [T][B][L]: idx_c[t][j][:] = idx[t][kept_ids[j]][:]
+ *              for j < n_kept (same strides as idx); rows j >= n_kept are
+ *              left untouched.  Must not alias idx.
+ *   ws         device workspace of ss_filter_batch_workspace_bytes(T, B, L)
+ *              bytes, 256-byte aligned
+ */
+int32_t ss_filter_batch(const ss_tables *tables, const int32_t *idx, int32_t B,
+                        int32_t L, int32_t alpha, uint8_t *skip_mask,
+                        int32_t *kept_ids, int32_t *n_kept, int32_t *idx_c,
+                        void *ws, size_t ws_bytes, void *stream);
+size_t ss_filter_batch_workspace_bytes(int32_t T, int32_t B, int32_t L);
+
+/*
+ * Pooled embedding lookup (section 2.1: the lookup of one sparse feature
+ * yields a single vector per table; bags are pooled by summation):
+ *     out[t][j][:] = sum_{l < L} W_t[ idx[t][j][l] ][:]      for j < n_valid
+ * A row that appears m times in a bag is added m times.  With L = 1 the
+ * result is a bit-exact copy of the row.
+ *
+ *   idx      device, int32 [T][Bcap][L]
+ *   n_valid  device, one int32 in [0, Bcap] (e.g. ss_filter_batch's n_kept),
+ *            or NULL meaning Bcap
+ *   out      device, fp32 [T][Bcap][dim], 16-byte aligned; rows j >= n_valid
+ *            are left untouched
+ */
+int32_t ss_embbag_forward(const ss_tables *tables, const int32_t *idx,
+                          int32_t Bcap, int32_t L, const int32_t *n_valid,
+                          float *out, void *stream);
+
+/*
+ * Backward of the pooled lookup fused with sparse SGD that skips stale rows
+ * (abstract, section 3.6: stale embeddings are identified and their updates
+ * skipped; section 2.3.1 counts the optimizer's embedding update among the
+ * dominant costs).  With sum pooling every lookup (t, j, l) receives
+ * grad[t][j][:].  For each row r of table t that is looked up at least once
+ * by a sample j < n_valid and whose stale bit is clear
+ *     W_t[r][:] -= lr * sum_{(j,l): idx[t][j][l] == r} grad[t][j][:]
+ * Rows whose stale bit is set are neither read nor written; bitmaps are not
+ * modified.  The sum is taken in fp32 in a fixed order (ascending sample, then
+ * position in the bag; long runs are split at fixed boundaries), so results
+ * are reproducible run to run.
+ *
+ *   grad  device, fp32 [T][Bcap][dim], 16-byte aligned, read only
+ *   ws    device workspace of ss_backward_workspace_bytes(T, Bcap, L, dim)
+ *         bytes, 256-byte aligned; contents on entry are ignored
+ */
+int32_t ss_embbag_backward_update(const ss_tables *tables, const int32_t *idx,
+                                  int32_t Bcap, int32_t L,
+                                  const int32_t *n_valid, const float *grad,
+                                  float lr, void *ws, size_t ws_bytes,
+                                  void *stream);
+size_t ss_backward_workspace_bytes(int32_t T, int32_t Bcap, int32_t L,
+                                   int32_t dim);
+
+/*
+ * Snapshot comparison (section 3.1.2 snapshots; Eq. 1 and Eq. 5).  For hot
+ * slot h of table t with r = hot_ids[t][h]:
+ *     drift = || W_t[r][:] - snapshot_t[h][:] ||_2        (accumulated in fp64)
+ *     stale = (threshold > 0) && (drift <= threshold)
+ * and if stale, bit r of stale_bits[t] is set (bits are only ever OR-ed in:
+ * once stale, a row stays stale).  Equality counts as stale because Eq. 1 calls
+ * a row varying only when the distance exceeds T.  threshold = 0 disables
+ * detection (plain training); threshold = +inf flags every hot row.  A NaN
+ * drift leaves the row varying.  If refresh_snapshot != 0, snapshot_t[h][:] is
+ * then overwritten with W_t[r][:].  To capture a first snapshot, call with
+ * threshold = 0 and refresh_snapshot = 1.
+ *
+ *   tables->stale_bits must not be NULL
+ *   hot_ids      device array of T device pointers, each int32 [H]; the row
+ *                ids of one table must be distinct (ascending order lets
+ *                neighbouring rows share one bitmap update, but is not needed)
+ *   snapshot     device array of T device pointers, each fp32 [H][dim]
+ *   stale_hot    NULL, or device array of T device pointers, each uint8 [H]:
+ *                this call's verdict per hot slot
+ *   drift        NULL, or device array of T device pointers, each fp64 [H]
+ *   stale_count  NULL, or device uint32 [T]: slots flagged stale by this call
+ */
+int32_t ss_detect_stale(const ss_tables *tables, int32_t *const *hot_ids,
+                        int32_t H, float **snapshot, float threshold,
+                        int32_t refresh_snapshot, uint8_t **stale_hot,
+                        double **drift, uint32_t *stale_count, void *stream);
+
+/*
+ * Measurement aid, off by default (not part of the method).  While enabled,
+ * every kernel the library launches is bracketed by a pair of HIP events on
+ * the launch stream (this is the one case in which the library creates HIP
+ * objects).  ss_profile_report waits for the recorded events, writes one line
+ * "kernel_name launches total_milliseconds" per kernel into buf (host memory,
+ * NUL terminated), and forgets them.  At most 2^20 launches are recorded
+ * between two reports.  Process-wide; meant for a single benchmarking thread.
+ */
+void ss_profile_enable(int32_t on);
+int32_t ss_profile_report(char *buf, size_t buf_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLIPSTREAM_H */

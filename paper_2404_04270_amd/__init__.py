@@ -11,6 +11,7 @@ _BINDING_NAMES = (
     "Tables", "ss_embbag_forward", "ss_embbag_backward_update",
     "ss_detect_stale", "ss_filter_batch", "ss_filter_batch_workspace_bytes",
     "ss_backward_workspace_bytes", "ss_last_error", "SlipstreamError",
+    "ss_profile_enable", "ss_profile_report", "HotState",
     "EmbeddingStep", "lib_path",
 )
 

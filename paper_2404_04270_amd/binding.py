@@ -1,0 +1,265 @@
+"""Thin ctypes binding of libslipstream.so (include/slipstream.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels
+behind the C ABI.  PyTorch supplies device memory and the current stream.
+There is no fallback: if the library is missing or a call fails, this raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+lib_path = os.path.join(_HERE, "libslipstream.so")
+
+SYMBOLS = (
+    "ss_last_error", "ss_filter_batch", "ss_filter_batch_workspace_bytes",
+    "ss_embbag_forward", "ss_embbag_backward_update",
+    "ss_backward_workspace_bytes", "ss_detect_stale", "ss_profile_enable",
+    "ss_profile_report",
+)
+
+
+class SlipstreamError(RuntimeError):
+    pass
+
+
+class _CTables(C.Structure):
+    _fields_ = [("num_tables", C.c_int32), ("dim", C.c_int32),
+                ("rows", C.c_int64), ("weights", C.c_void_p),
+                ("stale_bits", C.c_void_p)]
+
+
+def _load():
+    if not os.path.exists(lib_path):
+        raise SlipstreamError(
+            f"{lib_path} is missing: build it with "
+            "`python -c 'import __graft_entry__ as g; g.build()'` "
+            "(there is no CPU fallback)")
+    lib = C.CDLL(lib_path)
+    lib.ss_last_error.restype = C.c_char_p
+    lib.ss_filter_batch_workspace_bytes.restype = C.c_size_t
+    lib.ss_backward_workspace_bytes.restype = C.c_size_t
+    lib.ss_profile_enable.restype = None
+    for n in ("ss_filter_batch", "ss_embbag_forward",
+              "ss_embbag_backward_update", "ss_detect_stale",
+              "ss_profile_report"):
+        getattr(lib, n).restype = C.c_int32
+    return lib
+
+
+_lib = _load()
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise SlipstreamError(
+            f"[{rc}] " + _lib.ss_last_error().decode("utf-8", "replace"))
+
+
+def ss_last_error() -> str:
+    return _lib.ss_last_error().decode("utf-8", "replace")
+
+
+def ss_profile_enable(on: bool) -> None:
+    _lib.ss_profile_enable(C.c_int32(int(on)))
+
+
+def ss_profile_report() -> dict:
+    """{kernel: (launches, total_ms)} since the last report."""
+    buf = C.create_string_buffer(1 << 16)
+    _check(_lib.ss_profile_report(buf, C.c_size_t(len(buf))))
+    out = {}
+    for line in buf.value.decode().splitlines():
+        k, n, ms = line.split()
+        out[k] = (int(n), float(ms))
+    return out
+
+
+def _dev_ptr(t: Optional[torch.Tensor], dtype, name: str) -> C.c_void_p:
+    if t is None:
+        return C.c_void_p(None)
+    if not t.is_cuda:
+        raise SlipstreamError(f"{name}: need a device tensor")
+    if t.dtype != dtype:
+        raise SlipstreamError(f"{name}: need dtype {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise SlipstreamError(f"{name}: need a contiguous tensor")
+    return C.c_void_p(t.data_ptr())
+
+
+def _ptr_table(tensors: Sequence[torch.Tensor], device) -> torch.Tensor:
+    return torch.tensor([t.data_ptr() for t in tensors], dtype=torch.int64,
+                        device=device)
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+class Tables:
+    """T embedding tables [R, D] fp32 in HBM plus their stale bitmaps.
+
+    Holds the tensors alive together with the device arrays of pointers the
+    library reads.  `bits` may be None (no stale row anywhere).
+    """
+
+    def __init__(self, weights: Sequence[torch.Tensor],
+                 bits: Optional[Sequence[torch.Tensor]] = None):
+        self.weights: List[torch.Tensor] = list(weights)
+        w0 = self.weights[0]
+        self.device = w0.device
+        self.rows, self.dim = int(w0.shape[0]), int(w0.shape[1])
+        for w in self.weights:
+            _dev_ptr(w, torch.float32, "weights")
+            if tuple(w.shape) != (self.rows, self.dim):
+                raise SlipstreamError("weights: all tables need the same shape")
+        self.num_tables = len(self.weights)
+        self._wptr = _ptr_table(self.weights, self.device)
+        self.bits: Optional[List[torch.Tensor]] = None
+        self._bptr: Optional[torch.Tensor] = None
+        if bits is not None:
+            self.set_bits(bits)
+        self._refresh_struct()
+
+    @staticmethod
+    def bitmap_words(rows: int) -> int:
+        return (rows + 31) // 32
+
+    def new_bits(self) -> List[torch.Tensor]:
+        """Allocates zeroed bitmaps (int32 storage of the 32-bit words)."""
+        bits = [torch.zeros(self.bitmap_words(self.rows), dtype=torch.int32,
+                            device=self.device) for _ in range(self.num_tables)]
+        self.set_bits(bits)
+        return bits
+
+    def set_bits(self, bits: Optional[Sequence[torch.Tensor]]):
+        if bits is None:
+            self.bits, self._bptr = None, None
+        else:
+            self.bits = list(bits)
+            if len(self.bits) != self.num_tables:
+                raise SlipstreamError("bits: one bitmap per table")
+            for b in self.bits:
+                _dev_ptr(b, torch.int32, "bits")
+                if b.numel() < self.bitmap_words(self.rows):
+                    raise SlipstreamError("bits: bitmap too short")
+            self._bptr = _ptr_table(self.bits, self.device)
+        self._refresh_struct()
+
+    def _refresh_struct(self):
+        self.c = _CTables(
+            self.num_tables, self.dim, self.rows, self._wptr.data_ptr(),
+            None if self._bptr is None else self._bptr.data_ptr())
+
+    def struct_without_bits(self) -> _CTables:
+        return _CTables(self.num_tables, self.dim, self.rows,
+                        self._wptr.data_ptr(), None)
+
+
+def ss_filter_batch_workspace_bytes(T: int, B: int, L: int) -> int:
+    return int(_lib.ss_filter_batch_workspace_bytes(
+        C.c_int32(T), C.c_int32(B), C.c_int32(L)))
+
+
+def ss_backward_workspace_bytes(T: int, Bcap: int, L: int, dim: int) -> int:
+    return int(_lib.ss_backward_workspace_bytes(
+        C.c_int32(T), C.c_int32(Bcap), C.c_int32(L), C.c_int32(dim)))
+
+
+def _idx_shape(tables: Tables, idx: torch.Tensor):
+    if idx.dim() != 3 or idx.shape[0] != tables.num_tables:
+        raise SlipstreamError("idx: need int32 [T, B, L]")
+    return int(idx.shape[1]), int(idx.shape[2])
+
+
+def ss_filter_batch(tables: Tables, idx: torch.Tensor, alpha: int,
+                    skip_mask: torch.Tensor, kept_ids: torch.Tensor,
+                    n_kept: torch.Tensor, idx_c: torch.Tensor,
+                    ws: torch.Tensor, stream=None) -> None:
+    B, L = _idx_shape(tables, idx)
+    if skip_mask.numel() < B or kept_ids.numel() < B or n_kept.numel() < 1 \
+            or idx_c.numel() < idx.numel():
+        raise SlipstreamError("ss_filter_batch: an output tensor is too small")
+    _check(_lib.ss_filter_batch(
+        C.byref(tables.c), _dev_ptr(idx, torch.int32, "idx"), C.c_int32(B),
+        C.c_int32(L), C.c_int32(alpha),
+        _dev_ptr(skip_mask, torch.uint8, "skip_mask"),
+        _dev_ptr(kept_ids, torch.int32, "kept_ids"),
+        _dev_ptr(n_kept, torch.int32, "n_kept"),
+        _dev_ptr(idx_c, torch.int32, "idx_c"),
+        _dev_ptr(ws, torch.uint8, "ws"), C.c_size_t(ws.numel()),
+        _stream(stream)))
+
+
+def ss_embbag_forward(tables: Tables, idx: torch.Tensor,
+                      n_valid: Optional[torch.Tensor], out: torch.Tensor,
+                      stream=None) -> None:
+    Bcap, L = _idx_shape(tables, idx)
+    if out.numel() < tables.num_tables * Bcap * tables.dim:
+        raise SlipstreamError("ss_embbag_forward: out is too small")
+    _check(_lib.ss_embbag_forward(
+        C.byref(tables.c), _dev_ptr(idx, torch.int32, "idx"), C.c_int32(Bcap),
+        C.c_int32(L), _dev_ptr(n_valid, torch.int32, "n_valid"),
+        _dev_ptr(out, torch.float32, "out"), _stream(stream)))
+
+
+def ss_embbag_backward_update(tables: Tables, idx: torch.Tensor,
+                              n_valid: Optional[torch.Tensor],
+                              grad: torch.Tensor, lr: float, ws: torch.Tensor,
+                              stream=None) -> None:
+    Bcap, L = _idx_shape(tables, idx)
+    if grad.numel() < tables.num_tables * Bcap * tables.dim:
+        raise SlipstreamError("ss_embbag_backward_update: grad is too small")
+    _check(_lib.ss_embbag_backward_update(
+        C.byref(tables.c), _dev_ptr(idx, torch.int32, "idx"), C.c_int32(Bcap),
+        C.c_int32(L), _dev_ptr(n_valid, torch.int32, "n_valid"),
+        _dev_ptr(grad, torch.float32, "grad"), C.c_float(lr),
+        _dev_ptr(ws, torch.uint8, "ws"), C.c_size_t(ws.numel()),
+        _stream(stream)))
+
+
+class HotState:
+    """Hot row ids, their snapshots and the optional per-slot outputs of
+    ss_detect_stale, with the device pointer arrays the call needs."""
+
+    def __init__(self, tables: Tables, hot_ids: Sequence[torch.Tensor],
+                 diagnostics: bool = True):
+        dev = tables.device
+        self.hot_ids = list(hot_ids)
+        self.H = int(self.hot_ids[0].numel())
+        T = tables.num_tables
+        for h in self.hot_ids:
+            _dev_ptr(h, torch.int32, "hot_ids")
+            if h.numel() != self.H:
+                raise SlipstreamError("hot_ids: same H for every table")
+        self.snapshot = [torch.zeros(self.H, tables.dim, dtype=torch.float32,
+                                     device=dev) for _ in range(T)]
+        self.stale_count = torch.zeros(T, dtype=torch.int32, device=dev)
+        self._hptr = _ptr_table(self.hot_ids, dev)
+        self._sptr = _ptr_table(self.snapshot, dev)
+        self.stale_hot = self.drift = None
+        self._shptr = self._dptr = None
+        if diagnostics:
+            self.stale_hot = [torch.zeros(self.H, dtype=torch.uint8, device=dev)
+                              for _ in range(T)]
+            self.drift = [torch.zeros(self.H, dtype=torch.float64, device=dev)
+                          for _ in range(T)]
+            self._shptr = _ptr_table(self.stale_hot, dev)
+            self._dptr = _ptr_table(self.drift, dev)
+
+
+def ss_detect_stale(tables: Tables, hot: HotState, threshold: float,
+                    refresh_snapshot: bool = True, stream=None) -> None:
+    _check(_lib.ss_detect_stale(
+        C.byref(tables.c), C.c_void_p(hot._hptr.data_ptr()), C.c_int32(hot.H),
+        C.c_void_p(hot._sptr.data_ptr()), C.c_float(threshold),
+        C.c_int32(int(refresh_snapshot)),
+        C.c_void_p(None if hot._shptr is None else hot._shptr.data_ptr()),
+        C.c_void_p(None if hot._dptr is None else hot._dptr.data_ptr()),
+        _dev_ptr(hot.stale_count, torch.int32, "stale_count"), _stream(stream)))

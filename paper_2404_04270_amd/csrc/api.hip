@@ -1,0 +1,248 @@
+// C ABI of libslipstream: argument validation on the host, then launches.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <mutex>
+#include <vector>
+
+#include "ss_common.h"
+
+namespace ss {
+
+static thread_local char g_err[512] = "";
+
+int32_t fail(int32_t code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int32_t check_tables(const ss_tables *tb, const char *who)
+{
+    if (!tb) return fail(SS_ERR_INVALID_ARG, "%s: tables is NULL", who);
+    if (tb->num_tables < 1)
+        return fail(SS_ERR_INVALID_ARG, "%s: num_tables = %d", who, tb->num_tables);
+    if (tb->dim < 4 || tb->dim % 4 != 0 || tb->dim > 1024)
+        return fail(SS_ERR_INVALID_ARG,
+                    "%s: dim = %d (need a multiple of 4 in [4, 1024])", who, tb->dim);
+    if (tb->rows < 1 || tb->rows >= (1LL << 31))
+        return fail(SS_ERR_INVALID_ARG, "%s: rows = %lld (need 1 <= rows < 2^31)",
+                    who, (long long)tb->rows);
+    if (!tb->weights)
+        return fail(SS_ERR_INVALID_ARG, "%s: tables->weights is NULL", who);
+    return SS_OK;
+}
+
+int32_t check_launch(const char *who)
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return fail(SS_ERR_HIP, "%s: %s", who, hipGetErrorString(e));
+    return SS_OK;
+}
+
+// ---- optional per-kernel timing ---------------------------------------
+namespace {
+struct ProfRec {
+    const char *kernel;
+    hipEvent_t start, stop;
+};
+std::mutex g_prof_mu;
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+constexpr size_t kProfMax = 1u << 20;
+}  // namespace
+
+ProfScope::ProfScope(const char *kernel, hipStream_t s) : slot_(-1), s_(s)
+{
+    if (!g_prof_on) return;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (g_prof.size() >= kProfMax) return;
+    ProfRec r{kernel, nullptr, nullptr};
+    if (hipEventCreate(&r.start) != hipSuccess) return;
+    if (hipEventCreate(&r.stop) != hipSuccess) {
+        (void)hipEventDestroy(r.start);
+        return;
+    }
+    (void)hipEventRecord(r.start, s);
+    g_prof.push_back(r);
+    slot_ = (int)g_prof.size() - 1;
+}
+
+ProfScope::~ProfScope()
+{
+    if (slot_ < 0) return;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (slot_ < (int)g_prof.size()) (void)hipEventRecord(g_prof[slot_].stop, s_);
+}
+
+static int32_t check_batch(const char *who, const void *idx, int64_t B, int64_t L,
+                           int64_t T)
+{
+    if (!idx) return fail(SS_ERR_INVALID_ARG, "%s: idx is NULL", who);
+    if (B < 1) return fail(SS_ERR_INVALID_ARG, "%s: batch = %lld", who, (long long)B);
+    if (L < 1) return fail(SS_ERR_INVALID_ARG, "%s: L = %lld", who, (long long)L);
+    if (B * L >= (1LL << 31) || T * L >= (1LL << 31))
+        return fail(SS_ERR_UNSUPPORTED, "%s: B*L or T*L does not fit in int32", who);
+    return SS_OK;
+}
+
+static int32_t check_ws(const char *who, const void *ws, size_t have, size_t need)
+{
+    if (!ws) return fail(SS_ERR_WORKSPACE, "%s: workspace is NULL", who);
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0)
+        return fail(SS_ERR_WORKSPACE, "%s: workspace is not 256-byte aligned", who);
+    if (have < need)
+        return fail(SS_ERR_WORKSPACE, "%s: workspace has %zu bytes, needs %zu", who,
+                    have, need);
+    return SS_OK;
+}
+
+}  // namespace ss
+
+using namespace ss;
+
+extern "C" {
+
+const char *ss_last_error(void) { return g_err; }
+
+void ss_profile_enable(int32_t on)
+{
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_prof_on = on != 0;
+}
+
+int32_t ss_profile_report(char *buf, size_t buf_bytes)
+{
+    if (!buf || buf_bytes < 2)
+        return fail(SS_ERR_INVALID_ARG, "ss_profile_report: buffer missing");
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    struct Acc { const char *k; long n; double ms; };
+    std::vector<Acc> acc;
+    int32_t rc = SS_OK;
+    for (const ProfRec &r : g_prof) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.stop) != hipSuccess ||
+            hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess)
+            rc = fail(SS_ERR_HIP, "ss_profile_report: event query failed");
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+        size_t i = 0;
+        while (i < acc.size() && strcmp(acc[i].k, r.kernel) != 0) ++i;
+        if (i == acc.size()) acc.push_back(Acc{r.kernel, 0, 0.0});
+        acc[i].n += 1;
+        acc[i].ms += ms;
+    }
+    g_prof.clear();
+    size_t off = 0;
+    buf[0] = 0;
+    for (const Acc &a : acc) {
+        const int w = snprintf(buf + off, buf_bytes - off, "%s %ld %.6f\n", a.k,
+                               a.n, a.ms);
+        if (w < 0 || (size_t)w >= buf_bytes - off) {
+            buf[off] = 0;
+            return fail(SS_ERR_INVALID_ARG, "ss_profile_report: buffer too small");
+        }
+        off += (size_t)w;
+    }
+    return rc;
+}
+
+size_t ss_filter_batch_workspace_bytes(int32_t T, int32_t B, int32_t L)
+{
+    if (T < 1 || B < 1 || L < 1) return 0;
+    return filter_ws_bytes(T, B, L);
+}
+
+size_t ss_backward_workspace_bytes(int32_t T, int32_t Bcap, int32_t L, int32_t dim)
+{
+    if (T < 1 || Bcap < 1 || L < 1 || dim < 4 || dim % 4 != 0) return 0;
+    if ((int64_t)Bcap * L >= (1LL << 31) - 4096) return 0;
+    return backward_ws_bytes(T, Bcap, L, dim);
+}
+
+int32_t ss_filter_batch(const ss_tables *tables, const int32_t *idx, int32_t B,
+                        int32_t L, int32_t alpha, uint8_t *skip_mask,
+                        int32_t *kept_ids, int32_t *n_kept, int32_t *idx_c,
+                        void *ws, size_t ws_bytes, void *stream)
+{
+    const char *who = "ss_filter_batch";
+    int32_t rc = check_tables(tables, who);
+    if (rc) return rc;
+    rc = check_batch(who, idx, B, L, tables->num_tables);
+    if (rc) return rc;
+    if (!skip_mask || !kept_ids || !n_kept || !idx_c)
+        return fail(SS_ERR_INVALID_ARG, "%s: an output pointer is NULL", who);
+    if (idx_c == idx)
+        return fail(SS_ERR_INVALID_ARG, "%s: idx_c must not alias idx", who);
+    rc = check_ws(who, ws, ws_bytes,
+                  filter_ws_bytes(tables->num_tables, B, L));
+    if (rc) return rc;
+    return launch_filter(tables, idx, B, L, alpha, skip_mask, kept_ids, n_kept,
+                         idx_c, ws, static_cast<hipStream_t>(stream));
+}
+
+int32_t ss_embbag_forward(const ss_tables *tables, const int32_t *idx,
+                          int32_t Bcap, int32_t L, const int32_t *n_valid,
+                          float *out, void *stream)
+{
+    const char *who = "ss_embbag_forward";
+    int32_t rc = check_tables(tables, who);
+    if (rc) return rc;
+    rc = check_batch(who, idx, Bcap, L, tables->num_tables);
+    if (rc) return rc;
+    if (!out) return fail(SS_ERR_INVALID_ARG, "%s: out is NULL", who);
+    if (reinterpret_cast<uintptr_t>(out) % 16 != 0)
+        return fail(SS_ERR_INVALID_ARG, "%s: out is not 16-byte aligned", who);
+    return launch_forward(tables, idx, Bcap, L, n_valid, out,
+                          static_cast<hipStream_t>(stream));
+}
+
+int32_t ss_embbag_backward_update(const ss_tables *tables, const int32_t *idx,
+                                  int32_t Bcap, int32_t L,
+                                  const int32_t *n_valid, const float *grad,
+                                  float lr, void *ws, size_t ws_bytes,
+                                  void *stream)
+{
+    const char *who = "ss_embbag_backward_update";
+    int32_t rc = check_tables(tables, who);
+    if (rc) return rc;
+    rc = check_batch(who, idx, Bcap, L, tables->num_tables);
+    if (rc) return rc;
+    if ((int64_t)Bcap * L >= (1LL << 31) - 4096)
+        return fail(SS_ERR_UNSUPPORTED, "%s: Bcap*L too large", who);
+    if (!grad) return fail(SS_ERR_INVALID_ARG, "%s: grad is NULL", who);
+    if (reinterpret_cast<uintptr_t>(grad) % 16 != 0)
+        return fail(SS_ERR_INVALID_ARG, "%s: grad is not 16-byte aligned", who);
+    rc = check_ws(who, ws, ws_bytes,
+                  backward_ws_bytes(tables->num_tables, Bcap, L, tables->dim));
+    if (rc) return rc;
+    return launch_backward(tables, idx, Bcap, L, n_valid, grad, lr, ws,
+                           static_cast<hipStream_t>(stream));
+}
+
+int32_t ss_detect_stale(const ss_tables *tables, int32_t *const *hot_ids,
+                        int32_t H, float **snapshot, float threshold,
+                        int32_t refresh_snapshot, uint8_t **stale_hot,
+                        double **drift, uint32_t *stale_count, void *stream)
+{
+    const char *who = "ss_detect_stale";
+    int32_t rc = check_tables(tables, who);
+    if (rc) return rc;
+    if (!tables->stale_bits)
+        return fail(SS_ERR_INVALID_ARG, "%s: tables->stale_bits is NULL", who);
+    if (!hot_ids || !snapshot)
+        return fail(SS_ERR_INVALID_ARG, "%s: hot_ids or snapshot is NULL", who);
+    if (H < 1) return fail(SS_ERR_INVALID_ARG, "%s: H = %d", who, H);
+    if (threshold != threshold)
+        return fail(SS_ERR_INVALID_ARG, "%s: threshold is NaN", who);
+    return launch_detect(tables, hot_ids, H, snapshot, threshold,
+                         refresh_snapshot != 0, stale_hot, drift, stale_count,
+                         static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

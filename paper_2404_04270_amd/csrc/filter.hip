@@ -1,0 +1,138 @@
+// ss_filter_batch: input classifier (section 3.4, Eq. 6-8) plus a stable
+// stream compaction of the kept samples.
+//
+// Kernel 1 gives each sample one lane.  It walks the sample's T*L lookups,
+// probing one bit per lookup (the bitmaps are small and stay in L2), and stops
+// as soon as the verdict is fixed: the count reached alpha, or it can no
+// longer reach it.  With alpha = T*L almost every sample is decided by its
+// first non-stale lookup, so the kernel reads little more than idx[0][*][0].
+// A wavefront ballot plus popcount yields the number of kept samples per
+// workgroup.
+// Kernel 2 turns the per-workgroup counts into offsets (each workgroup sums the
+// counts before it: at most a few hundred values), ranks its kept samples with
+// ballot + popcount prefix sums, writes kept_ids in ascending order and copies
+// the index rows of the kept samples, table by table, to their compacted place.
+#include "ss_common.h"
+
+namespace ss {
+
+__global__ __launch_bounds__(kWG) void filter_flag_kernel(
+    const uint32_t *const *__restrict__ bits, const int32_t *__restrict__ idx,
+    int T, int B, int L, int alpha, uint8_t *__restrict__ skip_mask,
+    int32_t *__restrict__ block_kept)
+{
+    const int b = blockIdx.x * kWG + threadIdx.x;
+    bool keep = false;
+    if (b < B) {
+        const int total = T * L;
+        bool skip;
+        if (alpha <= 0) {
+            skip = true;
+        } else if (alpha > total || bits == nullptr) {
+            skip = false;
+        } else {
+            int c = 0, remaining = total;
+            bool decided = false;
+            for (int t = 0; t < T && !decided; ++t) {
+                const uint32_t *__restrict__ bt = bits[t];
+                const int32_t *__restrict__ ip = idx + ((int64_t)t * B + b) * L;
+                for (int l = 0; l < L; ++l) {
+                    if (bt) c += bit_set(bt, (uint32_t)ip[l]) ? 1 : 0;
+                    --remaining;
+                    if (c >= alpha || c + remaining < alpha) {
+                        decided = true;
+                        break;
+                    }
+                }
+            }
+            skip = c >= alpha;
+        }
+        skip_mask[b] = skip ? 1 : 0;
+        keep = !skip;
+    }
+    __shared__ int s_cnt[kWG / 64];
+    const unsigned long long bal = __ballot(keep);
+    if ((threadIdx.x & 63) == 0) s_cnt[threadIdx.x >> 6] = __popcll(bal);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int s = 0;
+        for (int w = 0; w < kWG / 64; ++w) s += s_cnt[w];
+        block_kept[blockIdx.x] = s;
+    }
+}
+
+__global__ __launch_bounds__(kWG) void filter_compact_kernel(
+    const int32_t *__restrict__ idx, int T, int B, int L,
+    const uint8_t *__restrict__ skip_mask,
+    const int32_t *__restrict__ block_kept, int32_t *__restrict__ kept_ids,
+    int32_t *__restrict__ n_kept, int32_t *__restrict__ idx_c)
+{
+    __shared__ int s_red[kWG / 64];
+    __shared__ int s_wbase[kWG / 64];
+    __shared__ int32_t s_list[kWG];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    // samples kept by the workgroups before this one
+    int part = 0;
+    for (int i = tid; i < (int)blockIdx.x; i += kWG) part += block_kept[i];
+    for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
+    if (lane == 0) s_red[wave] = part;
+
+    const int b = blockIdx.x * kWG + tid;
+    const bool keep = b < B && skip_mask[b] == 0;
+    const unsigned long long bal = __ballot(keep);
+    const int before = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) s_wbase[wave] = __popcll(bal);
+    __syncthreads();
+    int base = 0, wbase = 0, nk = 0;
+    for (int w = 0; w < kWG / 64; ++w) {
+        base += s_red[w];
+        if (w < wave) wbase += s_wbase[w];
+        nk += s_wbase[w];
+    }
+    if (keep) {
+        kept_ids[base + wbase + before] = b;
+        s_list[wbase + before] = b;
+    }
+    if (blockIdx.x == gridDim.x - 1 && tid == 0) *n_kept = base + nk;
+    __syncthreads();
+
+    // idx_c[t][base + k][:] = idx[t][s_list[k]][:]
+    const int per_table = nk * L;
+    for (int t = 0; t < T; ++t) {
+        const int32_t *__restrict__ src = idx + (int64_t)t * B * L;
+        int32_t *__restrict__ dst = idx_c + ((int64_t)t * B + base) * L;
+        for (int e = tid; e < per_table; e += kWG) {
+            const int k = e / L, l = e - k * L;
+            dst[e] = src[(int64_t)s_list[k] * L + l];
+        }
+    }
+}
+
+size_t filter_ws_bytes(int T, int B, int L)
+{
+    (void)T; (void)L;
+    const size_t blocks = ((size_t)B + kWG - 1) / kWG;
+    return align_up(blocks * sizeof(int32_t), 256);
+}
+
+int32_t launch_filter(const ss_tables *tb, const int32_t *idx, int B, int L,
+                      int alpha, uint8_t *skip_mask, int32_t *kept_ids,
+                      int32_t *n_kept, int32_t *idx_c, void *ws, hipStream_t s)
+{
+    const int blocks = (B + kWG - 1) / kWG;
+    int32_t *block_kept = static_cast<int32_t *>(ws);
+    {
+        ProfScope prof("filter_flag_kernel", s);
+    hipLaunchKernelGGL(filter_flag_kernel, dim3(blocks), dim3(kWG), 0, s,
+                       tb->stale_bits, idx, tb->num_tables, B, L, alpha,
+                       skip_mask, block_kept);
+    }
+    ProfScope prof("filter_compact_kernel", s);
+    hipLaunchKernelGGL(filter_compact_kernel, dim3(blocks), dim3(kWG), 0, s,
+                       idx, tb->num_tables, B, L, skip_mask, block_kept,
+                       kept_ids, n_kept, idx_c);
+    return check_launch("ss_filter_batch");
+}
+
+}  // namespace ss

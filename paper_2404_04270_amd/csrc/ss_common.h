@@ -1,0 +1,88 @@
+// Internal helpers shared by the kernels of libslipstream (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "slipstream.h"
+
+namespace ss {
+
+constexpr int kWG = 256;                    // threads per workgroup (4 wavefronts)
+constexpr uint32_t kNoRow = 0xFFFFFFFFu;    // sentinel key: "no lookup here"
+
+// Records the calling thread's error text; returns `code`.
+int32_t fail(int32_t code, const char *fmt, ...);
+// Common checks of an ss_tables argument.
+int32_t check_tables(const ss_tables *tb, const char *who);
+// hipGetLastError() after a launch -> SS_OK / SS_ERR_HIP.
+int32_t check_launch(const char *who);
+
+// Optional per-kernel timing (ss_profile_enable): brackets the launches made
+// inside its scope with a pair of HIP events on the launch stream.
+class ProfScope {
+public:
+    ProfScope(const char *kernel, hipStream_t s);
+    ~ProfScope();
+private:
+    int slot_;
+    hipStream_t s_;
+};
+
+// Lanes that cooperate on one row: one float4 per lane, a power of two <= 64.
+inline int lanes_per_row(int dim)
+{
+    int d4 = dim / 4, g = 1;
+    while (g < d4 && g < 64) g <<= 1;
+    return g;
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Calls f.template operator()<G>() for the power of two G in [1, 64].
+#define SS_DISPATCH_G(g, ...)                                   \
+    switch (g) {                                                \
+    case 1: { constexpr int G = 1; __VA_ARGS__; } break;        \
+    case 2: { constexpr int G = 2; __VA_ARGS__; } break;        \
+    case 4: { constexpr int G = 4; __VA_ARGS__; } break;        \
+    case 8: { constexpr int G = 8; __VA_ARGS__; } break;        \
+    case 16: { constexpr int G = 16; __VA_ARGS__; } break;      \
+    case 32: { constexpr int G = 32; __VA_ARGS__; } break;      \
+    default: { constexpr int G = 64; __VA_ARGS__; } break;      \
+    }
+
+__device__ __forceinline__ int clamp_valid(const int32_t *n_valid, int cap)
+{
+    if (!n_valid) return cap;
+    int n = *n_valid;
+    return n < 0 ? 0 : (n > cap ? cap : n);
+}
+
+// w - lr * g, element by element
+__device__ __forceinline__ float4 sgd(float4 w, float4 g, float lr)
+{
+    return make_float4(w.x - lr * g.x, w.y - lr * g.y, w.z - lr * g.z,
+                       w.w - lr * g.w);
+}
+
+__device__ __forceinline__ bool bit_set(const uint32_t *bits, uint32_t r)
+{
+    return (bits[r >> 5] >> (r & 31)) & 1u;
+}
+
+// Entry points of the kernel families (each in its own .hip file).
+int32_t launch_forward(const ss_tables *tb, const int32_t *idx, int Bcap, int L,
+                       const int32_t *n_valid, float *out, hipStream_t s);
+int32_t launch_filter(const ss_tables *tb, const int32_t *idx, int B, int L,
+                      int alpha, uint8_t *skip_mask, int32_t *kept_ids,
+                      int32_t *n_kept, int32_t *idx_c, void *ws, hipStream_t s);
+int32_t launch_detect(const ss_tables *tb, int32_t *const *hot_ids, int H,
+                      float **snapshot, float threshold, int refresh,
+                      uint8_t **stale_hot, double **drift,
+                      uint32_t *stale_count, hipStream_t s);
+int32_t launch_backward(const ss_tables *tb, const int32_t *idx, int Bcap, int L,
+                        const int32_t *n_valid, const float *grad, float lr,
+                        void *ws, hipStream_t s);
+size_t backward_ws_bytes(int T, int Bcap, int L, int dim);
+size_t filter_ws_bytes(int T, int B, int L);
+
+}  // namespace ss

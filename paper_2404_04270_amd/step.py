@@ -1,0 +1,67 @@
+"""One training iteration of the embedding side, enqueued on the GPU.
+
+Order (Algorithm 1 of the paper): filter_batch -> forward -> (gradients of the
+kept samples arrive from the dense part of the model) -> backward_update ->
+every K iterations: the first time capture the snapshot (the first period is
+the warm-up of section 3.1.1), afterwards detect_stale with a snapshot refresh.
+
+This class only owns buffers and issues the four library calls in order;
+nothing here synchronises with the host.
+"""
+from __future__ import annotations
+
+from typing import Optional, Sequence
+
+import torch
+
+from . import binding as B
+
+
+class EmbeddingStep:
+    def __init__(self, weights: Sequence[torch.Tensor],
+                 hot_ids: Sequence[torch.Tensor], batch: int, bag: int,
+                 lr: float, threshold: float, snapshot_every: int,
+                 alpha: Optional[int] = None, diagnostics: bool = True):
+        self.tables = B.Tables(weights)
+        self.bits = self.tables.new_bits()
+        self.hot = B.HotState(self.tables, hot_ids, diagnostics=diagnostics)
+        T, D = self.tables.num_tables, self.tables.dim
+        dev = self.tables.device
+        self.batch, self.bag = batch, bag
+        self.lr, self.threshold, self.K = float(lr), float(threshold), int(snapshot_every)
+        self.alpha = T * bag if alpha is None else int(alpha)
+        self.skip_mask = torch.zeros(batch, dtype=torch.uint8, device=dev)
+        self.kept_ids = torch.zeros(batch, dtype=torch.int32, device=dev)
+        self.n_kept = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.idx_c = torch.zeros(T, batch, bag, dtype=torch.int32, device=dev)
+        self.pooled = torch.zeros(T, batch, D, dtype=torch.float32, device=dev)
+        self.ws_filter = torch.empty(
+            max(256, B.ss_filter_batch_workspace_bytes(T, batch, bag)),
+            dtype=torch.uint8, device=dev)
+        self.ws_backward = torch.empty(
+            B.ss_backward_workspace_bytes(T, batch, bag, D),
+            dtype=torch.uint8, device=dev)
+        self.it = 0
+        self.have_snapshot = False
+
+    def filter_forward(self, idx: torch.Tensor) -> None:
+        """Classify and compact the batch, then pool the kept samples."""
+        B.ss_filter_batch(self.tables, idx, self.alpha, self.skip_mask,
+                          self.kept_ids, self.n_kept, self.idx_c, self.ws_filter)
+        B.ss_embbag_forward(self.tables, self.idx_c, self.n_kept, self.pooled)
+
+    def backward(self, grad_c: torch.Tensor) -> bool:
+        """grad_c: fp32 [T, B, D], row j = gradient of the j-th kept sample.
+        Returns True if this iteration ended with a detect pass."""
+        B.ss_embbag_backward_update(self.tables, self.idx_c, self.n_kept, grad_c,
+                                    self.lr, self.ws_backward)
+        detected = False
+        if (self.it + 1) % self.K == 0:
+            if not self.have_snapshot:
+                B.ss_detect_stale(self.tables, self.hot, 0.0, True)
+                self.have_snapshot = True
+            else:
+                B.ss_detect_stale(self.tables, self.hot, self.threshold, True)
+                detected = True
+        self.it += 1
+        return detected

@@ -125,6 +125,18 @@ class Workload:
         w -= np.float32(c.init_bound)
         return w
 
+    def weights_device(self, table: int, device):
+        """Same law as `weights`, drawn on the device (for tables too large to
+        draw on the host in reasonable time).  A different stream of numbers
+        than `weights`: callers that compare against the CPU copy it back."""
+        import torch
+        c = self.cfg
+        gen = torch.Generator(device=device)
+        gen.manual_seed(c.seed * 1000 + table)
+        w = torch.empty((c.rows, c.dim), dtype=torch.float32, device=device)
+        w.uniform_(-c.init_bound, c.init_bound, generator=gen)
+        return w
+
     def grads(self, it: int) -> np.ndarray:
         """fp32 [T, B, D]: gradient of the loss w.r.t. each pooled vector."""
         c = self.cfg

@@ -1,0 +1,378 @@
+"""GPU parity: every call of the C ABI against the CPU oracle on the same
+seeded inputs, element by element.
+
+Bars: bit-exact for skip masks, kept ids, compacted indices, stale verdicts and
+bitmaps (rows whose drift lies within 1e-6 relative of the threshold are left
+out of the verdict check); rtol 1e-5 / atol 1e-6 for fp32 pooled outputs and
+updated weights.  Sizes span several tiles, ragged tails, both sort paths and
+all strip lengths of the update kernel.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle.protocol import OracleRun
+from paper_2404_04270_amd import workload as wl
+
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 1e-5, 1e-6
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2404_04270_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def dev():
+    return torch.device("cuda:0")
+
+
+def to_dev(arrs, dev):
+    return [torch.from_numpy(np.ascontiguousarray(a)).to(dev) for a in arrs]
+
+
+def bits_to_dev(bits, dev):
+    return [torch.from_numpy(b.view(np.int32).copy()).to(dev) for b in bits]
+
+
+def bits_from_dev(bits):
+    return [b.cpu().numpy().view(np.uint32) for b in bits]
+
+
+def rand_tables(rng, T, R, D):
+    return [rng.uniform(-0.05, 0.05, (R, D)).astype(np.float32) for _ in range(T)]
+
+
+def zipf_idx(rng, T, B, L, R, a=1.2):
+    return ((rng.zipf(a, (T, B, L)) - 1) % R).astype(np.int32)
+
+
+def random_bits(rng, T, R, frac):
+    out = []
+    for _ in range(T):
+        flags = rng.random(R) < frac
+        pad = np.zeros((R + 31) // 32 * 32, dtype=np.uint8)
+        pad[:R] = flags
+        out.append(np.packbits(pad, bitorder="little").view(np.uint32).copy())
+    return out
+
+
+# --------------------------------------------------------------- forward
+@pytest.mark.parametrize("T,R,D,Bc,L,nv", [
+    (3, 1000, 16, 700, 1, None),     # one-hot, ragged tile
+    (2, 5000, 64, 1025, 1, 999),     # n_valid below capacity
+    (2, 3000, 128, 333, 20, None),   # multi-hot with duplicates
+    (1, 200, 4, 70, 3, 0),           # nothing valid
+    (2, 500, 48, 130, 9, 77),        # dim not a power of two, unroll tail
+    (1, 300, 260, 40, 11, None),     # dim above 256: several float4 per lane
+])
+def test_forward_matches_oracle(B, dev, T, R, D, Bc, L, nv):
+    rng = np.random.default_rng(100 + D + L)
+    W = rand_tables(rng, T, R, D)
+    idx = zipf_idx(rng, T, Bc, L, R)
+    ref = oracle.embbag_forward(W, idx, nv)
+    tb = B.Tables(to_dev(W, dev))
+    out = torch.full((T, Bc, D), 7.0, dtype=torch.float32, device=dev)
+    n_valid = None if nv is None else torch.tensor([nv], dtype=torch.int32, device=dev)
+    B.ss_embbag_forward(tb, torch.from_numpy(idx).to(dev), n_valid, out)
+    got = out.cpu().numpy()
+    n = Bc if nv is None else nv
+    if L == 1:
+        assert np.array_equal(got[:, :n], ref[:, :n])          # pure gather
+    else:
+        np.testing.assert_allclose(got[:, :n], ref[:, :n], rtol=RTOL, atol=ATOL)
+    assert np.all(got[:, n:] == 7.0)                           # tail untouched
+
+
+# ---------------------------------------------------------------- filter
+@pytest.mark.parametrize("T,R,Bn,L,frac", [
+    (3, 2000, 1000, 1, 0.5), (8, 500, 257, 2, 0.9), (2, 100, 5, 20, 0.97),
+    (26, 4000, 4100, 1, 0.8),
+])
+def test_filter_matches_oracle(B, dev, T, R, Bn, L, frac):
+    rng = np.random.default_rng(200 + T + L)
+    idx = zipf_idx(rng, T, Bn, L, R)
+    bits = random_bits(rng, T, R, frac)
+    W = to_dev(rand_tables(rng, T, R, 4), dev)
+    tb = B.Tables(W, bits_to_dev(bits, dev))
+    ws = torch.empty(max(256, B.ss_filter_batch_workspace_bytes(T, Bn, L)),
+                     dtype=torch.uint8, device=dev)
+    idx_d = torch.from_numpy(idx).to(dev)
+    for alpha in sorted({0, 1, T * L // 2, T * L - 1, T * L, T * L + 1}):
+        skip = torch.zeros(Bn, dtype=torch.uint8, device=dev)
+        kept = torch.full((Bn,), -1, dtype=torch.int32, device=dev)
+        nk = torch.full((1,), -1, dtype=torch.int32, device=dev)
+        idx_c = torch.full((T, Bn, L), -1, dtype=torch.int32, device=dev)
+        B.ss_filter_batch(tb, idx_d, alpha, skip, kept, nk, idx_c, ws)
+        r_skip, r_kept, r_idx_c = oracle.filter_batch(R, bits, idx, alpha)
+        n = int(nk.item())
+        assert n == len(r_kept), alpha
+        assert np.array_equal(skip.cpu().numpy(), r_skip)
+        assert np.array_equal(kept.cpu().numpy()[:n], r_kept)
+        assert np.all(kept.cpu().numpy()[n:] == -1)
+        got_c = idx_c.cpu().numpy()
+        assert np.array_equal(got_c[:, :n], r_idx_c[:, :n])
+        assert np.all(got_c[:, n:] == -1)
+
+
+def test_filter_without_bitmaps_keeps_everything(B, dev):
+    T, R, Bn, L = 4, 100, 300, 2
+    rng = np.random.default_rng(210)
+    idx = zipf_idx(rng, T, Bn, L, R)
+    tb = B.Tables(to_dev(rand_tables(rng, T, R, 4), dev))
+    ws = torch.empty(256, dtype=torch.uint8, device=dev)
+    skip = torch.ones(Bn, dtype=torch.uint8, device=dev)
+    kept = torch.zeros(Bn, dtype=torch.int32, device=dev)
+    nk = torch.zeros(1, dtype=torch.int32, device=dev)
+    idx_c = torch.zeros((T, Bn, L), dtype=torch.int32, device=dev)
+    B.ss_filter_batch(tb, torch.from_numpy(idx).to(dev), T * L, skip, kept, nk, idx_c, ws)
+    assert int(nk.item()) == Bn and not skip.any()
+    assert np.array_equal(kept.cpu().numpy(), np.arange(Bn))
+    assert np.array_equal(idx_c.cpu().numpy(), idx)
+
+
+# ---------------------------------------------------------------- detect
+def run_detect(B, dev, W, bits, hot, snap, thr, refresh):
+    tb = B.Tables(to_dev(W, dev), bits_to_dev(bits, dev))
+    hs = B.HotState(tb, to_dev(hot, dev))
+    for t in range(len(W)):
+        hs.snapshot[t].copy_(torch.from_numpy(snap[t]))
+    B.ss_detect_stale(tb, hs, thr, refresh)
+    torch.cuda.synchronize()
+    return tb, hs
+
+
+@pytest.mark.parametrize("T,R,D,H,thr", [
+    (3, 5000, 16, 700, 2e-3), (2, 3000, 64, 333, 4e-3), (2, 4000, 128, 65, 6e-3),
+    (1, 900, 260, 50, 8e-3), (2, 2000, 4, 1000, 1e-3),
+])
+def test_detect_matches_oracle(B, dev, T, R, D, H, thr):
+    rng = np.random.default_rng(300 + D)
+    W = rand_tables(rng, T, R, D)
+    hot = [np.sort(rng.choice(R, H, replace=False)).astype(np.int32) for _ in range(T)]
+    # snapshot = rows plus noise whose norm straddles the threshold
+    snap = []
+    for t in range(T):
+        scale = rng.uniform(0, 2 * thr / math.sqrt(D), (H, 1))
+        snap.append((W[t][hot[t]] + scale * rng.choice([-1.0, 1.0], (H, D))).astype(np.float32))
+    bits0 = random_bits(rng, T, R, 0.01)
+    for refresh in (False, True):
+        bits_ref = [b.copy() for b in bits0]
+        snap_ref = [s.copy() for s in snap]
+        r_sh, r_dr, r_cnt = oracle.detect_stale(W, bits_ref, hot, snap_ref, thr, refresh)
+        tb, hs = run_detect(B, dev, W, bits0, hot, snap, thr, refresh)
+        for t in range(T):
+            dr = hs.drift[t].cpu().numpy()
+            np.testing.assert_allclose(dr, r_dr[t], rtol=1e-12, atol=0)
+            graded = np.abs(r_dr[t] - thr) > 1e-6 * thr
+            assert graded.sum() > 0.9 * H
+            sh = hs.stale_hot[t].cpu().numpy()
+            assert np.array_equal(sh[graded], r_sh[t][graded])
+            assert 0 < r_sh[t].sum() < H
+            if graded.all():
+                assert np.array_equal(bits_from_dev(tb.bits)[t], bits_ref[t])
+                assert int(hs.stale_count[t].item()) == int(r_cnt[t])
+            assert np.array_equal(hs.snapshot[t].cpu().numpy(), snap_ref[t])
+
+
+def test_detect_threshold_zero_captures_and_infinity_flags_all(B, dev):
+    rng = np.random.default_rng(310)
+    T, R, D, H = 2, 1000, 16, 100
+    W = rand_tables(rng, T, R, D)
+    hot = [np.sort(rng.choice(R, H, replace=False)).astype(np.int32) for _ in range(T)]
+    snap = [np.zeros((H, D), np.float32) for _ in range(T)]
+    bits = [np.zeros((R + 31) // 32, np.uint32) for _ in range(T)]
+    tb, hs = run_detect(B, dev, W, bits, hot, snap, 0.0, True)      # capture
+    for t in range(T):
+        assert not bits_from_dev(tb.bits)[t].any()
+        assert np.array_equal(hs.snapshot[t].cpu().numpy(), W[t][hot[t]])
+        assert int(hs.stale_count[t].item()) == 0
+    B.ss_detect_stale(tb, hs, math.inf, False)
+    ref_bits = [b.copy() for b in bits]
+    oracle.detect_stale(W, ref_bits, hot, [W[t][hot[t]].copy() for t in range(T)],
+                        math.inf, False)
+    for t in range(T):
+        assert np.array_equal(bits_from_dev(tb.bits)[t], ref_bits[t])
+        assert int(hs.stale_count[t].item()) == H
+
+
+# -------------------------------------------------------------- backward
+BACKWARD_CASES = [
+    # T, R, D, Bcap, L, n_valid, stale fraction, zipf a
+    (3, 1000, 16, 700, 1, None, 0.0, 1.2),      # LDS sort, strip 4, D=16
+    (2, 50000, 64, 8192, 1, None, 0.1, 1.2),    # LDS sort at 8192 lookups
+    (2, 3000, 128, 300, 20, 250, 0.2, 1.2),     # multi-hot, ragged n_valid
+    (1, 100, 64, 4096, 4, None, 0.0, 1.05),     # few rows: runs cross workgroups
+    (2, 1 << 20, 64, 40000, 1, 39999, 0.05, 1.1),   # global radix sort path
+    (1, 70000, 128, 5000, 20, None, 0.1, 1.2),  # global sort + heavy duplicates
+    (26, 100000, 64, 8192, 1, None, 0.0, 1.2),  # many workgroups: strip 8
+    (8, 200000, 128, 4096, 20, None, 0.02, 1.2),  # strip 16, global sort
+    (1, 3, 16, 3000, 1, None, 0.0, 1.5),        # three rows only
+    (1, 500, 48, 200, 3, None, 0.3, 1.3),       # dim not a power of two
+    (1, 300, 260, 100, 2, None, 0.3, 1.3),      # dim above 256
+    (2, 400, 4, 5000, 1, 0, 0.0, 1.2),          # nothing valid
+]
+
+
+@pytest.mark.parametrize("T,R,D,Bc,L,nv,stale,za", BACKWARD_CASES)
+def test_backward_update_matches_oracle(B, dev, T, R, D, Bc, L, nv, stale, za):
+    rng = np.random.default_rng(400 + T * 7 + D + L + Bc)
+    W = rand_tables(rng, T, R, D)
+    idx = zipf_idx(rng, T, Bc, L, R, za)
+    grad = rng.normal(0, 0.01, (T, Bc, D)).astype(np.float32)
+    bits = random_bits(rng, T, R, stale) if stale > 0 else None
+    if bits is not None:
+        for b in bits:
+            b[0] |= np.uint32(3)               # freeze the two hottest rows too
+    ref = [w.copy() for w in W]
+    oracle.embbag_backward_update(ref, bits, idx, grad, 0.01, nv)
+
+    tb = B.Tables(to_dev(W, dev), None if bits is None else bits_to_dev(bits, dev))
+    ws = torch.empty(B.ss_backward_workspace_bytes(T, Bc, L, D), dtype=torch.uint8, device=dev)
+    ws.fill_(0xAB)                              # contents on entry are ignored
+    n_valid = None if nv is None else torch.tensor([nv], dtype=torch.int32, device=dev)
+    idx_d = torch.from_numpy(idx).to(dev)
+    grad_d = torch.from_numpy(grad).to(dev)
+    B.ss_embbag_backward_update(tb, idx_d, n_valid, grad_d, 0.01, ws)
+    got = [w.cpu().numpy() for w in tb.weights]
+    n = Bc if nv is None else nv
+    for t in range(T):
+        np.testing.assert_allclose(got[t], ref[t], rtol=RTOL, atol=ATOL)
+        touched = np.zeros(R, bool)
+        touched[idx[t, :n].reshape(-1)] = True
+        if bits is not None:
+            flags = np.unpackbits(bits[t].view(np.uint8), bitorder="little")[:R].astype(bool)
+            touched &= ~flags
+            assert np.array_equal(bits_from_dev(tb.bits)[t], bits[t])
+        # rows that must not move are bit-identical, rows that must move did
+        assert np.array_equal(got[t][~touched], W[t][~touched])
+        if touched.any():
+            moved = np.any(got[t][touched] != W[t][touched], axis=1)
+            assert moved.mean() > 0.99
+
+    # same call again on fresh tables: bit-identical (fixed summation order)
+    tb2 = B.Tables(to_dev(W, dev), None if bits is None else bits_to_dev(bits, dev))
+    ws.fill_(0x11)
+    B.ss_embbag_backward_update(tb2, idx_d, n_valid, grad_d, 0.01, ws)
+    for t in range(T):
+        assert torch.equal(tb2.weights[t], tb.weights[t])
+
+
+def test_backward_closed_form_heavy_row(B, dev):
+    # one row hit by every lookup of a large batch: dW = -lr * L * sum_j g_j
+    T, R, D, Bc, L = 1, 64, 64, 20000, 2
+    W = [np.ones((R, D), np.float32)]
+    idx = np.full((T, Bc, L), 17, dtype=np.int32)
+    rng = np.random.default_rng(450)
+    grad = rng.normal(0, 0.01, (T, Bc, D)).astype(np.float32)
+    tb = B.Tables(to_dev(W, dev))
+    ws = torch.empty(B.ss_backward_workspace_bytes(T, Bc, L, D), dtype=torch.uint8, device=dev)
+    B.ss_embbag_backward_update(tb, torch.from_numpy(idx).to(dev), None,
+                                torch.from_numpy(grad).to(dev), 0.5, ws)
+    got = tb.weights[0].cpu().numpy()
+    exact = 1.0 - 0.5 * L * grad[0].astype(np.float64).sum(axis=0)
+    np.testing.assert_allclose(got[17], exact, rtol=RTOL, atol=ATOL)
+    assert np.all(np.delete(got, 17, axis=0) == 1.0)
+
+
+# ------------------------------------------------------- whole protocol
+def run_lockstep(B, dev, cfg, n_iters, threshold, n_hot=None):
+    """Oracle and GPU side by side; returns the number of borderline overrides."""
+    from paper_2404_04270_amd.step import EmbeddingStep
+    w = wl.Workload(cfg)
+    idx = w.indices(0, n_iters)
+    hot = wl.hot_set(idx, cfg.rows, n_hot or cfg.hot_rows)
+    W0 = [w.weights(t) for t in range(cfg.num_tables)]
+    ref = OracleRun([x.copy() for x in W0], hot, cfg.lr, threshold, cfg.snapshot_every)
+    gpu = EmbeddingStep(to_dev(W0, dev), to_dev(hot, dev), cfg.batch, cfg.bag,
+                        cfg.lr, threshold, cfg.snapshot_every)
+    overrides = skipped = detects = 0
+    for it in range(n_iters):
+        g = w.grads(it)
+        r = ref.step(idx[it], g)
+        gpu.filter_forward(torch.from_numpy(idx[it]).to(dev))
+        nk = int(gpu.n_kept.item())
+        assert nk == r["n_kept"], it
+        assert np.array_equal(gpu.skip_mask.cpu().numpy(), r["skip"]), it
+        assert np.array_equal(gpu.kept_ids.cpu().numpy()[:nk], r["kept"]), it
+        assert np.array_equal(gpu.idx_c.cpu().numpy()[:, :nk], r["idx_c"][:, :nk]), it
+        np.testing.assert_allclose(gpu.pooled.cpu().numpy()[:, :nk], r["pooled"][:, :nk],
+                                   rtol=RTOL, atol=ATOL)
+        skipped += cfg.batch - nk
+        g_c = np.zeros_like(g)
+        g_c[:, :nk] = g[:, r["kept"]]
+        detected = gpu.backward(torch.from_numpy(g_c).to(dev))
+        assert detected == r["detected"]
+        if detected:
+            detects += 1
+            r_sh, r_dr, _ = ref.last_detect
+            for t in range(cfg.num_tables):
+                sh = gpu.hot.stale_hot[t].cpu().numpy()
+                if math.isfinite(threshold) and threshold > 0:
+                    border = np.abs(r_dr[t] - threshold) <= 1e-6 * threshold
+                else:
+                    border = np.zeros_like(sh, dtype=bool)
+                assert np.array_equal(sh[~border], r_sh[t][~border]), (it, t)
+                diff = np.flatnonzero(sh != r_sh[t])
+                overrides += diff.size
+                if diff.size:        # keep the two trajectories in lock step
+                    gpu.bits[t].copy_(torch.from_numpy(ref.bits[t].view(np.int32)))
+                assert np.array_equal(bits_from_dev(gpu.bits)[t], ref.bits[t]), (it, t)
+    for t in range(cfg.num_tables):
+        np.testing.assert_allclose(gpu.tables.weights[t].cpu().numpy(), ref.W[t],
+                                   rtol=RTOL, atol=ATOL)
+    n_stale = sum(int(np.unpackbits(b.view(np.uint8)).sum()) for b in ref.bits)
+    return dict(overrides=overrides, skipped=skipped, detects=detects, stale=n_stale)
+
+
+def test_protocol_config1_full_run(B, dev):
+    cfg = wl.CONFIGS[1]
+    s = run_lockstep(B, dev, cfg, cfg.iters, cfg.threshold)
+    assert s["detects"] == cfg.iters // cfg.snapshot_every - 1
+    assert s["stale"] > 0                       # this workload does flag rows
+    assert s["overrides"] == 0
+
+
+def test_protocol_config1_threshold_infinity_skips_all_hot_samples(B, dev):
+    cfg = wl.CONFIGS[1].scaled(zipf_alpha=1.6, num_tables=3)
+    s = run_lockstep(B, dev, cfg, 50, math.inf)
+    assert s["stale"] == cfg.num_tables * cfg.hot_rows
+    assert s["skipped"] > 0
+
+
+def test_protocol_config2_prefix(B, dev):
+    cfg = wl.CONFIGS[2]
+    s = run_lockstep(B, dev, cfg, 160, cfg.threshold)
+    assert s["detects"] == 2 and s["overrides"] == 0
+
+
+def test_protocol_multihot_small(B, dev):
+    cfg = wl.CONFIGS[4].scaled(rows=20000, batch=256, snapshot_every=5, hot_frac=0.005,
+                               threshold=2e-3)
+    s = run_lockstep(B, dev, cfg, 24, cfg.threshold)
+    assert s["detects"] == 3
+
+
+# -------------------------------------------------------- error handling
+def test_invalid_arguments_are_rejected_before_launch(B, dev):
+    rng = np.random.default_rng(500)
+    tb = B.Tables(to_dev(rand_tables(rng, 2, 100, 16), dev))
+    idx = torch.zeros((2, 8, 1), dtype=torch.int32, device=dev)
+    out = torch.zeros((2, 8, 16), dtype=torch.float32, device=dev)
+    small = torch.empty(256, dtype=torch.uint8, device=dev)
+    with pytest.raises(B.SlipstreamError, match="workspace"):
+        B.ss_embbag_backward_update(tb, idx, None, out, 0.01, small)
+    hs = B.HotState(tb, [torch.zeros(4, dtype=torch.int32, device=dev)] * 2)
+    with pytest.raises(B.SlipstreamError, match="stale_bits"):
+        B.ss_detect_stale(tb, hs, 1e-3, True)
+    bad = B.Tables(to_dev(rand_tables(rng, 1, 10, 6), dev))
+    with pytest.raises(B.SlipstreamError, match="dim"):
+        B.ss_embbag_forward(bad, torch.zeros((1, 2, 1), dtype=torch.int32, device=dev),
+                            None, torch.zeros((1, 2, 6), dtype=torch.float32, device=dev))
+    torch.cuda.synchronize()
