@@ -30,7 +30,12 @@ def parse():
     ap.add_argument("--threshold", type=float, default=None,
                     help="drift threshold T (default: the config's; inf freezes all hot rows)")
     ap.add_argument("--ring", type=int, default=16, help="distinct batches cycled through")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="issue everything on one stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 1 GiB device copy (calibrates rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters against a known size)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     return ap.parse_args()
 
@@ -70,9 +75,18 @@ def main():
     n_grads = 4
     grads = [torch.from_numpy(w.grads(k)).to(dev) for k in range(n_grads)]
     step = EmbeddingStep(weights, [torch.from_numpy(h).to(dev) for h in hot],
-                         Bn, L, cfg.lr, thr, cfg.snapshot_every, diagnostics=False)
+                         Bn, L, cfg.lr, thr, cfg.snapshot_every, diagnostics=False,
+                         overlap=not args.no_overlap)
     torch.cuda.synchronize()
     setup_s = time.time() - t0
+
+    if args.copy_probe:
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
 
     def run(n, start_it):
         for k in range(n):
@@ -125,7 +139,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "tables": T, "rows": R, "dim": D, "batch": Bn,
                    "bag": L, "zipf_alpha": cfg.zipf_alpha, "threshold": thr,
-                   "snapshot_every": cfg.snapshot_every, "ring": args.ring},
+                   "snapshot_every": cfg.snapshot_every, "ring": args.ring,
+                   "streams": 1 if args.no_overlap else 2},
         "roofline": roofline,
         "whole_step": {"algorithmic_bytes": step_bytes,
                        "achieved_GBs": step_bytes / (ms_per_step * 1e-3) / 1e9,

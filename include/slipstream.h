@@ -49,7 +49,7 @@ enum {
 const char *ss_last_error(void);
 
 typedef struct {
-    int32_t num_tables;    /* T >= 1 */
+    int32_t num_tables;    /* 1 <= T <= 65535 */
     int32_t dim;           /* d: floats per row, multiple of 4, <= 1024 */
     int64_t rows;          /* m: rows of every table, 1 <= rows < 2^31 */
     float **weights;       /* device array of T device pointers, each [rows][dim] */
@@ -122,6 +122,25 @@ int32_t ss_embbag_backward_update(const ss_tables *tables, const int32_t *idx,
                                   void *stream);
 size_t ss_backward_workspace_bytes(int32_t T, int32_t Bcap, int32_t L,
                                    int32_t dim);
+
+/*
+ * The same update in two halves, for callers that want to overlap them with
+ * other work.  ss_embbag_backward_prepare groups the lookups of every table by
+ * row (and drops the lookups of stale rows); it depends only on idx, n_valid
+ * and the stale bitmaps, not on the gradients, so it can run on a second stream
+ * next to the forward pass and the dense part of the model.
+ * ss_embbag_backward_apply then sums the gradients per row and applies the SGD
+ * step.  ss_embbag_backward_update(...) is exactly prepare(...) followed by
+ * apply(...) on one stream.  The caller orders the two halves (same stream, or
+ * an event), passes the same tables, Bcap, L and workspace to both, and leaves
+ * the workspace and the bitmaps untouched in between.
+ */
+int32_t ss_embbag_backward_prepare(const ss_tables *tables, const int32_t *idx,
+                                   int32_t Bcap, int32_t L, const int32_t *n_valid,
+                                   void *ws, size_t ws_bytes, void *stream);
+int32_t ss_embbag_backward_apply(const ss_tables *tables, int32_t Bcap, int32_t L,
+                                 const float *grad, float lr, void *ws,
+                                 size_t ws_bytes, void *stream);
 
 /*
  * Snapshot comparison (section 3.1.2 snapshots; Eq. 1 and Eq. 5).  For hot

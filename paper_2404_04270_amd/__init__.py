@@ -12,6 +12,7 @@ _BINDING_NAMES = (
     "ss_detect_stale", "ss_filter_batch", "ss_filter_batch_workspace_bytes",
     "ss_backward_workspace_bytes", "ss_last_error", "SlipstreamError",
     "ss_profile_enable", "ss_profile_report", "HotState",
+    "ss_embbag_backward_prepare", "ss_embbag_backward_apply",
     "EmbeddingStep", "lib_path",
 )
 

@@ -19,7 +19,7 @@ SYMBOLS = (
     "ss_last_error", "ss_filter_batch", "ss_filter_batch_workspace_bytes",
     "ss_embbag_forward", "ss_embbag_backward_update",
     "ss_backward_workspace_bytes", "ss_detect_stale", "ss_profile_enable",
-    "ss_profile_report",
+    "ss_profile_report", "ss_embbag_backward_prepare", "ss_embbag_backward_apply",
 )
 
 
@@ -46,7 +46,8 @@ def _load():
     lib.ss_profile_enable.restype = None
     for n in ("ss_filter_batch", "ss_embbag_forward",
               "ss_embbag_backward_update", "ss_detect_stale",
-              "ss_profile_report"):
+              "ss_profile_report", "ss_embbag_backward_prepare",
+              "ss_embbag_backward_apply"):
         getattr(lib, n).restype = C.c_int32
     return lib
 
@@ -222,6 +223,26 @@ def ss_embbag_backward_update(tables: Tables, idx: torch.Tensor,
         _dev_ptr(grad, torch.float32, "grad"), C.c_float(lr),
         _dev_ptr(ws, torch.uint8, "ws"), C.c_size_t(ws.numel()),
         _stream(stream)))
+
+
+def ss_embbag_backward_prepare(tables: Tables, idx: torch.Tensor,
+                               n_valid: Optional[torch.Tensor], ws: torch.Tensor,
+                               stream=None) -> None:
+    Bcap, L = _idx_shape(tables, idx)
+    _check(_lib.ss_embbag_backward_prepare(
+        C.byref(tables.c), _dev_ptr(idx, torch.int32, "idx"), C.c_int32(Bcap),
+        C.c_int32(L), _dev_ptr(n_valid, torch.int32, "n_valid"),
+        _dev_ptr(ws, torch.uint8, "ws"), C.c_size_t(ws.numel()), _stream(stream)))
+
+
+def ss_embbag_backward_apply(tables: Tables, Bcap: int, L: int, grad: torch.Tensor,
+                             lr: float, ws: torch.Tensor, stream=None) -> None:
+    if grad.numel() < tables.num_tables * Bcap * tables.dim:
+        raise SlipstreamError("ss_embbag_backward_apply: grad is too small")
+    _check(_lib.ss_embbag_backward_apply(
+        C.byref(tables.c), C.c_int32(Bcap), C.c_int32(L),
+        _dev_ptr(grad, torch.float32, "grad"), C.c_float(lr),
+        _dev_ptr(ws, torch.uint8, "ws"), C.c_size_t(ws.numel()), _stream(stream)))
 
 
 class HotState:

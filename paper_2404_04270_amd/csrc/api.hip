@@ -24,8 +24,9 @@ int32_t fail(int32_t code, const char *fmt, ...)
 int32_t check_tables(const ss_tables *tb, const char *who)
 {
     if (!tb) return fail(SS_ERR_INVALID_ARG, "%s: tables is NULL", who);
-    if (tb->num_tables < 1)
-        return fail(SS_ERR_INVALID_ARG, "%s: num_tables = %d", who, tb->num_tables);
+    if (tb->num_tables < 1 || tb->num_tables > 65535)
+        return fail(SS_ERR_INVALID_ARG, "%s: num_tables = %d (need 1..65535)", who,
+                    tb->num_tables);
     if (tb->dim < 4 || tb->dim % 4 != 0 || tb->dim > 1024)
         return fail(SS_ERR_INVALID_ARG,
                     "%s: dim = %d (need a multiple of 4 in [4, 1024])", who, tb->dim);
@@ -202,6 +203,52 @@ int32_t ss_embbag_forward(const ss_tables *tables, const int32_t *idx,
                           static_cast<hipStream_t>(stream));
 }
 
+static int32_t check_backward(const char *who, const ss_tables *tables, int32_t Bcap,
+                              int32_t L, const void *ws, size_t ws_bytes)
+{
+    int32_t rc = check_tables(tables, who);
+    if (rc) return rc;
+    if (Bcap < 1) return fail(SS_ERR_INVALID_ARG, "%s: batch = %d", who, Bcap);
+    if (L < 1) return fail(SS_ERR_INVALID_ARG, "%s: L = %d", who, L);
+    if ((int64_t)Bcap * L >= (1LL << 31) - 4096)
+        return fail(SS_ERR_UNSUPPORTED, "%s: Bcap*L too large", who);
+    return check_ws(who, ws, ws_bytes,
+                    backward_ws_bytes(tables->num_tables, Bcap, L, tables->dim));
+}
+
+static int32_t check_grad(const char *who, const float *grad)
+{
+    if (!grad) return fail(SS_ERR_INVALID_ARG, "%s: grad is NULL", who);
+    if (reinterpret_cast<uintptr_t>(grad) % 16 != 0)
+        return fail(SS_ERR_INVALID_ARG, "%s: grad is not 16-byte aligned", who);
+    return SS_OK;
+}
+
+int32_t ss_embbag_backward_prepare(const ss_tables *tables, const int32_t *idx,
+                                   int32_t Bcap, int32_t L, const int32_t *n_valid,
+                                   void *ws, size_t ws_bytes, void *stream)
+{
+    const char *who = "ss_embbag_backward_prepare";
+    int32_t rc = check_backward(who, tables, Bcap, L, ws, ws_bytes);
+    if (rc) return rc;
+    if (!idx) return fail(SS_ERR_INVALID_ARG, "%s: idx is NULL", who);
+    return launch_backward_prepare(tables, idx, Bcap, L, n_valid, ws,
+                                   static_cast<hipStream_t>(stream));
+}
+
+int32_t ss_embbag_backward_apply(const ss_tables *tables, int32_t Bcap, int32_t L,
+                                 const float *grad, float lr, void *ws,
+                                 size_t ws_bytes, void *stream)
+{
+    const char *who = "ss_embbag_backward_apply";
+    int32_t rc = check_backward(who, tables, Bcap, L, ws, ws_bytes);
+    if (rc) return rc;
+    rc = check_grad(who, grad);
+    if (rc) return rc;
+    return launch_backward_apply(tables, Bcap, L, grad, lr, ws,
+                                 static_cast<hipStream_t>(stream));
+}
+
 int32_t ss_embbag_backward_update(const ss_tables *tables, const int32_t *idx,
                                   int32_t Bcap, int32_t L,
                                   const int32_t *n_valid, const float *grad,
@@ -209,20 +256,16 @@ int32_t ss_embbag_backward_update(const ss_tables *tables, const int32_t *idx,
                                   void *stream)
 {
     const char *who = "ss_embbag_backward_update";
-    int32_t rc = check_tables(tables, who);
+    int32_t rc = check_backward(who, tables, Bcap, L, ws, ws_bytes);
     if (rc) return rc;
-    rc = check_batch(who, idx, Bcap, L, tables->num_tables);
+    if (!idx) return fail(SS_ERR_INVALID_ARG, "%s: idx is NULL", who);
+    rc = check_grad(who, grad);
     if (rc) return rc;
-    if ((int64_t)Bcap * L >= (1LL << 31) - 4096)
-        return fail(SS_ERR_UNSUPPORTED, "%s: Bcap*L too large", who);
-    if (!grad) return fail(SS_ERR_INVALID_ARG, "%s: grad is NULL", who);
-    if (reinterpret_cast<uintptr_t>(grad) % 16 != 0)
-        return fail(SS_ERR_INVALID_ARG, "%s: grad is not 16-byte aligned", who);
-    rc = check_ws(who, ws, ws_bytes,
-                  backward_ws_bytes(tables->num_tables, Bcap, L, tables->dim));
+    rc = launch_backward_prepare(tables, idx, Bcap, L, n_valid, ws,
+                                 static_cast<hipStream_t>(stream));
     if (rc) return rc;
-    return launch_backward(tables, idx, Bcap, L, n_valid, grad, lr, ws,
-                           static_cast<hipStream_t>(stream));
+    return launch_backward_apply(tables, Bcap, L, grad, lr, ws,
+                                 static_cast<hipStream_t>(stream));
 }
 
 int32_t ss_detect_stale(const ss_tables *tables, int32_t *const *hot_ids,

@@ -6,18 +6,23 @@
 //  1. SORT the lookups of each table by row id (stable, so equal rows keep the
 //     order "ascending sample, then position in bag").  The payload is the
 //     sample number, which is all the gradient gather needs.
-//       - up to 16384 lookups per table: one 1024-thread workgroup per table
-//         holds keys and payloads in registers and runs an LSD radix sort whose
-//         exchange buffers live in LDS (one launch);
-//       - more: a global LSD radix sort, 8 bits per pass, three launches per
-//         pass (per-tile digit histogram, scan, stable scatter).
+//       - up to 16384 lookups per table: one launch; the table is cut into
+//         classes by the low bits of the row id and a 1024-thread workgroup per
+//         class runs an LSD radix sort on the remaining bits with keys and
+//         payloads in registers and the exchange buffers in LDS (the apply
+//         stage needs equal rows adjacent, not ascending);
+//       - more: a global LSD radix sort, up to 10 bits per pass, two launches
+//         per pass: per-tile digit histograms, then a stable scatter whose
+//         workgroups each derive their own offsets from the histograms.
+//     A lookup whose row is stale is given the sentinel key when the keys are
+//     first read, so it sorts behind all real lookups and costs nothing later.
 //     Ranking inside a wavefront uses ballots: the lanes that hold the same
 //     digit are found with one ballot per digit bit, a popcount of the lower
 //     lanes gives the rank, and one lane per digit bumps the wavefront's LDS
 //     counter.  Tables are padded with sentinel keys to a multiple of 2048.
 //
 //  2. APPLY walks the sorted list in strips of S lookups per group of G lanes
-//     (one float4 of the row per lane).  All gradient rows of the strip and the
+//     (one f4 of the row per lane).  All gradient rows of the strip and the
 //     weight rows of the runs that end in it are requested up front, then the
 //     runs are summed in order.  A run that lies inside one strip is applied
 //     right away.  Runs that cross strip borders leave a leading / trailing
@@ -28,8 +33,8 @@
 //  3. FIXUP: one workgroup per run that crossed a workgroup border adds its
 //     pieces in a fixed order and applies the update.
 //
-// Rows whose stale bit is set are skipped before any gradient or weight of
-// theirs is read.  There are no floating-point atomics: every sum has a fixed
+// Rows whose stale bit is set drop out in stage 1, before any gradient or
+// weight of theirs is read.  There are no floating-point atomics: every sum has a fixed
 // order, so the result is reproducible.
 #include "ss_common.h"
 
@@ -42,6 +47,8 @@ constexpr int kLdsSortMax = 16384;     // largest table the one-launch sort take
 constexpr uint32_t kNoPrev = 0xFFFFFFFEu;
 constexpr int kRsThreads = 256;        // global radix sort: threads per tile
 constexpr int kRsItems = 8;            // ... keys per thread (tile = 2048 = kPad)
+constexpr int kRsMaxBits = 10;         // ... widest digit
+constexpr int kRsMaxDig = 1 << kRsMaxBits;
 
 __device__ __forceinline__ uint64_t lanes_below(int lane)
 {
@@ -60,6 +67,35 @@ __device__ __forceinline__ uint64_t match_digit(uint32_t d, int nbits)
     return m;
 }
 
+// Stable rank of this lane's key among the keys its wavefront has seen so far
+// with the same digit: the lowest lane of each digit group bumps the
+// wavefront's LDS counter once for the whole group and hands the old value to
+// the others.  cnt points at the wavefront's counters (one per digit).
+__device__ __forceinline__ uint32_t wave_rank(uint32_t *cnt, uint32_t d, int nbits,
+                                              int lane)
+{
+    const uint64_t m = match_digit(d, nbits);
+    const uint32_t before = __popcll(m & lanes_below(lane));
+    uint32_t base = 0;
+    if (before == 0) base = atomicAdd(&cnt[d], (uint32_t)__popcll(m));
+    base = __shfl(base, __ffsll((long long)m) - 1);
+    return base + before;
+}
+
+// Gives the sentinel key to lookups of stale rows.  All bitmap words are
+// requested before the first one is used.
+template <int N>
+__device__ __forceinline__ void drop_stale(gptr<const uint32_t> bt, uint32_t (&key)[N])
+{
+    if (!bt) return;
+    uint32_t word[N];
+#pragma unroll
+    for (int r = 0; r < N; ++r) word[r] = bt[key[r] == kNoRow ? 0u : key[r] >> 5];
+#pragma unroll
+    for (int r = 0; r < N; ++r)
+        if (key[r] != kNoRow && ((word[r] >> (key[r] & 31)) & 1u)) key[r] = kNoRow;
+}
+
 // Bits of the pass-th of npass digits when key_bits are split as evenly as
 // possible (earlier passes take the extra bits).
 __host__ __device__ inline int pass_bits(int key_bits, int npass, int pass)
@@ -68,234 +104,295 @@ __host__ __device__ inline int pass_bits(int key_bits, int npass, int pass)
 }
 
 // ---------------------------------------------------------------------------
-// Stage 1a: whole table in one workgroup.
+// Stage 1a: up to 16384 lookups per table, one launch.
+// The apply stage needs equal rows to be neighbours, not ascending rows, so a
+// table is cut into P classes by the low bits of the row id and each class is
+// sorted by the remaining bits by its own workgroup: P times the parallelism of
+// a whole-table sort and fewer digit passes.  Every workgroup reads all lookups
+// of its table (cheap at this size), keeps its class in the original order,
+// and learns from the same read where its class starts in the output (the
+// number of lookups in lower classes).  Output order: class, remaining bits,
+// original position; sentinels last.
 // ---------------------------------------------------------------------------
 template <int ITEMS>
-__global__ __launch_bounds__(1024) void lds_sort_kernel(
+__global__ __launch_bounds__(1024) void class_sort_kernel(
     const int32_t *__restrict__ idx, int Bcap, int L,
-    const int32_t *__restrict__ n_valid, int key_bits,
-    uint32_t *__restrict__ out_keys, uint32_t *__restrict__ out_vals, int NP)
+    const int32_t *__restrict__ n_valid, const uint32_t *const *__restrict__ bits,
+    int key_bits, int class_bits, uint32_t *__restrict__ out_keys,
+    uint32_t *__restrict__ out_vals, int NP)
 {
     constexpr int NW = 16, CAP = 1024 * ITEMS;
     __shared__ uint32_t s_keys[CAP];
     __shared__ uint32_t s_vals[CAP];
-    __shared__ uint32_t s_cnt[NW * 256];
-    __shared__ uint32_t s_dig[256];
-    __shared__ uint32_t s_wsum[4];
-    volatile uint32_t *v_cnt = s_cnt;
+    __shared__ uint32_t s_cnt[2 * NW * 64];   // two sets: one is cleared while the
+    __shared__ uint32_t s_dig[64];            // other is in use
+    __shared__ uint32_t s_mine[NW], s_below[NW], s_real[NW];
 
-    const int t = blockIdx.x;
+    const int cls = blockIdx.x, t = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = clamp_valid(n_valid, Bcap) * L;
     const int32_t *__restrict__ ip = idx + (int64_t)t * Bcap * L;
+    const auto bt = as_global(bits ? bits[t] : nullptr);
+    const uint32_t cmask = (1u << class_bits) - 1u;
 
     uint32_t key[ITEMS], val[ITEMS], rank[ITEMS];
 #pragma unroll
     for (int r = 0; r < ITEMS; ++r) {
         const int pos = wave * ITEMS * 64 + r * 64 + lane;
-        if (pos < n) {
-            key[r] = (uint32_t)ip[pos];
-            val[r] = (uint32_t)(pos / L);
-        } else {
-            key[r] = kNoRow;
-            val[r] = 0;
-        }
+        key[r] = pos < n ? (uint32_t)ip[pos] : kNoRow;
+        val[r] = pos < n ? (uint32_t)(L == 1 ? pos : pos / L) : 0u;
     }
+    drop_stale(bt, key);
 
-    const int npass = (key_bits + 7) / 8;
-    int shift = 0;
-    for (int pass = 0; pass < npass; ++pass) {
-        const int nb = pass_bits(key_bits, npass, pass);
-        const uint32_t dmask = (1u << nb) - 1u;
-        for (int i = tid; i < NW * 256; i += 1024) s_cnt[i] = 0;
-        __syncthreads();
+    // keep my class, in order; count the lookups of lower classes
+    uint32_t c_mine = 0, c_below = 0, c_real = 0, slot[ITEMS];
 #pragma unroll
-        for (int r = 0; r < ITEMS; ++r) {
-            const uint32_t d = (key[r] >> shift) & dmask;
-            const uint64_t m = match_digit(d, nb);
-            const uint32_t before = __popcll(m & lanes_below(lane));
-            const uint32_t base = v_cnt[wave * 256 + d];
-            rank[r] = base + before;
-            if (before == 0) v_cnt[wave * 256 + d] = base + (uint32_t)__popcll(m);
+    for (int r = 0; r < ITEMS; ++r) {
+        const bool real = key[r] != kNoRow;
+        const uint32_t kc = key[r] & cmask;
+        const uint64_t bm = __ballot(real && kc == (uint32_t)cls);
+        slot[r] = c_mine + __popcll(bm & lanes_below(lane));
+        c_mine += __popcll(bm);
+        c_below += __popcll(__ballot(real && kc < (uint32_t)cls));
+        c_real += __popcll(__ballot(real));
+    }
+    if (lane == 0) {
+        s_mine[wave] = c_mine;
+        s_below[wave] = c_below;
+        s_real[wave] = c_real;
+    }
+    __syncthreads();
+    uint32_t woff = 0, m = 0, n_below = 0, n_real = 0;
+    for (int w = 0; w < NW; ++w) {
+        if (w < wave) woff += s_mine[w];
+        m += s_mine[w];
+        n_below += s_below[w];
+        n_real += s_real[w];
+    }
+#pragma unroll
+    for (int r = 0; r < ITEMS; ++r)
+        if (key[r] != kNoRow && (key[r] & cmask) == (uint32_t)cls) {
+            s_keys[woff + slot[r]] = key[r];
+            s_vals[woff + slot[r]] = val[r];
         }
-        __syncthreads();
-        // per digit: exclusive offsets of the wavefronts, total of the digit
-        if (tid <= (int)dmask) {
-            uint32_t run = 0;
-            for (int w = 0; w < NW; ++w) {
-                const uint32_t c = s_cnt[w * 256 + tid];
-                s_cnt[w * 256 + tid] = run;
-                run += c;
+    __syncthreads();
+
+    // LSD radix sort of the m kept lookups on bits [class_bits, key_bits).
+    // Digits of at most 6 bits: one wavefront can then turn the 16 x 64 counters
+    // into offsets with shuffles alone, which leaves three barriers per pass.
+    const int rounds = ((int)m + 1023) >> 10;       // keys per thread, <= ITEMS
+    const int rem_bits = key_bits - class_bits;
+    const int npass = (rem_bits + 5) / 6;
+    int shift = class_bits;
+    for (int i = tid; i < 2 * NW * 64; i += 1024) s_cnt[i] = 0;
+    __syncthreads();
+    for (int pass = 0; pass < npass; ++pass) {
+        uint32_t *cnt = s_cnt + (pass & 1) * (NW * 64);       // this pass
+        uint32_t *cnt_next = s_cnt + ((pass + 1) & 1) * (NW * 64);
+#pragma unroll
+        for (int r = 0; r < ITEMS; ++r)
+            if (r < rounds) {
+                const uint32_t pos = wave * rounds * 64 + r * 64 + lane;
+                key[r] = pos < m ? s_keys[pos] : kNoRow;
+                val[r] = pos < m ? s_vals[pos] : 0u;
             }
-            s_dig[tid] = run;
-        }
+        const int nb = pass_bits(rem_bits, npass, pass);
+        const uint32_t dmask = (1u << nb) - 1u;
+#pragma unroll
+        for (int r = 0; r < ITEMS; ++r)
+            if (r < rounds) {
+                const uint32_t d = (key[r] >> shift) & dmask;
+                rank[r] = wave_rank(cnt + wave * 64, d, nb, lane);
+            }
         __syncthreads();
-        // exclusive scan of the digit totals (first four wavefronts)
-        uint32_t incl = 0, mine = 0;
-        if (tid < 256) {
-            mine = tid <= (int)dmask ? s_dig[tid] : 0;
-            incl = mine;
+        if (wave == 0) {
+            // lane d: offsets of the 16 wavefronts for digit d, then digit starts
+            uint32_t run = 0;
+            if (lane <= (int)dmask)
+                for (int w = 0; w < NW; ++w) {
+                    const uint32_t c = cnt[w * 64 + lane];
+                    cnt[w * 64 + lane] = run;
+                    run += c;
+                }
+            uint32_t incl = run;
             for (int off = 1; off < 64; off <<= 1) {
                 const uint32_t up = __shfl_up(incl, off);
                 if (lane >= off) incl += up;
             }
-            if (lane == 63) s_wsum[wave] = incl;
-        }
-        __syncthreads();
-        if (tid < 256) {
-            uint32_t wb = 0;
-            for (int w = 0; w < wave; ++w) wb += s_wsum[w];
-            s_dig[tid] = wb + incl - mine;
+            s_dig[lane] = incl - run;
+        } else {
+            for (int i = tid - 64; i < NW * 64; i += 1024 - 64) cnt_next[i] = 0;
         }
         __syncthreads();
 #pragma unroll
-        for (int r = 0; r < ITEMS; ++r) {
-            const uint32_t d = (key[r] >> shift) & dmask;
-            const uint32_t p = s_dig[d] + s_cnt[wave * 256 + d] + rank[r];
-            s_keys[p] = key[r];
-            s_vals[p] = val[r];
-        }
-        __syncthreads();
-        if (pass + 1 < npass) {
-#pragma unroll
-            for (int r = 0; r < ITEMS; ++r) {
-                const int pos = wave * ITEMS * 64 + r * 64 + lane;
-                key[r] = s_keys[pos];
-                val[r] = s_vals[pos];
+        for (int r = 0; r < ITEMS; ++r)
+            if (r < rounds) {
+                const uint32_t d = (key[r] >> shift) & dmask;
+                const uint32_t p = s_dig[d] + cnt[wave * 64 + d] + rank[r];
+                if (p < m) {            // sentinels rank behind every real key
+                    s_keys[p] = key[r];
+                    s_vals[p] = val[r];
+                }
             }
-        }
+        __syncthreads();
         shift += nb;
     }
-    const int lim = CAP < NP ? CAP : NP;
-    for (int i = tid; i < lim; i += 1024) {
-        out_keys[(int64_t)t * NP + i] = s_keys[i];
-        out_vals[(int64_t)t * NP + i] = s_vals[i];
+    uint32_t *__restrict__ ok = out_keys + (int64_t)t * NP;
+    uint32_t *__restrict__ ov = out_vals + (int64_t)t * NP;
+    for (uint32_t i = tid; i < m; i += 1024) {
+        ok[n_below + i] = s_keys[i];
+        ov[n_below + i] = s_vals[i];
     }
+    if (cls == 0)
+        for (uint32_t i = n_real + tid; i < (uint32_t)NP; i += 1024) {
+            ok[i] = kNoRow;
+            ov[i] = 0;
+        }
 }
 
 // ---------------------------------------------------------------------------
 // Stage 1b: global LSD radix sort, one pass = histogram, scan, scatter.
-// Tile = 2048 keys; hist layout [table][digit][tile].
+// Tile = 2048 keys; hist layout [table][tile][digit].
 // ---------------------------------------------------------------------------
 template <bool FIRST>
-__device__ __forceinline__ void rs_load(const int32_t *__restrict__ idx, int L, int n,
+__device__ __forceinline__ void rs_load(const int32_t *__restrict__ ip, int L, int n,
                                         const uint32_t *__restrict__ in_keys,
-                                        const uint32_t *__restrict__ in_vals,
-                                        int64_t table_off_idx, int64_t table_off,
-                                        int pos, uint32_t &key, uint32_t &val)
+                                        const uint32_t *__restrict__ in_vals, int pos,
+                                        uint32_t &key, uint32_t &val)
 {
     if (FIRST) {
-        if (pos < n) {
-            key = (uint32_t)idx[table_off_idx + pos];
-            val = (uint32_t)(pos / L);
-        } else {
-            key = kNoRow;
-            val = 0;
-        }
+        key = pos < n ? (uint32_t)ip[pos] : kNoRow;
+        val = pos < n ? (uint32_t)(L == 1 ? pos : pos / L) : 0u;
     } else {
-        key = in_keys[table_off + pos];
-        val = in_vals[table_off + pos];
+        key = in_keys[pos];
+        val = in_vals ? in_vals[pos] : 0u;
     }
 }
 
 template <bool FIRST>
 __global__ __launch_bounds__(kRsThreads) void rs_hist_kernel(
     const int32_t *__restrict__ idx, int Bcap, int L,
-    const int32_t *__restrict__ n_valid, const uint32_t *__restrict__ in_keys,
-    int NP, int shift, int nb, uint32_t *__restrict__ hist, int tiles)
+    const int32_t *__restrict__ n_valid, const uint32_t *const *__restrict__ bits,
+    const uint32_t *__restrict__ in_keys, int NP, int shift, int nb,
+    uint32_t *__restrict__ hist, int tiles)
 {
-    __shared__ uint32_t s_hist[256];
+    __shared__ uint32_t s_hist[kRsMaxDig];
     const int t = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
     const int n = clamp_valid(n_valid, Bcap) * L;
-    const uint32_t dmask = (1u << nb) - 1u;
-    s_hist[tid] = 0;
+    const int ndig = 1 << nb;
+    const uint32_t dmask = ndig - 1;
+    const int32_t *__restrict__ ip = idx + (int64_t)t * Bcap * L;
+    const auto bt = as_global((FIRST && bits) ? bits[t] : nullptr);
+    const uint32_t *__restrict__ kin = FIRST ? nullptr : in_keys + (int64_t)t * NP;
+    for (int i = tid; i < ndig; i += kRsThreads) s_hist[i] = 0;
     __syncthreads();
+    uint32_t key[kRsItems], val;
 #pragma unroll
-    for (int r = 0; r < kRsItems; ++r) {
-        const int pos = tile * kPad + r * kRsThreads + tid;
-        uint32_t key, val;
-        rs_load<FIRST>(idx, L, n, in_keys, in_keys, (int64_t)t * Bcap * L,
-                       (int64_t)t * NP, pos, key, val);
-        atomicAdd(&s_hist[(key >> shift) & dmask], 1u);
-    }
+    for (int r = 0; r < kRsItems; ++r)
+        rs_load<FIRST>(ip, L, n, kin, nullptr, tile * kPad + r * kRsThreads + tid,
+                       key[r], val);
+    if (FIRST) drop_stale(bt, key);
+#pragma unroll
+    for (int r = 0; r < kRsItems; ++r) atomicAdd(&s_hist[(key[r] >> shift) & dmask], 1u);
     __syncthreads();
-    if (tid <= (int)dmask)
-        hist[((int64_t)t * 256 + tid) * tiles + tile] = s_hist[tid];
+    for (int i = tid; i < ndig; i += kRsThreads)
+        hist[((int64_t)t * tiles + tile) * kRsMaxDig + i] = s_hist[i];
 }
 
-// Exclusive scan over the (digit-major, tile-minor) histogram of each table.
-__global__ __launch_bounds__(1024) void rs_scan_kernel(uint32_t *__restrict__ hist,
-                                                       int tiles, int nb)
+// Stable scatter of one tile.  The workgroup first turns the table's histograms
+// into the start offset of each of its digits: (keys with a smaller digit in
+// the whole table) + (keys with this digit in earlier tiles).
+template <bool FIRST>
+__global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
+    const int32_t *__restrict__ idx, int Bcap, int L,
+    const int32_t *__restrict__ n_valid, const uint32_t *const *__restrict__ bits,
+    const uint32_t *__restrict__ in_keys, const uint32_t *__restrict__ in_vals,
+    uint32_t *__restrict__ out_keys, uint32_t *__restrict__ out_vals, int NP,
+    int shift, int nb, const uint32_t *__restrict__ hist, int tiles)
 {
-    __shared__ uint32_t s_wsum[16];
-    const int t = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    uint32_t *h = hist + (int64_t)t * 256 * tiles;
-    const int len = (1 << nb) * tiles;
-    const int per = (len + 1023) / 1024;
-    const int lo = tid * per, hi = lo + per < len ? lo + per : len;
-    uint32_t sum = 0;
-    for (int i = lo; i < hi; ++i) sum += h[i];
-    uint32_t incl = sum;
+    constexpr int NW = kRsThreads / 64;
+    __shared__ uint32_t s_cnt[NW * kRsMaxDig];   // per wavefront and digit
+    __shared__ uint32_t s_base[kRsMaxDig];       // start offset of each digit
+    __shared__ uint32_t s_wsum[NW];
+    const int t = blockIdx.y, tile = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = clamp_valid(n_valid, Bcap) * L;
+    const int ndig = 1 << nb;
+    const uint32_t dmask = ndig - 1;
+    const int32_t *__restrict__ ip = idx + (int64_t)t * Bcap * L;
+    const auto bt = as_global((FIRST && bits) ? bits[t] : nullptr);
+    const uint32_t *__restrict__ kin = FIRST ? nullptr : in_keys + (int64_t)t * NP;
+    const uint32_t *__restrict__ vin = FIRST ? nullptr : in_vals + (int64_t)t * NP;
+
+    uint32_t key[kRsItems], val[kRsItems], rank[kRsItems];
+#pragma unroll
+    for (int r = 0; r < kRsItems; ++r)   // wavefront w owns quarter w of the tile
+        rs_load<FIRST>(ip, L, n, kin, vin,
+                       tile * kPad + wave * (kRsItems * 64) + r * 64 + lane, key[r],
+                       val[r]);
+    if (FIRST) drop_stale(bt, key);
+
+    // digit offsets from the histograms; each thread owns ndig / 256 digits
+    for (int i = tid; i < NW * ndig; i += kRsThreads) s_cnt[i] = 0;
+    const int dpt = (ndig + kRsThreads - 1) / kRsThreads;   // 1, 2 or 4
+    uint32_t tot[4] = {0, 0, 0, 0}, early[4] = {0, 0, 0, 0}, run = 0;
+    for (int q = 0; q < dpt; ++q) {
+        const int d = tid * dpt + q;
+        if (d < ndig) {
+            const uint32_t *__restrict__ h = hist + (int64_t)t * tiles * kRsMaxDig + d;
+            int k = 0;
+            for (; k + 8 <= tiles; k += 8) {
+                uint32_t c[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) c[u] = h[(int64_t)(k + u) * kRsMaxDig];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    tot[q] += c[u];
+                    if (k + u < tile) early[q] += c[u];
+                }
+            }
+            for (; k < tiles; ++k) {
+                const uint32_t c = h[(int64_t)k * kRsMaxDig];
+                tot[q] += c;
+                if (k < tile) early[q] += c;
+            }
+        }
+        run += tot[q];
+    }
+    uint32_t incl = run;
     for (int off = 1; off < 64; off <<= 1) {
         const uint32_t up = __shfl_up(incl, off);
         if (lane >= off) incl += up;
     }
     if (lane == 63) s_wsum[wave] = incl;
     __syncthreads();
-    uint32_t run = incl - sum;
-    for (int w = 0; w < wave; ++w) run += s_wsum[w];
-    for (int i = lo; i < hi; ++i) {
-        const uint32_t c = h[i];
-        h[i] = run;
-        run += c;
+    uint32_t start = incl - run;
+    for (int w = 0; w < wave; ++w) start += s_wsum[w];
+    for (int q = 0; q < dpt; ++q) {
+        const int d = tid * dpt + q;
+        if (d < ndig) s_base[d] = start + early[q];
+        start += tot[q];
     }
-}
 
-template <bool FIRST>
-__global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
-    const int32_t *__restrict__ idx, int Bcap, int L,
-    const int32_t *__restrict__ n_valid, const uint32_t *__restrict__ in_keys,
-    const uint32_t *__restrict__ in_vals, uint32_t *__restrict__ out_keys,
-    uint32_t *__restrict__ out_vals, int NP, int shift, int nb,
-    const uint32_t *__restrict__ hist, int tiles)
-{
-    constexpr int NW = kRsThreads / 64;
-    __shared__ uint32_t s_cnt[NW * 256];
-    volatile uint32_t *v_cnt = s_cnt;
-    const int t = blockIdx.y, tile = blockIdx.x;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n = clamp_valid(n_valid, Bcap) * L;
-    const uint32_t dmask = (1u << nb) - 1u;
-    for (int i = tid; i < NW * 256; i += kRsThreads) s_cnt[i] = 0;
-    __syncthreads();
-    uint32_t key[kRsItems], val[kRsItems], rank[kRsItems];
 #pragma unroll
     for (int r = 0; r < kRsItems; ++r) {
-        // wavefront w owns the contiguous quarter w of the tile, in order
-        const int pos = tile * kPad + wave * (kRsItems * 64) + r * 64 + lane;
-        rs_load<FIRST>(idx, L, n, in_keys, in_vals, (int64_t)t * Bcap * L,
-                       (int64_t)t * NP, pos, key[r], val[r]);
         const uint32_t d = (key[r] >> shift) & dmask;
-        const uint64_t m = match_digit(d, nb);
-        const uint32_t before = __popcll(m & lanes_below(lane));
-        const uint32_t base = v_cnt[wave * 256 + d];
-        rank[r] = base + before;
-        if (before == 0) v_cnt[wave * 256 + d] = base + (uint32_t)__popcll(m);
+        rank[r] = wave_rank(s_cnt + wave * ndig, d, nb, lane);
     }
     __syncthreads();
-    if (tid <= (int)dmask) {
-        uint32_t run = hist[((int64_t)t * 256 + tid) * tiles + tile];
+    for (int d = tid; d < ndig; d += kRsThreads) {
+        uint32_t acc = s_base[d];
         for (int w = 0; w < NW; ++w) {
-            const uint32_t c = s_cnt[w * 256 + tid];
-            s_cnt[w * 256 + tid] = run;
-            run += c;
+            const uint32_t c = s_cnt[w * ndig + d];
+            s_cnt[w * ndig + d] = acc;
+            acc += c;
         }
     }
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < kRsItems; ++r) {
         const uint32_t d = (key[r] >> shift) & dmask;
-        const int64_t p = (int64_t)t * NP + s_cnt[wave * 256 + d] + rank[r];
+        const int64_t p = (int64_t)t * NP + s_cnt[wave * ndig + d] + rank[r];
         out_keys[p] = key[r];
         out_vals[p] = val[r];
     }
@@ -311,28 +408,38 @@ __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
 // ---------------------------------------------------------------------------
 template <int G, int S>
 __global__ __launch_bounds__(kWG) void apply_kernel(
-    float *const *__restrict__ weights, const uint32_t *const *__restrict__ bits,
-    const uint32_t *__restrict__ keys, const uint32_t *__restrict__ vals, int NP,
-    const float *__restrict__ grad, int Bcap, int D4, float lr,
-    int wgs_per_table, uint32_t *__restrict__ meta_trail_row,
-    uint8_t *__restrict__ meta_lead_state, float4 *__restrict__ part_lead,
-    float4 *__restrict__ part_trail)
+    float *const *__restrict__ weights, const uint32_t *__restrict__ keys,
+    const uint32_t *__restrict__ vals, int NP, const float *__restrict__ grad,
+    int Bcap, int D4, float lr, int wgs_per_table, bool xcd_aware,
+    uint32_t *__restrict__ meta_trail_row, uint8_t *__restrict__ meta_lead_state,
+    f4 *__restrict__ part_lead, f4 *__restrict__ part_trail)
 {
     constexpr int NG = kWG / G;
-    __shared__ float4 s_lead[kWG];
-    __shared__ float4 s_trail[kWG];
+    __shared__ f4 s_lead[kWG];
+    __shared__ f4 s_trail[kWG];
     __shared__ uint32_t s_trail_row[NG];
     __shared__ uint8_t s_lead_state[NG];
 
-    const int t = blockIdx.x / wgs_per_table;
-    const int wg = blockIdx.x - t * wgs_per_table;
+    // With several lookups per bag every gradient row is read L times from
+    // scattered strips.  If the tables can be dealt evenly to the 8 XCDs, all
+    // workgroups of table t run on XCD t % 8, whose L2 then holds that table's
+    // gradients (workgroups go to the XCDs round-robin).
+    int t, wg;
+    if (xcd_aware) {
+        const int x = blockIdx.x & 7, k = blockIdx.x >> 3;
+        const int tl = k / wgs_per_table;
+        wg = k - tl * wgs_per_table;
+        t = tl * 8 + x;
+    } else {
+        t = blockIdx.x / wgs_per_table;
+        wg = blockIdx.x - t * wgs_per_table;
+    }
     const int tid = threadIdx.x, g = tid / G, c = tid % G;
     const uint32_t *__restrict__ kp = keys + (int64_t)t * NP;
     const uint32_t *__restrict__ vp = vals + (int64_t)t * NP;
-    const uint32_t *__restrict__ bt = bits ? bits[t] : nullptr;
-    float4 *__restrict__ W = reinterpret_cast<float4 *>(weights[t]);
-    const float4 *__restrict__ G4 =
-        reinterpret_cast<const float4 *>(grad) + (int64_t)t * Bcap * D4;
+    const auto W = as_global(reinterpret_cast<f4 *>(weights[t]));
+    const f4 *__restrict__ G4 =
+        reinterpret_cast<const f4 *>(grad) + (int64_t)t * Bcap * D4;
     const int wg_base = wg * NG * S;
     const int base = wg_base + g * S;
 
@@ -347,13 +454,13 @@ __global__ __launch_bounds__(kWG) void apply_kernel(
     const uint32_t prev = base > 0 ? kp[base - 1] : kNoPrev;
     const uint32_t next = base + S < NP ? kp[base + S] : kNoRow;
 
-    // live: a real lookup whose row is not stale.  Equal within a run.
+    // live: a real lookup (stale and padding lookups carry the sentinel key)
     bool live[S], is_end[S], whole[S];
     {
         bool has_head = row[0] != prev;
 #pragma unroll
         for (int i = 0; i < S; ++i) {
-            live[i] = row[i] != kNoRow && !(bt && bit_set(bt, row[i]));
+            live[i] = row[i] != kNoRow;
             is_end[i] = (i == S - 1) || row[i + 1] != row[i];
             const bool ends_here = (i < S - 1) || next != row[i];
             whole[i] = is_end[i] && has_head && ends_here;   // run inside the strip
@@ -393,19 +500,19 @@ __global__ __launch_bounds__(kWG) void apply_kernel(
     for (int cb = 0; cb < D4; cb += G) {
         const int col = cb + c;
         const bool active = col < D4;
-        float4 gv[S], wv[S];
+        f4 gv[S], wv[S];
 #pragma unroll
         for (int i = 0; i < S; ++i)
             if (live[i] && active) gv[i] = G4[(int64_t)smp[i] * D4 + col];
 #pragma unroll
         for (int i = 0; i < S; ++i)
             if (whole[i] && live[i] && active) wv[i] = W[(int64_t)row[i] * D4 + col];
-        float4 w_trail = make_float4(0.f, 0.f, 0.f, 0.f);
+        f4 w_trail = f4{0.f, 0.f, 0.f, 0.f};
         if (has_trail && live[S - 1] && active)
             w_trail = W[(int64_t)row[S - 1] * D4 + col];
 
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        float4 lead_sum = acc, trail_sum = acc;
+        f4 acc = f4{0.f, 0.f, 0.f, 0.f};
+        f4 lead_sum = acc, trail_sum = acc;
         bool first_run = true;
 #pragma unroll
         for (int i = 0; i < S; ++i) {
@@ -419,7 +526,7 @@ __global__ __launch_bounds__(kWG) void apply_kernel(
                 } else {
                     trail_sum = acc;   // only the last run can get here
                 }
-                acc = make_float4(0.f, 0.f, 0.f, 0.f);
+                acc = f4{0.f, 0.f, 0.f, 0.f};
                 first_run = false;
             }
         }
@@ -429,7 +536,7 @@ __global__ __launch_bounds__(kWG) void apply_kernel(
 
         // stitch the runs that cross strip borders, in strip order
         if (s_trail_row[g] != kNoRow) {
-            float4 sum = s_trail[tid];
+            f4 sum = s_trail[tid];
             bool ended = false;
             for (int q = g + 1; q < NG; ++q) {
                 sum = sum + s_lead[q * G + c];
@@ -445,7 +552,7 @@ __global__ __launch_bounds__(kWG) void apply_kernel(
         if (g == 0) {
             uint8_t st = s_lead_state[0];
             if (st != 0) {
-                float4 sum = s_lead[c];
+                f4 sum = s_lead[c];
                 int q = 0;
                 while (st == 2 && q + 1 < NG) {
                     ++q;
@@ -466,21 +573,18 @@ __global__ __launch_bounds__(kWG) void apply_kernel(
 // ---------------------------------------------------------------------------
 template <int G>
 __global__ __launch_bounds__(kWG) void fixup_kernel(
-    float *const *__restrict__ weights, const uint32_t *const *__restrict__ bits,
-    int D4, float lr, int wgs_per_table,
+    float *const *__restrict__ weights, int D4, float lr, int wgs_per_table,
     const uint32_t *__restrict__ meta_trail_row,
     const uint8_t *__restrict__ meta_lead_state,
-    const float4 *__restrict__ part_lead, const float4 *__restrict__ part_trail)
+    const f4 *__restrict__ part_lead, const f4 *__restrict__ part_trail)
 {
     constexpr int NG = kWG / G;
     __shared__ int s_end;
-    __shared__ float4 s_part[kWG];
+    __shared__ f4 s_part[kWG];
     const int t = blockIdx.x / wgs_per_table;
     const int wg = blockIdx.x - t * wgs_per_table;
     const uint32_t row = meta_trail_row[t * wgs_per_table + wg];
     if (row == kNoRow) return;
-    const uint32_t *__restrict__ bt = bits ? bits[t] : nullptr;
-    if (bt && bit_set(bt, row)) return;
 
     const int tid = threadIdx.x, g = tid / G, c = tid % G;
     const uint8_t *__restrict__ ls = meta_lead_state + (int64_t)t * wgs_per_table;
@@ -500,13 +604,13 @@ __global__ __launch_bounds__(kWG) void fixup_kernel(
 
     // pieces: trail(wg), lead(wg+1), ..., lead(end); group g sums every NG-th
     const int npieces = end - wg + 1;
-    float4 *__restrict__ W = reinterpret_cast<float4 *>(weights[t]);
-    const float4 *__restrict__ PL = part_lead + (int64_t)t * wgs_per_table * D4;
-    const float4 *__restrict__ PT = part_trail + (int64_t)t * wgs_per_table * D4;
+    const auto W = as_global(reinterpret_cast<f4 *>(weights[t]));
+    const f4 *__restrict__ PL = part_lead + (int64_t)t * wgs_per_table * D4;
+    const f4 *__restrict__ PT = part_trail + (int64_t)t * wgs_per_table * D4;
     for (int cb = 0; cb < D4; cb += G) {
         const int col = cb + c;
         const bool active = col < D4;
-        float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+        f4 sum = f4{0.f, 0.f, 0.f, 0.f};
         if (active)
             for (int k = g; k < npieces; k += NG)
                 sum = sum + (k == 0 ? PT[(int64_t)wg * D4 + col]
@@ -514,7 +618,7 @@ __global__ __launch_bounds__(kWG) void fixup_kernel(
         s_part[tid] = sum;
         __syncthreads();
         if (g == 0 && active) {
-            float4 tot = s_part[c];
+            f4 tot = s_part[c];
             const int used = npieces < NG ? npieces : NG;
             for (int q = 1; q < used; ++q) tot = tot + s_part[q * G + c];
             const int64_t o = (int64_t)row * D4 + col;
@@ -550,7 +654,7 @@ Layout make_layout(int T, int Bcap, int L, int dim)
     y.vals0 = take(arr);
     y.keys1 = take(arr);
     y.vals1 = take(arr);
-    y.hist = take((size_t)T * 256 * y.tiles * sizeof(uint32_t));
+    y.hist = take((size_t)T * kRsMaxDig * y.tiles * sizeof(uint32_t));
     y.trail_row = take((size_t)T * y.max_wgs * sizeof(uint32_t));
     y.lead_state = take((size_t)T * y.max_wgs);
     y.part_lead = take((size_t)T * y.max_wgs * dim * sizeof(float));
@@ -566,14 +670,10 @@ int key_bits_for(int64_t rows)
     return b;
 }
 
-// Strip length: long strips cut the number of pieces, short ones give a small
-// problem enough workgroups to occupy the chip.
-int pick_strip(int64_t total_lookups, int ng)
-{
-    if (total_lookups / (ng * 16) >= 1024) return 16;
-    if (total_lookups / (ng * 8) >= 1024) return 8;
-    return 4;
-}
+// Strip length (lookups per lane group in the apply stage).  Short strips keep
+// the register footprint small enough for five wavefronts per SIMD; rows of 512
+// bytes and more were measured faster with 8 (fewer pieces to stitch).
+int pick_strip(int lanes_per_group) { return lanes_per_group <= 16 ? 4 : 8; }
 
 }  // namespace
 
@@ -582,11 +682,19 @@ size_t backward_ws_bytes(int T, int Bcap, int L, int dim)
     return make_layout(T, Bcap, L, dim).total;
 }
 
-int32_t launch_backward(const ss_tables *tb, const int32_t *idx, int Bcap, int L,
-                        const int32_t *n_valid, const float *grad, float lr,
-                        void *ws, hipStream_t s)
+// Which of the two key/payload buffers holds the sorted lists after stage 1.
+static int sorted_buffer(const Layout &y, int key_bits)
 {
-    const int T = tb->num_tables, D4 = tb->dim / 4;
+    if (y.NP <= kLdsSortMax) return 0;
+    const int npass = (key_bits + kRsMaxBits - 1) / kRsMaxBits;
+    return (npass - 1) & 1;      // pass 0 writes buffer 0, then they alternate
+}
+
+int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bcap,
+                                int L, const int32_t *n_valid, void *ws,
+                                hipStream_t s)
+{
+    const int T = tb->num_tables;
     const Layout y = make_layout(T, Bcap, L, tb->dim);
     char *w8 = static_cast<char *>(ws);
     uint32_t *keys[2] = {reinterpret_cast<uint32_t *>(w8 + y.keys0),
@@ -599,72 +707,86 @@ int32_t launch_backward(const ss_tables *tb, const int32_t *idx, int Bcap, int L
 
     if (y.NP <= kLdsSortMax) {
         const int items = y.NP / 1024;   // NP is a multiple of 2048
-#define SS_LDS_SORT(I)                                                          \
-    ProfScope prof("lds_sort_kernel", s);                                        \
-    hipLaunchKernelGGL(lds_sort_kernel<I>, dim3(T), dim3(1024), 0, s, idx, Bcap, \
-                       L, n_valid, key_bits, keys[0], vals[0], y.NP)
+        int class_bits = 0;              // about 1024 lookups per class
+        while ((1024 << class_bits) < y.NP && class_bits < key_bits) ++class_bits;
+        const dim3 grid(1 << class_bits, T);
+        ProfScope prof("class_sort_kernel", s);
+#define SS_LDS_SORT(I)                                                            \
+    hipLaunchKernelGGL(class_sort_kernel<I>, grid, dim3(1024), 0, s, idx, Bcap, L, \
+                       n_valid, tb->stale_bits, key_bits, class_bits, keys[0],     \
+                       vals[0], y.NP)
         if (items <= 2) { SS_LDS_SORT(2); }
         else if (items <= 4) { SS_LDS_SORT(4); }
         else if (items <= 8) { SS_LDS_SORT(8); }
         else { SS_LDS_SORT(16); }
 #undef SS_LDS_SORT
     } else {
-        const int npass = (key_bits + 7) / 8;
+        const int npass = (key_bits + kRsMaxBits - 1) / kRsMaxBits;
         const dim3 grid(y.tiles, T);
         int shift = 0;
         for (int pass = 0; pass < npass; ++pass) {
             const int nb = pass_bits(key_bits, npass, pass);
             const int in = cur, out = pass == 0 ? 0 : 1 - cur;
             {
-            ProfScope prof("rs_hist_kernel", s);
-            if (pass == 0) {
-                hipLaunchKernelGGL(rs_hist_kernel<true>, grid, dim3(kRsThreads), 0,
-                                   s, idx, Bcap, L, n_valid, nullptr, y.NP, shift,
-                                   nb, hist, y.tiles);
-            } else {
-                hipLaunchKernelGGL(rs_hist_kernel<false>, grid, dim3(kRsThreads), 0,
-                                   s, idx, Bcap, L, n_valid, keys[in], y.NP, shift,
-                                   nb, hist, y.tiles);
-            }
-            }
-            {
-            ProfScope prof("rs_scan_kernel", s);
-            hipLaunchKernelGGL(rs_scan_kernel, dim3(T), dim3(1024), 0, s, hist,
-                               y.tiles, nb);
+                ProfScope prof("rs_hist_kernel", s);
+                if (pass == 0)
+                    hipLaunchKernelGGL(rs_hist_kernel<true>, grid, dim3(kRsThreads),
+                                       0, s, idx, Bcap, L, n_valid, tb->stale_bits,
+                                       nullptr, y.NP, shift, nb, hist, y.tiles);
+                else
+                    hipLaunchKernelGGL(rs_hist_kernel<false>, grid, dim3(kRsThreads),
+                                       0, s, idx, Bcap, L, n_valid, nullptr,
+                                       keys[in], y.NP, shift, nb, hist, y.tiles);
             }
             ProfScope prof("rs_scatter_kernel", s);
-            if (pass == 0) {
-                hipLaunchKernelGGL(rs_scatter_kernel<true>, grid, dim3(kRsThreads),
-                                   0, s, idx, Bcap, L, n_valid, nullptr, nullptr,
-                                   keys[out], vals[out], y.NP, shift, nb, hist,
-                                   y.tiles);
-            } else {
+            if (pass == 0)
+                hipLaunchKernelGGL(rs_scatter_kernel<true>, grid, dim3(kRsThreads), 0,
+                                   s, idx, Bcap, L, n_valid, tb->stale_bits, nullptr,
+                                   nullptr, keys[out], vals[out], y.NP, shift, nb,
+                                   hist, y.tiles);
+            else
                 hipLaunchKernelGGL(rs_scatter_kernel<false>, grid, dim3(kRsThreads),
-                                   0, s, idx, Bcap, L, n_valid, keys[in], vals[in],
-                                   keys[out], vals[out], y.NP, shift, nb, hist,
-                                   y.tiles);
-            }
+                                   0, s, idx, Bcap, L, n_valid, nullptr, keys[in],
+                                   vals[in], keys[out], vals[out], y.NP, shift, nb,
+                                   hist, y.tiles);
             cur = out;
             shift += nb;
         }
     }
+    if (cur != sorted_buffer(y, key_bits))
+        return fail(SS_ERR_HIP, "ss_embbag_backward_prepare: internal buffer mismatch");
+    return check_launch("ss_embbag_backward_prepare");
+}
+
+int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float *grad,
+                              float lr, void *ws, hipStream_t s)
+{
+    const int T = tb->num_tables, D4 = tb->dim / 4;
+    const Layout y = make_layout(T, Bcap, L, tb->dim);
+    char *w8 = static_cast<char *>(ws);
+    uint32_t *keys[2] = {reinterpret_cast<uint32_t *>(w8 + y.keys0),
+                         reinterpret_cast<uint32_t *>(w8 + y.keys1)};
+    uint32_t *vals[2] = {reinterpret_cast<uint32_t *>(w8 + y.vals0),
+                         reinterpret_cast<uint32_t *>(w8 + y.vals1)};
+    const int cur = sorted_buffer(y, key_bits_for(tb->rows));
 
     const int g = lanes_per_row(tb->dim);
     const int ng = kWG / g;
-    const int strip = pick_strip((int64_t)T * y.NP, ng);
+    const int strip = pick_strip(g);
     const int wgs = y.NP / (ng * strip);
     uint32_t *trail_row = reinterpret_cast<uint32_t *>(w8 + y.trail_row);
     uint8_t *lead_state = reinterpret_cast<uint8_t *>(w8 + y.lead_state);
-    float4 *part_lead = reinterpret_cast<float4 *>(w8 + y.part_lead);
-    float4 *part_trail = reinterpret_cast<float4 *>(w8 + y.part_trail);
+    f4 *part_lead = reinterpret_cast<f4 *>(w8 + y.part_lead);
+    f4 *part_trail = reinterpret_cast<f4 *>(w8 + y.part_trail);
     const int64_t blocks = (int64_t)wgs * T;
+    const bool xcd_aware = L > 1 && T % 8 == 0;
     if (blocks > 0x7fffffffLL)
-        return fail(SS_ERR_UNSUPPORTED, "ss_embbag_backward_update: grid too large");
+        return fail(SS_ERR_UNSUPPORTED, "ss_embbag_backward_apply: grid too large");
 #define SS_APPLY(S_)                                                             \
     SS_DISPATCH_G(g, hipLaunchKernelGGL(                                         \
                          (apply_kernel<G, S_>), dim3((unsigned)blocks), dim3(kWG), \
-                         0, s, tb->weights, tb->stale_bits, keys[cur], vals[cur],  \
-                         y.NP, grad, Bcap, D4, lr, wgs, trail_row, lead_state,     \
+                         0, s, tb->weights, keys[cur], vals[cur], y.NP, grad,      \
+                         Bcap, D4, lr, wgs, xcd_aware, trail_row, lead_state,      \
                          part_lead, part_trail))
     {
     ProfScope prof("apply_kernel", s);
@@ -675,10 +797,10 @@ int32_t launch_backward(const ss_tables *tb, const int32_t *idx, int Bcap, int L
 #undef SS_APPLY
     ProfScope prof("fixup_kernel", s);
     SS_DISPATCH_G(g, hipLaunchKernelGGL(fixup_kernel<G>, dim3((unsigned)blocks),
-                                        dim3(kWG), 0, s, tb->weights,
-                                        tb->stale_bits, D4, lr, wgs, trail_row,
-                                        lead_state, part_lead, part_trail));
-    return check_launch("ss_embbag_backward_update");
+                                        dim3(kWG), 0, s, tb->weights, D4, lr, wgs,
+                                        trail_row, lead_state, part_lead,
+                                        part_trail));
+    return check_launch("ss_embbag_backward_apply");
 }
 
 }  // namespace ss

@@ -2,7 +2,7 @@
 // Eq. 5 of the paper), thresholded into the stale bitmap, with the snapshot
 // refresh fused in so the hot rows are read from HBM once.
 //
-// A group of G lanes owns one hot slot; each lane holds one float4 of the row
+// A group of G lanes owns one hot slot; each lane holds one f4 of the row
 // and of its snapshot, squares the fp64 differences and the group reduces them
 // with wavefront shuffles.  fp64 is used because the verdict is compared
 // bit-exactly with a reference outside a 1e-6 relative band around T, which an
@@ -39,14 +39,13 @@ __global__ __launch_bounds__(kWG) void detect_kernel(
     uint32_t r = kNoRow;
     double acc = 0.0;
     if (valid) {
-        r = (uint32_t)hot_ids[t][h];
-        const float4 *__restrict__ W =
-            reinterpret_cast<const float4 *>(weights[t]) + (int64_t)r * D4;
-        float4 *__restrict__ S =
-            reinterpret_cast<float4 *>(snapshot[t]) + (int64_t)h * D4;
+        r = (uint32_t)as_global(hot_ids[t])[h];
+        const auto W =
+            as_global(reinterpret_cast<const f4 *>(weights[t])) + (int64_t)r * D4;
+        const auto S = as_global(reinterpret_cast<f4 *>(snapshot[t])) + (int64_t)h * D4;
         for (int col = c; col < D4; col += G) {
-            const float4 w = W[col];
-            const float4 s = S[col];
+            const f4 w = W[col];
+            const f4 s = S[col];
             const double ex = (double)w.x - (double)s.x;
             const double ey = (double)w.y - (double)s.y;
             const double ez = (double)w.z - (double)s.z;
@@ -65,8 +64,8 @@ __global__ __launch_bounds__(kWG) void detect_kernel(
     if (valid && c == 0) {
         const double dist = sqrt(acc);
         stale = threshold > 0.0f && dist <= (double)threshold;
-        if (stale_hot && stale_hot[t]) stale_hot[t][h] = stale ? 1 : 0;
-        if (drift && drift[t]) drift[t][h] = dist;
+        if (stale_hot && stale_hot[t]) as_global(stale_hot[t])[h] = stale ? 1 : 0;
+        if (drift && drift[t]) as_global(drift[t])[h] = dist;
     }
     if (c == 0) {
         s_row[g] = r;
@@ -82,7 +81,7 @@ __global__ __launch_bounds__(kWG) void detect_kernel(
             uint32_t mask = 0;
             for (int q = k; q < SLOTS && s_row[q] != kNoRow && (s_row[q] >> 5) == word; ++q)
                 if (s_flag[q]) mask |= 1u << (s_row[q] & 31);
-            if (mask) atomicOr(&bits[t][word], mask);
+            if (mask) atomicOr((uint32_t *)&as_global(bits[t])[word], mask);
         }
         if (stale_count) {
             const unsigned long long bal = __ballot(s_flag[k] != 0);

@@ -8,10 +8,11 @@
 // first non-stale lookup, so the kernel reads little more than idx[0][*][0].
 // A wavefront ballot plus popcount yields the number of kept samples per
 // workgroup.
-// Kernel 2 turns the per-workgroup counts into offsets (each workgroup sums the
-// counts before it: at most a few hundred values), ranks its kept samples with
-// ballot + popcount prefix sums, writes kept_ids in ascending order and copies
-// the index rows of the kept samples, table by table, to their compacted place.
+// Kernel 2 runs one workgroup per (tile of 256 samples, table).  It turns the
+// per-tile counts into an offset (summing the counts before it: at most a few
+// hundred values), ranks the tile's kept samples with ballot + popcount prefix
+// sums, writes kept_ids in ascending order and copies the index rows of the kept
+// samples of its table to their compacted place.
 #include "ss_common.h"
 
 namespace ss {
@@ -34,7 +35,7 @@ __global__ __launch_bounds__(kWG) void filter_flag_kernel(
             int c = 0, remaining = total;
             bool decided = false;
             for (int t = 0; t < T && !decided; ++t) {
-                const uint32_t *__restrict__ bt = bits[t];
+                const auto bt = as_global(bits[t]);
                 const int32_t *__restrict__ ip = idx + ((int64_t)t * B + b) * L;
                 for (int l = 0; l < L; ++l) {
                     if (bt) c += bit_set(bt, (uint32_t)ip[l]) ? 1 : 0;
@@ -62,17 +63,20 @@ __global__ __launch_bounds__(kWG) void filter_flag_kernel(
 }
 
 __global__ __launch_bounds__(kWG) void filter_compact_kernel(
-    const int32_t *__restrict__ idx, int T, int B, int L,
+    const int32_t *__restrict__ idx, int B, int L,
     const uint8_t *__restrict__ skip_mask,
     const int32_t *__restrict__ block_kept, int32_t *__restrict__ kept_ids,
     int32_t *__restrict__ n_kept, int32_t *__restrict__ idx_c)
 {
+    // grid: x = tile of 256 samples, y = table.  Every (x, y) workgroup repeats
+    // the cheap ranking of tile x and copies the index rows of table y only.
     __shared__ int s_red[kWG / 64];
     __shared__ int s_wbase[kWG / 64];
     __shared__ int32_t s_list[kWG];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int t = blockIdx.y;
 
-    // samples kept by the workgroups before this one
+    // samples kept by the tiles before this one
     int part = 0;
     for (int i = tid; i < (int)blockIdx.x; i += kWG) part += block_kept[i];
     for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
@@ -91,20 +95,30 @@ __global__ __launch_bounds__(kWG) void filter_compact_kernel(
         nk += s_wbase[w];
     }
     if (keep) {
-        kept_ids[base + wbase + before] = b;
+        if (t == 0) kept_ids[base + wbase + before] = b;
         s_list[wbase + before] = b;
     }
-    if (blockIdx.x == gridDim.x - 1 && tid == 0) *n_kept = base + nk;
+    if (t == 0 && blockIdx.x == gridDim.x - 1 && tid == 0) *n_kept = base + nk;
     __syncthreads();
 
     // idx_c[t][base + k][:] = idx[t][s_list[k]][:]
-    const int per_table = nk * L;
-    for (int t = 0; t < T; ++t) {
-        const int32_t *__restrict__ src = idx + (int64_t)t * B * L;
-        int32_t *__restrict__ dst = idx_c + ((int64_t)t * B + base) * L;
-        for (int e = tid; e < per_table; e += kWG) {
-            const int k = e / L, l = e - k * L;
-            dst[e] = src[(int64_t)s_list[k] * L + l];
+    const int32_t *__restrict__ src = idx + (int64_t)t * B * L;
+    int32_t *__restrict__ dst = idx_c + ((int64_t)t * B + base) * L;
+    if (L == 1) {
+        if (tid < nk) dst[tid] = src[s_list[tid]];
+    } else {
+        const int total = nk * L;
+        for (int e0 = tid; e0 < total; e0 += 4 * kWG) {
+            int32_t v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = e0 + u * kWG;
+                const int k = e / L, l = e - k * L;
+                v[u] = e < total ? src[(int64_t)s_list[k] * L + l] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (e0 + u * kWG < total) dst[e0 + u * kWG] = v[u];
         }
     }
 }
@@ -129,8 +143,8 @@ int32_t launch_filter(const ss_tables *tb, const int32_t *idx, int B, int L,
                        skip_mask, block_kept);
     }
     ProfScope prof("filter_compact_kernel", s);
-    hipLaunchKernelGGL(filter_compact_kernel, dim3(blocks), dim3(kWG), 0, s,
-                       idx, tb->num_tables, B, L, skip_mask, block_kept,
+    hipLaunchKernelGGL(filter_compact_kernel, dim3(blocks, tb->num_tables),
+                       dim3(kWG), 0, s, idx, B, L, skip_mask, block_kept,
                        kept_ids, n_kept, idx_c);
     return check_launch("ss_filter_batch");
 }

@@ -3,57 +3,102 @@
 //
 // Bound by HBM: every looked-up row is read once (duplicates hit L2 / MALL),
 // every pooled row written once, no arithmetic for L = 1.  A group of G lanes
-// owns one bag; each lane carries one float4 of the row, so a wavefront reads
+// owns a bag; each lane carries one f4 of the row, so a wavefront reads
 // 64/G rows per load instruction with 16-byte accesses that cover whole rows.
-// The indices of up to 8 lookups are fetched first and their row loads issued
-// back to back, so each lane keeps 8 independent 16-byte loads in flight.
+// What limits a gather is the number of independent loads in flight, so
+//   - one-hot bags (L = 1): a group takes 8 bags, fetches their 8 indices, then
+//     issues the 8 row loads back to back before the first store;
+//   - multi-hot bags: the indices of up to 24 lookups of the bag are fetched
+//     first and their row loads issued together.
+// When the number of tables is a multiple of 8, the workgroups of table t all
+// run on XCD t % 8 (workgroups are dealt to the 8 XCDs round-robin), so the hot
+// rows of a table are cached in one L2 instead of all eight.
 #include "ss_common.h"
 
 namespace ss {
 
+// blockIdx -> (table, tile).  xcd_aware needs T % 8 == 0.
+__device__ __forceinline__ void block_to_table_tile(int tiles_per_table, bool xcd_aware,
+                                                    int &t, int &tile)
+{
+    const int b = blockIdx.x;
+    if (xcd_aware) {
+        const int x = b & 7, k = b >> 3;
+        const int tl = k / tiles_per_table;
+        tile = k - tl * tiles_per_table;
+        t = tl * 8 + x;
+    } else {
+        t = b / tiles_per_table;
+        tile = b - t * tiles_per_table;
+    }
+}
+
 template <int G>
+__global__ __launch_bounds__(kWG) void forward_onehot_kernel(
+    const float *const *__restrict__ weights, const int32_t *__restrict__ idx,
+    int Bcap, const int32_t *__restrict__ n_valid, float *__restrict__ out,
+    int D4, int tiles_per_table, bool xcd_aware)
+{
+    constexpr int GROUPS = kWG / G, BPG = 8;
+    int t, tile;
+    block_to_table_tile(tiles_per_table, xcd_aware, t, tile);
+    const int n = clamp_valid(n_valid, Bcap);
+    const int g = threadIdx.x / G, c = threadIdx.x % G;
+    const int j0 = tile * GROUPS * BPG + g;      // bags j0 + k * GROUPS
+    if (j0 >= n) return;
+    const auto W = as_global(reinterpret_cast<const f4 *>(weights[t]));
+    const int32_t *__restrict__ ip = idx + (int64_t)t * Bcap;
+    f4 *__restrict__ o = reinterpret_cast<f4 *>(out) + (int64_t)t * Bcap * D4;
+
+    // bags past n_valid re-read bag j0 (always valid) and store nothing
+    int32_t r[BPG];
+#pragma unroll
+    for (int k = 0; k < BPG; ++k) {
+        const int j = j0 + k * GROUPS;
+        r[k] = ip[j < n ? j : j0];
+    }
+    for (int col = c; col < D4; col += G) {
+        f4 v[BPG];
+#pragma unroll
+        for (int k = 0; k < BPG; ++k) v[k] = W[(int64_t)r[k] * D4 + col];
+#pragma unroll
+        for (int k = 0; k < BPG; ++k)
+            if (j0 + k * GROUPS < n) o[(int64_t)(j0 + k * GROUPS) * D4 + col] = v[k];
+    }
+}
+
+// U = row loads issued together per lane.
+template <int G, int U>
 __global__ __launch_bounds__(kWG) void forward_kernel(
     const float *const *__restrict__ weights, const int32_t *__restrict__ idx,
     int Bcap, int L, const int32_t *__restrict__ n_valid,
-    float *__restrict__ out, int D4, int tiles_per_table)
+    float *__restrict__ out, int D4, int tiles_per_table, bool xcd_aware)
 {
     constexpr int BAGS = kWG / G;
-    const int t = blockIdx.x / tiles_per_table;
-    const int tile = blockIdx.x - t * tiles_per_table;
+    int t, tile;
+    block_to_table_tile(tiles_per_table, xcd_aware, t, tile);
     const int n = clamp_valid(n_valid, Bcap);
     const int j = tile * BAGS + (int)threadIdx.x / G;
     if (j >= n) return;
     const int c = threadIdx.x % G;
-    const float4 *__restrict__ W = reinterpret_cast<const float4 *>(weights[t]);
+    const auto W = as_global(reinterpret_cast<const f4 *>(weights[t]));
     const int32_t *__restrict__ ip = idx + ((int64_t)t * Bcap + j) * L;
-    float4 *__restrict__ o =
-        reinterpret_cast<float4 *>(out) + ((int64_t)t * Bcap + j) * D4;
+    f4 *__restrict__ o = reinterpret_cast<f4 *>(out) + ((int64_t)t * Bcap + j) * D4;
 
     for (int col = c; col < D4; col += G) {
-        // first row initialises the sum, so that L = 1 is a bit-exact copy
-        float4 acc = W[(int64_t)ip[0] * D4 + col];
-        int l = 1;
-        for (; l + 8 <= L; l += 8) {
-            int32_t r[8];
-            float4 v[8];
+        // the first row initialises the sum; later rows are added in bag order
+        f4 acc = f4{0.f, 0.f, 0.f, 0.f};
+        for (int l = 0; l < L; l += U) {
+            int32_t r[U];
+            f4 v[U];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) r[k] = ip[l + k];
+            for (int k = 0; k < U; ++k) r[k] = ip[l + k < L ? l + k : l];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] = W[(int64_t)r[k] * D4 + col];
+            for (int k = 0; k < U; ++k) v[k] = W[(int64_t)r[k] * D4 + col];
+            if (l == 0) acc = v[0];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) acc = acc + v[k];
-        }
-        if (l < L) {
-            int32_t r[8];
-            float4 v[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) r[k] = (l + k < L) ? ip[l + k] : 0;
-#pragma unroll
-            for (int k = 0; k < 8; ++k)
-                if (l + k < L) v[k] = W[(int64_t)r[k] * D4 + col];
-#pragma unroll
-            for (int k = 0; k < 8; ++k)
-                if (l + k < L) acc = acc + v[k];
+            for (int k = 0; k < U; ++k)
+                if (l + k < L && (l + k) > 0) acc = acc + v[k];
         }
         o[col] = acc;
     }
@@ -64,15 +109,30 @@ int32_t launch_forward(const ss_tables *tb, const int32_t *idx, int Bcap, int L,
 {
     const int D4 = tb->dim / 4;
     const int g = lanes_per_row(tb->dim);
-    const int bags = kWG / g;
+    const int bags = (kWG / g) * (L == 1 ? 8 : 1);
     const int tiles = (Bcap + bags - 1) / bags;
     const int64_t blocks = (int64_t)tiles * tb->num_tables;
+    const bool xcd_aware = tb->num_tables % 8 == 0;
     if (blocks > 0x7fffffffLL)
         return fail(SS_ERR_UNSUPPORTED, "ss_embbag_forward: grid too large");
     ProfScope prof("forward_kernel", s);
-    SS_DISPATCH_G(g, hipLaunchKernelGGL(forward_kernel<G>, dim3((unsigned)blocks),
-                                        dim3(kWG), 0, s, tb->weights, idx, Bcap,
-                                        L, n_valid, out, D4, tiles));
+    if (L == 1) {
+        SS_DISPATCH_G(g, hipLaunchKernelGGL(forward_onehot_kernel<G>,
+                                            dim3((unsigned)blocks), dim3(kWG), 0, s,
+                                            tb->weights, idx, Bcap, n_valid, out,
+                                            D4, tiles, xcd_aware));
+    } else {
+#define SS_FWD(U_)                                                                \
+    SS_DISPATCH_G(g, hipLaunchKernelGGL((forward_kernel<G, U_>),                   \
+                                        dim3((unsigned)blocks), dim3(kWG), 0, s,   \
+                                        tb->weights, idx, Bcap, L, n_valid, out,   \
+                                        D4, tiles, xcd_aware))
+        // enough loads per lane to cover the bag in one or two rounds
+        if (L <= 8) { SS_FWD(8); }
+        else if (L <= 16 || L > 24) { SS_FWD(16); }
+        else { SS_FWD(24); }
+#undef SS_FWD
+    }
     return check_launch("ss_embbag_forward");
 }
 

@@ -28,7 +28,7 @@ private:
     hipStream_t s_;
 };
 
-// Lanes that cooperate on one row: one float4 per lane, a power of two <= 64.
+// Lanes that cooperate on one row: one f4 per lane, a power of two <= 64.
 inline int lanes_per_row(int dim)
 {
     int d4 = dim / 4, g = 1;
@@ -57,14 +57,23 @@ __device__ __forceinline__ int clamp_valid(const int32_t *n_valid, int cap)
     return n < 0 ? 0 : (n > cap ? cap : n);
 }
 
+// Four consecutive floats of a row: a native vector, so that it can be loaded
+// and stored through pointers of any address space with one 16-byte access.
+typedef float f4 __attribute__((ext_vector_type(4)));
+
 // w - lr * g, element by element
-__device__ __forceinline__ float4 sgd(float4 w, float4 g, float lr)
+__device__ __forceinline__ f4 sgd(f4 w, f4 g, float lr) { return w - lr * g; }
+
+// Pointers read out of a device array of pointers (tables, bitmaps, snapshots)
+// carry no address space, which would make every access through them a FLAT
+// instruction.  They always point into global memory: say so.
+template <typename T> using gptr = T __attribute__((address_space(1))) *;
+template <typename T> __device__ __forceinline__ gptr<T> as_global(T *p)
 {
-    return make_float4(w.x - lr * g.x, w.y - lr * g.y, w.z - lr * g.z,
-                       w.w - lr * g.w);
+    return (gptr<T>)p;
 }
 
-__device__ __forceinline__ bool bit_set(const uint32_t *bits, uint32_t r)
+__device__ __forceinline__ bool bit_set(gptr<const uint32_t> bits, uint32_t r)
 {
     return (bits[r >> 5] >> (r & 31)) & 1u;
 }
@@ -79,9 +88,11 @@ int32_t launch_detect(const ss_tables *tb, int32_t *const *hot_ids, int H,
                       float **snapshot, float threshold, int refresh,
                       uint8_t **stale_hot, double **drift,
                       uint32_t *stale_count, hipStream_t s);
-int32_t launch_backward(const ss_tables *tb, const int32_t *idx, int Bcap, int L,
-                        const int32_t *n_valid, const float *grad, float lr,
-                        void *ws, hipStream_t s);
+int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bcap,
+                                int L, const int32_t *n_valid, void *ws,
+                                hipStream_t s);
+int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float *grad,
+                              float lr, void *ws, hipStream_t s);
 size_t backward_ws_bytes(int T, int Bcap, int L, int dim);
 size_t filter_ws_bytes(int T, int B, int L);
 

@@ -5,8 +5,10 @@ kept samples arrive from the dense part of the model) -> backward_update ->
 every K iterations: the first time capture the snapshot (the first period is
 the warm-up of section 3.1.1), afterwards detect_stale with a snapshot refresh.
 
-This class only owns buffers and issues the four library calls in order;
-nothing here synchronises with the host.
+This class only owns buffers and issues the library calls in order; nothing
+here synchronises with the host.  With overlap=True the grouping half of the
+backward pass (which needs only the indices) is issued on a second stream
+right after the filter, so that it runs next to the forward pass.
 """
 from __future__ import annotations
 
@@ -21,7 +23,8 @@ class EmbeddingStep:
     def __init__(self, weights: Sequence[torch.Tensor],
                  hot_ids: Sequence[torch.Tensor], batch: int, bag: int,
                  lr: float, threshold: float, snapshot_every: int,
-                 alpha: Optional[int] = None, diagnostics: bool = True):
+                 alpha: Optional[int] = None, diagnostics: bool = True,
+                 overlap: bool = False):
         self.tables = B.Tables(weights)
         self.bits = self.tables.new_bits()
         self.hot = B.HotState(self.tables, hot_ids, diagnostics=diagnostics)
@@ -43,18 +46,35 @@ class EmbeddingStep:
             dtype=torch.uint8, device=dev)
         self.it = 0
         self.have_snapshot = False
+        self.overlap = overlap
+        if overlap:
+            self.side = torch.cuda.Stream(device=dev)      # default priority
+            self.ev_filtered = torch.cuda.Event()
+            self.ev_grouped = torch.cuda.Event()
 
     def filter_forward(self, idx: torch.Tensor) -> None:
         """Classify and compact the batch, then pool the kept samples."""
         B.ss_filter_batch(self.tables, idx, self.alpha, self.skip_mask,
                           self.kept_ids, self.n_kept, self.idx_c, self.ws_filter)
+        if self.overlap:
+            main = torch.cuda.current_stream()
+            self.ev_filtered.record(main)
+            self.side.wait_event(self.ev_filtered)
+            B.ss_embbag_backward_prepare(self.tables, self.idx_c, self.n_kept,
+                                         self.ws_backward, stream=self.side)
+            self.ev_grouped.record(self.side)
         B.ss_embbag_forward(self.tables, self.idx_c, self.n_kept, self.pooled)
 
     def backward(self, grad_c: torch.Tensor) -> bool:
         """grad_c: fp32 [T, B, D], row j = gradient of the j-th kept sample.
         Returns True if this iteration ended with a detect pass."""
-        B.ss_embbag_backward_update(self.tables, self.idx_c, self.n_kept, grad_c,
-                                    self.lr, self.ws_backward)
+        if self.overlap:
+            torch.cuda.current_stream().wait_event(self.ev_grouped)
+            B.ss_embbag_backward_apply(self.tables, self.batch, self.bag, grad_c,
+                                       self.lr, self.ws_backward)
+        else:
+            B.ss_embbag_backward_update(self.tables, self.idx_c, self.n_kept, grad_c,
+                                        self.lr, self.ws_backward)
         detected = False
         if (self.it + 1) % self.K == 0:
             if not self.have_snapshot:
