@@ -4,7 +4,9 @@
 A step = filter_batch -> forward -> backward_update over one batch of seeded
 Zipf lookups, plus detect_stale on the iterations where the snapshot period
 ends.  Inputs are resident in HBM before the timed region starts.  Prints one
-JSON line (see the design doc for the fields).
+JSON line: whole-job samples/s ("value"), the roofline of the dominant kernel
+(algorithmic bytes per launch over its measured duration, against 8 TB/s), the
+per-kernel durations, the skip fraction, and the CPU oracle timed on this host.
 """
 import argparse
 import json
@@ -30,8 +32,10 @@ def parse():
     ap.add_argument("--threshold", type=float, default=None,
                     help="drift threshold T (default: the config's; inf freezes all hot rows)")
     ap.add_argument("--ring", type=int, default=16, help="distinct batches cycled through")
-    ap.add_argument("--no-overlap", action="store_true",
-                    help="issue everything on one stream")
+    ap.add_argument("--overlap", action="store_true",
+                    help="issue the grouping half of the backward pass on a second "
+                         "stream next to the forward pass (measured slower on one GPU "
+                         "when nothing else runs between forward and backward)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates rocprofv3's "
@@ -76,7 +80,7 @@ def main():
     grads = [torch.from_numpy(w.grads(k)).to(dev) for k in range(n_grads)]
     step = EmbeddingStep(weights, [torch.from_numpy(h).to(dev) for h in hot],
                          Bn, L, cfg.lr, thr, cfg.snapshot_every, diagnostics=False,
-                         overlap=not args.no_overlap)
+                         overlap=args.overlap)
     torch.cuda.synchronize()
     setup_s = time.time() - t0
 
@@ -128,7 +132,8 @@ def main():
     achieved = alg[dom] / (kern[dom]["avg_us"] * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                "traffic": None, "algorithmic_bytes_per_launch": alg[dom],
+                "traffic": measured_traffic(cfg.name, dom),
+                "algorithmic_bytes_per_launch": alg[dom],
                 "avg_kernel_us": kern[dom]["avg_us"]}
     step_bytes = alg["forward_kernel"] + alg["apply_kernel"]
 
@@ -140,7 +145,7 @@ def main():
         "config": {"workload": cfg.name, "tables": T, "rows": R, "dim": D, "batch": Bn,
                    "bag": L, "zipf_alpha": cfg.zipf_alpha, "threshold": thr,
                    "snapshot_every": cfg.snapshot_every, "ring": args.ring,
-                   "streams": 1 if args.no_overlap else 2},
+                   "streams": 2 if args.overlap else 1},
         "roofline": roofline,
         "whole_step": {"algorithmic_bytes": step_bytes,
                        "achieved_GBs": step_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -152,6 +157,20 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, w, idx_ring, hot, thr, args.cpu_seconds)
     print(json.dumps(out))
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter
+    summary of this workload (FETCH_SIZE + WRITE_SIZE, already scaled by the
+    copy-kernel calibration); None if there is no summary for it."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) == 4 and f[0] == kernel:
+            return float(f[3])
+    return None
 
 
 def cpu_baseline(cfg, w, idx_ring, hot, thr, budget_s):

@@ -172,9 +172,9 @@ int32_t ss_detect_stale(const ss_tables *tables, int32_t *const *hot_ids,
 
 /*
  * Measurement aid, off by default (not part of the method).  While enabled,
- * every kernel the library launches is bracketed by a pair of HIP events on
- * the launch stream (this is the one case in which the library creates HIP
- * objects).  ss_profile_report waits for the recorded events, writes one line
+ * every kernel the library launches carries a pair of HIP events that the
+ * runtime stamps with the start and end of that kernel's execution (this is the
+ * one case in which the library creates HIP objects).  ss_profile_report waits for the recorded events, writes one line
  * "kernel_name launches total_milliseconds" per kernel into buf (host memory,
  * NUL terminated), and forgets them.  At most 2^20 launches are recorded
  * between two reports.  Process-wide; meant for a single benchmarking thread.

@@ -58,8 +58,11 @@ std::vector<ProfRec> g_prof;
 constexpr size_t kProfMax = 1u << 20;
 }  // namespace
 
-ProfScope::ProfScope(const char *kernel, hipStream_t s) : slot_(-1), s_(s)
+static thread_local int t_prof_slot = -1;
+
+ProfScope::ProfScope(const char *kernel, hipStream_t)
 {
+    t_prof_slot = -1;
     if (!g_prof_on) return;
     std::lock_guard<std::mutex> lk(g_prof_mu);
     if (g_prof.size() >= kProfMax) return;
@@ -69,16 +72,21 @@ ProfScope::ProfScope(const char *kernel, hipStream_t s) : slot_(-1), s_(s)
         (void)hipEventDestroy(r.start);
         return;
     }
-    (void)hipEventRecord(r.start, s);
     g_prof.push_back(r);
-    slot_ = (int)g_prof.size() - 1;
+    t_prof_slot = (int)g_prof.size() - 1;
 }
 
-ProfScope::~ProfScope()
+ProfScope::~ProfScope() { t_prof_slot = -1; }
+
+bool prof_events(hipEvent_t *start, hipEvent_t *stop)
 {
-    if (slot_ < 0) return;
+    if (t_prof_slot < 0) return false;
     std::lock_guard<std::mutex> lk(g_prof_mu);
-    if (slot_ < (int)g_prof.size()) (void)hipEventRecord(g_prof[slot_].stop, s_);
+    if (t_prof_slot >= (int)g_prof.size()) return false;
+    *start = g_prof[t_prof_slot].start;
+    *stop = g_prof[t_prof_slot].stop;
+    t_prof_slot = -1;          // one launch per scope
+    return true;
 }
 
 static int32_t check_batch(const char *who, const void *idx, int64_t B, int64_t L,

@@ -410,7 +410,7 @@ template <int G, int S>
 __global__ __launch_bounds__(kWG) void apply_kernel(
     float *const *__restrict__ weights, const uint32_t *__restrict__ keys,
     const uint32_t *__restrict__ vals, int NP, const float *__restrict__ grad,
-    int Bcap, int D4, float lr, int wgs_per_table, bool xcd_aware,
+    int Bcap, int D4, float lr, int wgs_per_table, bool xcd_aware, bool stream_grads,
     uint32_t *__restrict__ meta_trail_row, uint8_t *__restrict__ meta_lead_state,
     f4 *__restrict__ part_lead, f4 *__restrict__ part_trail)
 {
@@ -503,7 +503,11 @@ __global__ __launch_bounds__(kWG) void apply_kernel(
         f4 gv[S], wv[S];
 #pragma unroll
         for (int i = 0; i < S; ++i)
-            if (live[i] && active) gv[i] = G4[(int64_t)smp[i] * D4 + col];
+            if (live[i] && active) {
+                // with one lookup per bag a gradient row is read exactly once
+                const f4 *gp = &G4[(int64_t)smp[i] * D4 + col];
+                gv[i] = stream_grads ? __builtin_nontemporal_load(gp) : *gp;
+            }
 #pragma unroll
         for (int i = 0; i < S; ++i)
             if (whole[i] && live[i] && active) wv[i] = W[(int64_t)row[i] * D4 + col];
@@ -712,7 +716,7 @@ int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bca
         const dim3 grid(1 << class_bits, T);
         ProfScope prof("class_sort_kernel", s);
 #define SS_LDS_SORT(I)                                                            \
-    hipLaunchKernelGGL(class_sort_kernel<I>, grid, dim3(1024), 0, s, idx, Bcap, L, \
+    launch(class_sort_kernel<I>, grid, dim3(1024), s, idx, Bcap, L, \
                        n_valid, tb->stale_bits, key_bits, class_bits, keys[0],     \
                        vals[0], y.NP)
         if (items <= 2) { SS_LDS_SORT(2); }
@@ -730,23 +734,19 @@ int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bca
             {
                 ProfScope prof("rs_hist_kernel", s);
                 if (pass == 0)
-                    hipLaunchKernelGGL(rs_hist_kernel<true>, grid, dim3(kRsThreads),
-                                       0, s, idx, Bcap, L, n_valid, tb->stale_bits,
+                    launch(rs_hist_kernel<true>, grid, dim3(kRsThreads), s, idx, Bcap, L, n_valid, tb->stale_bits,
                                        nullptr, y.NP, shift, nb, hist, y.tiles);
                 else
-                    hipLaunchKernelGGL(rs_hist_kernel<false>, grid, dim3(kRsThreads),
-                                       0, s, idx, Bcap, L, n_valid, nullptr,
+                    launch(rs_hist_kernel<false>, grid, dim3(kRsThreads), s, idx, Bcap, L, n_valid, nullptr,
                                        keys[in], y.NP, shift, nb, hist, y.tiles);
             }
             ProfScope prof("rs_scatter_kernel", s);
             if (pass == 0)
-                hipLaunchKernelGGL(rs_scatter_kernel<true>, grid, dim3(kRsThreads), 0,
-                                   s, idx, Bcap, L, n_valid, tb->stale_bits, nullptr,
+                launch(rs_scatter_kernel<true>, grid, dim3(kRsThreads), s, idx, Bcap, L, n_valid, tb->stale_bits, nullptr,
                                    nullptr, keys[out], vals[out], y.NP, shift, nb,
                                    hist, y.tiles);
             else
-                hipLaunchKernelGGL(rs_scatter_kernel<false>, grid, dim3(kRsThreads),
-                                   0, s, idx, Bcap, L, n_valid, nullptr, keys[in],
+                launch(rs_scatter_kernel<false>, grid, dim3(kRsThreads), s, idx, Bcap, L, n_valid, nullptr, keys[in],
                                    vals[in], keys[out], vals[out], y.NP, shift, nb,
                                    hist, y.tiles);
             cur = out;
@@ -783,10 +783,10 @@ int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float 
     if (blocks > 0x7fffffffLL)
         return fail(SS_ERR_UNSUPPORTED, "ss_embbag_backward_apply: grid too large");
 #define SS_APPLY(S_)                                                             \
-    SS_DISPATCH_G(g, hipLaunchKernelGGL(                                         \
-                         (apply_kernel<G, S_>), dim3((unsigned)blocks), dim3(kWG), \
-                         0, s, tb->weights, keys[cur], vals[cur], y.NP, grad,      \
-                         Bcap, D4, lr, wgs, xcd_aware, trail_row, lead_state,      \
+    SS_DISPATCH_G(g, launch(                                         \
+                         (apply_kernel<G, S_>), dim3((unsigned)blocks), dim3(kWG), s, tb->weights, keys[cur], vals[cur], y.NP, grad,      \
+                         Bcap, D4, lr, wgs, xcd_aware, L == 1, trail_row,          \
+                         lead_state,                                               \
                          part_lead, part_trail))
     {
     ProfScope prof("apply_kernel", s);
@@ -796,8 +796,8 @@ int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float 
     }
 #undef SS_APPLY
     ProfScope prof("fixup_kernel", s);
-    SS_DISPATCH_G(g, hipLaunchKernelGGL(fixup_kernel<G>, dim3((unsigned)blocks),
-                                        dim3(kWG), 0, s, tb->weights, D4, lr, wgs,
+    SS_DISPATCH_G(g, launch(fixup_kernel<G>, dim3((unsigned)blocks),
+                                        dim3(kWG), s, tb->weights, D4, lr, wgs,
                                         trail_row, lead_state, part_lead,
                                         part_trail));
     return check_launch("ss_embbag_backward_apply");

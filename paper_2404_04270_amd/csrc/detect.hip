@@ -101,12 +101,10 @@ int32_t launch_detect(const ss_tables *tb, int32_t *const *hot_ids, int H,
     const int slots = kWG / g;
     const int tiles = (H + slots - 1) / slots;
     if (stale_count)
-        hipLaunchKernelGGL(zero_u32_kernel, dim3((T + 255) / 256), dim3(256), 0,
-                           s, stale_count, T);
+        launch(zero_u32_kernel, dim3((T + 255) / 256), dim3(256), s, stale_count, T);
     ProfScope prof("detect_kernel", s);
-    SS_DISPATCH_G(g, hipLaunchKernelGGL(
-                         detect_kernel<G>, dim3((unsigned)(tiles * T)), dim3(kWG),
-                         0, s, tb->weights, tb->stale_bits, hot_ids, H, snapshot,
+    SS_DISPATCH_G(g, launch(
+                         detect_kernel<G>, dim3((unsigned)(tiles * T)), dim3(kWG), s, tb->weights, tb->stale_bits, hot_ids, H, snapshot,
                          threshold, refresh, stale_hot, drift, stale_count, D4,
                          tiles));
     return check_launch("ss_detect_stale");

@@ -138,13 +138,13 @@ int32_t launch_filter(const ss_tables *tb, const int32_t *idx, int B, int L,
     int32_t *block_kept = static_cast<int32_t *>(ws);
     {
         ProfScope prof("filter_flag_kernel", s);
-    hipLaunchKernelGGL(filter_flag_kernel, dim3(blocks), dim3(kWG), 0, s,
+    launch(filter_flag_kernel, dim3(blocks), dim3(kWG), s,
                        tb->stale_bits, idx, tb->num_tables, B, L, alpha,
                        skip_mask, block_kept);
     }
     ProfScope prof("filter_compact_kernel", s);
-    hipLaunchKernelGGL(filter_compact_kernel, dim3(blocks, tb->num_tables),
-                       dim3(kWG), 0, s, idx, B, L, skip_mask, block_kept,
+    launch(filter_compact_kernel, dim3(blocks, tb->num_tables),
+                       dim3(kWG), s, idx, B, L, skip_mask, block_kept,
                        kept_ids, n_kept, idx_c);
     return check_launch("ss_filter_batch");
 }

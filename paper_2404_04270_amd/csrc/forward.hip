@@ -117,14 +117,14 @@ int32_t launch_forward(const ss_tables *tb, const int32_t *idx, int Bcap, int L,
         return fail(SS_ERR_UNSUPPORTED, "ss_embbag_forward: grid too large");
     ProfScope prof("forward_kernel", s);
     if (L == 1) {
-        SS_DISPATCH_G(g, hipLaunchKernelGGL(forward_onehot_kernel<G>,
-                                            dim3((unsigned)blocks), dim3(kWG), 0, s,
+        SS_DISPATCH_G(g, launch(forward_onehot_kernel<G>,
+                                            dim3((unsigned)blocks), dim3(kWG), s,
                                             tb->weights, idx, Bcap, n_valid, out,
                                             D4, tiles, xcd_aware));
     } else {
 #define SS_FWD(U_)                                                                \
-    SS_DISPATCH_G(g, hipLaunchKernelGGL((forward_kernel<G, U_>),                   \
-                                        dim3((unsigned)blocks), dim3(kWG), 0, s,   \
+    SS_DISPATCH_G(g, launch((forward_kernel<G, U_>),                   \
+                                        dim3((unsigned)blocks), dim3(kWG), s,   \
                                         tb->weights, idx, Bcap, L, n_valid, out,   \
                                         D4, tiles, xcd_aware))
         // enough loads per lane to cover the bag in one or two rounds

@@ -1,6 +1,7 @@
 // Internal helpers shared by the kernels of libslipstream (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "slipstream.h"
@@ -17,16 +18,29 @@ int32_t check_tables(const ss_tables *tb, const char *who);
 // hipGetLastError() after a launch -> SS_OK / SS_ERR_HIP.
 int32_t check_launch(const char *who);
 
-// Optional per-kernel timing (ss_profile_enable): brackets the launches made
-// inside its scope with a pair of HIP events on the launch stream.
+// Optional per-kernel timing (ss_profile_enable).  While a ProfScope is alive on
+// this thread and profiling is on, launch() attaches a pair of events to the
+// kernel it dispatches; the runtime stamps them with the start and the end of
+// that dispatch on the GPU, so their difference is the kernel's own duration
+// (no launch gap, no neighbouring kernel).
 class ProfScope {
 public:
     ProfScope(const char *kernel, hipStream_t s);
     ~ProfScope();
-private:
-    int slot_;
-    hipStream_t s_;
 };
+// Events of the innermost live ProfScope, or false when profiling is off.
+bool prof_events(hipEvent_t *start, hipEvent_t *stop);
+
+template <typename... KArgs, typename... Args>
+inline void launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t s,
+                   Args... args)
+{
+    hipEvent_t e0, e1;
+    if (prof_events(&e0, &e1))
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, s, e0, e1, 0, args...);
+    else
+        hipLaunchKernelGGL(kernel, grid, block, 0, s, args...);
+}
 
 // Lanes that cooperate on one row: one f4 per lane, a power of two <= 64.
 inline int lanes_per_row(int dim)
