@@ -36,6 +36,9 @@ def parse():
                     help="issue the grouping half of the backward pass on a second "
                          "stream next to the forward pass (measured slower on one GPU "
                          "when nothing else runs between forward and backward)")
+    ap.add_argument("--grouped-forward", action="store_true",
+                    help="use ss_embbag_forward_grouped (forward and the grouping half of "
+                         "the backward pass in one launch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates rocprofv3's "
@@ -80,7 +83,7 @@ def main():
     grads = [torch.from_numpy(w.grads(k)).to(dev) for k in range(n_grads)]
     step = EmbeddingStep(weights, [torch.from_numpy(h).to(dev) for h in hot],
                          Bn, L, cfg.lr, thr, cfg.snapshot_every, diagnostics=False,
-                         overlap=args.overlap)
+                         overlap=args.overlap, grouped_forward=args.grouped_forward)
     torch.cuda.synchronize()
     setup_s = time.time() - t0
 
@@ -126,6 +129,7 @@ def main():
     row_b = D * 4
     alg = {
         "forward_kernel": U * row_b + nnz * 4 + T * Bn * row_b * kept_frac,
+        "forward_group_kernel": U * row_b + nnz * 4 + T * Bn * row_b * kept_frac,
         "apply_kernel": T * Bn * row_b * kept_frac + nnz * 4 + 2 * U * row_b,
     }
     dom = max((k for k in kern if k in alg), key=lambda k: kern[k]["total_ms"])
@@ -136,6 +140,7 @@ def main():
                 "algorithmic_bytes_per_launch": alg[dom],
                 "avg_kernel_us": kern[dom]["avg_us"]}
     step_bytes = alg["forward_kernel"] + alg["apply_kernel"]
+    # (filter: < 2 % of the step's bytes; grouping and fixup carry no algorithmic bytes)
 
     out = {
         "metric": "train samples/s through embedding fwd+update+stale-skip; achieved HBM GB/s",
@@ -145,7 +150,8 @@ def main():
         "config": {"workload": cfg.name, "tables": T, "rows": R, "dim": D, "batch": Bn,
                    "bag": L, "zipf_alpha": cfg.zipf_alpha, "threshold": thr,
                    "snapshot_every": cfg.snapshot_every, "ring": args.ring,
-                   "streams": 2 if args.overlap else 1},
+                   "streams": 2 if args.overlap else 1,
+                   "grouped_forward": bool(args.grouped_forward)},
         "roofline": roofline,
         "whole_step": {"algorithmic_bytes": step_bytes,
                        "achieved_GBs": step_bytes / (ms_per_step * 1e-3) / 1e9,

@@ -143,6 +143,21 @@ int32_t ss_embbag_backward_apply(const ss_tables *tables, int32_t Bcap, int32_t 
                                  size_t ws_bytes, void *stream);
 
 /*
+ * ss_embbag_forward(...) and ss_embbag_backward_prepare(...) of the same batch in
+ * one call: out receives the pooled vectors, bwd_ws is left ready for
+ * ss_embbag_backward_apply.  Both halves read the same indices, and the grouping
+ * is bound by latency while the gather is bound by HBM, so for one-hot batches
+ * of at most 16384 lookups per table (and row ids + sample numbers that fit 31
+ * bits together) a single launch runs the grouping in the shadow of the gather;
+ * other shapes get the two launches back to back.  Results are identical to the
+ * separate calls.
+ */
+int32_t ss_embbag_forward_grouped(const ss_tables *tables, const int32_t *idx,
+                                  int32_t Bcap, int32_t L, const int32_t *n_valid,
+                                  float *out, void *bwd_ws, size_t bwd_ws_bytes,
+                                  void *stream);
+
+/*
  * Snapshot comparison (section 3.1.2 snapshots; Eq. 1 and Eq. 5).  For hot
  * slot h of table t with r = hot_ids[t][h]:
  *     drift = || W_t[r][:] - snapshot_t[h][:] ||_2        (accumulated in fp64)

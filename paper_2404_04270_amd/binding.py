@@ -20,6 +20,7 @@ SYMBOLS = (
     "ss_embbag_forward", "ss_embbag_backward_update",
     "ss_backward_workspace_bytes", "ss_detect_stale", "ss_profile_enable",
     "ss_profile_report", "ss_embbag_backward_prepare", "ss_embbag_backward_apply",
+    "ss_embbag_forward_grouped",
 )
 
 
@@ -47,7 +48,7 @@ def _load():
     for n in ("ss_filter_batch", "ss_embbag_forward",
               "ss_embbag_backward_update", "ss_detect_stale",
               "ss_profile_report", "ss_embbag_backward_prepare",
-              "ss_embbag_backward_apply"):
+              "ss_embbag_backward_apply", "ss_embbag_forward_grouped"):
         getattr(lib, n).restype = C.c_int32
     return lib
 
@@ -233,6 +234,19 @@ def ss_embbag_backward_prepare(tables: Tables, idx: torch.Tensor,
         C.byref(tables.c), _dev_ptr(idx, torch.int32, "idx"), C.c_int32(Bcap),
         C.c_int32(L), _dev_ptr(n_valid, torch.int32, "n_valid"),
         _dev_ptr(ws, torch.uint8, "ws"), C.c_size_t(ws.numel()), _stream(stream)))
+
+
+def ss_embbag_forward_grouped(tables: Tables, idx: torch.Tensor,
+                              n_valid: Optional[torch.Tensor], out: torch.Tensor,
+                              bwd_ws: torch.Tensor, stream=None) -> None:
+    Bcap, L = _idx_shape(tables, idx)
+    if out.numel() < tables.num_tables * Bcap * tables.dim:
+        raise SlipstreamError("ss_embbag_forward_grouped: out is too small")
+    _check(_lib.ss_embbag_forward_grouped(
+        C.byref(tables.c), _dev_ptr(idx, torch.int32, "idx"), C.c_int32(Bcap),
+        C.c_int32(L), _dev_ptr(n_valid, torch.int32, "n_valid"),
+        _dev_ptr(out, torch.float32, "out"), _dev_ptr(bwd_ws, torch.uint8, "bwd_ws"),
+        C.c_size_t(bwd_ws.numel()), _stream(stream)))
 
 
 def ss_embbag_backward_apply(tables: Tables, Bcap: int, L: int, grad: torch.Tensor,

@@ -244,6 +244,31 @@ int32_t ss_embbag_backward_prepare(const ss_tables *tables, const int32_t *idx,
                                    static_cast<hipStream_t>(stream));
 }
 
+int32_t ss_embbag_forward_grouped(const ss_tables *tables, const int32_t *idx,
+                                  int32_t Bcap, int32_t L, const int32_t *n_valid,
+                                  float *out, void *bwd_ws, size_t bwd_ws_bytes,
+                                  void *stream)
+{
+    const char *who = "ss_embbag_forward_grouped";
+    int32_t rc = check_backward(who, tables, Bcap, L, bwd_ws, bwd_ws_bytes);
+    if (rc) return rc;
+    if (!idx) return fail(SS_ERR_INVALID_ARG, "%s: idx is NULL", who);
+    if (!out) return fail(SS_ERR_INVALID_ARG, "%s: out is NULL", who);
+    if (reinterpret_cast<uintptr_t>(out) % 16 != 0)
+        return fail(SS_ERR_INVALID_ARG, "%s: out is not 16-byte aligned", who);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (can_fuse_forward_group(tables, Bcap, L)) {
+        uint32_t *keys, *vals;
+        int NP;
+        backward_first_buffers(tables->num_tables, Bcap, L, tables->dim, bwd_ws, &keys,
+                               &vals, &NP);
+        return launch_forward_group(tables, idx, Bcap, n_valid, out, keys, vals, NP, s);
+    }
+    rc = launch_forward(tables, idx, Bcap, L, n_valid, out, s);
+    if (rc) return rc;
+    return launch_backward_prepare(tables, idx, Bcap, L, n_valid, bwd_ws, s);
+}
+
 int32_t ss_embbag_backward_apply(const ss_tables *tables, int32_t Bcap, int32_t L,
                                  const float *grad, float lr, void *ws,
                                  size_t ws_bytes, void *stream)

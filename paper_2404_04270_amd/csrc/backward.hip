@@ -36,6 +36,7 @@
 // Rows whose stale bit is set drop out in stage 1, before any gradient or
 // weight of theirs is read.  There are no floating-point atomics: every sum has a fixed
 // order, so the result is reproducible.
+#include "group_body.h"
 #include "ss_common.h"
 
 namespace ss {
@@ -50,204 +51,18 @@ constexpr int kRsItems = 8;            // ... keys per thread (tile = 2048 = kPa
 constexpr int kRsMaxBits = 10;         // ... widest digit
 constexpr int kRsMaxDig = 1 << kRsMaxBits;
 
-__device__ __forceinline__ uint64_t lanes_below(int lane)
-{
-    return (1ull << lane) - 1ull;
-}
-
-// Lanes of this wavefront whose digit equals mine (all 64 lanes must call).
-__device__ __forceinline__ uint64_t match_digit(uint32_t d, int nbits)
-{
-    uint64_t m = ~0ull;
-    for (int b = 0; b < nbits; ++b) {
-        const bool one = (d >> b) & 1u;
-        const uint64_t bal = __ballot(one);
-        m &= one ? bal : ~bal;
-    }
-    return m;
-}
-
-// Stable rank of this lane's key among the keys its wavefront has seen so far
-// with the same digit: the lowest lane of each digit group bumps the
-// wavefront's LDS counter once for the whole group and hands the old value to
-// the others.  cnt points at the wavefront's counters (one per digit).
-__device__ __forceinline__ uint32_t wave_rank(uint32_t *cnt, uint32_t d, int nbits,
-                                              int lane)
-{
-    const uint64_t m = match_digit(d, nbits);
-    const uint32_t before = __popcll(m & lanes_below(lane));
-    uint32_t base = 0;
-    if (before == 0) base = atomicAdd(&cnt[d], (uint32_t)__popcll(m));
-    base = __shfl(base, __ffsll((long long)m) - 1);
-    return base + before;
-}
-
-// Gives the sentinel key to lookups of stale rows.  All bitmap words are
-// requested before the first one is used.
-template <int N>
-__device__ __forceinline__ void drop_stale(gptr<const uint32_t> bt, uint32_t (&key)[N])
-{
-    if (!bt) return;
-    uint32_t word[N];
-#pragma unroll
-    for (int r = 0; r < N; ++r) word[r] = bt[key[r] == kNoRow ? 0u : key[r] >> 5];
-#pragma unroll
-    for (int r = 0; r < N; ++r)
-        if (key[r] != kNoRow && ((word[r] >> (key[r] & 31)) & 1u)) key[r] = kNoRow;
-}
-
-// Bits of the pass-th of npass digits when key_bits are split as evenly as
-// possible (earlier passes take the extra bits).
-__host__ __device__ inline int pass_bits(int key_bits, int npass, int pass)
-{
-    return key_bits / npass + (pass < key_bits % npass ? 1 : 0);
-}
-
-// ---------------------------------------------------------------------------
-// Stage 1a: up to 16384 lookups per table, one launch.
-// The apply stage needs equal rows to be neighbours, not ascending rows, so a
-// table is cut into P classes by the low bits of the row id and each class is
-// sorted by the remaining bits by its own workgroup: P times the parallelism of
-// a whole-table sort and fewer digit passes.  Every workgroup reads all lookups
-// of its table (cheap at this size), keeps its class in the original order,
-// and learns from the same read where its class starts in the output (the
-// number of lookups in lower classes).  Output order: class, remaining bits,
-// original position; sentinels last.
-// ---------------------------------------------------------------------------
-template <int ITEMS>
+// Stage 1a (class sort, one launch for up to 16384 lookups per table) lives in
+// group_body.h, shared with the fused forward + grouping launch.
+template <int ITEMS, bool PACKED>
 __global__ __launch_bounds__(1024) void class_sort_kernel(
     const int32_t *__restrict__ idx, int Bcap, int L,
     const int32_t *__restrict__ n_valid, const uint32_t *const *__restrict__ bits,
-    int key_bits, int class_bits, uint32_t *__restrict__ out_keys,
+    int key_bits, int class_bits, int val_bits, uint32_t *__restrict__ out_keys,
     uint32_t *__restrict__ out_vals, int NP)
 {
-    constexpr int NW = 16, CAP = 1024 * ITEMS;
-    __shared__ uint32_t s_keys[CAP];
-    __shared__ uint32_t s_vals[CAP];
-    __shared__ uint32_t s_cnt[2 * NW * 64];   // two sets: one is cleared while the
-    __shared__ uint32_t s_dig[64];            // other is in use
-    __shared__ uint32_t s_mine[NW], s_below[NW], s_real[NW];
-
-    const int cls = blockIdx.x, t = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n = clamp_valid(n_valid, Bcap) * L;
-    const int32_t *__restrict__ ip = idx + (int64_t)t * Bcap * L;
-    const auto bt = as_global(bits ? bits[t] : nullptr);
-    const uint32_t cmask = (1u << class_bits) - 1u;
-
-    uint32_t key[ITEMS], val[ITEMS], rank[ITEMS];
-#pragma unroll
-    for (int r = 0; r < ITEMS; ++r) {
-        const int pos = wave * ITEMS * 64 + r * 64 + lane;
-        key[r] = pos < n ? (uint32_t)ip[pos] : kNoRow;
-        val[r] = pos < n ? (uint32_t)(L == 1 ? pos : pos / L) : 0u;
-    }
-    drop_stale(bt, key);
-
-    // keep my class, in order; count the lookups of lower classes
-    uint32_t c_mine = 0, c_below = 0, c_real = 0, slot[ITEMS];
-#pragma unroll
-    for (int r = 0; r < ITEMS; ++r) {
-        const bool real = key[r] != kNoRow;
-        const uint32_t kc = key[r] & cmask;
-        const uint64_t bm = __ballot(real && kc == (uint32_t)cls);
-        slot[r] = c_mine + __popcll(bm & lanes_below(lane));
-        c_mine += __popcll(bm);
-        c_below += __popcll(__ballot(real && kc < (uint32_t)cls));
-        c_real += __popcll(__ballot(real));
-    }
-    if (lane == 0) {
-        s_mine[wave] = c_mine;
-        s_below[wave] = c_below;
-        s_real[wave] = c_real;
-    }
-    __syncthreads();
-    uint32_t woff = 0, m = 0, n_below = 0, n_real = 0;
-    for (int w = 0; w < NW; ++w) {
-        if (w < wave) woff += s_mine[w];
-        m += s_mine[w];
-        n_below += s_below[w];
-        n_real += s_real[w];
-    }
-#pragma unroll
-    for (int r = 0; r < ITEMS; ++r)
-        if (key[r] != kNoRow && (key[r] & cmask) == (uint32_t)cls) {
-            s_keys[woff + slot[r]] = key[r];
-            s_vals[woff + slot[r]] = val[r];
-        }
-    __syncthreads();
-
-    // LSD radix sort of the m kept lookups on bits [class_bits, key_bits).
-    // Digits of at most 6 bits: one wavefront can then turn the 16 x 64 counters
-    // into offsets with shuffles alone, which leaves three barriers per pass.
-    const int rounds = ((int)m + 1023) >> 10;       // keys per thread, <= ITEMS
-    const int rem_bits = key_bits - class_bits;
-    const int npass = (rem_bits + 5) / 6;
-    int shift = class_bits;
-    for (int i = tid; i < 2 * NW * 64; i += 1024) s_cnt[i] = 0;
-    __syncthreads();
-    for (int pass = 0; pass < npass; ++pass) {
-        uint32_t *cnt = s_cnt + (pass & 1) * (NW * 64);       // this pass
-        uint32_t *cnt_next = s_cnt + ((pass + 1) & 1) * (NW * 64);
-#pragma unroll
-        for (int r = 0; r < ITEMS; ++r)
-            if (r < rounds) {
-                const uint32_t pos = wave * rounds * 64 + r * 64 + lane;
-                key[r] = pos < m ? s_keys[pos] : kNoRow;
-                val[r] = pos < m ? s_vals[pos] : 0u;
-            }
-        const int nb = pass_bits(rem_bits, npass, pass);
-        const uint32_t dmask = (1u << nb) - 1u;
-#pragma unroll
-        for (int r = 0; r < ITEMS; ++r)
-            if (r < rounds) {
-                const uint32_t d = (key[r] >> shift) & dmask;
-                rank[r] = wave_rank(cnt + wave * 64, d, nb, lane);
-            }
-        __syncthreads();
-        if (wave == 0) {
-            // lane d: offsets of the 16 wavefronts for digit d, then digit starts
-            uint32_t run = 0;
-            if (lane <= (int)dmask)
-                for (int w = 0; w < NW; ++w) {
-                    const uint32_t c = cnt[w * 64 + lane];
-                    cnt[w * 64 + lane] = run;
-                    run += c;
-                }
-            uint32_t incl = run;
-            for (int off = 1; off < 64; off <<= 1) {
-                const uint32_t up = __shfl_up(incl, off);
-                if (lane >= off) incl += up;
-            }
-            s_dig[lane] = incl - run;
-        } else {
-            for (int i = tid - 64; i < NW * 64; i += 1024 - 64) cnt_next[i] = 0;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int r = 0; r < ITEMS; ++r)
-            if (r < rounds) {
-                const uint32_t d = (key[r] >> shift) & dmask;
-                const uint32_t p = s_dig[d] + cnt[wave * 64 + d] + rank[r];
-                if (p < m) {            // sentinels rank behind every real key
-                    s_keys[p] = key[r];
-                    s_vals[p] = val[r];
-                }
-            }
-        __syncthreads();
-        shift += nb;
-    }
-    uint32_t *__restrict__ ok = out_keys + (int64_t)t * NP;
-    uint32_t *__restrict__ ov = out_vals + (int64_t)t * NP;
-    for (uint32_t i = tid; i < m; i += 1024) {
-        ok[n_below + i] = s_keys[i];
-        ov[n_below + i] = s_vals[i];
-    }
-    if (cls == 0)
-        for (uint32_t i = n_real + tid; i < (uint32_t)NP; i += 1024) {
-            ok[i] = kNoRow;
-            ov[i] = 0;
-        }
+    class_sort_body<ITEMS, PACKED>(blockIdx.x, blockIdx.y, idx, Bcap, L, n_valid, bits,
+                                   key_bits, class_bits, val_bits, out_keys, out_vals,
+                                   NP);
 }
 
 // ---------------------------------------------------------------------------
@@ -686,6 +501,16 @@ size_t backward_ws_bytes(int T, int Bcap, int L, int dim)
     return make_layout(T, Bcap, L, dim).total;
 }
 
+void backward_first_buffers(int T, int Bcap, int L, int dim, void *ws, uint32_t **keys,
+                            uint32_t **vals, int *NP)
+{
+    const Layout y = make_layout(T, Bcap, L, dim);
+    char *w8 = static_cast<char *>(ws);
+    *keys = reinterpret_cast<uint32_t *>(w8 + y.keys0);
+    *vals = reinterpret_cast<uint32_t *>(w8 + y.vals0);
+    *NP = y.NP;
+}
+
 // Which of the two key/payload buffers holds the sorted lists after stage 1.
 static int sorted_buffer(const Layout &y, int key_bits)
 {
@@ -710,19 +535,24 @@ int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bca
     int cur = 0;   // buffer that holds the sorted lists
 
     if (y.NP <= kLdsSortMax) {
-        const int items = y.NP / 1024;   // NP is a multiple of 2048
-        int class_bits = 0;              // about 1024 lookups per class
-        while ((1024 << class_bits) < y.NP && class_bits < key_bits) ++class_bits;
-        const dim3 grid(1 << class_bits, T);
+        const ClassSortPlan cp = plan_class_sort(y.NP, Bcap, key_bits);
+        const dim3 grid(1 << cp.class_bits, T);
         ProfScope prof("class_sort_kernel", s);
-#define SS_LDS_SORT(I)                                                            \
-    launch(class_sort_kernel<I>, grid, dim3(1024), s, idx, Bcap, L, \
-                       n_valid, tb->stale_bits, key_bits, class_bits, keys[0],     \
-                       vals[0], y.NP)
-        if (items <= 2) { SS_LDS_SORT(2); }
-        else if (items <= 4) { SS_LDS_SORT(4); }
-        else if (items <= 8) { SS_LDS_SORT(8); }
-        else { SS_LDS_SORT(16); }
+#define SS_LDS_SORT(I, P)                                                          \
+    launch(class_sort_kernel<I, P>, grid, dim3(1024), s, idx, Bcap, L, n_valid,     \
+           tb->stale_bits, key_bits, cp.class_bits, cp.val_bits, keys[0], vals[0],  \
+           y.NP)
+        if (cp.packed) {
+            if (cp.items == 2) { SS_LDS_SORT(2, true); }
+            else if (cp.items == 4) { SS_LDS_SORT(4, true); }
+            else if (cp.items == 8) { SS_LDS_SORT(8, true); }
+            else { SS_LDS_SORT(16, true); }
+        } else {
+            if (cp.items == 2) { SS_LDS_SORT(2, false); }
+            else if (cp.items == 4) { SS_LDS_SORT(4, false); }
+            else if (cp.items == 8) { SS_LDS_SORT(8, false); }
+            else { SS_LDS_SORT(16, false); }
+        }
 #undef SS_LDS_SORT
     } else {
         const int npass = (key_bits + kRsMaxBits - 1) / kRsMaxBits;

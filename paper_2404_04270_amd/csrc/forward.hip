@@ -13,25 +13,10 @@
 // When the number of tables is a multiple of 8, the workgroups of table t all
 // run on XCD t % 8 (workgroups are dealt to the 8 XCDs round-robin), so the hot
 // rows of a table are cached in one L2 instead of all eight.
+#include "forward_body.h"
 #include "ss_common.h"
 
 namespace ss {
-
-// blockIdx -> (table, tile).  xcd_aware needs T % 8 == 0.
-__device__ __forceinline__ void block_to_table_tile(int tiles_per_table, bool xcd_aware,
-                                                    int &t, int &tile)
-{
-    const int b = blockIdx.x;
-    if (xcd_aware) {
-        const int x = b & 7, k = b >> 3;
-        const int tl = k / tiles_per_table;
-        tile = k - tl * tiles_per_table;
-        t = tl * 8 + x;
-    } else {
-        t = b / tiles_per_table;
-        tile = b - t * tiles_per_table;
-    }
-}
 
 template <int G>
 __global__ __launch_bounds__(kWG) void forward_onehot_kernel(
@@ -39,32 +24,8 @@ __global__ __launch_bounds__(kWG) void forward_onehot_kernel(
     int Bcap, const int32_t *__restrict__ n_valid, float *__restrict__ out,
     int D4, int tiles_per_table, bool xcd_aware)
 {
-    constexpr int GROUPS = kWG / G, BPG = 8;
-    int t, tile;
-    block_to_table_tile(tiles_per_table, xcd_aware, t, tile);
-    const int n = clamp_valid(n_valid, Bcap);
-    const int g = threadIdx.x / G, c = threadIdx.x % G;
-    const int j0 = tile * GROUPS * BPG + g;      // bags j0 + k * GROUPS
-    if (j0 >= n) return;
-    const auto W = as_global(reinterpret_cast<const f4 *>(weights[t]));
-    const int32_t *__restrict__ ip = idx + (int64_t)t * Bcap;
-    f4 *__restrict__ o = reinterpret_cast<f4 *>(out) + (int64_t)t * Bcap * D4;
-
-    // bags past n_valid re-read bag j0 (always valid) and store nothing
-    int32_t r[BPG];
-#pragma unroll
-    for (int k = 0; k < BPG; ++k) {
-        const int j = j0 + k * GROUPS;
-        r[k] = ip[j < n ? j : j0];
-    }
-    for (int col = c; col < D4; col += G) {
-        f4 v[BPG];
-#pragma unroll
-        for (int k = 0; k < BPG; ++k) v[k] = W[(int64_t)r[k] * D4 + col];
-#pragma unroll
-        for (int k = 0; k < BPG; ++k)
-            if (j0 + k * GROUPS < n) o[(int64_t)(j0 + k * GROUPS) * D4 + col] = v[k];
-    }
+    forward_onehot_body<G, kWG>(blockIdx.x, weights, idx, Bcap, n_valid, out, D4,
+                                tiles_per_table, xcd_aware);
 }
 
 // U = row loads issued together per lane.
@@ -76,7 +37,7 @@ __global__ __launch_bounds__(kWG) void forward_kernel(
 {
     constexpr int BAGS = kWG / G;
     int t, tile;
-    block_to_table_tile(tiles_per_table, xcd_aware, t, tile);
+    block_to_table_tile(blockIdx.x, tiles_per_table, xcd_aware, t, tile);
     const int n = clamp_valid(n_valid, Bcap);
     const int j = tile * BAGS + (int)threadIdx.x / G;
     if (j >= n) return;

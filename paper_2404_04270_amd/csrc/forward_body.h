@@ -1,0 +1,60 @@
+// One-hot pooled lookup as a device function, so that it can run as a kernel
+// of its own or as one role of the fused forward + grouping launch.
+#pragma once
+#include "ss_common.h"
+
+namespace ss {
+
+// block index b -> (table, tile).  xcd_aware needs T % 8 == 0: workgroups are
+// dealt to the 8 XCDs round-robin, so table t then stays on XCD t % 8.
+__device__ __forceinline__ void block_to_table_tile(int b, int tiles_per_table,
+                                                    bool xcd_aware, int &t, int &tile)
+{
+    if (xcd_aware) {
+        const int x = b & 7, k = b >> 3;
+        const int tl = k / tiles_per_table;
+        tile = k - tl * tiles_per_table;
+        t = tl * 8 + x;
+    } else {
+        t = b / tiles_per_table;
+        tile = b - t * tiles_per_table;
+    }
+}
+
+// L = 1: a group of G lanes takes 8 bags, fetches their indices, then issues
+// the 8 row loads back to back before the first store.
+template <int G, int THREADS>
+__device__ __forceinline__ void forward_onehot_body(
+    int b, const float *const *__restrict__ weights, const int32_t *__restrict__ idx,
+    int Bcap, const int32_t *__restrict__ n_valid, float *__restrict__ out, int D4,
+    int tiles_per_table, bool xcd_aware)
+{
+    constexpr int GROUPS = THREADS / G, BPG = 8;
+    int t, tile;
+    block_to_table_tile(b, tiles_per_table, xcd_aware, t, tile);
+    const int n = clamp_valid(n_valid, Bcap);
+    const int g = threadIdx.x / G, c = threadIdx.x % G;
+    const int j0 = tile * GROUPS * BPG + g;      // bags j0 + k * GROUPS
+    if (j0 >= n) return;
+    const auto W = as_global(reinterpret_cast<const f4 *>(weights[t]));
+    const int32_t *__restrict__ ip = idx + (int64_t)t * Bcap;
+    f4 *__restrict__ o = reinterpret_cast<f4 *>(out) + (int64_t)t * Bcap * D4;
+
+    // bags past n_valid re-read bag j0 (always valid) and store nothing
+    int32_t r[BPG];
+#pragma unroll
+    for (int k = 0; k < BPG; ++k) {
+        const int j = j0 + k * GROUPS;
+        r[k] = ip[j < n ? j : j0];
+    }
+    for (int col = c; col < D4; col += G) {
+        f4 v[BPG];
+#pragma unroll
+        for (int k = 0; k < BPG; ++k) v[k] = W[(int64_t)r[k] * D4 + col];
+#pragma unroll
+        for (int k = 0; k < BPG; ++k)
+            if (j0 + k * GROUPS < n) o[(int64_t)(j0 + k * GROUPS) * D4 + col] = v[k];
+    }
+}
+
+}  // namespace ss

@@ -24,7 +24,7 @@ class EmbeddingStep:
                  hot_ids: Sequence[torch.Tensor], batch: int, bag: int,
                  lr: float, threshold: float, snapshot_every: int,
                  alpha: Optional[int] = None, diagnostics: bool = True,
-                 overlap: bool = False):
+                 overlap: bool = False, grouped_forward: bool = False):
         self.tables = B.Tables(weights)
         self.bits = self.tables.new_bits()
         self.hot = B.HotState(self.tables, hot_ids, diagnostics=diagnostics)
@@ -47,6 +47,8 @@ class EmbeddingStep:
         self.it = 0
         self.have_snapshot = False
         self.overlap = overlap
+        # forward and the grouping half of the backward pass in one call
+        self.grouped_forward = grouped_forward and not overlap
         if overlap:
             self.side = torch.cuda.Stream(device=dev)      # default priority
             self.ev_filtered = torch.cuda.Event()
@@ -63,13 +65,18 @@ class EmbeddingStep:
             B.ss_embbag_backward_prepare(self.tables, self.idx_c, self.n_kept,
                                          self.ws_backward, stream=self.side)
             self.ev_grouped.record(self.side)
-        B.ss_embbag_forward(self.tables, self.idx_c, self.n_kept, self.pooled)
+        if self.grouped_forward:
+            B.ss_embbag_forward_grouped(self.tables, self.idx_c, self.n_kept,
+                                        self.pooled, self.ws_backward)
+        else:
+            B.ss_embbag_forward(self.tables, self.idx_c, self.n_kept, self.pooled)
 
     def backward(self, grad_c: torch.Tensor) -> bool:
         """grad_c: fp32 [T, B, D], row j = gradient of the j-th kept sample.
         Returns True if this iteration ended with a detect pass."""
-        if self.overlap:
-            torch.cuda.current_stream().wait_event(self.ev_grouped)
+        if self.overlap or self.grouped_forward:
+            if self.overlap:
+                torch.cuda.current_stream().wait_event(self.ev_grouped)
             B.ss_embbag_backward_apply(self.tables, self.batch, self.bag, grad_c,
                                        self.lr, self.ws_backward)
         else:

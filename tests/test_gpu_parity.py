@@ -281,8 +281,41 @@ def test_backward_closed_form_heavy_row(B, dev):
     assert np.all(np.delete(got, 17, axis=0) == 1.0)
 
 
+@pytest.mark.parametrize("T,R,D,Bc,L", [(3, 5000, 64, 3000, 1), (26, 1000000, 64, 8192, 1),
+                                        (2, 3000, 16, 700, 1), (2, 4000, 128, 500, 3),
+                                        (1, 1 << 30, 64, 4096, 1)])
+def test_forward_grouped_equals_forward_plus_prepare(B, dev, T, R, D, Bc, L):
+    rng = np.random.default_rng(470 + T)
+    Rsmall = min(R, 50000)            # tables hold Rsmall rows; indices stay below it
+    W = rand_tables(rng, T, Rsmall, D)
+    idx = torch.from_numpy(zipf_idx(rng, T, Bc, L, Rsmall)).to(dev)
+    grad = torch.from_numpy(rng.normal(0, 0.01, (T, Bc, D)).astype(np.float32)).to(dev)
+    bits = random_bits(rng, T, Rsmall, 0.1)
+    nv = torch.tensor([Bc - 7], dtype=torch.int32, device=dev)
+
+    def tables():
+        tb = B.Tables(to_dev(W, dev), bits_to_dev(bits, dev))
+        if R > Rsmall:                # claim a wide row-id range: unpacked grouping path
+            tb.rows = R
+            tb._refresh_struct()
+        return tb
+    a, b = tables(), tables()
+    ws = torch.empty(B.ss_backward_workspace_bytes(T, Bc, L, D), dtype=torch.uint8, device=dev)
+    out_a = torch.zeros((T, Bc, D), dtype=torch.float32, device=dev)
+    out_b = torch.zeros_like(out_a)
+    B.ss_embbag_forward(a, idx, nv, out_a)
+    B.ss_embbag_backward_update(a, idx, nv, grad, 0.01, ws)
+    ws.fill_(0x33)
+    B.ss_embbag_forward_grouped(b, idx, nv, out_b, ws)
+    B.ss_embbag_backward_apply(b, Bc, L, grad, 0.01, ws)
+    assert torch.equal(out_a, out_b)
+    for t in range(T):
+        assert torch.equal(a.weights[t], b.weights[t])
+
+
 # ------------------------------------------------------- whole protocol
-def run_lockstep(B, dev, cfg, n_iters, threshold, n_hot=None, overlap=False):
+def run_lockstep(B, dev, cfg, n_iters, threshold, n_hot=None, overlap=False,
+                 grouped_forward=False):
     """Oracle and GPU side by side; returns the number of borderline overrides."""
     from paper_2404_04270_amd.step import EmbeddingStep
     w = wl.Workload(cfg)
@@ -291,7 +324,8 @@ def run_lockstep(B, dev, cfg, n_iters, threshold, n_hot=None, overlap=False):
     W0 = [w.weights(t) for t in range(cfg.num_tables)]
     ref = OracleRun([x.copy() for x in W0], hot, cfg.lr, threshold, cfg.snapshot_every)
     gpu = EmbeddingStep(to_dev(W0, dev), to_dev(hot, dev), cfg.batch, cfg.bag,
-                        cfg.lr, threshold, cfg.snapshot_every, overlap=overlap)
+                        cfg.lr, threshold, cfg.snapshot_every, overlap=overlap,
+                        grouped_forward=grouped_forward)
     overrides = skipped = detects = 0
     for it in range(n_iters):
         g = w.grads(it)
@@ -341,9 +375,10 @@ def test_protocol_config1_full_run(B, dev):
     assert s["overrides"] == 0
 
 
-def test_protocol_config1_threshold_infinity_skips_all_hot_samples(B, dev):
+@pytest.mark.parametrize("grouped", [False, True])
+def test_protocol_config1_threshold_infinity_skips_all_hot_samples(B, dev, grouped):
     cfg = wl.CONFIGS[1].scaled(zipf_alpha=1.6, num_tables=3)
-    s = run_lockstep(B, dev, cfg, 50, math.inf)
+    s = run_lockstep(B, dev, cfg, 50, math.inf, grouped_forward=grouped)
     assert s["stale"] == cfg.num_tables * cfg.hot_rows
     assert s["skipped"] > 0
 
