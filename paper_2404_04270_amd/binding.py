@@ -13,7 +13,7 @@ from typing import List, Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-lib_path = os.path.join(_HERE, "libslipstream.so")
+lib_path = os.environ.get("SLIPSTREAM_LIB", os.path.join(_HERE, "libslipstream.so"))
 
 SYMBOLS = (
     "ss_last_error", "ss_filter_batch", "ss_filter_batch_workspace_bytes",

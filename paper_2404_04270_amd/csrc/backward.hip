@@ -50,6 +50,8 @@ constexpr int kRsThreads = 256;        // global radix sort: threads per tile
 constexpr int kRsItems = 8;            // ... keys per thread (tile = 2048 = kPad)
 constexpr int kRsMaxBits = 10;         // ... widest digit
 constexpr int kRsMaxDig = 1 << kRsMaxBits;
+constexpr int kApplyWG = 256;           // apply stage: threads per workgroup (512 and
+                                        // 1024 were measured slower: 22 and 38 us vs 18)
 
 // Stage 1a (class sort, one launch for up to 16384 lookups per table) lives in
 // group_body.h, shared with the fused forward + grouping launch.
@@ -222,33 +224,21 @@ __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
 // sums part_lead / part_trail of dim floats each.
 // ---------------------------------------------------------------------------
 template <int G, int S>
-__global__ __launch_bounds__(kWG) void apply_kernel(
+__global__ __launch_bounds__(kApplyWG) void apply_kernel(
     float *const *__restrict__ weights, const uint32_t *__restrict__ keys,
     const uint32_t *__restrict__ vals, int NP, const float *__restrict__ grad,
-    int Bcap, int D4, float lr, int wgs_per_table, bool xcd_aware, bool stream_grads,
+    int Bcap, int D4, float lr, int wgs_per_table, bool stream_grads,
     uint32_t *__restrict__ meta_trail_row, uint8_t *__restrict__ meta_lead_state,
     f4 *__restrict__ part_lead, f4 *__restrict__ part_trail)
 {
-    constexpr int NG = kWG / G;
-    __shared__ f4 s_lead[kWG];
-    __shared__ f4 s_trail[kWG];
+    constexpr int NG = kApplyWG / G;
+    __shared__ f4 s_lead[kApplyWG];
+    __shared__ f4 s_trail[kApplyWG];
     __shared__ uint32_t s_trail_row[NG];
     __shared__ uint8_t s_lead_state[NG];
 
-    // With several lookups per bag every gradient row is read L times from
-    // scattered strips.  If the tables can be dealt evenly to the 8 XCDs, all
-    // workgroups of table t run on XCD t % 8, whose L2 then holds that table's
-    // gradients (workgroups go to the XCDs round-robin).
-    int t, wg;
-    if (xcd_aware) {
-        const int x = blockIdx.x & 7, k = blockIdx.x >> 3;
-        const int tl = k / wgs_per_table;
-        wg = k - tl * wgs_per_table;
-        t = tl * 8 + x;
-    } else {
-        t = blockIdx.x / wgs_per_table;
-        wg = blockIdx.x - t * wgs_per_table;
-    }
+    const int t = blockIdx.x / wgs_per_table;
+    const int wg = blockIdx.x - t * wgs_per_table;
     const int tid = threadIdx.x, g = tid / G, c = tid % G;
     const uint32_t *__restrict__ kp = keys + (int64_t)t * NP;
     const uint32_t *__restrict__ vp = vals + (int64_t)t * NP;
@@ -460,7 +450,7 @@ Layout make_layout(int T, int Bcap, int L, int dim)
     y.NP = (int)align_up((size_t)nnz, kPad);
     y.tiles = y.NP / kPad;
     const int g = lanes_per_row(dim);
-    const int ng = kWG / g;
+    const int ng = kApplyWG / g;
     y.max_wgs = y.NP / (ng * 4);          // smallest strip is 4 lookups
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -601,7 +591,7 @@ int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float 
     const int cur = sorted_buffer(y, key_bits_for(tb->rows));
 
     const int g = lanes_per_row(tb->dim);
-    const int ng = kWG / g;
+    const int ng = kApplyWG / g;
     const int strip = pick_strip(g);
     const int wgs = y.NP / (ng * strip);
     uint32_t *trail_row = reinterpret_cast<uint32_t *>(w8 + y.trail_row);
@@ -609,13 +599,12 @@ int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float 
     f4 *part_lead = reinterpret_cast<f4 *>(w8 + y.part_lead);
     f4 *part_trail = reinterpret_cast<f4 *>(w8 + y.part_trail);
     const int64_t blocks = (int64_t)wgs * T;
-    const bool xcd_aware = L > 1 && T % 8 == 0;
     if (blocks > 0x7fffffffLL)
         return fail(SS_ERR_UNSUPPORTED, "ss_embbag_backward_apply: grid too large");
 #define SS_APPLY(S_)                                                             \
     SS_DISPATCH_G(g, launch(                                         \
-                         (apply_kernel<G, S_>), dim3((unsigned)blocks), dim3(kWG), s, tb->weights, keys[cur], vals[cur], y.NP, grad,      \
-                         Bcap, D4, lr, wgs, xcd_aware, L == 1, trail_row,          \
+                         (apply_kernel<G, S_>), dim3((unsigned)blocks), dim3(kApplyWG), s, tb->weights, keys[cur], vals[cur], y.NP, grad,      \
+                         Bcap, D4, lr, wgs, L == 1, trail_row,          \
                          lead_state,                                               \
                          part_lead, part_trail))
     {

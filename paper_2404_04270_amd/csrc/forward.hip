@@ -10,9 +10,9 @@
 //     issues the 8 row loads back to back before the first store;
 //   - multi-hot bags: the indices of up to 24 lookups of the bag are fetched
 //     first and their row loads issued together.
-// When the number of tables is a multiple of 8, the workgroups of table t all
-// run on XCD t % 8 (workgroups are dealt to the 8 XCDs round-robin), so the hot
-// rows of a table are cached in one L2 instead of all eight.
+// Pinning all workgroups of a table to one XCD (so that its hot rows live in one
+// L2 instead of eight) was measured and dropped: no change at 8 tables x 10M rows
+// (29.1 vs 28.8 us), the 256 MB memory-side cache already absorbs the re-reads.
 #include "forward_body.h"
 #include "ss_common.h"
 
@@ -22,10 +22,10 @@ template <int G>
 __global__ __launch_bounds__(kWG) void forward_onehot_kernel(
     const float *const *__restrict__ weights, const int32_t *__restrict__ idx,
     int Bcap, const int32_t *__restrict__ n_valid, float *__restrict__ out,
-    int D4, int tiles_per_table, bool xcd_aware)
+    int D4, int tiles_per_table)
 {
     forward_onehot_body<G, kWG>(blockIdx.x, weights, idx, Bcap, n_valid, out, D4,
-                                tiles_per_table, xcd_aware);
+                                tiles_per_table);
 }
 
 // U = row loads issued together per lane.
@@ -33,11 +33,11 @@ template <int G, int U>
 __global__ __launch_bounds__(kWG) void forward_kernel(
     const float *const *__restrict__ weights, const int32_t *__restrict__ idx,
     int Bcap, int L, const int32_t *__restrict__ n_valid,
-    float *__restrict__ out, int D4, int tiles_per_table, bool xcd_aware)
+    float *__restrict__ out, int D4, int tiles_per_table)
 {
     constexpr int BAGS = kWG / G;
     int t, tile;
-    block_to_table_tile(blockIdx.x, tiles_per_table, xcd_aware, t, tile);
+    block_to_table_tile(blockIdx.x, tiles_per_table, t, tile);
     const int n = clamp_valid(n_valid, Bcap);
     const int j = tile * BAGS + (int)threadIdx.x / G;
     if (j >= n) return;
@@ -73,7 +73,6 @@ int32_t launch_forward(const ss_tables *tb, const int32_t *idx, int Bcap, int L,
     const int bags = (kWG / g) * (L == 1 ? 8 : 1);
     const int tiles = (Bcap + bags - 1) / bags;
     const int64_t blocks = (int64_t)tiles * tb->num_tables;
-    const bool xcd_aware = tb->num_tables % 8 == 0;
     if (blocks > 0x7fffffffLL)
         return fail(SS_ERR_UNSUPPORTED, "ss_embbag_forward: grid too large");
     ProfScope prof("forward_kernel", s);
@@ -81,13 +80,13 @@ int32_t launch_forward(const ss_tables *tb, const int32_t *idx, int Bcap, int L,
         SS_DISPATCH_G(g, launch(forward_onehot_kernel<G>,
                                             dim3((unsigned)blocks), dim3(kWG), s,
                                             tb->weights, idx, Bcap, n_valid, out,
-                                            D4, tiles, xcd_aware));
+                                            D4, tiles));
     } else {
 #define SS_FWD(U_)                                                                \
     SS_DISPATCH_G(g, launch((forward_kernel<G, U_>),                   \
                                         dim3((unsigned)blocks), dim3(kWG), s,   \
                                         tb->weights, idx, Bcap, L, n_valid, out,   \
-                                        D4, tiles, xcd_aware))
+                                        D4, tiles))
         // enough loads per lane to cover the bag in one or two rounds
         if (L <= 8) { SS_FWD(8); }
         else if (L <= 16 || L > 24) { SS_FWD(16); }

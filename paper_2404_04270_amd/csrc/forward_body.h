@@ -5,20 +5,12 @@
 
 namespace ss {
 
-// block index b -> (table, tile).  xcd_aware needs T % 8 == 0: workgroups are
-// dealt to the 8 XCDs round-robin, so table t then stays on XCD t % 8.
-__device__ __forceinline__ void block_to_table_tile(int b, int tiles_per_table,
-                                                    bool xcd_aware, int &t, int &tile)
+// block index b -> (table, tile)
+__device__ __forceinline__ void block_to_table_tile(int b, int tiles_per_table, int &t,
+                                                    int &tile)
 {
-    if (xcd_aware) {
-        const int x = b & 7, k = b >> 3;
-        const int tl = k / tiles_per_table;
-        tile = k - tl * tiles_per_table;
-        t = tl * 8 + x;
-    } else {
-        t = b / tiles_per_table;
-        tile = b - t * tiles_per_table;
-    }
+    t = b / tiles_per_table;
+    tile = b - t * tiles_per_table;
 }
 
 // L = 1: a group of G lanes takes 8 bags, fetches their indices, then issues
@@ -27,11 +19,11 @@ template <int G, int THREADS>
 __device__ __forceinline__ void forward_onehot_body(
     int b, const float *const *__restrict__ weights, const int32_t *__restrict__ idx,
     int Bcap, const int32_t *__restrict__ n_valid, float *__restrict__ out, int D4,
-    int tiles_per_table, bool xcd_aware)
+    int tiles_per_table)
 {
     constexpr int GROUPS = THREADS / G, BPG = 8;
     int t, tile;
-    block_to_table_tile(b, tiles_per_table, xcd_aware, t, tile);
+    block_to_table_tile(b, tiles_per_table, t, tile);
     const int n = clamp_valid(n_valid, Bcap);
     const int g = threadIdx.x / G, c = threadIdx.x % G;
     const int j0 = tile * GROUPS * BPG + g;      // bags j0 + k * GROUPS

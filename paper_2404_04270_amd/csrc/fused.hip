@@ -19,7 +19,7 @@ template <int G, int ITEMS>
 __global__ __launch_bounds__(1024) void forward_group_kernel(
     const float *const *__restrict__ weights, const int32_t *__restrict__ idx,
     int Bcap, const int32_t *__restrict__ n_valid, float *__restrict__ out, int D4,
-    int tiles_per_table, bool xcd_aware, const uint32_t *const *__restrict__ bits,
+    int tiles_per_table, const uint32_t *const *__restrict__ bits,
     int key_bits, int class_bits, int val_bits, uint32_t *__restrict__ out_keys,
     uint32_t *__restrict__ out_vals, int NP, int group_blocks, bool interleave)
 {
@@ -43,7 +43,7 @@ __global__ __launch_bounds__(1024) void forward_group_kernel(
                                      out_vals, NP);
     } else {
         forward_onehot_body<G, 1024>(fb, weights, idx, Bcap, n_valid, out, D4,
-                                     tiles_per_table, xcd_aware);
+                                     tiles_per_table);
     }
 }
 
@@ -76,7 +76,7 @@ int32_t launch_forward_group(const ss_tables *tb, const int32_t *idx, int Bcap,
 #define SS_FG(I)                                                                    \
     SS_DISPATCH_G(g, launch(forward_group_kernel<G, I>, dim3((unsigned)blocks),     \
                             dim3(1024), s, tb->weights, idx, Bcap, n_valid, out, D4, \
-                            tiles, false, tb->stale_bits, key_bits, cp.class_bits,   \
+                            tiles, tb->stale_bits, key_bits, cp.class_bits,   \
                             cp.val_bits, keys, vals, NP, group_blocks,              \
                             (int64_t)tiles * T >= 2 * (int64_t)group_blocks))
     if (cp.items == 2) { SS_FG(2); }

@@ -217,6 +217,11 @@ BACKWARD_CASES = [
     (1, 500, 48, 200, 3, None, 0.3, 1.3),       # dim not a power of two
     (1, 300, 260, 100, 2, None, 0.3, 1.3),      # dim above 256
     (2, 400, 4, 5000, 1, 0, 0.0, 1.2),          # nothing valid
+    (1, 1, 4, 1, 1, None, 0.0, 1.2),            # one table, one row, one sample
+    (2, 9000, 64, 16384, 1, None, 0.05, 1.2),   # largest table the one-launch sort takes
+    (2, 9000, 64, 16385, 1, None, 0.05, 1.2),   # one more: global radix sort
+    (1, 5000, 32, 2048, 8, 2047, 1.0, 1.2),     # every row stale: nothing may move
+    (3, 70000, 16, 2049, 1, 1, 0.0, 1.2),       # a single valid sample
 ]
 
 
