@@ -2,7 +2,7 @@
 
 Only tests, the smoke check and the benchmark's CPU-baseline leg import this
 package.  It compiles `ss_oracle.c` with gcc on first use (or when the source
-is newer than the library) and exposes the four calls on NumPy arrays.
+is newer than the library) and exposes its calls on NumPy arrays.
 Nothing here touches the HIP library.
 """
 from __future__ import annotations
@@ -39,7 +39,8 @@ def _load():
     if _lib is None:
         _lib = C.CDLL(build())
         for name in ("oracle_embbag_forward", "oracle_embbag_backward_update",
-                     "oracle_detect_stale", "oracle_filter_batch"):
+                     "oracle_detect_stale", "oracle_filter_batch",
+                     "oracle_sample_drop", "oracle_drop_stats"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -172,3 +173,44 @@ def filter_batch(rows: int, stale_bits: Optional[Sequence[Optional[np.ndarray]]]
         C.c_void_p(idx_c.ctypes.data))
     _check_rc(rc, "filter_batch")
     return skip, kept[:n_kept.value].copy(), idx_c
+
+
+def sample_drop(weights: Sequence[np.ndarray], hot_ids: Sequence[np.ndarray],
+                snapshot: Sequence[np.ndarray], sidx: np.ndarray, alpha: int,
+                thresholds: Sequence[float]) -> np.ndarray:
+    """sidx int32 [T, S, L] -> uint32 [len(thresholds)]: droppable sampled inputs."""
+    T = len(weights)
+    R, D = weights[0].shape
+    H = hot_ids[0].shape[0]
+    _check(sidx, np.int32, "sidx")
+    assert sidx.ndim == 3 and sidx.shape[0] == T
+    S, L = sidx.shape[1], sidx.shape[2]
+    for t in range(T):
+        _check(weights[t], np.float32, "weights")
+        _check(hot_ids[t], np.int32, "hot_ids")
+        _check(snapshot[t], np.float32, "snapshot")
+        assert snapshot[t].shape == (H, D) and hot_ids[t].shape == (H,)
+        assert np.all(np.diff(hot_ids[t]) > 0), "hot_ids must be ascending"
+    thr = np.ascontiguousarray(thresholds, dtype=np.float32)
+    counts = np.zeros(thr.size, dtype=np.uint32)
+    rc = _load().oracle_sample_drop(
+        C.c_int(T), C.c_int64(R), C.c_int(D), _ptr_array(weights, T),
+        _ptr_array(hot_ids, T), C.c_int(H), _ptr_array(snapshot, T),
+        C.c_void_p(sidx.ctypes.data), C.c_int(S), C.c_int(L), C.c_int(alpha),
+        C.c_void_p(thr.ctypes.data), C.c_int(thr.size),
+        C.c_void_p(counts.ctypes.data))
+    _check_rc(rc, "sample_drop")
+    return counts
+
+
+def drop_stats(count: int, n_samples: int, population: int, n_hot_inputs: int,
+               t_crit: float) -> dict:
+    """Eq. 2-4: share D, sd, interval half-width, and the same on the count scale."""
+    out = (C.c_double * 8)()
+    rc = _load().oracle_drop_stats(C.c_uint32(count), C.c_int64(n_samples),
+                                   C.c_int64(population), C.c_int64(n_hot_inputs),
+                                   C.c_double(t_crit), out)
+    if rc != 0:
+        raise ValueError("drop_stats: inconsistent arguments")
+    keys = ("D", "sd", "half", "lo", "hi", "D_bar", "D_bar_lo", "D_bar_hi")
+    return dict(zip(keys, list(out)))

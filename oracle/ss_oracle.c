@@ -22,6 +22,12 @@
  *                      column of the paper's alpha table), partition identity
  *   general alpha between 1 and T*L-1: the paper's own drop percentages need
  *   its datasets, so for those values parity is pinned by brute force only.
+ *   sample_drop      - exact counts from constructed drifts, T = 0 / infinity,
+ *                      monotone in T, agreement with detect_stale + filter_batch
+ *   drop_stats       - binomial closed forms, vanishing interval for a full
+ *                      sample, the paper's critical value 3.340
+ *   the search for T over the sampled drop estimates has no stated stopping
+ *   rule in the paper: parity unpinned for it (it is host control flow).
  */
 #include <math.h>
 #include <stdint.h>
@@ -223,5 +229,101 @@ int oracle_filter_batch(int T, int64_t R, uint32_t *const *stale_bits,
                 idx_c[((int64_t)t * B + j) * L + l] =
                     idx[((int64_t)t * B + kept_ids[j]) * L + l];
     *n_kept = nk;
+    return 0;
+}
+
+/*
+ * Sampling block (section 3.3): how many of a sample of inputs could be dropped
+ * at each of several candidate thresholds.
+ *
+ * For sampled input s (its lookups sidx[t][s][l]) and threshold T_k, a lookup
+ * counts as stale when its row is a hot row (it has a snapshot) and the Euclidean
+ * distance between the row and its snapshot does not exceed T_k (Eq. 1, with the
+ * same readings as oracle_detect_stale: equality is stale, T_k = 0 flags nothing,
+ * rows outside the hot set are never stale).  The input is droppable when at
+ * least alpha of its T*L lookups are stale (section 3.4), and
+ *     counts[k] = number of droppable inputs among the n_samples sampled ones,
+ * which is |S| * D of Eq. 2.  Eq. 2 as printed sums the indicator of "varying"
+ * while calling the result the dropped share; the dropped share is what is
+ * wanted, so the indicator of "stale" is summed.  Nothing is modified.
+ * hot_ids[t] must be ascending.
+ */
+int oracle_sample_drop(int T, int64_t R, int D, float *const *W,
+                       int32_t *const *hot_ids, int H, float *const *snapshot,
+                       const int32_t *sidx, int n_samples, int L, int alpha,
+                       const float *thresholds, int n_thr, uint32_t *counts)
+{
+    for (int k = 0; k < n_thr; ++k)
+        counts[k] = 0;
+    for (int s = 0; s < n_samples; ++s) {
+        for (int k = 0; k < n_thr; ++k) {
+            double thr = (double)thresholds[k];
+            int stale_lookups = 0;
+            for (int t = 0; t < T; ++t) {
+                for (int l = 0; l < L; ++l) {
+                    int64_t r = sidx[((int64_t)t * n_samples + s) * L + l];
+                    if (r < 0 || r >= R)
+                        return -1;
+                    int h = -1;                 /* hot slot of row r, if any */
+                    for (int lo = 0, hi = H - 1; lo <= hi;) {
+                        int mid = lo + (hi - lo) / 2;
+                        if (hot_ids[t][mid] == r) { h = mid; break; }
+                        if (hot_ids[t][mid] < r) lo = mid + 1; else hi = mid - 1;
+                    }
+                    if (h < 0)
+                        continue;
+                    const float *w = W[t] + r * D;
+                    const float *sn = snapshot[t] + (int64_t)h * D;
+                    double d2 = 0.0;
+                    for (int d = 0; d < D; ++d) {
+                        double e = (double)w[d] - (double)sn[d];
+                        d2 += e * e;
+                    }
+                    if (thr > 0.0 && sqrt(d2) <= thr)
+                        ++stale_lookups;
+                }
+            }
+            if (stale_lookups >= alpha)
+                ++counts[k];
+        }
+    }
+    return 0;
+}
+
+/*
+ * Estimate of the dropped share with its confidence interval (Eq. 2-4).
+ *     D    = count / |S|                                   (Eq. 2)
+ *     sd   = sqrt( (1/|S|) * sum_s (delta_s - D)^2 )        (Eq. 3)
+ *          = sqrt( D (1 - D) )   because delta_s is 0 or 1
+ *     half = t * sqrt( ((I - |S|) / I) * (sd^2 / |S|) )     (Eq. 4; the paper writes
+ *            both |S| and m for the sample size: they are the same number)
+ * on the scale of the share D.  The paper states the interval around
+ * D_bar = D * I_hot, the expected number of dropped hot inputs; that interval is
+ * out[0..1] scaled by I_hot and is returned too.  t is the critical value the
+ * caller supplies (the paper uses 3.340 for 99.9 %).  I is the population the
+ * sample was drawn from.
+ * out = { D, sd, half, D - half, D + half, D_bar, D_bar - half*I_hot, D_bar + half*I_hot }
+ */
+int oracle_drop_stats(uint32_t count, int64_t n_samples, int64_t population,
+                      int64_t n_hot_inputs, double t_crit, double *out)
+{
+    if (n_samples <= 0 || population < n_samples || count > (uint64_t)n_samples)
+        return -3;
+    double n = (double)n_samples;
+    double Dk = (double)count / n;
+    /* Eq. 3 written out over the two kinds of samples */
+    double ss = (double)count * (1.0 - Dk) * (1.0 - Dk) +
+                ((double)n_samples - (double)count) * (0.0 - Dk) * (0.0 - Dk);
+    double sd = sqrt(ss / n);
+    double fpc = ((double)population - n) / (double)population;
+    double half = t_crit * sqrt(fpc * (sd * sd / n));
+    out[0] = Dk;
+    out[1] = sd;
+    out[2] = half;
+    out[3] = Dk - half;
+    out[4] = Dk + half;
+    out[5] = Dk * (double)n_hot_inputs;
+    out[6] = (Dk - half) * (double)n_hot_inputs;
+    out[7] = (Dk + half) * (double)n_hot_inputs;
     return 0;
 }

@@ -389,3 +389,100 @@ def test_protocol_stale_set_is_monotone_and_cold_rows_follow_sgd():
         nonhot = np.setdiff1d(np.flatnonzero(
             np.unpackbits(run.bits[t].view(np.uint8), bitorder="little")), hot[t])
         assert nonhot.size == 0          # only hot rows can ever be flagged
+
+
+# -------------------------------------------------- sampling block (Eq. 1-4)
+def sample_problem(D=16):
+    """Two tables; hot rows with drifts constructed exactly: slot h of table t has
+    W = S + a*1 with a = 2^-12 * (h + 1), so drift = a * sqrt(D) (D = 16: 4a)."""
+    R, H = 60, 5
+    hot = [np.array([3, 10, 11, 40, 59], dtype=np.int32),
+           np.array([0, 7, 20, 21, 30], dtype=np.int32)]
+    rng = np.random.default_rng(40)
+    W = [rng.uniform(-1, 1, (R, D)).astype(np.float32) for _ in range(2)]
+    W = [np.round(w * 64) / 64 for w in W]
+    W = [w.astype(np.float32) for w in W]
+    snap = []
+    for t in range(2):
+        a = (2.0 ** -12) * (np.arange(H) + 1)
+        snap.append((W[t][hot[t]] - a[:, None]).astype(np.float32))
+    drift = 4.0 * (2.0 ** -12) * (np.arange(H) + 1)      # exact, same for both tables
+    return W, hot, snap, drift
+
+
+def test_sample_drop_exact_counts_from_constructed_drifts():
+    W, hot, snap, drift = sample_problem()
+    # inputs: (table0 row, table1 row), L = 1
+    rows0 = [3, 10, 11, 40, 59, 3, 5, 40]        # 5 is not hot
+    rows1 = [0, 7, 20, 21, 30, 30, 0, 1]         # 1 is not hot
+    sidx = np.array([[[r] for r in rows0], [[r] for r in rows1]], dtype=np.int32)
+    slot = lambda ids, r: int(np.flatnonzero(ids == r)[0]) if r in ids else None
+    thr = [0.0, float(drift[0]), float(np.nextafter(np.float32(drift[0]), np.float32(0))),
+           float(drift[2]), float(drift[4]), math.inf]
+    for alpha in (1, 2):
+        got = oracle.sample_drop(W, hot, snap, sidx, alpha, thr)
+        want = []
+        for T_ in thr:
+            n = 0
+            for a, b in zip(rows0, rows1):
+                c = 0
+                for ids, r in ((hot[0], a), (hot[1], b)):
+                    h = slot(ids, r)
+                    if h is not None and T_ > 0 and drift[h] <= np.float32(T_):
+                        c += 1
+                n += c >= alpha
+            want.append(n)
+        assert got.tolist() == want, alpha
+        assert got[0] == 0                                  # T = 0 flags nothing
+        assert np.all(np.diff(got.astype(int)) >= 0) or thr != sorted(thr)
+    # alpha = 2, T = inf: inputs whose both rows are hot (6 of the 8)
+    assert oracle.sample_drop(W, hot, snap, sidx, 2, [math.inf])[0] == 6
+    # alpha above the number of lookups: nothing can be dropped; alpha = 0: all
+    assert oracle.sample_drop(W, hot, snap, sidx, 3, [math.inf])[0] == 0
+    assert oracle.sample_drop(W, hot, snap, sidx, 0, [0.0])[0] == 8
+
+
+def test_sample_drop_agrees_with_detect_then_filter():
+    # dropping at threshold T == detect_stale at T followed by filter_batch
+    rng = np.random.default_rng(41)
+    T, R, D, H, S, L = 3, 200, 8, 40, 150, 2
+    W = rand_tables(rng, T, R, D)
+    hot = [np.sort(rng.choice(R, H, replace=False)).astype(np.int32) for _ in range(T)]
+    snap = [(W[t][hot[t]] + rng.normal(0, 1e-3, (H, D))).astype(np.float32) for t in range(T)]
+    sidx = np.stack([rng.choice(hot[t], (S, L)) for t in range(T)]).astype(np.int32)
+    sidx[:, ::7] = rng.integers(0, R, (T, len(range(0, S, 7)), L))     # some cold lookups
+    thr = [5e-4, 2e-3, 3e-3, 6e-3]
+    for alpha in (1, 3, T * L):
+        got = oracle.sample_drop(W, hot, snap, sidx, alpha, thr)
+        for k, T_ in enumerate(thr):
+            bits = [np.zeros((R + 31) // 32, np.uint32) for _ in range(T)]
+            oracle.detect_stale(W, bits, hot, [s.copy() for s in snap], T_, refresh=False)
+            skip, _, _ = oracle.filter_batch(R, bits, sidx, alpha)
+            assert got[k] == skip.sum()
+    assert 0 < got[1] < S
+
+
+def test_drop_stats_closed_forms_and_paper_constant():
+    t_paper = [float(l.split()[1]) for l in open(os.path.join(GOLDEN, "t_critical.txt"))
+               if l.strip() and not l.startswith("#")][0]
+    assert t_paper == 3.340
+    st = oracle.drop_stats(30, 100, 100000, 50000, t_paper)
+    assert st["D"] == 0.3
+    assert abs(st["sd"] - math.sqrt(0.3 * 0.7)) < 1e-15            # binary indicator
+    half = t_paper * math.sqrt((100000 - 100) / 100000 * (0.3 * 0.7) / 100)
+    assert abs(st["half"] - half) < 1e-15
+    assert abs(st["lo"] - (0.3 - half)) < 1e-15 and abs(st["hi"] - (0.3 + half)) < 1e-15
+    assert st["D_bar"] == 0.3 * 50000
+    assert abs(st["D_bar_hi"] - (0.3 + half) * 50000) < 1e-9
+    # the whole population sampled: no uncertainty left
+    full = oracle.drop_stats(40, 200, 200, 200, t_paper)
+    assert full["half"] == 0.0 and full["D"] == 0.2
+    # no variation in the sample: sd = 0
+    assert oracle.drop_stats(0, 50, 1000, 1000, t_paper)["sd"] == 0.0
+    assert oracle.drop_stats(50, 50, 1000, 1000, t_paper)["sd"] == 0.0
+    # four times the sample: half the width (up to the population correction)
+    a = oracle.drop_stats(30, 100, 10**9, 1, 1.0)["half"]
+    b = oracle.drop_stats(120, 400, 10**9, 1, 1.0)["half"]
+    assert abs(a / b - 2.0) < 1e-6
+    with pytest.raises(ValueError):
+        oracle.drop_stats(5, 4, 100, 100, 1.0)
