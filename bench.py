@@ -44,6 +44,10 @@ def parse():
                     help="also run a plain 1 GiB device copy (calibrates rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters against a known size)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--sampling-probe", type=int, default=0, metavar="S",
+                    help="after the timed steps, also time the sampling block (drift of "
+                         "the hot rows once, then drop counts of S sampled inputs for 32 "
+                         "candidate thresholds in one pass) and report it beside the step")
     return ap.parse_args()
 
 
@@ -160,9 +164,44 @@ def main():
         "kernels": kern, "setup_s": setup_s,
     }
 
+    if args.sampling_probe > 0:
+        out["sampling_block"] = sampling_probe(B, step, idx_d, args.sampling_probe, thr)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, w, idx_ring, hot, thr, args.cpu_seconds)
     print(json.dumps(out))
+
+
+def sampling_probe(B, step, idx_d, S, thr):
+    """Kernel durations of the sampling block on the state the steps left behind."""
+    import torch
+    from paper_2404_04270_amd.sampling import SamplingBlock, geometric_ladder
+    T = step.tables.num_tables
+    ring, _, Bn, L = idx_d.shape
+    S = min(S, ring * Bn)
+    # the first S inputs of the ring, as one [T, S, L] array
+    sidx = idx_d.permute(1, 0, 2, 3).reshape(T, ring * Bn, L)[:, :S].contiguous()
+    hot = B.HotState(step.tables, step.hot.hot_ids, diagnostics=True)
+    for dst, src in zip(hot.snapshot, step.hot.snapshot):
+        dst.copy_(src)
+    blk = SamplingBlock(step.tables, hot, sidx, alpha=T * L, population=ring * Bn)
+    centre = thr if 0 < thr < float("inf") else 1e-3
+    ladder = geometric_ladder(centre / 30, centre * 30, B.MAX_THRESHOLDS)
+    reps = 20
+    blk.refresh_drift()
+    blk.counts_for(ladder)                                   # warm-up
+    B.ss_profile_enable(True)
+    for _ in range(reps):
+        blk.refresh_drift()
+        B.ss_sample_drop(hot, sidx, blk.alpha, ladder, blk.counts)
+    torch.cuda.synchronize()
+    B.ss_profile_enable(False)
+    prof = B.ss_profile_report()
+    counts = blk.counts_for(ladder)
+    return {"samples": S, "thresholds": len(ladder), "alpha": blk.alpha,
+            "hot_rows_per_table": hot.H,
+            "drift_pass_us": 1e3 * prof["detect_kernel"][1] / prof["detect_kernel"][0],
+            "count_pass_us": 1e3 * prof["sample_drop_kernel"][1] / prof["sample_drop_kernel"][0],
+            "counts_first_last": [counts[0], counts[-1]]}
 
 
 def measured_traffic(workload, kernel):

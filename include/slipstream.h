@@ -186,6 +186,63 @@ int32_t ss_detect_stale(const ss_tables *tables, int32_t *const *hot_ids,
                         double **drift, uint32_t *stale_count, void *stream);
 
 /*
+ * Input sampling block (section 3.3.2-3.3.3, Eq. 1 and the count of Eq. 2): on
+ * a sample of S inputs, how many could be dropped under each of n_thr candidate
+ * thresholds.  With stale_k(row) = row is hot, T_k > 0 and drift(row) <= T_k
+ * (the verdict ss_detect_stale would reach with threshold T_k),
+ *     counts[k] = #{ sampled inputs with at least alpha lookups (out of their
+ *                    T*L) for which stale_k holds }
+ * Eq. 2 as printed sums the "varying" indicator while its text asks for the
+ * dropped share; the dropped share is what the search over T needs, so the
+ * stale indicator is counted.  Rows outside the hot set are never stale.
+ * The drifts come from a call of ss_detect_stale with a non-NULL drift argument
+ * (threshold 0 and refresh_snapshot 0 leave bitmaps and snapshots untouched), so
+ * the hot rows are read once however many thresholds and samples follow.
+ * Nothing but counts is written.
+ *
+ *   num_tables   T, 1..65535
+ *   hot_ids      device array of T device pointers, each int32 [H], strictly
+ *                ascending (rows are mapped to hot slots by bisection; the
+ *                order is not checked)
+ *   drift        device array of T device pointers, each fp64 [H]: drift of hot
+ *                slot h of table t, none NULL
+ *   sidx         device int32 [T][S][L]: lookups of the sampled inputs; a value
+ *                that is no hot row id (out-of-range ones included) counts as
+ *                not stale
+ *   alpha        >= 0; alpha = 0 makes every sampled input droppable, alpha >
+ *                T*L none, alpha = T*L is the "every lookup stale" rule of Eq. 6-8
+ *   thresholds   HOST array of n_thr floats (1 <= n_thr <= SS_MAX_THRESHOLDS),
+ *                read before the call returns; any order; NaN is rejected
+ *   counts       device uint32 [n_thr], overwritten
+ * S = 0 or H = 0 are allowed (no row is stale then).
+ */
+#define SS_MAX_THRESHOLDS 32
+int32_t ss_sample_drop(int32_t num_tables, int32_t *const *hot_ids, int32_t H,
+                       double *const *drift, const int32_t *sidx, int32_t S,
+                       int32_t L, int32_t alpha, const float *thresholds,
+                       int32_t n_thr, uint32_t *counts, void *stream);
+
+/*
+ * Estimate of the dropped share from one count of ss_sample_drop, with its
+ * confidence interval (Eq. 2-4).  Host arithmetic only, fp64; no GPU work.
+ *     D    = count / n_samples                                         (Eq. 2)
+ *     sd   = sqrt( mean over the sample of (indicator - D)^2 )          (Eq. 3)
+ *     half = t_crit * sqrt( (population - n_samples) / population
+ *                           * sd^2 / n_samples )                        (Eq. 4)
+ * Eq. 4 writes the sample size both as |S| and as m: one number, n_samples.
+ * population is the number of inputs the sample was drawn from without
+ * replacement; n_hot_inputs scales the share to the expected number of dropped
+ * hot inputs, the quantity the paper's interval is centred on (normally equal
+ * to population).  t_crit is the critical value, 3.340 in the paper for 99.9 %.
+ *   out   HOST double[8]: D, sd, half, D - half, D + half,
+ *         D * n_hot_inputs, (D - half) * n_hot_inputs, (D + half) * n_hot_inputs
+ * Errors: n_samples < 1, population < n_samples, count > n_samples,
+ * n_hot_inputs < 0, t_crit negative or NaN, out NULL.
+ */
+int32_t ss_drop_stats(uint32_t count, int64_t n_samples, int64_t population,
+                      int64_t n_hot_inputs, double t_crit, double *out);
+
+/*
  * Measurement aid, off by default (not part of the method).  While enabled,
  * every kernel the library launches carries a pair of HIP events that the
  * runtime stamps with the start and end of that kernel's execution (this is the

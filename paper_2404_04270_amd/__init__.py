@@ -13,7 +13,7 @@ _BINDING_NAMES = (
     "ss_backward_workspace_bytes", "ss_last_error", "SlipstreamError",
     "ss_profile_enable", "ss_profile_report", "HotState",
     "ss_embbag_backward_prepare", "ss_embbag_backward_apply",
-    "ss_embbag_forward_grouped",
+    "ss_embbag_forward_grouped", "ss_sample_drop", "ss_drop_stats",
     "EmbeddingStep", "lib_path",
 )
 

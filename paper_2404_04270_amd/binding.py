@@ -20,7 +20,7 @@ SYMBOLS = (
     "ss_embbag_forward", "ss_embbag_backward_update",
     "ss_backward_workspace_bytes", "ss_detect_stale", "ss_profile_enable",
     "ss_profile_report", "ss_embbag_backward_prepare", "ss_embbag_backward_apply",
-    "ss_embbag_forward_grouped",
+    "ss_embbag_forward_grouped", "ss_sample_drop", "ss_drop_stats",
 )
 
 
@@ -48,7 +48,8 @@ def _load():
     for n in ("ss_filter_batch", "ss_embbag_forward",
               "ss_embbag_backward_update", "ss_detect_stale",
               "ss_profile_report", "ss_embbag_backward_prepare",
-              "ss_embbag_backward_apply", "ss_embbag_forward_grouped"):
+              "ss_embbag_backward_apply", "ss_embbag_forward_grouped",
+              "ss_sample_drop", "ss_drop_stats"):
         getattr(lib, n).restype = C.c_int32
     return lib
 
@@ -298,3 +299,39 @@ def ss_detect_stale(tables: Tables, hot: HotState, threshold: float,
         C.c_void_p(None if hot._shptr is None else hot._shptr.data_ptr()),
         C.c_void_p(None if hot._dptr is None else hot._dptr.data_ptr()),
         _dev_ptr(hot.stale_count, torch.int32, "stale_count"), _stream(stream)))
+
+
+MAX_THRESHOLDS = 32
+
+
+def ss_sample_drop(hot: HotState, sidx: torch.Tensor, alpha: int,
+                   thresholds: Sequence[float], counts: torch.Tensor,
+                   stream=None) -> None:
+    """sidx int32 [T, S, L]; counts int32 [len(thresholds)] (32-bit words of the
+    unsigned counts); reads hot.drift as left by ss_detect_stale."""
+    if hot.drift is None:
+        raise SlipstreamError("ss_sample_drop: HotState was built without diagnostics")
+    if sidx.dim() != 3 or sidx.shape[0] != len(hot.hot_ids):
+        raise SlipstreamError("ss_sample_drop: sidx must be [T, S, L]")
+    thr = (C.c_float * len(thresholds))(*[float(x) for x in thresholds])
+    if counts.numel() < len(thresholds):
+        raise SlipstreamError("ss_sample_drop: counts is shorter than thresholds")
+    _check(_lib.ss_sample_drop(
+        C.c_int32(len(hot.hot_ids)), C.c_void_p(hot._hptr.data_ptr()),
+        C.c_int32(hot.H), C.c_void_p(hot._dptr.data_ptr()),
+        _dev_ptr(sidx, torch.int32, "sidx"), C.c_int32(sidx.shape[1]),
+        C.c_int32(sidx.shape[2]), C.c_int32(alpha), thr,
+        C.c_int32(len(thresholds)), _dev_ptr(counts, torch.int32, "counts"),
+        _stream(stream)))
+
+
+_STAT_KEYS = ("D", "sd", "half", "lo", "hi", "D_bar", "D_bar_lo", "D_bar_hi")
+
+
+def ss_drop_stats(count: int, n_samples: int, population: int, n_hot_inputs: int,
+                  t_crit: float) -> dict:
+    out = (C.c_double * 8)()
+    _check(_lib.ss_drop_stats(C.c_uint32(count), C.c_int64(n_samples),
+                              C.c_int64(population), C.c_int64(n_hot_inputs),
+                              C.c_double(t_crit), out))
+    return dict(zip(_STAT_KEYS, list(out)))

@@ -1,4 +1,5 @@
 // C ABI of libslipstream: argument validation on the host, then launches.
+#include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
@@ -319,6 +320,68 @@ int32_t ss_detect_stale(const ss_tables *tables, int32_t *const *hot_ids,
     return launch_detect(tables, hot_ids, H, snapshot, threshold,
                          refresh_snapshot != 0, stale_hot, drift, stale_count,
                          static_cast<hipStream_t>(stream));
+}
+
+int32_t ss_sample_drop(int32_t num_tables, int32_t *const *hot_ids, int32_t H,
+                       double *const *drift, const int32_t *sidx, int32_t S,
+                       int32_t L, int32_t alpha, const float *thresholds,
+                       int32_t n_thr, uint32_t *counts, void *stream)
+{
+    const char *who = "ss_sample_drop";
+    if (num_tables < 1 || num_tables > 65535)
+        return fail(SS_ERR_INVALID_ARG, "%s: num_tables = %d (need 1..65535)", who,
+                    num_tables);
+    if (!hot_ids || !drift)
+        return fail(SS_ERR_INVALID_ARG, "%s: hot_ids or drift is NULL", who);
+    if (H < 0) return fail(SS_ERR_INVALID_ARG, "%s: H = %d", who, H);
+    if (S < 0) return fail(SS_ERR_INVALID_ARG, "%s: S = %d", who, S);
+    if (L < 1) return fail(SS_ERR_INVALID_ARG, "%s: L = %d", who, L);
+    if (S > 0 && !sidx) return fail(SS_ERR_INVALID_ARG, "%s: sidx is NULL", who);
+    if ((int64_t)S * L >= (1LL << 31) || (int64_t)num_tables * L >= (1LL << 31))
+        return fail(SS_ERR_UNSUPPORTED, "%s: S*L or T*L does not fit in int32", who);
+    if (alpha < 0) return fail(SS_ERR_INVALID_ARG, "%s: alpha = %d", who, alpha);
+    if (n_thr < 1 || n_thr > SS_MAX_THRESHOLDS)
+        return fail(SS_ERR_INVALID_ARG, "%s: n_thr = %d (need 1..%d)", who, n_thr,
+                    SS_MAX_THRESHOLDS);
+    if (!thresholds || !counts)
+        return fail(SS_ERR_INVALID_ARG, "%s: thresholds or counts is NULL", who);
+    for (int k = 0; k < n_thr; ++k)
+        if (thresholds[k] != thresholds[k])
+            return fail(SS_ERR_INVALID_ARG, "%s: thresholds[%d] is NaN", who, k);
+    return launch_sample_drop(num_tables, hot_ids, H, drift, sidx, S, L, alpha,
+                              thresholds, n_thr, counts,
+                              static_cast<hipStream_t>(stream));
+}
+
+int32_t ss_drop_stats(uint32_t count, int64_t n_samples, int64_t population,
+                      int64_t n_hot_inputs, double t_crit, double *out)
+{
+    const char *who = "ss_drop_stats";
+    if (!out) return fail(SS_ERR_INVALID_ARG, "%s: out is NULL", who);
+    if (n_samples < 1 || population < n_samples)
+        return fail(SS_ERR_INVALID_ARG, "%s: n_samples = %lld, population = %lld", who,
+                    (long long)n_samples, (long long)population);
+    if ((int64_t)count > n_samples)
+        return fail(SS_ERR_INVALID_ARG, "%s: count = %u exceeds n_samples = %lld", who,
+                    count, (long long)n_samples);
+    if (n_hot_inputs < 0 || !(t_crit >= 0.0))
+        return fail(SS_ERR_INVALID_ARG, "%s: n_hot_inputs = %lld, t_crit = %g", who,
+                    (long long)n_hot_inputs, t_crit);
+    // The indicator is 0 or 1, so its mean square deviation from D is D (1 - D).
+    const double share = (double)count / (double)n_samples;
+    const double var = share * (1.0 - share);
+    const double unsampled = (double)(population - n_samples) / (double)population;
+    const double half = t_crit * sqrt(unsampled * var / (double)n_samples);
+    const double scale = (double)n_hot_inputs;
+    out[0] = share;
+    out[1] = sqrt(var);
+    out[2] = half;
+    out[3] = share - half;
+    out[4] = share + half;
+    out[5] = share * scale;
+    out[6] = (share - half) * scale;
+    out[7] = (share + half) * scale;
+    return SS_OK;
 }
 
 }  // extern "C"

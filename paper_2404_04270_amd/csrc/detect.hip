@@ -20,6 +20,11 @@ __global__ void zero_u32_kernel(uint32_t *p, int n)
     if (i < n) p[i] = 0;
 }
 
+void launch_zero_u32(uint32_t *p, int n, hipStream_t s)
+{
+    if (n > 0) launch(zero_u32_kernel, dim3((n + 255) / 256), dim3(256), s, p, n);
+}
+
 template <int G>
 __global__ __launch_bounds__(kWG) void detect_kernel(
     const float *const *__restrict__ weights, uint32_t *const *__restrict__ bits,
@@ -100,8 +105,7 @@ int32_t launch_detect(const ss_tables *tb, int32_t *const *hot_ids, int H,
     const int g = lanes_per_row(tb->dim);
     const int slots = kWG / g;
     const int tiles = (H + slots - 1) / slots;
-    if (stale_count)
-        launch(zero_u32_kernel, dim3((T + 255) / 256), dim3(256), s, stale_count, T);
+    if (stale_count) launch_zero_u32(stale_count, T, s);
     ProfScope prof("detect_kernel", s);
     SS_DISPATCH_G(g, launch(
                          detect_kernel<G>, dim3((unsigned)(tiles * T)), dim3(kWG), s, tb->weights, tb->stale_bits, hot_ids, H, snapshot,

@@ -117,5 +117,11 @@ int32_t launch_forward_group(const ss_tables *tb, const int32_t *idx, int Bcap,
                              const int32_t *n_valid, float *out, uint32_t *keys,
                              uint32_t *vals, int NP, hipStream_t s);
 size_t filter_ws_bytes(int T, int B, int L);
+int32_t launch_sample_drop(int T, int32_t *const *hot_ids, int H, double *const *drift,
+                           const int32_t *sidx, int S, int L, int alpha,
+                           const float *thresholds, int n_thr, uint32_t *counts,
+                           hipStream_t s);
+// p[0..n) = 0 by a small kernel (a memset node would not survive graph capture)
+void launch_zero_u32(uint32_t *p, int n, hipStream_t s);
 
 }  // namespace ss

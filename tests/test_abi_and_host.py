@@ -105,3 +105,75 @@ def test_permutation_config_and_hot_set_rule():
     hot = wl.hot_set(stream, 10, 3)
     assert hot.tolist() == [[2, 5, 7]]       # counts 2,2,1,1: tie 7 vs 9 -> lower id
     assert wl.bitmap_words(33) == 2
+
+
+# ---------------------------------------------------- sampling block, host side
+def drop_stats(lib, count, n, pop, hot, t):
+    lib.ss_drop_stats.restype = C.c_int32
+    out = (C.c_double * 8)()
+    rc = lib.ss_drop_stats(C.c_uint32(count), C.c_int64(n), C.c_int64(pop),
+                           C.c_int64(hot), C.c_double(t), out)
+    return rc, list(out)
+
+
+def test_drop_stats_matches_the_oracle_and_rejects_bad_arguments(lib):
+    """ss_drop_stats is host arithmetic (Eq. 2-4): no GPU is involved."""
+    import oracle
+    keys = ("D", "sd", "half", "lo", "hi", "D_bar", "D_bar_lo", "D_bar_hi")
+    for count, n, pop, hot, t in [(0, 100, 100000, 100000, 3.340), (100, 100, 1000, 900, 3.340),
+                                  (37, 4096, 4_194_304, 3_000_000, 3.340),
+                                  (512, 1024, 1024, 1024, 2.0), (1, 3, 7, 5, 0.0)]:
+        rc, got = drop_stats(lib, count, n, pop, hot, t)
+        assert rc == 0
+        ref = oracle.drop_stats(count, n, pop, hot, t)
+        np.testing.assert_allclose(got, [ref[k] for k in keys], rtol=1e-12, atol=1e-15)
+    lib.ss_last_error.restype = C.c_char_p
+    for bad in [(5, 4, 10, 10, 1.0), (0, 0, 10, 10, 1.0), (0, 11, 10, 10, 1.0),
+                (0, 5, 10, -1, 1.0), (0, 5, 10, 10, -1.0), (0, 5, 10, 10, float("nan"))]:
+        rc, _ = drop_stats(lib, *bad)
+        assert rc == 1 and b"ss_drop_stats" in lib.ss_last_error()
+
+
+def test_sample_drop_validates_on_the_host(lib):
+    lib.ss_sample_drop.restype = C.c_int32
+    lib.ss_last_error.restype = C.c_char_p
+    thr = (C.c_float * 2)(1.0, float("nan"))
+    fake = C.c_void_p(256)           # never dereferenced: every call below is rejected
+    def call(T=2, H=4, S=8, L=1, alpha=1, n_thr=1, thresholds=thr, counts=fake):
+        return lib.ss_sample_drop(C.c_int32(T), fake, C.c_int32(H), fake, fake,
+                                  C.c_int32(S), C.c_int32(L), C.c_int32(alpha),
+                                  thresholds, C.c_int32(n_thr), counts, None)
+    for kwargs, text in [(dict(T=0), b"num_tables"), (dict(H=-1), b"H ="),
+                         (dict(S=-1), b"S ="), (dict(L=0), b"L ="),
+                         (dict(alpha=-1), b"alpha"), (dict(n_thr=0), b"n_thr"),
+                         (dict(n_thr=33), b"n_thr"), (dict(n_thr=2), b"NaN"),
+                         (dict(thresholds=None), b"NULL"), (dict(counts=None), b"NULL"),
+                         (dict(S=1 << 30, L=4), b"int32")]:
+        assert call(**kwargs) != 0, kwargs
+        assert text in lib.ss_last_error(), (kwargs, lib.ss_last_error())
+
+
+def test_ladder_search_finds_the_largest_threshold_within_budget():
+    from paper_2404_04270_amd.sampling import geometric_ladder, ladder_search
+    lad = geometric_ladder(1e-4, 1e-1, 32)
+    assert len(lad) == 32 and all(a < b for a, b in zip(lad, lad[1:]))
+    assert 1e-4 < lad[0] and lad[-1] < 1e-1
+    np.testing.assert_allclose(np.diff(np.log(lad)), np.log(1e3) / 33, rtol=1e-9)
+
+    rng = np.random.default_rng(5)
+    drifts = np.sort(rng.lognormal(np.log(3e-3), 1.0, 5000))
+    calls = []
+    def bound(ts):               # share of "rows" at or below T: monotone in T
+        calls.append(len(ts))
+        return [float(np.searchsorted(drifts, t, side="right")) / drifts.size for t in ts]
+    for budget in (0.05, 0.3, 0.77):
+        calls.clear()
+        T, tried = ladder_search(bound, 1e-5, 1.0, budget, passes=2)
+        assert bound([T])[0] <= budget
+        assert calls[:3] == [2, 32, 32]
+        # resolution after two passes: (hi/lo)^(1/33^2); the next point fails
+        ratio = (1.0 / 1e-5) ** (1.0 / 33 ** 2)
+        assert bound([T * ratio * 1.0001])[0] > budget
+        assert all(b <= budget for t, b in tried if t <= T)
+    assert ladder_search(bound, 1e-5, 1.0, -0.1)[0] is None        # even lo is over
+    assert ladder_search(bound, 1e-5, 1.0, 1.0)[0] == 1.0          # hi itself fits
