@@ -392,18 +392,28 @@ __global__ __launch_bounds__(kWG) void fixup_kernel(
     __shared__ f4 s_part[kWG];
     const int t = blockIdx.x / wgs_per_table;
     const int wg = blockIdx.x - t * wgs_per_table;
-    const uint32_t row = meta_trail_row[t * wgs_per_table + wg];
-    if (row == kNoRow) return;
-
     const int tid = threadIdx.x, g = tid / G, c = tid % G;
     const uint8_t *__restrict__ ls = meta_lead_state + (int64_t)t * wgs_per_table;
+    // Both loads are issued before either is looked at, and the row itself is
+    // fetched before the pieces are: this kernel is a chain of dependent round
+    // trips to memory and little else, so every link taken out counts.
+    const uint32_t row = meta_trail_row[t * wgs_per_table + wg];
+    const int q0 = wg + 1 + tid;
+    const uint8_t ls0 = q0 < wgs_per_table ? ls[q0] : (uint8_t)2;
+    if (row == kNoRow) return;
+
+    const auto W = as_global(reinterpret_cast<f4 *>(weights[t]));
+    f4 w0 = f4{0.f, 0.f, 0.f, 0.f};
+    if (g == 0 && c < D4) w0 = W[(int64_t)row * D4 + c];
+
     // the run ends in the first later workgroup whose leading run stops there
     if (tid == 0) s_end = 0x7fffffff;
     __syncthreads();
     int end = 0x7fffffff;
     for (int b0 = wg + 1; b0 < wgs_per_table; b0 += kWG) {
         const int q = b0 + tid;
-        if (q < wgs_per_table && ls[q] != 2) atomicMin(&s_end, q);
+        const uint8_t st = b0 == wg + 1 ? ls0 : (q < wgs_per_table ? ls[q] : (uint8_t)2);
+        if (q < wgs_per_table && st != 2) atomicMin(&s_end, q);
         __syncthreads();
         end = s_end;
         __syncthreads();
@@ -413,17 +423,30 @@ __global__ __launch_bounds__(kWG) void fixup_kernel(
 
     // pieces: trail(wg), lead(wg+1), ..., lead(end); group g sums every NG-th
     const int npieces = end - wg + 1;
-    const auto W = as_global(reinterpret_cast<f4 *>(weights[t]));
     const f4 *__restrict__ PL = part_lead + (int64_t)t * wgs_per_table * D4;
     const f4 *__restrict__ PT = part_trail + (int64_t)t * wgs_per_table * D4;
     for (int cb = 0; cb < D4; cb += G) {
         const int col = cb + c;
         const bool active = col < D4;
         f4 sum = f4{0.f, 0.f, 0.f, 0.f};
-        if (active)
-            for (int k = g; k < npieces; k += NG)
-                sum = sum + (k == 0 ? PT[(int64_t)wg * D4 + col]
-                                    : PL[(int64_t)(wg + k) * D4 + col]);
+        if (active) {
+            // a long run has hundreds of pieces: fetch eight at a time, then add
+            // them in piece order (the order of the sum is part of the result)
+            constexpr int UN = 8;
+            for (int k0 = g; k0 < npieces; k0 += NG * UN) {
+                f4 v[UN];
+#pragma unroll
+                for (int u = 0; u < UN; ++u) {
+                    const int k = k0 + u * NG;
+                    const int kk = k < npieces ? k : k0;      // in range, value unused
+                    v[u] = kk == 0 ? PT[(int64_t)wg * D4 + col]
+                                   : PL[(int64_t)(wg + kk) * D4 + col];
+                }
+#pragma unroll
+                for (int u = 0; u < UN; ++u)
+                    if (k0 + u * NG < npieces) sum = sum + v[u];
+            }
+        }
         s_part[tid] = sum;
         __syncthreads();
         if (g == 0 && active) {
@@ -431,7 +454,7 @@ __global__ __launch_bounds__(kWG) void fixup_kernel(
             const int used = npieces < NG ? npieces : NG;
             for (int q = 1; q < used; ++q) tot = tot + s_part[q * G + c];
             const int64_t o = (int64_t)row * D4 + col;
-            W[o] = sgd(W[o], tot, lr);
+            W[o] = sgd(cb == 0 ? w0 : W[o], tot, lr);
         }
         __syncthreads();
     }

@@ -20,8 +20,11 @@
 
 namespace ss {
 
+// Thresholds as the kernel compares them: widened to fp64 on the host, and -1
+// where no row may be stale (threshold 0 or an unused slot), since a drift is
+// never below 0.  They arrive as kernel arguments and stay in scalar registers.
 struct Ladder {
-    float thr[SS_MAX_THRESHOLDS];
+    double thr[SS_MAX_THRESHOLDS];
 };
 
 constexpr int kBatch = 4;     // searches a lane keeps in flight
@@ -77,9 +80,8 @@ __global__ __launch_bounds__(kWG) void sample_drop_kernel(
                 const double d = dr[i][base[i]];
 #pragma unroll
                 for (int k = 0; k < SS_MAX_THRESHOLDS; ++k) {
-                    const float th = ladder.thr[k];
                     // same verdict as ss_detect_stale; a NaN drift compares false
-                    const bool stale = hot && k < n_thr && th > 0.0f && d <= (double)th;
+                    const bool stale = hot && d <= ladder.thr[k];
                     cnt[k] += stale ? 1u : 0u;
                 }
             }
@@ -110,7 +112,7 @@ int32_t launch_sample_drop(int T, int32_t *const *hot_ids, int H, double *const 
     if (S > 0) {
         Ladder ladder;
         for (int k = 0; k < SS_MAX_THRESHOLDS; ++k)
-            ladder.thr[k] = k < n_thr ? thresholds[k] : 0.0f;
+            ladder.thr[k] = k < n_thr && thresholds[k] > 0.0f ? (double)thresholds[k] : -1.0;
         const int TL = T * L;
         int g = 1;
         while (g < 64 && g * kBatch < TL) g <<= 1;

@@ -71,11 +71,19 @@ def random_bits(rng, T, R, frac):
     (1, 200, 4, 70, 3, 0),           # nothing valid
     (2, 500, 48, 130, 9, 77),        # dim not a power of two, unroll tail
     (1, 300, 260, 40, 11, None),     # dim above 256: several float4 per lane
+    (2, 400, 16, 300, 1, 0),         # one-hot, nothing valid
+    (1, 300, 260, 40, 1, 33),        # one-hot, dim above 256
+    (3, 700, 48, 1000, 1, 333),      # one-hot, dim not a power of two
+    (8, 3000, 16, 70000, 1, 65000),  # one-hot pipeline: 2-3 batches per workgroup
+    (26, 5000, 64, 8269, 1, None),   # 3-4 batches per workgroup, ragged last tile
+    (26, 5000, 64, 14000, 1, 13999), # 5-6 batches per workgroup
 ])
 def test_forward_matches_oracle(B, dev, T, R, D, Bc, L, nv):
     rng = np.random.default_rng(100 + D + L)
     W = rand_tables(rng, T, R, D)
     idx = zipf_idx(rng, T, Bc, L, R)
+    if nv is not None:
+        idx[:, nv:] = -1             # bags past n_valid hold no usable index
     ref = oracle.embbag_forward(W, idx, nv)
     tb = B.Tables(to_dev(W, dev))
     out = torch.full((T, Bc, D), 7.0, dtype=torch.float32, device=dev)
