@@ -40,7 +40,9 @@ def _load():
         _lib = C.CDLL(build())
         for name in ("oracle_embbag_forward", "oracle_embbag_backward_update",
                      "oracle_detect_stale", "oracle_filter_batch",
-                     "oracle_sample_drop", "oracle_drop_stats"):
+                     "oracle_sample_drop", "oracle_drop_stats",
+                     "oracle_count_accesses", "oracle_select_hot_ratio",
+                     "oracle_select_hot_top"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -214,3 +216,51 @@ def drop_stats(count: int, n_samples: int, population: int, n_hot_inputs: int,
         raise ValueError("drop_stats: inconsistent arguments")
     keys = ("D", "sd", "half", "lo", "hi", "D_bar", "D_bar_lo", "D_bar_hi")
     return dict(zip(keys, list(out)))
+
+
+def count_accesses(rows: int, idx: np.ndarray, counts: Sequence[np.ndarray],
+                   n_valid: Optional[int] = None) -> None:
+    """counts: T uint32 arrays [rows], advanced in place."""
+    _check(idx, np.int32, "idx")
+    T, B, L = idx.shape
+    for c in counts:
+        _check(c, np.uint32, "counts")
+        assert c.shape == (rows,)
+    rc = _load().oracle_count_accesses(
+        C.c_int(T), C.c_int64(rows), C.c_void_p(idx.ctypes.data), C.c_int(B),
+        C.c_int(L), C.c_int(B if n_valid is None else n_valid), _ptr_array(counts, T))
+    _check_rc(rc, "count_accesses")
+
+
+def _hot_outputs(T: int, rows: int, cap: int):
+    ids = [np.full(cap, -1, dtype=np.int32) for _ in range(T)]
+    bits = [np.zeros((rows + 31) // 32, dtype=np.uint32) for _ in range(T)]
+    return ids, bits
+
+
+def select_hot_ratio(counts: Sequence[np.ndarray], lam: float, total: int, cap: int):
+    """Returns (hot_ids: T int32 arrays [cap], -1 past n_hot; bitmaps; n_hot uint32 [T])."""
+    T, rows = len(counts), counts[0].shape[0]
+    ids, bits = _hot_outputs(T, rows, cap)
+    n_hot = np.zeros(T, dtype=np.uint32)
+    rc = _load().oracle_select_hot_ratio(
+        C.c_int(T), C.c_int64(rows), _ptr_array(counts, T), C.c_double(lam),
+        C.c_int64(total), C.c_int(cap), _ptr_array(ids, T), _ptr_array(bits, T),
+        C.c_void_p(n_hot.ctypes.data))
+    if rc == -3:
+        raise ValueError("select_hot_ratio: need total >= 1")
+    _check_rc(rc, "select_hot_ratio")
+    return ids, bits, n_hot
+
+
+def select_hot_top(counts: Sequence[np.ndarray], H: int):
+    """Returns (hot_ids: T int32 arrays [H] ascending; bitmaps)."""
+    T, rows = len(counts), counts[0].shape[0]
+    ids, bits = _hot_outputs(T, rows, H)
+    rc = _load().oracle_select_hot_top(
+        C.c_int(T), C.c_int64(rows), _ptr_array(counts, T), C.c_int(H),
+        _ptr_array(ids, T), _ptr_array(bits, T))
+    if rc == -3:
+        raise ValueError("select_hot_top: need 0 <= H <= rows")
+    _check_rc(rc, "select_hot_top")
+    return ids, bits

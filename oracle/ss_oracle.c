@@ -28,6 +28,11 @@
  *                      sample, the paper's critical value 3.340
  *   the search for T over the sampled drop estimates has no stated stopping
  *   rule in the paper: parity unpinned for it (it is host control flow).
+ *   count_accesses   - library histogram (bincount), additivity over calls
+ *   select_hot_ratio - brute force with exact rationals, the paper's reading of
+ *                      lambda = 1e-6 as "one access in a million"
+ *   select_hot_top   - brute force (repeated arg-max), library lexicographic
+ *                      sort, ties to the lower row id, the harness's own hot set
  */
 #include <math.h>
 #include <stdint.h>
@@ -325,5 +330,124 @@ int oracle_drop_stats(uint32_t count, int64_t n_samples, int64_t population,
     out[5] = Dk * (double)n_hot_inputs;
     out[6] = (Dk - half) * (double)n_hot_inputs;
     out[7] = (Dk + half) * (double)n_hot_inputs;
+    return 0;
+}
+
+/*
+ * Access counters of the preprocessing phase (section 3.1 and the first loop of
+ * Algorithm 1: one counter C_i per embedding entry, advanced for every sampled
+ * input that reads entry i):
+ *     counts[t][r] += #{ (j, l) : j < n_valid, idx[t][j][l] == r }
+ * Counters accumulate over calls; the caller zeroes them once.
+ */
+int oracle_count_accesses(int T, int64_t R, const int32_t *idx, int B, int L,
+                          int n_valid, uint32_t *const *counts)
+{
+    for (int t = 0; t < T; ++t) {
+        for (int j = 0; j < n_valid; ++j) {
+            for (int l = 0; l < L; ++l) {
+                int64_t r = idx[((int64_t)t * B + j) * L + l];
+                if (r < 0 || r >= R)
+                    return -1;
+                counts[t][r] += 1u;
+            }
+        }
+    }
+    return 0;
+}
+
+static void write_hot_set(int64_t R, const uint8_t *is_hot, int cap, int32_t *ids,
+                          uint32_t *bits, uint32_t *n_hot)
+{
+    uint32_t n = 0;
+    if (bits)
+        memset(bits, 0, (size_t)((R + 31) / 32) * sizeof(uint32_t));
+    for (int64_t r = 0; r < R; ++r) {
+        if (!is_hot[r])
+            continue;
+        if (bits)
+            bits[r >> 5] |= 1u << (r & 31);
+        if ((int64_t)n < cap)
+            ids[n] = (int32_t)r;
+        ++n;
+    }
+    *n_hot = n;
+}
+
+/*
+ * Hotness rule of section 3.1 / Algorithm 1: entry r of table t is hot when its
+ * share of the accesses reaches lambda,
+ *     C_r / total >= lambda
+ * with the quotient taken in fp64 (correctly rounded, so that a share written
+ * as a decimal, say 30 of 10000 against lambda = 0.003, compares as equal).
+ * total >= 1 is the number of accesses each table received (inputs * L).
+ * Outputs per table: the hot row ids in ascending order (the first `cap` of
+ * them), the hot bitmap (bits[t] may be NULL; overwritten, not OR-ed), and the
+ * number of hot rows n_hot[t] (which may exceed cap).
+ */
+int oracle_select_hot_ratio(int T, int64_t R, uint32_t *const *counts, double lambda,
+                            int64_t total, int cap, int32_t *const *hot_ids,
+                            uint32_t *const *hot_bits, uint32_t *n_hot)
+{
+    if (total < 1)
+        return -3;
+    uint8_t *is_hot = (uint8_t *)malloc((size_t)R);
+    if (!is_hot)
+        return -2;
+    for (int t = 0; t < T; ++t) {
+        for (int64_t r = 0; r < R; ++r)
+            is_hot[r] = (double)counts[t][r] / (double)total >= lambda;
+        write_hot_set(R, is_hot, cap, hot_ids[t], hot_bits ? hot_bits[t] : NULL,
+                      &n_hot[t]);
+    }
+    free(is_hot);
+    return 0;
+}
+
+/* order: larger count first, lower row id first among equal counts */
+typedef struct {
+    uint32_t count;
+    int32_t row;
+} counted_row;
+
+static int by_count_then_row(const void *a, const void *b)
+{
+    const counted_row *x = (const counted_row *)a, *y = (const counted_row *)b;
+    if (x->count != y->count)
+        return x->count > y->count ? -1 : 1;
+    return x->row < y->row ? -1 : (x->row > y->row ? 1 : 0);
+}
+
+/*
+ * "Hot set = the H most accessed rows of each table" (the workloads state the
+ * hot set as a share of the rows): rank the rows by count, larger first, equal
+ * counts by lower row id, keep the first H, and report them in ascending row
+ * order.  H <= R.
+ */
+int oracle_select_hot_top(int T, int64_t R, uint32_t *const *counts, int H,
+                          int32_t *const *hot_ids, uint32_t *const *hot_bits)
+{
+    if (H < 0 || H > R)
+        return -3;
+    counted_row *rank = (counted_row *)malloc((size_t)R * sizeof(counted_row));
+    uint8_t *is_hot = (uint8_t *)malloc((size_t)R);
+    if (!rank || !is_hot) {
+        free(rank); free(is_hot);
+        return -2;
+    }
+    for (int t = 0; t < T; ++t) {
+        for (int64_t r = 0; r < R; ++r) {
+            rank[r].count = counts[t][r];
+            rank[r].row = (int32_t)r;
+        }
+        qsort(rank, (size_t)R, sizeof(counted_row), by_count_then_row);
+        memset(is_hot, 0, (size_t)R);
+        for (int k = 0; k < H; ++k)
+            is_hot[rank[k].row] = 1;
+        uint32_t n;
+        write_hot_set(R, is_hot, H, hot_ids[t], hot_bits ? hot_bits[t] : NULL, &n);
+    }
+    free(rank);
+    free(is_hot);
     return 0;
 }

@@ -486,3 +486,103 @@ def test_drop_stats_closed_forms_and_paper_constant():
     assert abs(a / b - 2.0) < 1e-6
     with pytest.raises(ValueError):
         oracle.drop_stats(5, 4, 100, 100, 1.0)
+
+
+# ------------------------------------------------- hot-set identification
+def unpack_bits(bits, R):
+    return np.unpackbits(bits.view(np.uint8), bitorder="little")[:R].astype(bool)
+
+
+def test_count_accesses_is_a_histogram_and_accumulates():
+    rng = np.random.default_rng(50)
+    T, R, B, L = 3, 97, 400, 4
+    idx = ((rng.zipf(1.3, (T, B, L)) - 1) % R).astype(np.int32)
+    counts = [np.zeros(R, np.uint32) for _ in range(T)]
+    oracle.count_accesses(R, idx, counts)
+    for t in range(T):
+        assert np.array_equal(counts[t], np.bincount(idx[t].ravel(), minlength=R))
+        assert counts[t].sum() == B * L
+    # a second batch adds on top; only the first n_valid inputs of it count
+    idx2 = rng.integers(0, R, (T, B, L)).astype(np.int32)
+    idx2[:, 123:] = -1                       # must not be read
+    oracle.count_accesses(R, idx2, counts, n_valid=123)
+    for t in range(T):
+        both = np.concatenate([idx[t].ravel(), idx2[t, :123].ravel()])
+        assert np.array_equal(counts[t], np.bincount(both, minlength=R))
+    with pytest.raises(IndexError):
+        oracle.count_accesses(R, np.full((T, 1, 1), R, np.int32), counts)
+
+
+def test_select_hot_ratio_brute_force_and_the_papers_lambda():
+    from fractions import Fraction
+    lam, acc, out_of = [float(x) for x in
+                        [l for l in open(os.path.join(GOLDEN, "lambda_hot.txt"))
+                         if l.strip() and not l.startswith("#")][0].split()]
+    # one access in a million is hot at lambda = 1e-6; half that share is not
+    counts = [np.array([0, 1, 2, 1000], np.uint32)]
+    ids, bits, n = oracle.select_hot_ratio(counts, lam, int(out_of), cap=4)
+    assert n[0] == 3 and ids[0].tolist() == [1, 2, 3, -1]
+    assert unpack_bits(bits[0], 4).tolist() == [False, True, True, True]
+    ids, bits, n = oracle.select_hot_ratio(counts, lam, 2 * int(out_of), cap=4)
+    assert ids[0].tolist() == [2, 3, -1, -1] and n[0] == 2
+
+    rng = np.random.default_rng(51)
+    T, R = 3, 301
+    counts = [rng.zipf(1.2, R).astype(np.uint32) % 5000 for _ in range(T)]
+    total = 10000
+    counts[0][:4] = [30, 29, 31, 317]            # shares that equal a lambda below
+    for lam in ("0", "0.0009765625", "0.003", "0.0317", "0.2", "1"):
+        ids, bits, n = oracle.select_hot_ratio(counts, float(lam), total, cap=R)
+        for t in range(T):
+            # exact rational comparison with lambda as the decimal it was written as
+            want = [r for r in range(R)
+                    if Fraction(int(counts[t][r]), total) >= Fraction(lam)]
+            assert n[t] == len(want)
+            assert ids[t][:n[t]].tolist() == want and np.all(ids[t][n[t]:] == -1)
+            assert np.flatnonzero(unpack_bits(bits[t], R)).tolist() == want
+            assert not np.any(np.unpackbits(bits[t].view(np.uint8), bitorder="little")[R:])
+    # a list shorter than the hot set keeps the lowest ids and still reports the size
+    ids, bits, n = oracle.select_hot_ratio(counts, 0.0, total, cap=10)
+    assert n[0] == R and ids[0].tolist() == list(range(10))
+    # the bitmap is rewritten, not accumulated
+    assert oracle.select_hot_ratio(counts, 1.0, total, cap=R)[1][0].sum() == 0
+    with pytest.raises(ValueError):
+        oracle.select_hot_ratio(counts, 0.5, 0, cap=R)
+
+
+def test_select_hot_top_brute_force_ties_and_the_harness_rule():
+    rng = np.random.default_rng(52)
+    T, R = 2, 40
+    counts = [rng.integers(0, 6, R).astype(np.uint32) for _ in range(T)]    # many ties
+    for H in (0, 1, 7, 39, 40):
+        ids, bits = oracle.select_hot_top(counts, H)
+        for t in range(T):
+            left = {r: int(counts[t][r]) for r in range(R)}
+            want = []
+            for _ in range(H):                   # repeated arg-max, lowest id on ties
+                best = max(left.values())
+                r = min(k for k, v in left.items() if v == best)
+                want.append(r)
+                del left[r]
+            assert ids[t].tolist() == sorted(want)
+            assert np.flatnonzero(unpack_bits(bits[t], R)).tolist() == sorted(want)
+    # all counts equal: the H lowest row ids
+    flat = [np.full(R, 3, np.uint32)]
+    assert oracle.select_hot_top(flat, 5)[0][0].tolist() == [0, 1, 2, 3, 4]
+    # library lexicographic sort on a larger case
+    R = 5000
+    counts = [(rng.zipf(1.2, R) % 50).astype(np.uint32)]
+    ids, _ = oracle.select_hot_top(counts, 500)
+    order = np.lexsort((np.arange(R), -counts[0].astype(np.int64)))[:500]
+    assert np.array_equal(ids[0], np.sort(order))
+    assert counts[0][ids[0]].min() >= np.delete(counts[0], ids[0]).max()
+    with pytest.raises(ValueError):
+        oracle.select_hot_top(counts, R + 1)
+    # counting then selecting reproduces the hot set the harness derives on its own
+    cfg = wl.CONFIGS[1]
+    stream = wl.Workload(cfg).indices(0, 20)
+    cnt = [np.zeros(cfg.rows, np.uint32) for _ in range(cfg.num_tables)]
+    for it in range(stream.shape[0]):
+        oracle.count_accesses(cfg.rows, stream[it], cnt)
+    ids, _ = oracle.select_hot_top(cnt, cfg.hot_rows)
+    assert np.array_equal(np.stack(ids), wl.hot_set(stream, cfg.rows, cfg.hot_rows))
