@@ -48,6 +48,10 @@ def parse():
                     help="after the timed steps, also time the sampling block (drift of "
                          "the hot rows once, then drop counts of S sampled inputs for 32 "
                          "candidate thresholds in one pass) and report it beside the step")
+    ap.add_argument("--hotset-probe", action="store_true",
+                    help="after the timed steps, also time the hot-set identification "
+                         "(access counters over the ring of batches, then the top-H rows "
+                         "of every table) and report it beside the step")
     return ap.parse_args()
 
 
@@ -166,9 +170,46 @@ def main():
 
     if args.sampling_probe > 0:
         out["sampling_block"] = sampling_probe(B, step, idx_d, args.sampling_probe, thr)
+    if args.hotset_probe:
+        out["hot_set"] = hotset_probe(B, step, idx_d, cfg.hot_rows, hot)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, w, idx_ring, hot, thr, args.cpu_seconds)
     print(json.dumps(out))
+
+
+def hotset_probe(B, step, idx_d, H, hot_ref):
+    """Durations of counting and selecting on the device, checked against the
+    hot set the harness derived on the host from the same ring of batches."""
+    import torch
+    T, R, dev = step.tables.num_tables, step.tables.rows, step.tables.device
+    ring = idx_d.shape[0]
+    ac = B.AccessCounters(T, R, dev)
+    ws = torch.empty(max(256, B.ss_select_hot_workspace_bytes(T, R)), dtype=torch.uint8,
+                     device=dev)
+    ids = [torch.zeros(H, dtype=torch.int32, device=dev) for _ in range(T)]
+    for k in range(ring):                                    # warm-up and the real counts
+        B.ss_count_accesses(ac, idx_d[k])
+    B.ss_select_hot_top(ac, H, ids, None, ws)
+    torch.cuda.synchronize()
+    same = all(torch.equal(ids[t].cpu(), torch.from_numpy(hot_ref[t])) for t in range(T))
+    scratch = B.AccessCounters(T, R, dev)
+    B.ss_profile_enable(True)
+    for k in range(ring):
+        B.ss_count_accesses(scratch, idx_d[k])
+    torch.cuda.synchronize()
+    B.ss_profile_enable(False)
+    prof = B.ss_profile_report()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 5
+    e0.record()
+    for _ in range(reps):
+        B.ss_select_hot_top(ac, H, ids, None, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    return {"hot_rows_per_table": H, "matches_host_rule": bool(same),
+            "count_pass_us_per_batch": 1e3 * prof["count_kernel"][1] / prof["count_kernel"][0],
+            "select_top_us": 1e3 * e0.elapsed_time(e1) / reps,
+            "counter_bytes": 4 * T * R}
 
 
 def sampling_probe(B, step, idx_d, S, thr):

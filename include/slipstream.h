@@ -7,8 +7,11 @@
  * keeps periodic snapshots of the frequently accessed ("hot") rows, marks a hot
  * row stale once the Euclidean distance between two consecutive snapshots of it
  * no longer exceeds a threshold T (Eq. 1, Eq. 5), stops updating stale rows and
- * drops the inputs that only reach stale rows (Eq. 6-8).  The four calls below
- * are the pieces of one training iteration that touch the tables.
+ * drops the inputs that only reach stale rows (Eq. 6-8).  ss_filter_batch,
+ * ss_embbag_forward, ss_embbag_backward_update and ss_detect_stale are the pieces
+ * of one training iteration that touch the tables; the calls after them set the
+ * method up: the sampling block that prices candidate thresholds (section 3.3)
+ * and the identification of the hot rows (section 3.1).
  *
  * Conventions common to all calls
  *   - Return value: SS_OK or an SS_ERR_* code; ss_last_error() gives the text
@@ -241,6 +244,57 @@ int32_t ss_sample_drop(int32_t num_tables, int32_t *const *hot_ids, int32_t H,
  */
 int32_t ss_drop_stats(uint32_t count, int64_t n_samples, int64_t population,
                       int64_t n_hot_inputs, double t_crit, double *out);
+
+/*
+ * Access counters of the preprocessing phase (section 3.1; first loop of
+ * Algorithm 1: one counter per embedding entry, advanced for every sampled
+ * input that reads the entry):
+ *     counts[t][r] += #{ (j, l) : j < n_valid, idx[t][j][l] == r }
+ * Counters accumulate over calls (32-bit, wrapping); the caller zeroes them once.
+ *   idx       device int32 [T][B][L]
+ *   n_valid   NULL (all B inputs count) or device int32: inputs j >= *n_valid are
+ *             not read
+ *   counts    device array of T device pointers, each uint32 [rows]
+ */
+int32_t ss_count_accesses(int32_t num_tables, int64_t rows, const int32_t *idx,
+                          int32_t B, int32_t L, const int32_t *n_valid,
+                          uint32_t *const *counts, void *stream);
+
+/* Bytes of 256-byte-aligned device scratch the two selections below need
+ * (0 for arguments they would reject). */
+size_t ss_select_hot_workspace_bytes(int32_t num_tables, int64_t rows);
+
+/*
+ * Hot rows by the paper's share rule (section 3.1, Algorithm 1): row r of
+ * table t is hot when
+ *     counts[t][r] / total >= lambda        (the quotient taken in fp64)
+ * where total >= 1 is the number of accesses each table received (inputs * L).
+ * lambda <= 0 makes every row hot.  Per table the call writes
+ *   hot_ids[t]   int32 [cap]: the hot row ids in ascending order; if there are
+ *                more than cap, the cap lowest; entries past n_hot[t] untouched
+ *                (hot_ids may be NULL when cap = 0)
+ *   hot_bits[t]  NULL array, or bitmaps of ceil(rows/32) words each, overwritten
+ *                (not OR-ed): bit r set iff row r is hot; usable as the second
+ *                bitmap of ss_filter_batch to split inputs into hot and cold
+ *   n_hot        NULL, or device uint32 [T]: number of hot rows (may exceed cap)
+ * All device memory; ws as sized by ss_select_hot_workspace_bytes.
+ */
+int32_t ss_select_hot_ratio(int32_t num_tables, int64_t rows, uint32_t *const *counts,
+                            double lambda, int64_t total, int32_t cap,
+                            int32_t *const *hot_ids, uint32_t *const *hot_bits,
+                            uint32_t *n_hot, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Hot rows as the H most accessed rows of each table (how the workloads of this
+ * build state their hot sets: a share of the rows).  Rows are ranked by count,
+ * larger first, equal counts by lower row id; the first H form the hot set,
+ * written to hot_ids[t] (int32 [H]) in ascending row order and, if hot_bits is
+ * not NULL, as bitmaps (overwritten).  0 <= H <= rows.  The result has the
+ * layout ss_detect_stale and ss_sample_drop expect of hot_ids.
+ */
+int32_t ss_select_hot_top(int32_t num_tables, int64_t rows, uint32_t *const *counts,
+                          int32_t H, int32_t *const *hot_ids, uint32_t *const *hot_bits,
+                          void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Measurement aid, off by default (not part of the method).  While enabled,

@@ -14,6 +14,8 @@ _BINDING_NAMES = (
     "ss_profile_enable", "ss_profile_report", "HotState",
     "ss_embbag_backward_prepare", "ss_embbag_backward_apply",
     "ss_embbag_forward_grouped", "ss_sample_drop", "ss_drop_stats",
+    "ss_count_accesses", "ss_select_hot_workspace_bytes", "ss_select_hot_ratio",
+    "ss_select_hot_top", "AccessCounters",
     "EmbeddingStep", "lib_path",
 )
 

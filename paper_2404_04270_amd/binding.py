@@ -21,6 +21,8 @@ SYMBOLS = (
     "ss_backward_workspace_bytes", "ss_detect_stale", "ss_profile_enable",
     "ss_profile_report", "ss_embbag_backward_prepare", "ss_embbag_backward_apply",
     "ss_embbag_forward_grouped", "ss_sample_drop", "ss_drop_stats",
+    "ss_count_accesses", "ss_select_hot_workspace_bytes", "ss_select_hot_ratio",
+    "ss_select_hot_top",
 )
 
 
@@ -44,12 +46,14 @@ def _load():
     lib.ss_last_error.restype = C.c_char_p
     lib.ss_filter_batch_workspace_bytes.restype = C.c_size_t
     lib.ss_backward_workspace_bytes.restype = C.c_size_t
+    lib.ss_select_hot_workspace_bytes.restype = C.c_size_t
     lib.ss_profile_enable.restype = None
     for n in ("ss_filter_batch", "ss_embbag_forward",
               "ss_embbag_backward_update", "ss_detect_stale",
               "ss_profile_report", "ss_embbag_backward_prepare",
               "ss_embbag_backward_apply", "ss_embbag_forward_grouped",
-              "ss_sample_drop", "ss_drop_stats"):
+              "ss_sample_drop", "ss_drop_stats", "ss_count_accesses",
+              "ss_select_hot_ratio", "ss_select_hot_top"):
         getattr(lib, n).restype = C.c_int32
     return lib
 
@@ -335,3 +339,83 @@ def ss_drop_stats(count: int, n_samples: int, population: int, n_hot_inputs: int
                               C.c_int64(population), C.c_int64(n_hot_inputs),
                               C.c_double(t_crit), out))
     return dict(zip(_STAT_KEYS, list(out)))
+
+
+class AccessCounters:
+    """uint32 counters [rows] per table (int32 storage) and their pointer array."""
+
+    def __init__(self, num_tables: int, rows: int, device):
+        self.rows, self.device = int(rows), device
+        self.counts = [torch.zeros(rows, dtype=torch.int32, device=device)
+                       for _ in range(num_tables)]
+        self._cptr = _ptr_table(self.counts, device)
+
+
+def _opt_ptr_table(tensors, dtype, name, device):
+    if tensors is None:
+        return None
+    for x in tensors:
+        _dev_ptr(x, dtype, name)
+    return _ptr_table(tensors, device)
+
+
+def ss_count_accesses(counters: AccessCounters, idx: torch.Tensor,
+                      n_valid: Optional[torch.Tensor] = None, stream=None) -> None:
+    if idx.dim() != 3 or idx.shape[0] != len(counters.counts):
+        raise SlipstreamError("ss_count_accesses: idx must be [T, B, L]")
+    _check(_lib.ss_count_accesses(
+        C.c_int32(len(counters.counts)), C.c_int64(counters.rows),
+        _dev_ptr(idx, torch.int32, "idx"), C.c_int32(idx.shape[1]),
+        C.c_int32(idx.shape[2]), _dev_ptr(n_valid, torch.int32, "n_valid"),
+        C.c_void_p(counters._cptr.data_ptr()), _stream(stream)))
+
+
+def ss_select_hot_workspace_bytes(T: int, rows: int) -> int:
+    return int(_lib.ss_select_hot_workspace_bytes(C.c_int32(T), C.c_int64(rows)))
+
+
+def ss_select_hot_ratio(counters: AccessCounters, lam: float, total: int,
+                        hot_ids: Optional[Sequence[torch.Tensor]],
+                        hot_bits: Optional[Sequence[torch.Tensor]],
+                        n_hot: Optional[torch.Tensor], ws: torch.Tensor,
+                        stream=None) -> None:
+    """hot_ids: T int32 tensors of one length (the cap), or None."""
+    dev = counters.device
+    T = len(counters.counts)
+    cap = 0 if hot_ids is None else int(hot_ids[0].numel())
+    if hot_ids is not None and any(h.numel() != cap for h in hot_ids):
+        raise SlipstreamError("ss_select_hot_ratio: hot_ids need one length")
+    if hot_bits is not None and any(b.numel() < Tables.bitmap_words(counters.rows)
+                                    for b in hot_bits):
+        raise SlipstreamError("ss_select_hot_ratio: bitmap too short")
+    if n_hot is not None and n_hot.numel() < T:
+        raise SlipstreamError("ss_select_hot_ratio: n_hot is shorter than T")
+    ip = _opt_ptr_table(hot_ids, torch.int32, "hot_ids", dev)
+    bp = _opt_ptr_table(hot_bits, torch.int32, "hot_bits", dev)
+    _check(_lib.ss_select_hot_ratio(
+        C.c_int32(T), C.c_int64(counters.rows), C.c_void_p(counters._cptr.data_ptr()),
+        C.c_double(lam), C.c_int64(total), C.c_int32(cap),
+        C.c_void_p(None if ip is None else ip.data_ptr()),
+        C.c_void_p(None if bp is None else bp.data_ptr()),
+        _dev_ptr(n_hot, torch.int32, "n_hot"), _dev_ptr(ws, torch.uint8, "ws"),
+        C.c_size_t(ws.numel()), _stream(stream)))
+
+
+def ss_select_hot_top(counters: AccessCounters, H: int,
+                      hot_ids: Optional[Sequence[torch.Tensor]],
+                      hot_bits: Optional[Sequence[torch.Tensor]], ws: torch.Tensor,
+                      stream=None) -> None:
+    dev = counters.device
+    T = len(counters.counts)
+    if hot_ids is not None and any(h.numel() < H for h in hot_ids):
+        raise SlipstreamError("ss_select_hot_top: hot_ids shorter than H")
+    if hot_bits is not None and any(b.numel() < Tables.bitmap_words(counters.rows)
+                                    for b in hot_bits):
+        raise SlipstreamError("ss_select_hot_top: bitmap too short")
+    ip = _opt_ptr_table(hot_ids, torch.int32, "hot_ids", dev)
+    bp = _opt_ptr_table(hot_bits, torch.int32, "hot_bits", dev)
+    _check(_lib.ss_select_hot_top(
+        C.c_int32(T), C.c_int64(counters.rows), C.c_void_p(counters._cptr.data_ptr()),
+        C.c_int32(H), C.c_void_p(None if ip is None else ip.data_ptr()),
+        C.c_void_p(None if bp is None else bp.data_ptr()),
+        _dev_ptr(ws, torch.uint8, "ws"), C.c_size_t(ws.numel()), _stream(stream)))

@@ -101,6 +101,16 @@ static int32_t check_batch(const char *who, const void *idx, int64_t B, int64_t 
     return SS_OK;
 }
 
+static int32_t check_hot_tables(const char *who, int32_t T, int64_t rows)
+{
+    if (T < 1 || T > 65535)
+        return fail(SS_ERR_INVALID_ARG, "%s: num_tables = %d (need 1..65535)", who, T);
+    if (rows < 1 || rows >= (1LL << 31))
+        return fail(SS_ERR_INVALID_ARG, "%s: rows = %lld (need 1 <= rows < 2^31)", who,
+                    (long long)rows);
+    return SS_OK;
+}
+
 static int32_t check_ws(const char *who, const void *ws, size_t have, size_t need)
 {
     if (!ws) return fail(SS_ERR_WORKSPACE, "%s: workspace is NULL", who);
@@ -382,6 +392,75 @@ int32_t ss_drop_stats(uint32_t count, int64_t n_samples, int64_t population,
     out[6] = (share - half) * scale;
     out[7] = (share + half) * scale;
     return SS_OK;
+}
+
+int32_t ss_count_accesses(int32_t num_tables, int64_t rows, const int32_t *idx, int32_t B,
+                          int32_t L, const int32_t *n_valid, uint32_t *const *counts,
+                          void *stream)
+{
+    const char *who = "ss_count_accesses";
+    int32_t rc = check_hot_tables(who, num_tables, rows);
+    if (rc) return rc;
+    rc = check_batch(who, idx, B, L, num_tables);
+    if (rc) return rc;
+    if (!counts) return fail(SS_ERR_INVALID_ARG, "%s: counts is NULL", who);
+    return launch_count_accesses(num_tables, idx, B, L, n_valid, counts,
+                                 static_cast<hipStream_t>(stream));
+}
+
+size_t ss_select_hot_workspace_bytes(int32_t num_tables, int64_t rows)
+{
+    if (num_tables < 1 || num_tables > 65535 || rows < 1 || rows >= (1LL << 31)) return 0;
+    return select_hot_ws_bytes(num_tables, rows);
+}
+
+int32_t ss_select_hot_ratio(int32_t num_tables, int64_t rows, uint32_t *const *counts,
+                            double lambda, int64_t total, int32_t cap,
+                            int32_t *const *hot_ids, uint32_t *const *hot_bits,
+                            uint32_t *n_hot, void *ws, size_t ws_bytes, void *stream)
+{
+    const char *who = "ss_select_hot_ratio";
+    int32_t rc = check_hot_tables(who, num_tables, rows);
+    if (rc) return rc;
+    if (!counts) return fail(SS_ERR_INVALID_ARG, "%s: counts is NULL", who);
+    if (lambda != lambda) return fail(SS_ERR_INVALID_ARG, "%s: lambda is NaN", who);
+    if (total < 1) return fail(SS_ERR_INVALID_ARG, "%s: total = %lld", who, (long long)total);
+    if (cap < 0 || (cap > 0 && !hot_ids))
+        return fail(SS_ERR_INVALID_ARG, "%s: cap = %d, hot_ids %s", who, cap,
+                    hot_ids ? "given" : "NULL");
+    rc = check_ws(who, ws, ws_bytes, select_hot_ws_bytes(num_tables, rows));
+    if (rc) return rc;
+    // Smallest count whose share reaches lambda, with the share taken exactly as
+    // the definition has it: an fp64 quotient.  The quotient grows with the
+    // count, so a product gives the neighbourhood and two short loops the answer.
+    const double tot = (double)total, x = lambda * tot;
+    const uint64_t limit = 1ull << 32;               // "no 32-bit count is enough"
+    uint64_t need = !(x > 0.0) ? 0 : (x >= 4294967296.0 ? limit : (uint64_t)ceil(x));
+    while (need > 0 && (double)(need - 1) / tot >= lambda) --need;
+    while (need < limit && (double)need / tot < lambda) ++need;
+    const uint32_t c = need == 0 ? 0u : (uint32_t)(need - 1);
+    const uint32_t e = need == 0 ? 0xFFFFFFFFu : 0u;
+    return launch_select_hot(num_tables, rows, counts, false, c, e, cap > 0 ? hot_ids : nullptr,
+                             cap, hot_bits, n_hot, ws, static_cast<hipStream_t>(stream));
+}
+
+int32_t ss_select_hot_top(int32_t num_tables, int64_t rows, uint32_t *const *counts,
+                          int32_t H, int32_t *const *hot_ids, uint32_t *const *hot_bits,
+                          void *ws, size_t ws_bytes, void *stream)
+{
+    const char *who = "ss_select_hot_top";
+    int32_t rc = check_hot_tables(who, num_tables, rows);
+    if (rc) return rc;
+    if (!counts) return fail(SS_ERR_INVALID_ARG, "%s: counts is NULL", who);
+    if (H < 0 || H > rows)
+        return fail(SS_ERR_INVALID_ARG, "%s: H = %d (need 0 <= H <= rows)", who, H);
+    if (H > 0 && !hot_ids) return fail(SS_ERR_INVALID_ARG, "%s: hot_ids is NULL", who);
+    rc = check_ws(who, ws, ws_bytes, select_hot_ws_bytes(num_tables, rows));
+    if (rc) return rc;
+    // H = 0: no count is above the largest one, and no equal row is taken
+    return launch_select_hot(num_tables, rows, counts, H > 0, H > 0 ? 0u : 0xFFFFFFFFu,
+                             (uint32_t)H, H > 0 ? hot_ids : nullptr, H, hot_bits, nullptr, ws,
+                             static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

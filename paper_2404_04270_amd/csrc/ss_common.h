@@ -121,6 +121,16 @@ int32_t launch_sample_drop(int T, int32_t *const *hot_ids, int H, double *const 
                            const int32_t *sidx, int S, int L, int alpha,
                            const float *thresholds, int n_thr, uint32_t *counts,
                            hipStream_t s);
+int32_t launch_count_accesses(int T, const int32_t *idx, int Bcap, int L,
+                              const int32_t *n_valid, uint32_t *const *counts,
+                              hipStream_t s);
+size_t select_hot_ws_bytes(int T, int64_t R);
+// Rows with count > c, and the first e rows (by id) with count == c; with `top`
+// set, c and e are first replaced by the outcome of a radix select for the e
+// largest counts.
+int32_t launch_select_hot(int T, int64_t R, uint32_t *const *counts, bool top, uint32_t c,
+                          uint32_t e, int32_t *const *hot_ids, int cap,
+                          uint32_t *const *hot_bits, uint32_t *n_hot, void *ws, hipStream_t s);
 // p[0..n) = 0 by a small kernel (a memset node would not survive graph capture)
 void launch_zero_u32(uint32_t *p, int n, hipStream_t s);
 
