@@ -177,3 +177,41 @@ def test_ladder_search_finds_the_largest_threshold_within_budget():
         assert all(b <= budget for t, b in tried if t <= T)
     assert ladder_search(bound, 1e-5, 1.0, -0.1)[0] is None        # even lo is over
     assert ladder_search(bound, 1e-5, 1.0, 1.0)[0] == 1.0          # hi itself fits
+
+
+def test_hot_set_calls_validate_on_the_host(lib):
+    lib.ss_select_hot_workspace_bytes.restype = C.c_size_t
+    lib.ss_last_error.restype = C.c_char_p
+    for name in ("ss_count_accesses", "ss_select_hot_ratio", "ss_select_hot_top"):
+        getattr(lib, name).restype = C.c_int32
+    small = lib.ss_select_hot_workspace_bytes(C.c_int32(1), C.c_int64(100))
+    big = lib.ss_select_hot_workspace_bytes(C.c_int32(26), C.c_int64(1_000_000))
+    assert 0 < small < big and small % 256 == 0 and big % 256 == 0
+    assert lib.ss_select_hot_workspace_bytes(C.c_int32(0), C.c_int64(100)) == 0
+    assert lib.ss_select_hot_workspace_bytes(C.c_int32(1), C.c_int64(1 << 31)) == 0
+    fake = C.c_void_p(256)                  # never dereferenced: every call is rejected
+
+    def count(T=2, rows=100, idx=fake, B=4, L=1, counts=fake):
+        return lib.ss_count_accesses(C.c_int32(T), C.c_int64(rows), idx, C.c_int32(B),
+                                     C.c_int32(L), None, counts, None)
+    for kw, text in [(dict(T=0), b"num_tables"), (dict(rows=0), b"rows"),
+                     (dict(idx=None), b"idx"), (dict(B=0), b"batch"), (dict(L=0), b"L ="),
+                     (dict(counts=None), b"counts")]:
+        assert count(**kw) != 0 and text in lib.ss_last_error(), kw
+
+    def ratio(lam=0.5, total=10, cap=4, ids=fake, ws=fake, ws_bytes=1 << 20):
+        return lib.ss_select_hot_ratio(C.c_int32(2), C.c_int64(100), fake, C.c_double(lam),
+                                       C.c_int64(total), C.c_int32(cap), ids, None, None, ws,
+                                       C.c_size_t(ws_bytes), None)
+    for kw, text in [(dict(lam=float("nan")), b"NaN"), (dict(total=0), b"total"),
+                     (dict(cap=-1), b"cap"), (dict(ids=None), b"hot_ids"),
+                     (dict(ws=None), b"workspace"), (dict(ws_bytes=8), b"workspace"),
+                     (dict(ws=C.c_void_p(264)), b"aligned")]:
+        assert ratio(**kw) != 0 and text in lib.ss_last_error(), kw
+
+    def top(H=5, ids=fake, ws_bytes=1 << 20):
+        return lib.ss_select_hot_top(C.c_int32(2), C.c_int64(100), fake, C.c_int32(H), ids,
+                                     None, fake, C.c_size_t(ws_bytes), None)
+    for kw, text in [(dict(H=-1), b"H ="), (dict(H=101), b"H ="), (dict(ids=None), b"hot_ids"),
+                     (dict(ws_bytes=0), b"workspace")]:
+        assert top(**kw) != 0 and text in lib.ss_last_error(), kw
