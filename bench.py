@@ -52,6 +52,9 @@ def parse():
                     help="after the timed steps, also time the hot-set identification "
                          "(access counters over the ring of batches, then the top-H rows "
                          "of every table) and report it beside the step")
+    ap.add_argument("--layernorm-probe", action="store_true",
+                    help="after the timed steps, also time LayerNorm forward and backward "
+                         "over the pooled vectors of one batch")
     return ap.parse_args()
 
 
@@ -170,11 +173,51 @@ def main():
 
     if args.sampling_probe > 0:
         out["sampling_block"] = sampling_probe(B, step, idx_d, args.sampling_probe, thr)
+    if args.layernorm_probe:
+        out["layernorm"] = layernorm_probe(B, step, grads)
     if args.hotset_probe:
         out["hot_set"] = hotset_probe(B, step, idx_d, cfg.hot_rows, hot)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, w, idx_ring, hot, thr, args.cpu_seconds)
     print(json.dumps(out))
+
+
+def layernorm_probe(B, step, grads):
+    """Kernel durations and achieved HBM rates of the feature normalization."""
+    import torch
+    x = step.pooled
+    T, Bn, D = x.shape
+    dev = x.device
+    gamma = torch.ones(T, D, device=dev)
+    beta = torch.zeros(T, D, device=dev)
+    y = torch.empty_like(x)
+    dx = torch.empty_like(x)
+    mean = torch.empty(T, Bn, device=dev)
+    rstd = torch.empty(T, Bn, device=dev)
+    dgamma, dbeta = torch.empty(T, D, device=dev), torch.empty(T, D, device=dev)
+    ws = torch.empty(max(256, B.ss_layernorm_backward_workspace_bytes(T, D, Bn)),
+                     dtype=torch.uint8, device=dev)
+
+    def once(k):
+        B.ss_layernorm_forward(x, step.n_kept, gamma, beta, 1e-5, y, mean, rstd)
+        B.ss_layernorm_backward(grads[k % len(grads)], x, step.n_kept, gamma, mean, rstd, dx,
+                                dgamma, dbeta, ws)
+    for k in range(5):
+        once(k)
+    torch.cuda.synchronize()
+    B.ss_profile_enable(True)
+    for k in range(40):
+        once(k)
+    torch.cuda.synchronize()
+    B.ss_profile_enable(False)
+    prof = B.ss_profile_report()
+    kept = int(step.n_kept.item())
+    elems = T * kept * D
+    fwd_us = 1e3 * prof["ln_forward_kernel"][1] / prof["ln_forward_kernel"][0]
+    bwd_us = 1e3 * prof["ln_backward_kernel"][1] / prof["ln_backward_kernel"][0]
+    return {"forward_us": fwd_us, "forward_GBs": 8 * elems / fwd_us / 1e3,
+            "backward_us": bwd_us, "backward_GBs": 12 * elems / bwd_us / 1e3,
+            "algorithmic_bytes": {"forward": 8 * elems, "backward": 12 * elems}}
 
 
 def hotset_probe(B, step, idx_d, H, hot_ref):

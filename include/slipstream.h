@@ -297,6 +297,43 @@ int32_t ss_select_hot_top(int32_t num_tables, int64_t rows, uint32_t *const *cou
                           void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Feature normalization of the pooled vectors (section 3.5: a LayerNorm layer
+ * brings every sparse vector to zero mean and unit variance; one layer per
+ * table).  For each vector v = x[t][j][:], j < n_valid:
+ *     mu = mean_d(v),  var = mean_d((v - mu)^2),  rstd = 1 / sqrt(var + eps)
+ *     y[t][j][d] = gamma[t][d] * (v_d - mu) * rstd + beta[t][d]
+ *   x, y      device fp32 [T][Bcap][dim], 16-byte aligned (the layout of
+ *             ss_embbag_forward's output); y may be x itself
+ *   gamma, beta  device fp32 [T][dim], or NULL for 1 and 0
+ *   mean, rstd   device fp32 [T][Bcap], written for j < n_valid (the backward
+ *             pass reads them)
+ *   n_valid   as for ss_embbag_forward; vectors j >= n_valid are left untouched
+ *   eps >= 0
+ */
+int32_t ss_layernorm_forward(int32_t num_tables, int32_t dim, const float *x,
+                             int32_t Bcap, const int32_t *n_valid, const float *gamma,
+                             const float *beta, float eps, float *y, float *mean,
+                             float *rstd, void *stream);
+
+/*
+ * Gradient of ss_layernorm_forward.  With xh = (x - mu) * rstd and g = gamma * dy:
+ *     dx[t][j][d]  = rstd * ( g_d - mean_d(g) - xh_d * mean_d(g * xh) )
+ *     dgamma[t][d] = sum_{j < n_valid} dy[t][j][d] * xh[t][j][d]
+ *     dbeta[t][d]  = sum_{j < n_valid} dy[t][j][d]
+ * dx is the gradient ss_embbag_backward_update expects.  dx may be dy itself.
+ * dgamma / dbeta (device fp32 [T][dim]) may be NULL; if either is given, ws must
+ * hold ss_layernorm_backward_workspace_bytes(...) bytes, 256-byte aligned.  The
+ * sums over the batch are taken in a fixed order.
+ */
+int32_t ss_layernorm_backward(int32_t num_tables, int32_t dim, const float *dy,
+                              const float *x, int32_t Bcap, const int32_t *n_valid,
+                              const float *gamma, const float *mean, const float *rstd,
+                              float *dx, float *dgamma, float *dbeta, void *ws,
+                              size_t ws_bytes, void *stream);
+size_t ss_layernorm_backward_workspace_bytes(int32_t num_tables, int32_t dim,
+                                             int32_t Bcap);
+
+/*
  * Measurement aid, off by default (not part of the method).  While enabled,
  * every kernel the library launches carries a pair of HIP events that the
  * runtime stamps with the start and end of that kernel's execution (this is the

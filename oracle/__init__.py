@@ -42,7 +42,8 @@ def _load():
                      "oracle_detect_stale", "oracle_filter_batch",
                      "oracle_sample_drop", "oracle_drop_stats",
                      "oracle_count_accesses", "oracle_select_hot_ratio",
-                     "oracle_select_hot_top"):
+                     "oracle_select_hot_top", "oracle_layernorm_forward",
+                     "oracle_layernorm_backward"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -264,3 +265,47 @@ def select_hot_top(counts: Sequence[np.ndarray], H: int):
         raise ValueError("select_hot_top: need 0 <= H <= rows")
     _check_rc(rc, "select_hot_top")
     return ids, bits
+
+
+def _opt(a: Optional[np.ndarray], name: str):
+    if a is None:
+        return None
+    _check(a, np.float32, name)
+    return C.c_void_p(a.ctypes.data)
+
+
+def layernorm_forward(x: np.ndarray, gamma: Optional[np.ndarray], beta: Optional[np.ndarray],
+                      eps: float, n_valid: Optional[int] = None):
+    """x fp32 [T, Bcap, D]; gamma, beta fp32 [T, D] or None.
+    Returns (y [T, Bcap, D], mean [T, Bcap], rstd [T, Bcap]); rows j >= n_valid are zero."""
+    _check(x, np.float32, "x")
+    T, Bcap, D = x.shape
+    y = np.zeros_like(x)
+    mean = np.zeros((T, Bcap), np.float32)
+    rstd = np.zeros((T, Bcap), np.float32)
+    rc = _load().oracle_layernorm_forward(
+        C.c_int(T), C.c_int(D), C.c_void_p(x.ctypes.data), C.c_int(Bcap),
+        C.c_int(Bcap if n_valid is None else n_valid), _opt(gamma, "gamma"),
+        _opt(beta, "beta"), C.c_double(eps), C.c_void_p(y.ctypes.data),
+        C.c_void_p(mean.ctypes.data), C.c_void_p(rstd.ctypes.data))
+    _check_rc(rc, "layernorm_forward")
+    return y, mean, rstd
+
+
+def layernorm_backward(dy: np.ndarray, x: np.ndarray, gamma: Optional[np.ndarray],
+                       eps: float, n_valid: Optional[int] = None):
+    """Returns (dx [T, Bcap, D], dgamma [T, D], dbeta [T, D])."""
+    _check(x, np.float32, "x")
+    _check(dy, np.float32, "dy")
+    assert dy.shape == x.shape
+    T, Bcap, D = x.shape
+    dx = np.zeros_like(x)
+    dgamma = np.zeros((T, D), np.float32)
+    dbeta = np.zeros((T, D), np.float32)
+    rc = _load().oracle_layernorm_backward(
+        C.c_int(T), C.c_int(D), C.c_void_p(dy.ctypes.data), C.c_void_p(x.ctypes.data),
+        C.c_int(Bcap), C.c_int(Bcap if n_valid is None else n_valid), _opt(gamma, "gamma"),
+        C.c_double(eps), C.c_void_p(dx.ctypes.data), C.c_void_p(dgamma.ctypes.data),
+        C.c_void_p(dbeta.ctypes.data))
+    _check_rc(rc, "layernorm_backward")
+    return dx, dgamma, dbeta

@@ -33,6 +33,8 @@
  *                      lambda = 1e-6 as "one access in a million"
  *   select_hot_top   - brute force (repeated arg-max), library lexicographic
  *                      sort, ties to the lower row id, the harness's own hot set
+ *   layernorm        - zero mean / unit variance of the output, the library's
+ *                      layer norm and its autograd, central differences
  */
 #include <math.h>
 #include <stdint.h>
@@ -449,5 +451,103 @@ int oracle_select_hot_top(int T, int64_t R, uint32_t *const *counts, int H,
     }
     free(rank);
     free(is_hot);
+    return 0;
+}
+
+/*
+ * Feature normalization of the pooled vectors (section 3.5: every sparse vector
+ * is brought to zero mean and unit variance by a LayerNorm layer).  For each
+ * vector x = x[t][j][:] of length D, j < n_valid:
+ *     mu    = (1/D) sum_d x_d
+ *     var   = (1/D) sum_d (x_d - mu)^2
+ *     rstd  = 1 / sqrt(var + eps)
+ *     y_d   = gamma[t][d] * (x_d - mu) * rstd + beta[t][d]
+ * gamma / beta may be NULL (1 and 0).  mean and rstd are returned per vector.
+ * All arithmetic in fp64, one rounding on store.
+ */
+int oracle_layernorm_forward(int T, int D, const float *x, int Bcap, int n_valid,
+                             const float *gamma, const float *beta, double eps,
+                             float *y, float *mean, float *rstd)
+{
+    for (int t = 0; t < T; ++t) {
+        for (int j = 0; j < n_valid; ++j) {
+            const float *xv = x + ((int64_t)t * Bcap + j) * D;
+            float *yv = y + ((int64_t)t * Bcap + j) * D;
+            double mu = 0.0, var = 0.0;
+            for (int d = 0; d < D; ++d)
+                mu += (double)xv[d];
+            mu /= D;
+            for (int d = 0; d < D; ++d)
+                var += ((double)xv[d] - mu) * ((double)xv[d] - mu);
+            var /= D;
+            double rs = 1.0 / sqrt(var + eps);
+            for (int d = 0; d < D; ++d) {
+                double g = gamma ? (double)gamma[(int64_t)t * D + d] : 1.0;
+                double b = beta ? (double)beta[(int64_t)t * D + d] : 0.0;
+                yv[d] = (float)(g * ((double)xv[d] - mu) * rs + b);
+            }
+            mean[(int64_t)t * Bcap + j] = (float)mu;
+            rstd[(int64_t)t * Bcap + j] = (float)rs;
+        }
+    }
+    return 0;
+}
+
+/*
+ * Gradient of the above.  With xh_d = (x_d - mu) * rstd and g_d = gamma_d * dy_d:
+ *     dx_d      = rstd * ( g_d - mean_d(g) - xh_d * mean_d(g * xh) )
+ *     dgamma_d  = sum_{j < n_valid} dy[t][j][d] * xh[t][j][d]
+ *     dbeta_d   = sum_{j < n_valid} dy[t][j][d]
+ * mu and rstd are recomputed from x in fp64 (they are not inputs here), so the
+ * result does not inherit the rounding of a stored fp32 rstd.
+ */
+int oracle_layernorm_backward(int T, int D, const float *dy, const float *x, int Bcap,
+                              int n_valid, const float *gamma, double eps, float *dx,
+                              float *dgamma, float *dbeta)
+{
+    double *xh = (double *)malloc((size_t)D * sizeof(double));
+    double *dg = (double *)malloc((size_t)D * sizeof(double));
+    double *db = (double *)malloc((size_t)D * sizeof(double));
+    if (!xh || !dg || !db) {
+        free(xh); free(dg); free(db);
+        return -2;
+    }
+    for (int t = 0; t < T; ++t) {
+        for (int d = 0; d < D; ++d)
+            dg[d] = db[d] = 0.0;
+        for (int j = 0; j < n_valid; ++j) {
+            const float *xv = x + ((int64_t)t * Bcap + j) * D;
+            const float *dv = dy + ((int64_t)t * Bcap + j) * D;
+            float *ov = dx + ((int64_t)t * Bcap + j) * D;
+            double mu = 0.0, var = 0.0;
+            for (int d = 0; d < D; ++d)
+                mu += (double)xv[d];
+            mu /= D;
+            for (int d = 0; d < D; ++d)
+                var += ((double)xv[d] - mu) * ((double)xv[d] - mu);
+            var /= D;
+            double rs = 1.0 / sqrt(var + eps);
+            double m_g = 0.0, m_gx = 0.0;
+            for (int d = 0; d < D; ++d) {
+                double g = (gamma ? (double)gamma[(int64_t)t * D + d] : 1.0) * (double)dv[d];
+                xh[d] = ((double)xv[d] - mu) * rs;
+                m_g += g;
+                m_gx += g * xh[d];
+                dg[d] += (double)dv[d] * xh[d];
+                db[d] += (double)dv[d];
+            }
+            m_g /= D;
+            m_gx /= D;
+            for (int d = 0; d < D; ++d) {
+                double g = (gamma ? (double)gamma[(int64_t)t * D + d] : 1.0) * (double)dv[d];
+                ov[d] = (float)(rs * (g - m_g - xh[d] * m_gx));
+            }
+        }
+        for (int d = 0; d < D; ++d) {
+            if (dgamma) dgamma[(int64_t)t * D + d] = (float)dg[d];
+            if (dbeta) dbeta[(int64_t)t * D + d] = (float)db[d];
+        }
+    }
+    free(xh); free(dg); free(db);
     return 0;
 }

@@ -15,7 +15,8 @@ _BINDING_NAMES = (
     "ss_embbag_backward_prepare", "ss_embbag_backward_apply",
     "ss_embbag_forward_grouped", "ss_sample_drop", "ss_drop_stats",
     "ss_count_accesses", "ss_select_hot_workspace_bytes", "ss_select_hot_ratio",
-    "ss_select_hot_top", "AccessCounters",
+    "ss_select_hot_top", "AccessCounters", "ss_layernorm_forward",
+    "ss_layernorm_backward", "ss_layernorm_backward_workspace_bytes",
     "EmbeddingStep", "lib_path",
 )
 

@@ -22,7 +22,8 @@ SYMBOLS = (
     "ss_profile_report", "ss_embbag_backward_prepare", "ss_embbag_backward_apply",
     "ss_embbag_forward_grouped", "ss_sample_drop", "ss_drop_stats",
     "ss_count_accesses", "ss_select_hot_workspace_bytes", "ss_select_hot_ratio",
-    "ss_select_hot_top",
+    "ss_select_hot_top", "ss_layernorm_forward", "ss_layernorm_backward",
+    "ss_layernorm_backward_workspace_bytes",
 )
 
 
@@ -47,13 +48,15 @@ def _load():
     lib.ss_filter_batch_workspace_bytes.restype = C.c_size_t
     lib.ss_backward_workspace_bytes.restype = C.c_size_t
     lib.ss_select_hot_workspace_bytes.restype = C.c_size_t
+    lib.ss_layernorm_backward_workspace_bytes.restype = C.c_size_t
     lib.ss_profile_enable.restype = None
     for n in ("ss_filter_batch", "ss_embbag_forward",
               "ss_embbag_backward_update", "ss_detect_stale",
               "ss_profile_report", "ss_embbag_backward_prepare",
               "ss_embbag_backward_apply", "ss_embbag_forward_grouped",
               "ss_sample_drop", "ss_drop_stats", "ss_count_accesses",
-              "ss_select_hot_ratio", "ss_select_hot_top"):
+              "ss_select_hot_ratio", "ss_select_hot_top", "ss_layernorm_forward",
+              "ss_layernorm_backward"):
         getattr(lib, n).restype = C.c_int32
     return lib
 
@@ -419,3 +422,53 @@ def ss_select_hot_top(counters: AccessCounters, H: int,
         C.c_int32(H), C.c_void_p(None if ip is None else ip.data_ptr()),
         C.c_void_p(None if bp is None else bp.data_ptr()),
         _dev_ptr(ws, torch.uint8, "ws"), C.c_size_t(ws.numel()), _stream(stream)))
+
+
+def _ln_shape(x: torch.Tensor):
+    if x.dim() != 3:
+        raise SlipstreamError("layernorm: need fp32 [T, Bcap, D]")
+    return int(x.shape[0]), int(x.shape[1]), int(x.shape[2])
+
+
+def ss_layernorm_forward(x: torch.Tensor, n_valid: Optional[torch.Tensor],
+                         gamma: Optional[torch.Tensor], beta: Optional[torch.Tensor],
+                         eps: float, y: torch.Tensor, mean: torch.Tensor,
+                         rstd: torch.Tensor, stream=None) -> None:
+    T, Bcap, D = _ln_shape(x)
+    if y.shape != x.shape or mean.numel() < T * Bcap or rstd.numel() < T * Bcap:
+        raise SlipstreamError("ss_layernorm_forward: an output tensor is too small")
+    for p, name in ((gamma, "gamma"), (beta, "beta")):
+        if p is not None and tuple(p.shape) != (T, D):
+            raise SlipstreamError(f"ss_layernorm_forward: {name} must be [T, D]")
+    _check(_lib.ss_layernorm_forward(
+        C.c_int32(T), C.c_int32(D), _dev_ptr(x, torch.float32, "x"), C.c_int32(Bcap),
+        _dev_ptr(n_valid, torch.int32, "n_valid"), _dev_ptr(gamma, torch.float32, "gamma"),
+        _dev_ptr(beta, torch.float32, "beta"), C.c_float(eps),
+        _dev_ptr(y, torch.float32, "y"), _dev_ptr(mean, torch.float32, "mean"),
+        _dev_ptr(rstd, torch.float32, "rstd"), _stream(stream)))
+
+
+def ss_layernorm_backward_workspace_bytes(T: int, dim: int, Bcap: int) -> int:
+    return int(_lib.ss_layernorm_backward_workspace_bytes(
+        C.c_int32(T), C.c_int32(dim), C.c_int32(Bcap)))
+
+
+def ss_layernorm_backward(dy: torch.Tensor, x: torch.Tensor,
+                          n_valid: Optional[torch.Tensor], gamma: Optional[torch.Tensor],
+                          mean: torch.Tensor, rstd: torch.Tensor, dx: torch.Tensor,
+                          dgamma: Optional[torch.Tensor], dbeta: Optional[torch.Tensor],
+                          ws: Optional[torch.Tensor], stream=None) -> None:
+    T, Bcap, D = _ln_shape(x)
+    if dy.shape != x.shape or dx.shape != x.shape:
+        raise SlipstreamError("ss_layernorm_backward: dy, x and dx need one shape")
+    for p, name in ((gamma, "gamma"), (dgamma, "dgamma"), (dbeta, "dbeta")):
+        if p is not None and tuple(p.shape) != (T, D):
+            raise SlipstreamError(f"ss_layernorm_backward: {name} must be [T, D]")
+    _check(_lib.ss_layernorm_backward(
+        C.c_int32(T), C.c_int32(D), _dev_ptr(dy, torch.float32, "dy"),
+        _dev_ptr(x, torch.float32, "x"), C.c_int32(Bcap),
+        _dev_ptr(n_valid, torch.int32, "n_valid"), _dev_ptr(gamma, torch.float32, "gamma"),
+        _dev_ptr(mean, torch.float32, "mean"), _dev_ptr(rstd, torch.float32, "rstd"),
+        _dev_ptr(dx, torch.float32, "dx"), _dev_ptr(dgamma, torch.float32, "dgamma"),
+        _dev_ptr(dbeta, torch.float32, "dbeta"), _dev_ptr(ws, torch.uint8, "ws"),
+        C.c_size_t(0 if ws is None else ws.numel()), _stream(stream)))

@@ -463,4 +463,56 @@ int32_t ss_select_hot_top(int32_t num_tables, int64_t rows, uint32_t *const *cou
                              static_cast<hipStream_t>(stream));
 }
 
+static int32_t check_ln(const char *who, int32_t T, int32_t dim, int32_t Bcap)
+{
+    if (T < 1 || T > 65535)
+        return fail(SS_ERR_INVALID_ARG, "%s: num_tables = %d (need 1..65535)", who, T);
+    if (dim < 4 || dim % 4 != 0 || dim > 1024)
+        return fail(SS_ERR_INVALID_ARG, "%s: dim = %d (need a multiple of 4 in [4, 1024])",
+                    who, dim);
+    if (Bcap < 1) return fail(SS_ERR_INVALID_ARG, "%s: Bcap = %d", who, Bcap);
+    return SS_OK;
+}
+
+int32_t ss_layernorm_forward(int32_t num_tables, int32_t dim, const float *x, int32_t Bcap,
+                             const int32_t *n_valid, const float *gamma, const float *beta,
+                             float eps, float *y, float *mean, float *rstd, void *stream)
+{
+    const char *who = "ss_layernorm_forward";
+    int32_t rc = check_ln(who, num_tables, dim, Bcap);
+    if (rc) return rc;
+    if (!x || !y || !mean || !rstd)
+        return fail(SS_ERR_INVALID_ARG, "%s: x, y, mean or rstd is NULL", who);
+    if (!(eps >= 0.0f)) return fail(SS_ERR_INVALID_ARG, "%s: eps = %g", who, (double)eps);
+    return launch_layernorm_forward(num_tables, dim, x, Bcap, n_valid, gamma, beta, eps, y,
+                                    mean, rstd, static_cast<hipStream_t>(stream));
+}
+
+size_t ss_layernorm_backward_workspace_bytes(int32_t num_tables, int32_t dim, int32_t Bcap)
+{
+    if (num_tables < 1 || num_tables > 65535 || dim < 4 || dim % 4 != 0 || dim > 1024 ||
+        Bcap < 1)
+        return 0;
+    return layernorm_backward_ws_bytes(num_tables, dim, Bcap);
+}
+
+int32_t ss_layernorm_backward(int32_t num_tables, int32_t dim, const float *dy,
+                              const float *x, int32_t Bcap, const int32_t *n_valid,
+                              const float *gamma, const float *mean, const float *rstd,
+                              float *dx, float *dgamma, float *dbeta, void *ws,
+                              size_t ws_bytes, void *stream)
+{
+    const char *who = "ss_layernorm_backward";
+    int32_t rc = check_ln(who, num_tables, dim, Bcap);
+    if (rc) return rc;
+    if (!dy || !x || !mean || !rstd || !dx)
+        return fail(SS_ERR_INVALID_ARG, "%s: dy, x, mean, rstd or dx is NULL", who);
+    if (dgamma || dbeta) {
+        rc = check_ws(who, ws, ws_bytes, layernorm_backward_ws_bytes(num_tables, dim, Bcap));
+        if (rc) return rc;
+    }
+    return launch_layernorm_backward(num_tables, dim, dy, x, Bcap, n_valid, gamma, mean, rstd,
+                                     dx, dgamma, dbeta, ws, static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

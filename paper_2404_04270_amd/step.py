@@ -92,3 +92,49 @@ class EmbeddingStep:
                 detected = True
         self.it += 1
         return detected
+
+
+class SnapshotRing:
+    """N temporal snapshots of the hot rows (section 3.1.2 keeps N of them; the
+    comparison itself is always between two, Eq. 1 / Eq. 5).
+
+    The library compares the current rows with whichever stored snapshot it is
+    handed, so a ring needs no kernel of its own: it is N snapshot buffers and a
+    head.  `detect(threshold, lag)` measures the drift against the snapshot taken
+    `lag` pushes ago; with lag == depth that snapshot is the oldest one, which
+    the same launch then overwrites with the current rows (compare and refresh
+    read the hot rows once).  depth = 1, lag = 1 is the two-snapshot scheme of
+    Eq. 5 that EmbeddingStep uses.
+    """
+
+    def __init__(self, tables: B.Tables, hot_ids: Sequence[torch.Tensor], depth: int,
+                 diagnostics: bool = True):
+        if depth < 1:
+            raise ValueError("depth >= 1")
+        self.tables, self.depth = tables, depth
+        self.slots = [B.HotState(tables, hot_ids, diagnostics=diagnostics)
+                      for _ in range(depth)]
+        self.pushed = 0                       # snapshots taken so far
+
+    def _slot(self, lag: int) -> B.HotState:
+        """The snapshot taken `lag` pushes ago (lag = 1: the newest)."""
+        if not 1 <= lag <= min(self.depth, self.pushed):
+            raise ValueError(f"lag {lag}: {min(self.depth, self.pushed)} snapshots are held")
+        return self.slots[(self.pushed - lag) % self.depth]
+
+    def push(self) -> None:
+        """Store the current hot rows as the newest snapshot (drops the oldest)."""
+        B.ss_detect_stale(self.tables, self.slots[self.pushed % self.depth], 0.0, True)
+        self.pushed += 1
+
+    def detect(self, threshold: float, lag: int = 1, push: bool = True) -> B.HotState:
+        """Flag rows whose drift since `lag` snapshots ago is within the threshold;
+        returns the slot whose drift / verdict buffers this call filled."""
+        ref = self._slot(lag)
+        fused = push and lag == self.depth    # the reference is the slot to overwrite
+        B.ss_detect_stale(self.tables, ref, threshold, fused)
+        if fused:
+            self.pushed += 1
+        elif push:
+            self.push()
+        return ref

@@ -447,3 +447,51 @@ def test_invalid_arguments_are_rejected_before_launch(B, dev):
         B.ss_embbag_forward(bad, torch.zeros((1, 2, 1), dtype=torch.int32, device=dev),
                             None, torch.zeros((1, 2, 6), dtype=torch.float32, device=dev))
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------- snapshot ring
+@pytest.mark.parametrize("depth,lag", [(1, 1), (3, 3), (3, 1), (4, 2)])
+def test_snapshot_ring_compares_with_the_right_snapshot(B, dev, depth, lag):
+    """N temporal snapshots (section 3.1.2): the drift is taken against the
+    snapshot `lag` periods back, here checked against the oracle fed with that
+    snapshot from a plain host-side history."""
+    from paper_2404_04270_amd.step import SnapshotRing
+    rng = np.random.default_rng(700 + depth * 10 + lag)
+    T, R, D, H = 2, 1500, 32, 300
+    W = rand_tables(rng, T, R, D)
+    hot = [np.sort(rng.choice(R, H, replace=False)).astype(np.int32) for _ in range(T)]
+    tb = B.Tables(to_dev(W, dev))
+    tb.new_bits()
+    ring = SnapshotRing(tb, to_dev(hot, dev), depth)
+    history = []                                  # host copies of every snapshot taken
+    ref_bits = [np.zeros((R + 31) // 32, np.uint32) for _ in range(T)]
+    thr = 2e-3
+    for period in range(depth + 4):
+        # the tables move: shrinking steps, so that later periods flag more rows
+        step = 4e-3 / (1 + period) / math.sqrt(D)
+        for t in range(T):
+            W[t][hot[t]] += (step * rng.uniform(0, 1, (H, 1))
+                             * rng.choice([-1.0, 1.0], (H, D))).astype(np.float32)
+            tb.weights[t].copy_(torch.from_numpy(W[t]))
+        if ring.pushed < lag:
+            ring.push()
+            history.append([W[t][hot[t]].copy() for t in range(T)])
+            continue
+        snap = [s.copy() for s in history[-lag]]
+        r_sh, r_dr, _ = oracle.detect_stale(W, ref_bits, hot, snap, thr, refresh=False)
+        slot = ring.detect(thr, lag=lag)
+        history.append([W[t][hot[t]].copy() for t in range(T)])
+        for t in range(T):
+            np.testing.assert_allclose(slot.drift[t].cpu().numpy(), r_dr[t], rtol=1e-12)
+            graded = np.abs(r_dr[t] - thr) > 1e-6 * thr
+            assert graded.sum() > 0.99 * H
+            assert np.array_equal(slot.stale_hot[t].cpu().numpy()[graded], r_sh[t][graded])
+            if graded.all():
+                assert np.array_equal(bits_from_dev(tb.bits)[t], ref_bits[t])
+        # the ring now holds the last `depth` snapshots, newest first by lag
+        for k in range(1, min(depth, ring.pushed) + 1):
+            for t in range(T):
+                assert np.array_equal(ring._slot(k).snapshot[t].cpu().numpy(), history[-k][t])
+    assert sum(int(b.sum()) for b in ref_bits) > 0
+    with pytest.raises(ValueError):
+        ring._slot(depth + 1)

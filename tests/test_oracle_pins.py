@@ -586,3 +586,70 @@ def test_select_hot_top_brute_force_ties_and_the_harness_rule():
         oracle.count_accesses(cfg.rows, stream[it], cnt)
     ids, _ = oracle.select_hot_top(cnt, cfg.hot_rows)
     assert np.array_equal(np.stack(ids), wl.hot_set(stream, cfg.rows, cfg.hot_rows))
+
+
+# ------------------------------------------------------ feature normalization
+def test_layernorm_forward_invariants_and_library():
+    rng = np.random.default_rng(60)
+    T, Bc, D = 3, 17, 24
+    x = (rng.normal(0.3, 2.0, (T, Bc, D)) * rng.uniform(0.01, 5, (T, Bc, 1))).astype(np.float32)
+    # without affine: every vector has zero mean and unit variance (section 3.5)
+    y, mean, rstd = oracle.layernorm_forward(x, None, None, 0.0)
+    assert np.abs(y.astype(np.float64).mean(-1)).max() < 1e-6
+    assert np.abs(y.astype(np.float64).var(-1) - 1.0).max() < 1e-5
+    np.testing.assert_allclose(mean, x.astype(np.float64).mean(-1), rtol=1e-6, atol=1e-7)
+    np.testing.assert_allclose(rstd, 1 / x.astype(np.float64).std(-1), rtol=1e-6)
+    # the library's layer norm, one per table, with affine parameters and eps
+    gamma = rng.normal(1, 0.5, (T, D)).astype(np.float32)
+    beta = rng.normal(0, 0.5, (T, D)).astype(np.float32)
+    y, _, _ = oracle.layernorm_forward(x, gamma, beta, 1e-5, n_valid=11)
+    for t in range(T):
+        ref = torch.nn.functional.layer_norm(
+            torch.from_numpy(x[t]).double(), (D,), torch.from_numpy(gamma[t]).double(),
+            torch.from_numpy(beta[t]).double(), 1e-5).numpy()
+        np.testing.assert_allclose(y[t, :11], ref[:11], rtol=1e-6, atol=1e-7)
+        assert not y[t, 11:].any()                       # rows past n_valid untouched
+    # a shift of the input changes nothing, a scale only through eps
+    y0 = oracle.layernorm_forward(x, gamma, beta, 0.0)[0]
+    y1 = oracle.layernorm_forward((x * 4 + 2).astype(np.float32), gamma, beta, 0.0)[0]
+    np.testing.assert_allclose(y0, y1, rtol=1e-4, atol=1e-5)
+
+
+def test_layernorm_backward_autograd_and_central_differences():
+    rng = np.random.default_rng(61)
+    T, Bc, D = 2, 9, 12
+    x = rng.normal(0, 1.5, (T, Bc, D)).astype(np.float32)
+    dy = rng.normal(0, 1, (T, Bc, D)).astype(np.float32)
+    gamma = rng.normal(1, 0.5, (T, D)).astype(np.float32)
+    beta = rng.normal(0, 0.5, (T, D)).astype(np.float32)
+    eps, nv = 1e-5, 7
+    dx, dgamma, dbeta = oracle.layernorm_backward(dy, x, gamma, eps, n_valid=nv)
+    for t in range(T):
+        xt = torch.from_numpy(x[t, :nv]).double().requires_grad_()
+        gt = torch.from_numpy(gamma[t]).double().requires_grad_()
+        bt = torch.from_numpy(beta[t]).double().requires_grad_()
+        torch.nn.functional.layer_norm(xt, (D,), gt, bt, eps).backward(
+            torch.from_numpy(dy[t, :nv]).double())
+        np.testing.assert_allclose(dx[t, :nv], xt.grad.numpy(), rtol=1e-6, atol=1e-7)
+        np.testing.assert_allclose(dgamma[t], gt.grad.numpy(), rtol=1e-6, atol=1e-7)
+        np.testing.assert_allclose(dbeta[t], bt.grad.numpy(), rtol=1e-6, atol=1e-7)
+        assert not dx[t, nv:].any()
+    # central differences of  sum(dy * y)  in one coordinate of x, no library involved
+    def loss(xm):
+        y, _, _ = oracle.layernorm_forward(xm, gamma, beta, eps)
+        return float((y.astype(np.float64) * dy).sum())
+    dx_all = oracle.layernorm_backward(dy, x, gamma, eps)[0]
+    for (t, j, d) in [(0, 0, 0), (1, 8, 11), (0, 4, 5)]:
+        h = 1e-2
+        xp, xm = x.copy(), x.copy()
+        xp[t, j, d] += h
+        xm[t, j, d] -= h
+        num = (loss(xp) - loss(xm)) / (float(xp[t, j, d]) - float(xm[t, j, d]))
+        assert abs(num - dx_all[t, j, d]) < 2e-3 * max(1.0, abs(num))
+    # the gradient is orthogonal to the two directions LayerNorm removes
+    g = dx_all.astype(np.float64)
+    assert np.abs(g.sum(-1)).max() < 1e-5
+    # no affine parameters: gamma = 1
+    d1 = oracle.layernorm_backward(dy, x, None, eps)[0]
+    d2 = oracle.layernorm_backward(dy, x, np.ones((T, D), np.float32), eps)[0]
+    assert np.array_equal(d1, d2)
