@@ -211,6 +211,11 @@ def layernorm_probe(B, step, grads):
         B.ss_layernorm_forward(x, step.n_kept, gamma, beta, 1e-5, y, mean, rstd)
         B.ss_layernorm_backward(grads[k % len(grads)], x, step.n_kept, gamma, mean, rstd, dx,
                                 dgamma, dbeta, ws)
+        # the same two passes with the pooled vectors formed from the tables on the fly
+        B.ss_embbag_forward_ln(step.tables, step.idx_c, step.n_kept, gamma, beta, 1e-5, y,
+                               mean, rstd)
+        B.ss_embbag_ln_backward(step.tables, step.idx_c, step.n_kept, grads[k % len(grads)],
+                                gamma, mean, rstd, dx, dgamma, dbeta, ws)
     for k in range(5):
         once(k)
     torch.cuda.synchronize()
@@ -224,9 +229,12 @@ def layernorm_probe(B, step, grads):
     elems = T * kept * D
     fwd_us = 1e3 * prof["ln_forward_kernel"][1] / prof["ln_forward_kernel"][0]
     bwd_us = 1e3 * prof["ln_backward_kernel"][1] / prof["ln_backward_kernel"][0]
+    pf_us = 1e3 * prof["ln_forward_pool_kernel"][1] / prof["ln_forward_pool_kernel"][0]
+    pb_us = 1e3 * prof["ln_backward_pool_kernel"][1] / prof["ln_backward_pool_kernel"][0]
     return {"forward_us": fwd_us, "forward_GBs": 8 * elems / fwd_us / 1e3,
             "backward_us": bwd_us, "backward_GBs": 12 * elems / bwd_us / 1e3,
-            "algorithmic_bytes": {"forward": 8 * elems, "backward": 12 * elems}}
+            "algorithmic_bytes": {"forward": 8 * elems, "backward": 12 * elems},
+            "pooled_in_one_pass": {"forward_us": pf_us, "backward_us": pb_us}}
 
 
 def hotset_probe(B, step, idx_d, H, hot_ref):

@@ -334,6 +334,30 @@ size_t ss_layernorm_backward_workspace_bytes(int32_t num_tables, int32_t dim,
                                              int32_t Bcap);
 
 /*
+ * The pooled lookup (section 2.1) and its feature normalization (section 3.5) in
+ * one pass each way, without the pooled tensor ever being stored:
+ *   ss_embbag_forward_ln(...)  = ss_embbag_forward into a temporary x, then
+ *                                ss_layernorm_forward(x) -> y, mean, rstd
+ *   ss_embbag_ln_backward(...) = the same temporary x formed again from the
+ *                                tables, then ss_layernorm_backward(dy, x) -> dx,
+ *                                dgamma, dbeta
+ * Results are bit-identical to the separate calls.  ss_embbag_ln_backward must
+ * see the tables as the forward pass saw them, i.e. it runs before
+ * ss_embbag_backward_update of the same batch, whose gradient argument dx is.
+ * Arguments as in the separate calls; ws as for ss_layernorm_backward (dim and
+ * num_tables taken from tables).
+ */
+int32_t ss_embbag_forward_ln(const ss_tables *tables, const int32_t *idx, int32_t Bcap,
+                             int32_t L, const int32_t *n_valid, const float *gamma,
+                             const float *beta, float eps, float *y, float *mean,
+                             float *rstd, void *stream);
+int32_t ss_embbag_ln_backward(const ss_tables *tables, const int32_t *idx, int32_t Bcap,
+                              int32_t L, const int32_t *n_valid, const float *dy,
+                              const float *gamma, const float *mean, const float *rstd,
+                              float *dx, float *dgamma, float *dbeta, void *ws,
+                              size_t ws_bytes, void *stream);
+
+/*
  * Measurement aid, off by default (not part of the method).  While enabled,
  * every kernel the library launches carries a pair of HIP events that the
  * runtime stamps with the start and end of that kernel's execution (this is the

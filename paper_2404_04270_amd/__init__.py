@@ -17,6 +17,7 @@ _BINDING_NAMES = (
     "ss_count_accesses", "ss_select_hot_workspace_bytes", "ss_select_hot_ratio",
     "ss_select_hot_top", "AccessCounters", "ss_layernorm_forward",
     "ss_layernorm_backward", "ss_layernorm_backward_workspace_bytes",
+    "ss_embbag_forward_ln", "ss_embbag_ln_backward",
     "EmbeddingStep", "lib_path",
 )
 

@@ -23,7 +23,8 @@ SYMBOLS = (
     "ss_embbag_forward_grouped", "ss_sample_drop", "ss_drop_stats",
     "ss_count_accesses", "ss_select_hot_workspace_bytes", "ss_select_hot_ratio",
     "ss_select_hot_top", "ss_layernorm_forward", "ss_layernorm_backward",
-    "ss_layernorm_backward_workspace_bytes",
+    "ss_layernorm_backward_workspace_bytes", "ss_embbag_forward_ln",
+    "ss_embbag_ln_backward",
 )
 
 
@@ -56,7 +57,7 @@ def _load():
               "ss_embbag_backward_apply", "ss_embbag_forward_grouped",
               "ss_sample_drop", "ss_drop_stats", "ss_count_accesses",
               "ss_select_hot_ratio", "ss_select_hot_top", "ss_layernorm_forward",
-              "ss_layernorm_backward"):
+              "ss_layernorm_backward", "ss_embbag_forward_ln", "ss_embbag_ln_backward"):
         getattr(lib, n).restype = C.c_int32
     return lib
 
@@ -472,3 +473,44 @@ def ss_layernorm_backward(dy: torch.Tensor, x: torch.Tensor,
         _dev_ptr(dx, torch.float32, "dx"), _dev_ptr(dgamma, torch.float32, "dgamma"),
         _dev_ptr(dbeta, torch.float32, "dbeta"), _dev_ptr(ws, torch.uint8, "ws"),
         C.c_size_t(0 if ws is None else ws.numel()), _stream(stream)))
+
+
+def ss_embbag_forward_ln(tables: Tables, idx: torch.Tensor, n_valid: Optional[torch.Tensor],
+                         gamma: Optional[torch.Tensor], beta: Optional[torch.Tensor],
+                         eps: float, y: torch.Tensor, mean: torch.Tensor,
+                         rstd: torch.Tensor, stream=None) -> None:
+    Bcap, L = _idx_shape(tables, idx)
+    T, D = tables.num_tables, tables.dim
+    if tuple(y.shape) != (T, Bcap, D) or mean.numel() < T * Bcap or rstd.numel() < T * Bcap:
+        raise SlipstreamError("ss_embbag_forward_ln: an output tensor has the wrong size")
+    for p, name in ((gamma, "gamma"), (beta, "beta")):
+        if p is not None and tuple(p.shape) != (T, D):
+            raise SlipstreamError(f"ss_embbag_forward_ln: {name} must be [T, D]")
+    _check(_lib.ss_embbag_forward_ln(
+        C.byref(tables.c), _dev_ptr(idx, torch.int32, "idx"), C.c_int32(Bcap), C.c_int32(L),
+        _dev_ptr(n_valid, torch.int32, "n_valid"), _dev_ptr(gamma, torch.float32, "gamma"),
+        _dev_ptr(beta, torch.float32, "beta"), C.c_float(eps),
+        _dev_ptr(y, torch.float32, "y"), _dev_ptr(mean, torch.float32, "mean"),
+        _dev_ptr(rstd, torch.float32, "rstd"), _stream(stream)))
+
+
+def ss_embbag_ln_backward(tables: Tables, idx: torch.Tensor, n_valid: Optional[torch.Tensor],
+                          dy: torch.Tensor, gamma: Optional[torch.Tensor],
+                          mean: torch.Tensor, rstd: torch.Tensor, dx: torch.Tensor,
+                          dgamma: Optional[torch.Tensor], dbeta: Optional[torch.Tensor],
+                          ws: Optional[torch.Tensor], stream=None) -> None:
+    Bcap, L = _idx_shape(tables, idx)
+    T, D = tables.num_tables, tables.dim
+    if tuple(dy.shape) != (T, Bcap, D) or dx.shape != dy.shape:
+        raise SlipstreamError("ss_embbag_ln_backward: dy and dx must be [T, Bcap, D]")
+    for p, name in ((gamma, "gamma"), (dgamma, "dgamma"), (dbeta, "dbeta")):
+        if p is not None and tuple(p.shape) != (T, D):
+            raise SlipstreamError(f"ss_embbag_ln_backward: {name} must be [T, D]")
+    _check(_lib.ss_embbag_ln_backward(
+        C.byref(tables.c), _dev_ptr(idx, torch.int32, "idx"), C.c_int32(Bcap), C.c_int32(L),
+        _dev_ptr(n_valid, torch.int32, "n_valid"), _dev_ptr(dy, torch.float32, "dy"),
+        _dev_ptr(gamma, torch.float32, "gamma"), _dev_ptr(mean, torch.float32, "mean"),
+        _dev_ptr(rstd, torch.float32, "rstd"), _dev_ptr(dx, torch.float32, "dx"),
+        _dev_ptr(dgamma, torch.float32, "dgamma"), _dev_ptr(dbeta, torch.float32, "dbeta"),
+        _dev_ptr(ws, torch.uint8, "ws"), C.c_size_t(0 if ws is None else ws.numel()),
+        _stream(stream)))

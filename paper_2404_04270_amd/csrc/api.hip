@@ -484,8 +484,27 @@ int32_t ss_layernorm_forward(int32_t num_tables, int32_t dim, const float *x, in
     if (!x || !y || !mean || !rstd)
         return fail(SS_ERR_INVALID_ARG, "%s: x, y, mean or rstd is NULL", who);
     if (!(eps >= 0.0f)) return fail(SS_ERR_INVALID_ARG, "%s: eps = %g", who, (double)eps);
-    return launch_layernorm_forward(num_tables, dim, x, Bcap, n_valid, gamma, beta, eps, y,
-                                    mean, rstd, static_cast<hipStream_t>(stream));
+    return launch_layernorm_forward(num_tables, dim, x, nullptr, nullptr, 1, Bcap, n_valid,
+                                    gamma, beta, eps, y, mean, rstd,
+                                    static_cast<hipStream_t>(stream));
+}
+
+int32_t ss_embbag_forward_ln(const ss_tables *tables, const int32_t *idx, int32_t Bcap,
+                             int32_t L, const int32_t *n_valid, const float *gamma,
+                             const float *beta, float eps, float *y, float *mean,
+                             float *rstd, void *stream)
+{
+    const char *who = "ss_embbag_forward_ln";
+    int32_t rc = check_tables(tables, who);
+    if (rc) return rc;
+    rc = check_batch(who, idx, Bcap, L, tables->num_tables);
+    if (rc) return rc;
+    if (!y || !mean || !rstd)
+        return fail(SS_ERR_INVALID_ARG, "%s: y, mean or rstd is NULL", who);
+    if (!(eps >= 0.0f)) return fail(SS_ERR_INVALID_ARG, "%s: eps = %g", who, (double)eps);
+    return launch_layernorm_forward(tables->num_tables, tables->dim, nullptr, tables->weights,
+                                    idx, L, Bcap, n_valid, gamma, beta, eps, y, mean, rstd,
+                                    static_cast<hipStream_t>(stream));
 }
 
 size_t ss_layernorm_backward_workspace_bytes(int32_t num_tables, int32_t dim, int32_t Bcap)
@@ -511,7 +530,31 @@ int32_t ss_layernorm_backward(int32_t num_tables, int32_t dim, const float *dy,
         rc = check_ws(who, ws, ws_bytes, layernorm_backward_ws_bytes(num_tables, dim, Bcap));
         if (rc) return rc;
     }
-    return launch_layernorm_backward(num_tables, dim, dy, x, Bcap, n_valid, gamma, mean, rstd,
+    return launch_layernorm_backward(num_tables, dim, dy, x, nullptr, nullptr, 1, Bcap, n_valid,
+                                     gamma, mean, rstd, dx, dgamma, dbeta, ws,
+                                     static_cast<hipStream_t>(stream));
+}
+
+int32_t ss_embbag_ln_backward(const ss_tables *tables, const int32_t *idx, int32_t Bcap,
+                              int32_t L, const int32_t *n_valid, const float *dy,
+                              const float *gamma, const float *mean, const float *rstd,
+                              float *dx, float *dgamma, float *dbeta, void *ws,
+                              size_t ws_bytes, void *stream)
+{
+    const char *who = "ss_embbag_ln_backward";
+    int32_t rc = check_tables(tables, who);
+    if (rc) return rc;
+    rc = check_batch(who, idx, Bcap, L, tables->num_tables);
+    if (rc) return rc;
+    if (!dy || !mean || !rstd || !dx)
+        return fail(SS_ERR_INVALID_ARG, "%s: dy, mean, rstd or dx is NULL", who);
+    if (dgamma || dbeta) {
+        rc = check_ws(who, ws, ws_bytes,
+                      layernorm_backward_ws_bytes(tables->num_tables, tables->dim, Bcap));
+        if (rc) return rc;
+    }
+    return launch_layernorm_backward(tables->num_tables, tables->dim, dy, nullptr,
+                                     tables->weights, idx, L, Bcap, n_valid, gamma, mean, rstd,
                                      dx, dgamma, dbeta, ws, static_cast<hipStream_t>(stream));
 }
 

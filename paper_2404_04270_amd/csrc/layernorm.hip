@@ -13,6 +13,12 @@
 // batch: each workgroup adds up its vectors column by column in a fixed order
 // and writes one partial row; a second kernel adds the partial rows in index
 // order, so dgamma and dbeta do not depend on scheduling.
+//
+// Both kernels also come in a form that pools the vector from the tables on the
+// fly (the sum of the bag's rows, in bag order, exactly as ss_embbag_forward
+// forms it) instead of reading it from memory: the pooled tensor is then never
+// written nor read, which at 26 x 8192 x 64 takes 109 MB out of the 273 MB the
+// two passes move.
 #include "ss_common.h"
 
 namespace ss {
@@ -43,63 +49,131 @@ __device__ __forceinline__ void load_row(const f4 *__restrict__ p, int c, int D4
     }
 }
 
+// Where a vector comes from: memory (x != nullptr), or the bag of rows it is the
+// sum of.
+struct XSource {
+    const float *x;                  // [T][Bcap][dim]
+    const float *const *weights;     // tables
+    const int32_t *idx;              // [T][Bcap][L]
+    int L;
+};
+
+// v = sum over the bag of W_t[idx[t][j][l]][:], rows added in bag order; four
+// row loads are in flight at a time.
 template <int G, int P>
+__device__ __forceinline__ void pool_row(const XSource &src, int t, int64_t vec, int c, int D4,
+                                         f4 (&v)[P])
+{
+    const auto W = as_global(reinterpret_cast<const f4 *>(src.weights[t]));
+    const int32_t *__restrict__ ip = src.idx + vec * src.L;
+    constexpr int U = 4;
+#pragma unroll
+    for (int i = 0; i < P; ++i) v[i] = f4{0.f, 0.f, 0.f, 0.f};
+    for (int l0 = 0; l0 < src.L; l0 += U) {
+        int32_t r[U];
+        f4 w[U][P];
+#pragma unroll
+        for (int u = 0; u < U; ++u) r[u] = ip[l0 + u < src.L ? l0 + u : l0];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int i = 0; i < P; ++i) {
+                const int col = c + i * G;
+                w[u][i] = W[(int64_t)r[u] * D4 + (col < D4 ? col : 0)];
+            }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (l0 + u < src.L) {
+#pragma unroll
+                for (int i = 0; i < P; ++i) v[i] = (l0 + u == 0) ? w[u][i] : v[i] + w[u][i];
+            }
+    }
+    // lanes and slots past the row loaded column 0 to stay in bounds: they hold zeros,
+    // as after load_row
+#pragma unroll
+    for (int i = 0; i < P; ++i)
+        if (c + i * G >= D4) v[i] = f4{0.f, 0.f, 0.f, 0.f};
+}
+
+template <int G, int P, bool POOL>
+__device__ __forceinline__ void fetch_x(const XSource &src, int t, int64_t vec, int c, int D4,
+                                        f4 (&v)[P])
+{
+    if (POOL)
+        pool_row<G, P>(src, t, vec, c, D4, v);
+    else
+        load_row<G, P>(reinterpret_cast<const f4 *>(src.x) + vec * D4, c, D4, v);
+}
+
+// A group takes V vectors of its tile (V = 4 while a vector is one f4 per lane):
+// all their loads are issued before the first of them is normalised, which is
+// what a pass that only streams needs most.
+template <int G, int P, bool POOL>
 __global__ __launch_bounds__(kWG) void ln_forward_kernel(
-    const float *__restrict__ x, int Bcap, const int32_t *__restrict__ n_valid,
+    XSource src, int Bcap, const int32_t *__restrict__ n_valid,
     const float *__restrict__ gamma, const float *__restrict__ beta, float eps,
-    float *__restrict__ y, float *__restrict__ mean, float *__restrict__ rstd, int D4,
+    float *y, float *__restrict__ mean, float *__restrict__ rstd, int D4,
     int tiles_per_table)
 {
-    constexpr int NG = kWG / G;
+    constexpr int NG = kWG / G, V = P == 1 ? 4 : 1;
     const int t = blockIdx.x / tiles_per_table;
     const int tile = blockIdx.x - t * tiles_per_table;
     const int n = clamp_valid(n_valid, Bcap);
     const int g = threadIdx.x / G, c = threadIdx.x % G;
-    const int j = tile * NG + g;
-    if (j >= n) return;                       // whole groups leave together
-    const int64_t vec = (int64_t)t * Bcap + j;
-    const f4 *__restrict__ xp = reinterpret_cast<const f4 *>(x) + vec * D4;
-    f4 *__restrict__ yp = reinterpret_cast<f4 *>(y) + vec * D4;
+    const int j0 = tile * NG * V + g;         // vectors j0 + k * NG
+    if (j0 >= n) return;                      // whole groups leave together
     const float inv_d = 1.0f / (float)(D4 * 4);
 
-    f4 v[P];
-    load_row<G, P>(xp, c, D4, v);
-    float s = 0.f;
+    f4 v[V][P];
 #pragma unroll
-    for (int i = 0; i < P; ++i) s += hsum(v[i]);
-    const float mu = group_sum<G>(s) * inv_d;
-    float q = 0.f;
-#pragma unroll
-    for (int i = 0; i < P; ++i) {
-        if (c + i * G < D4) {
-            v[i] = v[i] - mu;
-            q += hsum(v[i] * v[i]);
-        }
+    for (int k = 0; k < V; ++k) {
+        // vectors past n_valid fetch vector j0 again (always valid) and store nothing
+        const int j = j0 + k * NG < n ? j0 + k * NG : j0;
+        fetch_x<G, P, POOL>(src, t, (int64_t)t * Bcap + j, c, D4, v[k]);
     }
-    const float var = group_sum<G>(q) * inv_d;
-    const float rs = 1.0f / sqrtf(var + eps);
 #pragma unroll
-    for (int i = 0; i < P; ++i) {
-        const int col = c + i * G;
-        if (col < D4) {
-            f4 o = v[i] * rs;
-            if (gamma) o = o * reinterpret_cast<const f4 *>(gamma)[(int64_t)t * D4 + col];
-            if (beta) o = o + reinterpret_cast<const f4 *>(beta)[(int64_t)t * D4 + col];
-            yp[col] = o;
+    for (int k = 0; k < V; ++k) {
+        const int j = j0 + k * NG;
+        if (j >= n) break;
+        const int64_t vec = (int64_t)t * Bcap + j;
+        f4 *yp = reinterpret_cast<f4 *>(y) + vec * D4;       // may be x's own row
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < P; ++i) s += hsum(v[k][i]);
+        const float mu = group_sum<G>(s) * inv_d;
+        float q = 0.f;
+#pragma unroll
+        for (int i = 0; i < P; ++i) {
+            if (c + i * G < D4) {
+                v[k][i] = v[k][i] - mu;
+                q += hsum(v[k][i] * v[k][i]);
+            }
         }
-    }
-    if (c == 0) {
-        mean[vec] = mu;
-        rstd[vec] = rs;
+        const float var = group_sum<G>(q) * inv_d;
+        const float rs = 1.0f / sqrtf(var + eps);
+#pragma unroll
+        for (int i = 0; i < P; ++i) {
+            const int col = c + i * G;
+            if (col < D4) {
+                f4 o = v[k][i] * rs;
+                if (gamma) o = o * reinterpret_cast<const f4 *>(gamma)[(int64_t)t * D4 + col];
+                if (beta) o = o + reinterpret_cast<const f4 *>(beta)[(int64_t)t * D4 + col];
+                yp[col] = o;
+            }
+        }
+        if (c == 0) {
+            mean[vec] = mu;
+            rstd[vec] = rs;
+        }
     }
 }
 
 // Workgroup b of a table takes vectors [b * NG * kLnTiles, (b+1) * NG * kLnTiles);
 // group g takes every NG-th of them.  Partial parameter gradients: one row of
 // dim floats per workgroup for dgamma and one for dbeta.
-template <int G, int P>
+template <int G, int P, bool POOL>
 __global__ __launch_bounds__(kWG) void ln_backward_kernel(
-    const float *dy, const float *__restrict__ x, int Bcap,
+    const float *dy, XSource src, int Bcap,
     const int32_t *__restrict__ n_valid, const float *__restrict__ gamma,
     const float *__restrict__ mean, const float *__restrict__ rstd, float *dx, int D4,
     int wgs_per_table, f4 *__restrict__ part_dgamma, f4 *__restrict__ part_dbeta)
@@ -128,8 +202,8 @@ __global__ __launch_bounds__(kWG) void ln_backward_kernel(
         if (j >= n) break;                    // later vectors of this group are past n too
         const int64_t vec = (int64_t)t * Bcap + j;
         f4 xv[P], dv[P];
-        load_row<G, P>(reinterpret_cast<const f4 *>(x) + vec * D4, c, D4, xv);
         load_row<G, P>(reinterpret_cast<const f4 *>(dy) + vec * D4, c, D4, dv);
+        fetch_x<G, P, POOL>(src, t, vec, c, D4, xv);
         const float mu = mean[vec], rs = rstd[vec];
         float s1 = 0.f, s2 = 0.f;
 #pragma unroll
@@ -199,20 +273,25 @@ int backward_wgs(int dim, int Bcap)
 
 }  // namespace
 
-int32_t launch_layernorm_forward(int T, int dim, const float *x, int Bcap,
-                                 const int32_t *n_valid, const float *gamma,
-                                 const float *beta, float eps, float *y, float *mean,
-                                 float *rstd, hipStream_t s)
+int32_t launch_layernorm_forward(int T, int dim, const float *x, const float *const *weights,
+                                 const int32_t *idx, int L, int Bcap, const int32_t *n_valid,
+                                 const float *gamma, const float *beta, float eps, float *y,
+                                 float *mean, float *rstd, hipStream_t s)
 {
+    const XSource src{x, weights, idx, L};
     const int D4 = dim / 4, g = lanes_per_row(dim);
-    const int ng = kWG / g;
-    const int tiles = (Bcap + ng - 1) / ng;
+    const int per_tile = (kWG / g) * (D4 <= g ? 4 : 1);      // as V in the kernel
+    const int tiles = (Bcap + per_tile - 1) / per_tile;
     if ((int64_t)tiles * T > 0x7fffffffLL)
         return fail(SS_ERR_UNSUPPORTED, "ss_layernorm_forward: grid too large");
-    ProfScope prof("ln_forward_kernel", s);
-#define SS_LN_FWD(P_)                                                                  \
-    launch(ln_forward_kernel<G, P_>, dim3((unsigned)(tiles * T)), dim3(kWG), s, x, Bcap, \
-           n_valid, gamma, beta, eps, y, mean, rstd, D4, tiles)
+    ProfScope prof(x ? "ln_forward_kernel" : "ln_forward_pool_kernel", s);
+#define SS_LN_FWD(P_)                                                                   \
+    if (x)                                                                              \
+        launch(ln_forward_kernel<G, P_, false>, dim3((unsigned)(tiles * T)), dim3(kWG), s, \
+               src, Bcap, n_valid, gamma, beta, eps, y, mean, rstd, D4, tiles);         \
+    else                                                                                \
+        launch(ln_forward_kernel<G, P_, true>, dim3((unsigned)(tiles * T)), dim3(kWG), s, \
+               src, Bcap, n_valid, gamma, beta, eps, y, mean, rstd, D4, tiles)
     SS_DISPATCH_G(g, if constexpr (G < 64) { SS_LN_FWD(1); } else {
         if (D4 <= 64) { SS_LN_FWD(1); } else if (D4 <= 128) { SS_LN_FWD(2); } else { SS_LN_FWD(4); }
     });
@@ -225,11 +304,13 @@ size_t layernorm_backward_ws_bytes(int T, int dim, int Bcap)
     return align_up((size_t)2 * T * backward_wgs(dim, Bcap) * dim * sizeof(float), 256);
 }
 
-int32_t launch_layernorm_backward(int T, int dim, const float *dy, const float *x, int Bcap,
-                                  const int32_t *n_valid, const float *gamma,
+int32_t launch_layernorm_backward(int T, int dim, const float *dy, const float *x,
+                                  const float *const *weights, const int32_t *idx, int L,
+                                  int Bcap, const int32_t *n_valid, const float *gamma,
                                   const float *mean, const float *rstd, float *dx,
                                   float *dgamma, float *dbeta, void *ws, hipStream_t s)
 {
+    const XSource src{x, weights, idx, L};
     const int D4 = dim / 4, g = lanes_per_row(dim);
     const int wgs = backward_wgs(dim, Bcap);
     if ((int64_t)wgs * T > 0x7fffffffLL)
@@ -238,10 +319,14 @@ int32_t launch_layernorm_backward(int T, int dim, const float *dy, const float *
     f4 *pg = params ? static_cast<f4 *>(ws) : nullptr;
     f4 *pb = params ? pg + (size_t)T * wgs * D4 : nullptr;
     {
-        ProfScope prof("ln_backward_kernel", s);
-#define SS_LN_BWD(P_)                                                                  \
-    launch(ln_backward_kernel<G, P_>, dim3((unsigned)(wgs * T)), dim3(kWG), s, dy, x, Bcap, \
-           n_valid, gamma, mean, rstd, dx, D4, wgs, pg, pb)
+        ProfScope prof(x ? "ln_backward_kernel" : "ln_backward_pool_kernel", s);
+#define SS_LN_BWD(P_)                                                                   \
+    if (x)                                                                              \
+        launch(ln_backward_kernel<G, P_, false>, dim3((unsigned)(wgs * T)), dim3(kWG), s, dy, \
+               src, Bcap, n_valid, gamma, mean, rstd, dx, D4, wgs, pg, pb);             \
+    else                                                                                \
+        launch(ln_backward_kernel<G, P_, true>, dim3((unsigned)(wgs * T)), dim3(kWG), s, dy, \
+               src, Bcap, n_valid, gamma, mean, rstd, dx, D4, wgs, pg, pb)
         SS_DISPATCH_G(g, if constexpr (G < 64) { SS_LN_BWD(1); } else {
             if (D4 <= 64) { SS_LN_BWD(1); } else if (D4 <= 128) { SS_LN_BWD(2); } else { SS_LN_BWD(4); }
         });

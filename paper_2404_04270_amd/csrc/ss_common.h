@@ -131,13 +131,16 @@ size_t select_hot_ws_bytes(int T, int64_t R);
 int32_t launch_select_hot(int T, int64_t R, uint32_t *const *counts, bool top, uint32_t c,
                           uint32_t e, int32_t *const *hot_ids, int cap,
                           uint32_t *const *hot_bits, uint32_t *n_hot, void *ws, hipStream_t s);
-int32_t launch_layernorm_forward(int T, int dim, const float *x, int Bcap,
-                                 const int32_t *n_valid, const float *gamma,
-                                 const float *beta, float eps, float *y, float *mean,
-                                 float *rstd, hipStream_t s);
+// x != nullptr: vectors are read from x; x == nullptr: they are pooled from
+// weights / idx / L on the fly.
+int32_t launch_layernorm_forward(int T, int dim, const float *x, const float *const *weights,
+                                 const int32_t *idx, int L, int Bcap, const int32_t *n_valid,
+                                 const float *gamma, const float *beta, float eps, float *y,
+                                 float *mean, float *rstd, hipStream_t s);
 size_t layernorm_backward_ws_bytes(int T, int dim, int Bcap);
-int32_t launch_layernorm_backward(int T, int dim, const float *dy, const float *x, int Bcap,
-                                  const int32_t *n_valid, const float *gamma,
+int32_t launch_layernorm_backward(int T, int dim, const float *dy, const float *x,
+                                  const float *const *weights, const int32_t *idx, int L,
+                                  int Bcap, const int32_t *n_valid, const float *gamma,
                                   const float *mean, const float *rstd, float *dx,
                                   float *dgamma, float *dbeta, void *ws, hipStream_t s);
 // p[0..n) = 0 by a small kernel (a memset node would not survive graph capture)

@@ -151,3 +151,65 @@ def test_layernorm_between_forward_and_update_at_config3_shape(B, dev):
     for t in range(T):
         got = weights[t][torch.from_numpy(rows[t]).to(dev).long()].cpu().numpy()
         np.testing.assert_allclose(got, mini[t][:rows[t].size], rtol=RTOL, atol=ATOL * 35)
+
+
+@pytest.mark.parametrize("T,R,D,Bc,L,nv", [
+    (3, 1000, 16, 700, 1, None),
+    (2, 5000, 64, 1025, 1, 999),
+    (2, 3000, 128, 333, 20, 300),      # multi-hot: the bag is summed on the fly
+    (2, 500, 48, 130, 9, 77),
+    (1, 300, 260, 40, 3, None),        # two f4 per lane
+    (1, 200, 1024, 20, 2, 11),         # four f4 per lane
+    (2, 400, 16, 300, 1, 0),
+])
+def test_pooled_layernorm_in_one_pass_equals_the_two_calls(B, dev, T, R, D, Bc, L, nv):
+    """ss_embbag_forward_ln / ss_embbag_ln_backward against the separate calls
+    (bit for bit: same arithmetic on the same pooled values) and the oracle."""
+    rng = np.random.default_rng(1700 + D + L + Bc)
+    W = [rng.uniform(-0.05, 0.05, (R, D)).astype(np.float32) for _ in range(T)]
+    idx = ((rng.zipf(1.2, (T, Bc, L)) - 1) % R).astype(np.int32)
+    if nv is not None:
+        idx[:, nv:] = -1                        # bags past n_valid hold no usable index
+    n = Bc if nv is None else nv
+    gamma = rng.normal(1, 0.3, (T, D)).astype(np.float32)
+    beta = rng.normal(0, 0.3, (T, D)).astype(np.float32)
+    dy = rng.normal(0, 0.01, (T, Bc, D)).astype(np.float32)
+    eps = 1e-5
+    tb = B.Tables([dv(w, dev) for w in W])
+    idx_d, n_valid = dv(idx, dev), (None if nv is None else
+                                    torch.tensor([nv], dtype=torch.int32, device=dev))
+    g_d, b_d, dy_d = dv(gamma, dev), dv(beta, dev), dv(dy, dev)
+
+    def outputs():
+        return (torch.full((T, Bc, D), 7.0, dtype=torch.float32, device=dev),
+                torch.full((T, Bc), 7.0, dtype=torch.float32, device=dev),
+                torch.full((T, Bc), 7.0, dtype=torch.float32, device=dev))
+    # the two calls
+    x = torch.full((T, Bc, D), 7.0, dtype=torch.float32, device=dev)
+    B.ss_embbag_forward(tb, idx_d, n_valid, x)
+    y2, mean2, rstd2 = outputs()
+    B.ss_layernorm_forward(x, n_valid, g_d, b_d, eps, y2, mean2, rstd2)
+    ws = torch.empty(max(256, B.ss_layernorm_backward_workspace_bytes(T, D, Bc)),
+                     dtype=torch.uint8, device=dev)
+    dx2, dg2, db2 = (torch.full((T, Bc, D), 7.0, device=dev), torch.zeros(T, D, device=dev),
+                     torch.zeros(T, D, device=dev))
+    B.ss_layernorm_backward(dy_d, x, n_valid, g_d, mean2, rstd2, dx2, dg2, db2, ws)
+    # one pass each way
+    y1, mean1, rstd1 = outputs()
+    B.ss_embbag_forward_ln(tb, idx_d, n_valid, g_d, b_d, eps, y1, mean1, rstd1)
+    dx1, dg1, db1 = (torch.full((T, Bc, D), 7.0, device=dev), torch.zeros(T, D, device=dev),
+                     torch.zeros(T, D, device=dev))
+    B.ss_embbag_ln_backward(tb, idx_d, n_valid, dy_d, g_d, mean1, rstd1, dx1, dg1, db1, ws)
+    for a, b in ((y1, y2), (mean1, mean2), (rstd1, rstd2), (dx1, dx2), (dg1, dg2), (db1, db2)):
+        assert torch.equal(a, b)
+    # and the oracle, from its own pooled vectors
+    x_ref = oracle.embbag_forward(W, idx, nv)
+    r_y, _, _ = oracle.layernorm_forward(x_ref, gamma, beta, eps, nv)
+    r_dx, r_dg, r_db = oracle.layernorm_backward(dy, x_ref, gamma, eps, nv)
+    # rstd is ~ 1/(0.03 sqrt(L)): rounding of the pooled value is amplified by it
+    amp = 40.0
+    np.testing.assert_allclose(y1.cpu().numpy()[:, :n], r_y[:, :n], rtol=RTOL, atol=ATOL * amp)
+    np.testing.assert_allclose(dx1.cpu().numpy()[:, :n], r_dx[:, :n], rtol=RTOL, atol=ATOL * amp)
+    np.testing.assert_allclose(dg1.cpu().numpy(), r_dg, rtol=1e-4, atol=1e-5 * np.sqrt(max(n, 1)))
+    np.testing.assert_allclose(db1.cpu().numpy(), r_db, rtol=1e-4, atol=1e-6 * np.sqrt(max(n, 1)))
+    assert torch.all(y1[:, n:] == 7.0) and torch.all(dx1[:, n:] == 7.0)
