@@ -495,3 +495,72 @@ def test_snapshot_ring_compares_with_the_right_snapshot(B, dev, depth, lag):
     assert sum(int(b.sum()) for b in ref_bits) > 0
     with pytest.raises(ValueError):
         ring._slot(depth + 1)
+
+
+# ------------------------------------------------------- many small tables
+def test_every_call_with_two_thousand_tables(B, dev):
+    """Grids are laid out as tables x tiles: a model with thousands of tiny
+    tables exercises the table dimension of every launch (the limit is 65535)."""
+    rng = np.random.default_rng(800)
+    T, R, D, Bn, L, H = 2000, 37, 8, 70, 2, 5
+    W = rand_tables(rng, T, R, D)
+    idx = zipf_idx(rng, T, Bn, L, R)
+    bits = random_bits(rng, T, R, 0.2)
+    tb = B.Tables(to_dev(W, dev), bits_to_dev(bits, dev))
+    idx_d = torch.from_numpy(idx).to(dev)
+    # filter
+    alpha = T * L // 5
+    skip = torch.zeros(Bn, dtype=torch.uint8, device=dev)
+    kept = torch.zeros(Bn, dtype=torch.int32, device=dev)
+    nk = torch.zeros(1, dtype=torch.int32, device=dev)
+    idx_c = torch.zeros((T, Bn, L), dtype=torch.int32, device=dev)
+    ws_f = torch.empty(max(256, B.ss_filter_batch_workspace_bytes(T, Bn, L)),
+                       dtype=torch.uint8, device=dev)
+    B.ss_filter_batch(tb, idx_d, alpha, skip, kept, nk, idx_c, ws_f)
+    r_skip, r_kept, r_idx_c = oracle.filter_batch(R, bits, idx, alpha)
+    n = int(nk.item())
+    assert n == len(r_kept) and 0 < n < Bn
+    assert np.array_equal(skip.cpu().numpy(), r_skip)
+    assert np.array_equal(idx_c.cpu().numpy()[:, :n], r_idx_c[:, :n])
+    # forward
+    out = torch.zeros((T, Bn, D), dtype=torch.float32, device=dev)
+    B.ss_embbag_forward(tb, idx_c, nk, out)
+    ref = oracle.embbag_forward(W, r_idx_c, n)
+    np.testing.assert_allclose(out.cpu().numpy()[:, :n], ref[:, :n], rtol=RTOL, atol=ATOL)
+    # backward
+    grad = rng.normal(0, 0.01, (T, Bn, D)).astype(np.float32)
+    ws_b = torch.empty(B.ss_backward_workspace_bytes(T, Bn, L, D), dtype=torch.uint8, device=dev)
+    B.ss_embbag_backward_update(tb, idx_c, nk, torch.from_numpy(grad).to(dev), 0.05, ws_b)
+    ref_w = [w.copy() for w in W]
+    oracle.embbag_backward_update(ref_w, bits, r_idx_c, grad, 0.05, n)
+    for t in range(0, T, 97):
+        np.testing.assert_allclose(tb.weights[t].cpu().numpy(), ref_w[t], rtol=RTOL, atol=ATOL)
+    # detect
+    hot = [np.sort(rng.choice(R, H, replace=False)).astype(np.int32) for _ in range(T)]
+    hs = B.HotState(tb, to_dev(hot, dev))
+    snap = [(ref_w[t][hot[t]] + rng.normal(0, 1e-3, (H, D))).astype(np.float32) for t in range(T)]
+    for t in range(T):
+        hs.snapshot[t].copy_(torch.from_numpy(snap[t]))
+    W_now = [w.cpu().numpy() for w in tb.weights]
+    ref_bits = [b.copy() for b in bits]
+    r_sh, r_dr, r_cnt = oracle.detect_stale(W_now, ref_bits, hot, [s.copy() for s in snap],
+                                            3e-3, True)
+    B.ss_detect_stale(tb, hs, 3e-3, True)
+    got_bits = bits_from_dev(tb.bits)
+    for t in range(T):
+        if (np.abs(r_dr[t] - 3e-3) > 1e-6 * 3e-3).all():
+            assert np.array_equal(got_bits[t], ref_bits[t])
+    assert 0 < int(r_cnt.sum()) < T * H
+    # counters and hot set
+    ac = B.AccessCounters(T, R, dev)
+    B.ss_count_accesses(ac, idx_d)
+    cnt = [np.zeros(R, np.uint32) for _ in range(T)]
+    oracle.count_accesses(R, idx, cnt)
+    ids = [torch.zeros(H, dtype=torch.int32, device=dev) for _ in range(T)]
+    ws_s = torch.empty(max(256, B.ss_select_hot_workspace_bytes(T, R)), dtype=torch.uint8,
+                       device=dev)
+    B.ss_select_hot_top(ac, H, ids, None, ws_s)
+    r_ids, _ = oracle.select_hot_top(cnt, H)
+    for t in range(T):
+        assert np.array_equal(ac.counts[t].cpu().numpy().view(np.uint32), cnt[t])
+        assert np.array_equal(ids[t].cpu().numpy(), r_ids[t])
