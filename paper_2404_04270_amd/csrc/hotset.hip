@@ -118,29 +118,31 @@ __global__ __launch_bounds__(kWG) void sel_hist_kernel(
     if (v) atomicAdd(&hist[((int64_t)t * 4 + pass) * 256 + threadIdx.x], v);
 }
 
-// Largest digit d with  #(rows above d) < e <= #(rows at or above d).
+// Largest digit d with  #(rows above d) < e <= #(rows at or above d): every
+// thread owns a digit, the counts above it come from a suffix scan in LDS, and
+// the one thread whose digit satisfies the condition writes the state.
 __global__ __launch_bounds__(256) void sel_pick_kernel(SelState *__restrict__ state,
                                                         int pass,
                                                         const uint32_t *__restrict__ hist)
 {
-    __shared__ uint32_t s_h[256];
-    const int t = blockIdx.x;
-    s_h[threadIdx.x] = hist[((int64_t)t * 4 + pass) * 256 + threadIdx.x];
+    __shared__ uint32_t s_suf[256];
+    const int t = blockIdx.x, d = threadIdx.x;
+    const uint32_t h = hist[((int64_t)t * 4 + pass) * 256 + d];
+    const SelState st = state[t];
+    s_suf[d] = h;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        SelState st = state[t];
-        uint32_t above = 0;
-        int d = 255;
-        // e >= 1 and the matching rows number at least e, so the loop stops at a
-        // digit that is present; d >= 0 guards against an inconsistent histogram
-        while (d > 0 && above + s_h[d] < st.e) {
-            above += s_h[d];
-            --d;
-        }
-        st.c |= (uint32_t)d << (24 - 8 * pass);
-        st.e -= above;
-        state[t] = st;
+    // inclusive suffix sums: s_suf[d] = sum of h over digits >= d
+    for (int off = 1; off < 256; off <<= 1) {
+        const uint32_t add = d + off < 256 ? s_suf[d + off] : 0u;
+        __syncthreads();
+        s_suf[d] += add;
+        __syncthreads();
     }
+    const uint32_t at_or_above = s_suf[d], above = at_or_above - h;
+    // e >= 1 and the rows still in the race number at least e, so exactly one digit
+    // qualifies (and it is present: h > 0)
+    if (above < st.e && st.e <= at_or_above)
+        state[t] = SelState{st.c | ((uint32_t)d << (24 - 8 * pass)), st.e - above};
 }
 
 // Wavefront w of the workgroup takes rows base + (k * 4 + w) * 64 + lane in step
@@ -185,14 +187,15 @@ __global__ __launch_bounds__(kWG) void sel_count_kernel(
 }
 
 // Exclusive scan of the block totals of one table; n_hot = what the write step
-// will emit (before any cap).
-__global__ __launch_bounds__(1024) void sel_scan_kernel(
+// will emit (before any cap).  Each thread owns a contiguous piece of the
+// blocks; the 256 piece totals are scanned with wavefront shuffles.
+__global__ __launch_bounds__(kWG) void sel_scan_kernel(
     const uint2 *__restrict__ block_counts, uint2 *__restrict__ block_before, int nb,
     const SelState *__restrict__ state, uint32_t *__restrict__ n_hot)
 {
-    __shared__ uint32_t s_gt[1024], s_eq[1024];
-    const int t = blockIdx.x, tid = threadIdx.x;
-    const int per = (nb + 1023) / 1024;
+    __shared__ uint32_t s_wgt[4], s_weq[4];
+    const int t = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int per = (nb + kWG - 1) / kWG;
     const int b0 = tid * per, b1 = b0 + per < nb ? b0 + per : nb;
     const uint2 *__restrict__ bc = block_counts + (int64_t)t * nb;
     uint2 *__restrict__ bb = block_before + (int64_t)t * nb;
@@ -201,31 +204,37 @@ __global__ __launch_bounds__(1024) void sel_scan_kernel(
         gt += bc[b].x;
         eq += bc[b].y;
     }
-    s_gt[tid] = gt;
-    s_eq[tid] = eq;
-    __syncthreads();
-    // inclusive Hillis-Steele scan over the 1024 partial sums
-    for (int off = 1; off < 1024; off <<= 1) {
-        uint32_t a = 0, c = 0;
-        if (tid >= off) {
-            a = s_gt[tid - off];
-            c = s_eq[tid - off];
+    uint32_t inc_gt = gt, inc_eq = eq;                  // inclusive within the wavefront
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t a = __shfl_up(inc_gt, off), c = __shfl_up(inc_eq, off);
+        if (lane >= off) {
+            inc_gt += a;
+            inc_eq += c;
         }
-        __syncthreads();
-        s_gt[tid] += a;
-        s_eq[tid] += c;
-        __syncthreads();
     }
-    uint32_t run_gt = s_gt[tid] - gt, run_eq = s_eq[tid] - eq;
+    if (lane == 63) {
+        s_wgt[wave] = inc_gt;
+        s_weq[wave] = inc_eq;
+    }
+    __syncthreads();
+    uint32_t run_gt = inc_gt - gt, run_eq = inc_eq - eq, tot_gt = 0, tot_eq = 0;
+    for (int w = 0; w < 4; ++w) {
+        if (w < wave) {
+            run_gt += s_wgt[w];
+            run_eq += s_weq[w];
+        }
+        tot_gt += s_wgt[w];
+        tot_eq += s_weq[w];
+    }
     for (int b = b0; b < b1; ++b) {
         const uint2 v = bc[b];
         bb[b] = make_uint2(run_gt, run_eq);
         run_gt += v.x;
         run_eq += v.y;
     }
-    if (tid == 1023 && n_hot) {
+    if (tid == 0 && n_hot) {
         const uint32_t e = state[t].e;
-        n_hot[t] = s_gt[1023] + (s_eq[1023] < e ? s_eq[1023] : e);
+        n_hot[t] = tot_gt + (tot_eq < e ? tot_eq : e);
     }
 }
 
@@ -321,7 +330,7 @@ void compact(int T, int64_t R, uint32_t *const *counts, const SelLayout &y, char
     uint2 *bb = reinterpret_cast<uint2 *>(w8 + y.block_before);
     launch(sel_count_kernel, dim3(y.nb, T), dim3(kWG), s, counts, R, (const SelState *)state,
            bc, y.nb);
-    launch(sel_scan_kernel, dim3(T), dim3(1024), s, (const uint2 *)bc, bb, y.nb,
+    launch(sel_scan_kernel, dim3(T), dim3(kWG), s, (const uint2 *)bc, bb, y.nb,
            (const SelState *)state, n_hot);
     ProfScope prof("sel_write_kernel", s);
     launch(sel_write_kernel, dim3(y.nb, T), dim3(kWG), s, counts, R, (const SelState *)state,

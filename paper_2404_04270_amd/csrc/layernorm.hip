@@ -246,23 +246,41 @@ __global__ __launch_bounds__(kWG) void ln_backward_kernel(
     }
 }
 
-// out[t][:] = sum over the workgroups' partial rows, in workgroup order
+// out[t][:] = sum over the workgroups' partial rows.  One workgroup per table and
+// f4 column block: thread (part, col) adds every kParts-th partial row starting at
+// `part`, then the kParts sums of a column are added in part order; the order is
+// fixed by the shape alone.
+constexpr int kRedCols = 16;                 // f4 columns per workgroup
+constexpr int kParts = kWG / kRedCols;       // 16 partial sums per column
+
 __global__ __launch_bounds__(kWG) void ln_param_reduce_kernel(
     const f4 *__restrict__ part_dgamma, const f4 *__restrict__ part_dbeta,
     int wgs_per_table, int D4, float *__restrict__ dgamma, float *__restrict__ dbeta)
 {
+    __shared__ f4 s_g[kWG], s_b[kWG];
     const int t = blockIdx.y;
-    const int col = blockIdx.x * kWG + threadIdx.x;
-    if (col >= D4) return;
-    const f4 *__restrict__ pg = part_dgamma + (int64_t)t * wgs_per_table * D4 + col;
-    const f4 *__restrict__ pb = part_dbeta + (int64_t)t * wgs_per_table * D4 + col;
+    const int part = threadIdx.x / kRedCols;
+    const int col = blockIdx.x * kRedCols + threadIdx.x % kRedCols;
     f4 sg = f4{0.f, 0.f, 0.f, 0.f}, sb = sg;
-    for (int w = 0; w < wgs_per_table; ++w) {
-        sg = sg + pg[(int64_t)w * D4];
-        sb = sb + pb[(int64_t)w * D4];
+    if (col < D4) {
+        const f4 *__restrict__ pg = part_dgamma + (int64_t)t * wgs_per_table * D4 + col;
+        const f4 *__restrict__ pb = part_dbeta + (int64_t)t * wgs_per_table * D4 + col;
+        for (int w = part; w < wgs_per_table; w += kParts) {
+            sg = sg + pg[(int64_t)w * D4];
+            sb = sb + pb[(int64_t)w * D4];
+        }
     }
-    if (dgamma) reinterpret_cast<f4 *>(dgamma)[(int64_t)t * D4 + col] = sg;
-    if (dbeta) reinterpret_cast<f4 *>(dbeta)[(int64_t)t * D4 + col] = sb;
+    s_g[threadIdx.x] = sg;
+    s_b[threadIdx.x] = sb;
+    __syncthreads();
+    if (part == 0 && col < D4) {
+        for (int q = 1; q < kParts; ++q) {
+            sg = sg + s_g[q * kRedCols + threadIdx.x];
+            sb = sb + s_b[q * kRedCols + threadIdx.x];
+        }
+        if (dgamma) reinterpret_cast<f4 *>(dgamma)[(int64_t)t * D4 + col] = sg;
+        if (dbeta) reinterpret_cast<f4 *>(dbeta)[(int64_t)t * D4 + col] = sb;
+    }
 }
 
 int backward_wgs(int dim, int Bcap)
@@ -333,7 +351,7 @@ int32_t launch_layernorm_backward(int T, int dim, const float *dy, const float *
 #undef SS_LN_BWD
     }
     if (params)
-        launch(ln_param_reduce_kernel, dim3((D4 + kWG - 1) / kWG, T), dim3(kWG), s,
+        launch(ln_param_reduce_kernel, dim3((D4 + kRedCols - 1) / kRedCols, T), dim3(kWG), s,
                (const f4 *)pg, (const f4 *)pb, wgs, D4, dgamma, dbeta);
     return check_launch("ss_layernorm_backward");
 }
