@@ -215,3 +215,12 @@ def test_hot_set_calls_validate_on_the_host(lib):
     for kw, text in [(dict(H=-1), b"H ="), (dict(H=101), b"H ="), (dict(ids=None), b"hot_ids"),
                      (dict(ws_bytes=0), b"workspace")]:
         assert top(**kw) != 0 and text in lib.ss_last_error(), kw
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
