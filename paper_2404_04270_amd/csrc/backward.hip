@@ -502,6 +502,12 @@ int key_bits_for(int64_t rows)
     return b;
 }
 
+// Bits the global radix sort has to order.  The sentinel key of dropped and padding
+// lookups is all ones, so it must differ from every row id within these bits, or a
+// single-pass sort would file it with the last row and cut that row's run into
+// pieces: one more bit than the row ids need when rows is a power of two.
+int radix_bits_for(int64_t rows) { return key_bits_for(rows + 1); }
+
 // Strip length (lookups per lane group in the apply stage).  Short strips keep
 // the register footprint small enough for five wavefronts per SIMD; rows of 512
 // bytes and more were measured faster with 8 (fewer pieces to stitch).
@@ -525,10 +531,10 @@ void backward_first_buffers(int T, int Bcap, int L, int dim, void *ws, uint32_t 
 }
 
 // Which of the two key/payload buffers holds the sorted lists after stage 1.
-static int sorted_buffer(const Layout &y, int key_bits)
+static int sorted_buffer(const Layout &y, int64_t rows)
 {
     if (y.NP <= kLdsSortMax) return 0;
-    const int npass = (key_bits + kRsMaxBits - 1) / kRsMaxBits;
+    const int npass = (radix_bits_for(rows) + kRsMaxBits - 1) / kRsMaxBits;
     return (npass - 1) & 1;      // pass 0 writes buffer 0, then they alternate
 }
 
@@ -568,11 +574,12 @@ int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bca
         }
 #undef SS_LDS_SORT
     } else {
-        const int npass = (key_bits + kRsMaxBits - 1) / kRsMaxBits;
+        const int sort_bits = radix_bits_for(tb->rows);
+        const int npass = (sort_bits + kRsMaxBits - 1) / kRsMaxBits;
         const dim3 grid(y.tiles, T);
         int shift = 0;
         for (int pass = 0; pass < npass; ++pass) {
-            const int nb = pass_bits(key_bits, npass, pass);
+            const int nb = pass_bits(sort_bits, npass, pass);
             const int in = cur, out = pass == 0 ? 0 : 1 - cur;
             {
                 ProfScope prof("rs_hist_kernel", s);
@@ -596,7 +603,7 @@ int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bca
             shift += nb;
         }
     }
-    if (cur != sorted_buffer(y, key_bits))
+    if (cur != sorted_buffer(y, tb->rows))
         return fail(SS_ERR_HIP, "ss_embbag_backward_prepare: internal buffer mismatch");
     return check_launch("ss_embbag_backward_prepare");
 }
@@ -611,7 +618,7 @@ int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float 
                          reinterpret_cast<uint32_t *>(w8 + y.keys1)};
     uint32_t *vals[2] = {reinterpret_cast<uint32_t *>(w8 + y.vals0),
                          reinterpret_cast<uint32_t *>(w8 + y.vals1)};
-    const int cur = sorted_buffer(y, key_bits_for(tb->rows));
+    const int cur = sorted_buffer(y, tb->rows);
 
     const int g = lanes_per_row(tb->dim);
     const int ng = kApplyWG / g;

@@ -230,6 +230,9 @@ BACKWARD_CASES = [
     (2, 9000, 64, 16385, 1, None, 0.05, 1.2),   # one more: global radix sort
     (1, 5000, 32, 2048, 8, 2047, 1.0, 1.2),     # every row stale: nothing may move
     (3, 70000, 16, 2049, 1, 1, 0.0, 1.2),       # a single valid sample
+    (4, 64, 64, 1000, 20, None, 0.05, 1.2),     # global sort, rows a power of two: the
+    (1, 1024, 16, 20000, 1, None, 0.3, 1.05),   # last row id shares its low bits with
+    (2, 1 << 20, 16, 17000, 1, None, 0.2, 1.02),  # the key of dropped lookups
 ]
 
 
@@ -564,3 +567,55 @@ def test_every_call_with_two_thousand_tables(B, dev):
     for t in range(T):
         assert np.array_equal(ac.counts[t].cpu().numpy().view(np.uint32), cnt[t])
         assert np.array_equal(ids[t].cpu().numpy(), r_ids[t])
+
+
+# ------------------------------------------------------------ random shapes
+def test_random_small_shapes_through_the_whole_step(B, dev):
+    """Forty seeded random geometries (tables, rows, dim, batch, bag, stale share,
+    valid count, alpha), each run filter -> forward -> backward against the
+    oracle: ragged tiles, strips and classes of every kind in one sweep."""
+    rng = np.random.default_rng(4242)
+    for case in range(40):
+        T = int(rng.integers(1, 7))
+        R = int(rng.choice([1, 2, 31, 64, 65, 1000, 4097, 70000]))
+        D = int(rng.choice([4, 8, 16, 32, 48, 64, 128, 200, 256, 512]))
+        L = int(rng.choice([1, 1, 1, 2, 3, 7, 20]))
+        Bn = int(rng.choice([1, 2, 63, 64, 65, 255, 256, 257, 1000, 2049]))
+        if Bn * L > 20000:
+            Bn = 20000 // L
+        frac = float(rng.choice([0.0, 0.05, 0.5, 0.95]))
+        za = float(rng.choice([1.05, 1.2, 2.0]))
+        W = rand_tables(rng, T, R, D)
+        idx = zipf_idx(rng, T, Bn, L, R, za)
+        bits = random_bits(rng, T, R, frac) if frac > 0 else None
+        alpha = int(rng.choice([1, max(1, T * L // 2), T * L, T * L + 1]))
+        tag = (case, T, R, D, L, Bn, frac, za, alpha)
+        tb = B.Tables(to_dev(W, dev), None if bits is None else bits_to_dev(bits, dev))
+        idx_d = torch.from_numpy(idx).to(dev)
+        skip = torch.zeros(Bn, dtype=torch.uint8, device=dev)
+        kept = torch.zeros(Bn, dtype=torch.int32, device=dev)
+        nk = torch.zeros(1, dtype=torch.int32, device=dev)
+        idx_c = torch.full((T, Bn, L), -1, dtype=torch.int32, device=dev)
+        ws_f = torch.empty(max(256, B.ss_filter_batch_workspace_bytes(T, Bn, L)),
+                           dtype=torch.uint8, device=dev)
+        B.ss_filter_batch(tb, idx_d, alpha, skip, kept, nk, idx_c, ws_f)
+        r_skip, r_kept, r_idx_c = oracle.filter_batch(R, bits, idx, alpha)
+        n = int(nk.item())
+        assert n == len(r_kept), tag
+        assert np.array_equal(skip.cpu().numpy(), r_skip), tag
+        assert np.array_equal(idx_c.cpu().numpy()[:, :n], r_idx_c[:, :n]), tag
+        out = torch.full((T, Bn, D), 3.0, dtype=torch.float32, device=dev)
+        B.ss_embbag_forward(tb, idx_c, nk, out)
+        ref = oracle.embbag_forward(W, r_idx_c, n)
+        np.testing.assert_allclose(out.cpu().numpy()[:, :n], ref[:, :n], rtol=RTOL, atol=ATOL,
+                                   err_msg=str(tag))
+        assert torch.all(out[:, n:] == 3.0), tag
+        grad = rng.normal(0, 0.01, (T, Bn, D)).astype(np.float32)
+        ws_b = torch.empty(B.ss_backward_workspace_bytes(T, Bn, L, D), dtype=torch.uint8,
+                           device=dev)
+        B.ss_embbag_backward_update(tb, idx_c, nk, torch.from_numpy(grad).to(dev), 0.02, ws_b)
+        ref_w = [w.copy() for w in W]
+        oracle.embbag_backward_update(ref_w, bits, r_idx_c, grad, 0.02, n)
+        for t in range(T):
+            np.testing.assert_allclose(tb.weights[t].cpu().numpy(), ref_w[t], rtol=RTOL,
+                                       atol=ATOL, err_msg=str(tag))
