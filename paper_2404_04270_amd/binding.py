@@ -348,10 +348,20 @@ def ss_drop_stats(count: int, n_samples: int, population: int, n_hot_inputs: int
 class AccessCounters:
     """uint32 counters [rows] per table (int32 storage) and their pointer array."""
 
-    def __init__(self, num_tables: int, rows: int, device):
+    def __init__(self, num_tables: int, rows: int, device, counts=None):
+        """counts: existing int32 tensors [rows], one per table (e.g. views of one
+        allocation); allocated and zeroed when omitted."""
         self.rows, self.device = int(rows), device
-        self.counts = [torch.zeros(rows, dtype=torch.int32, device=device)
-                       for _ in range(num_tables)]
+        if counts is None:
+            counts = [torch.zeros(rows, dtype=torch.int32, device=device)
+                      for _ in range(num_tables)]
+        self.counts = list(counts)
+        if len(self.counts) != num_tables:
+            raise SlipstreamError("AccessCounters: one counter array per table")
+        for c in self.counts:
+            _dev_ptr(c, torch.int32, "counts")
+            if c.numel() != self.rows:
+                raise SlipstreamError("AccessCounters: each array needs `rows` entries")
         self._cptr = _ptr_table(self.counts, device)
 
 

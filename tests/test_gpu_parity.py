@@ -619,3 +619,45 @@ def test_random_small_shapes_through_the_whole_step(B, dev):
         for t in range(T):
             np.testing.assert_allclose(tb.weights[t].cpu().numpy(), ref_w[t], rtol=RTOL,
                                        atol=ATOL, err_msg=str(tag))
+
+
+def test_the_largest_number_of_tables(B, dev):
+    """65535 tables (the limit of the table dimension of a launch), two rows each:
+    filter, forward, update and the hot-set calls still address every table."""
+    rng = np.random.default_rng(810)
+    T, R, D, Bn, L = 65535, 2, 4, 3, 1
+    Wall = rng.uniform(-0.05, 0.05, (T, R, D)).astype(np.float32)
+    W = [Wall[t] for t in range(T)]
+    idx = rng.integers(0, R, (T, Bn, L)).astype(np.int32)
+    big = torch.from_numpy(Wall).to(dev)
+    tb = B.Tables([big[t] for t in range(T)])            # views of one allocation
+    idx_d = torch.from_numpy(idx).to(dev)
+    out = torch.zeros((T, Bn, D), dtype=torch.float32, device=dev)
+    B.ss_embbag_forward(tb, idx_d, None, out)
+    assert np.array_equal(out.cpu().numpy(), Wall[np.arange(T)[:, None], idx[:, :, 0]])
+    grad = rng.normal(0, 0.01, (T, Bn, D)).astype(np.float32)
+    ws_b = torch.empty(B.ss_backward_workspace_bytes(T, Bn, L, D), dtype=torch.uint8, device=dev)
+    B.ss_embbag_backward_update(tb, idx_d, None, torch.from_numpy(grad).to(dev), 0.05, ws_b)
+    ref_w = [w.copy() for w in W]
+    oracle.embbag_backward_update(ref_w, None, idx, grad, 0.05)
+    np.testing.assert_allclose(big.cpu().numpy(), np.stack(ref_w), rtol=RTOL, atol=ATOL)
+    # no bitmaps: the filter keeps everything
+    skip = torch.ones(Bn, dtype=torch.uint8, device=dev)
+    kept = torch.zeros(Bn, dtype=torch.int32, device=dev)
+    nk = torch.zeros(1, dtype=torch.int32, device=dev)
+    idx_c = torch.zeros((T, Bn, L), dtype=torch.int32, device=dev)
+    ws_f = torch.empty(max(256, B.ss_filter_batch_workspace_bytes(T, Bn, L)),
+                       dtype=torch.uint8, device=dev)
+    B.ss_filter_batch(tb, idx_d, T * L, skip, kept, nk, idx_c, ws_f)
+    assert int(nk.item()) == Bn and torch.equal(idx_c, idx_d)
+    # counters and the most accessed row of every table
+    cnt_all = torch.zeros((T, R), dtype=torch.int32, device=dev)
+    ac = B.AccessCounters(T, R, dev, counts=[cnt_all[t] for t in range(T)])
+    B.ss_count_accesses(ac, idx_d)
+    want = np.stack([np.bincount(idx[t].ravel(), minlength=R) for t in range(T)])
+    assert np.array_equal(cnt_all.cpu().numpy(), want)
+    ids_all = torch.full((T, 1), -1, dtype=torch.int32, device=dev)
+    ws_s = torch.empty(max(256, B.ss_select_hot_workspace_bytes(T, R)), dtype=torch.uint8,
+                       device=dev)
+    B.ss_select_hot_top(ac, 1, [ids_all[t] for t in range(T)], None, ws_s)
+    assert np.array_equal(ids_all.cpu().numpy()[:, 0], np.argmax(want, axis=1))
