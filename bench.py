@@ -3,7 +3,10 @@
 
 A step = filter_batch -> forward -> backward_update over one batch of seeded
 Zipf lookups, plus detect_stale on the iterations where the snapshot period
-ends.  Inputs are resident in HBM before the timed region starts.  Prints one
+ends.  By default the index-only work of the coming batches (filter_batch and the
+grouping half of the update) runs on a second stream next to the forward and
+update kernels of the current batch; --serial issues everything in order on one
+stream.  Inputs are resident in HBM before the timed region starts.  Prints one
 JSON line: whole-job samples/s ("value"), the roofline of the dominant kernel
 (algorithmic bytes per launch over its measured duration, against 8 TB/s), the
 per-kernel durations, the skip fraction, and the CPU oracle timed on this host.
@@ -39,6 +42,13 @@ def parse():
     ap.add_argument("--grouped-forward", action="store_true",
                     help="use ss_embbag_forward_grouped (forward and the grouping half of "
                          "the backward pass in one launch)")
+    ap.add_argument("--pipeline-every", type=int, default=8,
+                    help="batches between two cross-stream events of the pipelined step")
+    ap.add_argument("--serial", action="store_true",
+                    help="issue every call of a batch on one stream, one batch after the other "
+                         "(EmbeddingStep).  Default: PipelinedStep, which classifies and groups "
+                         "the coming batches on a second stream while the current one is in its "
+                         "forward and update kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates rocprofv3's "
@@ -69,6 +79,7 @@ def unique_rows_per_batch(idx_ring):
 
 def main():
     args = parse()
+    args.pipeline = not (args.serial or args.overlap or args.grouped_forward)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
               "(no collectives or sharding are part of it)" % args.gpus, file=sys.stderr)
@@ -76,7 +87,7 @@ def main():
     import torch
     from paper_2404_04270_amd import binding as B
     from paper_2404_04270_amd import workload as wl
-    from paper_2404_04270_amd.step import EmbeddingStep
+    from paper_2404_04270_amd.step import EmbeddingStep, PipelinedStep
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
@@ -92,9 +103,14 @@ def main():
     idx_d = torch.from_numpy(idx_ring).to(dev)
     n_grads = 4
     grads = [torch.from_numpy(w.grads(k)).to(dev) for k in range(n_grads)]
-    step = EmbeddingStep(weights, [torch.from_numpy(h).to(dev) for h in hot],
-                         Bn, L, cfg.lr, thr, cfg.snapshot_every, diagnostics=False,
-                         overlap=args.overlap, grouped_forward=args.grouped_forward)
+    hot_d = [torch.from_numpy(h).to(dev) for h in hot]
+    if args.pipeline:
+        step = PipelinedStep(weights, hot_d, Bn, L, cfg.lr, thr, cfg.snapshot_every,
+                             diagnostics=False, every=args.pipeline_every)
+    else:
+        step = EmbeddingStep(weights, hot_d, Bn, L, cfg.lr, thr, cfg.snapshot_every,
+                             diagnostics=False, overlap=args.overlap,
+                             grouped_forward=args.grouped_forward)
     torch.cuda.synchronize()
     setup_s = time.time() - t0
 
@@ -107,6 +123,17 @@ def main():
         del a, b
 
     def run(n, start_it):
+        if args.pipeline:
+            # exactly n batches; index work is submitted as far ahead as the ring takes
+            nxt, end = start_it, start_it + n
+            for k in range(n):
+                it = start_it + k
+                while nxt < end and step.room() > 0:
+                    step.submit(idx_d[nxt % args.ring])
+                    nxt += 1
+                step.forward()
+                step.backward(grads[it % n_grads])
+            return
         for k in range(n):
             it = start_it + k
             step.filter_forward(idx_d[it % args.ring])
@@ -170,7 +197,9 @@ def main():
         "config": {"workload": cfg.name, "tables": T, "rows": R, "dim": D, "batch": Bn,
                    "bag": L, "zipf_alpha": cfg.zipf_alpha, "threshold": thr,
                    "snapshot_every": cfg.snapshot_every, "ring": args.ring,
-                   "streams": 2 if args.overlap else 1,
+                   "streams": 2 if (args.overlap or args.pipeline) else 1,
+                   "pipelined": bool(args.pipeline),
+                   "pipeline_every": args.pipeline_every if args.pipeline else None,
                    "grouped_forward": bool(args.grouped_forward)},
         "roofline": roofline, "roofline_all": roofline_all,
         "whole_step": {"algorithmic_bytes": step_bytes,

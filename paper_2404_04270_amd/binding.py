@@ -524,3 +524,97 @@ def ss_embbag_ln_backward(tables: Tables, idx: torch.Tensor, n_valid: Optional[t
         _dev_ptr(dgamma, torch.float32, "dgamma"), _dev_ptr(dbeta, torch.float32, "dbeta"),
         _dev_ptr(ws, torch.uint8, "ws"), C.c_size_t(0 if ws is None else ws.numel()),
         _stream(stream)))
+
+
+# ---------------------------------------------------------------------------
+# Calls with their arguments marshalled once.  A training loop issues the same
+# few calls with the same buffers thousands of times; checking and converting
+# every argument each time costs more host time than the GPU needs for a step
+# at small shapes.  prepared_*() checks the buffers once and returns a function
+# that takes only what changes (a tensor or two and the stream handle).
+# ---------------------------------------------------------------------------
+def stream_handle(stream=None) -> C.c_void_p:
+    return _stream(stream)
+
+
+def prepared_filter_batch(tables: Tables, B: int, L: int, alpha: int,
+                          skip_mask: torch.Tensor, kept_ids: torch.Tensor,
+                          n_kept: torch.Tensor, idx_c: torch.Tensor, ws: torch.Tensor):
+    """call(idx, handle): idx int32 [T, B, L] contiguous on the device (not rechecked)."""
+    if skip_mask.numel() < B or kept_ids.numel() < B or n_kept.numel() < 1 \
+            or idx_c.numel() < tables.num_tables * B * L:
+        raise SlipstreamError("prepared_filter_batch: an output tensor is too small")
+    fn, tref = _lib.ss_filter_batch, C.byref(tables.c)
+    fixed = (C.c_int32(B), C.c_int32(L), C.c_int32(alpha),
+             _dev_ptr(skip_mask, torch.uint8, "skip_mask"),
+             _dev_ptr(kept_ids, torch.int32, "kept_ids"),
+             _dev_ptr(n_kept, torch.int32, "n_kept"), _dev_ptr(idx_c, torch.int32, "idx_c"),
+             _dev_ptr(ws, torch.uint8, "ws"), C.c_size_t(ws.numel()))
+
+    def call(idx: torch.Tensor, handle: C.c_void_p) -> None:
+        rc = fn(tref, C.c_void_p(idx.data_ptr()), *fixed, handle)
+        if rc:
+            _check(rc)
+    return call
+
+
+def prepared_forward(tables: Tables, idx: torch.Tensor, n_valid: Optional[torch.Tensor],
+                     out: torch.Tensor):
+    """call(handle)."""
+    Bcap, L = _idx_shape(tables, idx)
+    if out.numel() < tables.num_tables * Bcap * tables.dim:
+        raise SlipstreamError("prepared_forward: out is too small")
+    fn = _lib.ss_embbag_forward
+    args = (C.byref(tables.c), _dev_ptr(idx, torch.int32, "idx"), C.c_int32(Bcap), C.c_int32(L),
+            _dev_ptr(n_valid, torch.int32, "n_valid"), _dev_ptr(out, torch.float32, "out"))
+
+    def call(handle: C.c_void_p) -> None:
+        rc = fn(*args, handle)
+        if rc:
+            _check(rc)
+    return call
+
+
+def prepared_backward_prepare(tables: Tables, idx: torch.Tensor,
+                              n_valid: Optional[torch.Tensor], ws: torch.Tensor):
+    """call(handle)."""
+    Bcap, L = _idx_shape(tables, idx)
+    fn = _lib.ss_embbag_backward_prepare
+    args = (C.byref(tables.c), _dev_ptr(idx, torch.int32, "idx"), C.c_int32(Bcap), C.c_int32(L),
+            _dev_ptr(n_valid, torch.int32, "n_valid"), _dev_ptr(ws, torch.uint8, "ws"),
+            C.c_size_t(ws.numel()))
+
+    def call(handle: C.c_void_p) -> None:
+        rc = fn(*args, handle)
+        if rc:
+            _check(rc)
+    return call
+
+
+def prepared_backward_apply(tables: Tables, Bcap: int, L: int, lr: float, ws: torch.Tensor):
+    """call(grad, handle): grad fp32 [T, Bcap, D] contiguous on the device (not rechecked)."""
+    fn = _lib.ss_embbag_backward_apply
+    head = (C.byref(tables.c), C.c_int32(Bcap), C.c_int32(L))
+    tail = (C.c_float(lr), _dev_ptr(ws, torch.uint8, "ws"), C.c_size_t(ws.numel()))
+
+    def call(grad: torch.Tensor, handle: C.c_void_p) -> None:
+        rc = fn(*head, C.c_void_p(grad.data_ptr()), *tail, handle)
+        if rc:
+            _check(rc)
+    return call
+
+
+def prepared_backward_update(tables: Tables, idx: torch.Tensor,
+                             n_valid: Optional[torch.Tensor], lr: float, ws: torch.Tensor):
+    """call(grad, handle)."""
+    Bcap, L = _idx_shape(tables, idx)
+    fn = _lib.ss_embbag_backward_update
+    head = (C.byref(tables.c), _dev_ptr(idx, torch.int32, "idx"), C.c_int32(Bcap), C.c_int32(L),
+            _dev_ptr(n_valid, torch.int32, "n_valid"))
+    tail = (C.c_float(lr), _dev_ptr(ws, torch.uint8, "ws"), C.c_size_t(ws.numel()))
+
+    def call(grad: torch.Tensor, handle: C.c_void_p) -> None:
+        rc = fn(*head, C.c_void_p(grad.data_ptr()), *tail, handle)
+        if rc:
+            _check(rc)
+    return call

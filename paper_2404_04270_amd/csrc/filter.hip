@@ -1,13 +1,14 @@
 // ss_filter_batch: input classifier (section 3.4, Eq. 6-8) plus a stable
 // stream compaction of the kept samples.
 //
-// Kernel 1 gives each sample one lane.  It walks the sample's T*L lookups,
-// probing one bit per lookup (the bitmaps are small and stay in L2), and stops
-// as soon as the verdict is fixed: the count reached alpha, or it can no
-// longer reach it.  With alpha = T*L almost every sample is decided by its
-// first non-stale lookup, so the kernel reads little more than idx[0][*][0].
-// A wavefront ballot plus popcount yields the number of kept samples per
-// workgroup.
+// Kernel 1 gives each sample four lanes, which probe one bit per lookup (the
+// bitmaps are small and stay in L2) in chunks of 32 lookups, all loads of a
+// chunk in flight together, and stop as soon as the verdict is fixed: the count
+// reached alpha, or it can no longer reach it.  (One lane per sample probing one
+// lookup at a time is as fast while nothing is stale, but its chain of
+// dependent loads grows with every stale lookup: 21 us at 26 tables once the hot
+// rows are frozen.)  A wavefront ballot plus popcount yields the number of kept
+// samples per tile.
 // Kernel 2 runs one workgroup per (tile of 256 samples, table).  It turns the
 // per-tile counts into an offset (summing the counts before it: at most a few
 // hundred values), ranks the tile's kept samples with ballot + popcount prefix
@@ -17,12 +18,23 @@
 
 namespace ss {
 
-__global__ __launch_bounds__(kWG) void filter_flag_kernel(
+// One workgroup per tile of 256 samples, four lanes per sample.  The lookups of a
+// sample are taken 32 at a time (8 per lane): their indices are requested
+// together, then their bitmap words together, so a chunk costs two round trips
+// to memory however many of its lookups are stale.  After each chunk the four
+// lanes add up their counts and stop once the verdict is fixed.  (The first chunk
+// is four lookups only.)
+constexpr int kFlagLanes = 4;                    // lanes per sample
+constexpr int kFlagProbes = 8;                   // lookups per lane and chunk
+constexpr int kFlagWG = kWG * kFlagLanes;        // 1024 threads: 256 samples
+
+__global__ __launch_bounds__(kFlagWG) void filter_flag_kernel(
     const uint32_t *const *__restrict__ bits, const int32_t *__restrict__ idx,
     int T, int B, int L, int alpha, uint8_t *__restrict__ skip_mask,
     int32_t *__restrict__ block_kept)
 {
-    const int b = blockIdx.x * kWG + threadIdx.x;
+    const int c = threadIdx.x % kFlagLanes;
+    const int b = blockIdx.x * kWG + threadIdx.x / kFlagLanes;
     bool keep = false;
     if (b < B) {
         const int total = T * L;
@@ -32,32 +44,51 @@ __global__ __launch_bounds__(kWG) void filter_flag_kernel(
         } else if (alpha > total || bits == nullptr) {
             skip = false;
         } else {
-            int c = 0, remaining = total;
-            bool decided = false;
-            for (int t = 0; t < T && !decided; ++t) {
-                const auto bt = as_global(bits[t]);
-                const int32_t *__restrict__ ip = idx + ((int64_t)t * B + b) * L;
-                for (int l = 0; l < L; ++l) {
-                    if (bt) c += bit_set(bt, (uint32_t)ip[l]) ? 1 : 0;
-                    --remaining;
-                    if (c >= alpha || c + remaining < alpha) {
-                        decided = true;
-                        break;
-                    }
+            int count = 0;                       // stale lookups so far (all four lanes)
+            // The first chunk is one lookup per lane: while few rows are stale, four
+            // lookups settle almost every sample, and the kernel reads no more than
+            // that.  Later chunks take eight per lane.
+            int per_lane = 1;
+            for (int q0 = 0; q0 < total;) {
+                const int chunk = kFlagLanes * per_lane;
+                uint32_t row[kFlagProbes];
+                gptr<const uint32_t> bt[kFlagProbes];
+                bool live[kFlagProbes];
+#pragma unroll
+                for (int i = 0; i < kFlagProbes; ++i) {
+                    const int q = q0 + i * kFlagLanes + c;
+                    const int qq = (i < per_lane && q < total) ? q : 0;
+                    const int t = qq / L, l = qq - t * L;
+                    bt[i] = as_global(bits[t]);
+                    live[i] = i < per_lane && q < total && bt[i] != nullptr;
+                    row[i] = live[i] ? (uint32_t)idx[((int64_t)t * B + b) * L + l] : 0u;
                 }
+                uint32_t word[kFlagProbes];
+#pragma unroll
+                for (int i = 0; i < kFlagProbes; ++i) word[i] = live[i] ? bt[i][row[i] >> 5] : 0u;
+                int mine = 0;
+#pragma unroll
+                for (int i = 0; i < kFlagProbes; ++i) mine += (word[i] >> (row[i] & 31)) & 1u;
+                mine += __shfl_xor(mine, 1, kFlagLanes);
+                mine += __shfl_xor(mine, 2, kFlagLanes);
+                count += mine;
+                q0 += chunk;
+                const int remaining = total > q0 ? total - q0 : 0;
+                if (count >= alpha || count + remaining < alpha) break;
+                per_lane = kFlagProbes;
             }
-            skip = c >= alpha;
+            skip = count >= alpha;
         }
-        skip_mask[b] = skip ? 1 : 0;
-        keep = !skip;
+        if (c == 0) skip_mask[b] = skip ? 1 : 0;
+        keep = !skip && c == 0;
     }
-    __shared__ int s_cnt[kWG / 64];
+    __shared__ int s_cnt[kFlagWG / 64];
     const unsigned long long bal = __ballot(keep);
     if ((threadIdx.x & 63) == 0) s_cnt[threadIdx.x >> 6] = __popcll(bal);
     __syncthreads();
     if (threadIdx.x == 0) {
         int s = 0;
-        for (int w = 0; w < kWG / 64; ++w) s += s_cnt[w];
+        for (int w = 0; w < kFlagWG / 64; ++w) s += s_cnt[w];
         block_kept[blockIdx.x] = s;
     }
 }
@@ -138,7 +169,7 @@ int32_t launch_filter(const ss_tables *tb, const int32_t *idx, int B, int L,
     int32_t *block_kept = static_cast<int32_t *>(ws);
     {
         ProfScope prof("filter_flag_kernel", s);
-    launch(filter_flag_kernel, dim3(blocks), dim3(kWG), s,
+    launch(filter_flag_kernel, dim3(blocks), dim3(kFlagWG), s,
                        tb->stale_bits, idx, tb->num_tables, B, L, alpha,
                        skip_mask, block_kept);
     }

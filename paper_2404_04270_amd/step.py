@@ -138,3 +138,208 @@ class SnapshotRing:
         elif push:
             self.push()
         return ref
+
+
+class PipelinedStep:
+    """The same iteration with the index work of the coming batches taken off the
+    critical path.
+
+    Classifying a batch and grouping its lookups by row (ss_filter_batch,
+    ss_embbag_backward_prepare) need the indices and the stale bitmaps only, not
+    the weights: they can run while earlier batches are still in their forward
+    and update kernels, which are bound by memory traffic and leave room on the
+    compute units for these latency-bound kernels.  submit() enqueues them on a
+    second stream (default priority) into a ring of buffer sets; forward() and
+    backward() run on the stream that was current when the object was built.
+
+    An event recorded on one stream and waited for on the other costs about ten
+    microseconds of GPU time on this platform, a sixth of a whole step, so the
+    two streams do not meet once per batch: each records an event only every
+    `every` batches ("everything up to batch k is done"), and a stream waits only
+    when the batch it needs is not yet covered by an event it has waited for.
+    The ring holds 3 * every sets and the index work may run 2 * every batches
+    ahead; callers that submit less far ahead still get correct results, only with
+    more events (one is recorded on demand).
+
+    Results are those of EmbeddingStep bit for bit: the only reordering is that
+    index work of later batches runs before the update of earlier ones, which it
+    does not read.  It does read the stale bitmaps, so batches after one that ends
+    with a detect pass are held back until that pass is enqueued.
+    """
+
+    class _Set:
+        def __init__(self, T, batch, bag, D, dev):
+            self.skip_mask = torch.zeros(batch, dtype=torch.uint8, device=dev)
+            self.kept_ids = torch.zeros(batch, dtype=torch.int32, device=dev)
+            self.n_kept = torch.zeros(1, dtype=torch.int32, device=dev)
+            self.idx_c = torch.zeros(T, batch, bag, dtype=torch.int32, device=dev)
+            self.ws_filter = torch.empty(
+                max(256, B.ss_filter_batch_workspace_bytes(T, batch, bag)),
+                dtype=torch.uint8, device=dev)
+            self.ws_backward = torch.empty(
+                B.ss_backward_workspace_bytes(T, batch, bag, D), dtype=torch.uint8, device=dev)
+            self.idx = None                        # keeps the index tensor alive
+
+    class _Marks:
+        """Events of one stream, each with the last batch it covers."""
+
+        def __init__(self):
+            self.recorded = []        # (covers_up_to_batch, event), ascending
+            self.waited = -1          # the other stream knows batches <= this are done
+
+        def record(self, stream, covers: int) -> None:
+            ev = torch.cuda.Event()
+            ev.record(stream)
+            self.recorded.append((covers, ev))
+
+        def cover(self, other_stream, batch: int) -> bool:
+            """Makes other_stream wait until `batch` is done, if it does not know yet.
+            False if no recorded event covers the batch."""
+            if batch <= self.waited:
+                return True
+            for covers, ev in self.recorded:
+                if covers >= batch:
+                    other_stream.wait_event(ev)
+                    self.waited = covers
+                    self.recorded = [m for m in self.recorded if m[0] > covers]
+                    return True
+            return False
+
+    def __init__(self, weights: Sequence[torch.Tensor],
+                 hot_ids: Sequence[torch.Tensor], batch: int, bag: int,
+                 lr: float, threshold: float, snapshot_every: int,
+                 alpha: Optional[int] = None, diagnostics: bool = True, every: int = 4):
+        self.tables = B.Tables(weights)
+        self.bits = self.tables.new_bits()
+        self.hot = B.HotState(self.tables, hot_ids, diagnostics=diagnostics)
+        T, D = self.tables.num_tables, self.tables.dim
+        dev = self.tables.device
+        self.batch, self.bag = batch, bag
+        self.lr, self.threshold, self.K = float(lr), float(threshold), int(snapshot_every)
+        self.alpha = T * bag if alpha is None else int(alpha)
+        self.pooled = torch.zeros(T, batch, D, dtype=torch.float32, device=dev)
+        self.every = max(1, int(every))
+        # Three groups of `every` sets, of which two may be in use ahead of the batch
+        # being trained on: the set a new batch takes over was then last used at least
+        # `every` batches ago, which an event recorded by the training stream already
+        # covers, and the training stream finds an event of the index stream that
+        # covers the batch it starts.  With less slack each stream would have to
+        # record an extra event for almost every batch.
+        self.sets = [self._Set(T, batch, bag, D, dev) for _ in range(3 * self.every)]
+        for s in self.sets:       # arguments marshalled once (the bitmaps are attached)
+            s.filter = B.prepared_filter_batch(self.tables, batch, bag, self.alpha, s.skip_mask,
+                                               s.kept_ids, s.n_kept, s.idx_c, s.ws_filter)
+            s.group = B.prepared_backward_prepare(self.tables, s.idx_c, s.n_kept, s.ws_backward)
+            s.lookup = B.prepared_forward(self.tables, s.idx_c, s.n_kept, self.pooled)
+            s.update = B.prepared_backward_apply(self.tables, batch, bag, self.lr,
+                                                 s.ws_backward)
+        self.side = torch.cuda.Stream(device=dev)              # default priority
+        self.side_handle = B.stream_handle(self.side)
+        # the training stream is the one current now (asking torch for it on every
+        # call costs more host time than the launch it is needed for)
+        self.main = torch.cuda.current_stream(dev)
+        self.main_handle = B.stream_handle(self.main)
+        self.indexed = self._Marks()      # side stream: index work done up to batch ...
+        self.trained = self._Marks()      # main stream: update done up to batch ...
+        self.submitted = 0        # batches handed to submit()
+        self.issued = 0           # ... whose index work is enqueued
+        self.forwarded = 0        # batches whose forward() was enqueued
+        self.it = 0               # batches whose backward() was enqueued
+        self.held_back = []       # batches waiting for a detect pass before them
+        self.last_detect = -1     # last batch that ended with a detect pass
+        self.have_snapshot = False
+
+    # what the batch in flight produced
+    def _cur(self) -> "PipelinedStep._Set":
+        return self.sets[(self.forwarded - 1) % len(self.sets)]
+
+    skip_mask = property(lambda self: self._cur().skip_mask)
+    kept_ids = property(lambda self: self._cur().kept_ids)
+    n_kept = property(lambda self: self._cur().n_kept)
+    idx_c = property(lambda self: self._cur().idx_c)
+
+    def _boundary(self, k: int) -> bool:
+        return (k + 1) % self.K == 0
+
+    def _boundary_in(self, lo: int, hi: int) -> bool:
+        """Does a batch in [lo, hi) end with a snapshot / detect pass?"""
+        first = (lo // self.K + 1) * self.K - 1          # first such batch at or after lo
+        return first < hi
+
+    def room(self) -> int:
+        """How many more batches submit() takes right now."""
+        return 2 * self.every - (self.submitted - self.it)
+
+    def submit(self, idx: torch.Tensor, ready: Optional[torch.cuda.Event] = None) -> None:
+        """Index work of the next batch.
+
+        idx must stay untouched until the batch's backward() has run.  If idx is
+        still being produced on some stream, pass the event recorded after its
+        producer; without one it is taken to be complete already.
+        """
+        if self.room() <= 0:
+            raise RuntimeError("PipelinedStep: too far ahead (see room())")
+        k = self.submitted
+        self.submitted += 1
+        # a boundary batch before this one that has not had its backward() yet?
+        if self.held_back or self._boundary_in(self.it, k):
+            self.held_back.append((idx, ready))
+            return
+        self._issue(k, idx, ready)
+
+    def _issue(self, k: int, idx: torch.Tensor, ready: Optional[torch.cuda.Event]) -> None:
+        assert k == self.issued
+        s = self.sets[k % len(self.sets)]
+        if ready is not None:
+            self.side.wait_event(ready)
+        # the set's previous batch must be over, and so must the last detect pass
+        need = max(k - len(self.sets), self.last_detect)
+        if need >= 0 and not self.trained.cover(self.side, need):
+            self.trained.record(self.main, self.it - 1)
+            assert self.trained.cover(self.side, need)
+        s.idx = idx
+        s.filter(idx, self.side_handle)
+        s.group(self.side_handle)
+        self.issued += 1
+        if self.issued % self.every == 0:
+            self.indexed.record(self.side, k)
+
+    def forward(self) -> torch.Tensor:
+        """Pooled lookup of the oldest submitted batch; returns the pooled tensor."""
+        k = self.forwarded
+        if k != self.it or k >= self.issued:
+            raise RuntimeError("PipelinedStep: forward() needs a submitted batch and the "
+                               "previous batch finished")
+        s = self.sets[k % len(self.sets)]
+        if not self.indexed.cover(self.main, k):
+            self.indexed.record(self.side, self.issued - 1)      # on demand
+            assert self.indexed.cover(self.main, k)
+        self.forwarded += 1
+        s.lookup(self.main_handle)
+        return self.pooled
+
+    def backward(self, grad_c: torch.Tensor) -> bool:
+        """Update with the gradients of the kept samples; True after a detect pass."""
+        if self.forwarded != self.it + 1:
+            raise RuntimeError("PipelinedStep: backward() follows forward()")
+        s = self._cur()
+        main = self.main
+        s.update(grad_c, self.main_handle)
+        detected = False
+        k = self.it
+        if self._boundary(k):
+            if not self.have_snapshot:
+                B.ss_detect_stale(self.tables, self.hot, 0.0, True, stream=main)
+                self.have_snapshot = True
+            else:
+                B.ss_detect_stale(self.tables, self.hot, self.threshold, True, stream=main)
+                detected = True
+            self.last_detect = k
+        self.it += 1
+        if self.it % self.every == 0:
+            self.trained.record(main, k)
+        # batches that waited for this batch's detect pass
+        while self.held_back and not self._boundary_in(self.it, self.issued):
+            idx, ready = self.held_back.pop(0)
+            self._issue(self.issued, idx, ready)
+        return detected
