@@ -331,7 +331,7 @@ def test_forward_grouped_equals_forward_plus_prepare(B, dev, T, R, D, Bc, L):
 
 # ------------------------------------------------------- whole protocol
 def run_lockstep(B, dev, cfg, n_iters, threshold, n_hot=None, overlap=False,
-                 grouped_forward=False, pipelined=False):
+                 grouped_forward=False, pipelined=False, max_ahead=10 ** 9):
     """Oracle and GPU side by side; returns the number of borderline overrides."""
     from paper_2404_04270_amd.step import EmbeddingStep, PipelinedStep
     w = wl.Workload(cfg)
@@ -354,7 +354,8 @@ def run_lockstep(B, dev, cfg, n_iters, threshold, n_hot=None, overlap=False,
         g = w.grads(it)
         r = ref.step(idx[it], g)
         if pipelined:
-            while ahead < n_iters and gpu.room() > 0:    # index work as far ahead as it goes
+            # index work as far ahead as the ring (or the caller) allows
+            while ahead < n_iters and gpu.room() > 0 and ahead - it < max_ahead:
                 gpu.submit(idx_dev[ahead])
                 ahead += 1
             gpu.forward()
@@ -440,6 +441,15 @@ def test_protocol_pipelined_skips_and_multihot(B, dev):
                                threshold=2e-3)
     s = run_lockstep(B, dev, cfg, 24, cfg.threshold, pipelined=3)
     assert s["detects"] == 3
+
+
+def test_protocol_pipelined_with_little_lookahead(B, dev):
+    """A caller that submits only one batch (or three) ahead: the streams then
+    need events that were not recorded on schedule and record them on demand."""
+    cfg = wl.CONFIGS[1].scaled(snapshot_every=7)
+    for every, ahead in ((4, 1), (4, 3), (2, 2)):
+        s = run_lockstep(B, dev, cfg, 45, cfg.threshold, pipelined=every, max_ahead=ahead)
+        assert s["detects"] == 45 // 7 - 1 and s["overrides"] == 0
 
 
 def test_pipelined_step_refuses_calls_out_of_order(B, dev):
