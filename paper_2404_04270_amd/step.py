@@ -208,7 +208,7 @@ class PipelinedStep:
     def __init__(self, weights: Sequence[torch.Tensor],
                  hot_ids: Sequence[torch.Tensor], batch: int, bag: int,
                  lr: float, threshold: float, snapshot_every: int,
-                 alpha: Optional[int] = None, diagnostics: bool = True, every: int = 4):
+                 alpha: Optional[int] = None, diagnostics: bool = True, every: int = 8):
         self.tables = B.Tables(weights)
         self.bits = self.tables.new_bits()
         self.hot = B.HotState(self.tables, hot_ids, diagnostics=diagnostics)
