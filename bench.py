@@ -44,6 +44,11 @@ def parse():
                          "the backward pass in one launch)")
     ap.add_argument("--pipeline-every", type=int, default=8,
                     help="batches between two cross-stream events of the pipelined step")
+    ap.add_argument("--index-streams", type=int, default=0,
+                    help="streams the index work of the pipelined step is spread over "
+                         "(0: two when the grouping of a batch is a chain of launches too small "
+                         "to fill the chip, i.e. more than 16384 lookups per table in fewer than "
+                         "256 tiles of 2048 over all tables; else one)")
     ap.add_argument("--serial", action="store_true",
                     help="issue every call of a batch on one stream, one batch after the other "
                          "(EmbeddingStep).  Default: PipelinedStep, which classifies and groups "
@@ -104,9 +109,14 @@ def main():
     n_grads = 4
     grads = [torch.from_numpy(w.grads(k)).to(dev) for k in range(n_grads)]
     hot_d = [torch.from_numpy(h).to(dev) for h in hot]
+    if args.index_streams <= 0:
+        per_table = Bn * L
+        small_chain = per_table > 16384 and T * ((per_table + 2047) // 2048) < 256
+        args.index_streams = 2 if small_chain else 1
     if args.pipeline:
         step = PipelinedStep(weights, hot_d, Bn, L, cfg.lr, thr, cfg.snapshot_every,
-                             diagnostics=False, every=args.pipeline_every)
+                             diagnostics=False, every=args.pipeline_every,
+                             index_streams=args.index_streams)
     else:
         step = EmbeddingStep(weights, hot_d, Bn, L, cfg.lr, thr, cfg.snapshot_every,
                              diagnostics=False, overlap=args.overlap,
@@ -197,7 +207,7 @@ def main():
         "config": {"workload": cfg.name, "tables": T, "rows": R, "dim": D, "batch": Bn,
                    "bag": L, "zipf_alpha": cfg.zipf_alpha, "threshold": thr,
                    "snapshot_every": cfg.snapshot_every, "ring": args.ring,
-                   "streams": 2 if (args.overlap or args.pipeline) else 1,
+                   "streams": (1 + args.index_streams) if args.pipeline else (2 if args.overlap else 1),
                    "pipelined": bool(args.pipeline),
                    "pipeline_every": args.pipeline_every if args.pipeline else None,
                    "grouped_forward": bool(args.grouped_forward)},

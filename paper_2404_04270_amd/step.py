@@ -157,8 +157,8 @@ class PipelinedStep:
     two streams do not meet once per batch: each records an event only every
     `every` batches ("everything up to batch k is done"), and a stream waits only
     when the batch it needs is not yet covered by an event it has waited for.
-    The ring holds 3 * every sets and the index work may run 2 * every batches
-    ahead; callers that submit less far ahead still get correct results, only with
+    The ring holds 3 * every sets (times the number of index streams) and the
+    index work may run two thirds of the ring ahead; callers that submit less far ahead still get correct results, only with
     more events (one is recorded on demand).
 
     Results are those of EmbeddingStep bit for bit: the only reordering is that
@@ -181,34 +181,37 @@ class PipelinedStep:
             self.idx = None                        # keeps the index tensor alive
 
     class _Marks:
-        """Events of one stream, each with the last batch it covers."""
+        """Events of one stream, each with the last batch it covers, and what each
+        stream that waits on them already knows."""
 
         def __init__(self):
             self.recorded = []        # (covers_up_to_batch, event), ascending
-            self.waited = -1          # the other stream knows batches <= this are done
+            self.known = {}           # waiting stream (by position) -> batches <= this are done
 
         def record(self, stream, covers: int) -> None:
             ev = torch.cuda.Event()
             ev.record(stream)
             self.recorded.append((covers, ev))
+            if len(self.recorded) > 64:
+                del self.recorded[0]
 
-        def cover(self, other_stream, batch: int) -> bool:
-            """Makes other_stream wait until `batch` is done, if it does not know yet.
+        def cover(self, waiter: int, waiting_stream, batch: int) -> bool:
+            """Makes waiting_stream wait until `batch` is done, if it does not know yet.
             False if no recorded event covers the batch."""
-            if batch <= self.waited:
+            if batch <= self.known.get(waiter, -1):
                 return True
             for covers, ev in self.recorded:
                 if covers >= batch:
-                    other_stream.wait_event(ev)
-                    self.waited = covers
-                    self.recorded = [m for m in self.recorded if m[0] > covers]
+                    waiting_stream.wait_event(ev)
+                    self.known[waiter] = covers
                     return True
             return False
 
     def __init__(self, weights: Sequence[torch.Tensor],
                  hot_ids: Sequence[torch.Tensor], batch: int, bag: int,
                  lr: float, threshold: float, snapshot_every: int,
-                 alpha: Optional[int] = None, diagnostics: bool = True, every: int = 8):
+                 alpha: Optional[int] = None, diagnostics: bool = True, every: int = 8,
+                 index_streams: int = 1):
         self.tables = B.Tables(weights)
         self.bits = self.tables.new_bits()
         self.hot = B.HotState(self.tables, hot_ids, diagnostics=diagnostics)
@@ -225,7 +228,8 @@ class PipelinedStep:
         # covers, and the training stream finds an event of the index stream that
         # covers the batch it starts.  With less slack each stream would have to
         # record an extra event for almost every batch.
-        self.sets = [self._Set(T, batch, bag, D, dev) for _ in range(3 * self.every)]
+        n_side = max(1, int(index_streams))
+        self.sets = [self._Set(T, batch, bag, D, dev) for _ in range(3 * self.every * n_side)]
         for s in self.sets:       # arguments marshalled once (the bitmaps are attached)
             s.filter = B.prepared_filter_batch(self.tables, batch, bag, self.alpha, s.skip_mask,
                                                s.kept_ids, s.n_kept, s.idx_c, s.ws_filter)
@@ -233,13 +237,17 @@ class PipelinedStep:
             s.lookup = B.prepared_forward(self.tables, s.idx_c, s.n_kept, self.pooled)
             s.update = B.prepared_backward_apply(self.tables, batch, bag, self.lr,
                                                  s.ws_backward)
-        self.side = torch.cuda.Stream(device=dev)              # default priority
-        self.side_handle = B.stream_handle(self.side)
+        # Index streams (default priority); batch k goes to stream k mod n.  More than
+        # one pays when the index work of a batch takes longer than its training
+        # kernels (one huge table: the grouping is a chain of small launches).
+        self.sides = [torch.cuda.Stream(device=dev) for _ in range(max(1, int(index_streams)))]
+        self.side_handles = [B.stream_handle(st) for st in self.sides]
         # the training stream is the one current now (asking torch for it on every
         # call costs more host time than the launch it is needed for)
         self.main = torch.cuda.current_stream(dev)
         self.main_handle = B.stream_handle(self.main)
-        self.indexed = self._Marks()      # side stream: index work done up to batch ...
+        # index work of this stream's batches done up to batch ... (one per index stream)
+        self.indexed = [self._Marks() for _ in self.sides]
         self.trained = self._Marks()      # main stream: update done up to batch ...
         self.submitted = 0        # batches handed to submit()
         self.issued = 0           # ... whose index work is enqueued
@@ -268,7 +276,7 @@ class PipelinedStep:
 
     def room(self) -> int:
         """How many more batches submit() takes right now."""
-        return 2 * self.every - (self.submitted - self.it)
+        return 2 * self.every * len(self.sides) - (self.submitted - self.it)
 
     def submit(self, idx: torch.Tensor, ready: Optional[torch.cuda.Event] = None) -> None:
         """Index work of the next batch.
@@ -290,19 +298,22 @@ class PipelinedStep:
     def _issue(self, k: int, idx: torch.Tensor, ready: Optional[torch.cuda.Event]) -> None:
         assert k == self.issued
         s = self.sets[k % len(self.sets)]
+        j = k % len(self.sides)
+        side, handle = self.sides[j], self.side_handles[j]
         if ready is not None:
-            self.side.wait_event(ready)
+            side.wait_event(ready)
         # the set's previous batch must be over, and so must the last detect pass
         need = max(k - len(self.sets), self.last_detect)
-        if need >= 0 and not self.trained.cover(self.side, need):
+        if need >= 0 and not self.trained.cover(j, side, need):
             self.trained.record(self.main, self.it - 1)
-            assert self.trained.cover(self.side, need)
+            assert self.trained.cover(j, side, need)
         s.idx = idx
-        s.filter(idx, self.side_handle)
-        s.group(self.side_handle)
+        s.filter(idx, handle)
+        s.group(handle)
         self.issued += 1
-        if self.issued % self.every == 0:
-            self.indexed.record(self.side, k)
+        # every `every`-th batch of this stream
+        if (k // len(self.sides) + 1) % self.every == 0:
+            self.indexed[j].record(side, k)
 
     def forward(self) -> torch.Tensor:
         """Pooled lookup of the oldest submitted batch; returns the pooled tensor."""
@@ -311,9 +322,12 @@ class PipelinedStep:
             raise RuntimeError("PipelinedStep: forward() needs a submitted batch and the "
                                "previous batch finished")
         s = self.sets[k % len(self.sets)]
-        if not self.indexed.cover(self.main, k):
-            self.indexed.record(self.side, self.issued - 1)      # on demand
-            assert self.indexed.cover(self.main, k)
+        j = k % len(self.sides)
+        if not self.indexed[j].cover(0, self.main, k):
+            # on demand: this stream's last issued batch is the last one congruent to j
+            last = self.issued - 1 - (self.issued - 1 - j) % len(self.sides)
+            self.indexed[j].record(self.sides[j], last)
+            assert self.indexed[j].cover(0, self.main, k)
         self.forwarded += 1
         s.lookup(self.main_handle)
         return self.pooled

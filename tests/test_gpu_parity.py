@@ -331,7 +331,7 @@ def test_forward_grouped_equals_forward_plus_prepare(B, dev, T, R, D, Bc, L):
 
 # ------------------------------------------------------- whole protocol
 def run_lockstep(B, dev, cfg, n_iters, threshold, n_hot=None, overlap=False,
-                 grouped_forward=False, pipelined=False, max_ahead=10 ** 9):
+                 grouped_forward=False, pipelined=False, max_ahead=10 ** 9, index_streams=1):
     """Oracle and GPU side by side; returns the number of borderline overrides."""
     from paper_2404_04270_amd.step import EmbeddingStep, PipelinedStep
     w = wl.Workload(cfg)
@@ -341,7 +341,8 @@ def run_lockstep(B, dev, cfg, n_iters, threshold, n_hot=None, overlap=False,
     ref = OracleRun([x.copy() for x in W0], hot, cfg.lr, threshold, cfg.snapshot_every)
     if pipelined:
         gpu = PipelinedStep(to_dev(W0, dev), to_dev(hot, dev), cfg.batch, cfg.bag,
-                            cfg.lr, threshold, cfg.snapshot_every, every=pipelined)
+                            cfg.lr, threshold, cfg.snapshot_every, every=pipelined,
+                            index_streams=index_streams)
         idx_dev = torch.from_numpy(idx).to(dev)          # resident before any submit
         torch.cuda.synchronize()
         ahead = 0
@@ -450,6 +451,15 @@ def test_protocol_pipelined_with_little_lookahead(B, dev):
     for every, ahead in ((4, 1), (4, 3), (2, 2)):
         s = run_lockstep(B, dev, cfg, 45, cfg.threshold, pipelined=every, max_ahead=ahead)
         assert s["detects"] == 45 // 7 - 1 and s["overrides"] == 0
+
+
+@pytest.mark.parametrize("streams,every,ahead", [(2, 2, 10 ** 9), (3, 1, 10 ** 9), (2, 4, 3)])
+def test_protocol_pipelined_over_several_index_streams(B, dev, streams, every, ahead):
+    """Index work of consecutive batches on different streams."""
+    cfg = wl.CONFIGS[1].scaled(snapshot_every=7)
+    s = run_lockstep(B, dev, cfg, 60, cfg.threshold, pipelined=every, max_ahead=ahead,
+                     index_streams=streams)
+    assert s["detects"] == 60 // 7 - 1 and s["overrides"] == 0
 
 
 def test_pipelined_step_refuses_calls_out_of_order(B, dev):
