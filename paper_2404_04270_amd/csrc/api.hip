@@ -463,6 +463,24 @@ int32_t ss_select_hot_top(int32_t num_tables, int64_t rows, uint32_t *const *cou
                              static_cast<hipStream_t>(stream));
 }
 
+// Vectors are read and written 16 bytes at a time.
+static int32_t check_f4(const char *who, const void *p, const char *name)
+{
+    if (reinterpret_cast<uintptr_t>(p) % 16 != 0)
+        return fail(SS_ERR_INVALID_ARG, "%s: %s is not 16-byte aligned", who, name);
+    return SS_OK;
+}
+
+static int32_t check_f4_all(const char *who, const void *const *ptrs, const char *const *names,
+                            int n)
+{
+    for (int i = 0; i < n; ++i) {
+        const int32_t rc = check_f4(who, ptrs[i], names[i]);      // NULL passes
+        if (rc) return rc;
+    }
+    return SS_OK;
+}
+
 static int32_t check_ln(const char *who, int32_t T, int32_t dim, int32_t Bcap)
 {
     if (T < 1 || T > 65535)
@@ -484,6 +502,12 @@ int32_t ss_layernorm_forward(int32_t num_tables, int32_t dim, const float *x, in
     if (!x || !y || !mean || !rstd)
         return fail(SS_ERR_INVALID_ARG, "%s: x, y, mean or rstd is NULL", who);
     if (!(eps >= 0.0f)) return fail(SS_ERR_INVALID_ARG, "%s: eps = %g", who, (double)eps);
+    {
+        const void *const ptrs[] = {x, y, gamma, beta};
+        const char *const names[] = {"x", "y", "gamma", "beta"};
+        rc = check_f4_all(who, ptrs, names, 4);
+        if (rc) return rc;
+    }
     return launch_layernorm_forward(num_tables, dim, x, nullptr, nullptr, 1, Bcap, n_valid,
                                     gamma, beta, eps, y, mean, rstd,
                                     static_cast<hipStream_t>(stream));
@@ -502,6 +526,12 @@ int32_t ss_embbag_forward_ln(const ss_tables *tables, const int32_t *idx, int32_
     if (!y || !mean || !rstd)
         return fail(SS_ERR_INVALID_ARG, "%s: y, mean or rstd is NULL", who);
     if (!(eps >= 0.0f)) return fail(SS_ERR_INVALID_ARG, "%s: eps = %g", who, (double)eps);
+    {
+        const void *const ptrs[] = {y, gamma, beta};
+        const char *const names[] = {"y", "gamma", "beta"};
+        rc = check_f4_all(who, ptrs, names, 3);
+        if (rc) return rc;
+    }
     return launch_layernorm_forward(tables->num_tables, tables->dim, nullptr, tables->weights,
                                     idx, L, Bcap, n_valid, gamma, beta, eps, y, mean, rstd,
                                     static_cast<hipStream_t>(stream));
@@ -530,6 +560,12 @@ int32_t ss_layernorm_backward(int32_t num_tables, int32_t dim, const float *dy,
         rc = check_ws(who, ws, ws_bytes, layernorm_backward_ws_bytes(num_tables, dim, Bcap));
         if (rc) return rc;
     }
+    {
+        const void *const ptrs[] = {dy, x, dx, gamma, dgamma, dbeta};
+        const char *const names[] = {"dy", "x", "dx", "gamma", "dgamma", "dbeta"};
+        rc = check_f4_all(who, ptrs, names, 6);
+        if (rc) return rc;
+    }
     return launch_layernorm_backward(num_tables, dim, dy, x, nullptr, nullptr, 1, Bcap, n_valid,
                                      gamma, mean, rstd, dx, dgamma, dbeta, ws,
                                      static_cast<hipStream_t>(stream));
@@ -551,6 +587,12 @@ int32_t ss_embbag_ln_backward(const ss_tables *tables, const int32_t *idx, int32
     if (dgamma || dbeta) {
         rc = check_ws(who, ws, ws_bytes,
                       layernorm_backward_ws_bytes(tables->num_tables, tables->dim, Bcap));
+        if (rc) return rc;
+    }
+    {
+        const void *const ptrs[] = {dy, dx, gamma, dgamma, dbeta};
+        const char *const names[] = {"dy", "dx", "gamma", "dgamma", "dbeta"};
+        rc = check_f4_all(who, ptrs, names, 5);
         if (rc) return rc;
     }
     return launch_layernorm_backward(tables->num_tables, tables->dim, dy, nullptr,

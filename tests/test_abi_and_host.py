@@ -224,3 +224,33 @@ def test_bench_refuses_more_than_one_gpu():
                        capture_output=True, text=True, timeout=120)
     assert r.returncode != 0
     assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_layernorm_calls_validate_on_the_host(lib):
+    lib.ss_last_error.restype = C.c_char_p
+    lib.ss_layernorm_forward.restype = C.c_int32
+    lib.ss_layernorm_backward.restype = C.c_int32
+    lib.ss_layernorm_backward_workspace_bytes.restype = C.c_size_t
+    assert lib.ss_layernorm_backward_workspace_bytes(2, 64, 1000) % 256 == 0
+    assert lib.ss_layernorm_backward_workspace_bytes(2, 6, 1000) == 0        # dim % 4
+    ok = C.c_void_p(256)               # never dereferenced: every call below is rejected
+    odd = C.c_void_p(260)
+
+    def fwd(T=2, dim=16, x=ok, Bcap=8, gamma=None, eps=1e-5, y=ok, mean=ok, rstd=ok):
+        return lib.ss_layernorm_forward(C.c_int32(T), C.c_int32(dim), x, C.c_int32(Bcap), None,
+                                        gamma, None, C.c_float(eps), y, mean, rstd, None)
+    for kw, text in [(dict(T=0), b"num_tables"), (dict(dim=6), b"dim"), (dict(Bcap=0), b"Bcap"),
+                     (dict(x=None), b"NULL"), (dict(mean=None), b"NULL"),
+                     (dict(eps=-1.0), b"eps"), (dict(eps=float("nan")), b"eps"),
+                     (dict(x=odd), b"x is not 16-byte"), (dict(y=odd), b"y is not 16-byte"),
+                     (dict(gamma=odd), b"gamma is not 16-byte")]:
+        assert fwd(**kw) != 0 and text in lib.ss_last_error(), (kw, lib.ss_last_error())
+
+    def bwd(dy=ok, x=ok, dx=ok, dgamma=None, ws=None, ws_bytes=0):
+        return lib.ss_layernorm_backward(C.c_int32(2), C.c_int32(16), dy, x, C.c_int32(8), None,
+                                         None, ok, ok, dx, dgamma, None, ws, C.c_size_t(ws_bytes),
+                                         None)
+    for kw, text in [(dict(dy=None), b"NULL"), (dict(dx=odd), b"dx is not 16-byte"),
+                     (dict(dgamma=ok), b"workspace"),
+                     (dict(dgamma=ok, ws=ok, ws_bytes=16), b"workspace")]:
+        assert bwd(**kw) != 0 and text in lib.ss_last_error(), (kw, lib.ss_last_error())
