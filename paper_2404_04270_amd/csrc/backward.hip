@@ -223,22 +223,43 @@ __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
 // 2: that run covers the whole workgroup and goes on), and the two partial
 // sums part_lead / part_trail of dim floats each.
 // ---------------------------------------------------------------------------
-template <int G, int S>
+// Workgroups are handed to the eight XCDs in turn (block b runs on XCD b % 8),
+// and each XCD has an L2 of its own.  With several lookups per bag a gradient
+// row is read once per lookup, in the order of the sorted rows, i.e. at random:
+// the re-reads only hit L2 if the table's whole gradient block (B rows) stays
+// in it.  The first `pinned_blocks` blocks (a multiple of 8 tables) therefore
+// keep every table on one XCD; the other tables are spread as usual.
+__device__ __forceinline__ void apply_block_to_table(int b, int wgs_per_table,
+                                                     int pinned_blocks, int &t, int &wg)
+{
+    if (b < pinned_blocks) {
+        const int xcd = b & 7, j = b >> 3;
+        const int q = j / wgs_per_table;
+        t = q * 8 + xcd;
+        wg = j - q * wgs_per_table;
+    } else {
+        t = b / wgs_per_table;
+        wg = b - t * wgs_per_table;
+    }
+}
+
+template <int G, int S, bool FULL>
 __global__ __launch_bounds__(kApplyWG) void apply_kernel(
     float *const *__restrict__ weights, const uint32_t *__restrict__ keys,
     const uint32_t *__restrict__ vals, int NP, const float *__restrict__ grad,
-    int Bcap, int D4, float lr, int wgs_per_table, bool stream_grads,
-    uint32_t *__restrict__ meta_trail_row, uint8_t *__restrict__ meta_lead_state,
-    f4 *__restrict__ part_lead, f4 *__restrict__ part_trail)
+    int Bcap, int D4, float lr, int wgs_per_table, int pinned_blocks,
+    bool stream_grads, uint32_t *__restrict__ meta_trail_row,
+    uint8_t *__restrict__ meta_lead_state, f4 *__restrict__ part_lead,
+    f4 *__restrict__ part_trail)
 {
     constexpr int NG = kApplyWG / G;
+    // sum of the run that enters the strip from the left: up to its end, or
+    // over the whole strip when it goes on to the right
     __shared__ f4 s_lead[kApplyWG];
-    __shared__ f4 s_trail[kApplyWG];
-    __shared__ uint32_t s_trail_row[NG];
     __shared__ uint8_t s_lead_state[NG];
 
-    const int t = blockIdx.x / wgs_per_table;
-    const int wg = blockIdx.x - t * wgs_per_table;
+    int t, wg;
+    apply_block_to_table(blockIdx.x, wgs_per_table, pinned_blocks, t, wg);
     const int tid = threadIdx.x, g = tid / G, c = tid % G;
     const uint32_t *__restrict__ kp = keys + (int64_t)t * NP;
     const uint32_t *__restrict__ vp = vals + (int64_t)t * NP;
@@ -258,108 +279,92 @@ __global__ __launch_bounds__(kApplyWG) void apply_kernel(
     }
     const uint32_t prev = base > 0 ? kp[base - 1] : kNoPrev;
     const uint32_t next = base + S < NP ? kp[base + S] : kNoRow;
+    // only the last group looks at it: does its last run come from an earlier workgroup?
+    const uint32_t before_wg = (g == NG - 1 && wg_base > 0) ? kp[wg_base - 1] : kNoPrev;
 
-    // live: a real lookup (stale and padding lookups carry the sentinel key)
-    bool live[S], is_end[S], whole[S];
-    {
-        bool has_head = row[0] != prev;
+    // Stale and padding lookups carry the sentinel key, the largest there is:
+    // they form the last run of the table, which never ends and is never stored.
+    // Their payload is a valid sample number, so gradient loads need no guard.
+    //   end[i]: a run ends at lookup i;  put[i]: ... and it began in this strip,
+    //   so its sum is complete here and the row is updated right away.
+    const bool cont = row[0] == prev;       // the first run began before the strip
+    bool end[S], put[S];
+    bool open = cont;
 #pragma unroll
-        for (int i = 0; i < S; ++i) {
-            live[i] = row[i] != kNoRow;
-            is_end[i] = (i == S - 1) || row[i + 1] != row[i];
-            const bool ends_here = (i < S - 1) || next != row[i];
-            whole[i] = is_end[i] && has_head && ends_here;   // run inside the strip
-            if (is_end[i]) has_head = true;
-        }
+    for (int i = 0; i < S; ++i) {
+        end[i] = (i < S - 1 ? row[i + 1] : next) != row[i];
+        put[i] = end[i] && !open && row[i] != kNoRow;
+        open = open && !end[i];
     }
-    // Run that ends the strip: does it start here, does it go on?
-    bool last_has_head = row[0] != prev;
-#pragma unroll
-    for (int i = 0; i < S - 1; ++i)
-        if (row[i + 1] != row[i]) last_has_head = true;
-    const bool last_real = row[S - 1] != kNoRow;
-    const bool has_trail = last_real && last_has_head && next == row[S - 1];
-    // Run that begins the strip: is it a continuation?
-    const bool has_lead = row[0] != kNoRow && row[0] == prev;
-
-    if (c == 0) {
-        s_trail_row[g] = has_trail ? row[S - 1] : kNoRow;
-        uint8_t st = 0;
-        if (has_lead) {
-            // ends here unless the whole strip is this run and it continues
-            bool through = next == row[0];
-#pragma unroll
-            for (int i = 0; i < S - 1; ++i)
-                if (row[i + 1] != row[i]) through = false;
-            st = through ? 2 : 1;
-        }
-        s_lead_state[g] = st;
-    }
+    const bool through = open;              // one run covers the strip and goes on
+    const bool has_trail = !end[S - 1] && !through && row[S - 1] != kNoRow;
+    // 0: the strip starts a new run; 1: it starts inside a run that ends in it; 2: through
+    const uint8_t state = (cont && row[0] != kNoRow) ? (through ? 2 : 1) : 0;
+    if (c == 0) s_lead_state[g] = state;
     // workgroup-level metadata, written by every workgroup on every call
     if (g == NG - 1 && c == 0) {
-        const bool from_before = wg_base > 0 && kp[wg_base - 1] == row[S - 1];
-        const bool wg_trail = last_real && next == row[S - 1] && !from_before;
+        const bool wg_trail = row[S - 1] != kNoRow && !end[S - 1] &&
+                              before_wg != row[S - 1];
         meta_trail_row[t * wgs_per_table + wg] = wg_trail ? row[S - 1] : kNoRow;
     }
 
-    for (int cb = 0; cb < D4; cb += G) {
+    for (int cb = 0; FULL ? cb == 0 : cb < D4; cb += G) {
         const int col = cb + c;
-        const bool active = col < D4;
+        const bool active = FULL || col < D4;
         f4 gv[S], wv[S];
 #pragma unroll
         for (int i = 0; i < S; ++i)
-            if (live[i] && active) {
+        {
+            f4 v = f4{0.f, 0.f, 0.f, 0.f};
+            if (active) {
                 // with one lookup per bag a gradient row is read exactly once
-                const f4 *gp = &G4[(int64_t)smp[i] * D4 + col];
-                gv[i] = stream_grads ? __builtin_nontemporal_load(gp) : *gp;
+                const f4 *gp = &G4[(uint64_t)smp[i] * (uint32_t)D4 + (uint32_t)col];
+                v = stream_grads ? __builtin_nontemporal_load(gp) : *gp;
             }
-#pragma unroll
-        for (int i = 0; i < S; ++i)
-            if (whole[i] && live[i] && active) wv[i] = W[(int64_t)row[i] * D4 + col];
-        f4 w_trail = f4{0.f, 0.f, 0.f, 0.f};
-        if (has_trail && live[S - 1] && active)
-            w_trail = W[(int64_t)row[S - 1] * D4 + col];
-
-        f4 acc = f4{0.f, 0.f, 0.f, 0.f};
-        f4 lead_sum = acc, trail_sum = acc;
-        bool first_run = true;
+            gv[i] = v;
+        }
 #pragma unroll
         for (int i = 0; i < S; ++i) {
-            if (live[i] && active) acc = acc + gv[i];
-            if (is_end[i]) {
-                if (whole[i]) {
-                    if (live[i] && active)
-                        W[(int64_t)row[i] * D4 + col] = sgd(wv[i], acc, lr);
-                } else if (first_run && has_lead) {
-                    lead_sum = acc;
-                } else {
-                    trail_sum = acc;   // only the last run can get here
-                }
-                acc = f4{0.f, 0.f, 0.f, 0.f};
-                first_run = false;
-            }
+            f4 w = f4{0.f, 0.f, 0.f, 0.f};
+            if (put[i] && active) w = W[(uint64_t)row[i] * (uint32_t)D4 + (uint32_t)col];
+            wv[i] = w;
         }
-        s_lead[tid] = lead_sum;
-        s_trail[tid] = trail_sum;
+        f4 w_trail = f4{0.f, 0.f, 0.f, 0.f};
+        if (has_trail && active)
+            w_trail = W[(uint64_t)row[S - 1] * (uint32_t)D4 + (uint32_t)col];
+
+        f4 acc = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < S; ++i) {
+            if (active) acc = acc + gv[i];
+            if (put[i] && active)
+                W[(uint64_t)row[i] * (uint32_t)D4 + (uint32_t)col] = sgd(wv[i], acc, lr);
+            // the only other run that can end is the one that came in from the left
+            if (end[i] && !put[i]) s_lead[tid] = acc;
+            acc = end[i] ? f4{0.f, 0.f, 0.f, 0.f} : acc;
+        }
+        if (through) s_lead[tid] = acc;
         __syncthreads();
 
-        // stitch the runs that cross strip borders, in strip order
-        if (s_trail_row[g] != kNoRow) {
-            f4 sum = s_trail[tid];
+        // stitch the runs that cross strip borders, in strip order; acc is the
+        // sum of the run that leaves the strip to the right
+        if (has_trail) {
+            f4 sum = acc;
             bool ended = false;
             for (int q = g + 1; q < NG; ++q) {
                 sum = sum + s_lead[q * G + c];
                 if (s_lead_state[q] == 1) { ended = true; break; }
             }
             if (ended) {
-                if (live[S - 1] && active)
-                    W[(int64_t)row[S - 1] * D4 + col] = sgd(w_trail, sum, lr);
+                if (active)
+                    W[(uint64_t)row[S - 1] * (uint32_t)D4 + (uint32_t)col] =
+                        sgd(w_trail, sum, lr);
             } else if (active) {
                 part_trail[((int64_t)t * wgs_per_table + wg) * D4 + col] = sum;
             }
         }
         if (g == 0) {
-            uint8_t st = s_lead_state[0];
+            uint8_t st = state;
             if (st != 0) {
                 f4 sum = s_lead[c];
                 int q = 0;
@@ -373,7 +378,7 @@ __global__ __launch_bounds__(kApplyWG) void apply_kernel(
             }
             if (c == 0 && cb == 0) meta_lead_state[t * wgs_per_table + wg] = st;
         }
-        __syncthreads();
+        if (!FULL) __syncthreads();
     }
 }
 
@@ -631,17 +636,20 @@ int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float 
     const int64_t blocks = (int64_t)wgs * T;
     if (blocks > 0x7fffffffLL)
         return fail(SS_ERR_UNSUPPORTED, "ss_embbag_backward_apply: grid too large");
-#define SS_APPLY(S_)                                                             \
+    // one gradient block per L2: only worth it when gradient rows are re-read
+    const int pinned = L > 1 ? (T / 8) * 8 * wgs : 0;
+#define SS_APPLY(S_, F_)                                                           \
     SS_DISPATCH_G(g, launch(                                         \
-                         (apply_kernel<G, S_>), dim3((unsigned)blocks), dim3(kApplyWG), s, tb->weights, keys[cur], vals[cur], y.NP, grad,      \
-                         Bcap, D4, lr, wgs, L == 1, trail_row,          \
+                         (apply_kernel<G, S_, F_>), dim3((unsigned)blocks), dim3(kApplyWG), s, tb->weights, keys[cur], vals[cur], y.NP, grad,      \
+                         Bcap, D4, lr, wgs, pinned, L == 1, trail_row,  \
                          lead_state,                                               \
                          part_lead, part_trail))
     {
     ProfScope prof("apply_kernel", s);
-    if (strip == 16) { SS_APPLY(16); }
-    else if (strip == 8) { SS_APPLY(8); }
-    else { SS_APPLY(4); }
+    // a row that fills its group of lanes exactly needs no column loop and no guard
+    const bool full = D4 == g;
+    if (strip == 8) { if (full) { SS_APPLY(8, true); } else { SS_APPLY(8, false); } }
+    else { if (full) { SS_APPLY(4, true); } else { SS_APPLY(4, false); } }
     }
 #undef SS_APPLY
     ProfScope prof("fixup_kernel", s);
