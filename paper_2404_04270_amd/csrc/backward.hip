@@ -243,6 +243,49 @@ __device__ __forceinline__ void apply_block_to_table(int b, int wgs_per_table,
     }
 }
 
+// log2 of a power of two, at compile time
+constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x / 2); }
+
+// Four registers that hold "nothing yet": a value loaded under a condition needs
+// some content on the other path, and zeros would cost four moves each time.
+__device__ __forceinline__ f4 unset_f4()
+{
+    f4 v;
+    asm volatile("" : "=v"(v));
+    return v;
+}
+
+// Address of one lane's f4 of row r, given the address of that f4 in row 0.
+// When a row fills its group of lanes exactly (FULL), the row length is the
+// constant G and the 64-bit product becomes two 32-bit shifts.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+template <int G, bool FULL, typename P>
+__device__ __forceinline__ P row_ptr(P lane_base, uint32_t r, uint32_t d4)
+{
+    if (FULL) {
+        constexpr int SH = ilog2(G) + 4;
+        const u32x2 off = {r << SH, r >> (32 - SH)};
+        return (P)((gptr<char>)lane_base + __builtin_bit_cast(uint64_t, off));
+    }
+    return lane_base + (uint64_t)r * d4;
+}
+
+// The same for a gradient row.  A table's block of gradient rows is below 4 GiB
+// in the FULL variant (the host checks), so the offset fits 32 bits and the base
+// can stay in scalar registers.
+template <int G, bool FULL>
+__device__ __forceinline__ const f4 *grad_ptr(const f4 *table_base, uint32_t smp,
+                                              uint32_t col, uint32_t d4)
+{
+    if (FULL) {
+        constexpr int SH = ilog2(G) + 4;
+        const uint32_t off = (smp << SH) + (col << 4);
+        return reinterpret_cast<const f4 *>(reinterpret_cast<const char *>(table_base) +
+                                            off);
+    }
+    return table_base + ((uint64_t)smp * d4 + col);
+}
+
 template <int G, int S, bool FULL>
 __global__ __launch_bounds__(kApplyWG) void apply_kernel(
     float *const *__restrict__ weights, const uint32_t *__restrict__ keys,
@@ -268,6 +311,8 @@ __global__ __launch_bounds__(kApplyWG) void apply_kernel(
         reinterpret_cast<const f4 *>(grad) + (int64_t)t * Bcap * D4;
     const int wg_base = wg * NG * S;
     const int base = wg_base + g * S;
+    // f4 per row: a constant in the FULL variant, so that row * d4 is a shift
+    const uint32_t d4 = FULL ? (uint32_t)G : (uint32_t)D4;
 
     uint32_t row[S], smp[S];
 #pragma unroll
@@ -311,37 +356,37 @@ __global__ __launch_bounds__(kApplyWG) void apply_kernel(
     for (int cb = 0; FULL ? cb == 0 : cb < D4; cb += G) {
         const int col = cb + c;
         const bool active = FULL || col < D4;
+        const auto Wc = W + col;            // this lane's f4 of row 0
         f4 gv[S], wv[S];
 #pragma unroll
-        for (int i = 0; i < S; ++i)
-        {
-            f4 v = f4{0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < S; ++i) {
+            f4 v = unset_f4();
             if (active) {
                 // with one lookup per bag a gradient row is read exactly once
-                const f4 *gp = &G4[(uint64_t)smp[i] * (uint32_t)D4 + (uint32_t)col];
+                const f4 *gp = grad_ptr<G, FULL>(G4, smp[i], (uint32_t)col, d4);
                 v = stream_grads ? __builtin_nontemporal_load(gp) : *gp;
             }
             gv[i] = v;
         }
 #pragma unroll
         for (int i = 0; i < S; ++i) {
-            f4 w = f4{0.f, 0.f, 0.f, 0.f};
-            if (put[i] && active) w = W[(uint64_t)row[i] * (uint32_t)D4 + (uint32_t)col];
+            f4 w = unset_f4();
+            if (put[i] && active) w = *row_ptr<G, FULL>(Wc, row[i], d4);
             wv[i] = w;
         }
-        f4 w_trail = f4{0.f, 0.f, 0.f, 0.f};
-        if (has_trail && active)
-            w_trail = W[(uint64_t)row[S - 1] * (uint32_t)D4 + (uint32_t)col];
+        f4 w_trail = unset_f4();
+        if (has_trail && active) w_trail = *row_ptr<G, FULL>(Wc, row[S - 1], d4);
 
         f4 acc = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int i = 0; i < S; ++i) {
-            if (active) acc = acc + gv[i];
-            if (put[i] && active)
-                W[(uint64_t)row[i] * (uint32_t)D4 + (uint32_t)col] = sgd(wv[i], acc, lr);
-            // the only other run that can end is the one that came in from the left
-            if (end[i] && !put[i]) s_lead[tid] = acc;
+            if (active) acc = i == 0 ? gv[0] : acc + gv[i];
+            const f4 run = acc;
             acc = end[i] ? f4{0.f, 0.f, 0.f, 0.f} : acc;
+            if (put[i] && active)
+                *row_ptr<G, FULL>(Wc, row[i], d4) = sgd(wv[i], run, lr);
+            // the only other run that can end is the one that came in from the left
+            if (end[i] && !put[i]) s_lead[tid] = run;
         }
         if (through) s_lead[tid] = acc;
         __syncthreads();
@@ -357,8 +402,7 @@ __global__ __launch_bounds__(kApplyWG) void apply_kernel(
             }
             if (ended) {
                 if (active)
-                    W[(uint64_t)row[S - 1] * (uint32_t)D4 + (uint32_t)col] =
-                        sgd(w_trail, sum, lr);
+                    *row_ptr<G, FULL>(Wc, row[S - 1], d4) = sgd(w_trail, sum, lr);
             } else if (active) {
                 part_trail[((int64_t)t * wgs_per_table + wg) * D4 + col] = sum;
             }
@@ -647,7 +691,7 @@ int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float 
     {
     ProfScope prof("apply_kernel", s);
     // a row that fills its group of lanes exactly needs no column loop and no guard
-    const bool full = D4 == g;
+    const bool full = D4 == g && (int64_t)Bcap * tb->dim * 4 <= 0xFFFFFFFFLL;
     if (strip == 8) { if (full) { SS_APPLY(8, true); } else { SS_APPLY(8, false); } }
     else { if (full) { SS_APPLY(4, true); } else { SS_APPLY(4, false); } }
     }
