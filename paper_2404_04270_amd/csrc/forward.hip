@@ -28,8 +28,41 @@ __global__ __launch_bounds__(kWG) void forward_onehot_kernel(
                                 tiles_per_table);
 }
 
-// U = row loads issued together per lane.
-template <int G, int U>
+// Multi-hot bags.  All lanes of a workgroup see the same bag length, so the bag
+// is cut into pieces of 16, 8, 4, 2 and 1 lookups by scalar branches on the bits
+// of the length: every piece is straight-line code with a known number of row
+// loads, all pieces are requested before the first add (up to 31 loads in
+// flight per lane), and the rows are added in bag order.  Bags of 32 lookups or
+// more first run full rounds of 16.  FULL (a row fills its group of lanes
+// exactly) turns the row address into shifts.
+template <int N>
+__device__ __forceinline__ void fetch_ids(int32_t (&r)[N], const int32_t *__restrict__ ip)
+{
+#pragma unroll
+    for (int k = 0; k < N; ++k) r[k] = ip[k];
+}
+
+template <int N, int G, bool FULL, typename P>
+__device__ __forceinline__ void fetch_rows(f4 (&v)[N], const int32_t (&r)[N],
+                                           P lane_base, uint32_t d4)
+{
+#pragma unroll
+    for (int k = 0; k < N; ++k) v[k] = *row_ptr<G, FULL>(lane_base, (uint32_t)r[k], d4);
+}
+
+template <int N> __device__ __forceinline__ void unset_rows(f4 (&v)[N])
+{
+#pragma unroll
+    for (int k = 0; k < N; ++k) v[k] = unset_f4();
+}
+
+template <int N> __device__ __forceinline__ void add_rows(f4 &acc, const f4 (&v)[N])
+{
+#pragma unroll
+    for (int k = 0; k < N; ++k) acc = acc + v[k];
+}
+
+template <int G, bool FULL>
 __global__ __launch_bounds__(kWG) void forward_kernel(
     const float *const *__restrict__ weights, const int32_t *__restrict__ idx,
     int Bcap, int L, const int32_t *__restrict__ n_valid,
@@ -42,25 +75,43 @@ __global__ __launch_bounds__(kWG) void forward_kernel(
     const int j = tile * BAGS + (int)threadIdx.x / G;
     if (j >= n) return;
     const int c = threadIdx.x % G;
+    const uint32_t d4 = FULL ? (uint32_t)G : (uint32_t)D4;
     const auto W = as_global(reinterpret_cast<const f4 *>(weights[t]));
     const int32_t *__restrict__ ip = idx + ((int64_t)t * Bcap + j) * L;
-    f4 *__restrict__ o = reinterpret_cast<f4 *>(out) + ((int64_t)t * Bcap + j) * D4;
+    f4 *__restrict__ o = reinterpret_cast<f4 *>(out) + ((int64_t)t * Bcap + j) * d4;
 
-    for (int col = c; col < D4; col += G) {
-        // the first row initialises the sum; later rows are added in bag order
+    for (int col = c; FULL ? col == c : col < D4; col += G) {
+        const auto Wc = W + col;            // this lane's f4 of row 0
         f4 acc = f4{0.f, 0.f, 0.f, 0.f};
-        for (int l = 0; l < L; l += U) {
-            int32_t r[U];
-            f4 v[U];
-#pragma unroll
-            for (int k = 0; k < U; ++k) r[k] = ip[l + k < L ? l + k : l];
-#pragma unroll
-            for (int k = 0; k < U; ++k) v[k] = W[(int64_t)r[k] * D4 + col];
-            if (l == 0) acc = v[0];
-#pragma unroll
-            for (int k = 0; k < U; ++k)
-                if (l + k < L && (l + k) > 0) acc = acc + v[k];
+        const int32_t *__restrict__ q = ip;
+        int m = L;
+        for (; m >= 32; m -= 16, q += 16) {
+            int32_t r[16];
+            f4 a[16];
+            fetch_ids(r, q);
+            fetch_rows<16, G, FULL>(a, r, Wc, d4);
+            add_rows(acc, a);
         }
+        // loads come back in the order they were issued: all row numbers first,
+        // so that no wait for a row number also waits for rows
+        int32_t ra[16] = {}, rb[8] = {}, rd[4] = {}, re[2] = {}, rf[1] = {};
+        if (m & 16) { fetch_ids(ra, q); q += 16; }
+        if (m & 8) { fetch_ids(rb, q); q += 8; }
+        if (m & 4) { fetch_ids(rd, q); q += 4; }
+        if (m & 2) { fetch_ids(re, q); q += 2; }
+        if (m & 1) { fetch_ids(rf, q); }
+        f4 a[16], b[8], d[4], e[2], f[1];
+        unset_rows(a); unset_rows(b); unset_rows(d); unset_rows(e); unset_rows(f);
+        if (m & 16) fetch_rows<16, G, FULL>(a, ra, Wc, d4);
+        if (m & 8) fetch_rows<8, G, FULL>(b, rb, Wc, d4);
+        if (m & 4) fetch_rows<4, G, FULL>(d, rd, Wc, d4);
+        if (m & 2) fetch_rows<2, G, FULL>(e, re, Wc, d4);
+        if (m & 1) fetch_rows<1, G, FULL>(f, rf, Wc, d4);
+        if (m & 16) add_rows(acc, a);
+        if (m & 8) add_rows(acc, b);
+        if (m & 4) add_rows(acc, d);
+        if (m & 2) add_rows(acc, e);
+        if (m & 1) add_rows(acc, f);
         o[col] = acc;
     }
 }
@@ -82,15 +133,11 @@ int32_t launch_forward(const ss_tables *tb, const int32_t *idx, int Bcap, int L,
                                             tb->weights, idx, Bcap, n_valid, out,
                                             D4, tiles));
     } else {
-#define SS_FWD(U_)                                                                \
-    SS_DISPATCH_G(g, launch((forward_kernel<G, U_>),                   \
-                                        dim3((unsigned)blocks), dim3(kWG), s,   \
-                                        tb->weights, idx, Bcap, L, n_valid, out,   \
-                                        D4, tiles))
-        // enough loads per lane to cover the bag in one or two rounds
-        if (L <= 8) { SS_FWD(8); }
-        else if (L <= 16 || L > 24) { SS_FWD(16); }
-        else { SS_FWD(24); }
+#define SS_FWD(F_)                                                                \
+    SS_DISPATCH_G(g, launch((forward_kernel<G, F_>), dim3((unsigned)blocks),       \
+                            dim3(kWG), s, tb->weights, idx, Bcap, L, n_valid, out,  \
+                            D4, tiles))
+        if (D4 == g) { SS_FWD(true); } else { SS_FWD(false); }
 #undef SS_FWD
     }
     return check_launch("ss_embbag_forward");

@@ -87,6 +87,34 @@ template <typename T> __device__ __forceinline__ gptr<T> as_global(T *p)
     return (gptr<T>)p;
 }
 
+// log2 of a power of two, at compile time
+constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x / 2); }
+
+// Four registers that hold "nothing yet": a value loaded under a condition needs
+// some content on the other path, and zeros would cost four moves each time.
+__device__ __forceinline__ f4 unset_f4()
+{
+    f4 v;
+    asm volatile("" : "=v"(v));
+    return v;
+}
+
+// Address of one lane's f4 of row r, given the address of that f4 in row 0.
+// When a row fills its group of lanes exactly (FULL), the row length is the
+// constant G and the 64-bit product becomes two 32-bit shifts.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+template <int G, bool FULL, typename P>
+__device__ __forceinline__ P row_ptr(P lane_base, uint32_t r, uint32_t d4)
+{
+    if (FULL) {
+        constexpr int SH = ilog2(G) + 4;
+        const u32x2 off = {r << SH, r >> (32 - SH)};
+        return (P)((gptr<char>)lane_base + __builtin_bit_cast(uint64_t, off));
+    }
+    return lane_base + (uint64_t)r * d4;
+}
+
+
 __device__ __forceinline__ bool bit_set(gptr<const uint32_t> bits, uint32_t r)
 {
     return (bits[r >> 5] >> (r & 31)) & 1u;

@@ -77,6 +77,14 @@ def random_bits(rng, T, R, frac):
     (8, 3000, 16, 70000, 1, 65000),  # one-hot pipeline: 2-3 batches per workgroup
     (26, 5000, 64, 8269, 1, None),   # 3-4 batches per workgroup, ragged last tile
     (26, 5000, 64, 14000, 1, 13999), # 5-6 batches per workgroup
+    (2, 3000, 128, 100, 31, None),   # multi-hot: every piece size at once (16+8+4+2+1)
+    (2, 3000, 64, 90, 32, 80),       # one full round of 16, then a piece of 16
+    (1, 2000, 32, 60, 53, None),     # two full rounds, then 16+4+1
+    (2, 500, 48, 50, 40, None),      # long bags, dim not a power of two
+    (2, 900, 256, 37, 2, None),      # 64 lanes per row
+    (1, 900, 8, 300, 7, None),       # two lanes per row
+    (1, 900, 4, 300, 17, None),      # one lane per row
+    (2, 3000, 128, 64, 16, None),    # exactly one piece
 ])
 def test_forward_matches_oracle(B, dev, T, R, D, Bc, L, nv):
     rng = np.random.default_rng(100 + D + L)
@@ -233,6 +241,11 @@ BACKWARD_CASES = [
     (4, 64, 64, 1000, 20, None, 0.05, 1.2),     # global sort, rows a power of two: the
     (1, 1024, 16, 20000, 1, None, 0.3, 1.05),   # last row id shares its low bits with
     (2, 1 << 20, 16, 17000, 1, None, 0.2, 1.02),  # the key of dropped lookups
+    (2, 3000, 8, 700, 3, None, 0.1, 1.2),       # two lanes per row
+    (2, 3000, 256, 300, 5, None, 0.1, 1.2),     # 64 lanes per row, filled exactly
+    (1, 2000, 512, 200, 3, 150, 0.1, 1.2),      # two float4 per lane
+    (16, 5000, 128, 600, 20, None, 0.1, 1.2),   # multi-hot: tables pinned to XCDs
+    (11, 5000, 32, 500, 4, None, 0.1, 1.2),     # ... eight pinned, three spread
 ]
 
 
