@@ -147,9 +147,10 @@ __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
         rs_load<FIRST>(ip, L, n, kin, vin,
                        tile * kPad + wave * (kRsItems * 64) + r * 64 + lane, key[r],
                        val[r]);
-    if (FIRST) drop_stale(bt, key);
 
-    // digit offsets from the histograms; each thread owns ndig / 256 digits
+    // digit offsets from the histograms; each thread owns ndig / 256 digits.
+    // These loads depend on nothing: they go out right behind the keys, 32 tiles
+    // at a time, before anything waits for a key.
     for (int i = tid; i < NW * ndig; i += kRsThreads) s_cnt[i] = 0;
     const int dpt = (ndig + kRsThreads - 1) / kRsThreads;   // 1, 2 or 4
     uint32_t tot[4] = {0, 0, 0, 0}, early[4] = {0, 0, 0, 0}, run = 0;
@@ -157,25 +158,25 @@ __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
         const int d = tid * dpt + q;
         if (d < ndig) {
             const uint32_t *__restrict__ h = hist + (int64_t)t * tiles * kRsMaxDig + d;
-            int k = 0;
-            for (; k + 8 <= tiles; k += 8) {
-                uint32_t c[8];
+            for (int k = 0; k < tiles; k += 32) {
+                uint32_t c[32];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) c[u] = h[(int64_t)(k + u) * kRsMaxDig];
+                for (int u = 0; u < 32; ++u) {
+                    const int kk = k + u < tiles ? k + u : k;   // in range, unused
+                    c[u] = h[(int64_t)kk * kRsMaxDig];
+                }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    tot[q] += c[u];
+                for (int u = 0; u < 32; ++u) {
+                    if (k + u < tiles) tot[q] += c[u];
                     if (k + u < tile) early[q] += c[u];
                 }
-            }
-            for (; k < tiles; ++k) {
-                const uint32_t c = h[(int64_t)k * kRsMaxDig];
-                tot[q] += c;
-                if (k < tile) early[q] += c;
             }
         }
         run += tot[q];
     }
+
+    if (FIRST) drop_stale(bt, key);
+
     uint32_t incl = run;
     for (int off = 1; off < 64; off <<= 1) {
         const uint32_t up = __shfl_up(incl, off);
@@ -401,84 +402,167 @@ __global__ __launch_bounds__(kApplyWG) void apply_kernel(
 
 // ---------------------------------------------------------------------------
 // Stage 3: runs that cross workgroup borders.
+// One thread group (G lanes) per workgroup of the apply stage: it looks up
+// whether a run starts there and leaves it.  Most such runs end within the next
+// few workgroups; the group then adds the pieces itself (everything it needs is
+// requested at once: two round trips to memory in all).  The runs of the hottest
+// rows cover hundreds of workgroups: those are queued in LDS and afterwards
+// taken one at a time by all threads of the workgroup together.
 // ---------------------------------------------------------------------------
+// Pieces g, g + NG, g + 2 NG, ... of a run, added in that order, UN loads at a
+// time.  Piece 0 is the trailing sum of the workgroup the run starts in (*pt),
+// piece k the leading sum of the k-th workgroup after it (pl[k * D4]).
+template <int UN, int NG>
+__device__ __forceinline__ f4 sum_pieces(const f4 *__restrict__ pt,
+                                         const f4 *__restrict__ pl, int D4, int g,
+                                         int npieces)
+{
+    f4 sum = f4{0.f, 0.f, 0.f, 0.f};
+    for (int k0 = g; k0 < npieces; k0 += NG * UN) {
+        f4 v[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int k = k0 + u * NG;
+            const int kk = k < npieces ? k : k0;      // in range, value unused
+            v[u] = kk == 0 ? *pt : pl[(int64_t)kk * D4];
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u)
+            if (k0 + u * NG < npieces) sum = sum + v[u];
+    }
+    return sum;
+}
+
+constexpr int kNear = 8;     // a run that ends this many workgroups on is "short"
+
 template <int G>
 __global__ __launch_bounds__(kWG) void fixup_kernel(
     float *const *__restrict__ weights, int D4, float lr, int wgs_per_table,
-    const uint32_t *__restrict__ meta_trail_row,
+    int chunks_per_table, int per_chunk, const uint32_t *__restrict__ meta_trail_row,
     const uint8_t *__restrict__ meta_lead_state,
     const f4 *__restrict__ part_lead, const f4 *__restrict__ part_trail)
 {
     constexpr int NG = kWG / G;
+    __shared__ uint8_t s_state[kWG];     // lead states of the kWG workgroups after the first
+    __shared__ int s_long[NG];           // queue of long runs: workgroup they start in
+    __shared__ uint32_t s_long_row[NG];  // ... and their row
+    __shared__ int s_nlong;
     __shared__ int s_end;
     __shared__ f4 s_part[kWG];
-    const int t = blockIdx.x / wgs_per_table;
-    const int wg = blockIdx.x - t * wgs_per_table;
+    const int t = blockIdx.x / chunks_per_table;
+    const int chunk = blockIdx.x - t * chunks_per_table;
     const int tid = threadIdx.x, g = tid / G, c = tid % G;
+    // per_chunk = NG: every group checks a workgroup of the apply stage;
+    // per_chunk = 1: only the first does (for launches so small that one
+    // workgroup per run costs nothing and spares a long run the wait for short ones)
+    const int wg_first = chunk * per_chunk;
+    const int wg = wg_first + g;              // the apply workgroup this group checks
     const uint8_t *__restrict__ ls = meta_lead_state + (int64_t)t * wgs_per_table;
-    // Both loads are issued before either is looked at, and the row itself is
-    // fetched before the pieces are: this kernel is a chain of dependent round
-    // trips to memory and little else, so every link taken out counts.
-    const uint32_t row = meta_trail_row[t * wgs_per_table + wg];
-    const int q0 = wg + 1 + tid;
-    const uint8_t ls0 = q0 < wgs_per_table ? ls[q0] : (uint8_t)2;
-    if (row == kNoRow) return;
-
-    const auto W = as_global(reinterpret_cast<f4 *>(weights[t]));
-    f4 w0 = f4{0.f, 0.f, 0.f, 0.f};
-    if (g == 0 && c < D4) w0 = W[(int64_t)row * D4 + c];
-
-    // the run ends in the first later workgroup whose leading run stops there
-    if (tid == 0) s_end = 0x7fffffff;
-    __syncthreads();
-    int end = 0x7fffffff;
-    for (int b0 = wg + 1; b0 < wgs_per_table; b0 += kWG) {
-        const int q = b0 + tid;
-        const uint8_t st = b0 == wg + 1 ? ls0 : (q < wgs_per_table ? ls[q] : (uint8_t)2);
-        if (q < wgs_per_table && st != 2) atomicMin(&s_end, q);
-        __syncthreads();
-        end = s_end;
-        __syncthreads();
-        if (end != 0x7fffffff) break;
-    }
-    if (end == 0x7fffffff) return;   // cannot happen for a sorted list
-
-    // pieces: trail(wg), lead(wg+1), ..., lead(end); group g sums every NG-th
-    const int npieces = end - wg + 1;
     const f4 *__restrict__ PL = part_lead + (int64_t)t * wgs_per_table * D4;
     const f4 *__restrict__ PT = part_trail + (int64_t)t * wgs_per_table * D4;
-    for (int cb = 0; cb < D4; cb += G) {
-        const int col = cb + c;
-        const bool active = col < D4;
-        f4 sum = f4{0.f, 0.f, 0.f, 0.f};
-        if (active) {
-            // a long run has hundreds of pieces: fetch eight at a time, then add
-            // them in piece order (the order of the sum is part of the result)
-            constexpr int UN = 8;
-            for (int k0 = g; k0 < npieces; k0 += NG * UN) {
-                f4 v[UN];
+    const auto W = as_global(reinterpret_cast<f4 *>(weights[t]));
+
+    // One round trip: the row of the run that leaves each workgroup, and the lead
+    // states of the next kWG workgroups (enough to see where nearly every run ends).
+    const uint32_t row = (g < per_chunk && wg < wgs_per_table)
+                             ? meta_trail_row[t * wgs_per_table + wg]
+                             : kNoRow;
+    {
+        const int q = wg_first + 1 + tid;
+        s_state[tid] = q < wgs_per_table ? ls[q] : (uint8_t)2;
+    }
+    if (tid == 0) s_nlong = 0;
+    __syncthreads();
+
+    // the run ends in the first later workgroup whose leading run stops there
+    int last = -1;
 #pragma unroll
-                for (int u = 0; u < UN; ++u) {
-                    const int k = k0 + u * NG;
-                    const int kk = k < npieces ? k : k0;      // in range, value unused
-                    v[u] = kk == 0 ? PT[(int64_t)wg * D4 + col]
-                                   : PL[(int64_t)(wg + kk) * D4 + col];
+    for (int u = kNear - 1; u >= 0; --u)
+        if (g + u < kWG && s_state[g + u] != 2) last = u;
+    const bool mine = row != kNoRow;
+    const bool near = mine && last >= 0;
+    if (mine && !near && c == 0) {
+        const int slot = atomicAdd(&s_nlong, 1);
+        s_long[slot] = wg;
+        s_long_row[slot] = row;
+    }
+
+    if (near) {
+        for (int cb = 0; cb < D4; cb += G) {
+            const int col = cb + c;
+            if (col < D4) {
+                f4 v[kNear];
+                const f4 tr = PT[(int64_t)wg * D4 + col];
+#pragma unroll
+                for (int u = 0; u < kNear; ++u) {
+                    f4 x = f4{0.f, 0.f, 0.f, 0.f};
+                    if (u <= last) x = PL[(int64_t)(wg + 1 + u) * D4 + col];
+                    v[u] = x;
                 }
+                const int64_t o = (int64_t)row * D4 + col;
+                const f4 w0 = W[o];
+                f4 sum = tr;
 #pragma unroll
-                for (int u = 0; u < UN; ++u)
-                    if (k0 + u * NG < npieces) sum = sum + v[u];
+                for (int u = 0; u < kNear; ++u)
+                    if (u <= last) sum = sum + v[u];
+                W[o] = sgd(w0, sum, lr);
             }
         }
-        s_part[tid] = sum;
+    }
+    __syncthreads();
+
+    // long runs: all threads together, one run after the other
+    const int nlong = s_nlong;
+    for (int i = 0; i < nlong; ++i) {
+        const int w0g = s_long[i];
+        const uint32_t lrow = s_long_row[i];
+        if (tid == 0) s_end = 0x7fffffff;
         __syncthreads();
-        if (g == 0 && active) {
-            f4 tot = s_part[c];
-            const int used = npieces < NG ? npieces : NG;
-            for (int q = 1; q < used; ++q) tot = tot + s_part[q * G + c];
-            const int64_t o = (int64_t)row * D4 + col;
-            W[o] = sgd(cb == 0 ? w0 : W[o], tot, lr);
+        // first among the states already in LDS ...
+        {
+            const int k = w0g - wg_first + tid;
+            if (k < kWG && s_state[k] != 2) atomicMin(&s_end, w0g + 1 + tid);
         }
         __syncthreads();
+        int end = s_end;
+        __syncthreads();
+        // ... then, for the few runs longer than that, in memory
+        for (int b0 = wg_first + 1 + kWG; end == 0x7fffffff && b0 < wgs_per_table;
+             b0 += kWG) {
+            const int q = b0 + tid;
+            const uint8_t s2 = q < wgs_per_table ? ls[q] : (uint8_t)2;
+            if (q < wgs_per_table && s2 != 2) atomicMin(&s_end, q);
+            __syncthreads();
+            end = s_end;
+            __syncthreads();
+        }
+        if (end == 0x7fffffff) continue;   // cannot happen for a sorted list
+
+        // pieces: trail(w0g), lead(w0g + 1), ..., lead(end); group g adds every NG-th
+        const int npieces = end - w0g + 1;
+        for (int cb = 0; cb < D4; cb += G) {
+            const int col = cb + c;
+            const bool active = col < D4;
+            const int64_t o = (int64_t)lrow * D4 + col;
+            f4 w0 = f4{0.f, 0.f, 0.f, 0.f};
+            if (g == 0 && active) w0 = W[o];
+            f4 sum = f4{0.f, 0.f, 0.f, 0.f};
+            if (active) {
+                const f4 *pt = PT + (int64_t)w0g * D4 + col;
+                const f4 *pl = PL + (int64_t)w0g * D4 + col;
+                if (npieces <= 8 * NG) sum = sum_pieces<8, NG>(pt, pl, D4, g, npieces);
+                else sum = sum_pieces<16, NG>(pt, pl, D4, g, npieces);
+            }
+            s_part[tid] = sum;
+            __syncthreads();
+            if (g == 0 && active) {
+                f4 tot = s_part[c];
+                const int used = npieces < NG ? npieces : NG;
+                for (int q = 1; q < used; ++q) tot = tot + s_part[q * G + c];
+                W[o] = sgd(w0, tot, lr);
+            }
+            __syncthreads();
+        }
     }
 }
 
@@ -670,10 +754,13 @@ int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float 
     }
 #undef SS_APPLY
     ProfScope prof("fixup_kernel", s);
-    SS_DISPATCH_G(g, launch(fixup_kernel<G>, dim3((unsigned)blocks),
+    // apply workgroups looked at per workgroup of this launch
+    const int per_chunk = (int64_t)wgs * T <= 2048 ? 1 : kWG / g;
+    const int chunks = (wgs + per_chunk - 1) / per_chunk;
+    SS_DISPATCH_G(g, launch(fixup_kernel<G>, dim3((unsigned)(chunks * T)),
                                         dim3(kWG), s, tb->weights, D4, lr, wgs,
-                                        trail_row, lead_state, part_lead,
-                                        part_trail));
+                                        chunks, per_chunk, trail_row, lead_state,
+                                        part_lead, part_trail));
     return check_launch("ss_embbag_backward_apply");
 }
 
