@@ -147,36 +147,61 @@ __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
         rs_load<FIRST>(ip, L, n, kin, vin,
                        tile * kPad + wave * (kRsItems * 64) + r * 64 + lane, key[r],
                        val[r]);
+    if (FIRST) drop_stale(bt, key);
 
-    // digit offsets from the histograms; each thread owns ndig / 256 digits.
-    // These loads depend on nothing: they go out right behind the keys, 32 tiles
-    // at a time, before anything waits for a key.
+    // Digit offsets from the histograms; each thread owns ndig / 256 digits.
+    // This kernel runs about one wavefront per SIMD, so what it costs is the
+    // number of instructions a wavefront executes one after the other, not
+    // bytes: the loops over a thread's digits are unrolled (their sums stay in
+    // fixed registers), and a tile's histogram is addressed as (base common to
+    // all lanes) + (this lane's digit), which keeps the base in scalar registers.
     for (int i = tid; i < NW * ndig; i += kRsThreads) s_cnt[i] = 0;
     const int dpt = (ndig + kRsThreads - 1) / kRsThreads;   // 1, 2 or 4
     uint32_t tot[4] = {0, 0, 0, 0}, early[4] = {0, 0, 0, 0}, run = 0;
-    for (int q = 0; q < dpt; ++q) {
+    const uint32_t *__restrict__ ht = hist + (int64_t)t * tiles * kRsMaxDig;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
         const int d = tid * dpt + q;
-        if (d < ndig) {
-            const uint32_t *__restrict__ h = hist + (int64_t)t * tiles * kRsMaxDig + d;
-            for (int k = 0; k < tiles; k += 32) {
+        if (q < dpt && d < ndig) {
+            uint32_t all = 0, before = 0;
+            int k = 0;
+            // each round of loads is a trip to memory: 32 tiles per round first
+            for (; k + 32 <= tiles; k += 32) {
                 uint32_t c[32];
 #pragma unroll
-                for (int u = 0; u < 32; ++u) {
-                    const int kk = k + u < tiles ? k + u : k;   // in range, unused
-                    c[u] = h[(int64_t)kk * kRsMaxDig];
-                }
+                for (int u = 0; u < 32; ++u) c[u] = (ht + (k + u) * kRsMaxDig)[d];
 #pragma unroll
                 for (int u = 0; u < 32; ++u) {
-                    if (k + u < tiles) tot[q] += c[u];
-                    if (k + u < tile) early[q] += c[u];
+                    all += c[u];
+                    before += k + u < tile ? c[u] : 0u;
                 }
             }
+            for (; k + 8 <= tiles; k += 8) {
+                uint32_t c[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) c[u] = (ht + (k + u) * kRsMaxDig)[d];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    all += c[u];
+                    before += k + u < tile ? c[u] : 0u;
+                }
+            }
+            if (k < tiles) {        // up to seven more, requested together
+                uint32_t c[8];
+#pragma unroll
+                for (int u = 0; u < 7; ++u)
+                    c[u] = (ht + (k + u < tiles ? k + u : k) * kRsMaxDig)[d];
+#pragma unroll
+                for (int u = 0; u < 7; ++u) {
+                    all += k + u < tiles ? c[u] : 0u;
+                    before += k + u < tile ? c[u] : 0u;
+                }
+            }
+            tot[q] = all;
+            early[q] = before;
         }
         run += tot[q];
     }
-
-    if (FIRST) drop_stale(bt, key);
-
     uint32_t incl = run;
     for (int off = 1; off < 64; off <<= 1) {
         const uint32_t up = __shfl_up(incl, off);
@@ -186,9 +211,10 @@ __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
     __syncthreads();
     uint32_t start = incl - run;
     for (int w = 0; w < wave; ++w) start += s_wsum[w];
-    for (int q = 0; q < dpt; ++q) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
         const int d = tid * dpt + q;
-        if (d < ndig) s_base[d] = start + early[q];
+        if (q < dpt && d < ndig) s_base[d] = start + early[q];
         start += tot[q];
     }
 
