@@ -250,27 +250,7 @@ __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
 // 2: that run covers the whole workgroup and goes on), and the two partial
 // sums part_lead / part_trail of dim floats each.
 // ---------------------------------------------------------------------------
-// Workgroups are handed to the eight XCDs in turn (block b runs on XCD b % 8),
-// and each XCD has an L2 of its own.  With several lookups per bag a gradient
-// row is read once per lookup, in the order of the sorted rows, i.e. at random:
-// the re-reads only hit L2 if the table's whole gradient block (B rows) stays
-// in it.  The first `pinned_blocks` blocks (a multiple of 8 tables) therefore
-// keep every table on one XCD; the other tables are spread as usual.
-__device__ __forceinline__ void apply_block_to_table(int b, int wgs_per_table,
-                                                     int pinned_blocks, int &t, int &wg)
-{
-    if (b < pinned_blocks) {
-        const int xcd = b & 7, j = b >> 3;
-        const int q = j / wgs_per_table;
-        t = q * 8 + xcd;
-        wg = j - q * wgs_per_table;
-    } else {
-        t = b / wgs_per_table;
-        wg = b - t * wgs_per_table;
-    }
-}
-
-// The same for a gradient row.  A table's block of gradient rows is below 4 GiB
+// Address of one lane's f4 of a gradient row.  A table's block of gradient rows is below 4 GiB
 // in the FULL variant (the host checks), so the offset fits 32 bits and the base
 // can stay in scalar registers.
 template <int G, bool FULL>
@@ -302,7 +282,9 @@ __global__ __launch_bounds__(kApplyWG) void apply_kernel(
     __shared__ uint8_t s_lead_state[NG];
 
     int t, wg;
-    apply_block_to_table(blockIdx.x, wgs_per_table, pinned_blocks, t, wg);
+    // multi-hot bags: a table's gradient block is re-read by every lookup of a bag,
+    // in the order of the sorted rows; it only stays in L2 if the table has one
+    block_to_table_pinned(blockIdx.x, wgs_per_table, pinned_blocks, t, wg);
     const int tid = threadIdx.x, g = tid / G, c = tid % G;
     const uint32_t *__restrict__ kp = keys + (int64_t)t * NP;
     const uint32_t *__restrict__ vp = vals + (int64_t)t * NP;

@@ -66,11 +66,11 @@ template <int G, bool FULL>
 __global__ __launch_bounds__(kWG) void forward_kernel(
     const float *const *__restrict__ weights, const int32_t *__restrict__ idx,
     int Bcap, int L, const int32_t *__restrict__ n_valid,
-    float *__restrict__ out, int D4, int tiles_per_table)
+    float *__restrict__ out, int D4, int tiles_per_table, int pinned_blocks)
 {
     constexpr int BAGS = kWG / G;
     int t, tile;
-    block_to_table_tile(blockIdx.x, tiles_per_table, t, tile);
+    block_to_table_pinned(blockIdx.x, tiles_per_table, pinned_blocks, t, tile);
     const int n = clamp_valid(n_valid, Bcap);
     const int j = tile * BAGS + (int)threadIdx.x / G;
     if (j >= n) return;
@@ -136,7 +136,7 @@ int32_t launch_forward(const ss_tables *tb, const int32_t *idx, int Bcap, int L,
 #define SS_FWD(F_)                                                                \
     SS_DISPATCH_G(g, launch((forward_kernel<G, F_>), dim3((unsigned)blocks),       \
                             dim3(kWG), s, tb->weights, idx, Bcap, L, n_valid, out,  \
-                            D4, tiles))
+                            D4, tiles, (tb->num_tables / 8) * 8 * tiles))
         if (D4 == g) { SS_FWD(true); } else { SS_FWD(false); }
 #undef SS_FWD
     }

@@ -115,6 +115,26 @@ __device__ __forceinline__ P row_ptr(P lane_base, uint32_t r, uint32_t d4)
 }
 
 
+// Workgroups are handed to the eight XCDs in turn (block b runs on XCD b % 8),
+// and each XCD has an L2 of its own.  Where the same lines of a table are read
+// again and again (hot rows in a multi-hot forward pass, a table's gradient rows
+// in the update), they should sit in ONE L2 and not in eight: the first
+// `pinned_blocks` blocks (per_table blocks for each of a multiple of 8 tables)
+// keep every table on one XCD, the other tables are spread as usual.
+__device__ __forceinline__ void block_to_table_pinned(int b, int per_table,
+                                                      int pinned_blocks, int &t, int &i)
+{
+    if (b < pinned_blocks) {
+        const int xcd = b & 7, j = b >> 3;
+        const int q = j / per_table;
+        t = q * 8 + xcd;
+        i = j - q * per_table;
+    } else {
+        t = b / per_table;
+        i = b - t * per_table;
+    }
+}
+
 __device__ __forceinline__ bool bit_set(gptr<const uint32_t> bits, uint32_t r)
 {
     return (bits[r >> 5] >> (r & 31)) & 1u;
