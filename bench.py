@@ -42,8 +42,9 @@ def parse():
     ap.add_argument("--grouped-forward", action="store_true",
                     help="use ss_embbag_forward_grouped (forward and the grouping half of "
                          "the backward pass in one launch)")
-    ap.add_argument("--pipeline-every", type=int, default=8,
-                    help="batches between two cross-stream events of the pipelined step")
+    ap.add_argument("--pipeline-every", type=int, default=0,
+                    help="batches between two cross-stream events of the pipelined step "
+                         "(0: PipelinedStep's own choice)")
     ap.add_argument("--index-streams", type=int, default=0,
                     help="streams the index work of the pipelined step is spread over "
                          "(0: two when the grouping of a batch is a chain of launches too small "
@@ -115,7 +116,7 @@ def main():
         args.index_streams = 2 if small_chain else 1
     if args.pipeline:
         step = PipelinedStep(weights, hot_d, Bn, L, cfg.lr, thr, cfg.snapshot_every,
-                             diagnostics=False, every=args.pipeline_every,
+                             diagnostics=False, every=args.pipeline_every or None,
                              index_streams=args.index_streams)
     else:
         step = EmbeddingStep(weights, hot_d, Bn, L, cfg.lr, thr, cfg.snapshot_every,
@@ -209,7 +210,7 @@ def main():
                    "snapshot_every": cfg.snapshot_every, "ring": args.ring,
                    "streams": (1 + args.index_streams) if args.pipeline else (2 if args.overlap else 1),
                    "pipelined": bool(args.pipeline),
-                   "pipeline_every": args.pipeline_every if args.pipeline else None,
+                   "pipeline_every": step.every if args.pipeline else None,
                    "grouped_forward": bool(args.grouped_forward)},
         "roofline": roofline, "roofline_all": roofline_all,
         "whole_step": {"algorithmic_bytes": step_bytes,

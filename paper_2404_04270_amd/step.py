@@ -207,11 +207,28 @@ class PipelinedStep:
                     return True
             return False
 
+    RING_BYTES = 96 << 20     # what the grouped lists of the whole ring may take
+
+    @classmethod
+    def auto_every(cls, T: int, batch: int, bag: int, n_side: int) -> int:
+        """Batches between two cross-stream events: 8 (an event pair costs about
+        10 us of GPU time), or fewer when a ring of 3 * every * n_side sets would not
+        fit the 256 MB memory-side cache next to the step's own traffic: a grouped
+        list written by the index stream should still be there when the update
+        kernel reads it (measured at 8 tables x 81920 lookups: 99.9 / 102.1 / 104.0
+        us per step for every = 2 / 4 / 8)."""
+        # keys and payloads, two buffers each, padded to 2048 lookups per table
+        per_set = 16 * T * ((batch * bag + 2047) // 2048) * 2048
+        every = 8
+        while every > 2 and 3 * every * n_side * per_set > cls.RING_BYTES:
+            every //= 2
+        return every
+
     def __init__(self, weights: Sequence[torch.Tensor],
                  hot_ids: Sequence[torch.Tensor], batch: int, bag: int,
                  lr: float, threshold: float, snapshot_every: int,
-                 alpha: Optional[int] = None, diagnostics: bool = True, every: int = 8,
-                 index_streams: int = 1):
+                 alpha: Optional[int] = None, diagnostics: bool = True,
+                 every: Optional[int] = None, index_streams: int = 1):
         self.tables = B.Tables(weights)
         self.bits = self.tables.new_bits()
         self.hot = B.HotState(self.tables, hot_ids, diagnostics=diagnostics)
@@ -221,6 +238,9 @@ class PipelinedStep:
         self.lr, self.threshold, self.K = float(lr), float(threshold), int(snapshot_every)
         self.alpha = T * bag if alpha is None else int(alpha)
         self.pooled = torch.zeros(T, batch, D, dtype=torch.float32, device=dev)
+        n_side = max(1, int(index_streams))
+        if every is None:
+            every = self.auto_every(T, batch, bag, n_side)
         self.every = max(1, int(every))
         # Three groups of `every` sets, of which two may be in use ahead of the batch
         # being trained on: the set a new batch takes over was then last used at least
@@ -228,7 +248,6 @@ class PipelinedStep:
         # covers, and the training stream finds an event of the index stream that
         # covers the batch it starts.  With less slack each stream would have to
         # record an extra event for almost every batch.
-        n_side = max(1, int(index_streams))
         self.sets = [self._Set(T, batch, bag, D, dev) for _ in range(3 * self.every * n_side)]
         for s in self.sets:       # arguments marshalled once (the bitmaps are attached)
             s.filter = B.prepared_filter_batch(self.tables, batch, bag, self.alpha, s.skip_mask,

@@ -254,3 +254,18 @@ def test_layernorm_calls_validate_on_the_host(lib):
                      (dict(dgamma=ok), b"workspace"),
                      (dict(dgamma=ok, ws=ok, ws_bytes=16), b"workspace")]:
         assert bwd(**kw) != 0 and text in lib.ss_last_error(), (kw, lib.ss_last_error())
+
+
+def test_pipelined_step_picks_its_event_spacing_from_the_ring_size():
+    """Host logic only: 8 batches between events unless the grouped lists of a ring
+    of 3 * every * streams sets would outgrow their share of the memory-side cache."""
+    from paper_2404_04270_amd.step import PipelinedStep as P
+    assert P.auto_every(26, 8192, 1, 1) == 8         # 3.4 MB of lists per batch
+    assert P.auto_every(1, 65536, 1, 2) == 8
+    assert P.auto_every(8, 4096, 20, 1) == 2         # 10.5 MB per batch
+    assert P.auto_every(8, 4096, 20, 4) == 2         # never below 2
+    for T, b, L, n in [(26, 8192, 1, 1), (8, 4096, 20, 1), (4, 30000, 3, 2)]:
+        e = P.auto_every(T, b, L, n)
+        lists = 16 * T * ((b * L + 2047) // 2048) * 2048
+        assert e in (2, 4, 8) and (e == 2 or 3 * e * n * lists <= P.RING_BYTES)
+        assert e == 8 or 3 * 2 * e * n * lists > P.RING_BYTES      # the largest that fits
