@@ -30,8 +30,9 @@
 //     order; runs that cross workgroup borders leave their piece in the
 //     workspace.
 //
-//  3. FIXUP: one workgroup per run that crossed a workgroup border adds its
-//     pieces in a fixed order and applies the update.
+//  3. FIXUP: a lane group per workgroup of the apply stage checks whether a run
+//     left it; short runs are finished by that group, the few long ones by the
+//     whole workgroup, pieces added in a fixed order.
 //
 // Rows whose stale bit is set drop out in stage 1, before any gradient or
 // weight of theirs is read.  There are no floating-point atomics: every sum has a fixed
