@@ -40,17 +40,26 @@ def set_bits_np(R, rows):
     return np.packbits(flags, bitorder="little").view(np.uint32).copy()
 
 
-def test_config3_full_shape_lockstep(B, dev):
-    from paper_2404_04270_amd.step import EmbeddingStep
+@pytest.mark.parametrize("pipelined", [False, True])   # True: what bench.py times by default
+def test_config3_full_shape_lockstep(B, dev, pipelined):
+    from paper_2404_04270_amd.step import EmbeddingStep, PipelinedStep
     cfg = wl.CONFIGS[3].scaled(snapshot_every=2)     # full tables and batch; K shortened
     n_iters = 6                                      # capture at 1, detect at 3 and 5
     w = wl.Workload(cfg)
     idx = w.indices(0, n_iters)
     hot = wl.hot_set(idx, cfg.rows, cfg.hot_rows)
     W0 = [w.weights(t) for t in range(cfg.num_tables)]
-    gpu = EmbeddingStep([torch.from_numpy(x).to(dev) for x in W0],
-                        [torch.from_numpy(h).to(dev) for h in hot], cfg.batch, cfg.bag,
-                        cfg.lr, 3e-4, cfg.snapshot_every, alpha=2)
+    if pipelined:
+        gpu = PipelinedStep([torch.from_numpy(x).to(dev) for x in W0],
+                            [torch.from_numpy(h).to(dev) for h in hot], cfg.batch, cfg.bag,
+                            cfg.lr, 3e-4, cfg.snapshot_every, alpha=2)
+        idx_dev = torch.from_numpy(idx).to(dev)      # resident before any submit
+        torch.cuda.synchronize()
+        ahead = 0
+    else:
+        gpu = EmbeddingStep([torch.from_numpy(x).to(dev) for x in W0],
+                            [torch.from_numpy(h).to(dev) for h in hot], cfg.batch, cfg.bag,
+                            cfg.lr, 3e-4, cfg.snapshot_every, alpha=2)
     # alpha = 2: a sample is dropped once two of its 26 lookups hit stale rows, so
     # that the few iterations of this test do skip samples
     ref = OracleRun(W0, hot, cfg.lr, 3e-4, cfg.snapshot_every, alpha=2)   # updates W0
@@ -58,7 +67,13 @@ def test_config3_full_shape_lockstep(B, dev):
     for it in range(n_iters):
         g = w.grads(it)
         r = ref.step(idx[it], g)
-        gpu.filter_forward(torch.from_numpy(idx[it]).to(dev))
+        if pipelined:
+            while ahead < n_iters and gpu.room() > 0:    # index work as far ahead as allowed
+                gpu.submit(idx_dev[ahead])
+                ahead += 1
+            gpu.forward()
+        else:
+            gpu.filter_forward(torch.from_numpy(idx[it]).to(dev))
         nk = int(gpu.n_kept.item())
         assert nk == r["n_kept"]
         assert np.array_equal(gpu.skip_mask.cpu().numpy(), r["skip"])
