@@ -56,6 +56,9 @@ def parse():
                          "the coming batches on a second stream while the current one is in its "
                          "forward and update kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--permute", action="store_true",
+                    help="map rank -> row through a per-table random permutation (hot rows "
+                         "scattered over the table as in real data; config 2 always does)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters against a known size)")
@@ -98,6 +101,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     cfg = wl.CONFIGS[args.config]
+    if args.permute and not cfg.permute:
+        cfg = cfg.scaled(permute=True, name=cfg.name + "_permuted")
     thr = cfg.threshold if args.threshold is None else args.threshold
     T, R, D, Bn, L = cfg.num_tables, cfg.rows, cfg.dim, cfg.batch, cfg.bag
     w = wl.Workload(cfg)
@@ -162,6 +167,20 @@ def main():
     n_kept_last = int(step.n_kept.item())
     stale_rows = int(sum(int(torch.count_nonzero(b).item()) for b in step.bits))
 
+    # what a plain device copy sustains in this process (512 MiB read + 512 MiB written,
+    # outside the timed region): the ceiling the roofline fractions are also put against
+    ca = torch.empty(1 << 27, dtype=torch.float32, device=dev).normal_()
+    cb = torch.empty_like(ca)
+    cb.copy_(ca)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        cb.copy_(ca)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * ca.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del ca, cb
+
     # per-kernel durations: same steps again, each launch bracketed by events
     B.ss_profile_enable(True)
     run(args.steps, args.warmup + args.steps)
@@ -193,7 +212,8 @@ def main():
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                 "traffic": measured_traffic(cfg.name, dom),
                 "algorithmic_bytes_per_launch": alg[dom],
-                "avg_kernel_us": kern[dom]["avg_us"]}
+                "avg_kernel_us": kern[dom]["avg_us"],
+                "measured_copy_GBs": copy_gbs, "frac_of_measured_copy": achieved / copy_gbs}
     # the same figures for every kernel that carries algorithmic bytes
     roofline_all = {k: {"achieved": alg[k] / (kern[k]["avg_us"] * 1e-6) / 1e9,
                         "frac": alg[k] / (kern[k]["avg_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS,
@@ -202,6 +222,9 @@ def main():
                         "traffic": measured_traffic(cfg.name, k)}
                     for k in kern if k in alg}
     step_bytes = alg["forward_kernel"] + alg["apply_kernel"]
+    # "logical" bytes: every lookup counted as a row (nnz in place of the distinct rows)
+    logical_bytes = (nnz * row_b + nnz * 4 + T * Bn * row_b * kept_frac) + \
+                    (T * Bn * row_b * kept_frac + nnz * 4 + 2 * nnz * row_b)
     # (filter: < 2 % of the step's bytes; grouping and fixup carry no algorithmic bytes)
 
     out = {
@@ -219,8 +242,11 @@ def main():
         "roofline": roofline, "roofline_all": roofline_all,
         "whole_step": {"algorithmic_bytes": step_bytes,
                        "achieved_GBs": step_bytes / (ms_per_step * 1e-3) / 1e9,
-                       "frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
-        "skip_fraction": 1.0 - kept_frac, "stale_rows": stale_rows,
+                       "frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "logical_bytes": logical_bytes,
+                       "effective_GBs": logical_bytes / (ms_per_step * 1e-3) / 1e9},
+        "skip_fraction": 1.0 - kept_frac, "kept_samples_per_s": value * kept_frac,
+        "stale_rows": stale_rows,
         "kernels": kern, "setup_s": setup_s,
     }
 

@@ -1,14 +1,14 @@
 // ss_filter_batch: input classifier (section 3.4, Eq. 6-8) plus a stable
 // stream compaction of the kept samples.
 //
-// Kernel 1 gives each sample four lanes, which probe one bit per lookup (the
-// bitmaps are small and stay in L2) in chunks of 32 lookups, all loads of a
-// chunk in flight together, and stop as soon as the verdict is fixed: the count
-// reached alpha, or it can no longer reach it.  (One lane per sample probing one
-// lookup at a time is as fast while nothing is stale, but its chain of
-// dependent loads grows with every stale lookup: 21 us at 26 tables once the hot
-// rows are frozen.)  A wavefront ballot plus popcount yields the number of kept
-// samples per tile.
+// Kernel 1 gives each sample a group of lanes, which probe one bit per lookup
+// (the bitmaps are small and stay in L2) in chunks, all loads of a chunk in
+// flight together, and stop as soon as the verdict is fixed: the count reached
+// alpha, or it can no longer reach it.  (One lane per sample probing one lookup
+// at a time is as fast while nothing is stale, but its chain of dependent loads
+// grows with every stale lookup: 21 us at 26 tables once the hot rows are
+// frozen.)  A wavefront ballot plus popcount yields the number of kept samples
+// per workgroup.
 // Kernel 2 runs one workgroup per (tile of 256 samples, table).  It turns the
 // per-tile counts into an offset (summing the counts before it: at most a few
 // hundred values), ranks the tile's kept samples with ballot + popcount prefix
@@ -18,23 +18,27 @@
 
 namespace ss {
 
-// One workgroup per tile of 256 samples, four lanes per sample.  The lookups of a
-// sample are taken 32 at a time (8 per lane): their indices are requested
-// together, then their bitmap words together, so a chunk costs two round trips
-// to memory however many of its lookups are stale.  After each chunk the four
-// lanes add up their counts and stop once the verdict is fixed.  (The first chunk
-// is four lookups only.)
-constexpr int kFlagLanes = 4;                    // lanes per sample
+// LANES lanes per sample, 1024 / LANES samples per workgroup.  A chunk of lookups
+// costs two round trips to memory (indices, then bitmap words) however many of
+// them are stale.  The first chunk is one lookup per lane: while few rows are
+// stale that settles almost every sample, and the kernel reads no more than
+// that.  Later chunks take eight per lane.  The host picks LANES so that two
+// chunks cover all T * L lookups of a sample where it can: the kernel lasts as
+// long as its unluckiest sample, and with most hot rows frozen there is always
+// a sample that needs nearly all of them (160 lookups per sample, four lanes:
+// 16 us; 32 lanes: see the launch code).
 constexpr int kFlagProbes = 8;                   // lookups per lane and chunk
-constexpr int kFlagWG = kWG * kFlagLanes;        // 1024 threads: 256 samples
+constexpr int kFlagWG = 1024;
 
+template <int LANES>
 __global__ __launch_bounds__(kFlagWG) void filter_flag_kernel(
     const uint32_t *const *__restrict__ bits, const int32_t *__restrict__ idx,
     int T, int B, int L, int alpha, uint8_t *__restrict__ skip_mask,
     int32_t *__restrict__ block_kept)
 {
-    const int c = threadIdx.x % kFlagLanes;
-    const int b = blockIdx.x * kWG + threadIdx.x / kFlagLanes;
+    constexpr int SAMPLES = kFlagWG / LANES;
+    const int c = threadIdx.x % LANES;
+    const int b = blockIdx.x * SAMPLES + threadIdx.x / LANES;
     bool keep = false;
     if (b < B) {
         const int total = T * L;
@@ -44,19 +48,16 @@ __global__ __launch_bounds__(kFlagWG) void filter_flag_kernel(
         } else if (alpha > total || bits == nullptr) {
             skip = false;
         } else {
-            int count = 0;                       // stale lookups so far (all four lanes)
-            // The first chunk is one lookup per lane: while few rows are stale, four
-            // lookups settle almost every sample, and the kernel reads no more than
-            // that.  Later chunks take eight per lane.
+            int count = 0;                       // stale lookups so far (all lanes)
             int per_lane = 1;
             for (int q0 = 0; q0 < total;) {
-                const int chunk = kFlagLanes * per_lane;
+                const int chunk = LANES * per_lane;
                 uint32_t row[kFlagProbes];
                 gptr<const uint32_t> bt[kFlagProbes];
                 bool live[kFlagProbes];
 #pragma unroll
                 for (int i = 0; i < kFlagProbes; ++i) {
-                    const int q = q0 + i * kFlagLanes + c;
+                    const int q = q0 + i * LANES + c;
                     const int qq = (i < per_lane && q < total) ? q : 0;
                     const int t = qq / L, l = qq - t * L;
                     bt[i] = as_global(bits[t]);
@@ -69,8 +70,8 @@ __global__ __launch_bounds__(kFlagWG) void filter_flag_kernel(
                 int mine = 0;
 #pragma unroll
                 for (int i = 0; i < kFlagProbes; ++i) mine += (word[i] >> (row[i] & 31)) & 1u;
-                mine += __shfl_xor(mine, 1, kFlagLanes);
-                mine += __shfl_xor(mine, 2, kFlagLanes);
+#pragma unroll
+                for (int off = 1; off < LANES; off <<= 1) mine += __shfl_xor(mine, off, LANES);
                 count += mine;
                 q0 += chunk;
                 const int remaining = total > q0 ? total - q0 : 0;
@@ -96,11 +97,14 @@ __global__ __launch_bounds__(kFlagWG) void filter_flag_kernel(
 __global__ __launch_bounds__(kWG) void filter_compact_kernel(
     const int32_t *__restrict__ idx, int B, int L,
     const uint8_t *__restrict__ skip_mask,
-    const int32_t *__restrict__ block_kept, int32_t *__restrict__ kept_ids,
-    int32_t *__restrict__ n_kept, int32_t *__restrict__ idx_c)
+    const int32_t *__restrict__ block_kept, int per_tile,
+    int32_t *__restrict__ kept_ids, int32_t *__restrict__ n_kept,
+    int32_t *__restrict__ idx_c)
 {
     // grid: x = tile of 256 samples, y = table.  Every (x, y) workgroup repeats
     // the cheap ranking of tile x and copies the index rows of table y only.
+    // block_kept holds per_tile counts for every tile (one per workgroup of the
+    // flag kernel).
     __shared__ int s_red[kWG / 64];
     __shared__ int s_wbase[kWG / 64];
     __shared__ int32_t s_list[kWG];
@@ -109,7 +113,7 @@ __global__ __launch_bounds__(kWG) void filter_compact_kernel(
 
     // samples kept by the tiles before this one
     int part = 0;
-    for (int i = tid; i < (int)blockIdx.x; i += kWG) part += block_kept[i];
+    for (int i = tid; i < (int)blockIdx.x * per_tile; i += kWG) part += block_kept[i];
     for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
     if (lane == 0) s_red[wave] = part;
 
@@ -154,10 +158,19 @@ __global__ __launch_bounds__(kWG) void filter_compact_kernel(
     }
 }
 
+// Lanes per sample in the flag kernel: the fewest of 4 ... 64 with which two
+// chunks (one lookup per lane, then eight) cover all T * L lookups of a sample.
+static int flag_lanes(int64_t total)
+{
+    int lanes = 4;
+    while (lanes < 64 && (int64_t)lanes * (1 + kFlagProbes) < total) lanes *= 2;
+    return lanes;
+}
+
 size_t filter_ws_bytes(int T, int B, int L)
 {
-    (void)T; (void)L;
-    const size_t blocks = ((size_t)B + kWG - 1) / kWG;
+    const int samples = kFlagWG / flag_lanes((int64_t)T * L);
+    const size_t blocks = ((size_t)B + samples - 1) / samples;
     return align_up(blocks * sizeof(int32_t), 256);
 }
 
@@ -165,17 +178,30 @@ int32_t launch_filter(const ss_tables *tb, const int32_t *idx, int B, int L,
                       int alpha, uint8_t *skip_mask, int32_t *kept_ids,
                       int32_t *n_kept, int32_t *idx_c, void *ws, hipStream_t s)
 {
-    const int blocks = (B + kWG - 1) / kWG;
+    const int lanes = flag_lanes((int64_t)tb->num_tables * L);
+    const int samples = kFlagWG / lanes;             // per workgroup of the flag kernel
+    const int flag_blocks = (B + samples - 1) / samples;
+    const int tiles = (B + kWG - 1) / kWG;
     int32_t *block_kept = static_cast<int32_t *>(ws);
     {
         ProfScope prof("filter_flag_kernel", s);
-    launch(filter_flag_kernel, dim3(blocks), dim3(kFlagWG), s,
-                       tb->stale_bits, idx, tb->num_tables, B, L, alpha,
-                       skip_mask, block_kept);
+#define SS_FLAG(LANES_)                                                            \
+    launch(filter_flag_kernel<LANES_>, dim3(flag_blocks), dim3(kFlagWG), s,        \
+           tb->stale_bits, idx, tb->num_tables, B, L, alpha, skip_mask, block_kept)
+        switch (lanes) {
+        case 4: SS_FLAG(4); break;
+        case 8: SS_FLAG(8); break;
+        case 16: SS_FLAG(16); break;
+        case 32: SS_FLAG(32); break;
+        default: SS_FLAG(64); break;
+        }
+#undef SS_FLAG
     }
     ProfScope prof("filter_compact_kernel", s);
-    launch(filter_compact_kernel, dim3(blocks, tb->num_tables),
-                       dim3(kWG), s, idx, B, L, skip_mask, block_kept,
+    // the last tile may be covered by fewer workgroups of the flag kernel: a tile
+    // before it is always covered by exactly kWG / samples of them
+    launch(filter_compact_kernel, dim3(tiles, tb->num_tables),
+                       dim3(kWG), s, idx, B, L, skip_mask, block_kept, kWG / samples,
                        kept_ids, n_kept, idx_c);
     return check_launch("ss_filter_batch");
 }
