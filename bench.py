@@ -47,9 +47,7 @@ def parse():
                          "(0: PipelinedStep's own choice)")
     ap.add_argument("--index-streams", type=int, default=0,
                     help="streams the index work of the pipelined step is spread over "
-                         "(0: two when the grouping of a batch is a chain of launches too small "
-                         "to fill the chip, i.e. more than 16384 lookups per table in fewer than "
-                         "256 tiles of 2048 over all tables; else one)")
+                         "(0: PipelinedStep's own choice)")
     ap.add_argument("--serial", action="store_true",
                     help="issue every call of a batch on one stream, one batch after the other "
                          "(EmbeddingStep).  Default: PipelinedStep, which classifies and groups "
@@ -116,9 +114,7 @@ def main():
     grads = [torch.from_numpy(w.grads(k)).to(dev) for k in range(n_grads)]
     hot_d = [torch.from_numpy(h).to(dev) for h in hot]
     if args.index_streams <= 0:
-        per_table = Bn * L
-        small_chain = per_table > 16384 and T * ((per_table + 2047) // 2048) < 256
-        args.index_streams = 2 if small_chain else 1
+        args.index_streams = PipelinedStep.auto_streams(Bn, L)
     if args.pipeline:
         step = PipelinedStep(weights, hot_d, Bn, L, cfg.lr, thr, cfg.snapshot_every,
                              diagnostics=False, every=args.pipeline_every or None,

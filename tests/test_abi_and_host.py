@@ -260,6 +260,8 @@ def test_pipelined_step_picks_its_event_spacing_from_the_ring_size():
     """Host logic only: 8 batches between events unless the grouped lists of a ring
     of 3 * every * streams sets would outgrow their share of the memory-side cache."""
     from paper_2404_04270_amd.step import PipelinedStep as P
+    assert P.auto_streams(8192, 1) == 1 and P.auto_streams(16384, 1) == 1
+    assert P.auto_streams(65536, 1) == 2 and P.auto_streams(4096, 20) == 2
     assert P.auto_every(26, 8192, 1, 1) == 8         # 3.4 MB of lists per batch
     assert P.auto_every(1, 65536, 1, 2) == 8
     assert P.auto_every(8, 4096, 20, 1) == 2         # 10.5 MB per batch
