@@ -182,6 +182,9 @@ int32_t ss_embbag_forward_grouped(const ss_tables *tables, const int32_t *idx,
  *                this call's verdict per hot slot
  *   drift        NULL, or device array of T device pointers, each fp64 [H]
  *   stale_count  NULL, or device uint32 [T]: slots flagged stale by this call
+ *                (zeroed by the call, then one atomic add per workgroup that
+ *                flags a row: a diagnostic, it slows a pass in which most rows
+ *                are flagged; pass NULL on the training path)
  */
 int32_t ss_detect_stale(const ss_tables *tables, int32_t *const *hot_ids,
                         int32_t H, float **snapshot, float threshold,
