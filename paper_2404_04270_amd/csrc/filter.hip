@@ -25,8 +25,8 @@ namespace ss {
 // that.  Later chunks take eight per lane.  The host picks LANES so that two
 // chunks cover all T * L lookups of a sample where it can: the kernel lasts as
 // long as its unluckiest sample, and with most hot rows frozen there is always
-// a sample that needs nearly all of them (160 lookups per sample, four lanes:
-// 16 us; 32 lanes: see the launch code).
+// a sample that needs nearly all of them (160 lookups per sample: 16 us with
+// four lanes and six chunks, 7 us with 32 lanes and two).
 constexpr int kFlagProbes = 8;                   // lookups per lane and chunk
 constexpr int kFlagWG = 1024;
 

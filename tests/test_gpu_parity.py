@@ -227,8 +227,8 @@ BACKWARD_CASES = [
     (1, 100, 64, 4096, 4, None, 0.0, 1.05),     # few rows: runs cross workgroups
     (2, 1 << 20, 64, 40000, 1, 39999, 0.05, 1.1),   # global radix sort path
     (1, 70000, 128, 5000, 20, None, 0.1, 1.2),  # global sort + heavy duplicates
-    (26, 100000, 64, 8192, 1, None, 0.0, 1.2),  # many workgroups: strip 8
-    (8, 200000, 128, 4096, 20, None, 0.02, 1.2),  # strip 16, global sort
+    (26, 100000, 64, 8192, 1, None, 0.0, 1.2),  # many workgroups: strip 4
+    (8, 200000, 128, 4096, 20, None, 0.02, 1.2),  # strip 8, global sort, tables pinned to XCDs
     (1, 3, 16, 3000, 1, None, 0.0, 1.5),        # three rows only
     (1, 500, 48, 200, 3, None, 0.3, 1.3),       # dim not a power of two
     (1, 300, 260, 100, 2, None, 0.3, 1.3),      # dim above 256
