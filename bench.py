@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--index-streams", type=int, default=0,
                     help="streams the index work of the pipelined step is spread over "
                          "(0: PipelinedStep's own choice)")
+    ap.add_argument("--issue-thread", type=int, default=-1, choices=(-1, 0, 1),
+                    help="pipelined step: enqueue the index work from the library's own host "
+                         "thread (ss_issue_queue); -1: PipelinedStep's own choice")
     ap.add_argument("--serial", action="store_true",
                     help="issue every call of a batch on one stream, one batch after the other "
                          "(EmbeddingStep).  Default: PipelinedStep, which classifies and groups "
@@ -114,11 +117,12 @@ def main():
     grads = [torch.from_numpy(w.grads(k)).to(dev) for k in range(n_grads)]
     hot_d = [torch.from_numpy(h).to(dev) for h in hot]
     if args.index_streams <= 0:
-        args.index_streams = PipelinedStep.auto_streams(Bn, L)
+        args.index_streams = PipelinedStep.auto_streams(Bn, L, T)
     if args.pipeline:
         step = PipelinedStep(weights, hot_d, Bn, L, cfg.lr, thr, cfg.snapshot_every,
                              diagnostics=False, every=args.pipeline_every or None,
-                             index_streams=args.index_streams)
+                             index_streams=args.index_streams,
+                             issue_thread=None if args.issue_thread < 0 else bool(args.issue_thread))
     else:
         step = EmbeddingStep(weights, hot_d, Bn, L, cfg.lr, thr, cfg.snapshot_every,
                              diagnostics=False, overlap=args.overlap,
@@ -145,6 +149,7 @@ def main():
                     nxt += 1
                 step.forward()
                 step.backward(grads[it % n_grads])
+            step.flush()
             return
         for k in range(n):
             it = start_it + k
@@ -234,6 +239,7 @@ def main():
                    "streams": (1 + args.index_streams) if args.pipeline else (2 if args.overlap else 1),
                    "pipelined": bool(args.pipeline),
                    "pipeline_every": step.every if args.pipeline else None,
+                   "issue_thread": (step.queue is not None) if args.pipeline else None,
                    "grouped_forward": bool(args.grouped_forward)},
         "roofline": roofline, "roofline_all": roofline_all,
         "whole_step": {"algorithmic_bytes": step_bytes,

@@ -361,6 +361,56 @@ int32_t ss_embbag_ln_backward(const ss_tables *tables, const int32_t *idx, int32
                               size_t ws_bytes, void *stream);
 
 /*
+ * Issue queue: a host thread of the library's own that enqueues work on HIP
+ * streams, for callers whose single host thread cannot enqueue a batch as fast
+ * as the GPU finishes it (enqueueing one kernel costs the host about 3 us here;
+ * the index work of a batch - section 3.4, the input classifier, and the grouping
+ * half of the update - is up to eight kernels).  Jobs are issued in submission
+ * order.  Nothing here waits for the GPU or touches device memory.
+ *
+ *   ss_issue_queue_create   starts the thread, bound to the device that is
+ *                           current in the calling thread; *out owns it
+ *   ss_issue_queue_destroy  issues what is still queued, joins, frees
+ *   ss_issue_index_batch    = ss_filter_batch, then ss_embbag_backward_prepare on
+ *                           the idx_c / n_kept it produced, both on `stream`.
+ *                           Arguments as in those two calls (validated here, on
+ *                           the calling thread: an error is returned at once and
+ *                           nothing is queued); every buffer and the arrays that
+ *                           `tables` points to must stay valid until the job has
+ *                           run (the struct itself is copied)
+ *   ss_issue_wait_event     hipStreamWaitEvent(stream, event) as a job
+ *   ss_issue_record_event   hipEventRecord(event, stream) as a job
+ *   ss_issue_wait           blocks the calling host thread until job `ticket` has
+ *                           been ISSUED (not executed); returns the first error
+ *                           any job met.  Needed before another stream is made
+ *                           to wait for an event that the queue records: waiting
+ *                           for an event that has not been recorded yet is a no-op
+ *   ticket                  NULL, or host address that receives the job's number
+ *
+ * Events are plain HIP events without timing, as void *: ss_event_create /
+ * ss_event_destroy, and the two immediate calls a caller needs on its own
+ * streams, ss_event_record(event, stream) and ss_stream_wait_event(stream, event).
+ */
+typedef struct ss_issue_queue ss_issue_queue;
+int32_t ss_issue_queue_create(ss_issue_queue **out);
+int32_t ss_issue_queue_destroy(ss_issue_queue *queue);
+int32_t ss_issue_index_batch(ss_issue_queue *queue, const ss_tables *tables,
+                             const int32_t *idx, int32_t B, int32_t L, int32_t alpha,
+                             uint8_t *skip_mask, int32_t *kept_ids, int32_t *n_kept,
+                             int32_t *idx_c, void *ws_filter, size_t ws_filter_bytes,
+                             void *ws_backward, size_t ws_backward_bytes, void *stream,
+                             uint64_t *ticket);
+int32_t ss_issue_wait_event(ss_issue_queue *queue, void *event, void *stream,
+                            uint64_t *ticket);
+int32_t ss_issue_record_event(ss_issue_queue *queue, void *event, void *stream,
+                              uint64_t *ticket);
+int32_t ss_issue_wait(ss_issue_queue *queue, uint64_t ticket);
+int32_t ss_event_create(void **event);
+int32_t ss_event_destroy(void *event);
+int32_t ss_event_record(void *event, void *stream);
+int32_t ss_stream_wait_event(void *stream, void *event);
+
+/*
  * Measurement aid, off by default (not part of the method).  While enabled,
  * every kernel the library launches carries a pair of HIP events that the
  * runtime stamps with the start and end of that kernel's execution (this is the

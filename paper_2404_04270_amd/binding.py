@@ -24,7 +24,10 @@ SYMBOLS = (
     "ss_count_accesses", "ss_select_hot_workspace_bytes", "ss_select_hot_ratio",
     "ss_select_hot_top", "ss_layernorm_forward", "ss_layernorm_backward",
     "ss_layernorm_backward_workspace_bytes", "ss_embbag_forward_ln",
-    "ss_embbag_ln_backward",
+    "ss_embbag_ln_backward", "ss_issue_queue_create", "ss_issue_queue_destroy",
+    "ss_issue_index_batch", "ss_issue_wait_event", "ss_issue_record_event",
+    "ss_issue_wait", "ss_event_create", "ss_event_destroy", "ss_event_record",
+    "ss_stream_wait_event",
 )
 
 
@@ -57,7 +60,11 @@ def _load():
               "ss_embbag_backward_apply", "ss_embbag_forward_grouped",
               "ss_sample_drop", "ss_drop_stats", "ss_count_accesses",
               "ss_select_hot_ratio", "ss_select_hot_top", "ss_layernorm_forward",
-              "ss_layernorm_backward", "ss_embbag_forward_ln", "ss_embbag_ln_backward"):
+              "ss_layernorm_backward", "ss_embbag_forward_ln", "ss_embbag_ln_backward",
+              "ss_issue_queue_create", "ss_issue_queue_destroy", "ss_issue_index_batch",
+              "ss_issue_wait_event", "ss_issue_record_event", "ss_issue_wait",
+              "ss_event_create", "ss_event_destroy", "ss_event_record",
+              "ss_stream_wait_event"):
         getattr(lib, n).restype = C.c_int32
     return lib
 
@@ -623,3 +630,148 @@ def prepared_backward_update(tables: Tables, idx: torch.Tensor,
         if rc:
             _check(rc)
     return call
+
+
+# ---- issue queue (a host thread of the library that enqueues work on streams)
+def ss_issue_queue_create() -> C.c_void_p:
+    q = C.c_void_p()
+    _check(_lib.ss_issue_queue_create(C.byref(q)))
+    return q
+
+
+def ss_issue_queue_destroy(queue: C.c_void_p) -> None:
+    _check(_lib.ss_issue_queue_destroy(queue))
+
+
+def ss_issue_index_batch(queue: C.c_void_p, tables: Tables, idx: torch.Tensor, alpha: int,
+                         skip_mask: torch.Tensor, kept_ids: torch.Tensor,
+                         n_kept: torch.Tensor, idx_c: torch.Tensor, ws_filter: torch.Tensor,
+                         ws_backward: torch.Tensor, stream=None) -> int:
+    """ss_filter_batch + ss_embbag_backward_prepare as one queued job; returns its ticket."""
+    B, L = _idx_shape(tables, idx)
+    if skip_mask.numel() < B or kept_ids.numel() < B or n_kept.numel() < 1 \
+            or idx_c.numel() < tables.num_tables * B * L:
+        raise SlipstreamError("ss_issue_index_batch: an output tensor is too small")
+    t = C.c_uint64()
+    _check(_lib.ss_issue_index_batch(
+        queue, C.byref(tables.c), _dev_ptr(idx, torch.int32, "idx"), C.c_int32(B), C.c_int32(L),
+        C.c_int32(alpha), _dev_ptr(skip_mask, torch.uint8, "skip_mask"),
+        _dev_ptr(kept_ids, torch.int32, "kept_ids"), _dev_ptr(n_kept, torch.int32, "n_kept"),
+        _dev_ptr(idx_c, torch.int32, "idx_c"), _dev_ptr(ws_filter, torch.uint8, "ws_filter"),
+        C.c_size_t(ws_filter.numel()), _dev_ptr(ws_backward, torch.uint8, "ws_backward"),
+        C.c_size_t(ws_backward.numel()), _stream(stream), C.byref(t)))
+    return t.value
+
+
+def ss_issue_wait_event(queue: C.c_void_p, event: C.c_void_p, stream=None) -> int:
+    t = C.c_uint64()
+    _check(_lib.ss_issue_wait_event(queue, event, _stream(stream), C.byref(t)))
+    return t.value
+
+
+def ss_issue_record_event(queue: C.c_void_p, event: C.c_void_p, stream=None) -> int:
+    t = C.c_uint64()
+    _check(_lib.ss_issue_record_event(queue, event, _stream(stream), C.byref(t)))
+    return t.value
+
+
+def ss_issue_wait(queue: C.c_void_p, ticket: int) -> None:
+    _check(_lib.ss_issue_wait(queue, C.c_uint64(ticket)))
+
+
+def ss_event_create() -> C.c_void_p:
+    e = C.c_void_p()
+    _check(_lib.ss_event_create(C.byref(e)))
+    return e
+
+
+def ss_event_destroy(event: C.c_void_p) -> None:
+    _check(_lib.ss_event_destroy(event))
+
+
+def ss_event_record(event: C.c_void_p, stream=None) -> None:
+    _check(_lib.ss_event_record(event, _stream(stream)))
+
+
+def ss_stream_wait_event(stream, event: C.c_void_p) -> None:
+    _check(_lib.ss_stream_wait_event(_stream(stream), event))
+
+
+class IssueQueue:
+    """The library's issue thread (ss_issue_queue_*) and the plain HIP events that go
+    with it.  Tickets are the job numbers ss_issue_wait() takes."""
+
+    def __init__(self):
+        q = C.c_void_p()
+        _check(_lib.ss_issue_queue_create(C.byref(q)))
+        self._q = q
+        self._events = []
+
+    def close(self) -> None:
+        if self._q is not None:
+            _check(_lib.ss_issue_queue_destroy(self._q))     # issues what is queued, joins
+            self._q = None
+            for e in self._events:
+                _lib.ss_event_destroy(e)
+            self._events = []
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def new_event(self) -> C.c_void_p:
+        e = C.c_void_p()
+        _check(_lib.ss_event_create(C.byref(e)))
+        self._events.append(e)
+        return e
+
+    @staticmethod
+    def record_now(event: C.c_void_p, handle: C.c_void_p) -> None:
+        _check(_lib.ss_event_record(event, handle))
+
+    @staticmethod
+    def wait_now(handle: C.c_void_p, event: C.c_void_p) -> None:
+        _check(_lib.ss_stream_wait_event(handle, event))
+
+    def wait_event(self, event: C.c_void_p, handle: C.c_void_p) -> int:
+        t = C.c_uint64()
+        _check(_lib.ss_issue_wait_event(self._q, event, handle, C.byref(t)))
+        return t.value
+
+    def record_event(self, event: C.c_void_p, handle: C.c_void_p) -> int:
+        t = C.c_uint64()
+        _check(_lib.ss_issue_record_event(self._q, event, handle, C.byref(t)))
+        return t.value
+
+    def wait_issued(self, ticket: int) -> None:
+        _check(_lib.ss_issue_wait(self._q, C.c_uint64(ticket)))
+
+    def prepared_index_batch(self, tables: Tables, B: int, L: int, alpha: int,
+                             skip_mask: torch.Tensor, kept_ids: torch.Tensor,
+                             n_kept: torch.Tensor, idx_c: torch.Tensor,
+                             ws_filter: torch.Tensor, ws_backward: torch.Tensor):
+        """call(idx, handle) -> ticket: ss_issue_index_batch with everything but the
+        index tensor and the stream converted once."""
+        if skip_mask.numel() < B or kept_ids.numel() < B or n_kept.numel() < 1 \
+                or idx_c.numel() < tables.num_tables * B * L:
+            raise SlipstreamError("prepared_index_batch: an output tensor is too small")
+        fn, q, tref = _lib.ss_issue_index_batch, self._q, C.byref(tables.c)
+        fixed = (C.c_int32(B), C.c_int32(L), C.c_int32(alpha),
+                 _dev_ptr(skip_mask, torch.uint8, "skip_mask"),
+                 _dev_ptr(kept_ids, torch.int32, "kept_ids"),
+                 _dev_ptr(n_kept, torch.int32, "n_kept"),
+                 _dev_ptr(idx_c, torch.int32, "idx_c"),
+                 _dev_ptr(ws_filter, torch.uint8, "ws_filter"), C.c_size_t(ws_filter.numel()),
+                 _dev_ptr(ws_backward, torch.uint8, "ws_backward"),
+                 C.c_size_t(ws_backward.numel()))
+        ticket = C.c_uint64()
+        tptr = C.byref(ticket)
+
+        def call(idx: torch.Tensor, handle: C.c_void_p) -> int:
+            rc = fn(q, tref, C.c_void_p(idx.data_ptr()), *fixed, handle, tptr)
+            if rc:
+                _check(rc)
+            return ticket.value
+        return call

@@ -122,6 +122,35 @@ static int32_t check_ws(const char *who, const void *ws, size_t have, size_t nee
     return SS_OK;
 }
 
+int32_t check_filter(const char *who, const ss_tables *tables, const int32_t *idx,
+                     int32_t B, int32_t L, const uint8_t *skip_mask,
+                     const int32_t *kept_ids, const int32_t *n_kept,
+                     const int32_t *idx_c, const void *ws, size_t ws_bytes)
+{
+    int32_t rc = check_tables(tables, who);
+    if (rc) return rc;
+    rc = check_batch(who, idx, B, L, tables->num_tables);
+    if (rc) return rc;
+    if (!skip_mask || !kept_ids || !n_kept || !idx_c)
+        return fail(SS_ERR_INVALID_ARG, "%s: an output pointer is NULL", who);
+    if (idx_c == idx)
+        return fail(SS_ERR_INVALID_ARG, "%s: idx_c must not alias idx", who);
+    return check_ws(who, ws, ws_bytes, filter_ws_bytes(tables->num_tables, B, L));
+}
+
+int32_t check_backward(const char *who, const ss_tables *tables, int32_t Bcap,
+                       int32_t L, const void *ws, size_t ws_bytes)
+{
+    int32_t rc = check_tables(tables, who);
+    if (rc) return rc;
+    if (Bcap < 1) return fail(SS_ERR_INVALID_ARG, "%s: batch = %d", who, Bcap);
+    if (L < 1) return fail(SS_ERR_INVALID_ARG, "%s: L = %d", who, L);
+    if ((int64_t)Bcap * L >= (1LL << 31) - 4096)
+        return fail(SS_ERR_UNSUPPORTED, "%s: Bcap*L too large", who);
+    return check_ws(who, ws, ws_bytes,
+                    backward_ws_bytes(tables->num_tables, Bcap, L, tables->dim));
+}
+
 }  // namespace ss
 
 using namespace ss;
@@ -190,17 +219,8 @@ int32_t ss_filter_batch(const ss_tables *tables, const int32_t *idx, int32_t B,
                         int32_t *kept_ids, int32_t *n_kept, int32_t *idx_c,
                         void *ws, size_t ws_bytes, void *stream)
 {
-    const char *who = "ss_filter_batch";
-    int32_t rc = check_tables(tables, who);
-    if (rc) return rc;
-    rc = check_batch(who, idx, B, L, tables->num_tables);
-    if (rc) return rc;
-    if (!skip_mask || !kept_ids || !n_kept || !idx_c)
-        return fail(SS_ERR_INVALID_ARG, "%s: an output pointer is NULL", who);
-    if (idx_c == idx)
-        return fail(SS_ERR_INVALID_ARG, "%s: idx_c must not alias idx", who);
-    rc = check_ws(who, ws, ws_bytes,
-                  filter_ws_bytes(tables->num_tables, B, L));
+    const int32_t rc = check_filter("ss_filter_batch", tables, idx, B, L, skip_mask,
+                                    kept_ids, n_kept, idx_c, ws, ws_bytes);
     if (rc) return rc;
     return launch_filter(tables, idx, B, L, alpha, skip_mask, kept_ids, n_kept,
                          idx_c, ws, static_cast<hipStream_t>(stream));
@@ -220,19 +240,6 @@ int32_t ss_embbag_forward(const ss_tables *tables, const int32_t *idx,
         return fail(SS_ERR_INVALID_ARG, "%s: out is not 16-byte aligned", who);
     return launch_forward(tables, idx, Bcap, L, n_valid, out,
                           static_cast<hipStream_t>(stream));
-}
-
-static int32_t check_backward(const char *who, const ss_tables *tables, int32_t Bcap,
-                              int32_t L, const void *ws, size_t ws_bytes)
-{
-    int32_t rc = check_tables(tables, who);
-    if (rc) return rc;
-    if (Bcap < 1) return fail(SS_ERR_INVALID_ARG, "%s: batch = %d", who, Bcap);
-    if (L < 1) return fail(SS_ERR_INVALID_ARG, "%s: L = %d", who, L);
-    if ((int64_t)Bcap * L >= (1LL << 31) - 4096)
-        return fail(SS_ERR_UNSUPPORTED, "%s: Bcap*L too large", who);
-    return check_ws(who, ws, ws_bytes,
-                    backward_ws_bytes(tables->num_tables, Bcap, L, tables->dim));
 }
 
 static int32_t check_grad(const char *who, const float *grad)

@@ -17,6 +17,13 @@ int32_t fail(int32_t code, const char *fmt, ...);
 int32_t check_tables(const ss_tables *tb, const char *who);
 // hipGetLastError() after a launch -> SS_OK / SS_ERR_HIP.
 int32_t check_launch(const char *who);
+// Host-side checks of the arguments of ss_filter_batch and of the backward calls.
+int32_t check_filter(const char *who, const ss_tables *tables, const int32_t *idx,
+                     int32_t B, int32_t L, const uint8_t *skip_mask,
+                     const int32_t *kept_ids, const int32_t *n_kept,
+                     const int32_t *idx_c, const void *ws, size_t ws_bytes);
+int32_t check_backward(const char *who, const ss_tables *tables, int32_t Bcap,
+                       int32_t L, const void *ws, size_t ws_bytes);
 
 // Optional per-kernel timing (ss_profile_enable).  While a ProfScope is alive on
 // this thread and profiling is on, launch() attaches a pair of events to the

@@ -12,6 +12,7 @@ right after the filter, so that it runs next to the forward pass.
 """
 from __future__ import annotations
 
+import ctypes as C
 from typing import Optional, Sequence
 
 import torch
@@ -188,14 +189,14 @@ class PipelinedStep:
             self.recorded = []        # (covers_up_to_batch, event), ascending
             self.known = {}           # waiting stream (by position) -> batches <= this are done
 
-        def record(self, stream, covers: int) -> None:
+        def record(self, stream, handle, covers: int) -> None:
             ev = torch.cuda.Event()
             ev.record(stream)
             self.recorded.append((covers, ev))
             if len(self.recorded) > 64:
                 del self.recorded[0]
 
-        def cover(self, waiter: int, waiting_stream, batch: int) -> bool:
+        def cover(self, waiter: int, waiting_stream, waiting_handle, batch: int) -> bool:
             """Makes waiting_stream wait until `batch` is done, if it does not know yet.
             False if no recorded event covers the batch."""
             if batch <= self.known.get(waiter, -1):
@@ -203,6 +204,48 @@ class PipelinedStep:
             for covers, ev in self.recorded:
                 if covers >= batch:
                     waiting_stream.wait_event(ev)
+                    self.known[waiter] = covers
+                    return True
+            return False
+
+    class _QueueMarks:
+        """The same when the index streams are fed by the library's issue thread.
+
+        Everything that concerns an index stream goes through the queue, so that it
+        stays in order with the index work queued for that stream: the marks of an
+        index stream (by_queue) are recorded by the queue and waited for by the
+        training stream at once, after the host has made sure that the record has
+        been issued; the marks of the training stream are recorded at once and
+        waited for through the queue."""
+
+        def __init__(self, queue: "B.IssueQueue", by_queue: bool):
+            self.queue, self.by_queue = queue, by_queue
+            self.recorded = []        # (covers_up_to_batch, event, ticket), ascending
+            self.spare = []           # events of marks that were dropped, for re-use
+            self.known = {}
+
+        def record(self, stream, handle, covers: int) -> None:
+            ev = self.spare.pop() if self.spare else self.queue.new_event()
+            ticket = None
+            if self.by_queue:
+                ticket = self.queue.record_event(ev, handle)
+            else:
+                self.queue.record_now(ev, handle)
+            self.recorded.append((covers, ev, ticket))
+            if len(self.recorded) > 64:
+                # 64 marks back: issued and waited for long ago
+                self.spare.append(self.recorded.pop(0)[1])
+
+        def cover(self, waiter: int, waiting_stream, waiting_handle, batch: int) -> bool:
+            if batch <= self.known.get(waiter, -1):
+                return True
+            for covers, ev, ticket in self.recorded:
+                if covers >= batch:
+                    if self.by_queue:
+                        self.queue.wait_issued(ticket)     # a wait for an unrecorded event is a no-op
+                        self.queue.wait_now(waiting_handle, ev)
+                    else:
+                        self.queue.wait_event(ev, waiting_handle)
                     self.known[waiter] = covers
                     return True
             return False
@@ -225,21 +268,28 @@ class PipelinedStep:
         return every
 
     @staticmethod
-    def auto_streams(batch: int, bag: int) -> int:
-        """Index streams: two when a table has more than 16384 lookups per batch.  The
-        grouping is then a global radix sort, a chain of six small launches per batch
-        that lasts about as long as the training kernels; two such chains side by
-        side keep the index work ahead (one table x 65536 lookups: 44 against 77 us
-        per step; 8 tables x 81920 lookups: 88 against 104 us once the hot rows are
-        frozen, 101 either way before).  Below that size one stream is enough and a
-        second one costs 1-2 us."""
-        return 2 if batch * bag > 16384 else 1
+    def auto_streams(batch: int, bag: int, num_tables: int = 8) -> int:
+        """Index streams.  One while a table has at most 16384 lookups per batch (a
+        second one costs 1-2 us there).  Beyond that the grouping is a global radix
+        sort, a chain of six small launches per batch that lasts about as long as
+        the training kernels: two such chains side by side keep the index work ahead
+        (8 tables x 81920 lookups: 88 against 104 us per step once the hot rows are
+        frozen, 101 either way before).  Three when those launches are tiny (fewer
+        than 128 workgroups over all tables): the chain then lasts almost three
+        times as long as the training kernels (one table x 65536 lookups: 77 / 44 /
+        38 us per step with one / two / three streams, 35 us with three and the
+        issue thread; four are slower again)."""
+        lookups = batch * bag
+        if lookups <= 16384:
+            return 1
+        return 3 if num_tables * ((lookups + 2047) // 2048) < 128 else 2
 
     def __init__(self, weights: Sequence[torch.Tensor],
                  hot_ids: Sequence[torch.Tensor], batch: int, bag: int,
                  lr: float, threshold: float, snapshot_every: int,
                  alpha: Optional[int] = None, diagnostics: bool = True,
-                 every: Optional[int] = None, index_streams: Optional[int] = None):
+                 every: Optional[int] = None, index_streams: Optional[int] = None,
+                 issue_thread: Optional[bool] = None):
         self.tables = B.Tables(weights)
         self.bits = self.tables.new_bits()
         self.hot = B.HotState(self.tables, hot_ids, diagnostics=diagnostics)
@@ -250,7 +300,7 @@ class PipelinedStep:
         self.alpha = T * bag if alpha is None else int(alpha)
         self.pooled = torch.zeros(T, batch, D, dtype=torch.float32, device=dev)
         if index_streams is None:
-            index_streams = self.auto_streams(batch, bag)
+            index_streams = self.auto_streams(batch, bag, T)
         n_side = max(1, int(index_streams))
         if every is None:
             every = self.auto_every(T, batch, bag, n_side)
@@ -278,9 +328,25 @@ class PipelinedStep:
         # call costs more host time than the launch it is needed for)
         self.main = torch.cuda.current_stream(dev)
         self.main_handle = B.stream_handle(self.main)
-        # index work of this stream's batches done up to batch ... (one per index stream)
-        self.indexed = [self._Marks() for _ in self.sides]
-        self.trained = self._Marks()      # main stream: update done up to batch ...
+        # With issue_thread the index work is enqueued by a host thread of the library
+        # (ss_issue_queue): a kernel launch costs the host about 3 us, and where the
+        # kernels of a batch are short (one huge table; hot rows frozen) one host thread
+        # cannot enqueue eleven of them as fast as the GPU finishes them.
+        if issue_thread is None:         # where the index work is many tiny launches
+            issue_thread = n_side >= 3
+        self.queue = B.IssueQueue() if issue_thread else None
+        self._last_ticket = 0
+        if self.queue is not None:
+            for s in self.sets:
+                s.index = self.queue.prepared_index_batch(
+                    self.tables, batch, bag, self.alpha, s.skip_mask, s.kept_ids, s.n_kept,
+                    s.idx_c, s.ws_filter, s.ws_backward)
+            self.indexed = [self._QueueMarks(self.queue, True) for _ in self.sides]
+            self.trained = self._QueueMarks(self.queue, False)
+        else:
+            # index work of this stream's batches done up to batch ... (one per index stream)
+            self.indexed = [self._Marks() for _ in self.sides]
+            self.trained = self._Marks()      # main stream: update done up to batch ...
         self.submitted = 0        # batches handed to submit()
         self.issued = 0           # ... whose index work is enqueued
         self.forwarded = 0        # batches whose forward() was enqueued
@@ -288,6 +354,19 @@ class PipelinedStep:
         self.held_back = []       # batches waiting for a detect pass before them
         self.last_detect = -1     # last batch that ended with a detect pass
         self.have_snapshot = False
+
+    def flush(self) -> None:
+        """With issue_thread: returns once every submitted batch whose index work was
+        handed to the issue thread has been enqueued on its stream, so that a device
+        synchronisation after it covers that work.  A no-op otherwise."""
+        if self.queue is not None and self._last_ticket:
+            self.queue.wait_issued(self._last_ticket)
+
+    def close(self) -> None:
+        """Stops the issue thread (if any); the object must not be used afterwards."""
+        if self.queue is not None:
+            self.queue.close()
+            self.queue = None
 
     # what the batch in flight produced
     def _cur(self) -> "PipelinedStep._Set":
@@ -333,19 +412,25 @@ class PipelinedStep:
         j = k % len(self.sides)
         side, handle = self.sides[j], self.side_handles[j]
         if ready is not None:
-            side.wait_event(ready)
+            if self.queue is not None:
+                self.queue.wait_event(C.c_void_p(ready.cuda_event), handle)
+            else:
+                side.wait_event(ready)
         # the set's previous batch must be over, and so must the last detect pass
         need = max(k - len(self.sets), self.last_detect)
-        if need >= 0 and not self.trained.cover(j, side, need):
-            self.trained.record(self.main, self.it - 1)
-            assert self.trained.cover(j, side, need)
+        if need >= 0 and not self.trained.cover(j, side, handle, need):
+            self.trained.record(self.main, self.main_handle, self.it - 1)
+            assert self.trained.cover(j, side, handle, need)
         s.idx = idx
-        s.filter(idx, handle)
-        s.group(handle)
+        if self.queue is not None:
+            self._last_ticket = s.index(idx, handle)
+        else:
+            s.filter(idx, handle)
+            s.group(handle)
         self.issued += 1
         # every `every`-th batch of this stream
         if (k // len(self.sides) + 1) % self.every == 0:
-            self.indexed[j].record(side, k)
+            self.indexed[j].record(side, handle, k)
 
     def forward(self) -> torch.Tensor:
         """Pooled lookup of the oldest submitted batch; returns the pooled tensor."""
@@ -355,11 +440,11 @@ class PipelinedStep:
                                "previous batch finished")
         s = self.sets[k % len(self.sets)]
         j = k % len(self.sides)
-        if not self.indexed[j].cover(0, self.main, k):
+        if not self.indexed[j].cover(0, self.main, self.main_handle, k):
             # on demand: this stream's last issued batch is the last one congruent to j
             last = self.issued - 1 - (self.issued - 1 - j) % len(self.sides)
-            self.indexed[j].record(self.sides[j], last)
-            assert self.indexed[j].cover(0, self.main, k)
+            self.indexed[j].record(self.sides[j], self.side_handles[j], last)
+            assert self.indexed[j].cover(0, self.main, self.main_handle, k)
         self.forwarded += 1
         s.lookup(self.main_handle)
         return self.pooled
@@ -383,7 +468,7 @@ class PipelinedStep:
             self.last_detect = k
         self.it += 1
         if self.it % self.every == 0:
-            self.trained.record(main, k)
+            self.trained.record(main, self.main_handle, k)
         # batches that waited for this batch's detect pass
         while self.held_back and not self._boundary_in(self.it, self.issued):
             idx, ready = self.held_back.pop(0)

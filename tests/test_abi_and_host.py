@@ -261,7 +261,8 @@ def test_pipelined_step_picks_its_event_spacing_from_the_ring_size():
     of 3 * every * streams sets would outgrow their share of the memory-side cache."""
     from paper_2404_04270_amd.step import PipelinedStep as P
     assert P.auto_streams(8192, 1) == 1 and P.auto_streams(16384, 1) == 1
-    assert P.auto_streams(65536, 1) == 2 and P.auto_streams(4096, 20) == 2
+    assert P.auto_streams(65536, 1, 1) == 3 and P.auto_streams(4096, 20, 8) == 2
+    assert P.auto_streams(65536, 1, 8) == 2 and P.auto_streams(20000, 1, 1) == 3
     assert P.auto_every(26, 8192, 1, 1) == 8         # 3.4 MB of lists per batch
     assert P.auto_every(1, 65536, 1, 2) == 8
     assert P.auto_every(8, 4096, 20, 1) == 2         # 10.5 MB per batch
@@ -271,3 +272,23 @@ def test_pipelined_step_picks_its_event_spacing_from_the_ring_size():
         lists = 16 * T * ((b * L + 2047) // 2048) * 2048
         assert e in (2, 4, 8) and (e == 2 or 3 * e * n * lists <= P.RING_BYTES)
         assert e == 8 or 3 * 2 * e * n * lists > P.RING_BYTES      # the largest that fits
+
+
+def test_issue_queue_calls_validate_on_the_host(lib):
+    lib.ss_last_error.restype = C.c_char_p
+    for n in ("ss_issue_index_batch", "ss_issue_wait_event", "ss_issue_record_event",
+              "ss_issue_wait", "ss_event_record", "ss_stream_wait_event", "ss_event_create",
+              "ss_issue_queue_create", "ss_issue_queue_destroy", "ss_event_destroy"):
+        getattr(lib, n).restype = C.c_int32
+    ok = C.c_void_p(256)               # never dereferenced: every call below is rejected
+    assert lib.ss_issue_index_batch(None, None, ok, 8, 1, 1, ok, ok, ok, ok, ok, C.c_size_t(256),
+                                    ok, C.c_size_t(256), None, None) != 0
+    assert b"queue is NULL" in lib.ss_last_error()
+    assert lib.ss_issue_wait_event(None, ok, None, None) != 0
+    assert lib.ss_issue_record_event(None, ok, None, None) != 0
+    assert lib.ss_issue_wait(None, C.c_uint64(1)) != 0
+    assert lib.ss_event_record(None, None) != 0 and b"event is NULL" in lib.ss_last_error()
+    assert lib.ss_stream_wait_event(None, None) != 0
+    assert lib.ss_event_create(None) != 0
+    assert lib.ss_issue_queue_create(None) != 0
+    assert lib.ss_issue_queue_destroy(None) == 0 and lib.ss_event_destroy(None) == 0

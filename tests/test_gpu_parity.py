@@ -344,7 +344,8 @@ def test_forward_grouped_equals_forward_plus_prepare(B, dev, T, R, D, Bc, L):
 
 # ------------------------------------------------------- whole protocol
 def run_lockstep(B, dev, cfg, n_iters, threshold, n_hot=None, overlap=False,
-                 grouped_forward=False, pipelined=False, max_ahead=10 ** 9, index_streams=1):
+                 grouped_forward=False, pipelined=False, max_ahead=10 ** 9, index_streams=1,
+                 issue_thread=False):
     """Oracle and GPU side by side; returns the number of borderline overrides."""
     from paper_2404_04270_amd.step import EmbeddingStep, PipelinedStep
     w = wl.Workload(cfg)
@@ -355,7 +356,7 @@ def run_lockstep(B, dev, cfg, n_iters, threshold, n_hot=None, overlap=False,
     if pipelined:
         gpu = PipelinedStep(to_dev(W0, dev), to_dev(hot, dev), cfg.batch, cfg.bag,
                             cfg.lr, threshold, cfg.snapshot_every, every=pipelined,
-                            index_streams=index_streams)
+                            index_streams=index_streams, issue_thread=issue_thread)
         idx_dev = torch.from_numpy(idx).to(dev)          # resident before any submit
         torch.cuda.synchronize()
         ahead = 0
@@ -409,6 +410,8 @@ def run_lockstep(B, dev, cfg, n_iters, threshold, n_hot=None, overlap=False,
         np.testing.assert_allclose(gpu.tables.weights[t].cpu().numpy(), ref.W[t],
                                    rtol=RTOL, atol=ATOL)
     n_stale = sum(int(np.unpackbits(b.view(np.uint8)).sum()) for b in ref.bits)
+    if pipelined:
+        gpu.close()
     return dict(overrides=overrides, skipped=skipped, detects=detects, stale=n_stale)
 
 
@@ -473,6 +476,28 @@ def test_protocol_pipelined_over_several_index_streams(B, dev, streams, every, a
     s = run_lockstep(B, dev, cfg, 60, cfg.threshold, pipelined=every, max_ahead=ahead,
                      index_streams=streams)
     assert s["detects"] == 60 // 7 - 1 and s["overrides"] == 0
+
+
+@pytest.mark.parametrize("streams,every,ahead", [(1, 1, 10 ** 9), (1, 4, 10 ** 9), (2, 2, 10 ** 9),
+                                                 (3, 1, 2), (2, 4, 3)])
+def test_protocol_pipelined_through_the_issue_thread(B, dev, streams, every, ahead):
+    """The same lock-step runs with the index work enqueued by the library's own host
+    thread (ss_issue_queue): bit-identical index results, weights within tolerance."""
+    cfg = wl.CONFIGS[1].scaled(snapshot_every=7)
+    s = run_lockstep(B, dev, cfg, 60, cfg.threshold, pipelined=every, max_ahead=ahead,
+                     index_streams=streams, issue_thread=True)
+    assert s["detects"] == 60 // 7 - 1 and s["overrides"] == 0
+
+
+def test_protocol_issue_thread_skips_and_multihot(B, dev):
+    cfg = wl.CONFIGS[1].scaled(zipf_alpha=1.6, num_tables=3, snapshot_every=3)
+    s = run_lockstep(B, dev, cfg, 40, math.inf, pipelined=2, issue_thread=True)
+    assert s["stale"] == cfg.num_tables * cfg.hot_rows and s["skipped"] > 0
+    cfg = wl.CONFIGS[4].scaled(rows=20000, batch=256, snapshot_every=5, hot_frac=0.005,
+                               threshold=2e-3)
+    s = run_lockstep(B, dev, cfg, 24, cfg.threshold, pipelined=3, index_streams=2,
+                     issue_thread=True)
+    assert s["detects"] == 3
 
 
 def test_pipelined_step_refuses_calls_out_of_order(B, dev):
