@@ -284,6 +284,16 @@ class PipelinedStep:
             return 1
         return 3 if num_tables * ((lookups + 2047) // 2048) < 128 else 2
 
+    @staticmethod
+    def auto_issue_thread(T: int, batch: int, bag: int, n_side: int) -> bool:
+        """Whether the index work is enqueued by the library's issue thread: where a
+        batch is a string of launches at their latency floor, so that the host, not
+        the GPU, sets the pace.  That is the three-stream case above, and batches of
+        at most 65536 lookups over all tables (26 tables x 2048 lookups: 21 against
+        28 us per step).  Larger shapes gain nothing from it (26 x 8192: 49.8 us
+        either way)."""
+        return n_side >= 3 or T * batch * bag <= 65536
+
     def __init__(self, weights: Sequence[torch.Tensor],
                  hot_ids: Sequence[torch.Tensor], batch: int, bag: int,
                  lr: float, threshold: float, snapshot_every: int,
@@ -332,8 +342,8 @@ class PipelinedStep:
         # (ss_issue_queue): a kernel launch costs the host about 3 us, and where the
         # kernels of a batch are short (one huge table; hot rows frozen) one host thread
         # cannot enqueue eleven of them as fast as the GPU finishes them.
-        if issue_thread is None:         # where the index work is many tiny launches
-            issue_thread = n_side >= 3
+        if issue_thread is None:
+            issue_thread = self.auto_issue_thread(T, batch, bag, n_side)
         self.queue = B.IssueQueue() if issue_thread else None
         self._last_ticket = 0
         if self.queue is not None:

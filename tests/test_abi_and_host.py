@@ -263,6 +263,8 @@ def test_pipelined_step_picks_its_event_spacing_from_the_ring_size():
     assert P.auto_streams(8192, 1) == 1 and P.auto_streams(16384, 1) == 1
     assert P.auto_streams(65536, 1, 1) == 3 and P.auto_streams(4096, 20, 8) == 2
     assert P.auto_streams(65536, 1, 8) == 2 and P.auto_streams(20000, 1, 1) == 3
+    assert P.auto_issue_thread(26, 2048, 1, 1) and P.auto_issue_thread(1, 65536, 1, 3)
+    assert not P.auto_issue_thread(26, 8192, 1, 1) and not P.auto_issue_thread(8, 4096, 20, 2)
     assert P.auto_every(26, 8192, 1, 1) == 8         # 3.4 MB of lists per batch
     assert P.auto_every(1, 65536, 1, 2) == 8
     assert P.auto_every(8, 4096, 20, 1) == 2         # 10.5 MB per batch
