@@ -294,3 +294,12 @@ def test_issue_queue_calls_validate_on_the_host(lib):
     assert lib.ss_event_create(None) != 0
     assert lib.ss_issue_queue_create(None) != 0
     assert lib.ss_issue_queue_destroy(None) == 0 and lib.ss_event_destroy(None) == 0
+
+
+def test_issue_queue_needs_a_device():
+    import torch
+    from paper_2404_04270_amd import binding
+    if torch.cuda.is_available():
+        pytest.skip("a device is present: creation succeeds (covered by the GPU tests)")
+    with pytest.raises(binding.SlipstreamError, match="no current device"):
+        binding.IssueQueue()
