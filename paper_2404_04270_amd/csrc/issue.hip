@@ -228,7 +228,11 @@ int32_t ss_event_create(void **event)
 {
     if (!event) return fail(SS_ERR_INVALID_ARG, "ss_event_create: event is NULL");
     hipEvent_t e;
-    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess)
+    // Device-scope release: these events order streams of one device.  The default
+    // (a system-scope fence, for the host's benefit) writes caches back and
+    // invalidates them at every record, which the kernels that follow pay for.
+    if (hipEventCreateWithFlags(&e, hipEventDisableTiming | hipEventReleaseToDevice) !=
+        hipSuccess)
         return fail(SS_ERR_HIP, "ss_event_create: hipEventCreateWithFlags failed");
     *event = e;
     return SS_OK;
