@@ -183,18 +183,20 @@ class PipelinedStep:
 
     class _Marks:
         """Events of one stream, each with the last batch it covers, and what each
-        stream that waits on them already knows."""
+        stream that waits on them already knows.  The events are the library's
+        (device-scope release), recorded and waited for by the calling thread."""
 
         def __init__(self):
             self.recorded = []        # (covers_up_to_batch, event), ascending
+            self.spare = []           # events of marks that were dropped, for re-use
             self.known = {}           # waiting stream (by position) -> batches <= this are done
 
         def record(self, stream, handle, covers: int) -> None:
-            ev = torch.cuda.Event()
-            ev.record(stream)
+            ev = self.spare.pop() if self.spare else B.ss_event_create()
+            B.IssueQueue.record_now(ev, handle)
             self.recorded.append((covers, ev))
             if len(self.recorded) > 64:
-                del self.recorded[0]
+                self.spare.append(self.recorded.pop(0)[1])
 
         def cover(self, waiter: int, waiting_stream, waiting_handle, batch: int) -> bool:
             """Makes waiting_stream wait until `batch` is done, if it does not know yet.
@@ -203,10 +205,17 @@ class PipelinedStep:
                 return True
             for covers, ev in self.recorded:
                 if covers >= batch:
-                    waiting_stream.wait_event(ev)
+                    B.IssueQueue.wait_now(waiting_handle, ev)
                     self.known[waiter] = covers
                     return True
             return False
+
+        def close(self) -> None:
+            for _, ev in self.recorded:
+                B.ss_event_destroy(ev)
+            for ev in self.spare:
+                B.ss_event_destroy(ev)
+            self.recorded, self.spare = [], []
 
     class _QueueMarks:
         """The same when the index streams are fed by the library's issue thread.
@@ -377,6 +386,9 @@ class PipelinedStep:
         if self.queue is not None:
             self.queue.close()
             self.queue = None
+        else:
+            for m in self.indexed + [self.trained]:
+                m.close()
 
     # what the batch in flight produced
     def _cur(self) -> "PipelinedStep._Set":
