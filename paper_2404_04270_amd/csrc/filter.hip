@@ -101,8 +101,8 @@ __global__ __launch_bounds__(kWG) void filter_compact_kernel(
     int32_t *__restrict__ kept_ids, int32_t *__restrict__ n_kept,
     int32_t *__restrict__ idx_c)
 {
-    // grid: x = tile of 256 samples, y = table.  Every (x, y) workgroup repeats
-    // the cheap ranking of tile x and copies the index rows of table y only.
+    // grid: x = tile of 256 samples, y = table, z = part of the tile's rows.  Every
+    // workgroup repeats the cheap ranking of tile x and copies index rows of table y.
     // block_kept holds per_tile counts for every tile (one per workgroup of the
     // flag kernel).
     __shared__ int s_red[kWG / 64];
@@ -130,10 +130,11 @@ __global__ __launch_bounds__(kWG) void filter_compact_kernel(
         nk += s_wbase[w];
     }
     if (keep) {
-        if (t == 0) kept_ids[base + wbase + before] = b;
+        if (t == 0 && blockIdx.z == 0) kept_ids[base + wbase + before] = b;
         s_list[wbase + before] = b;
     }
-    if (t == 0 && blockIdx.x == gridDim.x - 1 && tid == 0) *n_kept = base + nk;
+    if (t == 0 && blockIdx.z == 0 && blockIdx.x == gridDim.x - 1 && tid == 0)
+        *n_kept = base + nk;
     __syncthreads();
 
     // idx_c[t][base + k][:] = idx[t][s_list[k]][:]
@@ -142,8 +143,11 @@ __global__ __launch_bounds__(kWG) void filter_compact_kernel(
     if (L == 1) {
         if (tid < nk) dst[tid] = src[s_list[tid]];
     } else {
+        // long bags: gridDim.z workgroups share the rows of a tile (each repeats the
+        // cheap ranking above), 4 * kWG elements at a time
         const int total = nk * L;
-        for (int e0 = tid; e0 < total; e0 += 4 * kWG) {
+        for (int e0 = tid + (int)blockIdx.z * 4 * kWG; e0 < total;
+             e0 += (int)gridDim.z * 4 * kWG) {
             int32_t v[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -200,7 +204,9 @@ int32_t launch_filter(const ss_tables *tb, const int32_t *idx, int B, int L,
     ProfScope prof("filter_compact_kernel", s);
     // the last tile may be covered by fewer workgroups of the flag kernel: a tile
     // before it is always covered by exactly kWG / samples of them
-    launch(filter_compact_kernel, dim3(tiles, tb->num_tables),
+    // one workgroup per 1024 index words of a tile's rows, at most eight
+    const int parts = L == 1 ? 1 : (L + 3) / 4 > 8 ? 8 : (L + 3) / 4;
+    launch(filter_compact_kernel, dim3(tiles, tb->num_tables, parts),
                        dim3(kWG), s, idx, B, L, skip_mask, block_kept, kWG / samples,
                        kept_ids, n_kept, idx_c);
     return check_launch("ss_filter_batch");
