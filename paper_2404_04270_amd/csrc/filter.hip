@@ -18,8 +18,8 @@
 
 namespace ss {
 
-// LANES lanes per sample, 1024 / LANES samples per workgroup.  A chunk of lookups
-// costs two round trips to memory (indices, then bitmap words) however many of
+// LANES lanes per sample, flag_wg(LANES) / LANES samples per workgroup.  A chunk
+// of lookups costs two round trips to memory (indices, then bitmap words) however many of
 // them are stale.  The first chunk is one lookup per lane: while few rows are
 // stale that settles almost every sample, and the kernel reads no more than
 // that.  Later chunks take eight per lane.  The host picks LANES so that two
@@ -28,14 +28,19 @@ namespace ss {
 // a sample that needs nearly all of them (160 lookups per sample: 16 us with
 // four lanes and six chunks, 7 us with 32 lanes and two).
 constexpr int kFlagProbes = 8;                   // lookups per lane and chunk
-constexpr int kFlagWG = 1024;
+// Threads per workgroup: 256 (1024 with 64 lanes per sample).  Beside the training
+// kernels a 1024-thread workgroup waits for a compute unit with sixteen free
+// wavefront slots: at 32 lanes per sample the kernel then took 13-15 us instead of
+// the 4 us it takes alone.
+constexpr int flag_wg(int lanes) { return lanes <= 32 ? 256 : 1024; }
 
 template <int LANES>
-__global__ __launch_bounds__(kFlagWG) void filter_flag_kernel(
+__global__ __launch_bounds__(flag_wg(LANES)) void filter_flag_kernel(
     const uint32_t *const *__restrict__ bits, const int32_t *__restrict__ idx,
     int T, int B, int L, int alpha, uint8_t *__restrict__ skip_mask,
     int32_t *__restrict__ block_kept)
 {
+    constexpr int kFlagWG = flag_wg(LANES);
     constexpr int SAMPLES = kFlagWG / LANES;
     const int c = threadIdx.x % LANES;
     const int b = blockIdx.x * SAMPLES + threadIdx.x / LANES;
@@ -173,7 +178,8 @@ static int flag_lanes(int64_t total)
 
 size_t filter_ws_bytes(int T, int B, int L)
 {
-    const int samples = kFlagWG / flag_lanes((int64_t)T * L);
+    const int lanes = flag_lanes((int64_t)T * L);
+    const int samples = flag_wg(lanes) / lanes;
     const size_t blocks = ((size_t)B + samples - 1) / samples;
     return align_up(blocks * sizeof(int32_t), 256);
 }
@@ -183,14 +189,14 @@ int32_t launch_filter(const ss_tables *tb, const int32_t *idx, int B, int L,
                       int32_t *n_kept, int32_t *idx_c, void *ws, hipStream_t s)
 {
     const int lanes = flag_lanes((int64_t)tb->num_tables * L);
-    const int samples = kFlagWG / lanes;             // per workgroup of the flag kernel
+    const int samples = flag_wg(lanes) / lanes;      // per workgroup of the flag kernel
     const int flag_blocks = (B + samples - 1) / samples;
     const int tiles = (B + kWG - 1) / kWG;
     int32_t *block_kept = static_cast<int32_t *>(ws);
     {
         ProfScope prof("filter_flag_kernel", s);
 #define SS_FLAG(LANES_)                                                            \
-    launch(filter_flag_kernel<LANES_>, dim3(flag_blocks), dim3(kFlagWG), s,        \
+    launch(filter_flag_kernel<LANES_>, dim3(flag_blocks), dim3(flag_wg(LANES_)), s, \
            tb->stale_bits, idx, tb->num_tables, B, L, alpha, skip_mask, block_kept)
         switch (lanes) {
         case 4: SS_FLAG(4); break;
