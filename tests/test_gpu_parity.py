@@ -293,10 +293,12 @@ def test_backward_update_matches_oracle(B, dev, T, R, D, Bc, L, nv, stale, za):
         assert torch.equal(tb2.weights[t], tb.weights[t])
 
 
-def test_backward_closed_form_heavy_row(B, dev):
-    # one row hit by every lookup of a large batch: dW = -lr * L * sum_j g_j
-    T, R, D, Bc, L = 1, 64, 64, 20000, 2
-    W = [np.ones((R, D), np.float32)]
+@pytest.mark.parametrize("T", [1, 4])      # 4: enough workgroups for the fixup to take several each
+def test_backward_closed_form_heavy_row(B, dev, T):
+    # one row hit by every lookup of a large batch: dW = -lr * L * sum_j g_j; the run
+    # covers more workgroups than the fixup stages lead states for in one go
+    R, D, Bc, L = 64, 64, 20000, 2
+    W = [np.ones((R, D), np.float32) for _ in range(T)]
     idx = np.full((T, Bc, L), 17, dtype=np.int32)
     rng = np.random.default_rng(450)
     grad = rng.normal(0, 0.01, (T, Bc, D)).astype(np.float32)
@@ -304,10 +306,11 @@ def test_backward_closed_form_heavy_row(B, dev):
     ws = torch.empty(B.ss_backward_workspace_bytes(T, Bc, L, D), dtype=torch.uint8, device=dev)
     B.ss_embbag_backward_update(tb, torch.from_numpy(idx).to(dev), None,
                                 torch.from_numpy(grad).to(dev), 0.5, ws)
-    got = tb.weights[0].cpu().numpy()
-    exact = 1.0 - 0.5 * L * grad[0].astype(np.float64).sum(axis=0)
-    np.testing.assert_allclose(got[17], exact, rtol=RTOL, atol=ATOL)
-    assert np.all(np.delete(got, 17, axis=0) == 1.0)
+    for t in range(T):
+        got = tb.weights[t].cpu().numpy()
+        exact = 1.0 - 0.5 * L * grad[t].astype(np.float64).sum(axis=0)
+        np.testing.assert_allclose(got[17], exact, rtol=RTOL, atol=ATOL)
+        assert np.all(np.delete(got, 17, axis=0) == 1.0)
 
 
 @pytest.mark.parametrize("T,R,D,Bc,L", [(3, 5000, 64, 3000, 1), (26, 1000000, 64, 8192, 1),
