@@ -293,6 +293,28 @@ def test_backward_update_matches_oracle(B, dev, T, R, D, Bc, L, nv, stale, za):
         assert torch.equal(tb2.weights[t], tb.weights[t])
 
 
+@pytest.mark.parametrize("T,D,Bc,L,per_row", [(4, 64, 16000, 1, 600), (8, 128, 3000, 20, 700),
+                                             (5, 64, 12000, 1, 520), (3, 16, 30000, 1, 2100)])
+def test_backward_many_runs_that_cross_several_workgroups(B, dev, T, D, Bc, L, per_row):
+    """Rows with `per_row` lookups each, side by side in the grouped list: every run
+    leaves its workgroup, most cover about nine of them (just past what a lane group
+    of the fixup stage finishes alone), so that one fixup workgroup queues several."""
+    rng = np.random.default_rng(455 + T)
+    R = 5000
+    W = rand_tables(rng, T, R, D)
+    flat = (np.arange(Bc * L) // per_row).astype(np.int32)
+    idx = np.stack([rng.permutation(flat).reshape(Bc, L) + 3 * t for t in range(T)]).astype(np.int32)
+    grad = rng.normal(0, 0.01, (T, Bc, D)).astype(np.float32)
+    ref = [w.copy() for w in W]
+    oracle.embbag_backward_update(ref, None, idx, grad, 0.01, None)
+    tb = B.Tables(to_dev(W, dev))
+    ws = torch.empty(B.ss_backward_workspace_bytes(T, Bc, L, D), dtype=torch.uint8, device=dev)
+    B.ss_embbag_backward_update(tb, torch.from_numpy(idx).to(dev), None,
+                                torch.from_numpy(grad).to(dev), 0.01, ws)
+    for t in range(T):
+        np.testing.assert_allclose(tb.weights[t].cpu().numpy(), ref[t], rtol=RTOL, atol=ATOL)
+
+
 @pytest.mark.parametrize("T", [1, 4])      # 4: enough workgroups for the fixup to take several each
 def test_backward_closed_form_heavy_row(B, dev, T):
     # one row hit by every lookup of a large batch: dW = -lr * L * sum_j g_j; the run
