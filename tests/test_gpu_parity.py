@@ -85,6 +85,9 @@ def random_bits(rng, T, R, frac):
     (1, 900, 8, 300, 7, None),       # two lanes per row
     (1, 900, 4, 300, 17, None),      # one lane per row
     (2, 3000, 128, 64, 16, None),    # exactly one piece
+    (11, 3000, 64, 300, 5, None),    # multi-hot: eight tables pinned to XCDs, three spread
+    (16, 2000, 32, 200, 20, 150),    # ... all pinned, two tables per XCD
+    (26, 1000, 16, 150, 3, None),    # ... 24 pinned, two spread
 ])
 def test_forward_matches_oracle(B, dev, T, R, D, Bc, L, nv):
     rng = np.random.default_rng(100 + D + L)
