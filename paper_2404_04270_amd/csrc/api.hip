@@ -276,11 +276,10 @@ int32_t ss_embbag_forward_grouped(const ss_tables *tables, const int32_t *idx,
         return fail(SS_ERR_INVALID_ARG, "%s: out is not 16-byte aligned", who);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (can_fuse_forward_group(tables, Bcap, L)) {
-        uint32_t *keys, *vals;
+        uint2 *ent;
         int NP;
-        backward_first_buffers(tables->num_tables, Bcap, L, tables->dim, bwd_ws, &keys,
-                               &vals, &NP);
-        return launch_forward_group(tables, idx, Bcap, n_valid, out, keys, vals, NP, s);
+        backward_first_buffers(tables->num_tables, Bcap, L, tables->dim, bwd_ws, &ent, &NP);
+        return launch_forward_group(tables, idx, Bcap, n_valid, out, ent, NP, s);
     }
     rc = launch_forward(tables, idx, Bcap, L, n_valid, out, s);
     if (rc) return rc;

@@ -63,12 +63,10 @@ template <int ITEMS, bool PACKED>
 __global__ __launch_bounds__(1024) void class_sort_kernel(
     const int32_t *__restrict__ idx, int Bcap, int L,
     const int32_t *__restrict__ n_valid, const uint32_t *const *__restrict__ bits,
-    int key_bits, int class_bits, int val_bits, uint32_t *__restrict__ out_keys,
-    uint32_t *__restrict__ out_vals, int NP)
+    int key_bits, int class_bits, int val_bits, uint2 *__restrict__ out_ent, int NP)
 {
     class_sort_body<ITEMS, PACKED>(blockIdx.x, blockIdx.y, idx, Bcap, L, n_valid, bits,
-                                   key_bits, class_bits, val_bits, out_keys, out_vals,
-                                   NP);
+                                   key_bits, class_bits, val_bits, out_ent, NP);
 }
 
 // ---------------------------------------------------------------------------
@@ -77,16 +75,19 @@ __global__ __launch_bounds__(1024) void class_sort_kernel(
 // ---------------------------------------------------------------------------
 template <bool FIRST>
 __device__ __forceinline__ void rs_load(const int32_t *__restrict__ ip, int L, int n,
-                                        const uint32_t *__restrict__ in_keys,
-                                        const uint32_t *__restrict__ in_vals, int pos,
-                                        uint32_t &key, uint32_t &val)
+                                        const uint2 *__restrict__ in_ent, bool want_val,
+                                        int pos, uint32_t &key, uint32_t &val)
 {
     if (FIRST) {
         key = pos < n ? (uint32_t)ip[pos] : kNoRow;
         val = pos < n ? (uint32_t)(L == 1 ? pos : pos / L) : 0u;
+    } else if (want_val) {
+        const uint2 e = in_ent[pos];
+        key = e.x;
+        val = e.y;
     } else {
-        key = in_keys[pos];
-        val = in_vals ? in_vals[pos] : 0u;
+        key = in_ent[pos].x;
+        val = 0u;
     }
 }
 
@@ -94,7 +95,7 @@ template <bool FIRST>
 __global__ __launch_bounds__(kRsHistThreads) void rs_hist_kernel(
     const int32_t *__restrict__ idx, int Bcap, int L,
     const int32_t *__restrict__ n_valid, const uint32_t *const *__restrict__ bits,
-    const uint32_t *__restrict__ in_keys, int NP, int shift, int nb,
+    const uint2 *__restrict__ in_ent, int NP, int shift, int nb,
     uint32_t *__restrict__ hist, int tiles)
 {
     __shared__ uint32_t s_hist[kRsMaxDig];
@@ -104,13 +105,13 @@ __global__ __launch_bounds__(kRsHistThreads) void rs_hist_kernel(
     const uint32_t dmask = ndig - 1;
     const int32_t *__restrict__ ip = idx + (int64_t)t * Bcap * L;
     const auto bt = as_global((FIRST && bits) ? bits[t] : nullptr);
-    const uint32_t *__restrict__ kin = FIRST ? nullptr : in_keys + (int64_t)t * NP;
+    const uint2 *__restrict__ ein = FIRST ? nullptr : in_ent + (int64_t)t * NP;
     for (int i = tid; i < ndig; i += kRsHistThreads) s_hist[i] = 0;
     __syncthreads();
     uint32_t key[kRsHistItems], val;
 #pragma unroll
     for (int r = 0; r < kRsHistItems; ++r)
-        rs_load<FIRST>(ip, L, n, kin, nullptr, tile * kPad + r * kRsHistThreads + tid,
+        rs_load<FIRST>(ip, L, n, ein, false, tile * kPad + r * kRsHistThreads + tid,
                        key[r], val);
     if (FIRST) drop_stale(bt, key);
 #pragma unroll
@@ -127,8 +128,7 @@ template <bool FIRST>
 __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
     const int32_t *__restrict__ idx, int Bcap, int L,
     const int32_t *__restrict__ n_valid, const uint32_t *const *__restrict__ bits,
-    const uint32_t *__restrict__ in_keys, const uint32_t *__restrict__ in_vals,
-    uint32_t *__restrict__ out_keys, uint32_t *__restrict__ out_vals, int NP,
+    const uint2 *__restrict__ in_ent, uint2 *__restrict__ out_ent, int NP,
     int shift, int nb, const uint32_t *__restrict__ hist, int tiles)
 {
     constexpr int NW = kRsThreads / 64;
@@ -142,13 +142,12 @@ __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
     const uint32_t dmask = ndig - 1;
     const int32_t *__restrict__ ip = idx + (int64_t)t * Bcap * L;
     const auto bt = as_global((FIRST && bits) ? bits[t] : nullptr);
-    const uint32_t *__restrict__ kin = FIRST ? nullptr : in_keys + (int64_t)t * NP;
-    const uint32_t *__restrict__ vin = FIRST ? nullptr : in_vals + (int64_t)t * NP;
+    const uint2 *__restrict__ ein = FIRST ? nullptr : in_ent + (int64_t)t * NP;
 
     uint32_t key[kRsItems], val[kRsItems], rank[kRsItems];
 #pragma unroll
     for (int r = 0; r < kRsItems; ++r)   // wavefront w owns a contiguous part of the tile
-        rs_load<FIRST>(ip, L, n, kin, vin,
+        rs_load<FIRST>(ip, L, n, ein, true,
                        tile * kPad + wave * (kRsItems * 64) + r * 64 + lane, key[r],
                        val[r]);
     if (FIRST) drop_stale(bt, key);
@@ -241,8 +240,7 @@ __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
     for (int r = 0; r < kRsItems; ++r) {
         const uint32_t d = (key[r] >> shift) & dmask;
         const int64_t p = (int64_t)t * NP + s_cnt[wave * ndig + d] + rank[r];
-        out_keys[p] = key[r];
-        out_vals[p] = val[r];
+        out_ent[p] = make_uint2(key[r], val[r]);      // one 8-byte store, not two of 4
     }
 }
 
@@ -272,8 +270,8 @@ __device__ __forceinline__ const f4 *grad_ptr(const f4 *table_base, uint32_t smp
 
 template <int G, int S, bool FULL>
 __global__ __launch_bounds__(kApplyWG) void apply_kernel(
-    float *const *__restrict__ weights, const uint32_t *__restrict__ keys,
-    const uint32_t *__restrict__ vals, int NP, const float *__restrict__ grad,
+    float *const *__restrict__ weights, const uint2 *__restrict__ ent, int NP,
+    const float *__restrict__ grad,
     int Bcap, int D4, float lr, int wgs_per_table, int pinned_blocks,
     bool stream_grads, uint32_t *__restrict__ meta_trail_row,
     uint8_t *__restrict__ meta_lead_state, f4 *__restrict__ part_lead,
@@ -290,8 +288,7 @@ __global__ __launch_bounds__(kApplyWG) void apply_kernel(
     // in the order of the sorted rows; it only stays in L2 if the table has one
     block_to_table_pinned(blockIdx.x, wgs_per_table, pinned_blocks, t, wg);
     const int tid = threadIdx.x, g = tid / G, c = tid % G;
-    const uint32_t *__restrict__ kp = keys + (int64_t)t * NP;
-    const uint32_t *__restrict__ vp = vals + (int64_t)t * NP;
+    const uint2 *__restrict__ ep = ent + (int64_t)t * NP;       // (row, sample) pairs
     const auto W = as_global(reinterpret_cast<f4 *>(weights[t]));
     const f4 *__restrict__ G4 =
         reinterpret_cast<const f4 *>(grad) + (int64_t)t * Bcap * D4;
@@ -302,16 +299,15 @@ __global__ __launch_bounds__(kApplyWG) void apply_kernel(
 
     uint32_t row[S], smp[S];
 #pragma unroll
-    for (int i = 0; i < S; i += 4) {
-        const uint4 k4 = *reinterpret_cast<const uint4 *>(kp + base + i);
-        const uint4 v4 = *reinterpret_cast<const uint4 *>(vp + base + i);
-        row[i] = k4.x; row[i + 1] = k4.y; row[i + 2] = k4.z; row[i + 3] = k4.w;
-        smp[i] = v4.x; smp[i + 1] = v4.y; smp[i + 2] = v4.z; smp[i + 3] = v4.w;
+    for (int i = 0; i < S; i += 2) {
+        const uint4 e2 = *reinterpret_cast<const uint4 *>(ep + base + i);   // two pairs
+        row[i] = e2.x; smp[i] = e2.y;
+        row[i + 1] = e2.z; smp[i + 1] = e2.w;
     }
-    const uint32_t prev = base > 0 ? kp[base - 1] : kNoPrev;
-    const uint32_t next = base + S < NP ? kp[base + S] : kNoRow;
+    const uint32_t prev = base > 0 ? ep[base - 1].x : kNoPrev;
+    const uint32_t next = base + S < NP ? ep[base + S].x : kNoRow;
     // only the last group looks at it: does its last run come from an earlier workgroup?
-    const uint32_t before_wg = (g == NG - 1 && wg_base > 0) ? kp[wg_base - 1] : kNoPrev;
+    const uint32_t before_wg = (g == NG - 1 && wg_base > 0) ? ep[wg_base - 1].x : kNoPrev;
 
     // Stale and padding lookups carry the sentinel key, the largest there is:
     // they form the last run of the table, which never ends and is never stored.
@@ -580,7 +576,7 @@ __global__ __launch_bounds__(kWG) void fixup_kernel(
 
 struct Layout {
     int NP, tiles, max_wgs;
-    size_t keys0, vals0, keys1, vals1, hist, trail_row, lead_state, part_lead,
+    size_t ent0, ent1, hist, trail_row, lead_state, part_lead,
         part_trail, total;
 };
 
@@ -599,11 +595,9 @@ Layout make_layout(int T, int Bcap, int L, int dim)
         off += align_up(bytes, 256);
         return o;
     };
-    const size_t arr = (size_t)T * y.NP * sizeof(uint32_t);
-    y.keys0 = take(arr);
-    y.vals0 = take(arr);
-    y.keys1 = take(arr);
-    y.vals1 = take(arr);
+    const size_t arr = (size_t)T * y.NP * sizeof(uint2);      // (row, sample) pairs
+    y.ent0 = take(arr);
+    y.ent1 = take(arr);
     y.hist = take((size_t)T * kRsMaxDig * y.tiles * sizeof(uint32_t));
     y.trail_row = take((size_t)T * y.max_wgs * sizeof(uint32_t));
     y.lead_state = take((size_t)T * y.max_wgs);
@@ -640,13 +634,12 @@ size_t backward_ws_bytes(int T, int Bcap, int L, int dim)
     return make_layout(T, Bcap, L, dim).total;
 }
 
-void backward_first_buffers(int T, int Bcap, int L, int dim, void *ws, uint32_t **keys,
-                            uint32_t **vals, int *NP)
+void backward_first_buffers(int T, int Bcap, int L, int dim, void *ws, uint2 **ent,
+                            int *NP)
 {
     const Layout y = make_layout(T, Bcap, L, dim);
     char *w8 = static_cast<char *>(ws);
-    *keys = reinterpret_cast<uint32_t *>(w8 + y.keys0);
-    *vals = reinterpret_cast<uint32_t *>(w8 + y.vals0);
+    *ent = reinterpret_cast<uint2 *>(w8 + y.ent0);
     *NP = y.NP;
 }
 
@@ -665,10 +658,8 @@ int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bca
     const int T = tb->num_tables;
     const Layout y = make_layout(T, Bcap, L, tb->dim);
     char *w8 = static_cast<char *>(ws);
-    uint32_t *keys[2] = {reinterpret_cast<uint32_t *>(w8 + y.keys0),
-                         reinterpret_cast<uint32_t *>(w8 + y.keys1)};
-    uint32_t *vals[2] = {reinterpret_cast<uint32_t *>(w8 + y.vals0),
-                         reinterpret_cast<uint32_t *>(w8 + y.vals1)};
+    uint2 *ent[2] = {reinterpret_cast<uint2 *>(w8 + y.ent0),
+                     reinterpret_cast<uint2 *>(w8 + y.ent1)};
     uint32_t *hist = reinterpret_cast<uint32_t *>(w8 + y.hist);
     const int key_bits = key_bits_for(tb->rows);
     int cur = 0;   // buffer that holds the sorted lists
@@ -679,7 +670,7 @@ int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bca
         ProfScope prof("class_sort_kernel", s);
 #define SS_LDS_SORT(I, P)                                                          \
     launch(class_sort_kernel<I, P>, grid, dim3(1024), s, idx, Bcap, L, n_valid,     \
-           tb->stale_bits, key_bits, cp.class_bits, cp.val_bits, keys[0], vals[0],  \
+           tb->stale_bits, key_bits, cp.class_bits, cp.val_bits, ent[0],            \
            y.NP)
         if (cp.packed) {
             if (cp.items == 2) { SS_LDS_SORT(2, true); }
@@ -708,16 +699,16 @@ int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bca
                                        nullptr, y.NP, shift, nb, hist, y.tiles);
                 else
                     launch(rs_hist_kernel<false>, grid, dim3(kRsHistThreads), s, idx, Bcap, L, n_valid, nullptr,
-                                       keys[in], y.NP, shift, nb, hist, y.tiles);
+                                       ent[in], y.NP, shift, nb, hist, y.tiles);
             }
             ProfScope prof("rs_scatter_kernel", s);
             if (pass == 0)
                 launch(rs_scatter_kernel<true>, grid, dim3(kRsThreads), s, idx, Bcap, L, n_valid, tb->stale_bits, nullptr,
-                                   nullptr, keys[out], vals[out], y.NP, shift, nb,
+                                   ent[out], y.NP, shift, nb,
                                    hist, y.tiles);
             else
-                launch(rs_scatter_kernel<false>, grid, dim3(kRsThreads), s, idx, Bcap, L, n_valid, nullptr, keys[in],
-                                   vals[in], keys[out], vals[out], y.NP, shift, nb,
+                launch(rs_scatter_kernel<false>, grid, dim3(kRsThreads), s, idx, Bcap, L, n_valid, nullptr, ent[in],
+                                   ent[out], y.NP, shift, nb,
                                    hist, y.tiles);
             cur = out;
             shift += nb;
@@ -734,10 +725,8 @@ int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float 
     const int T = tb->num_tables, D4 = tb->dim / 4;
     const Layout y = make_layout(T, Bcap, L, tb->dim);
     char *w8 = static_cast<char *>(ws);
-    uint32_t *keys[2] = {reinterpret_cast<uint32_t *>(w8 + y.keys0),
-                         reinterpret_cast<uint32_t *>(w8 + y.keys1)};
-    uint32_t *vals[2] = {reinterpret_cast<uint32_t *>(w8 + y.vals0),
-                         reinterpret_cast<uint32_t *>(w8 + y.vals1)};
+    uint2 *ent[2] = {reinterpret_cast<uint2 *>(w8 + y.ent0),
+                     reinterpret_cast<uint2 *>(w8 + y.ent1)};
     const int cur = sorted_buffer(y, tb->rows);
 
     const int g = lanes_per_row(tb->dim);
@@ -755,7 +744,7 @@ int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float 
     const int pinned = L > 1 ? (T / 8) * 8 * wgs : 0;
 #define SS_APPLY(S_, F_)                                                           \
     SS_DISPATCH_G(g, launch(                                         \
-                         (apply_kernel<G, S_, F_>), dim3((unsigned)blocks), dim3(kApplyWG), s, tb->weights, keys[cur], vals[cur], y.NP, grad,      \
+                         (apply_kernel<G, S_, F_>), dim3((unsigned)blocks), dim3(kApplyWG), s, tb->weights, ent[cur], y.NP, grad,      \
                          Bcap, D4, lr, wgs, pinned, L == 1, trail_row,  \
                          lead_state,                                               \
                          part_lead, part_trail))

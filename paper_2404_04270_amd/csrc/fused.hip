@@ -20,8 +20,8 @@ __global__ __launch_bounds__(1024) void forward_group_kernel(
     const float *const *__restrict__ weights, const int32_t *__restrict__ idx,
     int Bcap, const int32_t *__restrict__ n_valid, float *__restrict__ out, int D4,
     int tiles_per_table, const uint32_t *const *__restrict__ bits,
-    int key_bits, int class_bits, int val_bits, uint32_t *__restrict__ out_keys,
-    uint32_t *__restrict__ out_vals, int NP, int group_blocks, bool interleave)
+    int key_bits, int class_bits, int val_bits, uint2 *__restrict__ out_ent, int NP,
+    int group_blocks, bool interleave)
 {
     // Roles are interleaved (one grouping workgroup, two gather workgroups, ...)
     // while both last, so that every CU starts with a mix of the two.
@@ -39,8 +39,7 @@ __global__ __launch_bounds__(1024) void forward_group_kernel(
     if (gb >= 0) {
         const int classes = 1 << class_bits;
         class_sort_body<ITEMS, true>(gb % classes, gb / classes, idx, Bcap, 1, n_valid,
-                                     bits, key_bits, class_bits, val_bits, out_keys,
-                                     out_vals, NP);
+                                     bits, key_bits, class_bits, val_bits, out_ent, NP);
     } else {
         forward_onehot_body<G, 1024>(fb, weights, idx, Bcap, n_valid, out, D4,
                                      tiles_per_table);
@@ -58,8 +57,8 @@ bool can_fuse_forward_group(const ss_tables *tb, int Bcap, int L)
 }
 
 int32_t launch_forward_group(const ss_tables *tb, const int32_t *idx, int Bcap,
-                             const int32_t *n_valid, float *out, uint32_t *keys,
-                             uint32_t *vals, int NP, hipStream_t s)
+                             const int32_t *n_valid, float *out, uint2 *ent, int NP,
+                             hipStream_t s)
 {
     const int T = tb->num_tables, D4 = tb->dim / 4;
     int key_bits = 1;
@@ -77,7 +76,7 @@ int32_t launch_forward_group(const ss_tables *tb, const int32_t *idx, int Bcap,
     SS_DISPATCH_G(g, launch(forward_group_kernel<G, I>, dim3((unsigned)blocks),     \
                             dim3(1024), s, tb->weights, idx, Bcap, n_valid, out, D4, \
                             tiles, tb->stale_bits, key_bits, cp.class_bits,   \
-                            cp.val_bits, keys, vals, NP, group_blocks,              \
+                            cp.val_bits, ent, NP, group_blocks,                     \
                             (int64_t)tiles * T >= 2 * (int64_t)group_blocks))
     if (cp.items == 2) { SS_FG(2); }
     else if (cp.items == 4) { SS_FG(4); }

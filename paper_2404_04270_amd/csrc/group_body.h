@@ -77,8 +77,7 @@ template <int ITEMS, bool PACKED>
 __device__ __forceinline__ void class_sort_body(
     int cls, int t, const int32_t *__restrict__ idx, int Bcap, int L,
     const int32_t *__restrict__ n_valid, const uint32_t *const *__restrict__ bits,
-    int key_bits, int class_bits, int val_bits, uint32_t *__restrict__ out_keys,
-    uint32_t *__restrict__ out_vals, int NP)
+    int key_bits, int class_bits, int val_bits, uint2 *__restrict__ out_ent, int NP)
 {
     constexpr int NW = 16, CAP = 1024 * ITEMS;
     __shared__ uint32_t s_keys[CAP];
@@ -200,24 +199,19 @@ __device__ __forceinline__ void class_sort_body(
         __syncthreads();
         shift += nb;
     }
-    uint32_t *__restrict__ ok = out_keys + (int64_t)t * NP;
-    uint32_t *__restrict__ ov = out_vals + (int64_t)t * NP;
+    uint2 *__restrict__ oe = out_ent + (int64_t)t * NP;
     const uint32_t vmask = PACKED ? (1u << val_bits) - 1u : 0u;
     for (uint32_t i = tid; i < m; i += 1024) {
         const uint32_t w = s_keys[i];
-        if (PACKED) {
-            ok[n_below + i] = ((w >> val_bits) << class_bits) | (uint32_t)cls;
-            ov[n_below + i] = w & vmask;
-        } else {
-            ok[n_below + i] = w;
-            ov[n_below + i] = s_vals[i];
-        }
+        if (PACKED)
+            oe[n_below + i] = make_uint2(((w >> val_bits) << class_bits) | (uint32_t)cls,
+                                         w & vmask);
+        else
+            oe[n_below + i] = make_uint2(w, s_vals[i]);
     }
     if (cls == 0)
-        for (uint32_t i = n_real + tid; i < (uint32_t)NP; i += 1024) {
-            ok[i] = kNoRow;
-            ov[i] = 0;
-        }
+        for (uint32_t i = n_real + tid; i < (uint32_t)NP; i += 1024)
+            oe[i] = make_uint2(kNoRow, 0u);
 }
 
 // Host side: how the class sort is configured for a table geometry.

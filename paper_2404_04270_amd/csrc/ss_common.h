@@ -165,12 +165,12 @@ int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float 
 size_t backward_ws_bytes(int T, int Bcap, int L, int dim);
 // Where stage 1 of the backward pass leaves a table's grouped lookups when it
 // takes the one-launch path (buffer 0 of the workspace), and the padded length.
-void backward_first_buffers(int T, int Bcap, int L, int dim, void *ws, uint32_t **keys,
-                            uint32_t **vals, int *NP);
+void backward_first_buffers(int T, int Bcap, int L, int dim, void *ws, uint2 **ent,
+                            int *NP);
 bool can_fuse_forward_group(const ss_tables *tb, int Bcap, int L);
 int32_t launch_forward_group(const ss_tables *tb, const int32_t *idx, int Bcap,
-                             const int32_t *n_valid, float *out, uint32_t *keys,
-                             uint32_t *vals, int NP, hipStream_t s);
+                             const int32_t *n_valid, float *out, uint2 *ent, int NP,
+                             hipStream_t s);
 size_t filter_ws_bytes(int T, int B, int L);
 int32_t launch_sample_drop(int T, int32_t *const *hot_ids, int H, double *const *drift,
                            const int32_t *sidx, int S, int L, int alpha,
