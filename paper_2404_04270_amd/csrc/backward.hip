@@ -4,16 +4,18 @@
 // Three stages, all tables in every launch:
 //
 //  1. SORT the lookups of each table by row id (stable, so equal rows keep the
-//     order "ascending sample, then position in bag").  The payload is the
-//     sample number, which is all the gradient gather needs.
+//     order "ascending sample, then position in bag").  The lists hold
+//     (row, sample) pairs: the sample number is all the gradient gather needs.
 //       - up to 16384 lookups per table: one launch; the table is cut into
 //         classes by the low bits of the row id and a 1024-thread workgroup per
 //         class runs an LSD radix sort on the remaining bits with keys and
-//         payloads in registers and the exchange buffers in LDS (the apply
+//         sample numbers in registers and the exchange buffers in LDS (the apply
 //         stage needs equal rows adjacent, not ascending);
 //       - more: a global LSD radix sort, up to 10 bits per pass, two launches
 //         per pass: per-tile digit histograms, then a stable scatter whose
-//         workgroups each derive their own offsets from the histograms.
+//         workgroups each derive their own offsets from the histograms.  The
+//         first histogram launch also writes the (row, sample) pairs, so every
+//         scatter reads pairs and the bitmap is probed once per lookup.
 //     A lookup whose row is stale is given the sentinel key when the keys are
 //     first read, so it sorts behind all real lookups and costs nothing later.
 //     Ranking inside a wavefront uses ballots: the lanes that hold the same
@@ -95,8 +97,8 @@ template <bool FIRST>
 __global__ __launch_bounds__(kRsHistThreads) void rs_hist_kernel(
     const int32_t *__restrict__ idx, int Bcap, int L,
     const int32_t *__restrict__ n_valid, const uint32_t *const *__restrict__ bits,
-    const uint2 *__restrict__ in_ent, int NP, int shift, int nb,
-    uint32_t *__restrict__ hist, int tiles)
+    const uint2 *__restrict__ in_ent, uint2 *__restrict__ first_ent, int NP, int shift,
+    int nb, uint32_t *__restrict__ hist, int tiles)
 {
     __shared__ uint32_t s_hist[kRsMaxDig];
     const int t = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
@@ -108,12 +110,21 @@ __global__ __launch_bounds__(kRsHistThreads) void rs_hist_kernel(
     const uint2 *__restrict__ ein = FIRST ? nullptr : in_ent + (int64_t)t * NP;
     for (int i = tid; i < ndig; i += kRsHistThreads) s_hist[i] = 0;
     __syncthreads();
-    uint32_t key[kRsHistItems], val;
+    uint32_t key[kRsHistItems], val[kRsHistItems];
 #pragma unroll
     for (int r = 0; r < kRsHistItems; ++r)
         rs_load<FIRST>(ip, L, n, ein, false, tile * kPad + r * kRsHistThreads + tid,
-                       key[r], val);
-    if (FIRST) drop_stale(bt, key);
+                       key[r], val[r]);
+    if (FIRST) {
+        // The first pass turns the index tensor into (row, sample) pairs, with the
+        // sentinel for stale rows and padding, and leaves them for its scatter, which
+        // then needs neither the bitmap probes nor the division by the bag length.
+        drop_stale(bt, key);
+        uint2 *__restrict__ eo = first_ent + (int64_t)t * NP;
+#pragma unroll
+        for (int r = 0; r < kRsHistItems; ++r)
+            eo[tile * kPad + r * kRsHistThreads + tid] = make_uint2(key[r], val[r]);
+    }
 #pragma unroll
     for (int r = 0; r < kRsHistItems; ++r) atomicAdd(&s_hist[(key[r] >> shift) & dmask], 1u);
     __syncthreads();
@@ -124,12 +135,9 @@ __global__ __launch_bounds__(kRsHistThreads) void rs_hist_kernel(
 // Stable scatter of one tile.  The workgroup first turns the table's histograms
 // into the start offset of each of its digits: (keys with a smaller digit in
 // the whole table) + (keys with this digit in earlier tiles).
-template <bool FIRST>
 __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
-    const int32_t *__restrict__ idx, int Bcap, int L,
-    const int32_t *__restrict__ n_valid, const uint32_t *const *__restrict__ bits,
-    const uint2 *__restrict__ in_ent, uint2 *__restrict__ out_ent, int NP,
-    int shift, int nb, const uint32_t *__restrict__ hist, int tiles)
+    const uint2 *__restrict__ in_ent, uint2 *__restrict__ out_ent, int NP, int shift,
+    int nb, const uint32_t *__restrict__ hist, int tiles)
 {
     constexpr int NW = kRsThreads / 64;
     __shared__ uint32_t s_cnt[NW * kRsMaxDig];   // per wavefront and digit
@@ -137,20 +145,17 @@ __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
     __shared__ uint32_t s_wsum[NW];
     const int t = blockIdx.y, tile = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n = clamp_valid(n_valid, Bcap) * L;
     const int ndig = 1 << nb;
     const uint32_t dmask = ndig - 1;
-    const int32_t *__restrict__ ip = idx + (int64_t)t * Bcap * L;
-    const auto bt = as_global((FIRST && bits) ? bits[t] : nullptr);
-    const uint2 *__restrict__ ein = FIRST ? nullptr : in_ent + (int64_t)t * NP;
+    const uint2 *__restrict__ ein = in_ent + (int64_t)t * NP;
 
     uint32_t key[kRsItems], val[kRsItems], rank[kRsItems];
 #pragma unroll
-    for (int r = 0; r < kRsItems; ++r)   // wavefront w owns a contiguous part of the tile
-        rs_load<FIRST>(ip, L, n, ein, true,
-                       tile * kPad + wave * (kRsItems * 64) + r * 64 + lane, key[r],
-                       val[r]);
-    if (FIRST) drop_stale(bt, key);
+    for (int r = 0; r < kRsItems; ++r) {  // wavefront w owns a contiguous part of the tile
+        const uint2 e = ein[tile * kPad + wave * (kRsItems * 64) + r * 64 + lane];
+        key[r] = e.x;
+        val[r] = e.y;
+    }
 
     // Digit offsets from the histograms; each thread owns ndig / 256 digits.
     // This kernel runs about one wavefront per SIMD, so what it costs is the
@@ -311,7 +316,7 @@ __global__ __launch_bounds__(kApplyWG) void apply_kernel(
 
     // Stale and padding lookups carry the sentinel key, the largest there is:
     // they form the last run of the table, which never ends and is never stored.
-    // Their payload is a valid sample number, so gradient loads need no guard.
+    // Their second word is a valid sample number, so gradient loads need no guard.
     //   end[i]: a run ends at lookup i;  put[i]: ... and it began in this strip,
     //   so its sum is complete here and the row is updated right away.
     const bool cont = row[0] == prev;       // the first run began before the strip
@@ -643,7 +648,7 @@ void backward_first_buffers(int T, int Bcap, int L, int dim, void *ws, uint2 **e
     *NP = y.NP;
 }
 
-// Which of the two key/payload buffers holds the sorted lists after stage 1.
+// Which of the two pair buffers holds the sorted lists after stage 1.
 static int sorted_buffer(const Layout &y, int64_t rows)
 {
     if (y.NP <= kLdsSortMax) return 0;
@@ -691,25 +696,23 @@ int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bca
         int shift = 0;
         for (int pass = 0; pass < npass; ++pass) {
             const int nb = pass_bits(sort_bits, npass, pass);
-            const int in = cur, out = pass == 0 ? 0 : 1 - cur;
+            // the first pass reads the index tensor, leaves its (row, sample) pairs in
+            // buffer 1 and scatters them into buffer 0; then the buffers alternate
+            const int in = pass == 0 ? 1 : cur, out = pass == 0 ? 0 : 1 - cur;
             {
                 ProfScope prof("rs_hist_kernel", s);
                 if (pass == 0)
-                    launch(rs_hist_kernel<true>, grid, dim3(kRsHistThreads), s, idx, Bcap, L, n_valid, tb->stale_bits,
-                                       nullptr, y.NP, shift, nb, hist, y.tiles);
+                    launch(rs_hist_kernel<true>, grid, dim3(kRsHistThreads), s, idx, Bcap, L,
+                           n_valid, tb->stale_bits, nullptr, ent[1], y.NP, shift, nb, hist,
+                           y.tiles);
                 else
-                    launch(rs_hist_kernel<false>, grid, dim3(kRsHistThreads), s, idx, Bcap, L, n_valid, nullptr,
-                                       ent[in], y.NP, shift, nb, hist, y.tiles);
+                    launch(rs_hist_kernel<false>, grid, dim3(kRsHistThreads), s, idx, Bcap, L,
+                           n_valid, nullptr, ent[in], nullptr, y.NP, shift, nb, hist,
+                           y.tiles);
             }
             ProfScope prof("rs_scatter_kernel", s);
-            if (pass == 0)
-                launch(rs_scatter_kernel<true>, grid, dim3(kRsThreads), s, idx, Bcap, L, n_valid, tb->stale_bits, nullptr,
-                                   ent[out], y.NP, shift, nb,
-                                   hist, y.tiles);
-            else
-                launch(rs_scatter_kernel<false>, grid, dim3(kRsThreads), s, idx, Bcap, L, n_valid, nullptr, ent[in],
-                                   ent[out], y.NP, shift, nb,
-                                   hist, y.tiles);
+            launch(rs_scatter_kernel, grid, dim3(kRsThreads), s, ent[in], ent[out], y.NP,
+                   shift, nb, hist, y.tiles);
             cur = out;
             shift += nb;
         }
