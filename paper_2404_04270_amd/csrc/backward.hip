@@ -745,18 +745,20 @@ int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float 
         return fail(SS_ERR_UNSUPPORTED, "ss_embbag_backward_apply: grid too large");
     // one gradient block per L2: only worth it when gradient rows are re-read
     const int pinned = L > 1 ? (T / 8) * 8 * wgs : 0;
-#define SS_APPLY(S_, F_)                                                           \
-    SS_DISPATCH_G(g, launch(                                         \
-                         (apply_kernel<G, S_, F_>), dim3((unsigned)blocks), dim3(kApplyWG), s, tb->weights, ent[cur], y.NP, grad,      \
-                         Bcap, D4, lr, wgs, pinned, L == 1, trail_row,  \
-                         lead_state,                                               \
-                         part_lead, part_trail))
+#define SS_APPLY(S_, F_)                                                          \
+    SS_DISPATCH_G(g, launch((apply_kernel<G, S_, F_>), dim3((unsigned)blocks),    \
+                            dim3(kApplyWG), s, tb->weights, ent[cur], y.NP, grad, \
+                            Bcap, D4, lr, wgs, pinned, L == 1, trail_row,         \
+                            lead_state, part_lead, part_trail))
     {
-    ProfScope prof("apply_kernel", s);
-    // a row that fills its group of lanes exactly needs no column loop and no guard
-    const bool full = D4 == g && (int64_t)Bcap * tb->dim * 4 <= 0xFFFFFFFFLL;
-    if (strip == 8) { if (full) { SS_APPLY(8, true); } else { SS_APPLY(8, false); } }
-    else { if (full) { SS_APPLY(4, true); } else { SS_APPLY(4, false); } }
+        ProfScope prof("apply_kernel", s);
+        // a row that fills its group of lanes exactly needs no column loop and no guard
+        const bool full = D4 == g && (int64_t)Bcap * tb->dim * 4 <= 0xFFFFFFFFLL;
+        if (strip == 8) {
+            if (full) { SS_APPLY(8, true); } else { SS_APPLY(8, false); }
+        } else {
+            if (full) { SS_APPLY(4, true); } else { SS_APPLY(4, false); }
+        }
     }
 #undef SS_APPLY
     ProfScope prof("fixup_kernel", s);
