@@ -238,3 +238,61 @@ def test_config5_full_shape_sampled_with_skips_and_detect(B, dev):
             assert sh.all()
         del tb, hs
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("config", [4, 5])
+def test_pipelined_step_equals_call_by_call_step_at_full_shape(B, dev, config):
+    """The benchmark times PipelinedStep with its automatic settings (several index
+    streams at these shapes, the issue thread at config 5).  Every sum in the library
+    has a fixed order, so that step must leave bit for bit what the call-by-call
+    step leaves, whose calls the tests above hold against the oracle at this shape:
+    a property that can be checked at any size, on the device.  Threshold +inf and a
+    short period make the second boundary freeze every hot row, so the runs cover
+    capture, detection, dropped updates and (config 5) skipped samples."""
+    from paper_2404_04270_amd.step import EmbeddingStep, PipelinedStep
+    cfg = wl.CONFIGS[config]
+    T, R, Bn, L = cfg.num_tables, cfg.rows, cfg.batch, cfg.bag
+    n_iters, period = 14, 4
+    w = wl.Workload(cfg)
+    idx = w.indices(0, n_iters)
+    hot = [torch.from_numpy(h).to(dev) for h in wl.hot_set(idx, R, cfg.hot_rows)]
+    idx_d = torch.from_numpy(idx).to(dev)
+    wa = [w.weights_device(t, dev) for t in range(T)]
+    wb = [x.clone() for x in wa]
+    serial = EmbeddingStep(wa, hot, Bn, L, cfg.lr, math.inf, period)
+    pipe = PipelinedStep(wb, hot, Bn, L, cfg.lr, math.inf, period)
+    assert len(pipe.sides) >= 2                       # what bench.py runs at these shapes
+    torch.cuda.synchronize()
+    ahead = skipped = detects = 0
+    for it in range(n_iters):
+        g = torch.from_numpy(w.grads(it)).to(dev)
+        serial.filter_forward(idx_d[it])
+        while ahead < n_iters and pipe.room() > 0:
+            pipe.submit(idx_d[ahead])
+            ahead += 1
+        pipe.forward()
+        nk = int(serial.n_kept.item())
+        assert int(pipe.n_kept.item()) == nk, it
+        assert torch.equal(pipe.skip_mask, serial.skip_mask), it
+        assert torch.equal(pipe.kept_ids[:nk], serial.kept_ids[:nk]), it
+        assert torch.equal(pipe.pooled[:, :nk], serial.pooled[:, :nk]), it
+        skipped += Bn - nk
+        g_c = torch.zeros_like(g)
+        g_c[:, :nk] = g[:, serial.kept_ids[:nk].long()]
+        da = serial.backward(g_c)
+        db = pipe.backward(g_c)
+        assert da == db == (it + 1 in (2 * period, 3 * period)), it     # the first boundary captures
+        detects += int(da)
+    pipe.flush()
+    torch.cuda.synchronize()
+    assert detects == 2
+    for t in range(T):
+        assert torch.equal(wb[t], wa[t]), t
+        assert torch.equal(pipe.bits[t], serial.bits[t]), t
+        assert torch.equal(pipe.hot.snapshot[t], serial.hot.snapshot[t]), t
+        assert int(serial.hot.stale_hot[t].sum().item()) == hot[t].numel()   # all frozen
+    if config == 5:
+        assert skipped > 0                 # samples whose every lookup is stale
+    pipe.close()
+    del serial, pipe, wa, wb
+    torch.cuda.empty_cache()
