@@ -249,6 +249,8 @@ BACKWARD_CASES = [
     (1, 2000, 512, 200, 3, 150, 0.1, 1.2),      # two float4 per lane
     (16, 5000, 128, 600, 20, None, 0.1, 1.2),   # multi-hot: tables pinned to XCDs
     (11, 5000, 32, 500, 4, None, 0.1, 1.2),     # ... eight pinned, three spread
+    (2, 100000, 8, 250000, 4, 249000, 0.05, 1.1),   # a million lookups per table: 489 sort
+    (1, 2000000, 4, 1 << 20, 1, None, 0.0, 1.05),   # tiles; one lane per row, three passes
 ]
 
 
