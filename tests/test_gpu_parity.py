@@ -113,6 +113,12 @@ def test_forward_matches_oracle(B, dev, T, R, D, Bc, L, nv):
 @pytest.mark.parametrize("T,R,Bn,L,frac", [
     (3, 2000, 1000, 1, 0.5), (8, 500, 257, 2, 0.9), (2, 100, 5, 20, 0.97),
     (26, 4000, 4100, 1, 0.8),
+    (5, 2000, 300, 20, 0.95),     # 100 lookups per sample: 16 lanes each
+    (8, 3000, 700, 20, 0.9),      # 160: 32 lanes
+    (26, 1000, 200, 16, 0.97),    # 416: a whole wavefront per sample
+    (16, 500, 90, 40, 0.98),      # 640: more than one round of probes per lane; 8 copy parts
+    (2, 5000, 70000, 1, 0.7),     # many tiles of samples
+    (1, 64, 3000, 7, 0.9),        # one table
 ])
 def test_filter_matches_oracle(B, dev, T, R, Bn, L, frac):
     rng = np.random.default_rng(200 + T + L)
