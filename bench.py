@@ -29,8 +29,12 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=50)
+    # The timed region should be long against anything that happens once (a host
+    # thread descheduled for some tens of milliseconds would double a 20 ms
+    # region), and the warm-up should take every kind of launch once: the first
+    # period ends with a snapshot capture, the second with the first detect pass.
+    ap.add_argument("--steps", type=int, default=4000)
+    ap.add_argument("--warmup", type=int, default=250)
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--threshold", type=float, default=None,
                     help="drift threshold T (default: the config's; inf freezes all hot rows)")

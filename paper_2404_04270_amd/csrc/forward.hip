@@ -22,9 +22,12 @@ template <int G>
 __global__ __launch_bounds__(kWG) void forward_onehot_kernel(
     const float *const *__restrict__ weights, const int32_t *__restrict__ idx,
     int Bcap, const int32_t *__restrict__ n_valid, float *__restrict__ out,
-    int D4, int tiles_per_table)
+    int D4, int tiles_per_table, int pinned_blocks)
 {
-    forward_onehot_body<G, kWG>(blockIdx.x, weights, idx, Bcap, n_valid, out, D4,
+    // a table's hot rows are wanted by all its tiles: keep them in one L2
+    int t, tile;
+    block_to_table_pinned(blockIdx.x, tiles_per_table, pinned_blocks, t, tile);
+    forward_onehot_body<G, kWG>(t * tiles_per_table + tile, weights, idx, Bcap, n_valid, out, D4,
                                 tiles_per_table);
 }
 
@@ -131,7 +134,7 @@ int32_t launch_forward(const ss_tables *tb, const int32_t *idx, int Bcap, int L,
         SS_DISPATCH_G(g, launch(forward_onehot_kernel<G>,
                                             dim3((unsigned)blocks), dim3(kWG), s,
                                             tb->weights, idx, Bcap, n_valid, out,
-                                            D4, tiles));
+                                            D4, tiles, (tb->num_tables / 8) * 8 * tiles));
     } else {
 #define SS_FWD(F_)                                                                \
     SS_DISPATCH_G(g, launch((forward_kernel<G, F_>), dim3((unsigned)blocks),       \
