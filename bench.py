@@ -52,9 +52,9 @@ def parse():
     ap.add_argument("--index-streams", type=int, default=0,
                     help="streams the index work of the pipelined step is spread over "
                          "(0: PipelinedStep's own choice)")
-    ap.add_argument("--issue-thread", type=int, default=-1, choices=(-1, 0, 1),
+    ap.add_argument("--issue-thread", type=int, default=-1,
                     help="pipelined step: enqueue the index work from the library's own host "
-                         "thread (ss_issue_queue); -1: PipelinedStep's own choice")
+                         "threads (ss_issue_queue), that many; 0: none; -1: PipelinedStep's own choice")
     ap.add_argument("--serial", action="store_true",
                     help="issue every call of a batch on one stream, one batch after the other "
                          "(EmbeddingStep).  Default: PipelinedStep, which classifies and groups "
@@ -126,7 +126,7 @@ def main():
         step = PipelinedStep(weights, hot_d, Bn, L, cfg.lr, thr, cfg.snapshot_every,
                              diagnostics=False, every=args.pipeline_every or None,
                              index_streams=args.index_streams,
-                             issue_thread=None if args.issue_thread < 0 else bool(args.issue_thread))
+                             issue_thread=None if args.issue_thread < 0 else int(args.issue_thread))
     else:
         step = EmbeddingStep(weights, hot_d, Bn, L, cfg.lr, thr, cfg.snapshot_every,
                              diagnostics=False, overlap=args.overlap,
@@ -243,7 +243,7 @@ def main():
                    "streams": (1 + args.index_streams) if args.pipeline else (2 if args.overlap else 1),
                    "pipelined": bool(args.pipeline),
                    "pipeline_every": step.every if args.pipeline else None,
-                   "issue_thread": (step.queue is not None) if args.pipeline else None,
+                   "issue_threads": len(step.queues) if args.pipeline else None,
                    "grouped_forward": bool(args.grouped_forward)},
         "roofline": roofline, "roofline_all": roofline_all,
         "whole_step": {"algorithmic_bytes": step_bytes,

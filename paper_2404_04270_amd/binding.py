@@ -707,13 +707,18 @@ class IssueQueue:
         self._q = q
         self._events = []
 
-    def close(self) -> None:
+    def stop(self) -> None:
+        """Issues what is still queued and ends the thread; the events stay (jobs of
+        another queue may still name them)."""
         if self._q is not None:
             _check(_lib.ss_issue_queue_destroy(self._q))     # issues what is queued, joins
             self._q = None
-            for e in self._events:
-                _lib.ss_event_destroy(e)
-            self._events = []
+
+    def close(self) -> None:
+        self.stop()
+        for e in self._events:
+            _lib.ss_event_destroy(e)
+        self._events = []
 
     def __del__(self):
         try:

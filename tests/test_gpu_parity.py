@@ -514,14 +514,18 @@ def test_protocol_pipelined_over_several_index_streams(B, dev, streams, every, a
     assert s["detects"] == 60 // 7 - 1 and s["overrides"] == 0
 
 
-@pytest.mark.parametrize("streams,every,ahead", [(1, 1, 10 ** 9), (1, 4, 10 ** 9), (2, 2, 10 ** 9),
-                                                 (3, 1, 2), (2, 4, 3)])
-def test_protocol_pipelined_through_the_issue_thread(B, dev, streams, every, ahead):
+@pytest.mark.parametrize("streams,every,ahead,threads", [
+    (1, 1, 10 ** 9, True), (1, 4, 10 ** 9, True), (2, 2, 10 ** 9, True), (2, 4, 3, True),
+    (3, 1, 2, True),             # three streams or more: a thread for each
+    (3, 2, 10 ** 9, True), (4, 1, 10 ** 9, True),
+    (3, 2, 10 ** 9, 2),          # streams 0 and 2 share a thread
+    (3, 1, 10 ** 9, 1), (2, 2, 10 ** 9, 2)])
+def test_protocol_pipelined_through_the_issue_thread(B, dev, streams, every, ahead, threads):
     """The same lock-step runs with the index work enqueued by the library's own host
-    thread (ss_issue_queue): bit-identical index results, weights within tolerance."""
+    threads (ss_issue_queue): bit-identical index results, weights within tolerance."""
     cfg = wl.CONFIGS[1].scaled(snapshot_every=7)
     s = run_lockstep(B, dev, cfg, 60, cfg.threshold, pipelined=every, max_ahead=ahead,
-                     index_streams=streams, issue_thread=True)
+                     index_streams=streams, issue_thread=threads)
     assert s["detects"] == 60 // 7 - 1 and s["overrides"] == 0
 
 
@@ -534,6 +538,10 @@ def test_protocol_issue_thread_skips_and_multihot(B, dev):
     s = run_lockstep(B, dev, cfg, 24, cfg.threshold, pipelined=3, index_streams=2,
                      issue_thread=True)
     assert s["detects"] == 3
+    # global radix sort, three index streams with a thread each, rows frozen midway
+    cfg = wl.CONFIGS[5].scaled(rows=300000, batch=20000, snapshot_every=4, hot_frac=0.002)
+    s = run_lockstep(B, dev, cfg, 14, math.inf, pipelined=1, index_streams=3, issue_thread=True)
+    assert s["detects"] == 2 and s["skipped"] > 0
 
 
 def test_pipelined_step_refuses_calls_out_of_order(B, dev):
