@@ -172,6 +172,19 @@ def main():
     n_kept_last = int(step.n_kept.item())
     stale_rows = int(sum(int(torch.count_nonzero(b).item()) for b in step.bits))
 
+    # spread of the step time: the same work again in 20 separately timed pieces
+    # (each starts with an empty pipeline, which costs a 200-step piece about 0.1 us
+    # per step), outside the timed region
+    piece, pieces = max(1, min(200, args.steps)), []
+    for c in range(20):
+        torch.cuda.synchronize()
+        tp = time.perf_counter()
+        run(piece, args.warmup + args.steps + c * piece)
+        torch.cuda.synchronize()
+        pieces.append(1e6 * (time.perf_counter() - tp) / piece)
+    pieces.sort()
+    after_pieces = args.warmup + args.steps + 20 * piece
+
     # what a plain device copy sustains in this process (512 MiB read + 512 MiB written,
     # outside the timed region): the ceiling the roofline fractions are also put against
     ca = torch.empty(1 << 27, dtype=torch.float32, device=dev).normal_()
@@ -188,7 +201,7 @@ def main():
 
     # per-kernel durations: same steps again, each launch bracketed by events
     B.ss_profile_enable(True)
-    run(args.steps, args.warmup + args.steps)
+    run(args.steps, after_pieces)
     torch.cuda.synchronize()
     B.ss_profile_enable(False)
     prof = B.ss_profile_report()
@@ -253,6 +266,9 @@ def main():
                        "effective_GBs": logical_bytes / (ms_per_step * 1e-3) / 1e9},
         "skip_fraction": 1.0 - kept_frac, "kept_samples_per_s": value * kept_frac,
         "stale_rows": stale_rows,
+        "step_us_spread": {"pieces": 20, "steps_per_piece": piece,
+                           "median": 0.5 * (pieces[9] + pieces[10]), "min": pieces[0],
+                           "max": pieces[-1]},
         "kernels": kern, "setup_s": setup_s,
     }
 
