@@ -366,7 +366,10 @@ int32_t ss_embbag_ln_backward(const ss_tables *tables, const int32_t *idx, int32
  * as the GPU finishes it (enqueueing one kernel costs the host about 3 us here;
  * the index work of a batch - section 3.4, the input classifier, and the grouping
  * half of the update - is up to eight kernels).  Jobs are issued in submission
- * order.  Nothing here waits for the GPU or touches device memory.
+ * order.  Nothing here waits for the GPU or touches device memory.  A caller
+ * may hold several queues (say one per stream it feeds); they share nothing, so
+ * an event must outlive every queue that holds a job naming it: destroy the
+ * queues first, then the events.
  *
  *   ss_issue_queue_create   starts the thread, bound to the device that is
  *                           current in the calling thread; *out owns it
