@@ -124,7 +124,7 @@ int32_t launch_forward(const ss_tables *tb, const int32_t *idx, int Bcap, int L,
 {
     const int D4 = tb->dim / 4;
     const int g = lanes_per_row(tb->dim);
-    const int bags = (kWG / g) * (L == 1 ? 8 : 1);
+    const int bags = (kWG / g) * (L == 1 ? kOneHotBags : 1);
     const int tiles = (Bcap + bags - 1) / bags;
     const int64_t blocks = (int64_t)tiles * tb->num_tables;
     if (blocks > 0x7fffffffLL)

@@ -13,7 +13,9 @@ __device__ __forceinline__ void block_to_table_tile(int b, int tiles_per_table, 
     tile = b - t * tiles_per_table;
 }
 
-// L = 1: a group of G lanes takes 8 bags, fetches their indices, then issues
+constexpr int kOneHotBags = 8;     // bags per lane group in the one-hot kernel
+
+// L = 1: a group of G lanes takes kOneHotBags bags, fetches their indices, then issues
 // the 8 row loads back to back before the first store.
 template <int G, int THREADS>
 __device__ __forceinline__ void forward_onehot_body(
@@ -21,7 +23,7 @@ __device__ __forceinline__ void forward_onehot_body(
     int Bcap, const int32_t *__restrict__ n_valid, float *__restrict__ out, int D4,
     int tiles_per_table)
 {
-    constexpr int GROUPS = THREADS / G, BPG = 8;
+    constexpr int GROUPS = THREADS / G, BPG = kOneHotBags;
     int t, tile;
     block_to_table_tile(b, tiles_per_table, t, tile);
     const int n = clamp_valid(n_valid, Bcap);

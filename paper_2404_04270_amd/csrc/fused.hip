@@ -65,7 +65,7 @@ int32_t launch_forward_group(const ss_tables *tb, const int32_t *idx, int Bcap,
     while (key_bits < 31 && (1LL << key_bits) < tb->rows) ++key_bits;
     const ClassSortPlan cp = plan_class_sort(NP, Bcap, key_bits);
     const int g = lanes_per_row(tb->dim);
-    const int bags = (1024 / g) * 8;
+    const int bags = (1024 / g) * kOneHotBags;
     const int tiles = (Bcap + bags - 1) / bags;
     const int group_blocks = T << cp.class_bits;
     const int64_t blocks = (int64_t)tiles * T + group_blocks;
