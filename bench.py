@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--threshold", type=float, default=None,
                     help="drift threshold T (default: the config's; inf freezes all hot rows)")
     ap.add_argument("--ring", type=int, default=16, help="distinct batches cycled through")
+    ap.add_argument("--grad-buffers", type=int, default=4,
+                    help="distinct gradient tensors cycled through (4: together with the "
+                         "pooled output more than the 256 MB memory-side cache holds)")
     ap.add_argument("--overlap", action="store_true",
                     help="issue the grouping half of the backward pass on a second "
                          "stream next to the forward pass (measured slower on one GPU "
@@ -117,7 +120,7 @@ def main():
     hot = wl.hot_set(idx_ring, R, cfg.hot_rows)
     weights = [w.weights_device(t, dev) for t in range(T)]
     idx_d = torch.from_numpy(idx_ring).to(dev)
-    n_grads = 4
+    n_grads = max(1, args.grad_buffers)
     grads = [torch.from_numpy(w.grads(k)).to(dev) for k in range(n_grads)]
     hot_d = [torch.from_numpy(h).to(dev) for h in hot]
     if args.index_streams <= 0:
@@ -252,7 +255,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "tables": T, "rows": R, "dim": D, "batch": Bn,
                    "bag": L, "zipf_alpha": cfg.zipf_alpha, "threshold": thr,
-                   "snapshot_every": cfg.snapshot_every, "ring": args.ring,
+                   "snapshot_every": cfg.snapshot_every, "ring": args.ring, "grad_buffers": n_grads,
                    "streams": (1 + args.index_streams) if args.pipeline else (2 if args.overlap else 1),
                    "pipelined": bool(args.pipeline),
                    "pipeline_every": step.every if args.pipeline else None,
