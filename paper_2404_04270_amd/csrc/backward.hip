@@ -75,18 +75,17 @@ __global__ __launch_bounds__(1024) void class_sort_kernel(
 // Stage 1b: global LSD radix sort, one pass = histogram, scan, scatter.
 // Tile = 2048 keys; hist layout [table][tile][digit].
 // ---------------------------------------------------------------------------
+// What the histogram kernel reads at position `pos` of a table: in the first pass
+// the index tensor itself (the sample number is the position divided by the bag
+// length), afterwards the row id of the pair the previous pass left there.
 template <bool FIRST>
 __device__ __forceinline__ void rs_load(const int32_t *__restrict__ ip, int L, int n,
-                                        const uint2 *__restrict__ in_ent, bool want_val,
-                                        int pos, uint32_t &key, uint32_t &val)
+                                        const uint2 *__restrict__ in_ent, int pos,
+                                        uint32_t &key, uint32_t &val)
 {
     if (FIRST) {
         key = pos < n ? (uint32_t)ip[pos] : kNoRow;
         val = pos < n ? (uint32_t)(L == 1 ? pos : pos / L) : 0u;
-    } else if (want_val) {
-        const uint2 e = in_ent[pos];
-        key = e.x;
-        val = e.y;
     } else {
         key = in_ent[pos].x;
         val = 0u;
@@ -113,8 +112,7 @@ __global__ __launch_bounds__(kRsHistThreads) void rs_hist_kernel(
     uint32_t key[kRsHistItems], val[kRsHistItems];
 #pragma unroll
     for (int r = 0; r < kRsHistItems; ++r)
-        rs_load<FIRST>(ip, L, n, ein, false, tile * kPad + r * kRsHistThreads + tid,
-                       key[r], val[r]);
+        rs_load<FIRST>(ip, L, n, ein, tile * kPad + r * kRsHistThreads + tid, key[r], val[r]);
     if (FIRST) {
         // The first pass turns the index tensor into (row, sample) pairs, with the
         // sentinel for stale rows and padding, and leaves them for its scatter, which
