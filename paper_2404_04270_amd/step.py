@@ -314,7 +314,12 @@ class PipelinedStep:
                  lr: float, threshold: float, snapshot_every: int,
                  alpha: Optional[int] = None, diagnostics: bool = True,
                  every: Optional[int] = None, index_streams: Optional[int] = None,
-                 issue_thread: Optional[bool] = None):
+                 issue_thread=None):
+        """every: batches between two cross-stream events (None: auto_every);
+        index_streams: None = auto_streams; issue_thread: None = auto_issue_thread,
+        False / 0 = the calling thread enqueues everything, True = the library's issue
+        threads (one, or one per index stream from three streams on), an int = that
+        many threads (at most one per index stream)."""
         self.tables = B.Tables(weights)
         self.bits = self.tables.new_bits()
         self.hot = B.HotState(self.tables, hot_ids, diagnostics=diagnostics)
