@@ -64,6 +64,16 @@ def parse():
                          "the coming batches on a second stream while the current one is in its "
                          "forward and update kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prime", action="store_true",
+                    help="diagnostic: leave out the untimed priming batches that precede the "
+                         "warm-up (two snapshot periods and once round the pipeline's ring), "
+                         "so that whatever happens once lands in the warm-up or the timed region")
+    ap.add_argument("--no-extra-configs", action="store_true",
+                    help="only the workload named by --config: leave out the sub-records of "
+                         "the multi-hot workload and of the headline workload with all hot "
+                         "rows frozen")
+    ap.add_argument("--extra-steps", type=int, default=1000,
+                    help="timed steps of each sub-record (at least --steps)")
     ap.add_argument("--permute", action="store_true",
                     help="map rank -> row through a per-table random permutation (hot rows "
                          "scattered over the table as in real data; config 2 always does)")
@@ -94,102 +104,256 @@ def unique_rows_per_batch(idx_ring):
     return tot / idx_ring.shape[0]
 
 
-def main():
-    args = parse()
-    args.pipeline = not (args.serial or args.overlap or args.grouped_forward)
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
-              "(no collectives or sharding are part of it)" % args.gpus, file=sys.stderr)
-        sys.exit(2)
-    import torch
-    from paper_2404_04270_amd import binding as B
-    from paper_2404_04270_amd import workload as wl
-    from paper_2404_04270_amd.step import EmbeddingStep, PipelinedStep
+def prime_batches(step, pipelined, K):
+    """Untimed batches run before the warm-up, whatever --warmup says: enough for
+    everything that happens once to have happened.  Two snapshot periods (the first
+    ends with the capture, the second with the first detect pass) and, for the
+    pipelined step, once round the ring of buffer sets plus one more event period,
+    so that every set has been used, both streams have recorded events and waited
+    for the other's, and the pools the runtime grows on demand (events, completion
+    signals, kernel-argument memory) are at their steady size."""
+    if not pipelined:
+        return 2 * K + 1
+    return 2 * K + len(step.sets) + step.every
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    dev = torch.device("cuda:0")
-    cfg = wl.CONFIGS[args.config]
-    if args.permute and not cfg.permute:
-        cfg = cfg.scaled(permute=True, name=cfg.name + "_permuted")
-    thr = cfg.threshold if args.threshold is None else args.threshold
-    T, R, D, Bn, L = cfg.num_tables, cfg.rows, cfg.dim, cfg.batch, cfg.bag
-    w = wl.Workload(cfg)
 
-    t0 = time.time()
-    idx_ring = w.indices(0, args.ring)                          # [ring, T, B, L]
-    hot = wl.hot_set(idx_ring, R, cfg.hot_rows)
-    weights = [w.weights_device(t, dev) for t in range(T)]
-    idx_d = torch.from_numpy(idx_ring).to(dev)
-    n_grads = max(1, args.grad_buffers)
-    grads = [torch.from_numpy(w.grads(k)).to(dev) for k in range(n_grads)]
-    hot_d = [torch.from_numpy(h).to(dev) for h in hot]
-    if args.index_streams <= 0:
-        args.index_streams = PipelinedStep.auto_streams(Bn, L, T)
-    if args.pipeline:
-        step = PipelinedStep(weights, hot_d, Bn, L, cfg.lr, thr, cfg.snapshot_every,
-                             diagnostics=False, every=args.pipeline_every or None,
-                             index_streams=args.index_streams,
-                             issue_thread=None if args.issue_thread < 0 else int(args.issue_thread))
-    else:
-        step = EmbeddingStep(weights, hot_d, Bn, L, cfg.lr, thr, cfg.snapshot_every,
-                             diagnostics=False, overlap=args.overlap,
-                             grouped_forward=args.grouped_forward)
-    torch.cuda.synchronize()
-    setup_s = time.time() - t0
+class Measurement:
+    """One workload set up on the device, and the timed runs over it."""
 
-    if args.copy_probe:
-        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
-        b = torch.empty_like(a)
-        for _ in range(3):
-            b.copy_(a)
+    def __init__(self, args, config_no, threshold):
+        import torch
+        from paper_2404_04270_amd import workload as wl
+        from paper_2404_04270_amd.step import EmbeddingStep, PipelinedStep
+        self.torch, self.args = torch, args
+        dev = torch.device("cuda:0")
+        cfg = wl.CONFIGS[config_no]
+        if args.permute and not cfg.permute:
+            cfg = cfg.scaled(permute=True, name=cfg.name + "_permuted")
+        self.cfg = cfg
+        self.thr = cfg.threshold if threshold is None else threshold
+        T, R, Bn, L = cfg.num_tables, cfg.rows, cfg.batch, cfg.bag
+        self.w = w = wl.Workload(cfg)
+        t0 = time.time()
+        self.idx_ring = w.indices(0, args.ring)                     # [ring, T, B, L]
+        self.hot = wl.hot_set(self.idx_ring, R, cfg.hot_rows)
+        weights = [w.weights_device(t, dev) for t in range(T)]
+        self.idx_d = torch.from_numpy(self.idx_ring).to(dev)
+        self.n_grads = max(1, args.grad_buffers)
+        self.grads = [torch.from_numpy(w.grads(k)).to(dev) for k in range(self.n_grads)]
+        hot_d = [torch.from_numpy(h).to(dev) for h in self.hot]
+        self.pipelined = bool(args.pipeline)
+        self.index_streams = args.index_streams if args.index_streams > 0 else \
+            PipelinedStep.auto_streams(Bn, L, T)
+        if self.pipelined:
+            self.step = PipelinedStep(
+                weights, hot_d, Bn, L, cfg.lr, self.thr, cfg.snapshot_every,
+                diagnostics=False, every=args.pipeline_every or None,
+                index_streams=self.index_streams,
+                issue_thread=None if args.issue_thread < 0 else int(args.issue_thread))
+        else:
+            self.step = EmbeddingStep(weights, hot_d, Bn, L, cfg.lr, self.thr,
+                                      cfg.snapshot_every, diagnostics=False,
+                                      overlap=args.overlap,
+                                      grouped_forward=args.grouped_forward)
         torch.cuda.synchronize()
-        del a, b
+        self.setup_s = time.time() - t0
+        self.done = 0              # batches run so far (the next batch's number)
 
-    def run(n, start_it):
-        if args.pipeline:
-            # exactly n batches; index work is submitted as far ahead as the ring takes
-            nxt, end = start_it, start_it + n
-            for k in range(n):
-                it = start_it + k
+    def run(self, n, stamps=None):
+        """Exactly n more batches.  stamps: list that receives the host clock after
+        each batch has been enqueued (no synchronisation)."""
+        step, ring, grads, n_grads = self.step, self.args.ring, self.grads, self.n_grads
+        idx_d, start = self.idx_d, self.done
+        if self.pipelined:
+            # index work is submitted as far ahead as the ring takes, never past the n-th
+            nxt, end = start, start + n
+            for it in range(start, end):
                 while nxt < end and step.room() > 0:
-                    step.submit(idx_d[nxt % args.ring])
+                    step.submit(idx_d[nxt % ring])
                     nxt += 1
                 step.forward()
                 step.backward(grads[it % n_grads])
+                if stamps is not None:
+                    stamps.append(time.perf_counter())
             step.flush()
-            return
-        for k in range(n):
-            it = start_it + k
-            step.filter_forward(idx_d[it % args.ring])
-            step.backward(grads[it % n_grads])
+        else:
+            for it in range(start, start + n):
+                step.filter_forward(idx_d[it % ring])
+                step.backward(grads[it % n_grads])
+                if stamps is not None:
+                    stamps.append(time.perf_counter())
+        self.done += n
 
-    run(args.warmup, 0)
-    torch.cuda.synchronize()
-    kept_before = 0
-    t1 = time.perf_counter()
-    run(args.steps, args.warmup)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t1
-    ms_per_step = 1e3 * elapsed / args.steps
-    value = Bn * args.steps / elapsed
-    n_kept_last = int(step.n_kept.item())
-    stale_rows = int(sum(int(torch.count_nonzero(b).item()) for b in step.bits))
-
-    # spread of the step time: the same work again in 20 separately timed pieces
-    # (each starts with an empty pipeline, which costs a 200-step piece about 0.1 us
-    # per step), outside the timed region
-    piece, pieces = max(1, min(200, args.steps)), []
-    for c in range(20):
+    def timed(self, n):
+        """n batches between two device synchronisations: host seconds, the same
+        region between two events on the training stream (ms), and the host clock
+        after every batch."""
+        torch = self.torch
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        stamps = []
         torch.cuda.synchronize()
-        tp = time.perf_counter()
-        run(piece, args.warmup + args.steps + c * piece)
+        t1 = time.perf_counter()
+        e0.record()
+        self.run(n, stamps)
+        e1.record()
         torch.cuda.synchronize()
-        pieces.append(1e6 * (time.perf_counter() - tp) / piece)
-    pieces.sort()
-    after_pieces = args.warmup + args.steps + 20 * piece
+        elapsed = time.perf_counter() - t1
+        return elapsed, e0.elapsed_time(e1), t1, stamps
 
-    # what a plain device copy sustains in this process (512 MiB read + 512 MiB written,
-    # outside the timed region): the ceiling the roofline fractions are also put against
+    def kept_fraction(self):
+        """Share of the submitted samples that were kept, over the batches whose
+        counts are still on the device (the ring of buffer sets; the last batch for
+        the serial step)."""
+        step = self.step
+        if self.pipelined:
+            used = step.sets[:min(len(step.sets), self.done)]
+            return float(sum(int(s.n_kept.item()) for s in used)) / (len(used) * self.cfg.batch)
+        return int(step.n_kept.item()) / self.cfg.batch
+
+    def distinct_rows(self):
+        """Per batch, averaged over the ring and summed over tables, with the stale
+        bitmaps as they are now: (distinct rows the kept samples look up, the
+        distinct rows among them that are not stale, share of samples kept).  The
+        first is what the forward pass must read, the second what the update must
+        read and write."""
+        cfg = self.cfg
+        stale = [np.unpackbits(b.cpu().numpy().view(np.uint8), bitorder="little")[:cfg.rows]
+                 .astype(bool) for b in self.step.bits]
+        any_stale = any(s.any() for s in stale)
+        u_fwd = u_upd = kept = 0.0
+        for k in range(self.idx_ring.shape[0]):
+            idx = self.idx_ring[k]                                   # [T, B, L]
+            keep = np.ones(cfg.batch, dtype=bool)
+            if any_stale:               # skipped: every lookup of the sample is stale
+                all_stale = np.ones(cfg.batch, dtype=bool)
+                for t in range(cfg.num_tables):
+                    all_stale &= stale[t][idx[t]].all(axis=1)
+                keep = ~all_stale
+            kept += keep.mean()
+            for t in range(cfg.num_tables):
+                rows = np.unique(idx[t][keep])
+                u_fwd += rows.size
+                u_upd += rows.size - (int(stale[t][rows].sum()) if any_stale else 0)
+        n = self.idx_ring.shape[0]
+        return u_fwd / n, u_upd / n, kept / n
+
+    def record(self, steps, warmup, pieces=20):
+        """Primes, warms up, times `steps` batches, then measures the spread and the
+        per-kernel durations; returns the record of this workload."""
+        torch, args, cfg, step = self.torch, self.args, self.cfg, self.step
+        from paper_2404_04270_amd import binding as B
+        T, R, D, Bn, L = cfg.num_tables, cfg.rows, cfg.dim, cfg.batch, cfg.bag
+        n_prime = 0 if args.no_prime else prime_batches(step, self.pipelined,
+                                                        cfg.snapshot_every)
+        self.run(n_prime)
+        self.run(warmup)
+        elapsed, gpu_ms, t1, stamps = self.timed(steps)
+        ms_per_step = 1e3 * elapsed / steps
+        value = Bn * steps / elapsed
+        per = np.diff(np.array([t1] + stamps)) * 1e6       # host time per batch, us
+        timed_region = {
+            "host_ms": 1e3 * elapsed, "gpu_event_ms": gpu_ms,
+            "first_step_us": float(per[0]), "max_step_us": float(per.max()),
+            "argmax": int(per.argmax()), "median_us": float(np.median(per)),
+            "host_enqueue_done_ms": 1e3 * (stamps[-1] - t1),
+            "note": "host clock after each batch was enqueued (no synchronisation): "
+                    "what the calling thread spent per batch, not GPU time"}
+        stale_rows = int(sum(int(torch.count_nonzero(b).item()) for b in step.bits))
+        kept_frac = self.kept_fraction()
+
+        # spread of the step time: further pieces, each timed on its own (each starts
+        # with an empty pipeline), outside the timed region
+        piece = max(1, min(200, steps))
+        spread = sorted(1e6 * self.timed(piece)[0] / piece for _ in range(pieces))
+
+        # host time per batch with the GPU left to run behind (no synchronisation
+        # inside): what the calling thread needs to enqueue a batch
+        host_us = float(np.median(np.diff(np.array(self.timed(piece)[3])))) * 1e6
+
+        # per-kernel durations: the same steps again, each launch bracketed by events
+        n_prof = max(steps, 200)
+        B.ss_profile_enable(True)
+        self.run(n_prof)
+        torch.cuda.synchronize()
+        B.ss_profile_enable(False)
+        prof = B.ss_profile_report()
+        kern = {k: {"launches": n, "avg_us": 1e3 * ms / n, "total_ms": ms}
+                for k, (n, ms) in prof.items()}
+
+        # algorithmic bytes per launch (all tables are in one launch)
+        U_fwd, U_upd, kept_host = self.distinct_rows()
+        nnz = T * Bn * L
+        row_b = D * 4
+        alg = {
+            "forward_kernel": U_fwd * row_b + nnz * 4 * kept_frac + T * Bn * row_b * kept_frac,
+            "apply_kernel": T * Bn * row_b * kept_frac + nnz * 4 + 2 * U_upd * row_b,
+        }
+        alg["forward_group_kernel"] = alg["forward_kernel"]
+        # the dominant kernel: most GPU time; kernels within 3 % of it count as tied (at
+        # one-hot shapes forward and update are, and their order flips from run to run),
+        # and among tied ones the kernel that moves more algorithmic bytes is named
+        cands = [k for k in kern if k in alg]
+        longest = max(kern[k]["total_ms"] for k in cands)
+        dom = max((k for k in cands if kern[k]["total_ms"] >= 0.97 * longest),
+                  key=lambda k: alg[k])
+
+        def roof(k):
+            ach = alg[k] / (kern[k]["avg_us"] * 1e-6) / 1e9
+            traffic, src = measured_traffic(cfg.name, k, self.thr == cfg.threshold)
+            return {"achieved": ach, "frac": ach / HBM_PEAK_GBS,
+                    "algorithmic_bytes_per_launch": alg[k],
+                    "avg_kernel_us": kern[k]["avg_us"], "traffic": traffic,
+                    "traffic_source": src}
+        roofline = {"bound": "hbm", "kernel": dom, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+        roofline.update(roof(dom))
+        roofline_all = {k: roof(k) for k in kern if k in alg}
+        step_bytes = alg["forward_kernel"] + alg["apply_kernel"]
+        # "logical" bytes: every lookup counted as a row (nnz in place of the distinct rows)
+        logical_bytes = (nnz * row_b + nnz * 4 + T * Bn * row_b) * kept_frac + \
+                        (T * Bn * row_b * kept_frac + nnz * 4 + 2 * nnz * row_b * kept_frac)
+        # (filter: < 2 % of the step's bytes; grouping and fixup carry no algorithmic bytes)
+        med = 0.5 * (spread[(pieces - 1) // 2] + spread[pieces // 2])
+        return {
+            "value": value, "ms_per_step": ms_per_step, "steps": steps, "warmup": warmup,
+            "primed_batches": n_prime,
+            "config": {"workload": cfg.name, "tables": T, "rows": R, "dim": D, "batch": Bn,
+                       "bag": L, "zipf_alpha": cfg.zipf_alpha, "threshold": self.thr,
+                       "snapshot_every": cfg.snapshot_every, "ring": args.ring,
+                       "grad_buffers": self.n_grads,
+                       "streams": (1 + self.index_streams) if self.pipelined
+                       else (2 if args.overlap else 1),
+                       "pipelined": self.pipelined,
+                       "pipeline_every": step.every if self.pipelined else None,
+                       "issue_threads": len(step.queues) if self.pipelined else None,
+                       "grouped_forward": bool(args.grouped_forward)},
+            "timed_region": timed_region,
+            "roofline": roofline, "roofline_all": roofline_all,
+            "whole_step": {"algorithmic_bytes": step_bytes,
+                           "achieved_GBs": step_bytes / (ms_per_step * 1e-3) / 1e9,
+                           "frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9
+                           / HBM_PEAK_GBS,
+                           "frac_of_hbm_peak_at_spread_median": step_bytes / (med * 1e-6) / 1e9
+                           / HBM_PEAK_GBS,
+                           "logical_bytes": logical_bytes,
+                           "effective_GBs": logical_bytes / (ms_per_step * 1e-3) / 1e9},
+            "skip_fraction": 1.0 - kept_frac, "kept_samples_per_s": value * kept_frac,
+            "stale_rows": stale_rows,
+            "step_us_spread": {"pieces": pieces, "steps_per_piece": piece, "median": med,
+                               "min": spread[0], "max": spread[-1]},
+            "host_us_per_batch": host_us,
+            "kernels": kern, "setup_s": self.setup_s,
+        }
+
+    def close(self):
+        if self.pipelined:
+            self.torch.cuda.synchronize()
+            self.step.close()
+
+
+def copy_rate(torch, dev):
+    """What a plain device copy sustains in this process (512 MiB read + 512 MiB
+    written): the ceiling the roofline fractions are also put against."""
     ca = torch.empty(1 << 27, dtype=torch.float32, device=dev).normal_()
     cb = torch.empty_like(ca)
     cb.copy_(ca)
@@ -199,90 +363,75 @@ def main():
         cb.copy_(ca)
     e1.record()
     torch.cuda.synchronize()
-    copy_gbs = 5 * 2 * ca.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del ca, cb
+    return 5 * 2 * ca.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
-    # per-kernel durations: same steps again, each launch bracketed by events
-    B.ss_profile_enable(True)
-    run(args.steps, after_pieces)
-    torch.cuda.synchronize()
-    B.ss_profile_enable(False)
-    prof = B.ss_profile_report()
-    kern = {k: {"launches": n, "avg_us": 1e3 * ms / n, "total_ms": ms}
-            for k, (n, ms) in prof.items()}
 
-    # algorithmic bytes per launch (all tables are in one launch)
-    U = unique_rows_per_batch(idx_ring)          # distinct rows per batch, all tables
-    nnz = T * Bn * L
-    kept_frac = n_kept_last / Bn
-    row_b = D * 4
-    alg = {
-        "forward_kernel": U * row_b + nnz * 4 + T * Bn * row_b * kept_frac,
-        "forward_group_kernel": U * row_b + nnz * 4 + T * Bn * row_b * kept_frac,
-        "apply_kernel": T * Bn * row_b * kept_frac + nnz * 4 + 2 * U * row_b,
-    }
-    # the dominant kernel: most GPU time; kernels within 3 % of it count as tied (at
-    # one-hot shapes forward and update are, and their order flips from run to run),
-    # and among tied ones the kernel that moves more algorithmic bytes is named
-    cands = [k for k in kern if k in alg]
-    longest = max(kern[k]["total_ms"] for k in cands)
-    dom = max((k for k in cands if kern[k]["total_ms"] >= 0.97 * longest),
-              key=lambda k: alg[k])
-    achieved = alg[dom] / (kern[dom]["avg_us"] * 1e-6) / 1e9
-    roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved,
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                "traffic": measured_traffic(cfg.name, dom),
-                "algorithmic_bytes_per_launch": alg[dom],
-                "avg_kernel_us": kern[dom]["avg_us"],
-                "measured_copy_GBs": copy_gbs, "frac_of_measured_copy": achieved / copy_gbs}
-    # the same figures for every kernel that carries algorithmic bytes
-    roofline_all = {k: {"achieved": alg[k] / (kern[k]["avg_us"] * 1e-6) / 1e9,
-                        "frac": alg[k] / (kern[k]["avg_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                        "algorithmic_bytes_per_launch": alg[k],
-                        "avg_kernel_us": kern[k]["avg_us"],
-                        "traffic": measured_traffic(cfg.name, k)}
-                    for k in kern if k in alg}
-    step_bytes = alg["forward_kernel"] + alg["apply_kernel"]
-    # "logical" bytes: every lookup counted as a row (nnz in place of the distinct rows)
-    logical_bytes = (nnz * row_b + nnz * 4 + T * Bn * row_b * kept_frac) + \
-                    (T * Bn * row_b * kept_frac + nnz * 4 + 2 * nnz * row_b)
-    # (filter: < 2 % of the step's bytes; grouping and fixup carry no algorithmic bytes)
+def main():
+    args = parse()
+    args.pipeline = not (args.serial or args.overlap or args.grouped_forward)
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
+              "(no collectives or sharding are part of it)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2404_04270_amd import binding as B
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+
+    if args.copy_probe:
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+
+    m = Measurement(args, args.config, args.threshold)
+    rec = m.record(args.steps, args.warmup)
+    copy_gbs = copy_rate(torch, dev)
+    rec["roofline"]["measured_copy_GBs"] = copy_gbs
+    rec["roofline"]["frac_of_measured_copy"] = rec["roofline"]["achieved"] / copy_gbs
 
     out = {
         "metric": "train samples/s through embedding fwd+update+stale-skip; achieved HBM GB/s",
-        "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "value": rec.pop("value"), "unit": "samples/s", "n_gpus": 1,
+        "steps": rec.pop("steps"), "warmup": rec.pop("warmup"),
+        "ms_per_step": rec.pop("ms_per_step"), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": cfg.name, "tables": T, "rows": R, "dim": D, "batch": Bn,
-                   "bag": L, "zipf_alpha": cfg.zipf_alpha, "threshold": thr,
-                   "snapshot_every": cfg.snapshot_every, "ring": args.ring, "grad_buffers": n_grads,
-                   "streams": (1 + args.index_streams) if args.pipeline else (2 if args.overlap else 1),
-                   "pipelined": bool(args.pipeline),
-                   "pipeline_every": step.every if args.pipeline else None,
-                   "issue_threads": len(step.queues) if args.pipeline else None,
-                   "grouped_forward": bool(args.grouped_forward)},
-        "roofline": roofline, "roofline_all": roofline_all,
-        "whole_step": {"algorithmic_bytes": step_bytes,
-                       "achieved_GBs": step_bytes / (ms_per_step * 1e-3) / 1e9,
-                       "frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                       "logical_bytes": logical_bytes,
-                       "effective_GBs": logical_bytes / (ms_per_step * 1e-3) / 1e9},
-        "skip_fraction": 1.0 - kept_frac, "kept_samples_per_s": value * kept_frac,
-        "stale_rows": stale_rows,
-        "step_us_spread": {"pieces": 20, "steps_per_piece": piece,
-                           "median": 0.5 * (pieces[9] + pieces[10]), "min": pieces[0],
-                           "max": pieces[-1]},
-        "kernels": kern, "setup_s": setup_s,
     }
+    out.update(rec)
 
+    step, cfg = m.step, m.cfg
     if args.sampling_probe > 0:
-        out["sampling_block"] = sampling_probe(B, step, idx_d, args.sampling_probe, thr)
+        out["sampling_block"] = sampling_probe(B, step, m.idx_d, args.sampling_probe, m.thr)
     if args.layernorm_probe:
-        out["layernorm"] = layernorm_probe(B, step, grads)
+        out["layernorm"] = layernorm_probe(B, step, m.grads)
     if args.hotset_probe:
-        out["hot_set"] = hotset_probe(B, step, idx_d, cfg.hot_rows, hot)
+        out["hot_set"] = hotset_probe(B, step, m.idx_d, cfg.hot_rows, m.hot)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, w, idx_ring, hot, thr, args.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(cfg, m.w, m.idx_ring, m.hot, m.thr, args.cpu_seconds)
+    m.close()
+    headline = (args.config, m.thr)
+    del m, step
+    torch.cuda.empty_cache()
+
+    # The other graded workload, and the headline workload with every hot row frozen
+    # (the skip path busy), measured the same way in the same run.
+    if not args.no_extra_configs:
+        out["configs"] = []
+        n_sub = max(args.steps, args.extra_steps)
+        for config_no, thr in ((4, None), (3, float("inf"))):
+            mm = Measurement(args, config_no, thr)
+            if (config_no, mm.thr) == headline:
+                mm.close()
+                continue
+            sub = mm.record(n_sub, args.warmup, pieces=10)
+            sub["samples_per_s"] = sub.pop("value")
+            out["configs"].append(sub)
+            mm.close()
+            del mm
+            torch.cuda.empty_cache()
     print(json.dumps(out))
 
 
@@ -400,18 +549,22 @@ def sampling_probe(B, step, idx_d, S, thr):
             "counts_first_last": [counts[0], counts[-1]]}
 
 
-def measured_traffic(workload, kernel):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter
-    summary of this workload (FETCH_SIZE + WRITE_SIZE, already scaled by the
-    copy-kernel calibration); None if there is no summary for it."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
+def measured_traffic(workload, kernel, default_threshold=True):
+    """(HBM bytes per launch of `kernel`, where the figure comes from): FETCH_SIZE +
+    WRITE_SIZE from the committed rocprofv3 counter summary of this workload, each
+    already scaled by the copy-kernel calibration.  The counters are not collected
+    in this run; (None, reason) if no committed summary covers the kernel."""
+    if not default_threshold:
+        return None, "no committed counter summary for this threshold"
+    name = "hbm_traffic_%s.txt" % workload
+    path = os.path.join(ROOT, "profiles", name)
     if not os.path.exists(path):
-        return None
+        return None, "no committed counter summary for this workload"
     for line in open(path):
         f = line.split()
         if len(f) == 4 and f[0] == kernel:
-            return float(f[3])
-    return None
+            return float(f[3]), "profiles/" + name + " (rocprofv3 --pmc, separate runs)"
+    return None, "profiles/" + name + " has no line for this kernel"
 
 
 def cpu_baseline(cfg, w, idx_ring, hot, thr, budget_s):
@@ -436,8 +589,16 @@ def cpu_baseline(cfg, w, idx_ring, hot, thr, budget_s):
         el = time.perf_counter() - t0
         if el >= budget_s or n >= 2000:
             break
+    model = ""
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
     return {"value": cfg.batch * n / el, "unit": "samples/s", "cores": 1,
-            "kind": "oracle",
+            "kind": "oracle", "host_nproc": os.cpu_count(), "host_cpu": model,
             "sample": "%d iterations of the same workload after 1 warm-up, "
                       "single thread, %.1f s" % (n, el)}
 

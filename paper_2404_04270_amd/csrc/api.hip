@@ -90,6 +90,14 @@ bool prof_events(hipEvent_t *start, hipEvent_t *stop)
     return true;
 }
 
+__global__ void wait_marker_kernel() {}
+
+void after_stream_wait(hipStream_t s)
+{
+    if (!g_prof_on) return;
+    hipLaunchKernelGGL(wait_marker_kernel, dim3(1), dim3(64), 0, s);
+}
+
 static int32_t check_batch(const char *who, const void *idx, int64_t B, int64_t L,
                            int64_t T)
 {

@@ -72,6 +72,8 @@ void run_job(ss_issue_queue *q, const Job &j)
     case kWaitEvent:
         if (hipStreamWaitEvent(j.stream, j.event, 0) != hipSuccess)
             rc = fail(SS_ERR_HIP, "%s: hipStreamWaitEvent failed", who);
+        else
+            after_stream_wait(j.stream);
         break;
     case kRecordEvent:
         if (hipEventRecord(j.event, j.stream) != hipSuccess)
@@ -260,6 +262,7 @@ int32_t ss_stream_wait_event(void *stream, void *event)
     if (hipStreamWaitEvent(static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(event),
                            0) != hipSuccess)
         return fail(SS_ERR_HIP, "ss_stream_wait_event: hipStreamWaitEvent failed");
+    after_stream_wait(static_cast<hipStream_t>(stream));
     return SS_OK;
 }
 

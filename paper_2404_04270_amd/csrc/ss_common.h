@@ -37,6 +37,11 @@ public:
 };
 // Events of the innermost live ProfScope, or false when profiling is off.
 bool prof_events(hipEvent_t *start, hipEvent_t *stop);
+// While profiling is on, a stream that has just been made to wait for an event
+// gets an empty kernel of its own.  The runtime attaches the wait to the next
+// command of the stream, and the event pair of that command then spans the wait
+// as well: the empty kernel takes it, so that the kernel after it is timed alone.
+void after_stream_wait(hipStream_t s);
 
 template <typename... KArgs, typename... Args>
 inline void launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t s,

@@ -186,9 +186,12 @@ class PipelinedStep:
         stream that waits on them already knows.  The events are the library's
         (device-scope release), recorded and waited for by the calling thread."""
 
+        POOL = 66                 # 64 marks are kept, one is being recorded, one spare
+
         def __init__(self):
             self.recorded = []        # (covers_up_to_batch, event), ascending
-            self.spare = []           # events of marks that were dropped, for re-use
+            # every event this object will ever use, created before the first batch
+            self.spare = [B.ss_event_create() for _ in range(self.POOL)]
             self.known = {}           # waiting stream (by position) -> batches <= this are done
 
         def record(self, stream, handle, covers: int) -> None:
@@ -233,7 +236,8 @@ class PipelinedStep:
             self.queues, self.by_queue = queues, by_queue
             self.queue = queues[own % len(queues)]
             self.recorded = []        # (covers_up_to_batch, event, ticket), ascending
-            self.spare = []           # events of marks that were dropped, for re-use
+            # every event this object will ever use, created before the first batch
+            self.spare = [self.queue.new_event() for _ in range(PipelinedStep._Marks.POOL)]
             self.known = {}
 
         def record(self, stream, handle, covers: int) -> None:
