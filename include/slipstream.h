@@ -127,6 +127,31 @@ size_t ss_backward_workspace_bytes(int32_t T, int32_t Bcap, int32_t L,
                                    int32_t dim);
 
 /*
+ * ss_embbag_backward_update for callers that cannot allocate device memory and
+ * have no workspace to pass: code under HIP stream capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  The call allocates nothing and creates no HIP
+ * object (also while ss_profile_enable is on: its launches are not timed).  What
+ * the update keeps between its launches (sorted lookup lists, histograms, partial
+ * sums) lives in a buffer of SS_NOALLOC_SCRATCH_BYTES that is part of the
+ * library's device image: every GPU the library is used on holds one copy of it
+ * until the process ends.  Same arguments, kernels and results (bit for bit) as
+ * ss_embbag_backward_update without ws / ws_bytes.
+ *   - Shapes with ss_backward_workspace_bytes(T, Bcap, L, dim) above
+ *     SS_NOALLOC_SCRATCH_BYTES are rejected with SS_ERR_WORKSPACE; nothing is
+ *     enqueued.  (26 tables x 8192 one-hot lookups x dim 64 need 5.6 MB.)
+ *   - All calls on one GPU share that GPU's buffer: two calls whose work overlaps
+ *     on one GPU (different streams, or threads) race.  Calls on one stream, one
+ *     after the other, are safe; a call never reads what an earlier one left.
+ *   - The buffer's device address is looked up on the first call on each device
+ *     (a symbol lookup, no allocation): make that first call outside a capture.
+ */
+#define SS_NOALLOC_SCRATCH_BYTES (16u << 20)
+int32_t ss_embbag_backward_update_noalloc(const ss_tables *tables, const int32_t *idx,
+                                          int32_t Bcap, int32_t L,
+                                          const int32_t *n_valid, const float *grad,
+                                          float lr, void *stream);
+
+/*
  * The same update in two halves, for callers that want to overlap them with
  * other work.  ss_embbag_backward_prepare groups the lookups of every table by
  * row (and drops the lookups of stale rows); it depends only on idx, n_valid

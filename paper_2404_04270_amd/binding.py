@@ -27,7 +27,7 @@ SYMBOLS = (
     "ss_embbag_ln_backward", "ss_issue_queue_create", "ss_issue_queue_destroy",
     "ss_issue_index_batch", "ss_issue_wait_event", "ss_issue_record_event",
     "ss_issue_wait", "ss_event_create", "ss_event_destroy", "ss_event_record",
-    "ss_stream_wait_event",
+    "ss_stream_wait_event", "ss_embbag_backward_update_noalloc",
 )
 
 
@@ -64,7 +64,7 @@ def _load():
               "ss_issue_queue_create", "ss_issue_queue_destroy", "ss_issue_index_batch",
               "ss_issue_wait_event", "ss_issue_record_event", "ss_issue_wait",
               "ss_event_create", "ss_event_destroy", "ss_event_record",
-              "ss_stream_wait_event"):
+              "ss_stream_wait_event", "ss_embbag_backward_update_noalloc"):
         getattr(lib, n).restype = C.c_int32
     return lib
 
@@ -240,6 +240,21 @@ def ss_embbag_backward_update(tables: Tables, idx: torch.Tensor,
         _dev_ptr(grad, torch.float32, "grad"), C.c_float(lr),
         _dev_ptr(ws, torch.uint8, "ws"), C.c_size_t(ws.numel()),
         _stream(stream)))
+
+
+NOALLOC_SCRATCH_BYTES = 16 << 20
+
+
+def ss_embbag_backward_update_noalloc(tables: Tables, idx: torch.Tensor,
+                                      n_valid: Optional[torch.Tensor],
+                                      grad: torch.Tensor, lr: float, stream=None) -> None:
+    Bcap, L = _idx_shape(tables, idx)
+    if grad.numel() < tables.num_tables * Bcap * tables.dim:
+        raise SlipstreamError("ss_embbag_backward_update_noalloc: grad is too small")
+    _check(_lib.ss_embbag_backward_update_noalloc(
+        C.byref(tables.c), _dev_ptr(idx, torch.int32, "idx"), C.c_int32(Bcap),
+        C.c_int32(L), _dev_ptr(n_valid, torch.int32, "n_valid"),
+        _dev_ptr(grad, torch.float32, "grad"), C.c_float(lr), _stream(stream)))
 
 
 def ss_embbag_backward_prepare(tables: Tables, idx: torch.Tensor,

@@ -60,11 +60,15 @@ constexpr size_t kProfMax = 1u << 20;
 }  // namespace
 
 static thread_local int t_prof_slot = -1;
+static thread_local int t_prof_mute = 0;
+
+ProfMute::ProfMute() { ++t_prof_mute; }
+ProfMute::~ProfMute() { --t_prof_mute; }
 
 ProfScope::ProfScope(const char *kernel, hipStream_t)
 {
     t_prof_slot = -1;
-    if (!g_prof_on) return;
+    if (!g_prof_on || t_prof_mute > 0) return;
     std::lock_guard<std::mutex> lk(g_prof_mu);
     if (g_prof.size() >= kProfMax) return;
     ProfRec r{kernel, nullptr, nullptr};

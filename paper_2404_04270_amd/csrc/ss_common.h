@@ -35,6 +35,13 @@ public:
     ProfScope(const char *kernel, hipStream_t s);
     ~ProfScope();
 };
+// While one is alive on this thread, ProfScope records nothing (for entry points
+// that must not create HIP objects).
+class ProfMute {
+public:
+    ProfMute();
+    ~ProfMute();
+};
 // Events of the innermost live ProfScope, or false when profiling is off.
 bool prof_events(hipEvent_t *start, hipEvent_t *stop);
 // While profiling is on, a stream that has just been made to wait for an event
