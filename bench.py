@@ -12,6 +12,7 @@ JSON line: whole-job samples/s ("value"), the roofline of the dominant kernel
 per-kernel durations, the skip fraction, and the CPU oracle timed on this host.
 """
 import argparse
+import gc
 import json
 import os
 import sys
@@ -192,6 +193,11 @@ class Measurement:
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
         stamps = []
+        # The interpreter's cyclic garbage collector stays out of the region: a full
+        # collection takes 20-60 ms in a process that has imported torch (measured),
+        # as long as twenty to forty steps of the default workload.
+        gc_was_on = gc.isenabled()
+        gc.disable()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         e0.record()
@@ -199,6 +205,8 @@ class Measurement:
         e1.record()
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t1
+        if gc_was_on:
+            gc.enable()
         return elapsed, e0.elapsed_time(e1), t1, stamps
 
     def kept_fraction(self):
@@ -248,6 +256,7 @@ class Measurement:
                                                         cfg.snapshot_every)
         self.run(n_prime)
         self.run(warmup)
+        gc.collect()
         elapsed, gpu_ms, t1, stamps = self.timed(steps)
         ms_per_step = 1e3 * elapsed / steps
         value = Bn * steps / elapsed

@@ -14,6 +14,7 @@ workloads listed in `CONFIGS`.
 """
 from __future__ import annotations
 
+import functools
 from dataclasses import dataclass, replace
 from typing import Optional
 
@@ -68,12 +69,15 @@ CONFIGS = {
 CFG5_THRESHOLD_SWEEP = (0.0, 1e-5, 1e-4, 1e-3)
 
 
+@functools.lru_cache(maxsize=2)
 def zipf_cdf(rows: int, alpha: float) -> np.ndarray:
-    """Cumulative distribution of P(rank k) ~ k^-alpha, k = 1..rows (fp64)."""
+    """Cumulative distribution of P(rank k) ~ k^-alpha, k = 1..rows (fp64).
+    Read-only for callers: the last two tables are kept and shared."""
     pmf = np.arange(1, rows + 1, dtype=np.float64) ** (-alpha)
     cdf = np.cumsum(pmf)
     cdf /= cdf[-1]
     cdf[-1] = 1.0
+    cdf.setflags(write=False)
     return cdf
 
 
@@ -156,10 +160,26 @@ def hot_set(idx_stream: np.ndarray, rows: int, n_hot: int) -> np.ndarray:
     n_tables = idx_stream.shape[1]
     out = np.empty((n_tables, n_hot), dtype=np.int32)
     for t in range(n_tables):
-        cnt = np.bincount(idx_stream[:, t].reshape(-1), minlength=rows)
-        # sort by (count desc, row asc): stable argsort of -count
-        order = np.argsort(-cnt, kind="stable")[:n_hot]
-        out[t] = np.sort(order).astype(np.int32)
+        if n_hot == 0:
+            continue
+        # The first n_hot rows by (count descending, row ascending), without sorting
+        # all rows: c is the n_hot-th largest count; every row above it is in, and
+        # the places left go to the rows that have exactly c, lowest ids first.
+        flat = idx_stream[:, t].reshape(-1)
+        if rows <= max(1, flat.size):
+            ids, cnt = None, np.bincount(flat, minlength=rows)       # ids = 0 .. rows-1
+        else:
+            # far more rows than lookups: count only the rows that occur
+            ids, cnt = np.unique(flat, return_counts=True)
+            if ids.size < n_hot:       # not enough accessed rows: unaccessed ones, lowest first
+                rest = np.setdiff1d(np.arange(min(rows, n_hot + ids.size)), ids)
+                out[t] = np.sort(np.concatenate([ids, rest[: n_hot - ids.size]])).astype(np.int32)
+                continue
+        c = np.partition(cnt, cnt.size - n_hot)[cnt.size - n_hot]
+        above = np.flatnonzero(cnt > c)
+        ties = np.flatnonzero(cnt == c)[: n_hot - above.size]
+        pick = np.sort(np.concatenate([above, ties]))
+        out[t] = (pick if ids is None else ids[pick]).astype(np.int32)
     return out
 
 

@@ -107,6 +107,23 @@ def test_permutation_config_and_hot_set_rule():
     assert wl.bitmap_words(33) == 2
 
 
+def test_hot_set_equals_a_full_sort_by_count_then_row():
+    """The harness picks the hot rows without sorting every row; the rule it must
+    reproduce is "first n by (count descending, row ascending)", here written out
+    as a stable full sort, on both of its paths (dense counters; far more rows than
+    lookups) and at the edges (everything hot, ties at the cut, unaccessed rows)."""
+    rng = np.random.default_rng(12)
+    for R, n, H in [(10, 200, 3), (1000, 5000, 37), (50, 10, 50), (50, 10, 49), (7, 0, 3),
+                    (100000, 20, 30), (100000, 20, 5), (5000, 30, 4999), (5000, 30, 5000)]:
+        for _ in range(5):
+            s = rng.integers(0, R, (3, 2, n // 2 + 1 if n else 0, 1)).astype(np.int32)
+            got = wl.hot_set(s, R, H)
+            for t in range(2):
+                cnt = np.bincount(s[:, t].reshape(-1), minlength=R)
+                want = np.sort(np.argsort(-cnt, kind="stable")[:H])
+                assert np.array_equal(got[t], want), (R, n, H)
+
+
 # ---------------------------------------------------- sampling block, host side
 def drop_stats(lib, count, n, pop, hot, t):
     lib.ss_drop_stats.restype = C.c_int32

@@ -1,0 +1,288 @@
+"""The whole protocol at the stated workloads, GPU against the CPU oracle in lock
+step, through the step the benchmark times (PipelinedStep with its automatic
+settings: ring, index streams, issue threads).
+
+Configs 2 and 3 run their full length at their own K, T and alpha = T*L; the
+oracle holds the whole tables.  Configs 4 and 5 (41 GB and 51 GB of tables) run
+two snapshot periods and a batch (capture and first detect pass; config 5 runs a
+third period with the second detect pass, and prices every threshold of its sweep
+at both passes) at their own K, T and batch; the
+oracle works on the compact problem of every row the run touches plus the hot
+rows, renumbered in ascending order (a row's arithmetic does not depend on other
+rows, and ascending renumbering keeps every "lowest row id" rule), and a
+device-side comparison against a copy of the initial tables shows that no other
+row moved.
+
+Checked every iteration: n_kept, skip mask, kept ids, compacted indices (bit for
+bit) and the stale bitmaps (bit for bit, on the device).  Pooled outputs: every
+`pooled_every` iterations and at every snapshot boundary (rtol 1e-5 / atol 1e-6).
+Weights: at every boundary and at the end.  Verdicts of a detect pass: bit for bit
+outside |drift - T| <= 1e-6 T + 5e-9 (the second term is three times the largest
+difference seen between the drifts of two runs whose tables differ by the rounding
+of earlier updates); mismatches inside the band would be counted as overrides, and
+every test asserts that there were none.
+"""
+import math
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+import torch
+
+from oracle.protocol import OracleRun
+from paper_2404_04270_amd import workload as wl
+
+pytestmark = pytest.mark.gpu
+RTOL, ATOL = 1e-5, 1e-6
+BAND_ABS = 5e-9
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2404_04270_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def dev():
+    return torch.device("cuda:0")
+
+
+def close_on_device(got: torch.Tensor, ref_np: np.ndarray) -> int:
+    """Number of elements of `got` outside rtol / atol of the oracle's values."""
+    ref = torch.from_numpy(np.ascontiguousarray(ref_np)).to(got.device)
+    return int(((got - ref).abs() > ATOL + RTOL * ref.abs()).sum().item())
+
+
+def bits_to_dev(bits, dev):
+    return [torch.from_numpy(b.view(np.int32).copy()).to(dev) for b in bits]
+
+
+def all_indices(w, n_iters, pool):
+    """[n_iters, T, B, L] from the seeded generator, iterations drawn side by side."""
+    wl.zipf_cdf(w.cfg.rows, w.cfg.zipf_alpha)          # built once, before the threads
+    w.indices(0, 1)
+    parts = list(pool.map(lambda it: w.indices(it, 1)[0], range(n_iters)))
+    return np.stack(parts)
+
+
+class Prefetch:
+    """Gradients of the coming iterations, drawn by worker threads while the oracle
+    (one thread, outside the interpreter lock) works on the current one."""
+
+    def __init__(self, w, n_iters, pool, depth=12):
+        self.w, self.n, self.pool, self.depth = w, n_iters, pool, depth
+        self.futures = {}
+        self.next = 0
+
+    def get(self, it):
+        while self.next < self.n and self.next < it + self.depth:
+            self.futures[self.next] = self.pool.submit(self.w.grads, self.next)
+            self.next += 1
+        return self.futures.pop(it).result()
+
+
+def run_stated(B, dev, cfg, n_iters, compact, pooled_every, sweep=()):
+    from paper_2404_04270_amd.step import PipelinedStep
+    T, R, D, Bn, L, K = cfg.num_tables, cfg.rows, cfg.dim, cfg.batch, cfg.bag, cfg.snapshot_every
+    thr = cfg.threshold
+    pool = ThreadPoolExecutor(max_workers=8)
+    w = wl.Workload(cfg)
+    idx = all_indices(w, n_iters, pool)
+    hot = wl.hot_set(idx, R, cfg.hot_rows)
+
+    if compact:
+        weights = [w.weights_device(t, dev) for t in range(T)]
+        original = [x.clone() for x in weights]
+        rows = [np.union1d(np.unique(idx[:, t]), hot[t]).astype(np.int64) for t in range(T)]
+        rmax = max(r.size for r in rows)
+        rows_dev = [torch.from_numpy(r).to(dev) for r in rows]
+        W0 = []
+        for t in range(T):
+            m = np.zeros((rmax, D), dtype=np.float32)        # oracle tables share one shape
+            m[:rows[t].size] = weights[t][rows_dev[t]].cpu().numpy()
+            W0.append(m)
+        idx_ref = np.empty_like(idx)
+        hot_ref = []
+        for t in range(T):
+            remap = np.zeros(R, dtype=np.int32)
+            remap[rows[t]] = np.arange(rows[t].size, dtype=np.int32)
+            idx_ref[:, t] = remap[idx[:, t]]
+            hot_ref.append(remap[hot[t]])
+            del remap
+        hot_ref = np.stack(hot_ref)
+    else:
+        W0 = [w.weights(t) for t in range(T)]
+        weights = [torch.from_numpy(x).to(dev) for x in W0]
+        idx_ref, hot_ref, rows = idx, hot, None
+
+    ref = OracleRun(W0, hot_ref, cfg.lr, thr, K)               # updates W0 in place
+    gpu = PipelinedStep(weights, [torch.from_numpy(h).to(dev) for h in hot], Bn, L, cfg.lr,
+                        thr, K)                                # automatic settings
+    idx_dev = torch.from_numpy(idx).to(dev)                    # resident before any submit
+    torch.cuda.synchronize()
+
+    def ref_bits_in_device_layout():
+        if not compact:
+            return bits_to_dev(ref.bits, dev)
+        out = []
+        for t in range(T):
+            flags = np.unpackbits(ref.bits[t].view(np.uint8), bitorder="little")[:rows[t].size]
+            full = np.zeros((R + 31) // 32 * 32, dtype=np.uint8)
+            full[rows[t][flags.astype(bool)]] = 1
+            out.append(torch.from_numpy(np.packbits(full, bitorder="little").view(np.int32)
+                                        .copy()).to(dev))
+        return out
+
+    def weights_mismatches():
+        bad = 0
+        for t in range(T):
+            if compact:
+                bad += close_on_device(gpu.tables.weights[t][rows_dev[t]],
+                                       ref.W[t][:rows[t].size])
+            else:
+                bad += close_on_device(gpu.tables.weights[t], ref.W[t])
+        return bad
+
+    want_bits = ref_bits_in_device_layout()
+    grads = Prefetch(w, n_iters, pool)
+    stats = dict(overrides=0, in_band=0, skipped=0, detects=0, pooled_checks=0,
+                 weight_checks=0, side_checks=0)
+    ahead = 0
+    for it in range(n_iters):
+        g = grads.get(it)
+        boundary = (it + 1) % K == 0
+        sweep_now = bool(sweep) and boundary and ref.snapshot is not None
+        if sweep_now:                       # the snapshots this iteration's pass compares with
+            prev_ref = [x.copy() for x in ref.snapshot]
+        r = ref.step(idx_ref[it], g)
+        while ahead < n_iters and gpu.room() > 0:
+            gpu.submit(idx_dev[ahead])
+            ahead += 1
+        gpu.forward()
+        nk = int(gpu.n_kept.item())
+        assert nk == r["n_kept"], it
+        assert np.array_equal(gpu.skip_mask.cpu().numpy(), r["skip"]), it
+        assert np.array_equal(gpu.kept_ids.cpu().numpy()[:nk], r["kept"]), it
+        got_idx_c = gpu.idx_c.cpu().numpy()[:, :nk]
+        if compact:
+            for t in range(T):
+                assert np.array_equal(got_idx_c[t], rows[t][r["idx_c"][t, :nk]]), (it, t)
+        else:
+            assert np.array_equal(got_idx_c, r["idx_c"][:, :nk]), it
+        for t in range(T):                  # the bitmaps this batch was classified with
+            assert torch.equal(gpu.bits[t], want_bits[t]), (it, t)
+        if it % pooled_every == 0 or boundary or it == n_iters - 1:
+            assert close_on_device(gpu.pooled[:, :nk], r["pooled"][:, :nk]) == 0, it
+            stats["pooled_checks"] += 1
+        stats["skipped"] += Bn - nk
+        if nk == Bn:
+            g_c = g
+        else:
+            g_c = np.zeros_like(g)
+            g_c[:, :nk] = g[:, r["kept"]]
+        if sweep_now:
+            prev_dev = [x.clone() for x in gpu.hot.snapshot]
+        detected = gpu.backward(torch.from_numpy(g_c).to(dev))
+        assert detected == r["detected"], it
+        if sweep_now:
+            assert detected
+            stats["side_checks"] += check_sweep_after_pass(B, gpu, ref, prev_dev, prev_ref,
+                                                           sweep)
+        if detected:
+            stats["detects"] += 1
+            r_sh, r_dr, _ = ref.last_detect
+            for t in range(T):
+                sh = gpu.hot.stale_hot[t].cpu().numpy()
+                if math.isfinite(thr) and thr > 0:
+                    border = np.abs(r_dr[t] - thr) <= 1e-6 * thr + BAND_ABS
+                else:
+                    border = np.zeros(sh.shape, dtype=bool)
+                stats["in_band"] += int(border.sum())
+                assert np.array_equal(sh[~border], r_sh[t][~border]), (it, t)
+                stats["overrides"] += int((sh != r_sh[t]).sum())
+            assert stats["overrides"] == 0, it
+            want_bits = ref_bits_in_device_layout()
+        if boundary or it == n_iters - 1:
+            assert weights_mismatches() == 0, it
+            stats["weight_checks"] += 1
+    gpu.flush()
+    torch.cuda.synchronize()
+    for t in range(T):
+        assert torch.equal(gpu.bits[t], want_bits[t]), t
+    if compact:
+        # no row outside the touched set moved, and none of the hot rows that were
+        # frozen moved after their verdict (covered by the weight checks above)
+        for t in range(T):
+            changed = (gpu.tables.weights[t] != original[t]).any(dim=1)
+            allowed = torch.zeros(R, dtype=torch.bool, device=dev)
+            allowed[rows_dev[t]] = True
+            assert int((changed & ~allowed).sum().item()) == 0, t
+    stats["stale"] = sum(int(np.unpackbits(b.view(np.uint8)).sum()) for b in ref.bits)
+    gpu.close()
+    pool.shutdown()
+    print("\n[%s] %d iterations: %s" % (cfg.name, n_iters, stats))
+    return stats
+
+
+def check_sweep_after_pass(B, gpu, ref, prev_snapshot_dev, prev_snapshot_ref, thresholds):
+    """The drift of the pass that has just run is a function of (tables now, snapshot
+    before the pass).  With copies of that snapshot, the other thresholds of the
+    sweep are priced on both sides from the same state: ss_detect_stale into scratch
+    bitmaps with no refresh, against oracle.detect_stale likewise."""
+    import oracle
+    T, H = gpu.tables.num_tables, gpu.hot.H
+    n = 0
+    for thr in thresholds:
+        scratch = B.Tables(gpu.tables.weights)
+        scratch.new_bits()
+        hs = B.HotState(scratch, gpu.hot.hot_ids)
+        for t in range(T):
+            hs.snapshot[t].copy_(prev_snapshot_dev[t])
+        B.ss_detect_stale(scratch, hs, thr, False)
+        bits = [np.zeros_like(b) for b in ref.bits]
+        r_sh, r_dr, _ = oracle.detect_stale(ref.W, bits, ref.hot_ids,
+                                            [s.copy() for s in prev_snapshot_ref], thr, False)
+        for t in range(T):
+            sh = hs.stale_hot[t].cpu().numpy()
+            if math.isfinite(thr) and thr > 0:
+                border = np.abs(r_dr[t] - thr) <= 1e-6 * thr + BAND_ABS
+            else:
+                border = np.zeros(sh.shape, dtype=bool)
+            assert np.array_equal(sh[~border], r_sh[t][~border]), (thr, t)
+            assert int((sh != r_sh[t]).sum()) == 0, (thr, t)
+            n += sh.size
+            if thr == 0.0:
+                assert not sh.any()
+    return n
+
+
+def test_config2_full_run(B, dev):
+    cfg = wl.CONFIGS[2]
+    s = run_stated(B, dev, cfg, cfg.iters, compact=False, pooled_every=1)
+    assert s["detects"] == cfg.iters // cfg.snapshot_every - 1
+    assert s["overrides"] == 0 and s["weight_checks"] == cfg.iters // cfg.snapshot_every
+
+
+def test_config3_full_run(B, dev):
+    cfg = wl.CONFIGS[3]
+    s = run_stated(B, dev, cfg, cfg.iters, compact=False, pooled_every=10)
+    assert s["detects"] == cfg.iters // cfg.snapshot_every - 1
+    assert s["overrides"] == 0 and s["weight_checks"] == cfg.iters // cfg.snapshot_every
+    torch.cuda.empty_cache()
+
+
+def test_config4_two_periods_at_full_shape(B, dev):
+    cfg = wl.CONFIGS[4]
+    s = run_stated(B, dev, cfg, 2 * cfg.snapshot_every + 1, compact=True, pooled_every=10)
+    assert s["detects"] == 1 and s["overrides"] == 0
+    torch.cuda.empty_cache()
+
+
+def test_config5_three_periods_at_full_shape(B, dev):
+    cfg = wl.CONFIGS[5]
+    s = run_stated(B, dev, cfg, 3 * cfg.snapshot_every, compact=True, pooled_every=10,
+                   sweep=wl.CFG5_THRESHOLD_SWEEP)
+    assert s["detects"] == 2 and s["overrides"] == 0
+    assert s["side_checks"] == 2 * len(wl.CFG5_THRESHOLD_SWEEP) * cfg.hot_rows
+    torch.cuda.empty_cache()
