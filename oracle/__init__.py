@@ -18,6 +18,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ss_oracle.c")
 _LIB = os.path.join(_HERE, "libss_oracle.so")
 _lib = None
+# A differently built copy of the same source (the sanitizer build of the tests)
+# can stand in for the default library: loaded as it is, never rebuilt here.
+_LIB_OVERRIDE = os.environ.get("SS_ORACLE_LIB")
 
 
 def build(force: bool = False) -> str:
@@ -34,10 +37,21 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized(out_path: str) -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (host
+    code only); a process that loads it needs the ASan runtime preloaded."""
+    subprocess.run(
+        ["gcc", "-O1", "-g", "-std=c99", "-fPIC", "-shared", "-ffp-contract=off",
+         "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+         "-fno-omit-frame-pointer", "-Wall", "-Wextra", "-o", out_path, _SRC, "-lm"],
+        check=True)
+    return out_path
+
+
 def _load():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
+        _lib = C.CDLL(_LIB_OVERRIDE if _LIB_OVERRIDE else build())
         for name in ("oracle_embbag_forward", "oracle_embbag_backward_update",
                      "oracle_detect_stale", "oracle_filter_batch",
                      "oracle_sample_drop", "oracle_drop_stats",

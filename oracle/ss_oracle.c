@@ -150,8 +150,8 @@ int oracle_embbag_backward_update(int T, int64_t R, int D, float *const *W,
  *     stale = (T > 0) and (drift <= T)
  * Readings where the paper is silent: equality counts as stale ("> T" is
  * varying); T = 0 switches detection off so that a zero threshold means plain
- * training; a stale bit, once set, is never cleared (skipped "for the
- * remaining training process", section 1), so the bitmap is OR-ed; a NaN
+ * training; a stale bit, once set, is never cleared (section 1: a stale row stays
+ * skipped until training ends), so the bitmap is OR-ed; a NaN
  * drift compares false and leaves the row varying.
  * If refresh != 0 the snapshot row is then overwritten with the current row.
  * stale_hot[t][h] (0/1), drift[t][h] and stale_count[t] (rows flagged by this
@@ -253,7 +253,8 @@ int oracle_filter_batch(int T, int64_t R, uint32_t *const *stale_bits,
  * which is |S| * D of Eq. 2.  Eq. 2 as printed sums the indicator of "varying"
  * while calling the result the dropped share; the dropped share is what is
  * wanted, so the indicator of "stale" is summed.  Nothing is modified.
- * hot_ids[t] must be ascending.
+ * Whether a row is hot, and which snapshot slot it has, is read from a plain
+ * table with one entry per row, filled from hot_ids before the loops.
  */
 int oracle_sample_drop(int T, int64_t R, int D, float *const *W,
                        int32_t *const *hot_ids, int H, float *const *snapshot,
@@ -262,6 +263,21 @@ int oracle_sample_drop(int T, int64_t R, int D, float *const *W,
 {
     for (int k = 0; k < n_thr; ++k)
         counts[k] = 0;
+    /* slot_of[t][r] = hot slot of row r of table t, or -1 */
+    int32_t *slot_of = (int32_t *)malloc((size_t)T * (size_t)R * sizeof(int32_t));
+    if (!slot_of)
+        return -2;
+    for (int64_t i = 0; i < (int64_t)T * R; ++i)
+        slot_of[i] = -1;
+    for (int t = 0; t < T; ++t)
+        for (int h = 0; h < H; ++h) {
+            int64_t r = hot_ids[t][h];
+            if (r < 0 || r >= R) {
+                free(slot_of);
+                return -1;
+            }
+            slot_of[(int64_t)t * R + r] = h;
+        }
     for (int s = 0; s < n_samples; ++s) {
         for (int k = 0; k < n_thr; ++k) {
             double thr = (double)thresholds[k];
@@ -269,16 +285,13 @@ int oracle_sample_drop(int T, int64_t R, int D, float *const *W,
             for (int t = 0; t < T; ++t) {
                 for (int l = 0; l < L; ++l) {
                     int64_t r = sidx[((int64_t)t * n_samples + s) * L + l];
-                    if (r < 0 || r >= R)
+                    if (r < 0 || r >= R) {
+                        free(slot_of);
                         return -1;
-                    int h = -1;                 /* hot slot of row r, if any */
-                    for (int lo = 0, hi = H - 1; lo <= hi;) {
-                        int mid = lo + (hi - lo) / 2;
-                        if (hot_ids[t][mid] == r) { h = mid; break; }
-                        if (hot_ids[t][mid] < r) lo = mid + 1; else hi = mid - 1;
                     }
+                    int h = slot_of[(int64_t)t * R + r];
                     if (h < 0)
-                        continue;
+                        continue;                /* not a hot row: never stale */
                     const float *w = W[t] + r * D;
                     const float *sn = snapshot[t] + (int64_t)h * D;
                     double d2 = 0.0;
@@ -294,6 +307,7 @@ int oracle_sample_drop(int T, int64_t R, int D, float *const *W,
                 ++counts[k];
         }
     }
+    free(slot_of);
     return 0;
 }
 

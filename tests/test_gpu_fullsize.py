@@ -95,7 +95,7 @@ def test_config3_full_shape_lockstep(B, dev, pipelined):
                 # the two runs' tables differ by the rounding of earlier updates
                 # (about one ulp per element), so their drifts agree to ~1e-9
                 # absolute here, not to the 1e-12 of a call on identical inputs
-                border = np.abs(r_dr[t] - 3e-4) <= 1e-6 * 3e-4 + 1e-7
+                border = np.abs(r_dr[t] - 3e-4) <= 1e-6 * 3e-4 + 5e-9
                 assert not border.any()
                 assert np.array_equal(gpu.hot.stale_hot[t].cpu().numpy(), r_sh[t])
                 np.testing.assert_allclose(gpu.hot.drift[t].cpu().numpy(), r_dr[t],

@@ -430,9 +430,10 @@ def run_lockstep(B, dev, cfg, n_iters, threshold, n_hot=None, overlap=False,
             for t in range(cfg.num_tables):
                 sh = gpu.hot.stale_hot[t].cpu().numpy()
                 if math.isfinite(threshold) and threshold > 0:
-                    # 1e-6 relative, plus the ~1e-9 by which the drifts of two
-                    # runs differ once their tables differ by rounding
-                    border = np.abs(r_dr[t] - threshold) <= 1e-6 * threshold + 1e-7
+                    # 1e-6 relative, plus three times the 1.5e-9 by which the drifts
+                    # of two runs were seen to differ once their tables differ by the
+                    # rounding of earlier updates
+                    border = np.abs(r_dr[t] - threshold) <= 1e-6 * threshold + 5e-9
                 else:
                     border = np.zeros_like(sh, dtype=bool)
                 assert np.array_equal(sh[~border], r_sh[t][~border]), (it, t)
@@ -480,7 +481,7 @@ def test_protocol_multihot_small(B, dev, overlap):
     cfg = wl.CONFIGS[4].scaled(rows=20000, batch=256, snapshot_every=5, hot_frac=0.005,
                                threshold=2e-3)
     s = run_lockstep(B, dev, cfg, 24, cfg.threshold, overlap=overlap)
-    assert s["detects"] == 3
+    assert s["detects"] == 3 and s["overrides"] == 0
 
 
 def test_protocol_pipelined_skips_and_multihot(B, dev):
@@ -493,7 +494,7 @@ def test_protocol_pipelined_skips_and_multihot(B, dev):
     cfg = wl.CONFIGS[4].scaled(rows=20000, batch=256, snapshot_every=5, hot_frac=0.005,
                                threshold=2e-3)
     s = run_lockstep(B, dev, cfg, 24, cfg.threshold, pipelined=3)
-    assert s["detects"] == 3
+    assert s["detects"] == 3 and s["overrides"] == 0
 
 
 def test_protocol_pipelined_with_little_lookahead(B, dev):
@@ -537,11 +538,11 @@ def test_protocol_issue_thread_skips_and_multihot(B, dev):
                                threshold=2e-3)
     s = run_lockstep(B, dev, cfg, 24, cfg.threshold, pipelined=3, index_streams=2,
                      issue_thread=True)
-    assert s["detects"] == 3
+    assert s["detects"] == 3 and s["overrides"] == 0
     # global radix sort, three index streams with a thread each, rows frozen midway
     cfg = wl.CONFIGS[5].scaled(rows=300000, batch=20000, snapshot_every=4, hot_frac=0.002)
     s = run_lockstep(B, dev, cfg, 14, math.inf, pipelined=1, index_streams=3, issue_thread=True)
-    assert s["detects"] == 2 and s["skipped"] > 0
+    assert s["detects"] == 2 and s["skipped"] > 0 and s["overrides"] == 0
 
 
 def test_pipelined_step_refuses_calls_out_of_order(B, dev):

@@ -15,7 +15,10 @@ row moved.
 
 Checked every iteration: n_kept, skip mask, kept ids, compacted indices (bit for
 bit) and the stale bitmaps (bit for bit, on the device).  Pooled outputs: every
-`pooled_every` iterations and at every snapshot boundary (rtol 1e-5 / atol 1e-6).
+`pooled_every` iterations and at every snapshot boundary (rtol 1e-5 / atol L * 1e-6:
+in a run side by side the tables themselves agree only within the weight tolerance,
+and a pooled vector is the sum of L rows; calls on identical inputs are held to
+atol 1e-6 in test_gpu_parity.py and test_gpu_fullsize.py).
 Weights: at every boundary and at the end.  Verdicts of a detect pass: bit for bit
 outside |drift - T| <= 1e-6 T + 5e-9 (the second term is three times the largest
 difference seen between the drifts of two runs whose tables differ by the rounding
@@ -48,10 +51,19 @@ def dev():
     return torch.device("cuda:0")
 
 
-def close_on_device(got: torch.Tensor, ref_np: np.ndarray) -> int:
+def close_on_device(got: torch.Tensor, ref_np: np.ndarray, atol: float = ATOL) -> int:
     """Number of elements of `got` outside rtol / atol of the oracle's values."""
     ref = torch.from_numpy(np.ascontiguousarray(ref_np)).to(got.device)
-    return int(((got - ref).abs() > ATOL + RTOL * ref.abs()).sum().item())
+    err = (got - ref).abs()
+    bad = err > atol + RTOL * ref.abs()
+    n = int(bad.sum().item())
+    if n:                                   # say what the worst ones look like
+        where = torch.nonzero(bad)[:8]
+        for w_ in where.tolist():
+            i = tuple(w_)
+            print("  mismatch at %s: got %.9g want %.9g (|diff| %.3g)"
+                  % (i, float(got[i]), float(ref[i]), float(err[i])))
+    return n
 
 
 def bits_to_dev(bits, dev):
@@ -173,7 +185,10 @@ def run_stated(B, dev, cfg, n_iters, compact, pooled_every, sweep=()):
         for t in range(T):                  # the bitmaps this batch was classified with
             assert torch.equal(gpu.bits[t], want_bits[t]), (it, t)
         if it % pooled_every == 0 or boundary or it == n_iters - 1:
-            assert close_on_device(gpu.pooled[:, :nk], r["pooled"][:, :nk]) == 0, it
+            # The two runs' tables differ within the weight tolerance by now (each
+            # side rounds its own updates), and a pooled vector adds L of their rows,
+            # the hottest one often several times: L times the absolute term.
+            assert close_on_device(gpu.pooled[:, :nk], r["pooled"][:, :nk], L * ATOL) == 0, it
             stats["pooled_checks"] += 1
         stats["skipped"] += Bn - nk
         if nk == Bn:
