@@ -17,10 +17,15 @@
  *   - Return value: SS_OK or an SS_ERR_* code; ss_last_error() gives the text
  *     of the calling thread's last error.  On an error nothing was enqueued.
  *   - Arguments are validated on the host.  Row indices are NOT range-checked
- *     on the device: an index outside [0, rows) is undefined behaviour.
+ *     by the kernels: an index outside [0, rows) is undefined behaviour, unless
+ *     the checked mode is on (ss_check_enable below), which turns it into an
+ *     error return.
  *   - Every pointer marked "device" is device memory owned by the caller; the
  *     library allocates nothing, keeps no state between calls and never
- *     synchronises with the host.  Work is enqueued on `stream`
+ *     synchronises with the host.  (Exceptions, each stated at its declaration:
+ *     the issue queue, the profiling aid and the checked mode hold state;
+ *     ss_embbag_backward_update_noalloc uses a buffer inside the library's
+ *     device image; the checked mode waits for the GPU.)  Work is enqueued on `stream`
  *     (a hipStream_t passed as void*; NULL is the default stream) and the
  *     buffers must stay alive until that work has finished.
  *   - The ss_tables struct itself lives in HOST memory and is only read.
@@ -437,6 +442,32 @@ int32_t ss_event_create(void **event);
 int32_t ss_event_destroy(void *event);
 int32_t ss_event_record(void *event, void *stream);
 int32_t ss_stream_wait_event(void *stream, void *event);
+
+/*
+ * Range check of lookup indices (a debugging aid, not part of the method).
+ *
+ * ss_check_indices is one pass over an index tensor that reads nothing but the
+ * indices (and *n_valid): it cannot fault on a bad index.  It is enqueued like
+ * any other call and leaves in `report` (device, uint64 [2], 8-byte aligned)
+ *     report[0] = number of entries idx[t][j][l], j < n_valid, outside [0, rows)
+ *     report[1] = (t << 32) | (j * L + l) of the first such entry in (t, j, l)
+ *                 order, or all ones if there is none
+ * for the caller to read when it likes.
+ *
+ * Checked mode: on when the environment holds SS_CHECK=1 at the library's first
+ * call, or after ss_check_enable(1).  While it is on, every entry point that
+ * takes lookup indices or hot row ids (ss_filter_batch, ss_embbag_forward*,
+ * ss_embbag_backward_update / _prepare, ss_embbag_ln_backward, ss_count_accesses,
+ * ss_detect_stale, the jobs of ss_issue_index_batch) first runs that pass on
+ * `stream`, WAITS for it on the host and, if an id is out of range, returns
+ * SS_ERR_INVALID_ARG with the place in ss_last_error(); nothing else has been
+ * enqueued then, so no kernel of the library faults on the input.  The mode
+ * costs a host synchronisation per call and 16 bytes of device memory per GPU
+ * (allocated on first use); ss_embbag_backward_update_noalloc is not covered.
+ */
+int32_t ss_check_indices(int32_t num_tables, int64_t rows, const int32_t *idx, int32_t B,
+                         int32_t L, const int32_t *n_valid, uint64_t *report, void *stream);
+void ss_check_enable(int32_t on);
 
 /*
  * Measurement aid, off by default (not part of the method).  While enabled,

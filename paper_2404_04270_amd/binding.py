@@ -28,6 +28,7 @@ SYMBOLS = (
     "ss_issue_index_batch", "ss_issue_wait_event", "ss_issue_record_event",
     "ss_issue_wait", "ss_event_create", "ss_event_destroy", "ss_event_record",
     "ss_stream_wait_event", "ss_embbag_backward_update_noalloc",
+    "ss_check_indices", "ss_check_enable",
 )
 
 
@@ -64,8 +65,10 @@ def _load():
               "ss_issue_queue_create", "ss_issue_queue_destroy", "ss_issue_index_batch",
               "ss_issue_wait_event", "ss_issue_record_event", "ss_issue_wait",
               "ss_event_create", "ss_event_destroy", "ss_event_record",
-              "ss_stream_wait_event", "ss_embbag_backward_update_noalloc"):
+              "ss_stream_wait_event", "ss_embbag_backward_update_noalloc",
+              "ss_check_indices"):
         getattr(lib, n).restype = C.c_int32
+    lib.ss_check_enable.restype = None
     return lib
 
 
@@ -80,6 +83,28 @@ def _check(rc: int):
 
 def ss_last_error() -> str:
     return _lib.ss_last_error().decode("utf-8", "replace")
+
+
+def ss_check_enable(on: bool) -> None:
+    """Checked mode: ids are range-checked (with a host synchronisation) before
+    every call that takes them; out-of-range ids raise instead of faulting."""
+    _lib.ss_check_enable(C.c_int32(int(on)))
+
+
+def ss_check_indices(num_tables: int, rows: int, idx: torch.Tensor,
+                     n_valid: Optional[torch.Tensor], report: torch.Tensor,
+                     stream=None) -> None:
+    """report: int64 [2] on the device: (number of out-of-range entries,
+    table << 32 | position of the first one, or -1)."""
+    if idx.dim() != 3 or idx.shape[0] != num_tables:
+        raise SlipstreamError("ss_check_indices: idx must be [T, B, L]")
+    if report.numel() < 2:
+        raise SlipstreamError("ss_check_indices: report needs two words")
+    _check(_lib.ss_check_indices(
+        C.c_int32(num_tables), C.c_int64(rows), _dev_ptr(idx, torch.int32, "idx"),
+        C.c_int32(idx.shape[1]), C.c_int32(idx.shape[2]),
+        _dev_ptr(n_valid, torch.int32, "n_valid"), _dev_ptr(report, torch.int64, "report"),
+        _stream(stream)))
 
 
 def ss_profile_enable(on: bool) -> None:

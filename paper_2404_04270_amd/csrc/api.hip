@@ -234,6 +234,9 @@ int32_t ss_filter_batch(const ss_tables *tables, const int32_t *idx, int32_t B,
     const int32_t rc = check_filter("ss_filter_batch", tables, idx, B, L, skip_mask,
                                     kept_ids, n_kept, idx_c, ws, ws_bytes);
     if (rc) return rc;
+    if (int32_t bad = checked_indices("ss_filter_batch", tables->num_tables, tables->rows, idx,
+                                      B, L, nullptr, static_cast<hipStream_t>(stream)))
+        return bad;
     return launch_filter(tables, idx, B, L, alpha, skip_mask, kept_ids, n_kept,
                          idx_c, ws, static_cast<hipStream_t>(stream));
 }
@@ -250,6 +253,9 @@ int32_t ss_embbag_forward(const ss_tables *tables, const int32_t *idx,
     if (!out) return fail(SS_ERR_INVALID_ARG, "%s: out is NULL", who);
     if (reinterpret_cast<uintptr_t>(out) % 16 != 0)
         return fail(SS_ERR_INVALID_ARG, "%s: out is not 16-byte aligned", who);
+    rc = checked_indices(who, tables->num_tables, tables->rows, idx, Bcap, L, n_valid,
+                         static_cast<hipStream_t>(stream));
+    if (rc) return rc;
     return launch_forward(tables, idx, Bcap, L, n_valid, out,
                           static_cast<hipStream_t>(stream));
 }
@@ -270,6 +276,9 @@ int32_t ss_embbag_backward_prepare(const ss_tables *tables, const int32_t *idx,
     int32_t rc = check_backward(who, tables, Bcap, L, ws, ws_bytes);
     if (rc) return rc;
     if (!idx) return fail(SS_ERR_INVALID_ARG, "%s: idx is NULL", who);
+    rc = checked_indices(who, tables->num_tables, tables->rows, idx, Bcap, L, n_valid,
+                         static_cast<hipStream_t>(stream));
+    if (rc) return rc;
     return launch_backward_prepare(tables, idx, Bcap, L, n_valid, ws,
                                    static_cast<hipStream_t>(stream));
 }
@@ -287,6 +296,8 @@ int32_t ss_embbag_forward_grouped(const ss_tables *tables, const int32_t *idx,
     if (reinterpret_cast<uintptr_t>(out) % 16 != 0)
         return fail(SS_ERR_INVALID_ARG, "%s: out is not 16-byte aligned", who);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    rc = checked_indices(who, tables->num_tables, tables->rows, idx, Bcap, L, n_valid, s);
+    if (rc) return rc;
     if (can_fuse_forward_group(tables, Bcap, L)) {
         uint2 *ent;
         int NP;
@@ -323,6 +334,9 @@ int32_t ss_embbag_backward_update(const ss_tables *tables, const int32_t *idx,
     if (!idx) return fail(SS_ERR_INVALID_ARG, "%s: idx is NULL", who);
     rc = check_grad(who, grad);
     if (rc) return rc;
+    rc = checked_indices(who, tables->num_tables, tables->rows, idx, Bcap, L, n_valid,
+                         static_cast<hipStream_t>(stream));
+    if (rc) return rc;
     rc = launch_backward_prepare(tables, idx, Bcap, L, n_valid, ws,
                                  static_cast<hipStream_t>(stream));
     if (rc) return rc;
@@ -345,6 +359,9 @@ int32_t ss_detect_stale(const ss_tables *tables, int32_t *const *hot_ids,
     if (H < 1) return fail(SS_ERR_INVALID_ARG, "%s: H = %d", who, H);
     if (threshold != threshold)
         return fail(SS_ERR_INVALID_ARG, "%s: threshold is NaN", who);
+    rc = checked_hot_ids(who, tables->num_tables, tables->rows, hot_ids, H,
+                         static_cast<hipStream_t>(stream));
+    if (rc) return rc;
     return launch_detect(tables, hot_ids, H, snapshot, threshold,
                          refresh_snapshot != 0, stale_hot, drift, stale_count,
                          static_cast<hipStream_t>(stream));
@@ -422,6 +439,9 @@ int32_t ss_count_accesses(int32_t num_tables, int64_t rows, const int32_t *idx, 
     rc = check_batch(who, idx, B, L, num_tables);
     if (rc) return rc;
     if (!counts) return fail(SS_ERR_INVALID_ARG, "%s: counts is NULL", who);
+    rc = checked_indices(who, num_tables, rows, idx, B, L, n_valid,
+                         static_cast<hipStream_t>(stream));
+    if (rc) return rc;
     return launch_count_accesses(num_tables, idx, B, L, n_valid, counts,
                                  static_cast<hipStream_t>(stream));
 }
@@ -550,6 +570,9 @@ int32_t ss_embbag_forward_ln(const ss_tables *tables, const int32_t *idx, int32_
         rc = check_f4_all(who, ptrs, names, 3);
         if (rc) return rc;
     }
+    rc = checked_indices(who, tables->num_tables, tables->rows, idx, Bcap, L, n_valid,
+                         static_cast<hipStream_t>(stream));
+    if (rc) return rc;
     return launch_layernorm_forward(tables->num_tables, tables->dim, nullptr, tables->weights,
                                     idx, L, Bcap, n_valid, gamma, beta, eps, y, mean, rstd,
                                     static_cast<hipStream_t>(stream));
@@ -613,6 +636,9 @@ int32_t ss_embbag_ln_backward(const ss_tables *tables, const int32_t *idx, int32
         rc = check_f4_all(who, ptrs, names, 5);
         if (rc) return rc;
     }
+    rc = checked_indices(who, tables->num_tables, tables->rows, idx, Bcap, L, n_valid,
+                         static_cast<hipStream_t>(stream));
+    if (rc) return rc;
     return launch_layernorm_backward(tables->num_tables, tables->dim, dy, nullptr,
                                      tables->weights, idx, L, Bcap, n_valid, gamma, mean, rstd,
                                      dx, dgamma, dbeta, ws, static_cast<hipStream_t>(stream));

@@ -80,6 +80,9 @@ void run_job(ss_issue_queue *q, const Job &j)
             rc = fail(SS_ERR_HIP, "%s: hipEventRecord failed", who);
         break;
     case kIndexBatch:
+        rc = checked_indices(who, j.tables.num_tables, j.tables.rows, j.idx, j.B, j.L, nullptr,
+                             j.stream);
+        if (rc != SS_OK) break;
         rc = launch_filter(&j.tables, j.idx, j.B, j.L, j.alpha, j.skip_mask, j.kept_ids,
                            j.n_kept, j.idx_c, j.ws_filter, j.stream);
         if (rc == SS_OK)

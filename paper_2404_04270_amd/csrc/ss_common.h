@@ -25,6 +25,16 @@ int32_t check_filter(const char *who, const ss_tables *tables, const int32_t *id
 int32_t check_backward(const char *who, const ss_tables *tables, int32_t Bcap,
                        int32_t L, const void *ws, size_t ws_bytes);
 
+// Checked mode (SS_CHECK=1 / ss_check_enable): the ids are range-checked by a
+// kernel that reads nothing else, the host waits for its report, and an id
+// outside [0, rows) becomes SS_ERR_INVALID_ARG before anything else is
+// enqueued.  Both return SS_OK at once when the mode is off.
+bool check_mode();
+int32_t checked_indices(const char *who, int T, int64_t rows, const int32_t *idx, int cap,
+                        int L, const int32_t *n_valid, hipStream_t s);
+int32_t checked_hot_ids(const char *who, int T, int64_t rows, int32_t *const *hot_ids, int H,
+                        hipStream_t s);
+
 // Optional per-kernel timing (ss_profile_enable).  While a ProfScope is alive on
 // this thread and profiling is on, launch() attaches a pair of events to the
 // kernel it dispatches; the runtime stamps them with the start and the end of
