@@ -375,6 +375,35 @@ def copy_rate(torch, dev):
     return 5 * 2 * ca.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
+def random_row_rate(torch, B, m):
+    """What gathers of random rows of this length sustain on this GPU, through the
+    library's own lookup kernel: uniform random rows of the workload's tables (all
+    distinct, so every row comes from HBM), eight times the lookups of a batch per
+    launch, four index tensors in turn.  One-hot shapes move a row in and a row out
+    per lookup, multi-hot ones L rows in per row out; both sides are counted."""
+    cfg, dev = m.cfg, torch.device("cuda:0")
+    T, R, D, L = cfg.num_tables, cfg.rows, cfg.dim, cfg.bag
+    n = min(8 * cfg.batch, max(1, R // (2 * L)))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+    idx = [torch.randint(0, R, (T, n, L), dtype=torch.int32, device=dev, generator=gen)
+           for _ in range(4)]
+    out = torch.empty(T, n, D, dtype=torch.float32, device=dev)
+    for k in range(4):
+        B.ss_embbag_forward(m.step.tables, idx[k], None, out)
+    torch.cuda.synchronize()
+    B.ss_profile_enable(True)
+    for k in range(8):
+        B.ss_embbag_forward(m.step.tables, idx[k % 4], None, out)
+    torch.cuda.synchronize()
+    B.ss_profile_enable(False)
+    launches, ms = B.ss_profile_report()["forward_kernel"]
+    us = 1e3 * ms / launches
+    moved = T * n * (L + 1) * D * 4 + T * n * L * 4
+    return {"rows_per_launch": T * n * L, "row_bytes": D * 4, "kernel_us": us,
+            "GBs": moved / us / 1e3}
+
+
 def main():
     args = parse()
     args.pipeline = not (args.serial or args.overlap or args.grouped_forward)
@@ -401,6 +430,11 @@ def main():
     copy_gbs = copy_rate(torch, dev)
     rec["roofline"]["measured_copy_GBs"] = copy_gbs
     rec["roofline"]["frac_of_measured_copy"] = rec["roofline"]["achieved"] / copy_gbs
+    # the other measured ceiling: rows of this length at random places, which is what
+    # every kernel of the path reads and writes
+    rows = random_row_rate(torch, B, m)
+    rec["roofline"]["measured_random_rows"] = rows
+    rec["roofline"]["frac_of_measured_random_rows"] = rec["roofline"]["achieved"] / rows["GBs"]
 
     out = {
         "metric": "train samples/s through embedding fwd+update+stale-skip; achieved HBM GB/s",
