@@ -73,6 +73,9 @@ def parse():
                     help="only the workload named by --config: leave out the sub-records of "
                          "the multi-hot workload and of the headline workload with all hot "
                          "rows frozen")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="leave out the measured ceilings (device copy, rows at random places): "
+                         "their launches would be averaged into a profiler's per-kernel figures")
     ap.add_argument("--extra-steps", type=int, default=1000,
                     help="timed steps of each sub-record (at least --steps)")
     ap.add_argument("--permute", action="store_true",
@@ -90,6 +93,10 @@ def parse():
                     help="after the timed steps, also time the hot-set identification "
                          "(access counters over the ring of batches, then the top-H rows "
                          "of every table) and report it beside the step")
+    ap.add_argument("--row-gather-probe", action="store_true",
+                    help="after the timed steps, take the access pattern of the lookup and update "
+                         "kernels apart (cold Zipf batches, their distinct rows once each, uniform "
+                         "random rows, cache-resident rows, the head of the distribution removed)")
     ap.add_argument("--layernorm-probe", action="store_true",
                     help="after the timed steps, also time LayerNorm forward and backward "
                          "over the pooled vectors of one batch")
@@ -404,6 +411,103 @@ def random_row_rate(torch, B, m):
             "GBs": moved / us / 1e3}
 
 
+def row_gather_probe(torch, B, m):
+    """Where the time of the lookup and update kernels goes at this workload: the
+    same kernels on index tensors that take the access pattern apart.  Every case
+    cycles through 16 different batches, so that rows are cold without a flush
+    (a fill leaves dirty lines whose write-back would be charged to the kernel)."""
+    cfg, dev = m.cfg, torch.device("cuda:0")
+    T, R, D, Bn, L = cfg.num_tables, cfg.rows, cfg.dim, cfg.batch, cfg.bag
+    NB = 16
+    idx = m.w.indices(1000, NB)                                   # [NB, T, B, L]
+    tables = B.Tables(m.step.tables.weights)                      # same weights, own bitmaps
+    bits = tables.new_bits()
+    rng = np.random.default_rng(5)
+
+    def time_forward(batches, reps=2 * NB):
+        d = [torch.from_numpy(np.ascontiguousarray(b)).to(dev) for b in batches]
+        out = torch.empty(T, batches[0].shape[1], D, dtype=torch.float32, device=dev)
+        for k in range(len(d)):
+            B.ss_embbag_forward(tables, d[k], None, out)
+        torch.cuda.synchronize()
+        B.ss_profile_enable(True)
+        for k in range(reps):
+            B.ss_embbag_forward(tables, d[k % len(d)], None, out)
+        torch.cuda.synchronize()
+        B.ss_profile_enable(False)
+        n, ms = B.ss_profile_report()["forward_kernel"]
+        rows = float(np.mean([sum(np.unique(b[t]).size for t in range(T)) for b in batches[:4]]))
+        return {"lookups": int(T * batches[0].shape[1] * batches[0].shape[2]),
+                "distinct_rows": rows, "distinct_MB": rows * D * 4 / 1e6, "kernel_us": 1e3 * ms / n}
+
+    out = {}
+    zipf = [idx[k] for k in range(NB)]
+    out["zipf_batches_cold"] = time_forward(zipf)
+    out["zipf_batches_two_in_turn"] = time_forward(zipf[:2], reps=16)
+    # the distinct rows of each batch, looked up once each (bags of L, random order)
+    per = min(np.unique(idx[k, t]).size for k in range(NB) for t in range(T)) // L * L
+    once = [np.stack([rng.permutation(np.unique(idx[k, t]))[:per].reshape(-1, L)
+                      for t in range(T)]).astype(np.int32) for k in range(NB)]
+    out["distinct_rows_once_each"] = time_forward(once)
+    out["as_many_uniform_random_rows"] = time_forward(
+        [rng.integers(0, R, once[0].shape).astype(np.int32) for _ in range(NB)])
+    out["all_lookups_within_128_rows"] = time_forward(
+        [(idx[k] % 128).astype(np.int32) for k in range(NB)])
+
+    # the update with the most popular rows taken out (through the stale bitmap), and the
+    # lookup with those lookups removed from the bags: what a separate path for the
+    # head of the distribution could gain at most
+    ws = torch.empty(B.ss_backward_workspace_bytes(T, Bn, L, D), dtype=torch.uint8, device=dev)
+    idx_d = [torch.from_numpy(idx[k]).to(dev) for k in range(NB)]
+    order = [np.argsort(-np.bincount(idx[:, t].reshape(-1), minlength=R)[:1 << 16])[:32]
+             for t in range(T)]                                   # most popular rows per table
+    backup = [w.clone() for w in tables.weights] if cfg.table_bytes < 8e9 else None
+    for nh in (0, 8, 32):
+        for t in range(T):
+            bits[t].zero_()
+            if nh:
+                head = torch.from_numpy(order[t][:nh].astype(np.int64)).to(dev)
+                flags = torch.zeros(bits[t].numel() * 32, dtype=torch.bool, device=dev)
+                flags[head] = True
+                words = (flags.view(-1, 32).to(torch.int64) << torch.arange(32, device=dev)).sum(1)
+                bits[t].copy_(torch.where(words >= 2 ** 31, words - 2 ** 32, words).to(torch.int32))
+
+        def update(k):
+            B.ss_embbag_backward_prepare(tables, idx_d[k % NB], None, ws)
+            B.ss_embbag_backward_apply(tables, Bn, L, m.grads[k % m.n_grads], cfg.lr, ws)
+        for k in range(NB):
+            update(k)
+        torch.cuda.synchronize()
+        B.ss_profile_enable(True)
+        for k in range(2 * NB):
+            update(k)
+        torch.cuda.synchronize()
+        B.ss_profile_enable(False)
+        prof = B.ss_profile_report()
+        rec = {"apply_us": 1e3 * prof["apply_kernel"][1] / prof["apply_kernel"][0],
+               "fixup_us": 1e3 * prof["fixup_kernel"][1] / prof["fixup_kernel"][0]}
+        if nh and L > 1:
+            is_head = [np.isin(idx[:, t], order[t][:nh]) for t in range(T)]
+            share = float(np.mean(is_head))
+            Lr = max(1, int(round(L * (1 - share))))
+            cold = np.empty((NB, T, Bn, Lr), np.int32)
+            for k in range(NB):
+                for t in range(T):
+                    a = idx[k, t]
+                    o = np.argsort(is_head[t][k], axis=1, kind="stable")    # other lookups first
+                    srt = np.take_along_axis(a, o, axis=1)[:, :Lr]
+                    hd = np.take_along_axis(is_head[t][k], o, axis=1)[:, :Lr]
+                    first = np.where(hd[:, :1], (a[:, :1] + 1) % R, srt[:, :1])
+                    cold[k, t] = np.where(hd, first, srt)     # short bags repeat a row of theirs
+            rec["head_share_of_lookups"] = share
+            rec["forward_without_head"] = time_forward([cold[k] for k in range(NB)])
+        out["head_rows_removed_%d" % nh] = rec
+    if backup is not None:
+        for w, b in zip(tables.weights, backup):
+            w.copy_(b)
+    return out
+
+
 def main():
     args = parse()
     args.pipeline = not (args.serial or args.overlap or args.grouped_forward)
@@ -427,14 +531,15 @@ def main():
 
     m = Measurement(args, args.config, args.threshold)
     rec = m.record(args.steps, args.warmup)
-    copy_gbs = copy_rate(torch, dev)
-    rec["roofline"]["measured_copy_GBs"] = copy_gbs
-    rec["roofline"]["frac_of_measured_copy"] = rec["roofline"]["achieved"] / copy_gbs
-    # the other measured ceiling: rows of this length at random places, which is what
-    # every kernel of the path reads and writes
-    rows = random_row_rate(torch, B, m)
-    rec["roofline"]["measured_random_rows"] = rows
-    rec["roofline"]["frac_of_measured_random_rows"] = rec["roofline"]["achieved"] / rows["GBs"]
+    if not args.no_ceilings:
+        copy_gbs = copy_rate(torch, dev)
+        rec["roofline"]["measured_copy_GBs"] = copy_gbs
+        rec["roofline"]["frac_of_measured_copy"] = rec["roofline"]["achieved"] / copy_gbs
+        # the other measured ceiling: rows of this length at random places, which is what
+        # every kernel of the path reads and writes
+        rows = random_row_rate(torch, B, m)
+        rec["roofline"]["measured_random_rows"] = rows
+        rec["roofline"]["frac_of_measured_random_rows"] = rec["roofline"]["achieved"] / rows["GBs"]
 
     out = {
         "metric": "train samples/s through embedding fwd+update+stale-skip; achieved HBM GB/s",
@@ -448,6 +553,8 @@ def main():
     step, cfg = m.step, m.cfg
     if args.sampling_probe > 0:
         out["sampling_block"] = sampling_probe(B, step, m.idx_d, args.sampling_probe, m.thr)
+    if args.row_gather_probe:
+        out["row_gather_probe"] = row_gather_probe(torch, B, m)
     if args.layernorm_probe:
         out["layernorm"] = layernorm_probe(B, step, m.grads)
     if args.hotset_probe:
