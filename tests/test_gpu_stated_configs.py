@@ -2,11 +2,10 @@
 step, through the step the benchmark times (PipelinedStep with its automatic
 settings: ring, index streams, issue threads).
 
-Configs 2 and 3 run their full length at their own K, T and alpha = T*L; the
-oracle holds the whole tables.  Configs 4 and 5 (41 GB and 51 GB of tables) run
-two snapshot periods and a batch (capture and first detect pass; config 5 runs a
-third period with the second detect pass, and prices every threshold of its sweep
-at both passes) at their own K, T and batch; the
+All five stated workloads run their full length at their own K, T and
+alpha = T*L (config 1 in test_gpu_parity.py).  For configs 2 and 3 the oracle holds
+the whole tables.  For configs 4 and 5 (41 GB and 51 GB of tables; config 5 also
+prices every threshold of its sweep at each of its detect passes) the
 oracle works on the compact problem of every row the run touches plus the hot
 rows, renumbered in ascending order (a row's arithmetic does not depend on other
 rows, and ascending renumbering keeps every "lowest row id" rule), and a
@@ -287,17 +286,18 @@ def test_config3_full_run(B, dev):
     torch.cuda.empty_cache()
 
 
-def test_config4_two_periods_at_full_shape(B, dev):
+def test_config4_full_run_at_full_shape(B, dev):
     cfg = wl.CONFIGS[4]
-    s = run_stated(B, dev, cfg, 2 * cfg.snapshot_every + 1, compact=True, pooled_every=10)
-    assert s["detects"] == 1 and s["overrides"] == 0
+    s = run_stated(B, dev, cfg, cfg.iters, compact=True, pooled_every=20)
+    assert s["detects"] == cfg.iters // cfg.snapshot_every - 1 and s["overrides"] == 0
     torch.cuda.empty_cache()
 
 
-def test_config5_three_periods_at_full_shape(B, dev):
+def test_config5_full_run_at_full_shape_with_its_threshold_sweep(B, dev):
     cfg = wl.CONFIGS[5]
-    s = run_stated(B, dev, cfg, 3 * cfg.snapshot_every, compact=True, pooled_every=10,
+    s = run_stated(B, dev, cfg, cfg.iters, compact=True, pooled_every=20,
                    sweep=wl.CFG5_THRESHOLD_SWEEP)
-    assert s["detects"] == 2 and s["overrides"] == 0
-    assert s["side_checks"] == 2 * len(wl.CFG5_THRESHOLD_SWEEP) * cfg.hot_rows
+    detects = cfg.iters // cfg.snapshot_every - 1
+    assert s["detects"] == detects and s["overrides"] == 0
+    assert s["side_checks"] == detects * len(wl.CFG5_THRESHOLD_SWEEP) * cfg.hot_rows
     torch.cuda.empty_cache()
