@@ -444,6 +444,120 @@ int32_t ss_event_record(void *event, void *stream);
 int32_t ss_stream_wait_event(void *stream, void *event);
 
 /*
+ * The training iteration as a whole (Algorithm 1: drop the inputs that only
+ * reach stale entries, train on the rest, every K iterations compare the hot rows
+ * with their last snapshot; the first period is the warm-up of section 3.1.1 and
+ * ends with the capture of the first snapshot), scheduled so that the index work
+ * of the coming batches (ss_filter_batch, ss_embbag_backward_prepare: they read
+ * indices and stale bitmaps only) runs on index streams of the object's own while
+ * the current batch is in its lookup and update kernels on the caller's training
+ * stream.  Results are those of the calls issued one after the other on one
+ * stream, bit for bit: the only reordering is that index work of later batches
+ * runs before the update of earlier ones, which it does not read; batches after
+ * one that ends with a detect pass are held back until that pass is enqueued.
+ *
+ * An ss_step is a stateful host object: it owns its index streams (default
+ * priority), a fixed pool of events created at ss_step_create, and, if the plan
+ * asks for them, issue threads (ss_issue_queue).  It allocates no device memory:
+ * the caller hands over a ring of buffer sets and the pooled output.  Use from
+ * one host thread.  Per batch, in this order:
+ *     ss_step_submit(idx)      as far ahead as ss_step_room() allows (up to two
+ *                              thirds of the ring); idx must stay untouched until
+ *                              the batch's ss_step_backward has been called.  If
+ *                              idx is still being produced on some stream, pass
+ *                              the event recorded after its producer (a
+ *                              hipEvent_t as void *), else NULL
+ *     ss_step_forward          pooled lookup of the oldest submitted batch into
+ *                              `pooled` on the training stream; *set_used (may be
+ *                              NULL) = the buffer set that holds this batch's
+ *                              skip_mask, kept_ids, n_kept and idx_c
+ *     ss_step_backward(grad)   update with the gradients of the kept samples
+ *                              (layout of ss_embbag_backward_update), then, when
+ *                              the snapshot period ends, the capture or the
+ *                              detect pass; *detected (may be NULL) = 1 after a
+ *                              detect pass
+ * ss_step_flush returns once everything submitted so far has been handed to its
+ * stream (with issue threads; a no-op otherwise), so that a device
+ * synchronisation after it covers that work.  ss_step_destroy ends the threads,
+ * waits for the index streams and releases streams and events (the one call of
+ * this group that waits for the GPU).  Calls out of order return
+ * SS_ERR_INVALID_ARG and enqueue nothing.
+ *
+ * The plan: `every` batches between two cross-stream events, `index_streams`,
+ * `issue_threads` (0: the calling thread enqueues everything) and the number of
+ * buffer sets, 3 * every * index_streams.  ss_step_plan_for fills in what the
+ * caller left at 0 (every, index_streams) or -1 (issue_threads) with the measured
+ * choices for the shape, and sets num_sets.
+ */
+typedef struct {
+    int32_t every;
+    int32_t index_streams;
+    int32_t issue_threads;
+    int32_t num_sets;
+} ss_step_plan;
+
+/* One buffer set of the ring: the outputs of ss_filter_batch for the batch that
+ * occupies it and the workspaces of that batch (sizes as the workspace queries
+ * give them for T, B, L, dim); all device memory owned by the caller. */
+typedef struct {
+    uint8_t *skip_mask;    /* [B] */
+    int32_t *kept_ids;     /* [B] */
+    int32_t *n_kept;       /* one int32 */
+    int32_t *idx_c;        /* [T][B][L] */
+    void *ws_filter;
+    size_t ws_filter_bytes;
+    void *ws_backward;
+    size_t ws_backward_bytes;
+} ss_step_set;
+
+typedef struct ss_step ss_step;
+int32_t ss_step_plan_for(int32_t T, int32_t B, int32_t L, ss_step_plan *plan);
+/* hot_ids, snapshot, stale_hot, drift, stale_count: as for ss_detect_stale;
+ * sets: HOST array of plan->num_sets entries (copied); pooled: device fp32
+ * [T][B][dim]; train_stream: the caller's stream (NULL: the default stream);
+ * alpha as for ss_filter_batch (T * L: drop the inputs whose every lookup is stale). */
+int32_t ss_step_create(const ss_tables *tables, int32_t B, int32_t L, int32_t alpha, float lr,
+                       float threshold, int32_t snapshot_every, int32_t *const *hot_ids,
+                       int32_t H, float **snapshot, uint8_t **stale_hot, double **drift,
+                       uint32_t *stale_count, const ss_step_plan *plan, const ss_step_set *sets,
+                       float *pooled, void *train_stream, ss_step **out);
+int32_t ss_step_destroy(ss_step *step);
+int32_t ss_step_room(const ss_step *step);
+int32_t ss_step_submit(ss_step *step, const int32_t *idx, void *ready_event);
+int32_t ss_step_forward(ss_step *step, int32_t *set_used);
+int32_t ss_step_backward(ss_step *step, const float *grad, int32_t *detected);
+int32_t ss_step_flush(ss_step *step);
+
+/*
+ * The same scheduler with every operation it would enqueue handed to a callback
+ * instead (no GPU work at all): a test can record the program of streams, event
+ * records and waits that a sequence of ss_step_* calls produces, execute it under
+ * a scheduler of its own and check that every kernel would find its inputs
+ * complete.  Streams are numbered 0 .. index_streams - 1, the training stream is
+ * -1; events are numbered from 1; sets are ring positions.  The q_* callbacks
+ * stand for jobs handed to issue queue `queue` (they may be issued later; *ticket
+ * receives the job's number) and q_wait_issued for "block until that job has been
+ * issued".  Every callback returns SS_OK or an error code, which the call in
+ * progress passes on.
+ */
+typedef struct {
+    void *user;
+    int32_t (*index_now)(void *user, int32_t stream, int32_t set);
+    int32_t (*q_index)(void *user, int32_t queue, int32_t stream, int32_t set, uint64_t *ticket);
+    int32_t (*lookup)(void *user, int32_t set);
+    int32_t (*update)(void *user, int32_t set);
+    int32_t (*detect)(void *user, int32_t with_threshold);
+    int32_t (*record_now)(void *user, int32_t event, int32_t stream);
+    int32_t (*wait_now)(void *user, int32_t stream, int32_t event);
+    int32_t (*q_record)(void *user, int32_t queue, int32_t event, int32_t stream,
+                        uint64_t *ticket);
+    int32_t (*q_wait)(void *user, int32_t queue, int32_t event, int32_t stream, uint64_t *ticket);
+    int32_t (*q_wait_issued)(void *user, int32_t queue, uint64_t ticket);
+} ss_step_trace_ops;
+int32_t ss_step_create_traced(const ss_step_plan *plan, int32_t snapshot_every,
+                              const ss_step_trace_ops *callbacks, ss_step **out);
+
+/*
  * Range check of lookup indices (a debugging aid, not part of the method).
  *
  * ss_check_indices is one pass over an index tensor that reads nothing but the

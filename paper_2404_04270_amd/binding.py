@@ -29,6 +29,9 @@ SYMBOLS = (
     "ss_issue_wait", "ss_event_create", "ss_event_destroy", "ss_event_record",
     "ss_stream_wait_event", "ss_embbag_backward_update_noalloc",
     "ss_check_indices", "ss_check_enable",
+    "ss_step_plan_for", "ss_step_create", "ss_step_destroy", "ss_step_room",
+    "ss_step_submit", "ss_step_forward", "ss_step_backward", "ss_step_flush",
+    "ss_step_create_traced",
 )
 
 
@@ -66,7 +69,9 @@ def _load():
               "ss_issue_wait_event", "ss_issue_record_event", "ss_issue_wait",
               "ss_event_create", "ss_event_destroy", "ss_event_record",
               "ss_stream_wait_event", "ss_embbag_backward_update_noalloc",
-              "ss_check_indices"):
+              "ss_check_indices", "ss_step_plan_for", "ss_step_create", "ss_step_destroy",
+              "ss_step_room", "ss_step_submit", "ss_step_forward", "ss_step_backward",
+              "ss_step_flush", "ss_step_create_traced"):
         getattr(lib, n).restype = C.c_int32
     lib.ss_check_enable.restype = None
     return lib
@@ -578,98 +583,8 @@ def ss_embbag_ln_backward(tables: Tables, idx: torch.Tensor, n_valid: Optional[t
         _stream(stream)))
 
 
-# ---------------------------------------------------------------------------
-# Calls with their arguments marshalled once.  A training loop issues the same
-# few calls with the same buffers thousands of times; checking and converting
-# every argument each time costs more host time than the GPU needs for a step
-# at small shapes.  prepared_*() checks the buffers once and returns a function
-# that takes only what changes (a tensor or two and the stream handle).
-# ---------------------------------------------------------------------------
 def stream_handle(stream=None) -> C.c_void_p:
     return _stream(stream)
-
-
-def prepared_filter_batch(tables: Tables, B: int, L: int, alpha: int,
-                          skip_mask: torch.Tensor, kept_ids: torch.Tensor,
-                          n_kept: torch.Tensor, idx_c: torch.Tensor, ws: torch.Tensor):
-    """call(idx, handle): idx int32 [T, B, L] contiguous on the device (not rechecked)."""
-    if skip_mask.numel() < B or kept_ids.numel() < B or n_kept.numel() < 1 \
-            or idx_c.numel() < tables.num_tables * B * L:
-        raise SlipstreamError("prepared_filter_batch: an output tensor is too small")
-    fn, tref = _lib.ss_filter_batch, C.byref(tables.c)
-    fixed = (C.c_int32(B), C.c_int32(L), C.c_int32(alpha),
-             _dev_ptr(skip_mask, torch.uint8, "skip_mask"),
-             _dev_ptr(kept_ids, torch.int32, "kept_ids"),
-             _dev_ptr(n_kept, torch.int32, "n_kept"), _dev_ptr(idx_c, torch.int32, "idx_c"),
-             _dev_ptr(ws, torch.uint8, "ws"), C.c_size_t(ws.numel()))
-
-    def call(idx: torch.Tensor, handle: C.c_void_p) -> None:
-        rc = fn(tref, C.c_void_p(idx.data_ptr()), *fixed, handle)
-        if rc:
-            _check(rc)
-    return call
-
-
-def prepared_forward(tables: Tables, idx: torch.Tensor, n_valid: Optional[torch.Tensor],
-                     out: torch.Tensor):
-    """call(handle)."""
-    Bcap, L = _idx_shape(tables, idx)
-    if out.numel() < tables.num_tables * Bcap * tables.dim:
-        raise SlipstreamError("prepared_forward: out is too small")
-    fn = _lib.ss_embbag_forward
-    args = (C.byref(tables.c), _dev_ptr(idx, torch.int32, "idx"), C.c_int32(Bcap), C.c_int32(L),
-            _dev_ptr(n_valid, torch.int32, "n_valid"), _dev_ptr(out, torch.float32, "out"))
-
-    def call(handle: C.c_void_p) -> None:
-        rc = fn(*args, handle)
-        if rc:
-            _check(rc)
-    return call
-
-
-def prepared_backward_prepare(tables: Tables, idx: torch.Tensor,
-                              n_valid: Optional[torch.Tensor], ws: torch.Tensor):
-    """call(handle)."""
-    Bcap, L = _idx_shape(tables, idx)
-    fn = _lib.ss_embbag_backward_prepare
-    args = (C.byref(tables.c), _dev_ptr(idx, torch.int32, "idx"), C.c_int32(Bcap), C.c_int32(L),
-            _dev_ptr(n_valid, torch.int32, "n_valid"), _dev_ptr(ws, torch.uint8, "ws"),
-            C.c_size_t(ws.numel()))
-
-    def call(handle: C.c_void_p) -> None:
-        rc = fn(*args, handle)
-        if rc:
-            _check(rc)
-    return call
-
-
-def prepared_backward_apply(tables: Tables, Bcap: int, L: int, lr: float, ws: torch.Tensor):
-    """call(grad, handle): grad fp32 [T, Bcap, D] contiguous on the device (not rechecked)."""
-    fn = _lib.ss_embbag_backward_apply
-    head = (C.byref(tables.c), C.c_int32(Bcap), C.c_int32(L))
-    tail = (C.c_float(lr), _dev_ptr(ws, torch.uint8, "ws"), C.c_size_t(ws.numel()))
-
-    def call(grad: torch.Tensor, handle: C.c_void_p) -> None:
-        rc = fn(*head, C.c_void_p(grad.data_ptr()), *tail, handle)
-        if rc:
-            _check(rc)
-    return call
-
-
-def prepared_backward_update(tables: Tables, idx: torch.Tensor,
-                             n_valid: Optional[torch.Tensor], lr: float, ws: torch.Tensor):
-    """call(grad, handle)."""
-    Bcap, L = _idx_shape(tables, idx)
-    fn = _lib.ss_embbag_backward_update
-    head = (C.byref(tables.c), _dev_ptr(idx, torch.int32, "idx"), C.c_int32(Bcap), C.c_int32(L),
-            _dev_ptr(n_valid, torch.int32, "n_valid"))
-    tail = (C.c_float(lr), _dev_ptr(ws, torch.uint8, "ws"), C.c_size_t(ws.numel()))
-
-    def call(grad: torch.Tensor, handle: C.c_void_p) -> None:
-        rc = fn(*head, C.c_void_p(grad.data_ptr()), *tail, handle)
-        if rc:
-            _check(rc)
-    return call
 
 
 # ---- issue queue (a host thread of the library that enqueues work on streams)
@@ -793,30 +708,119 @@ class IssueQueue:
     def wait_issued(self, ticket: int) -> None:
         _check(_lib.ss_issue_wait(self._q, C.c_uint64(ticket)))
 
-    def prepared_index_batch(self, tables: Tables, B: int, L: int, alpha: int,
-                             skip_mask: torch.Tensor, kept_ids: torch.Tensor,
-                             n_kept: torch.Tensor, idx_c: torch.Tensor,
-                             ws_filter: torch.Tensor, ws_backward: torch.Tensor):
-        """call(idx, handle) -> ticket: ss_issue_index_batch with everything but the
-        index tensor and the stream converted once."""
-        if skip_mask.numel() < B or kept_ids.numel() < B or n_kept.numel() < 1 \
-                or idx_c.numel() < tables.num_tables * B * L:
-            raise SlipstreamError("prepared_index_batch: an output tensor is too small")
-        fn, q, tref = _lib.ss_issue_index_batch, self._q, C.byref(tables.c)
-        fixed = (C.c_int32(B), C.c_int32(L), C.c_int32(alpha),
-                 _dev_ptr(skip_mask, torch.uint8, "skip_mask"),
-                 _dev_ptr(kept_ids, torch.int32, "kept_ids"),
-                 _dev_ptr(n_kept, torch.int32, "n_kept"),
-                 _dev_ptr(idx_c, torch.int32, "idx_c"),
-                 _dev_ptr(ws_filter, torch.uint8, "ws_filter"), C.c_size_t(ws_filter.numel()),
-                 _dev_ptr(ws_backward, torch.uint8, "ws_backward"),
-                 C.c_size_t(ws_backward.numel()))
-        ticket = C.c_uint64()
-        tptr = C.byref(ticket)
 
-        def call(idx: torch.Tensor, handle: C.c_void_p) -> int:
-            rc = fn(q, tref, C.c_void_p(idx.data_ptr()), *fixed, handle, tptr)
-            if rc:
-                _check(rc)
-            return ticket.value
-        return call
+# ---- the training iteration as a whole (ss_step_*) -------------------------
+class StepPlan(C.Structure):
+    _fields_ = [("every", C.c_int32), ("index_streams", C.c_int32),
+                ("issue_threads", C.c_int32), ("num_sets", C.c_int32)]
+
+
+class StepSet(C.Structure):
+    _fields_ = [("skip_mask", C.c_void_p), ("kept_ids", C.c_void_p), ("n_kept", C.c_void_p),
+                ("idx_c", C.c_void_p), ("ws_filter", C.c_void_p), ("ws_filter_bytes", C.c_size_t),
+                ("ws_backward", C.c_void_p), ("ws_backward_bytes", C.c_size_t)]
+
+
+_TICKET = C.POINTER(C.c_uint64)
+
+
+class StepTraceOps(C.Structure):
+    """Callbacks of ss_step_create_traced (see include/slipstream.h)."""
+    INDEX_NOW = C.CFUNCTYPE(C.c_int32, C.c_void_p, C.c_int32, C.c_int32)
+    Q_INDEX = C.CFUNCTYPE(C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _TICKET)
+    ON_SET = C.CFUNCTYPE(C.c_int32, C.c_void_p, C.c_int32)
+    EVENT_NOW = C.CFUNCTYPE(C.c_int32, C.c_void_p, C.c_int32, C.c_int32)
+    Q_EVENT = C.CFUNCTYPE(C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _TICKET)
+    Q_WAIT_ISSUED = C.CFUNCTYPE(C.c_int32, C.c_void_p, C.c_int32, C.c_uint64)
+    _fields_ = [("user", C.c_void_p), ("index_now", INDEX_NOW), ("q_index", Q_INDEX),
+                ("lookup", ON_SET), ("update", ON_SET), ("detect", ON_SET),
+                ("record_now", EVENT_NOW), ("wait_now", EVENT_NOW), ("q_record", Q_EVENT),
+                ("q_wait", Q_EVENT), ("q_wait_issued", Q_WAIT_ISSUED)]
+
+
+def ss_step_plan_for(T: int, B: int, L: int, every: int = 0, index_streams: int = 0,
+                     issue_threads: int = -1) -> StepPlan:
+    """The plan for a shape; 0 / 0 / -1 leave the choice to the library."""
+    plan = StepPlan(int(every), int(index_streams), int(issue_threads), 0)
+    _check(_lib.ss_step_plan_for(C.c_int32(T), C.c_int32(B), C.c_int32(L), C.byref(plan)))
+    return plan
+
+
+def ss_step_create(tables: Tables, B: int, L: int, alpha: int, lr: float, threshold: float,
+                   snapshot_every: int, hot: HotState, plan: StepPlan, sets, pooled: torch.Tensor,
+                   stream=None) -> C.c_void_p:
+    """sets: plan.num_sets objects with skip_mask, kept_ids, n_kept, idx_c, ws_filter and
+    ws_backward tensors.  Returns the handle of the native step."""
+    if len(sets) != plan.num_sets:
+        raise SlipstreamError("ss_step_create: need plan.num_sets buffer sets")
+    if pooled.numel() < tables.num_tables * B * tables.dim:
+        raise SlipstreamError("ss_step_create: pooled is too small")
+    arr = (StepSet * len(sets))()
+    for a, s in zip(arr, sets):
+        if s.skip_mask.numel() < B or s.kept_ids.numel() < B or s.n_kept.numel() < 1 \
+                or s.idx_c.numel() < tables.num_tables * B * L:
+            raise SlipstreamError("ss_step_create: a tensor of a buffer set is too small")
+        a.skip_mask = _dev_ptr(s.skip_mask, torch.uint8, "skip_mask").value
+        a.kept_ids = _dev_ptr(s.kept_ids, torch.int32, "kept_ids").value
+        a.n_kept = _dev_ptr(s.n_kept, torch.int32, "n_kept").value
+        a.idx_c = _dev_ptr(s.idx_c, torch.int32, "idx_c").value
+        a.ws_filter = _dev_ptr(s.ws_filter, torch.uint8, "ws_filter").value
+        a.ws_filter_bytes = s.ws_filter.numel()
+        a.ws_backward = _dev_ptr(s.ws_backward, torch.uint8, "ws_backward").value
+        a.ws_backward_bytes = s.ws_backward.numel()
+    handle = C.c_void_p()
+    _check(_lib.ss_step_create(
+        C.byref(tables.c), C.c_int32(B), C.c_int32(L), C.c_int32(alpha), C.c_float(lr),
+        C.c_float(threshold), C.c_int32(snapshot_every), C.c_void_p(hot._hptr.data_ptr()),
+        C.c_int32(hot.H), C.c_void_p(hot._sptr.data_ptr()),
+        C.c_void_p(None if hot._shptr is None else hot._shptr.data_ptr()),
+        C.c_void_p(None if hot._dptr is None else hot._dptr.data_ptr()),
+        _dev_ptr(hot.stale_count, torch.int32, "stale_count"), C.byref(plan), arr,
+        _dev_ptr(pooled, torch.float32, "pooled"), _stream(stream), C.byref(handle)))
+    return handle
+
+
+def ss_step_create_traced(plan: StepPlan, snapshot_every: int, ops: StepTraceOps) -> C.c_void_p:
+    handle = C.c_void_p()
+    _check(_lib.ss_step_create_traced(C.byref(plan), C.c_int32(snapshot_every), C.byref(ops),
+                                      C.byref(handle)))
+    return handle
+
+
+def ss_step_destroy(step: C.c_void_p) -> None:
+    _check(_lib.ss_step_destroy(step))
+
+
+def ss_step_room(step: C.c_void_p) -> int:
+    return int(_lib.ss_step_room(step))
+
+
+def ss_step_submit(step: C.c_void_p, idx: torch.Tensor, ready_event=None) -> None:
+    """idx int32 [T, B, L] contiguous on the device (shape as given at creation, not
+    rechecked); ready_event: a torch.cuda.Event recorded after idx's producer, or None."""
+    ready = None if ready_event is None else C.c_void_p(ready_event.cuda_event)
+    rc = _lib.ss_step_submit(step, C.c_void_p(idx.data_ptr()), ready)
+    if rc:
+        _check(rc)
+
+
+def ss_step_forward(step: C.c_void_p) -> int:
+    """Returns the ring position of the buffer set that holds this batch's filter outputs."""
+    used = C.c_int32(-1)
+    rc = _lib.ss_step_forward(step, C.byref(used))
+    if rc:
+        _check(rc)
+    return used.value
+
+
+def ss_step_backward(step: C.c_void_p, grad: torch.Tensor) -> bool:
+    """grad fp32 [T, B, D] contiguous on the device (not rechecked); True after a detect pass."""
+    det = C.c_int32(0)
+    rc = _lib.ss_step_backward(step, C.c_void_p(grad.data_ptr()), C.byref(det))
+    if rc:
+        _check(rc)
+    return bool(det.value)
+
+
+def ss_step_flush(step: C.c_void_p) -> None:
+    _check(_lib.ss_step_flush(step))

@@ -1,0 +1,620 @@
+// ss_step: one training iteration after the other (Algorithm 1 of the paper: drop
+// the inputs that only reach stale entries, train on the rest, every K iterations
+// compare the hot rows with their last snapshot), with the index work of the coming
+// batches taken off the critical path.
+//
+// Classifying a batch and grouping its lookups by row (ss_filter_batch,
+// ss_embbag_backward_prepare) need the indices and the stale bitmaps only, not the
+// weights: they run for the coming batches on index streams of their own, into a
+// ring of buffer sets, while the current batch is in its lookup and update kernels
+// on the training stream.  An event recorded on one stream and waited for on
+// another costs about ten microseconds of GPU time on this platform, so the streams
+// do not meet once per batch: each records an event only every `every` batches
+// ("everything up to batch k is done"), and a stream waits only when the batch it
+// needs is not covered by an event it has waited for already.  The ring holds
+// 3 * every sets per index stream, of which two thirds may be in use ahead of the
+// batch being trained on: the set a new batch takes over was then last used at
+// least `every` batches ago, which an event of the training stream already covers.
+// The index work reads the stale bitmaps, so batches after one that ends with a
+// detect pass are held back until that pass has been enqueued.
+//
+// The scheduling logic talks to the GPU through a small table of operations
+// (StepOps).  The real table enqueues the library's kernels and HIP events, where
+// asked through ss_issue_queue threads; a second one hands every operation to
+// callbacks, which lets a test execute the recorded program of streams, events and
+// waits under a random scheduler on the CPU and check that every kernel finds its
+// inputs complete.
+#include <algorithm>
+#include <deque>
+#include <memory>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "ss_common.h"
+
+namespace ss {
+
+namespace {
+
+constexpr int kMainStream = -1;
+constexpr size_t kMarksKept = 64;     // recorded marks kept per stream
+constexpr int kEventPool = 66;        // ... one being recorded, one spare
+constexpr size_t kRingBytes = 96u << 20;
+
+struct StepOps {
+    virtual ~StepOps() {}
+    // ss_filter_batch + ss_embbag_backward_prepare of a batch into buffer set `set`,
+    // on index stream `stream`: at once, or as a job of issue queue `queue`
+    virtual int32_t index_now(int stream, int set, const int32_t *idx) = 0;
+    virtual int32_t q_index(int queue, int stream, int set, const int32_t *idx,
+                            uint64_t *ticket) = 0;
+    // on the training stream
+    virtual int32_t lookup(int set) = 0;
+    virtual int32_t update(int set, const float *grad) = 0;
+    virtual int32_t detect(float threshold) = 0;
+    // events; stream kMainStream is the training stream
+    virtual int32_t new_event(void **ev) = 0;
+    virtual int32_t record_now(void *ev, int stream) = 0;
+    virtual int32_t wait_now(int stream, void *ev) = 0;
+    virtual int32_t q_record(int queue, void *ev, int stream, uint64_t *ticket) = 0;
+    virtual int32_t q_wait(int queue, void *ev, int stream, uint64_t *ticket) = 0;
+    virtual int32_t q_wait_issued(int queue, uint64_t ticket) = 0;
+    virtual int32_t shutdown() = 0;    // queues drained and ended, then events destroyed
+};
+
+}  // namespace
+
+}  // namespace ss
+
+using ss::StepOps;
+
+struct ss_step {
+    std::unique_ptr<StepOps> ops;
+    int every = 1, n_side = 1, n_sets = 3, n_queues = 0, K = 1;
+    float threshold = 0.f;
+
+    // Events of one stream, each with the last batch it covers, and what each
+    // waiting stream already knows to be done.
+    struct Mark {
+        int64_t covers;
+        void *ev;
+        uint64_t ticket;
+    };
+    struct Marks {
+        std::deque<Mark> recorded;        // ascending in `covers`
+        std::vector<void *> spare;
+        std::vector<int64_t> known;       // by waiter: batches <= this are done
+        int stream = ss::kMainStream;     // the stream whose progress these marks tell
+        bool by_queue = false;            // recorded through that stream's issue queue
+        int queue = 0;
+    };
+    std::vector<Marks> indexed;           // one per index stream
+    Marks trained;                        // training stream: update done up to batch ...
+
+    int64_t submitted = 0, issued = 0, forwarded = 0, it = 0, last_detect = -1;
+    bool have_snapshot = false;
+    struct Held {
+        const int32_t *idx;
+        void *ready;
+    };
+    std::deque<Held> held_back;           // batches waiting for a detect pass before them
+    std::vector<uint64_t> last_ticket;    // per queue
+
+    int queue_of(int stream) const { return n_queues ? stream % n_queues : 0; }
+    bool boundary(int64_t k) const { return (k + 1) % K == 0; }
+    // does a batch in [lo, hi) end with a snapshot / detect pass?
+    bool boundary_in(int64_t lo, int64_t hi) const { return (lo / K + 1) * K - 1 < hi; }
+    int room() const { return (int)(2 * (int64_t)every * n_side - (submitted - it)); }
+
+    int32_t record(Marks &m, int64_t covers)
+    {
+        if (m.spare.empty())
+            return ss::fail(SS_ERR_HIP, "ss_step: event pool exhausted");
+        void *ev = m.spare.back();
+        m.spare.pop_back();
+        uint64_t ticket = 0;
+        const int32_t rc = (n_queues && m.by_queue) ? ops->q_record(m.queue, ev, m.stream, &ticket)
+                                                    : ops->record_now(ev, m.stream);
+        if (rc) return rc;
+        m.recorded.push_back(Mark{covers, ev, ticket});
+        if (m.recorded.size() > ss::kMarksKept) {     // that far back: issued and waited for long ago
+            m.spare.push_back(m.recorded.front().ev);
+            m.recorded.pop_front();
+        }
+        return SS_OK;
+    }
+
+    // Makes `waiting_stream` wait until `batch` is done on the marks' stream, if it
+    // does not know yet.  *covered = false if no recorded event covers the batch.
+    int32_t cover(Marks &m, int waiter, int waiting_stream, int64_t batch, bool *covered)
+    {
+        *covered = true;
+        if (batch <= m.known[waiter]) return SS_OK;
+        for (const Mark &mk : m.recorded) {
+            if (mk.covers < batch) continue;
+            int32_t rc;
+            if (!n_queues) {
+                rc = ops->wait_now(waiting_stream, mk.ev);
+            } else if (m.by_queue) {
+                // a wait for an event whose record has not been issued yet is a no-op
+                rc = ops->q_wait_issued(m.queue, mk.ticket);
+                if (!rc) rc = ops->wait_now(waiting_stream, mk.ev);
+            } else {      // the waiter is an index stream: through its queue, in order with its work
+                uint64_t t = 0;
+                rc = ops->q_wait(queue_of(waiting_stream), mk.ev, waiting_stream, &t);
+            }
+            if (rc) return rc;
+            m.known[waiter] = mk.covers;
+            return SS_OK;
+        }
+        *covered = false;
+        return SS_OK;
+    }
+
+    int32_t issue(int64_t k, const int32_t *idx, void *ready)
+    {
+        const int set = (int)(k % n_sets), j = (int)(k % n_side);
+        int32_t rc = SS_OK;
+        if (ready) {
+            uint64_t t = 0;
+            rc = n_queues ? ops->q_wait(queue_of(j), ready, j, &t) : ops->wait_now(j, ready);
+            if (rc) return rc;
+        }
+        // the set's previous batch must be over, and so must the last detect pass
+        const int64_t need = std::max<int64_t>(k - n_sets, last_detect);
+        if (need >= 0) {
+            bool ok = false;
+            rc = cover(trained, j, j, need, &ok);
+            if (rc) return rc;
+            if (!ok) {
+                rc = record(trained, it - 1);
+                if (rc) return rc;
+                rc = cover(trained, j, j, need, &ok);
+                if (rc) return rc;
+                if (!ok) return ss::fail(SS_ERR_HIP, "ss_step: internal: batch %lld not covered",
+                                         (long long)need);
+            }
+        }
+        if (n_queues)
+            rc = ops->q_index(queue_of(j), j, set, idx, &last_ticket[queue_of(j)]);
+        else
+            rc = ops->index_now(j, set, idx);
+        if (rc) return rc;
+        ++issued;
+        // every `every`-th batch of this stream, and a batch the training stream is about
+        // to ask for (right after a detect pass, or a caller that submits just in time):
+        // an event recorded later, on demand, would also cover, and so wait for, whatever
+        // index work has been enqueued behind this batch by then
+        if ((k / n_side + 1) % every == 0 || k - it < (int64_t)every * n_side)
+            rc = record(indexed[j], k);
+        return rc;
+    }
+
+    // Index work of up to `limit` held-back batches, as far as no detect pass is still
+    // due before them.  A few at a time: enqueueing a whole ring at once after a detect
+    // pass keeps the calling thread busy while the training stream runs dry.
+    int32_t drain(int limit)
+    {
+        while (limit > 0 && !held_back.empty() && !boundary_in(it, issued)) {
+            const Held h = held_back.front();
+            held_back.pop_front();
+            const int32_t rc = issue(issued, h.idx, h.ready);
+            if (rc) return rc;
+            --limit;
+        }
+        return SS_OK;
+    }
+};
+
+namespace ss {
+
+namespace {
+
+// Batches between two cross-stream events: 8, or fewer when the grouped lists of a
+// ring of 3 * every * streams sets would not fit the memory-side cache next to the
+// step's own traffic (a list written by an index stream should still be there when
+// the update kernel reads it).
+int auto_every(int T, int B, int L, int n_side)
+{
+    const size_t per_set = (size_t)16 * T * (((size_t)B * L + 2047) / 2048) * 2048;
+    int every = 8;
+    while (every > 2 && (size_t)3 * every * n_side * per_set > kRingBytes) every /= 2;
+    return every;
+}
+
+// Index streams: one while a table has at most 16384 lookups per batch; beyond that
+// the grouping is a chain of six small launches per batch that lasts about as long
+// as the training kernels, and two chains side by side keep the index work ahead;
+// three when those launches are tiny (fewer than 128 workgroups over all tables).
+int auto_streams(int T, int B, int L)
+{
+    const int64_t lookups = (int64_t)B * L;
+    if (lookups <= 16384) return 1;
+    return T * ((lookups + 2047) / 2048) < 128 ? 3 : 2;
+}
+
+// Issue threads: where a batch is a string of launches at their latency floor, so
+// that one host thread cannot enqueue them as fast as the GPU finishes them.
+int auto_threads(int T, int B, int L, int n_side)
+{
+    if (!(n_side >= 3 || (int64_t)T * B * L <= 65536)) return 0;
+    return n_side >= 3 ? n_side : 1;
+}
+
+// ---- the real operations: library kernels, HIP events, issue queues --------
+struct GpuOps final : StepOps {
+    ss_tables tables;
+    int B, L, alpha, H;
+    float lr;
+    std::vector<ss_step_set> sets;
+    int32_t *const *hot_ids;
+    float **snapshot;
+    uint8_t **stale_hot;
+    double **drift;
+    uint32_t *stale_count;
+    float *pooled;
+    hipStream_t main;
+    std::vector<hipStream_t> sides;
+    std::vector<ss_issue_queue *> queues;
+    std::vector<void *> events;
+
+    hipStream_t stream(int s) const { return s == kMainStream ? main : sides[s]; }
+
+    int32_t index_now(int s, int set, const int32_t *idx) override
+    {
+        const ss_step_set &b = sets[set];
+        int32_t rc = launch_filter(&tables, idx, B, L, alpha, b.skip_mask, b.kept_ids, b.n_kept,
+                                   b.idx_c, b.ws_filter, stream(s));
+        if (rc) return rc;
+        return launch_backward_prepare(&tables, b.idx_c, B, L, b.n_kept, b.ws_backward, stream(s));
+    }
+    int32_t q_index(int q, int s, int set, const int32_t *idx, uint64_t *ticket) override
+    {
+        const ss_step_set &b = sets[set];
+        return ss_issue_index_batch(queues[q], &tables, idx, B, L, alpha, b.skip_mask, b.kept_ids,
+                                    b.n_kept, b.idx_c, b.ws_filter, b.ws_filter_bytes,
+                                    b.ws_backward, b.ws_backward_bytes, stream(s), ticket);
+    }
+    int32_t lookup(int set) override
+    {
+        const ss_step_set &b = sets[set];
+        return launch_forward(&tables, b.idx_c, B, L, b.n_kept, pooled, main);
+    }
+    int32_t update(int set, const float *grad) override
+    {
+        return launch_backward_apply(&tables, B, L, grad, lr, sets[set].ws_backward, main);
+    }
+    int32_t detect(float threshold) override
+    {
+        return launch_detect(&tables, hot_ids, H, snapshot, threshold, 1, stale_hot, drift,
+                             stale_count, main);
+    }
+    int32_t new_event(void **ev) override
+    {
+        const int32_t rc = ss_event_create(ev);
+        if (!rc) events.push_back(*ev);
+        return rc;
+    }
+    int32_t record_now(void *ev, int s) override { return ss_event_record(ev, stream(s)); }
+    int32_t wait_now(int s, void *ev) override { return ss_stream_wait_event(stream(s), ev); }
+    int32_t q_record(int q, void *ev, int s, uint64_t *t) override
+    {
+        return ss_issue_record_event(queues[q], ev, stream(s), t);
+    }
+    int32_t q_wait(int q, void *ev, int s, uint64_t *t) override
+    {
+        return ss_issue_wait_event(queues[q], ev, stream(s), t);
+    }
+    int32_t q_wait_issued(int q, uint64_t t) override { return ss_issue_wait(queues[q], t); }
+    int32_t shutdown() override
+    {
+        int32_t rc = SS_OK;
+        // every queued job issued and every thread ended before any event goes: a job
+        // of one queue may name an event that another queue's marks own
+        for (ss_issue_queue *q : queues) {
+            const int32_t r = ss_issue_queue_destroy(q);
+            if (r && !rc) rc = r;
+        }
+        queues.clear();
+        for (hipStream_t s : sides) (void)hipStreamSynchronize(s);
+        for (void *e : events) (void)ss_event_destroy(e);
+        events.clear();
+        for (hipStream_t s : sides) (void)hipStreamDestroy(s);
+        sides.clear();
+        return rc;
+    }
+    ~GpuOps() override { (void)shutdown(); }
+};
+
+// ---- operations handed to callbacks (the CPU model check) ------------------
+struct TracedOps final : StepOps {
+    ss_step_trace_ops cb;
+    int next_event = 0;
+    int32_t index_now(int s, int set, const int32_t *) override { return cb.index_now(cb.user, s, set); }
+    int32_t q_index(int q, int s, int set, const int32_t *, uint64_t *t) override
+    {
+        return cb.q_index(cb.user, q, s, set, t);
+    }
+    int32_t lookup(int set) override { return cb.lookup(cb.user, set); }
+    int32_t update(int set, const float *) override { return cb.update(cb.user, set); }
+    int32_t detect(float thr) override { return cb.detect(cb.user, thr > 0.f ? 1 : 0); }
+    int32_t new_event(void **ev) override
+    {
+        *ev = reinterpret_cast<void *>(static_cast<uintptr_t>(++next_event));
+        return SS_OK;
+    }
+    static int id(void *ev) { return (int)reinterpret_cast<uintptr_t>(ev); }
+    int32_t record_now(void *ev, int s) override { return cb.record_now(cb.user, id(ev), s); }
+    int32_t wait_now(int s, void *ev) override { return cb.wait_now(cb.user, s, id(ev)); }
+    int32_t q_record(int q, void *ev, int s, uint64_t *t) override
+    {
+        return cb.q_record(cb.user, q, id(ev), s, t);
+    }
+    int32_t q_wait(int q, void *ev, int s, uint64_t *t) override
+    {
+        return cb.q_wait(cb.user, q, id(ev), s, t);
+    }
+    int32_t q_wait_issued(int q, uint64_t t) override { return cb.q_wait_issued(cb.user, q, t); }
+    int32_t shutdown() override { return SS_OK; }
+};
+
+int32_t check_plan(const char *who, int32_t T, int32_t B, int32_t L, const ss_step_plan *p)
+{
+    if (!p) return fail(SS_ERR_INVALID_ARG, "%s: plan is NULL", who);
+    if (T < 1 || T > 65535 || B < 1 || L < 1)
+        return fail(SS_ERR_INVALID_ARG, "%s: T = %d, B = %d, L = %d", who, T, B, L);
+    if (p->every < 1 || p->index_streams < 1 || p->index_streams > 16 || p->issue_threads < 0 ||
+        p->issue_threads > p->index_streams)
+        return fail(SS_ERR_INVALID_ARG,
+                    "%s: every = %d, index_streams = %d, issue_threads = %d (need every >= 1, "
+                    "1 <= streams <= 16, 0 <= threads <= streams)",
+                    who, p->every, p->index_streams, p->issue_threads);
+    if (p->num_sets != 3 * p->every * p->index_streams)
+        return fail(SS_ERR_INVALID_ARG, "%s: num_sets = %d, need 3 * every * index_streams = %d",
+                    who, p->num_sets, 3 * p->every * p->index_streams);
+    return SS_OK;
+}
+
+// Builds the scheduler state around a table of operations.
+int32_t make_step(std::unique_ptr<StepOps> ops, const ss_step_plan *plan, int32_t K,
+                  float threshold, ss_step **out)
+{
+    std::unique_ptr<ss_step> st(new (std::nothrow) ss_step);
+    if (!st) return fail(SS_ERR_HIP, "ss_step: out of host memory");
+    st->ops = std::move(ops);
+    st->every = plan->every;
+    st->n_side = plan->index_streams;
+    st->n_sets = plan->num_sets;
+    st->n_queues = plan->issue_threads;
+    st->K = K;
+    st->threshold = threshold;
+    st->last_ticket.assign(std::max(1, st->n_queues), 0);
+    st->indexed.resize(st->n_side);
+    auto fill = [&](ss_step::Marks &m, int stream, bool by_queue, int waiters) -> int32_t {
+        m.stream = stream;
+        m.by_queue = by_queue;
+        m.queue = st->queue_of(stream == kMainStream ? 0 : stream);
+        m.known.assign(waiters, -1);
+        for (int i = 0; i < kEventPool; ++i) {       // every event it will ever use, up front
+            void *ev = nullptr;
+            const int32_t rc = st->ops->new_event(&ev);
+            if (rc) return rc;
+            m.spare.push_back(ev);
+        }
+        return SS_OK;
+    };
+    for (int j = 0; j < st->n_side; ++j) {
+        const int32_t rc = fill(st->indexed[j], j, true, 1);        // waited for by the training stream
+        if (rc) return rc;
+    }
+    const int32_t rc = fill(st->trained, kMainStream, false, st->n_side);
+    if (rc) return rc;
+    *out = st.release();
+    return SS_OK;
+}
+
+}  // namespace
+
+}  // namespace ss
+
+using namespace ss;
+
+extern "C" {
+
+int32_t ss_step_plan_for(int32_t T, int32_t B, int32_t L, ss_step_plan *plan)
+{
+    const char *who = "ss_step_plan_for";
+    if (!plan) return fail(SS_ERR_INVALID_ARG, "%s: plan is NULL", who);
+    if (T < 1 || T > 65535 || B < 1 || L < 1 || (int64_t)B * L >= (1LL << 31))
+        return fail(SS_ERR_INVALID_ARG, "%s: T = %d, B = %d, L = %d", who, T, B, L);
+    if (plan->index_streams <= 0) plan->index_streams = auto_streams(T, B, L);
+    if (plan->index_streams > 16)
+        return fail(SS_ERR_INVALID_ARG, "%s: index_streams = %d (at most 16)", who,
+                    plan->index_streams);
+    if (plan->every <= 0) plan->every = auto_every(T, B, L, plan->index_streams);
+    if (plan->issue_threads < 0) plan->issue_threads = auto_threads(T, B, L, plan->index_streams);
+    if (plan->issue_threads > plan->index_streams) plan->issue_threads = plan->index_streams;
+    plan->num_sets = 3 * plan->every * plan->index_streams;
+    return SS_OK;
+}
+
+int32_t ss_step_create(const ss_tables *tables, int32_t B, int32_t L, int32_t alpha, float lr,
+                       float threshold, int32_t snapshot_every, int32_t *const *hot_ids,
+                       int32_t H, float **snapshot, uint8_t **stale_hot, double **drift,
+                       uint32_t *stale_count, const ss_step_plan *plan, const ss_step_set *sets,
+                       float *pooled, void *train_stream, ss_step **out)
+{
+    const char *who = "ss_step_create";
+    if (!out) return fail(SS_ERR_INVALID_ARG, "%s: out is NULL", who);
+    int32_t rc = check_tables(tables, who);
+    if (rc) return rc;
+    rc = check_plan(who, tables->num_tables, B, L, plan);
+    if (rc) return rc;
+    if (!tables->stale_bits)
+        return fail(SS_ERR_INVALID_ARG, "%s: tables->stale_bits is NULL", who);
+    if (!hot_ids || !snapshot || H < 1)
+        return fail(SS_ERR_INVALID_ARG, "%s: hot_ids or snapshot is NULL, or H = %d", who, H);
+    if (snapshot_every < 1)
+        return fail(SS_ERR_INVALID_ARG, "%s: snapshot_every = %d", who, snapshot_every);
+    if (threshold != threshold) return fail(SS_ERR_INVALID_ARG, "%s: threshold is NaN", who);
+    if (!sets || !pooled) return fail(SS_ERR_INVALID_ARG, "%s: sets or pooled is NULL", who);
+    if (reinterpret_cast<uintptr_t>(pooled) % 16 != 0)
+        return fail(SS_ERR_INVALID_ARG, "%s: pooled is not 16-byte aligned", who);
+    for (int i = 0; i < plan->num_sets; ++i) {
+        const ss_step_set &b = sets[i];
+        // (the index tensor comes with each batch: any other non-NULL address stands in)
+        rc = check_filter(who, tables, reinterpret_cast<const int32_t *>(pooled), B, L,
+                          b.skip_mask, b.kept_ids, b.n_kept, b.idx_c, b.ws_filter,
+                          b.ws_filter_bytes);
+        if (rc) return rc;
+        rc = check_backward(who, tables, B, L, b.ws_backward, b.ws_backward_bytes);
+        if (rc) return rc;
+    }
+    std::unique_ptr<GpuOps> ops(new (std::nothrow) GpuOps);
+    if (!ops) return fail(SS_ERR_HIP, "%s: out of host memory", who);
+    ops->tables = *tables;
+    ops->B = B;
+    ops->L = L;
+    ops->alpha = alpha;
+    ops->H = H;
+    ops->lr = lr;
+    ops->sets.assign(sets, sets + plan->num_sets);
+    ops->hot_ids = hot_ids;
+    ops->snapshot = snapshot;
+    ops->stale_hot = stale_hot;
+    ops->drift = drift;
+    ops->stale_count = stale_count;
+    ops->pooled = pooled;
+    ops->main = static_cast<hipStream_t>(train_stream);
+    for (int j = 0; j < plan->index_streams; ++j) {
+        hipStream_t s = nullptr;
+        // default priority; non-blocking, so that it never orders itself against the
+        // legacy default stream
+        if (hipStreamCreateWithFlags(&s, hipStreamNonBlocking) != hipSuccess)
+            return fail(SS_ERR_HIP, "%s: hipStreamCreateWithFlags failed", who);
+        ops->sides.push_back(s);
+    }
+    for (int q = 0; q < plan->issue_threads; ++q) {
+        ss_issue_queue *iq = nullptr;
+        rc = ss_issue_queue_create(&iq);
+        if (rc) return rc;
+        ops->queues.push_back(iq);
+    }
+    return make_step(std::move(ops), plan, snapshot_every, threshold, out);
+}
+
+int32_t ss_step_create_traced(const ss_step_plan *plan, int32_t snapshot_every,
+                              const ss_step_trace_ops *callbacks, ss_step **out)
+{
+    const char *who = "ss_step_create_traced";
+    if (!out || !callbacks) return fail(SS_ERR_INVALID_ARG, "%s: out or callbacks is NULL", who);
+    int32_t rc = check_plan(who, 1, 1, 1, plan);
+    if (rc) return rc;
+    if (snapshot_every < 1)
+        return fail(SS_ERR_INVALID_ARG, "%s: snapshot_every = %d", who, snapshot_every);
+    std::unique_ptr<TracedOps> ops(new (std::nothrow) TracedOps);
+    if (!ops) return fail(SS_ERR_HIP, "%s: out of host memory", who);
+    ops->cb = *callbacks;
+    return make_step(std::move(ops), plan, snapshot_every, 1.0f, out);
+}
+
+int32_t ss_step_destroy(ss_step *st)
+{
+    if (!st) return SS_OK;
+    const int32_t rc = st->ops->shutdown();
+    delete st;
+    return rc;
+}
+
+int32_t ss_step_room(const ss_step *st) { return st ? st->room() : 0; }
+
+int32_t ss_step_submit(ss_step *st, const int32_t *idx, void *ready_event)
+{
+    const char *who = "ss_step_submit";
+    if (!st) return fail(SS_ERR_INVALID_ARG, "%s: step is NULL", who);
+    if (!idx) return fail(SS_ERR_INVALID_ARG, "%s: idx is NULL", who);
+    if (st->room() <= 0)
+        return fail(SS_ERR_INVALID_ARG, "%s: too far ahead (see ss_step_room)", who);
+    const int64_t k = st->submitted++;
+    // a boundary batch before this one that has not had its update yet?
+    if (!st->held_back.empty() || st->boundary_in(st->it, k)) {
+        st->held_back.push_back(ss_step::Held{idx, ready_event});
+        return st->drain(2);
+    }
+    return st->issue(k, idx, ready_event);
+}
+
+int32_t ss_step_forward(ss_step *st, int32_t *set_used)
+{
+    const char *who = "ss_step_forward";
+    if (!st) return fail(SS_ERR_INVALID_ARG, "%s: step is NULL", who);
+    const int64_t k = st->forwarded;
+    if (k == st->it && k >= st->issued) {       // the batch may be waiting among the held ones
+        const int32_t rc = st->drain(1);
+        if (rc) return rc;
+    }
+    if (k != st->it || k >= st->issued)
+        return fail(SS_ERR_INVALID_ARG,
+                    "%s: needs a submitted batch and the previous batch finished", who);
+    const int set = (int)(k % st->n_sets), j = (int)(k % st->n_side);
+    bool ok = false;
+    int32_t rc = st->cover(st->indexed[j], 0, kMainStream, k, &ok);
+    if (rc) return rc;
+    if (!ok) {
+        // on demand: this stream's last issued batch is the last one congruent to j
+        const int64_t last = st->issued - 1 - (st->issued - 1 - j) % st->n_side;
+        rc = st->record(st->indexed[j], last);
+        if (rc) return rc;
+        rc = st->cover(st->indexed[j], 0, kMainStream, k, &ok);
+        if (rc) return rc;
+        if (!ok) return fail(SS_ERR_HIP, "%s: internal: batch %lld not covered", who, (long long)k);
+    }
+    ++st->forwarded;
+    if (set_used) *set_used = set;
+    return st->ops->lookup(set);
+}
+
+int32_t ss_step_backward(ss_step *st, const float *grad, int32_t *detected)
+{
+    const char *who = "ss_step_backward";
+    if (!st) return fail(SS_ERR_INVALID_ARG, "%s: step is NULL", who);
+    if (st->forwarded != st->it + 1)
+        return fail(SS_ERR_INVALID_ARG, "%s: follows ss_step_forward", who);
+    if (!grad) return fail(SS_ERR_INVALID_ARG, "%s: grad is NULL", who);
+    if (reinterpret_cast<uintptr_t>(grad) % 16 != 0)
+        return fail(SS_ERR_INVALID_ARG, "%s: grad is not 16-byte aligned", who);
+    const int64_t k = st->it;
+    int32_t rc = st->ops->update((int)(k % st->n_sets), grad);
+    if (rc) return rc;
+    int32_t det = 0;
+    if (st->boundary(k)) {
+        // the first period is the warm-up: its end captures the first snapshot
+        rc = st->ops->detect(st->have_snapshot ? st->threshold : 0.0f);
+        if (rc) return rc;
+        det = st->have_snapshot ? 1 : 0;
+        st->have_snapshot = true;
+        st->last_detect = k;
+    }
+    ++st->it;
+    if (st->it % st->every == 0) {
+        rc = st->record(st->trained, k);
+        if (rc) return rc;
+    }
+    if (detected) *detected = det;
+    // batches that waited for a detect pass (this one's, or an earlier one's)
+    return st->drain(2);
+}
+
+int32_t ss_step_flush(ss_step *st)
+{
+    if (!st) return fail(SS_ERR_INVALID_ARG, "ss_step_flush: step is NULL");
+    for (int q = 0; q < st->n_queues; ++q)
+        if (st->last_ticket[q]) {
+            const int32_t rc = st->ops->q_wait_issued(q, st->last_ticket[q]);
+            if (rc) return rc;
+        }
+    return SS_OK;
+}
+
+}  // extern "C"

@@ -273,24 +273,36 @@ def test_layernorm_calls_validate_on_the_host(lib):
         assert bwd(**kw) != 0 and text in lib.ss_last_error(), (kw, lib.ss_last_error())
 
 
-def test_pipelined_step_picks_its_event_spacing_from_the_ring_size():
-    """Host logic only: 8 batches between events unless the grouped lists of a ring
-    of 3 * every * streams sets would outgrow their share of the memory-side cache."""
+def test_step_plan_picks_streams_threads_and_event_spacing_for_the_shape():
+    """Host logic only (ss_step_plan_for): index streams and issue threads by the
+    size of a batch's index work, 8 batches between events unless the grouped lists
+    of a ring of 3 * every * streams sets would outgrow their share of the
+    memory-side cache."""
+    from paper_2404_04270_amd import binding
     from paper_2404_04270_amd.step import PipelinedStep as P
+    plan = binding.ss_step_plan_for
     assert P.auto_streams(8192, 1) == 1 and P.auto_streams(16384, 1) == 1
     assert P.auto_streams(65536, 1, 1) == 3 and P.auto_streams(4096, 20, 8) == 2
     assert P.auto_streams(65536, 1, 8) == 2 and P.auto_streams(20000, 1, 1) == 3
-    assert P.auto_issue_thread(26, 2048, 1, 1) and P.auto_issue_thread(1, 65536, 1, 3)
-    assert not P.auto_issue_thread(26, 8192, 1, 1) and not P.auto_issue_thread(8, 4096, 20, 2)
+    assert plan(26, 2048, 1).issue_threads == 1 and plan(1, 65536, 1).issue_threads == 3
+    assert plan(26, 8192, 1).issue_threads == 0 and plan(8, 4096, 20).issue_threads == 0
     assert P.auto_every(26, 8192, 1, 1) == 8         # 3.4 MB of lists per batch
     assert P.auto_every(1, 65536, 1, 2) == 8
     assert P.auto_every(8, 4096, 20, 1) == 2         # 10.5 MB per batch
     assert P.auto_every(8, 4096, 20, 4) == 2         # never below 2
+    ring_bytes = 96 << 20
     for T, b, L, n in [(26, 8192, 1, 1), (8, 4096, 20, 1), (4, 30000, 3, 2)]:
         e = P.auto_every(T, b, L, n)
         lists = 16 * T * ((b * L + 2047) // 2048) * 2048
-        assert e in (2, 4, 8) and (e == 2 or 3 * e * n * lists <= P.RING_BYTES)
-        assert e == 8 or 3 * 2 * e * n * lists > P.RING_BYTES      # the largest that fits
+        assert e in (2, 4, 8) and (e == 2 or 3 * e * n * lists <= ring_bytes)
+        assert e == 8 or 3 * 2 * e * n * lists > ring_bytes        # the largest that fits
+    # what the caller fixes stays; the ring follows
+    p = plan(26, 8192, 1, every=3, index_streams=2, issue_threads=5)
+    assert (p.every, p.index_streams, p.issue_threads, p.num_sets) == (3, 2, 2, 18)
+    with pytest.raises(binding.SlipstreamError):
+        plan(0, 8, 1)
+    with pytest.raises(binding.SlipstreamError):
+        plan(1, 8, 1, index_streams=17)
 
 
 def test_issue_queue_calls_validate_on_the_host(lib):

@@ -1,13 +1,14 @@
-"""Host logic of PipelinedStep, checked on the CPU against a model of streams.
+"""Host logic of the step scheduler (ss_step, csrc/step.hip), checked on the CPU
+against a model of streams.
 
-PipelinedStep spreads the calls of a batch over several streams and lets them meet
+The scheduler spreads the calls of a batch over several streams and lets them meet
 through events as rarely as it can.  A missing wait there would not fail loudly on
 the GPU: it would be a race that the parity tests only catch when the timing
-happens to be bad.  Here the library binding and the stream / event objects are
-replaced by recorders, PipelinedStep is driven through a few hundred batches, and
-the recorded program (per stream: kernels, event records, event waits) is then
-executed by a scheduler that picks runnable streams at random.  Whatever order it
-picks, every kernel must find its inputs complete:
+happens to be bad.  Here the scheduler is built with ss_step_create_traced, which
+hands every operation it would enqueue to a callback instead; it is driven through
+a few hundred batches, and the recorded program (per stream: kernels, event
+records, event waits) is then executed by a scheduler that picks runnable streams
+at random.  Whatever order it picks, every kernel must find its inputs complete:
 
   filter(k)   after update(k - ring) (the buffer set's previous batch) and after the
               detect pass of the last boundary batch before k (it reads the bitmaps);
@@ -18,209 +19,177 @@ picks, every kernel must find its inputs complete:
 
 and the program must run to its end (no wait for an event nobody records).  A wait
 takes the event's most recent record at the moment the wait is ENQUEUED, as HIP
-does; with issue threads, jobs reach their stream late and in bursts, which is what
-ss_issue_wait() is for.  Two planted mistakes (a cover() that claims everything is
-known; an ss_issue_wait() that does not wait) show that the checker sees such races.
+does; with issue threads, jobs reach their stream late and in bursts (here: when the
+model's queues are pumped, at random moments), which is what waiting for a job to
+have been issued is for.  Two planted mistakes (in the model, not in the library: a
+stream that drops the waits it is given; a "wait until issued" that does not wait)
+show that the checker sees such races.
 """
+import ctypes as C
 import random
-import types
 
 import pytest
-import torch
 
-from paper_2404_04270_amd import step as step_mod
+from paper_2404_04270_amd import binding as B
+
+MAIN = -1
 
 
 class Recorder:
-    """Streams as lists of enqueued operations, events as versioned marks."""
+    """Streams as lists of enqueued operations, events as versioned marks, issue
+    queues as lists of jobs that are issued when the model chooses."""
 
-    def __init__(self, rng, lazy):
+    def __init__(self, rng, lazy, n_queues, honour_wait_issued=True, drop_waits=False):
         self.rng, self.lazy = rng, lazy
-        self.streams = {}            # handle -> list of ops
-        self.latest = {}             # event id -> (stream handle, position) of its last record
-        self.n_events = 0
-        self.queues = []
+        self.honour_wait_issued, self.drop_waits = honour_wait_issued, drop_waits
+        self.streams = {}            # stream number -> list of ops
+        self.latest = {}             # event id -> (stream, position) of its last record
+        self.queues = [dict(jobs=[], submitted=0, issued=0) for _ in range(n_queues)]
         self.counts = dict(filter=0, lookup=0, update=0)
 
-    def stream(self, handle):
-        return self.streams.setdefault(handle, [])
+    def stream(self, s):
+        return self.streams.setdefault(s, [])
 
     # enqueue-time actions (called at once, or when a queue job is issued)
-    def kernel(self, handle, kind, batch):
-        self.stream(handle).append(("kernel", kind, batch))
+    def kernel(self, s, kind, batch):
+        self.stream(s).append(("kernel", kind, batch))
 
-    def record(self, handle, ev):
-        ops = self.stream(handle)
+    def record(self, s, ev):
+        ops = self.stream(s)
         ops.append(("record", ev))
-        self.latest[ev] = (handle, len(ops) - 1)
+        self.latest[ev] = (s, len(ops) - 1)
 
-    def wait(self, handle, ev):
+    def wait(self, s, ev):
+        if self.drop_waits:
+            return
         # binds to the last record enqueued so far; none: the wait is a no-op
-        self.stream(handle).append(("wait", self.latest.get(ev)))
+        self.stream(s).append(("wait", self.latest.get(ev)))
+
+    def index(self, s):
+        k = self.counts["filter"]
+        self.counts["filter"] += 1
+        return k
+
+    # issue queues
+    def push(self, q, job):
+        queue = self.queues[q]
+        queue["jobs"].append(job)
+        queue["submitted"] += 1
+        if not self.lazy:
+            self.pump(q, len(queue["jobs"]))
+        else:
+            self.pump_some()
+        return queue["submitted"]
+
+    def pump(self, q, n):
+        queue = self.queues[q]
+        while n > 0 and queue["jobs"]:
+            queue["jobs"].pop(0)()
+            queue["issued"] += 1
+            n -= 1
 
     def pump_some(self):
         """Issue threads make progress at moments of their own choosing."""
-        for q in self.queues:
+        for q in range(len(self.queues)):
             if self.rng.random() < 0.5:
-                q.pump(self.rng.randint(0, 4))
+                self.pump(q, self.rng.randint(0, 4))
+
+    def callbacks(self):
+        """The table of operations ss_step_create_traced takes."""
+        T = B.StepTraceOps
+
+        def index_now(_, s, st):
+            k = self.index(s)
+            self.kernel(s, "filter", k)
+            self.kernel(s, "group", k)
+            return 0
+
+        def q_index(_, q, s, st, ticket):
+            k = self.index(s)
+
+            def job():
+                self.kernel(s, "filter", k)
+                self.kernel(s, "group", k)
+            ticket[0] = self.push(q, job)
+            return 0
+
+        def lookup(_, st):
+            self.kernel(MAIN, "lookup", self.counts["lookup"])
+            self.counts["lookup"] += 1
+            self.pump_some()
+            return 0
+
+        def update(_, st):
+            self.kernel(MAIN, "update", self.counts["update"])
+            self.counts["update"] += 1
+            self.pump_some()
+            return 0
+
+        def detect(_, with_threshold):          # the capture is a launch of the same kernel
+            self.kernel(MAIN, "detect", self.counts["update"] - 1)
+            return 0
+
+        def record_now(_, ev, s):
+            self.record(s, ev)
+            self.pump_some()
+            return 0
+
+        def wait_now(_, s, ev):
+            self.wait(s, ev)
+            self.pump_some()
+            return 0
+
+        def q_record(_, q, ev, s, ticket):
+            ticket[0] = self.push(q, lambda: self.record(s, ev))
+            return 0
+
+        def q_wait(_, q, ev, s, ticket):
+            ticket[0] = self.push(q, lambda: self.wait(s, ev))
+            return 0
+
+        def q_wait_issued(_, q, ticket):
+            queue = self.queues[q]
+            assert ticket <= queue["submitted"]
+            if self.honour_wait_issued:
+                self.pump(q, ticket - queue["issued"])
+            return 0
+
+        self._keep = T(None, T.INDEX_NOW(index_now), T.Q_INDEX(q_index), T.ON_SET(lookup),
+                       T.ON_SET(update), T.ON_SET(detect), T.EVENT_NOW(record_now),
+                       T.EVENT_NOW(wait_now), T.Q_EVENT(q_record), T.Q_EVENT(q_wait),
+                       T.Q_WAIT_ISSUED(q_wait_issued))
+        return self._keep
 
 
-class FakeStream:
-    n = 0
+def drive(rng, n_batches, K, every, streams, threads, lazy, greedy, honour_wait_issued=True,
+          drop_waits=False):
+    if threads is True:              # a thread per stream from three streams on, else one
+        threads = streams if streams >= 3 else 1
+    plan = B.ss_step_plan_for(1, 1, 1, every, streams, int(threads))
+    assert (plan.every, plan.index_streams, plan.issue_threads) == (every, streams, min(int(threads), streams))
+    rec = Recorder(rng, lazy, plan.issue_threads, honour_wait_issued, drop_waits)
+    step = B.ss_step_create_traced(plan, K, rec.callbacks())
+    idx = C.c_int32(0)               # never read: the traced scheduler only passes it on
 
-    def __init__(self, device=None):
-        FakeStream.n += 1
-        self.handle = FakeStream.n
-
-
-def make_binding(rec, honour_wait_issued=True):
-    B = types.SimpleNamespace()
-
-    class Tables:
-        def __init__(self, weights):
-            self.num_tables, self.dim = len(weights), weights[0].shape[1]
-            self.device, self.c = weights[0].device, None
-
-        def new_bits(self):
-            return [torch.zeros(1, dtype=torch.int32) for _ in range(self.num_tables)]
-
-    class HotState:
-        def __init__(self, tables, hot_ids, diagnostics=True):
-            pass
-
-    class IssueQueue:
-        def __init__(self):
-            self.jobs, self.submitted, self.issued = [], 0, 0
-            rec.queues.append(self)
-
-        def _push(self, job):
-            self.jobs.append(job)
-            self.submitted += 1
-            if not rec.lazy:
-                self.pump(len(self.jobs))
-            else:
-                rec.pump_some()
-            return self.submitted
-
-        def pump(self, n):
-            while n > 0 and self.jobs:
-                self.jobs.pop(0)()
-                self.issued += 1
-                n -= 1
-
-        def new_event(self):
-            rec.n_events += 1
-            return rec.n_events
-
+    class _Idx:                      # what ss_step_submit's binding asks of a tensor
         @staticmethod
-        def record_now(ev, handle):
-            rec.record(handle, ev)
-            rec.pump_some()
-
-        @staticmethod
-        def wait_now(handle, ev):
-            rec.wait(handle, ev)
-            rec.pump_some()
-
-        def wait_event(self, ev, handle):
-            return self._push(lambda: rec.wait(handle, ev))
-
-        def record_event(self, ev, handle):
-            return self._push(lambda: rec.record(handle, ev))
-
-        def wait_issued(self, ticket):
-            assert ticket <= self.submitted
-            if honour_wait_issued:
-                self.pump(ticket - self.issued)
-
-        def prepared_index_batch(self, *a):
-            def call(idx, handle):
-                k = rec.counts["filter"]
-                rec.counts["filter"] += 1
-
-                def job():
-                    rec.kernel(handle, "filter", k)
-                    rec.kernel(handle, "group", k)
-                return self._push(job)
-            return call
-
-        def stop(self):
-            self.pump(len(self.jobs))
-
-        def close(self):
-            self.stop()
-
-    def prepared_filter_batch(*a):
-        def call(idx, handle):
-            k = rec.counts["filter"]
-            rec.counts["filter"] += 1
-            rec.kernel(handle, "filter", k)
-            rec.last_filtered = k
-        return call
-
-    def prepared_backward_prepare(*a):
-        return lambda handle: rec.kernel(handle, "group", rec.last_filtered)
-
-    def prepared_forward(*a):
-        def call(handle):
-            rec.kernel(handle, "lookup", rec.counts["lookup"])
-            rec.counts["lookup"] += 1
-            rec.pump_some()
-        return call
-
-    def prepared_backward_apply(*a):
-        def call(grad, handle):
-            rec.kernel(handle, "update", rec.counts["update"])
-            rec.counts["update"] += 1
-            rec.pump_some()
-        return call
-
-    def ss_detect_stale(tables, hot, thr, refresh, stream=None):
-        rec.kernel(stream.handle, "detect", rec.counts["update"] - 1)
-
-    def ss_event_create():
-        rec.n_events += 1
-        return rec.n_events
-
-    B.Tables, B.HotState, B.IssueQueue = Tables, HotState, IssueQueue
-    B.prepared_filter_batch = prepared_filter_batch
-    B.prepared_backward_prepare = prepared_backward_prepare
-    B.prepared_forward = prepared_forward
-    B.prepared_backward_apply = prepared_backward_apply
-    B.ss_detect_stale = ss_detect_stale
-    B.ss_event_create = ss_event_create
-    B.ss_event_destroy = lambda ev: None
-    B.ss_filter_batch_workspace_bytes = lambda T, b, L: 256
-    B.ss_backward_workspace_bytes = lambda T, b, L, D: 256
-    B.stream_handle = lambda st: st.handle
-    return B
-
-
-def drive(monkeypatch, rng, n_batches, K, every, streams, threads, lazy, greedy,
-          honour_wait_issued=True):
-    rec = Recorder(rng, lazy)
-    monkeypatch.setattr(step_mod, "B", make_binding(rec, honour_wait_issued))
-    monkeypatch.setattr(torch.cuda, "Stream", FakeStream)
-    main = FakeStream()
-    monkeypatch.setattr(torch.cuda, "current_stream", lambda dev=None: main)
-    W = [torch.zeros(4, 4) for _ in range(2)]
-    st = step_mod.PipelinedStep(W, [torch.zeros(1, dtype=torch.int32)] * 2, 8, 1, 0.01, 1e-3, K,
-                                every=every, index_streams=streams, issue_thread=threads)
-    idx, grad = torch.zeros(2, 8, 1, dtype=torch.int32), torch.zeros(2, 8, 4)
+        def data_ptr():
+            return C.addressof(idx)
     ahead = 0
     for it in range(n_batches):
-        want = st.room() if greedy else rng.randint(0, st.room())
-        while ahead < n_batches and st.room() > 0 and (want > 0 or ahead <= it):
-            st.submit(idx)
+        room = B.ss_step_room(step)
+        want = room if greedy else rng.randint(0, room)
+        while ahead < n_batches and B.ss_step_room(step) > 0 and (want > 0 or ahead <= it):
+            B.ss_step_submit(step, _Idx)
             ahead += 1
             want -= 1
-        st.forward()
-        st.backward(grad)
-    st.flush()
-    st.close()
-    for q in rec.queues:              # (only a broken wait_issued leaves any)
-        q.pump(len(q.jobs))
-    return rec, len(st.sets) if hasattr(st, "sets") else None
+        B.ss_step_forward(step)
+        B.ss_step_backward(step, _Idx)
+    B.ss_step_flush(step)
+    B.ss_step_destroy(step)
+    for q in range(len(rec.queues)):   # (only a broken "wait until issued" leaves any)
+        rec.pump(q, len(rec.queues[q]["jobs"]))
+    return rec, plan.num_sets
 
 
 def execute(rec, ring, K, rng):
@@ -290,12 +259,11 @@ CASES = [
 
 
 @pytest.mark.parametrize("K,every,streams,threads,lazy,greedy", CASES)
-def test_every_kernel_finds_its_inputs_complete(monkeypatch, K, every, streams, threads, lazy,
-                                                greedy):
+def test_every_kernel_finds_its_inputs_complete(K, every, streams, threads, lazy, greedy):
     for seed in range(4):
         rng = random.Random(1000 * seed + 17 * K + every + streams)
         n = 150
-        rec, ring = drive(monkeypatch, rng, n, K, every, streams, threads, lazy, greedy)
+        rec, ring = drive(rng, n, K, every, streams, threads, lazy, greedy)
         assert ring == 3 * every * streams
         for _ in range(6):
             bad, stuck, done = execute(rec, ring, K, rng)
@@ -307,12 +275,11 @@ def test_every_kernel_finds_its_inputs_complete(monkeypatch, K, every, streams, 
 
 
 @pytest.mark.parametrize("issue_threads", [0, 2])
-def test_the_checker_sees_a_missing_wait(monkeypatch, issue_threads):
-    """Planted mistake: marks that claim every batch is already known to the waiter."""
-    marks = step_mod.PipelinedStep._QueueMarks if issue_threads else step_mod.PipelinedStep._Marks
-    monkeypatch.setattr(marks, "cover", lambda self, *a: True)
+def test_the_checker_sees_a_missing_wait(issue_threads):
+    """Planted mistake (in the model): streams that drop the waits they are given."""
     rng = random.Random(5)
-    rec, ring = drive(monkeypatch, rng, 120, 7, 2, 2, issue_threads, bool(issue_threads), False)
+    rec, ring = drive(rng, 120, 7, 2, 2, issue_threads, bool(issue_threads), False,
+                      drop_waits=True)
     found = False
     for _ in range(20):
         bad, stuck, _ = execute(rec, ring, 7, rng)
@@ -320,13 +287,49 @@ def test_the_checker_sees_a_missing_wait(monkeypatch, issue_threads):
     assert found
 
 
-def test_the_checker_sees_a_wait_for_an_event_not_yet_recorded(monkeypatch):
-    """Planted mistake: ss_issue_wait() returns at once, so the training stream is made
-    to wait for events whose record is still sitting in an issue queue - a no-op."""
+def test_the_checker_sees_a_wait_for_an_event_not_yet_recorded():
+    """Planted mistake (in the model): "wait until that job has been issued" returns at
+    once, so the training stream is made to wait for events whose record is still
+    sitting in an issue queue - a no-op."""
     rng = random.Random(6)
-    rec, ring = drive(monkeypatch, rng, 120, 7, 2, 2, 2, True, False, honour_wait_issued=False)
+    rec, ring = drive(rng, 120, 7, 2, 2, 2, True, False, honour_wait_issued=False)
     found = False
     for _ in range(20):
         bad, stuck, _ = execute(rec, ring, 7, rng)
         found = found or bool(bad)
     assert found
+
+
+def test_calls_out_of_order_are_refused_and_enqueue_nothing():
+    rng = random.Random(7)
+    plan = B.ss_step_plan_for(1, 1, 1, 1, 1, 0)            # ring of 3: two batches ahead at most
+    rec = Recorder(rng, False, 0)
+    step = B.ss_step_create_traced(plan, 4, rec.callbacks())
+    word = C.c_int32(0)
+
+    class _Idx:
+        @staticmethod
+        def data_ptr():
+            return C.addressof(word)
+    with pytest.raises(B.SlipstreamError):
+        B.ss_step_forward(step)                            # nothing submitted
+    B.ss_step_submit(step, _Idx)
+    with pytest.raises(B.SlipstreamError):
+        B.ss_step_backward(step, _Idx)                     # no forward yet
+    B.ss_step_forward(step)
+    B.ss_step_submit(step, _Idx)
+    assert B.ss_step_room(step) == 0
+    with pytest.raises(B.SlipstreamError):
+        B.ss_step_submit(step, _Idx)                       # too far ahead
+    with pytest.raises(B.SlipstreamError):
+        B.ss_step_forward(step)                            # previous batch not finished
+    before = {s: len(ops) for s, ops in rec.streams.items()}
+    with pytest.raises(B.SlipstreamError):
+        B.ss_step_forward(step)
+    assert before == {s: len(ops) for s, ops in rec.streams.items()}
+    B.ss_step_backward(step, _Idx)
+    B.ss_step_forward(step)
+    B.ss_step_backward(step, _Idx)
+    B.ss_step_destroy(step)
+    kinds = [op[1] for ops in rec.streams.values() for op in ops if op[0] == "kernel"]
+    assert kinds.count("lookup") == 2 and kinds.count("update") == 2 and kinds.count("filter") == 2
