@@ -316,7 +316,8 @@ class Measurement:
 
         def roof(k):
             ach = alg[k] / (kern[k]["avg_us"] * 1e-6) / 1e9
-            traffic, src = measured_traffic(cfg.name, k, self.thr == cfg.threshold)
+            traffic, src = measured_traffic(cfg.name, k, self.thr == cfg.threshold,
+                                            self.thr == float("inf"))
             return {"achieved": ach, "frac": ach / HBM_PEAK_GBS,
                     "algorithmic_bytes_per_launch": alg[k],
                     "avg_kernel_us": kern[k]["avg_us"], "traffic": traffic,
@@ -699,14 +700,14 @@ def sampling_probe(B, step, idx_d, S, thr):
             "counts_first_last": [counts[0], counts[-1]]}
 
 
-def measured_traffic(workload, kernel, default_threshold=True):
+def measured_traffic(workload, kernel, default_threshold=True, frozen=False):
     """(HBM bytes per launch of `kernel`, where the figure comes from): FETCH_SIZE +
     WRITE_SIZE from the committed rocprofv3 counter summary of this workload, each
     already scaled by the copy-kernel calibration.  The counters are not collected
     in this run; (None, reason) if no committed summary covers the kernel."""
-    if not default_threshold:
+    if not default_threshold and not frozen:
         return None, "no committed counter summary for this threshold"
-    name = "hbm_traffic_%s.txt" % workload
+    name = "hbm_traffic_%s%s.txt" % (workload, "_hot_rows_frozen" if frozen else "")
     path = os.path.join(ROOT, "profiles", name)
     if not os.path.exists(path):
         return None, "no committed counter summary for this workload"
