@@ -90,6 +90,24 @@ int32_t ss_filter_batch(const ss_tables *tables, const int32_t *idx, int32_t B,
 size_t ss_filter_batch_workspace_bytes(int32_t T, int32_t B, int32_t L);
 
 /*
+ * ss_filter_batch, and in the same pass the split of the inputs into hot and
+ * cold ones (section 3.1: the hot inputs are those that read only hot entries;
+ * I = I_hot + I_cold): with hot_bits a second set of bitmaps in the layout of
+ * stale_bits (bit r of hot_bits[t] set iff row r of table t is hot, e.g. as
+ * ss_select_hot_top / ss_select_hot_ratio write them),
+ *     hot_mask[b] = 1 iff every one of the T*L lookups of sample b hits a hot row
+ * for every sample of the batch, skipped or kept (device uint8 [B]).  hot_bits:
+ * device array of T device pointers; NULL, or a NULL entry, means no hot row
+ * (in that table), so no input is hot.  Everything else as ss_filter_batch, same
+ * workspace; the indices are read once for both tests.
+ */
+int32_t ss_filter_batch_split(const ss_tables *tables, uint32_t *const *hot_bits,
+                              const int32_t *idx, int32_t B, int32_t L, int32_t alpha,
+                              uint8_t *skip_mask, uint8_t *hot_mask, int32_t *kept_ids,
+                              int32_t *n_kept, int32_t *idx_c, void *ws, size_t ws_bytes,
+                              void *stream);
+
+/*
  * Pooled embedding lookup (section 2.1: the lookup of one sparse feature
  * yields a single vector per table; bags are pooled by summation):
  *     out[t][j][:] = sum_{l < L} W_t[ idx[t][j][l] ][:]      for j < n_valid

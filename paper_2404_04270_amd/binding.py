@@ -31,7 +31,7 @@ SYMBOLS = (
     "ss_check_indices", "ss_check_enable",
     "ss_step_plan_for", "ss_step_create", "ss_step_destroy", "ss_step_room",
     "ss_step_submit", "ss_step_forward", "ss_step_backward", "ss_step_flush",
-    "ss_step_create_traced",
+    "ss_step_create_traced", "ss_filter_batch_split",
 )
 
 
@@ -71,7 +71,7 @@ def _load():
               "ss_stream_wait_event", "ss_embbag_backward_update_noalloc",
               "ss_check_indices", "ss_step_plan_for", "ss_step_create", "ss_step_destroy",
               "ss_step_room", "ss_step_submit", "ss_step_forward", "ss_step_backward",
-              "ss_step_flush", "ss_step_create_traced"):
+              "ss_step_flush", "ss_step_create_traced", "ss_filter_batch_split"):
         getattr(lib, n).restype = C.c_int32
     lib.ss_check_enable.restype = None
     return lib
@@ -243,6 +243,32 @@ def ss_filter_batch(tables: Tables, idx: torch.Tensor, alpha: int,
         _dev_ptr(idx_c, torch.int32, "idx_c"),
         _dev_ptr(ws, torch.uint8, "ws"), C.c_size_t(ws.numel()),
         _stream(stream)))
+
+
+def ss_filter_batch_split(tables: Tables, hot_bits: Optional[Sequence[torch.Tensor]],
+                          idx: torch.Tensor, alpha: int, skip_mask: torch.Tensor,
+                          hot_mask: torch.Tensor, kept_ids: torch.Tensor, n_kept: torch.Tensor,
+                          idx_c: torch.Tensor, ws: torch.Tensor, stream=None) -> None:
+    """ss_filter_batch plus hot_mask[b] = every lookup of sample b hits a row whose bit
+    is set in hot_bits (T bitmaps in the layout of the stale bitmaps, or None)."""
+    B, L = _idx_shape(tables, idx)
+    if skip_mask.numel() < B or hot_mask.numel() < B or kept_ids.numel() < B \
+            or n_kept.numel() < 1 or idx_c.numel() < idx.numel():
+        raise SlipstreamError("ss_filter_batch_split: an output tensor is too small")
+    hp = None
+    if hot_bits is not None:
+        if len(hot_bits) != tables.num_tables or any(
+                b.numel() < Tables.bitmap_words(tables.rows) for b in hot_bits):
+            raise SlipstreamError("ss_filter_batch_split: one bitmap of ceil(rows/32) words "
+                                  "per table")
+        hp = _opt_ptr_table(hot_bits, torch.int32, "hot_bits", tables.device)
+    _check(_lib.ss_filter_batch_split(
+        C.byref(tables.c), C.c_void_p(None if hp is None else hp.data_ptr()),
+        _dev_ptr(idx, torch.int32, "idx"), C.c_int32(B), C.c_int32(L), C.c_int32(alpha),
+        _dev_ptr(skip_mask, torch.uint8, "skip_mask"), _dev_ptr(hot_mask, torch.uint8, "hot_mask"),
+        _dev_ptr(kept_ids, torch.int32, "kept_ids"), _dev_ptr(n_kept, torch.int32, "n_kept"),
+        _dev_ptr(idx_c, torch.int32, "idx_c"), _dev_ptr(ws, torch.uint8, "ws"),
+        C.c_size_t(ws.numel()), _stream(stream)))
 
 
 def ss_embbag_forward(tables: Tables, idx: torch.Tensor,

@@ -241,6 +241,24 @@ int32_t ss_filter_batch(const ss_tables *tables, const int32_t *idx, int32_t B,
                          idx_c, ws, static_cast<hipStream_t>(stream));
 }
 
+int32_t ss_filter_batch_split(const ss_tables *tables, uint32_t *const *hot_bits,
+                              const int32_t *idx, int32_t B, int32_t L, int32_t alpha,
+                              uint8_t *skip_mask, uint8_t *hot_mask, int32_t *kept_ids,
+                              int32_t *n_kept, int32_t *idx_c, void *ws, size_t ws_bytes,
+                              void *stream)
+{
+    const char *who = "ss_filter_batch_split";
+    const int32_t rc = check_filter(who, tables, idx, B, L, skip_mask, kept_ids, n_kept, idx_c,
+                                    ws, ws_bytes);
+    if (rc) return rc;
+    if (!hot_mask) return fail(SS_ERR_INVALID_ARG, "%s: hot_mask is NULL", who);
+    if (int32_t bad = checked_indices(who, tables->num_tables, tables->rows, idx, B, L, nullptr,
+                                      static_cast<hipStream_t>(stream)))
+        return bad;
+    return launch_filter_split(tables, hot_bits, idx, B, L, alpha, skip_mask, hot_mask, kept_ids,
+                               n_kept, idx_c, ws, static_cast<hipStream_t>(stream));
+}
+
 int32_t ss_embbag_forward(const ss_tables *tables, const int32_t *idx,
                           int32_t Bcap, int32_t L, const int32_t *n_valid,
                           float *out, void *stream)

@@ -34,10 +34,16 @@ constexpr int kFlagProbes = 8;                   // lookups per lane and chunk
 // the 4 us it takes alone.
 constexpr int flag_wg(int lanes) { return lanes <= 32 ? 256 : 1024; }
 
-template <int LANES>
+// SPLIT: the same pass also classifies the sample against a second set of bitmaps
+// (the hot rows, section 3.1: an input that reads only hot entries is a hot input,
+// I = I_hot + I_cold): hot_mask[b] = 1 iff every lookup of the sample hits a row
+// whose hot bit is set.  The indices of a chunk are loaded once for both tests;
+// each test stops probing as soon as its verdict is fixed.
+template <int LANES, bool SPLIT>
 __global__ __launch_bounds__(flag_wg(LANES)) void filter_flag_kernel(
-    const uint32_t *const *__restrict__ bits, const int32_t *__restrict__ idx,
-    int T, int B, int L, int alpha, uint8_t *__restrict__ skip_mask,
+    const uint32_t *const *__restrict__ bits, const uint32_t *const *__restrict__ hot_bits,
+    const int32_t *__restrict__ idx, int T, int B, int L, int alpha,
+    uint8_t *__restrict__ skip_mask, uint8_t *__restrict__ hot_mask,
     int32_t *__restrict__ block_kept)
 {
     constexpr int kFlagWG = flag_wg(LANES);
@@ -47,45 +53,74 @@ __global__ __launch_bounds__(flag_wg(LANES)) void filter_flag_kernel(
     bool keep = false;
     if (b < B) {
         const int total = T * L;
-        bool skip;
+        bool skip = false;
+        bool stale_open = true;                  // is the stale verdict still undecided?
         if (alpha <= 0) {
             skip = true;
+            stale_open = false;
         } else if (alpha > total || bits == nullptr) {
-            skip = false;
-        } else {
-            int count = 0;                       // stale lookups so far (all lanes)
-            int per_lane = 1;
-            for (int q0 = 0; q0 < total;) {
-                const int chunk = LANES * per_lane;
-                uint32_t row[kFlagProbes];
-                gptr<const uint32_t> bt[kFlagProbes];
-                bool live[kFlagProbes];
+            stale_open = false;
+        }
+        bool hot_open = SPLIT && hot_bits != nullptr;
+        bool all_hot = hot_open;                 // no hot bitmaps: no input is hot
+        int count = 0;                           // stale lookups so far (all lanes)
+        int per_lane = 1;
+        for (int q0 = 0; q0 < total && (stale_open || hot_open);) {
+            const int chunk = LANES * per_lane;
+            uint32_t row[kFlagProbes];
+            int tab[kFlagProbes];
+            bool in[kFlagProbes];
 #pragma unroll
-                for (int i = 0; i < kFlagProbes; ++i) {
-                    const int q = q0 + i * LANES + c;
-                    const int qq = (i < per_lane && q < total) ? q : 0;
-                    const int t = qq / L, l = qq - t * L;
-                    bt[i] = as_global(bits[t]);
-                    live[i] = i < per_lane && q < total && bt[i] != nullptr;
-                    row[i] = live[i] ? (uint32_t)idx[((int64_t)t * B + b) * L + l] : 0u;
-                }
+            for (int i = 0; i < kFlagProbes; ++i) {
+                const int q = q0 + i * LANES + c;
+                in[i] = i < per_lane && q < total;
+                const int qq = in[i] ? q : 0;
+                const int t = qq / L, l = qq - t * L;
+                tab[i] = t;
+                row[i] = in[i] ? (uint32_t)idx[((int64_t)t * B + b) * L + l] : 0u;
+            }
+            if (stale_open) {
+                gptr<const uint32_t> bt[kFlagProbes];
                 uint32_t word[kFlagProbes];
 #pragma unroll
-                for (int i = 0; i < kFlagProbes; ++i) word[i] = live[i] ? bt[i][row[i] >> 5] : 0u;
+                for (int i = 0; i < kFlagProbes; ++i) bt[i] = as_global(bits[tab[i]]);
+#pragma unroll
+                for (int i = 0; i < kFlagProbes; ++i)
+                    word[i] = (in[i] && bt[i] != nullptr) ? bt[i][row[i] >> 5] : 0u;
                 int mine = 0;
 #pragma unroll
                 for (int i = 0; i < kFlagProbes; ++i) mine += (word[i] >> (row[i] & 31)) & 1u;
 #pragma unroll
                 for (int off = 1; off < LANES; off <<= 1) mine += __shfl_xor(mine, off, LANES);
                 count += mine;
-                q0 += chunk;
-                const int remaining = total > q0 ? total - q0 : 0;
-                if (count >= alpha || count + remaining < alpha) break;
-                per_lane = kFlagProbes;
             }
-            skip = count >= alpha;
+            if (SPLIT && hot_open) {
+                gptr<const uint32_t> ht[kFlagProbes];
+                uint32_t word[kFlagProbes];
+#pragma unroll
+                for (int i = 0; i < kFlagProbes; ++i) ht[i] = as_global(hot_bits[tab[i]]);
+#pragma unroll
+                for (int i = 0; i < kFlagProbes; ++i)
+                    word[i] = (in[i] && ht[i] != nullptr) ? ht[i][row[i] >> 5] : 0u;
+                int cold = 0;                    // lookups of this lane that miss the hot set
+#pragma unroll
+                for (int i = 0; i < kFlagProbes; ++i)
+                    cold += in[i] && !((word[i] >> (row[i] & 31)) & 1u);
+#pragma unroll
+                for (int off = 1; off < LANES; off <<= 1) cold += __shfl_xor(cold, off, LANES);
+                if (cold) {
+                    all_hot = false;
+                    hot_open = false;
+                }
+            }
+            q0 += chunk;
+            const int remaining = total > q0 ? total - q0 : 0;
+            if (stale_open && (count >= alpha || count + remaining < alpha)) stale_open = false;
+            per_lane = kFlagProbes;
         }
+        if (alpha > 0 && alpha <= total && bits != nullptr) skip = count >= alpha;
         if (c == 0) skip_mask[b] = skip ? 1 : 0;
+        if (SPLIT && c == 0) hot_mask[b] = all_hot ? 1 : 0;
         keep = !skip && c == 0;
     }
     __shared__ int s_cnt[kFlagWG / 64];
@@ -188,6 +223,15 @@ int32_t launch_filter(const ss_tables *tb, const int32_t *idx, int B, int L,
                       int alpha, uint8_t *skip_mask, int32_t *kept_ids,
                       int32_t *n_kept, int32_t *idx_c, void *ws, hipStream_t s)
 {
+    return launch_filter_split(tb, nullptr, idx, B, L, alpha, skip_mask, nullptr, kept_ids,
+                               n_kept, idx_c, ws, s);
+}
+
+int32_t launch_filter_split(const ss_tables *tb, uint32_t *const *hot_bits, const int32_t *idx,
+                            int B, int L, int alpha, uint8_t *skip_mask, uint8_t *hot_mask,
+                            int32_t *kept_ids, int32_t *n_kept, int32_t *idx_c, void *ws,
+                            hipStream_t s)
+{
     const int lanes = flag_lanes((int64_t)tb->num_tables * L);
     const int samples = flag_wg(lanes) / lanes;      // per workgroup of the flag kernel
     const int flag_blocks = (B + samples - 1) / samples;
@@ -196,8 +240,14 @@ int32_t launch_filter(const ss_tables *tb, const int32_t *idx, int B, int L,
     {
         ProfScope prof("filter_flag_kernel", s);
 #define SS_FLAG(LANES_)                                                            \
-    launch(filter_flag_kernel<LANES_>, dim3(flag_blocks), dim3(flag_wg(LANES_)), s, \
-           tb->stale_bits, idx, tb->num_tables, B, L, alpha, skip_mask, block_kept)
+    if (hot_mask)                                                                  \
+        launch(filter_flag_kernel<LANES_, true>, dim3(flag_blocks),                 \
+               dim3(flag_wg(LANES_)), s, tb->stale_bits, hot_bits, idx,             \
+               tb->num_tables, B, L, alpha, skip_mask, hot_mask, block_kept);       \
+    else                                                                           \
+        launch(filter_flag_kernel<LANES_, false>, dim3(flag_blocks),                \
+               dim3(flag_wg(LANES_)), s, tb->stale_bits, nullptr, idx,              \
+               tb->num_tables, B, L, alpha, skip_mask, nullptr, block_kept)
         switch (lanes) {
         case 4: SS_FLAG(4); break;
         case 8: SS_FLAG(8); break;

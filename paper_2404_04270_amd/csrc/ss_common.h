@@ -175,6 +175,12 @@ int32_t launch_forward(const ss_tables *tb, const int32_t *idx, int Bcap, int L,
 int32_t launch_filter(const ss_tables *tb, const int32_t *idx, int B, int L,
                       int alpha, uint8_t *skip_mask, int32_t *kept_ids,
                       int32_t *n_kept, int32_t *idx_c, void *ws, hipStream_t s);
+// The same with a second set of bitmaps (hot rows): hot_mask[b] = every lookup of
+// sample b is a hot row.  hot_mask == nullptr: the plain filter.
+int32_t launch_filter_split(const ss_tables *tb, uint32_t *const *hot_bits, const int32_t *idx,
+                            int B, int L, int alpha, uint8_t *skip_mask, uint8_t *hot_mask,
+                            int32_t *kept_ids, int32_t *n_kept, int32_t *idx_c, void *ws,
+                            hipStream_t s);
 int32_t launch_detect(const ss_tables *tb, int32_t *const *hot_ids, int H,
                       float **snapshot, float threshold, int refresh,
                       uint8_t **stale_hot, double **drift,

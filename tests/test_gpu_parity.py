@@ -570,3 +570,54 @@ def test_pipelined_step_refuses_calls_out_of_order(B, dev):
     st.forward()
     st.backward(grad)
     torch.cuda.synchronize()
+
+
+# ----------------------------------------- filter with the hot / cold split
+@pytest.mark.parametrize("T,R,Bn,L,stale_frac,hot_frac", [
+    (8, 10000, 128, 1, 0.3, 0.5), (26, 5000, 2049, 1, 0.9, 0.97), (3, 700, 999, 7, 0.5, 0.9),
+    (8, 4000, 513, 20, 0.97, 0.99), (1, 64, 300, 1, 0.5, 0.5), (2, 50, 77, 40, 1.0, 1.0),
+    (5, 3000, 1000, 3, 0.0, 0.0),
+    (26, 1000, 200, 16, 0.97, 0.995),   # 416 lookups per sample: a whole wavefront each
+    (16, 500, 90, 40, 0.98, 0.999)])    # 640: more than one round of probes per lane
+def test_filter_split_matches_oracle(B, dev, T, R, Bn, L, stale_frac, hot_frac):
+    """One pass gives the skip mask (count of stale lookups >= alpha), the compaction
+    and the hot / cold membership of every input (section 3.1: hot inputs read only
+    hot rows): each against the oracle's classifier, fed the stale bitmaps for the
+    one and the hot bitmaps with alpha = T*L for the other."""
+    rng = np.random.default_rng(T * 100 + Bn + L)
+    idx = zipf_idx(rng, T, Bn, L, R, 1.3)
+    stale = random_bits(rng, T, R, stale_frac)
+    hot = random_bits(rng, T, R, hot_frac)
+    n_forced = Bn // 3 if hot_frac > 0 else 0    # every row these samples read is made hot
+    for t in range(T):
+        rows = np.unique(idx[t, :n_forced])
+        np.bitwise_or.at(hot[t], rows >> 5, np.uint32(1) << (rows & 31).astype(np.uint32))
+    tb = B.Tables(to_dev(rand_tables(rng, T, R, 4), dev), bits_to_dev(stale, dev))
+    idx_d = torch.from_numpy(idx).to(dev)
+    ws = torch.empty(max(256, B.ss_filter_batch_workspace_bytes(T, Bn, L)), dtype=torch.uint8,
+                     device=dev)
+    want_hot, _, _ = oracle.filter_batch(R, hot, idx, T * L)
+    for alpha in (T * L, max(1, T * L // 2), 1, 0, T * L + 1):
+        skip = torch.full((Bn,), 7, dtype=torch.uint8, device=dev)
+        hot_mask = torch.full((Bn,), 7, dtype=torch.uint8, device=dev)
+        kept = torch.zeros(Bn, dtype=torch.int32, device=dev)
+        nk = torch.zeros(1, dtype=torch.int32, device=dev)
+        idx_c = torch.full((T, Bn, L), -1, dtype=torch.int32, device=dev)
+        B.ss_filter_batch_split(tb, bits_to_dev(hot, dev), idx_d, alpha, skip, hot_mask, kept,
+                                nk, idx_c, ws)
+        r_skip, r_kept, r_idx_c = oracle.filter_batch(R, stale, idx, alpha)
+        n = int(nk.item())
+        assert n == len(r_kept), alpha
+        assert np.array_equal(skip.cpu().numpy(), r_skip), alpha
+        assert np.array_equal(kept.cpu().numpy()[:n], r_kept), alpha
+        assert np.array_equal(idx_c.cpu().numpy()[:, :n], r_idx_c[:, :n]), alpha
+        assert np.array_equal(hot_mask.cpu().numpy(), want_hot), alpha
+    # no hot bitmaps at all: no input is hot; one table without a bitmap: likewise
+    hot_mask = torch.full((Bn,), 7, dtype=torch.uint8, device=dev)
+    B.ss_filter_batch_split(tb, None, idx_d, T * L, skip, hot_mask, kept, nk, idx_c, ws)
+    assert int(hot_mask.sum().item()) == 0
+    assert want_hot[:n_forced].all()
+    if hot_frac == 1.0:
+        assert want_hot.all()
+    if hot_frac == 0.0:
+        assert not want_hot.any()
