@@ -173,12 +173,18 @@ class Measurement:
         step, ring, grads, n_grads = self.step, self.args.ring, self.grads, self.n_grads
         idx_d, start = self.idx_d, self.done
         if self.pipelined:
-            # index work is submitted as far ahead as the ring takes, never past the n-th
+            # Index work is submitted ahead of the batch being trained on, never past the
+            # n-th, and at most two new batches per step: the lead grows to what the ring
+            # takes (room()) within a few steps, and a run that starts with an empty
+            # pipeline does not spend its first quarter millisecond enqueueing index
+            # work while the training stream has nothing to do.
             nxt, end = start, start + n
             for it in range(start, end):
-                while nxt < end and step.room() > 0:
+                fresh = 0
+                while nxt < end and step.room() > 0 and (fresh < 2 or nxt <= it):
                     step.submit(idx_d[nxt % ring])
                     nxt += 1
+                    fresh += 1
                 step.forward()
                 step.backward(grads[it % n_grads])
                 if stamps is not None:
