@@ -18,16 +18,19 @@ _BINDING_NAMES = (
     "ss_select_hot_top", "AccessCounters", "ss_layernorm_forward",
     "ss_layernorm_backward", "ss_layernorm_backward_workspace_bytes",
     "ss_embbag_forward_ln", "ss_embbag_ln_backward",
-    "EmbeddingStep", "lib_path",
+    "ss_embbag_backward_update_noalloc", "ss_filter_batch_split", "ss_check_enable",
+    "ss_check_indices", "ss_step_plan_for", "ss_step_create", "ss_step_destroy",
+    "ss_step_room", "ss_step_submit", "ss_step_forward", "ss_step_backward", "ss_step_flush",
+    "EmbeddingStep", "PipelinedStep", "lib_path",
 )
 
 
 def __getattr__(name):
     if name in _BINDING_NAMES or name in ("binding", "step"):
         import importlib
-        if name == "step" or name == "EmbeddingStep":
+        if name in ("step", "EmbeddingStep", "PipelinedStep"):
             mod = importlib.import_module(".step", __name__)
-            return mod if name == "step" else mod.EmbeddingStep
+            return mod if name == "step" else getattr(mod, name)
         mod = importlib.import_module(".binding", __name__)
         return mod if name == "binding" else getattr(mod, name)
     raise AttributeError(name)
