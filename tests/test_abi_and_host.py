@@ -305,6 +305,34 @@ def test_step_plan_picks_streams_threads_and_event_spacing_for_the_shape():
         plan(1, 8, 1, index_streams=17)
 
 
+def test_step_calls_validate_on_the_host(lib):
+    """ss_step_*: a bad plan or a missing argument is refused before any stream, event
+    or thread is created; calls on a NULL step are errors, destroying one is not."""
+    from paper_2404_04270_amd import binding
+    lib.ss_last_error.restype = C.c_char_p
+    for n in ("ss_step_create", "ss_step_create_traced", "ss_step_destroy", "ss_step_submit",
+              "ss_step_forward", "ss_step_backward", "ss_step_flush", "ss_step_room"):
+        getattr(lib, n).restype = C.c_int32
+    ok = C.c_void_p(256)               # never dereferenced: every call below is rejected
+    plan = binding.StepPlan(2, 1, 0, 7)                  # 3 * 2 * 1 = 6 sets, not 7
+    out = C.c_void_p()
+    ops = binding.StepTraceOps()
+    assert lib.ss_step_create_traced(C.byref(plan), 4, C.byref(ops), C.byref(out)) != 0
+    assert b"num_sets" in lib.ss_last_error()
+    plan = binding.StepPlan(2, 1, 3, 6)                  # more threads than streams
+    assert lib.ss_step_create_traced(C.byref(plan), 4, C.byref(ops), C.byref(out)) != 0
+    plan = binding.StepPlan(2, 1, 0, 6)
+    assert lib.ss_step_create_traced(C.byref(plan), 0, C.byref(ops), C.byref(out)) != 0
+    assert b"snapshot_every" in lib.ss_last_error()
+    assert lib.ss_step_create_traced(C.byref(plan), 4, None, C.byref(out)) != 0
+    assert lib.ss_step_create(None, 8, 1, 1, C.c_float(0.1), C.c_float(1e-3), 4, ok, 1, ok, None,
+                              None, None, C.byref(plan), ok, ok, None, C.byref(out)) != 0
+    assert b"tables is NULL" in lib.ss_last_error()
+    assert lib.ss_step_submit(None, ok, None) != 0 and lib.ss_step_forward(None, None) != 0
+    assert lib.ss_step_backward(None, ok, None) != 0 and lib.ss_step_flush(None) != 0
+    assert lib.ss_step_room(None) == 0 and lib.ss_step_destroy(None) == 0
+
+
 def test_issue_queue_calls_validate_on_the_host(lib):
     lib.ss_last_error.restype = C.c_char_p
     for n in ("ss_issue_index_batch", "ss_issue_wait_event", "ss_issue_record_event",

@@ -621,3 +621,52 @@ def test_filter_split_matches_oracle(B, dev, T, R, Bn, L, stale_frac, hot_frac):
         assert want_hot.all()
     if hot_frac == 0.0:
         assert not want_hot.any()
+
+
+def test_pipelined_step_waits_for_indices_still_being_produced(B, dev):
+    """submit(idx, ready=event): the index tensor is being written by a copy on another
+    stream when it is handed over; the index work must wait for the event recorded
+    after that copy (checked through both paths: enqueued by the calling thread, and
+    by an issue thread)."""
+    from paper_2404_04270_amd.step import EmbeddingStep, PipelinedStep
+    cfg = wl.CONFIGS[1].scaled(snapshot_every=5, iters=30)
+    w = wl.Workload(cfg)
+    idx = w.indices(0, cfg.iters)
+    hot = wl.hot_set(idx, cfg.rows, cfg.hot_rows)
+    W0 = [w.weights(t) for t in range(cfg.num_tables)]
+    serial = EmbeddingStep(to_dev(W0, dev), to_dev(hot, dev), cfg.batch, cfg.bag, cfg.lr,
+                           cfg.threshold, cfg.snapshot_every)
+    grads = [torch.from_numpy(w.grads(it)).to(dev) for it in range(cfg.iters)]
+    for it in range(cfg.iters):
+        serial.filter_forward(torch.from_numpy(idx[it]).to(dev))
+        nk = int(serial.n_kept.item())
+        g_c = torch.zeros_like(grads[it])
+        g_c[:, :nk] = grads[it][:, serial.kept_ids[:nk].long()]
+        grads[it] = g_c
+        serial.backward(g_c)
+    producer = torch.cuda.Stream(device=dev)
+    pinned = torch.from_numpy(idx).pin_memory()
+    filler = torch.empty(64 << 20, dtype=torch.uint8, device=dev)
+    for threads in (0, 1):
+        pipe = PipelinedStep(to_dev(W0, dev), to_dev(hot, dev), cfg.batch, cfg.bag, cfg.lr,
+                             cfg.threshold, cfg.snapshot_every, every=2, issue_thread=threads)
+        staged = [torch.full(idx[0].shape, -1, dtype=torch.int32, device=dev)
+                  for _ in range(cfg.iters)]
+        ahead = 0
+        for it in range(cfg.iters):
+            while ahead < cfg.iters and pipe.room() > 0:
+                with torch.cuda.stream(producer):
+                    filler.zero_()                       # keeps the producer busy for a while
+                    staged[ahead].copy_(pinned[ahead], non_blocking=True)
+                    ev = torch.cuda.Event()
+                    ev.record(producer)
+                pipe.submit(staged[ahead], ready=ev)
+                ahead += 1
+            pipe.forward()
+            pipe.backward(grads[it])
+        pipe.flush()
+        torch.cuda.synchronize()
+        for t in range(cfg.num_tables):
+            assert torch.equal(pipe.tables.weights[t], serial.tables.weights[t]), (threads, t)
+            assert torch.equal(pipe.bits[t], serial.bits[t]), (threads, t)
+        pipe.close()
