@@ -235,14 +235,16 @@ class Measurement:
     def distinct_rows(self):
         """Per batch, averaged over the ring and summed over tables, with the stale
         bitmaps as they are now: (distinct rows the kept samples look up, the
-        distinct rows among them that are not stale, share of samples kept).  The
-        first is what the forward pass must read, the second what the update must
-        read and write."""
+        distinct rows among them that are not stale, gradient rows the update needs =
+        kept (table, sample) pairs with at least one lookup of a row that is not
+        stale, share of samples kept).  The first is what the forward pass must read,
+        the second what the update must read and write, the third what it must read
+        of the gradients."""
         cfg = self.cfg
         stale = [np.unpackbits(b.cpu().numpy().view(np.uint8), bitorder="little")[:cfg.rows]
                  .astype(bool) for b in self.step.bits]
         any_stale = any(s.any() for s in stale)
-        u_fwd = u_upd = kept = 0.0
+        u_fwd = u_upd = g_rows = kept = 0.0
         for k in range(self.idx_ring.shape[0]):
             idx = self.idx_ring[k]                                   # [T, B, L]
             keep = np.ones(cfg.batch, dtype=bool)
@@ -256,8 +258,10 @@ class Measurement:
                 rows = np.unique(idx[t][keep])
                 u_fwd += rows.size
                 u_upd += rows.size - (int(stale[t][rows].sum()) if any_stale else 0)
+                g_rows += int((~stale[t][idx[t][keep]]).any(axis=1).sum()) if any_stale \
+                    else int(keep.sum())
         n = self.idx_ring.shape[0]
-        return u_fwd / n, u_upd / n, kept / n
+        return u_fwd / n, u_upd / n, g_rows / n, kept / n
 
     def record(self, steps, warmup, pieces=20):
         """Primes, warms up, times `steps` batches, then measures the spread and the
@@ -304,12 +308,12 @@ class Measurement:
                 for k, (n, ms) in prof.items()}
 
         # algorithmic bytes per launch (all tables are in one launch)
-        U_fwd, U_upd, kept_host = self.distinct_rows()
+        U_fwd, U_upd, grad_rows, kept_host = self.distinct_rows()
         nnz = T * Bn * L
         row_b = D * 4
         alg = {
             "forward_kernel": U_fwd * row_b + nnz * 4 * kept_frac + T * Bn * row_b * kept_frac,
-            "apply_kernel": T * Bn * row_b * kept_frac + nnz * 4 + 2 * U_upd * row_b,
+            "apply_kernel": grad_rows * row_b + nnz * 4 + 2 * U_upd * row_b,
         }
         alg["forward_group_kernel"] = alg["forward_kernel"]
         # the dominant kernel: most GPU time; kernels within 3 % of it count as tied (at
