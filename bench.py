@@ -470,8 +470,10 @@ def row_gather_probe(torch, B, m):
     # head of the distribution could gain at most
     ws = torch.empty(B.ss_backward_workspace_bytes(T, Bn, L, D), dtype=torch.uint8, device=dev)
     idx_d = [torch.from_numpy(idx[k]).to(dev) for k in range(NB)]
-    order = [np.argsort(-np.bincount(idx[:, t].reshape(-1), minlength=R)[:1 << 16])[:32]
-             for t in range(T)]                                   # most popular rows per table
+    order = []                                                    # most popular rows per table
+    for t in range(T):
+        vals, cnt = np.unique(idx[:, t], return_counts=True)
+        order.append(vals[np.argsort(-cnt, kind="stable")[:32]])
     backup = [w.clone() for w in tables.weights] if cfg.table_bytes < 8e9 else None
     for nh in (0, 8, 32):
         for t in range(T):
