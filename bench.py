@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--threshold", type=float, default=None,
                     help="drift threshold T (default: the config's; inf freezes all hot rows)")
+    ap.add_argument("--snapshot-every", type=int, default=0,
+                    help="snapshot period K in iterations (default: the config's)")
     ap.add_argument("--ring", type=int, default=16, help="distinct batches cycled through")
     ap.add_argument("--grad-buffers", type=int, default=4,
                     help="distinct gradient tensors cycled through (4: together with the "
@@ -137,6 +139,8 @@ class Measurement:
         cfg = wl.CONFIGS[config_no]
         if args.permute and not cfg.permute:
             cfg = cfg.scaled(permute=True, name=cfg.name + "_permuted")
+        if args.snapshot_every > 0:
+            cfg = cfg.scaled(snapshot_every=args.snapshot_every)
         self.cfg = cfg
         self.thr = cfg.threshold if threshold is None else threshold
         T, R, Bn, L = cfg.num_tables, cfg.rows, cfg.batch, cfg.bag
