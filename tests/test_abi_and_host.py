@@ -38,6 +38,18 @@ def test_library_exports_every_declared_symbol(lib):
         assert hasattr(lib, n), n
 
 
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 on its own (and as C++)."""
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "slipstream.h"\nint main(void) { return SS_OK; }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc,
+                    "-fsyntax-only", str(src)], check=True)
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Werror", "-I", inc, "-fsyntax-only",
+                    "-x", "c++", str(src)], check=True)
+
+
 def test_binding_names_match_the_header(lib):
     from paper_2404_04270_amd import binding
     assert sorted(binding.SYMBOLS) == declared_symbols()
