@@ -95,6 +95,10 @@ def parse():
                     help="after the timed steps, also time the hot-set identification "
                          "(access counters over the ring of batches, then the top-H rows "
                          "of every table) and report it beside the step")
+    ap.add_argument("--timeline", type=int, default=0, metavar="N",
+                    help="after the timed steps, run N more steps in trace mode (the kernels stamp "
+                         "the GPU clock themselves, the pipeline runs at its own pace) and report "
+                         "durations, gaps and overlap of the training stream's kernels")
     ap.add_argument("--row-gather-probe", action="store_true",
                     help="after the timed steps, take the access pattern of the lookup and update "
                          "kernels apart (cold Zipf batches, their distinct rows once each, uniform "
@@ -426,6 +430,48 @@ def random_row_rate(torch, B, m):
             "GBs": moved / us / 1e3}
 
 
+def timeline(torch, B, m, n):
+    """The free-running pipeline seen by the kernels' own clock stamps: per kernel its
+    mean duration, per pair of consecutive training-stream kernels the mean gap, and
+    how much index-stream kernel time ran beside the training stream's kernels."""
+    n = min(n, 32768 // 12)
+    m.run(64)
+    torch.cuda.synchronize()
+    B.ss_profile_enable(2)
+    t0 = time.perf_counter()
+    m.run(n)
+    torch.cuda.synchronize()
+    wall_us = 1e6 * (time.perf_counter() - t0) / n
+    ev = B.ss_profile_trace()
+    main_names = ("forward_kernel", "apply_kernel", "fixup_kernel", "detect_kernel")
+    main = sorted((a, b, k) for k, a, b in ev if k in main_names)
+    side = sorted((a, b, k) for k, a, b in ev if k not in main_names)
+    main = main[len(main) // 8:]                      # past the start of the pipeline
+    nb = sum(1 for e in main if e[2] == "apply_kernel")
+    span_us = (main[-1][1] - main[0][0]) / 1e3
+    dur, gaps = {}, {}
+    for a, b, k in main:
+        dur.setdefault(k, []).append((b - a) / 1e3)
+    for x, y in zip(main, main[1:]):
+        gaps.setdefault(x[2] + " -> " + y[2], []).append((y[0] - x[1]) / 1e3)
+    side = [e for e in side if e[0] >= main[0][0] and e[1] <= main[-1][1]]
+    sdur = {}
+    for a, b, k in side:
+        sdur.setdefault(k, []).append((b - a) / 1e3)
+
+    def stats(v):
+        v = sorted(v)
+        return {"n": len(v), "mean_us": sum(v) / len(v), "median_us": v[len(v) // 2],
+                "p90_us": v[len(v) * 9 // 10], "max_us": v[-1]}
+    return {"steps_traced": n, "wall_us_per_step": wall_us, "batches_analysed": nb,
+            "us_per_batch": span_us / max(1, nb),
+            "training_stream_kernels": {k: stats(v) for k, v in dur.items()},
+            "training_stream_gaps": {k: stats(v) for k, v in gaps.items()},
+            "training_stream_busy_us_per_batch": sum(sum(v) for v in dur.values()) / max(1, nb),
+            "training_stream_idle_us_per_batch": sum(sum(v) for v in gaps.values()) / max(1, nb),
+            "index_stream_kernels": {k: stats(v) for k, v in sdur.items()}}
+
+
 def row_gather_probe(torch, B, m):
     """Where the time of the lookup and update kernels goes at this workload: the
     same kernels on index tensors that take the access pattern apart.  Every case
@@ -570,6 +616,8 @@ def main():
     step, cfg = m.step, m.cfg
     if args.sampling_probe > 0:
         out["sampling_block"] = sampling_probe(B, step, m.idx_d, args.sampling_probe, m.thr)
+    if args.timeline > 0:
+        out["timeline"] = timeline(torch, B, m, args.timeline)
     if args.row_gather_probe:
         out["row_gather_probe"] = row_gather_probe(torch, B, m)
     if args.layernorm_probe:

@@ -602,16 +602,33 @@ int32_t ss_check_indices(int32_t num_tables, int64_t rows, const int32_t *idx, i
 void ss_check_enable(int32_t on);
 
 /*
- * Measurement aid, off by default (not part of the method).  While enabled,
- * every kernel the library launches carries a pair of HIP events that the
- * runtime stamps with the start and end of that kernel's execution (this is the
- * one case in which the library creates HIP objects).  ss_profile_report waits for the recorded events, writes one line
- * "kernel_name launches total_milliseconds" per kernel into buf (host memory,
- * NUL terminated), and forgets them.  At most 2^20 launches are recorded
- * between two reports.  Process-wide; meant for a single benchmarking thread.
+ * Measurement aids, off by default (not part of the method).  Process-wide; meant
+ * for a single benchmarking thread.
+ *
+ * ss_profile_enable(1): every kernel the library launches carries a pair of HIP
+ * events that the runtime stamps with the start and end of that kernel's execution
+ * (this and trace mode are the cases in which the library creates HIP objects or
+ * allocates).  ss_profile_report waits for the recorded events, writes one line
+ * "kernel_name launches total_milliseconds" per kernel into buf (host memory, NUL
+ * terminated), and forgets them.  At most 2^20 launches are recorded between two
+ * reports.  A launch with an event pair costs the host about 20 us, so a pipeline
+ * of several streams does not run at its own pace while this is on.
+ *
+ * ss_profile_enable(2): trace mode.  The kernels of the training iteration
+ * (classifier, grouping, lookup, update, fixup, detect) stamp the GPU's
+ * constant-rate clock themselves, when their first workgroups start and when each
+ * workgroup ends, into a device buffer of the library (32 MB, allocated at the
+ * first use); launches cost the host nothing extra, so the pipeline runs as it
+ * does untraced.  ss_profile_trace stops tracing, waits for the device and writes
+ * one line "kernel_name start_ns end_ns" per traced launch, in launch order,
+ * times relative to the earliest start (resolution 10 ns).  At most 32768
+ * launches per trace.
+ *
+ * ss_profile_enable(0) switches both off.
  */
-void ss_profile_enable(int32_t on);
+void ss_profile_enable(int32_t mode);
 int32_t ss_profile_report(char *buf, size_t buf_bytes);
+int32_t ss_profile_trace(char *buf, size_t buf_bytes);
 
 #ifdef __cplusplus
 }

@@ -31,7 +31,7 @@ SYMBOLS = (
     "ss_check_indices", "ss_check_enable",
     "ss_step_plan_for", "ss_step_create", "ss_step_destroy", "ss_step_room",
     "ss_step_submit", "ss_step_forward", "ss_step_backward", "ss_step_flush",
-    "ss_step_create_traced", "ss_filter_batch_split",
+    "ss_step_create_traced", "ss_filter_batch_split", "ss_profile_trace",
 )
 
 
@@ -71,7 +71,8 @@ def _load():
               "ss_stream_wait_event", "ss_embbag_backward_update_noalloc",
               "ss_check_indices", "ss_step_plan_for", "ss_step_create", "ss_step_destroy",
               "ss_step_room", "ss_step_submit", "ss_step_forward", "ss_step_backward",
-              "ss_step_flush", "ss_step_create_traced", "ss_filter_batch_split"):
+              "ss_step_flush", "ss_step_create_traced", "ss_filter_batch_split",
+              "ss_profile_trace"):
         getattr(lib, n).restype = C.c_int32
     lib.ss_check_enable.restype = None
     return lib
@@ -112,8 +113,22 @@ def ss_check_indices(num_tables: int, rows: int, idx: torch.Tensor,
         _stream(stream)))
 
 
-def ss_profile_enable(on: bool) -> None:
+def ss_profile_enable(on) -> None:
+    """False / 0: off; True / 1: an event pair per launch (ss_profile_report);
+    2: trace mode (ss_profile_trace)."""
     _lib.ss_profile_enable(C.c_int32(int(on)))
+
+
+def ss_profile_trace() -> list:
+    """[(kernel, start_ns, end_ns)] of the launches traced since ss_profile_enable(2),
+    in launch order; stops tracing."""
+    buf = C.create_string_buffer(4 << 20)
+    _check(_lib.ss_profile_trace(buf, C.c_size_t(len(buf))))
+    out = []
+    for line in buf.value.decode().splitlines():
+        k, a, b = line.split()
+        out.append((k, int(a), int(b)))
+    return out
 
 
 def ss_profile_report() -> dict:

@@ -61,6 +61,23 @@ constexpr size_t kProfMax = 1u << 20;
 
 static thread_local int t_prof_slot = -1;
 static thread_local int t_prof_mute = 0;
+static thread_local const char *t_prof_kernel = nullptr;   // name of the innermost live ProfScope
+
+// ---- trace mode ---------------------------------------------------------
+namespace {
+bool g_trace_on = false;
+unsigned long long *g_trace_buf = nullptr;                 // [2][kTraceMax][kTraceLanes]
+std::vector<const char *> g_trace_names;                   // kernel of each used slot
+}  // namespace
+
+TraceSlot next_trace_slot()
+{
+    if (!g_trace_on || t_prof_mute > 0 || !t_prof_kernel) return TraceSlot{nullptr};
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (!g_trace_buf || g_trace_names.size() >= kTraceMax) return TraceSlot{nullptr};
+    g_trace_names.push_back(t_prof_kernel);
+    return TraceSlot{g_trace_buf + (g_trace_names.size() - 1) * kTraceLanes};
+}
 
 ProfMute::ProfMute() { ++t_prof_mute; }
 ProfMute::~ProfMute() { --t_prof_mute; }
@@ -68,6 +85,7 @@ ProfMute::~ProfMute() { --t_prof_mute; }
 ProfScope::ProfScope(const char *kernel, hipStream_t)
 {
     t_prof_slot = -1;
+    t_prof_kernel = kernel;
     if (!g_prof_on || t_prof_mute > 0) return;
     std::lock_guard<std::mutex> lk(g_prof_mu);
     if (g_prof.size() >= kProfMax) return;
@@ -81,7 +99,11 @@ ProfScope::ProfScope(const char *kernel, hipStream_t)
     t_prof_slot = (int)g_prof.size() - 1;
 }
 
-ProfScope::~ProfScope() { t_prof_slot = -1; }
+ProfScope::~ProfScope()
+{
+    t_prof_slot = -1;
+    t_prof_kernel = nullptr;
+}
 
 bool prof_events(hipEvent_t *start, hipEvent_t *stop)
 {
@@ -174,7 +196,66 @@ const char *ss_last_error(void) { return g_err; }
 void ss_profile_enable(int32_t on)
 {
     std::lock_guard<std::mutex> lk(g_prof_mu);
-    g_prof_on = on != 0;
+    g_prof_on = on == 1;
+    g_trace_on = false;
+    if (on == 2) {
+        // trace mode: a device buffer of one slot per launch, start stamps at the
+        // largest value, end stamps at zero (a measurement aid may allocate)
+        const size_t words = kTraceMax * 2 * kTraceLanes;
+        if (!g_trace_buf &&
+            hipMalloc(reinterpret_cast<void **>(&g_trace_buf), words * 8) != hipSuccess) {
+            g_trace_buf = nullptr;
+            return;
+        }
+        (void)hipMemset(g_trace_buf, 0xFF, words / 2 * 8);
+        (void)hipMemset(g_trace_buf + words / 2, 0, words / 2 * 8);
+        (void)hipDeviceSynchronize();
+        g_trace_names.clear();
+        g_trace_on = true;
+    }
+}
+
+int32_t ss_profile_trace(char *buf, size_t buf_bytes)
+{
+    if (!buf || buf_bytes < 2)
+        return fail(SS_ERR_INVALID_ARG, "ss_profile_trace: buffer missing");
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_trace_on = false;
+    buf[0] = 0;
+    const size_t n = g_trace_names.size();
+    if (!g_trace_buf || n == 0) return SS_OK;
+    if (hipDeviceSynchronize() != hipSuccess)
+        return fail(SS_ERR_HIP, "ss_profile_trace: device synchronisation failed");
+    std::vector<unsigned long long> starts(n * kTraceLanes), ends(n * kTraceLanes);
+    if (hipMemcpy(starts.data(), g_trace_buf, starts.size() * 8, hipMemcpyDeviceToHost) !=
+            hipSuccess ||
+        hipMemcpy(ends.data(), g_trace_buf + kTraceMax * kTraceLanes, ends.size() * 8,
+                  hipMemcpyDeviceToHost) != hipSuccess)
+        return fail(SS_ERR_HIP, "ss_profile_trace: copy failed");
+    unsigned long long origin = ~0ull;
+    std::vector<unsigned long long> t0(n, ~0ull), t1(n, 0ull);
+    for (size_t i = 0; i < n; ++i) {
+        for (int l = 0; l < kTraceLanes; ++l) {
+            const unsigned long long a = starts[i * kTraceLanes + l], b = ends[i * kTraceLanes + l];
+            if (a < t0[i]) t0[i] = a;
+            if (b > t1[i]) t1[i] = b;
+        }
+        if (t0[i] < origin) origin = t0[i];
+    }
+    size_t off = 0;
+    for (size_t i = 0; i < n; ++i) {
+        if (t0[i] == ~0ull || t1[i] == 0ull) continue;          // the launch did not run
+        // the clock ticks at 100 MHz: 10 ns per tick
+        const int w = snprintf(buf + off, buf_bytes - off, "%s %llu %llu\n", g_trace_names[i],
+                               (t0[i] - origin) * 10ull, (t1[i] - origin) * 10ull);
+        if (w < 0 || (size_t)w >= buf_bytes - off) {
+            buf[off] = 0;
+            return fail(SS_ERR_INVALID_ARG, "ss_profile_trace: buffer too small");
+        }
+        off += (size_t)w;
+    }
+    g_trace_names.clear();
+    return SS_OK;
 }
 
 int32_t ss_profile_report(char *buf, size_t buf_bytes)

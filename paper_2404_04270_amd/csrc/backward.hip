@@ -65,10 +65,13 @@ template <int ITEMS, bool PACKED>
 __global__ __launch_bounds__(1024) void class_sort_kernel(
     const int32_t *__restrict__ idx, int Bcap, int L,
     const int32_t *__restrict__ n_valid, const uint32_t *const *__restrict__ bits,
-    int key_bits, int class_bits, int val_bits, uint2 *__restrict__ out_ent, int NP)
+    int key_bits, int class_bits, int val_bits, uint2 *__restrict__ out_ent, int NP,
+    TraceSlot ts)
 {
+    trace_begin(ts);
     class_sort_body<ITEMS, PACKED>(blockIdx.x, blockIdx.y, idx, Bcap, L, n_valid, bits,
                                    key_bits, class_bits, val_bits, out_ent, NP);
+    trace_end(ts);
 }
 
 // ---------------------------------------------------------------------------
@@ -97,9 +100,10 @@ __global__ __launch_bounds__(kRsHistThreads) void rs_hist_kernel(
     const int32_t *__restrict__ idx, int Bcap, int L,
     const int32_t *__restrict__ n_valid, const uint32_t *const *__restrict__ bits,
     const uint2 *__restrict__ in_ent, uint2 *__restrict__ first_ent, int NP, int shift,
-    int nb, uint32_t *__restrict__ hist, int tiles)
+    int nb, uint32_t *__restrict__ hist, int tiles, TraceSlot ts)
 {
     __shared__ uint32_t s_hist[kRsMaxDig];
+    trace_begin(ts);
     const int t = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
     const int n = clamp_valid(n_valid, Bcap) * L;
     const int ndig = 1 << nb;
@@ -128,6 +132,7 @@ __global__ __launch_bounds__(kRsHistThreads) void rs_hist_kernel(
     __syncthreads();
     for (int i = tid; i < ndig; i += kRsHistThreads)
         hist[((int64_t)t * tiles + tile) * kRsMaxDig + i] = s_hist[i];
+    trace_end(ts);
 }
 
 // Stable scatter of one tile.  The workgroup first turns the table's histograms
@@ -135,9 +140,10 @@ __global__ __launch_bounds__(kRsHistThreads) void rs_hist_kernel(
 // the whole table) + (keys with this digit in earlier tiles).
 __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
     const uint2 *__restrict__ in_ent, uint2 *__restrict__ out_ent, int NP, int shift,
-    int nb, const uint32_t *__restrict__ hist, int tiles)
+    int nb, const uint32_t *__restrict__ hist, int tiles, TraceSlot ts)
 {
     constexpr int NW = kRsThreads / 64;
+    trace_begin(ts);
     __shared__ uint32_t s_cnt[NW * kRsMaxDig];   // per wavefront and digit
     __shared__ uint32_t s_base[kRsMaxDig];       // start offset of each digit
     __shared__ uint32_t s_wsum[NW];
@@ -245,6 +251,7 @@ __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
         const int64_t p = (int64_t)t * NP + s_cnt[wave * ndig + d] + rank[r];
         out_ent[p] = make_uint2(key[r], val[r]);      // one 8-byte store, not two of 4
     }
+    trace_end(ts);
 }
 
 // ---------------------------------------------------------------------------
@@ -278,9 +285,10 @@ __global__ __launch_bounds__(kApplyWG) void apply_kernel(
     int Bcap, int D4, float lr, int wgs_per_table, int pinned_blocks,
     bool stream_grads, uint32_t *__restrict__ meta_trail_row,
     uint8_t *__restrict__ meta_lead_state, f4 *__restrict__ part_lead,
-    f4 *__restrict__ part_trail)
+    f4 *__restrict__ part_trail, TraceSlot ts)
 {
     constexpr int NG = kApplyWG / G;
+    trace_begin(ts);
     // sum of the run that enters the strip from the left: up to its end, or
     // over the whole strip when it goes on to the right
     __shared__ f4 s_lead[kApplyWG];
@@ -409,6 +417,7 @@ __global__ __launch_bounds__(kApplyWG) void apply_kernel(
         }
         if (!FULL) __syncthreads();
     }
+    trace_end(ts);
 }
 
 // ---------------------------------------------------------------------------
@@ -451,10 +460,11 @@ __global__ __launch_bounds__(kWG) void fixup_kernel(
     float *const *__restrict__ weights, int D4, float lr, int wgs_per_table,
     int chunks_per_table, int per_chunk, const uint32_t *__restrict__ meta_trail_row,
     const uint8_t *__restrict__ meta_lead_state,
-    const f4 *__restrict__ part_lead, const f4 *__restrict__ part_trail)
+    const f4 *__restrict__ part_lead, const f4 *__restrict__ part_trail, TraceSlot ts)
 {
     constexpr int NG = kWG / G;
-    __shared__ uint8_t s_state[kWG];     // lead states of the kWG workgroups after the first
+    __shared__ uint8_t s_state[kWG];
+    trace_begin(ts);     // lead states of the kWG workgroups after the first
     __shared__ int s_long[NG];           // queue of long runs: workgroup they start in
     __shared__ uint32_t s_long_row[NG];  // ... and their row
     __shared__ int s_nlong;
@@ -575,6 +585,7 @@ __global__ __launch_bounds__(kWG) void fixup_kernel(
             __syncthreads();
         }
     }
+    trace_end(ts);
 }
 
 struct Layout {

@@ -31,9 +31,10 @@ __global__ __launch_bounds__(kWG) void detect_kernel(
     const int32_t *const *__restrict__ hot_ids, int H,
     float *const *__restrict__ snapshot, float threshold, int refresh,
     uint8_t *const *__restrict__ stale_hot, double *const *__restrict__ drift,
-    uint32_t *__restrict__ stale_count, int D4, int tiles_per_table)
+    uint32_t *__restrict__ stale_count, int D4, int tiles_per_table, TraceSlot ts)
 {
     constexpr int SLOTS = kWG / G;
+    trace_begin(ts);
     __shared__ uint32_t s_row[SLOTS];
     __shared__ uint8_t s_flag[SLOTS];
     const int t = blockIdx.x / tiles_per_table;
@@ -93,6 +94,7 @@ __global__ __launch_bounds__(kWG) void detect_kernel(
             if ((k & 63) == 0 && bal) atomicAdd(&stale_count[t], (uint32_t)__popcll(bal));
         }
     }
+    trace_end(ts);
 }
 
 int32_t launch_detect(const ss_tables *tb, int32_t *const *hot_ids, int H,

@@ -44,9 +44,10 @@ __global__ __launch_bounds__(flag_wg(LANES)) void filter_flag_kernel(
     const uint32_t *const *__restrict__ bits, const uint32_t *const *__restrict__ hot_bits,
     const int32_t *__restrict__ idx, int T, int B, int L, int alpha,
     uint8_t *__restrict__ skip_mask, uint8_t *__restrict__ hot_mask,
-    int32_t *__restrict__ block_kept)
+    int32_t *__restrict__ block_kept, TraceSlot ts)
 {
     constexpr int kFlagWG = flag_wg(LANES);
+    trace_begin(ts);
     constexpr int SAMPLES = kFlagWG / LANES;
     const int c = threadIdx.x % LANES;
     const int b = blockIdx.x * SAMPLES + threadIdx.x / LANES;
@@ -132,6 +133,7 @@ __global__ __launch_bounds__(flag_wg(LANES)) void filter_flag_kernel(
         for (int w = 0; w < kFlagWG / 64; ++w) s += s_cnt[w];
         block_kept[blockIdx.x] = s;
     }
+    trace_end(ts);
 }
 
 __global__ __launch_bounds__(kWG) void filter_compact_kernel(
@@ -139,8 +141,9 @@ __global__ __launch_bounds__(kWG) void filter_compact_kernel(
     const uint8_t *__restrict__ skip_mask,
     const int32_t *__restrict__ block_kept, int per_tile,
     int32_t *__restrict__ kept_ids, int32_t *__restrict__ n_kept,
-    int32_t *__restrict__ idx_c)
+    int32_t *__restrict__ idx_c, TraceSlot ts)
 {
+    trace_begin(ts);
     // grid: x = tile of 256 samples, y = table, z = part of the tile's rows.  Every
     // workgroup repeats the cheap ranking of tile x and copies index rows of table y.
     // block_kept holds per_tile counts for every tile (one per workgroup of the
@@ -200,6 +203,7 @@ __global__ __launch_bounds__(kWG) void filter_compact_kernel(
                 if (e0 + u * kWG < total) dst[e0 + u * kWG] = v[u];
         }
     }
+    trace_end(ts);
 }
 
 // Lanes per sample in the flag kernel: the fewest of 4 ... 64 with which two

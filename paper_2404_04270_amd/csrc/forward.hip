@@ -22,13 +22,15 @@ template <int G>
 __global__ __launch_bounds__(kWG) void forward_onehot_kernel(
     const float *const *__restrict__ weights, const int32_t *__restrict__ idx,
     int Bcap, const int32_t *__restrict__ n_valid, float *__restrict__ out,
-    int D4, int tiles_per_table, int pinned_blocks)
+    int D4, int tiles_per_table, int pinned_blocks, TraceSlot ts)
 {
+    trace_begin(ts);
     // a table's hot rows are wanted by all its tiles: keep them in one L2
     int t, tile;
     block_to_table_pinned(blockIdx.x, tiles_per_table, pinned_blocks, t, tile);
     forward_onehot_body<G, kWG>(t * tiles_per_table + tile, weights, idx, Bcap, n_valid, out, D4,
                                 tiles_per_table);
+    trace_end(ts);
 }
 
 // Multi-hot bags.  All lanes of a workgroup see the same bag length, so the bag
@@ -69,9 +71,10 @@ template <int G, bool FULL>
 __global__ __launch_bounds__(kWG) void forward_kernel(
     const float *const *__restrict__ weights, const int32_t *__restrict__ idx,
     int Bcap, int L, const int32_t *__restrict__ n_valid,
-    float *__restrict__ out, int D4, int tiles_per_table, int pinned_blocks)
+    float *__restrict__ out, int D4, int tiles_per_table, int pinned_blocks, TraceSlot ts)
 {
     constexpr int BAGS = kWG / G;
+    trace_begin(ts);
     int t, tile;
     block_to_table_pinned(blockIdx.x, tiles_per_table, pinned_blocks, t, tile);
     const int n = clamp_valid(n_valid, Bcap);
@@ -117,6 +120,7 @@ __global__ __launch_bounds__(kWG) void forward_kernel(
         if (m & 1) add_rows(acc, f);
         o[col] = acc;
     }
+    trace_end(ts);
 }
 
 int32_t launch_forward(const ss_tables *tb, const int32_t *idx, int Bcap, int L,

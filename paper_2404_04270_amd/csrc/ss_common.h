@@ -60,15 +60,58 @@ bool prof_events(hipEvent_t *start, hipEvent_t *stop);
 // as well: the empty kernel takes it, so that the kernel after it is timed alone.
 void after_stream_wait(hipStream_t s);
 
+// Trace mode (ss_profile_enable(2)): the kernels of the training iteration stamp
+// the GPU's constant-rate clock when their first workgroups start and when each
+// workgroup ends, into a slot of a device buffer that belongs to the launch, so
+// that the real overlap and the gaps of a free-running pipeline can be read
+// afterwards; no event pair, no extra host cost.  A kernel opts in by taking a
+// TraceSlot as its last parameter; launch() then supplies it (a null slot while
+// tracing is off).
+constexpr int kTraceLanes = 64;
+constexpr size_t kTraceMax = 1u << 15;       // launches per trace
+struct TraceSlot {
+    // kTraceLanes start stamps of this launch; its end stamps lie kTraceMax * kTraceLanes
+    // words further on (all start stamps first, then all end stamps: two fills set
+    // the buffer up).  nullptr: tracing is off
+    unsigned long long *p;
+};
+TraceSlot next_trace_slot();
+
+__device__ __forceinline__ unsigned trace_block_id()
+{
+    return blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+}
+__device__ __forceinline__ void trace_begin(TraceSlot ts)
+{
+    if (ts.p && threadIdx.x == 0) {
+        const unsigned b = trace_block_id();
+        if (b < (unsigned)kTraceLanes) ts.p[b] = wall_clock64();
+    }
+}
+__device__ __forceinline__ void trace_end(TraceSlot ts)
+{
+    if (ts.p && threadIdx.x == 0)
+        atomicMax(&ts.p[kTraceMax * kTraceLanes + (trace_block_id() & (kTraceLanes - 1))],
+                  (unsigned long long)wall_clock64());
+}
+
 template <typename... KArgs, typename... Args>
 inline void launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t s,
                    Args... args)
 {
     hipEvent_t e0, e1;
-    if (prof_events(&e0, &e1))
-        hipExtLaunchKernelGGL(kernel, grid, block, 0, s, e0, e1, 0, args...);
-    else
-        hipLaunchKernelGGL(kernel, grid, block, 0, s, args...);
+    if constexpr (sizeof...(KArgs) == sizeof...(Args) + 1) {      // the kernel takes a TraceSlot
+        const TraceSlot ts = next_trace_slot();
+        if (prof_events(&e0, &e1))
+            hipExtLaunchKernelGGL(kernel, grid, block, 0, s, e0, e1, 0, args..., ts);
+        else
+            hipLaunchKernelGGL(kernel, grid, block, 0, s, args..., ts);
+    } else {
+        if (prof_events(&e0, &e1))
+            hipExtLaunchKernelGGL(kernel, grid, block, 0, s, e0, e1, 0, args...);
+        else
+            hipLaunchKernelGGL(kernel, grid, block, 0, s, args...);
+    }
 }
 
 // Lanes that cooperate on one row: one f4 per lane, a power of two <= 64.
