@@ -326,7 +326,45 @@ def test_backward_many_runs_that_cross_several_workgroups(B, dev, T, D, Bc, L, p
         np.testing.assert_allclose(tb.weights[t].cpu().numpy(), ref[t], rtol=RTOL, atol=ATOL)
 
 
-@pytest.mark.parametrize("T", [1, 4])      # 4: enough workgroups for the fixup to take several each
+@pytest.mark.parametrize("D,L", [(64, 1), (128, 6), (16, 1), (320, 2)])
+def test_backward_runs_across_workgroups_are_reproducible(B, dev, D, L):
+    """Runs of every length from 1 to several thousand lookups, many of them across
+    workgroup borders.  The pieces of such a run are added in a fixed order: 40 calls
+    give the same bits, they match the oracle, and a second update stage on the same
+    prepared workspace gives the same bits again."""
+    rng = np.random.default_rng(4600 + D + L)
+    T, R, Bc = 6, 40000, 24000 // L
+    W = rand_tables(rng, T, R, D)
+    lens = np.concatenate([rng.integers(1, 6, 3000), rng.integers(30, 400, 60),
+                           rng.integers(1000, 5000, 3)])
+    rows = np.repeat(rng.permutation(R)[:lens.size], lens)
+    idx = np.stack([np.resize(rng.permutation(rows), Bc * L).reshape(Bc, L)
+                    for _ in range(T)]).astype(np.int32)
+    grad = rng.normal(0, 0.01, (T, Bc, D)).astype(np.float32)
+    ref = [w.copy() for w in W]
+    oracle.embbag_backward_update(ref, None, idx, grad, 0.01, None)
+    idx_d, grad_d = torch.from_numpy(idx).to(dev), torch.from_numpy(grad).to(dev)
+    ws = torch.empty(B.ss_backward_workspace_bytes(T, Bc, L, D), dtype=torch.uint8, device=dev)
+    first = None
+    for rep in range(40):
+        tb = B.Tables(to_dev(W, dev))
+        if rep % 2:        # something else on the device between two calls
+            torch.empty(1 << 24, dtype=torch.float32, device=dev).normal_()
+        B.ss_embbag_backward_update(tb, idx_d, None, grad_d, 0.01, ws)
+        if first is None:
+            first = [w.clone() for w in tb.weights]
+            for t in range(T):
+                np.testing.assert_allclose(first[t].cpu().numpy(), ref[t], rtol=RTOL, atol=ATOL)
+        else:
+            for t in range(T):
+                assert torch.equal(tb.weights[t], first[t]), (rep, t)
+    tb = B.Tables(to_dev(W, dev))
+    B.ss_embbag_backward_apply(tb, Bc, L, grad_d, 0.01, ws)      # prepared by the last call
+    for t in range(T):
+        assert torch.equal(tb.weights[t], first[t]), t
+
+
+@pytest.mark.parametrize("T", [1, 4])
 def test_backward_closed_form_heavy_row(B, dev, T):
     # one row hit by every lookup of a large batch: dW = -lr * L * sum_j g_j; the run
     # covers more workgroups than the fixup stages lead states for in one go
