@@ -99,6 +99,9 @@ def parse():
                     help="after the timed steps, run N more steps in trace mode (the kernels stamp "
                          "the GPU clock themselves, the pipeline runs at its own pace) and report "
                          "durations, gaps and overlap of the training stream's kernels")
+    ap.add_argument("--timeline-dump", default=None, metavar="FILE",
+                    help="with --timeline: also write every traced launch to FILE, one line each: "
+                         "kernel, start and end in ns of the GPU clock")
     ap.add_argument("--row-gather-probe", action="store_true",
                     help="after the timed steps, take the access pattern of the lookup and update "
                          "kernels apart (cold Zipf batches, their distinct rows once each, uniform "
@@ -430,7 +433,7 @@ def random_row_rate(torch, B, m):
             "GBs": moved / us / 1e3}
 
 
-def timeline(torch, B, m, n):
+def timeline(torch, B, m, n, dump=None):
     """The free-running pipeline seen by the kernels' own clock stamps: per kernel its
     mean duration, per pair of consecutive training-stream kernels the mean gap, and
     how much index-stream kernel time ran beside the training stream's kernels."""
@@ -443,6 +446,10 @@ def timeline(torch, B, m, n):
     torch.cuda.synchronize()
     wall_us = 1e6 * (time.perf_counter() - t0) / n
     ev = B.ss_profile_trace()
+    if dump:            # every launch: kernel, first workgroup's start, last workgroup's end (ns)
+        with open(dump, "w") as f:
+            for k, a, b in ev:
+                f.write(f"{k} {a} {b}\n")
     main_names = ("forward_kernel", "apply_kernel", "fixup_kernel", "detect_kernel")
     main = sorted((a, b, k) for k, a, b in ev if k in main_names)
     side = sorted((a, b, k) for k, a, b in ev if k not in main_names)
@@ -617,7 +624,7 @@ def main():
     if args.sampling_probe > 0:
         out["sampling_block"] = sampling_probe(B, step, m.idx_d, args.sampling_probe, m.thr)
     if args.timeline > 0:
-        out["timeline"] = timeline(torch, B, m, args.timeline)
+        out["timeline"] = timeline(torch, B, m, args.timeline, args.timeline_dump)
     if args.row_gather_probe:
         out["row_gather_probe"] = row_gather_probe(torch, B, m)
     if args.layernorm_probe:
