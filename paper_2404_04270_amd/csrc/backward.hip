@@ -61,17 +61,17 @@ constexpr int kApplyWG = 256;           // apply stage: threads per workgroup (5
 
 // Stage 1a (class sort, one launch for up to 16384 lookups per table) lives in
 // group_body.h, shared with the fused forward + grouping launch.
-template <int ITEMS, bool PACKED>
+template <int ITEMS, bool PACKED, typename TS>
 __global__ __launch_bounds__(1024) void class_sort_kernel(
     const int32_t *__restrict__ idx, int Bcap, int L,
     const int32_t *__restrict__ n_valid, const uint32_t *const *__restrict__ bits,
     int key_bits, int class_bits, int val_bits, uint2 *__restrict__ out_ent, int NP,
-    TraceSlot ts)
+    TS ts)
 {
-    trace_begin(ts);
+    const unsigned long long trace_t0 = trace_begin<TS>();
     class_sort_body<ITEMS, PACKED>(blockIdx.x, blockIdx.y, idx, Bcap, L, n_valid, bits,
                                    key_bits, class_bits, val_bits, out_ent, NP);
-    trace_end(ts);
+    trace_end(ts, trace_t0);
 }
 
 // ---------------------------------------------------------------------------
@@ -95,15 +95,15 @@ __device__ __forceinline__ void rs_load(const int32_t *__restrict__ ip, int L, i
     }
 }
 
-template <bool FIRST>
+template <bool FIRST, typename TS>
 __global__ __launch_bounds__(kRsHistThreads) void rs_hist_kernel(
     const int32_t *__restrict__ idx, int Bcap, int L,
     const int32_t *__restrict__ n_valid, const uint32_t *const *__restrict__ bits,
     const uint2 *__restrict__ in_ent, uint2 *__restrict__ first_ent, int NP, int shift,
-    int nb, uint32_t *__restrict__ hist, int tiles, TraceSlot ts)
+    int nb, uint32_t *__restrict__ hist, int tiles, TS ts)
 {
     __shared__ uint32_t s_hist[kRsMaxDig];
-    trace_begin(ts);
+    const unsigned long long trace_t0 = trace_begin<TS>();
     const int t = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
     const int n = clamp_valid(n_valid, Bcap) * L;
     const int ndig = 1 << nb;
@@ -132,18 +132,19 @@ __global__ __launch_bounds__(kRsHistThreads) void rs_hist_kernel(
     __syncthreads();
     for (int i = tid; i < ndig; i += kRsHistThreads)
         hist[((int64_t)t * tiles + tile) * kRsMaxDig + i] = s_hist[i];
-    trace_end(ts);
+    trace_end(ts, trace_t0);
 }
 
 // Stable scatter of one tile.  The workgroup first turns the table's histograms
 // into the start offset of each of its digits: (keys with a smaller digit in
 // the whole table) + (keys with this digit in earlier tiles).
+template <typename TS>
 __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
     const uint2 *__restrict__ in_ent, uint2 *__restrict__ out_ent, int NP, int shift,
-    int nb, const uint32_t *__restrict__ hist, int tiles, TraceSlot ts)
+    int nb, const uint32_t *__restrict__ hist, int tiles, TS ts)
 {
     constexpr int NW = kRsThreads / 64;
-    trace_begin(ts);
+    const unsigned long long trace_t0 = trace_begin<TS>();
     __shared__ uint32_t s_cnt[NW * kRsMaxDig];   // per wavefront and digit
     __shared__ uint32_t s_base[kRsMaxDig];       // start offset of each digit
     __shared__ uint32_t s_wsum[NW];
@@ -251,7 +252,7 @@ __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
         const int64_t p = (int64_t)t * NP + s_cnt[wave * ndig + d] + rank[r];
         out_ent[p] = make_uint2(key[r], val[r]);      // one 8-byte store, not two of 4
     }
-    trace_end(ts);
+    trace_end(ts, trace_t0);
 }
 
 // ---------------------------------------------------------------------------
@@ -278,17 +279,17 @@ __device__ __forceinline__ const f4 *grad_ptr(const f4 *table_base, uint32_t smp
     return table_base + ((uint64_t)smp * d4 + col);
 }
 
-template <int G, int S, bool FULL>
+template <int G, int S, bool FULL, typename TS>
 __global__ __launch_bounds__(kApplyWG) void apply_kernel(
     float *const *__restrict__ weights, const uint2 *__restrict__ ent, int NP,
     const float *__restrict__ grad,
     int Bcap, int D4, float lr, int wgs_per_table, int pinned_blocks,
     bool stream_grads, uint32_t *__restrict__ meta_trail_row,
     uint8_t *__restrict__ meta_lead_state, f4 *__restrict__ part_lead,
-    f4 *__restrict__ part_trail, TraceSlot ts)
+    f4 *__restrict__ part_trail, TS ts)
 {
     constexpr int NG = kApplyWG / G;
-    trace_begin(ts);
+    const unsigned long long trace_t0 = trace_begin<TS>();
     // sum of the run that enters the strip from the left: up to its end, or
     // over the whole strip when it goes on to the right
     __shared__ f4 s_lead[kApplyWG];
@@ -417,7 +418,7 @@ __global__ __launch_bounds__(kApplyWG) void apply_kernel(
         }
         if (!FULL) __syncthreads();
     }
-    trace_end(ts);
+    trace_end(ts, trace_t0);
 }
 
 // ---------------------------------------------------------------------------
@@ -455,16 +456,16 @@ __device__ __forceinline__ f4 sum_pieces(const f4 *__restrict__ pt,
 
 constexpr int kNear = 8;     // a run that ends this many workgroups on is "short"
 
-template <int G>
+template <int G, typename TS>
 __global__ __launch_bounds__(kWG) void fixup_kernel(
     float *const *__restrict__ weights, int D4, float lr, int wgs_per_table,
     int chunks_per_table, int per_chunk, const uint32_t *__restrict__ meta_trail_row,
     const uint8_t *__restrict__ meta_lead_state,
-    const f4 *__restrict__ part_lead, const f4 *__restrict__ part_trail, TraceSlot ts)
+    const f4 *__restrict__ part_lead, const f4 *__restrict__ part_trail, TS ts)
 {
     constexpr int NG = kWG / G;
-    __shared__ uint8_t s_state[kWG];
-    trace_begin(ts);     // lead states of the kWG workgroups after the first
+    __shared__ uint8_t s_state[kWG];     // lead states of the kWG workgroups after the first
+    const unsigned long long trace_t0 = trace_begin<TS>();
     __shared__ int s_long[NG];           // queue of long runs: workgroup they start in
     __shared__ uint32_t s_long_row[NG];  // ... and their row
     __shared__ int s_nlong;
@@ -585,7 +586,7 @@ __global__ __launch_bounds__(kWG) void fixup_kernel(
             __syncthreads();
         }
     }
-    trace_end(ts);
+    trace_end(ts, trace_t0);
 }
 
 struct Layout {
@@ -683,7 +684,7 @@ int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bca
         const dim3 grid(1 << cp.class_bits, T);
         ProfScope prof("class_sort_kernel", s);
 #define SS_LDS_SORT(I, P)                                                          \
-    launch(class_sort_kernel<I, P>, grid, dim3(1024), s, idx, Bcap, L, n_valid,     \
+    launch(SS_BOTH(class_sort_kernel, I, P), grid, dim3(1024), s, idx, Bcap, L, n_valid,     \
            tb->stale_bits, key_bits, cp.class_bits, cp.val_bits, ent[0],            \
            y.NP)
         if (cp.packed) {
@@ -711,16 +712,16 @@ int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bca
             {
                 ProfScope prof("rs_hist_kernel", s);
                 if (pass == 0)
-                    launch(rs_hist_kernel<true>, grid, dim3(kRsHistThreads), s, idx, Bcap, L,
+                    launch(SS_BOTH(rs_hist_kernel, true), grid, dim3(kRsHistThreads), s, idx, Bcap, L,
                            n_valid, tb->stale_bits, nullptr, ent[1], y.NP, shift, nb, hist,
                            y.tiles);
                 else
-                    launch(rs_hist_kernel<false>, grid, dim3(kRsHistThreads), s, idx, Bcap, L,
+                    launch(SS_BOTH(rs_hist_kernel, false), grid, dim3(kRsHistThreads), s, idx, Bcap, L,
                            n_valid, nullptr, ent[in], nullptr, y.NP, shift, nb, hist,
                            y.tiles);
             }
             ProfScope prof("rs_scatter_kernel", s);
-            launch(rs_scatter_kernel, grid, dim3(kRsThreads), s, ent[in], ent[out], y.NP,
+            launch(rs_scatter_kernel<NoTrace>, rs_scatter_kernel<TraceSlot>, grid, dim3(kRsThreads), s, ent[in], ent[out], y.NP,
                    shift, nb, hist, y.tiles);
             cur = out;
             shift += nb;
@@ -755,7 +756,7 @@ int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float 
     // one gradient block per L2: only worth it when gradient rows are re-read
     const int pinned = L > 1 ? (T / 8) * 8 * wgs : 0;
 #define SS_APPLY(S_, F_)                                                          \
-    SS_DISPATCH_G(g, launch((apply_kernel<G, S_, F_>), dim3((unsigned)blocks),    \
+    SS_DISPATCH_G(g, launch(SS_BOTH(apply_kernel, G, S_, F_), dim3((unsigned)blocks),    \
                             dim3(kApplyWG), s, tb->weights, ent[cur], y.NP, grad, \
                             Bcap, D4, lr, wgs, pinned, L == 1, trail_row,         \
                             lead_state, part_lead, part_trail))
@@ -774,7 +775,7 @@ int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float 
     // apply workgroups looked at per workgroup of this launch
     const int per_chunk = (int64_t)wgs * T <= 2048 ? 1 : kWG / g;
     const int chunks = (wgs + per_chunk - 1) / per_chunk;
-    SS_DISPATCH_G(g, launch(fixup_kernel<G>, dim3((unsigned)(chunks * T)),
+    SS_DISPATCH_G(g, launch(SS_BOTH(fixup_kernel, G), dim3((unsigned)(chunks * T)),
                                         dim3(kWG), s, tb->weights, D4, lr, wgs,
                                         chunks, per_chunk, trail_row, lead_state,
                                         part_lead, part_trail));

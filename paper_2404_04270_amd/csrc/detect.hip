@@ -25,16 +25,16 @@ void launch_zero_u32(uint32_t *p, int n, hipStream_t s)
     if (n > 0) launch(zero_u32_kernel, dim3((n + 255) / 256), dim3(256), s, p, n);
 }
 
-template <int G>
+template <int G, typename TS>
 __global__ __launch_bounds__(kWG) void detect_kernel(
     const float *const *__restrict__ weights, uint32_t *const *__restrict__ bits,
     const int32_t *const *__restrict__ hot_ids, int H,
     float *const *__restrict__ snapshot, float threshold, int refresh,
     uint8_t *const *__restrict__ stale_hot, double *const *__restrict__ drift,
-    uint32_t *__restrict__ stale_count, int D4, int tiles_per_table, TraceSlot ts)
+    uint32_t *__restrict__ stale_count, int D4, int tiles_per_table, TS ts)
 {
     constexpr int SLOTS = kWG / G;
-    trace_begin(ts);
+    const unsigned long long trace_t0 = trace_begin<TS>();
     __shared__ uint32_t s_row[SLOTS];
     __shared__ uint8_t s_flag[SLOTS];
     const int t = blockIdx.x / tiles_per_table;
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kWG) void detect_kernel(
             if ((k & 63) == 0 && bal) atomicAdd(&stale_count[t], (uint32_t)__popcll(bal));
         }
     }
-    trace_end(ts);
+    trace_end(ts, trace_t0);
 }
 
 int32_t launch_detect(const ss_tables *tb, int32_t *const *hot_ids, int H,
@@ -109,10 +109,9 @@ int32_t launch_detect(const ss_tables *tb, int32_t *const *hot_ids, int H,
     const int tiles = (H + slots - 1) / slots;
     if (stale_count) launch_zero_u32(stale_count, T, s);
     ProfScope prof("detect_kernel", s);
-    SS_DISPATCH_G(g, launch(
-                         detect_kernel<G>, dim3((unsigned)(tiles * T)), dim3(kWG), s, tb->weights, tb->stale_bits, hot_ids, H, snapshot,
-                         threshold, refresh, stale_hot, drift, stale_count, D4,
-                         tiles));
+    SS_DISPATCH_G(g, launch(SS_BOTH(detect_kernel, G), dim3((unsigned)(tiles * T)), dim3(kWG), s,
+                            tb->weights, tb->stale_bits, hot_ids, H, snapshot, threshold,
+                            refresh, stale_hot, drift, stale_count, D4, tiles));
     return check_launch("ss_detect_stale");
 }
 

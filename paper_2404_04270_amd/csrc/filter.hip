@@ -39,15 +39,15 @@ constexpr int flag_wg(int lanes) { return lanes <= 32 ? 256 : 1024; }
 // I = I_hot + I_cold): hot_mask[b] = 1 iff every lookup of the sample hits a row
 // whose hot bit is set.  The indices of a chunk are loaded once for both tests;
 // each test stops probing as soon as its verdict is fixed.
-template <int LANES, bool SPLIT>
+template <int LANES, bool SPLIT, typename TS>
 __global__ __launch_bounds__(flag_wg(LANES)) void filter_flag_kernel(
     const uint32_t *const *__restrict__ bits, const uint32_t *const *__restrict__ hot_bits,
     const int32_t *__restrict__ idx, int T, int B, int L, int alpha,
     uint8_t *__restrict__ skip_mask, uint8_t *__restrict__ hot_mask,
-    int32_t *__restrict__ block_kept, TraceSlot ts)
+    int32_t *__restrict__ block_kept, TS ts)
 {
     constexpr int kFlagWG = flag_wg(LANES);
-    trace_begin(ts);
+    const unsigned long long trace_t0 = trace_begin<TS>();
     constexpr int SAMPLES = kFlagWG / LANES;
     const int c = threadIdx.x % LANES;
     const int b = blockIdx.x * SAMPLES + threadIdx.x / LANES;
@@ -133,17 +133,18 @@ __global__ __launch_bounds__(flag_wg(LANES)) void filter_flag_kernel(
         for (int w = 0; w < kFlagWG / 64; ++w) s += s_cnt[w];
         block_kept[blockIdx.x] = s;
     }
-    trace_end(ts);
+    trace_end(ts, trace_t0);
 }
 
+template <typename TS>
 __global__ __launch_bounds__(kWG) void filter_compact_kernel(
     const int32_t *__restrict__ idx, int B, int L,
     const uint8_t *__restrict__ skip_mask,
     const int32_t *__restrict__ block_kept, int per_tile,
     int32_t *__restrict__ kept_ids, int32_t *__restrict__ n_kept,
-    int32_t *__restrict__ idx_c, TraceSlot ts)
+    int32_t *__restrict__ idx_c, TS ts)
 {
-    trace_begin(ts);
+    const unsigned long long trace_t0 = trace_begin<TS>();
     // grid: x = tile of 256 samples, y = table, z = part of the tile's rows.  Every
     // workgroup repeats the cheap ranking of tile x and copies index rows of table y.
     // block_kept holds per_tile counts for every tile (one per workgroup of the
@@ -203,7 +204,7 @@ __global__ __launch_bounds__(kWG) void filter_compact_kernel(
                 if (e0 + u * kWG < total) dst[e0 + u * kWG] = v[u];
         }
     }
-    trace_end(ts);
+    trace_end(ts, trace_t0);
 }
 
 // Lanes per sample in the flag kernel: the fewest of 4 ... 64 with which two
@@ -245,11 +246,11 @@ int32_t launch_filter_split(const ss_tables *tb, uint32_t *const *hot_bits, cons
         ProfScope prof("filter_flag_kernel", s);
 #define SS_FLAG(LANES_)                                                            \
     if (hot_mask)                                                                  \
-        launch(filter_flag_kernel<LANES_, true>, dim3(flag_blocks),                 \
+        launch(SS_BOTH(filter_flag_kernel, LANES_, true), dim3(flag_blocks),         \
                dim3(flag_wg(LANES_)), s, tb->stale_bits, hot_bits, idx,             \
                tb->num_tables, B, L, alpha, skip_mask, hot_mask, block_kept);       \
     else                                                                           \
-        launch(filter_flag_kernel<LANES_, false>, dim3(flag_blocks),                \
+        launch(SS_BOTH(filter_flag_kernel, LANES_, false), dim3(flag_blocks),        \
                dim3(flag_wg(LANES_)), s, tb->stale_bits, nullptr, idx,              \
                tb->num_tables, B, L, alpha, skip_mask, nullptr, block_kept)
         switch (lanes) {
@@ -266,9 +267,9 @@ int32_t launch_filter_split(const ss_tables *tb, uint32_t *const *hot_bits, cons
     // before it is always covered by exactly kWG / samples of them
     // one workgroup per 1024 index words of a tile's rows, at most eight
     const int parts = L == 1 ? 1 : (L + 3) / 4 > 8 ? 8 : (L + 3) / 4;
-    launch(filter_compact_kernel, dim3(tiles, tb->num_tables, parts),
-                       dim3(kWG), s, idx, B, L, skip_mask, block_kept, kWG / samples,
-                       kept_ids, n_kept, idx_c);
+    launch(filter_compact_kernel<NoTrace>, filter_compact_kernel<TraceSlot>,
+           dim3(tiles, tb->num_tables, parts), dim3(kWG), s, idx, B, L, skip_mask, block_kept,
+           kWG / samples, kept_ids, n_kept, idx_c);
     return check_launch("ss_filter_batch");
 }
 

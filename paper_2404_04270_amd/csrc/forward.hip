@@ -18,19 +18,19 @@
 
 namespace ss {
 
-template <int G>
+template <int G, typename TS>
 __global__ __launch_bounds__(kWG) void forward_onehot_kernel(
     const float *const *__restrict__ weights, const int32_t *__restrict__ idx,
     int Bcap, const int32_t *__restrict__ n_valid, float *__restrict__ out,
-    int D4, int tiles_per_table, int pinned_blocks, TraceSlot ts)
+    int D4, int tiles_per_table, int pinned_blocks, TS ts)
 {
-    trace_begin(ts);
+    const unsigned long long trace_t0 = trace_begin<TS>();
     // a table's hot rows are wanted by all its tiles: keep them in one L2
     int t, tile;
     block_to_table_pinned(blockIdx.x, tiles_per_table, pinned_blocks, t, tile);
     forward_onehot_body<G, kWG>(t * tiles_per_table + tile, weights, idx, Bcap, n_valid, out, D4,
                                 tiles_per_table);
-    trace_end(ts);
+    trace_end(ts, trace_t0);
 }
 
 // Multi-hot bags.  All lanes of a workgroup see the same bag length, so the bag
@@ -67,14 +67,14 @@ template <int N> __device__ __forceinline__ void add_rows(f4 &acc, const f4 (&v)
     for (int k = 0; k < N; ++k) acc = acc + v[k];
 }
 
-template <int G, bool FULL>
+template <int G, bool FULL, typename TS>
 __global__ __launch_bounds__(kWG) void forward_kernel(
     const float *const *__restrict__ weights, const int32_t *__restrict__ idx,
     int Bcap, int L, const int32_t *__restrict__ n_valid,
-    float *__restrict__ out, int D4, int tiles_per_table, int pinned_blocks, TraceSlot ts)
+    float *__restrict__ out, int D4, int tiles_per_table, int pinned_blocks, TS ts)
 {
     constexpr int BAGS = kWG / G;
-    trace_begin(ts);
+    const unsigned long long trace_t0 = trace_begin<TS>();
     int t, tile;
     block_to_table_pinned(blockIdx.x, tiles_per_table, pinned_blocks, t, tile);
     const int n = clamp_valid(n_valid, Bcap);
@@ -120,7 +120,7 @@ __global__ __launch_bounds__(kWG) void forward_kernel(
         if (m & 1) add_rows(acc, f);
         o[col] = acc;
     }
-    trace_end(ts);
+    trace_end(ts, trace_t0);
 }
 
 int32_t launch_forward(const ss_tables *tb, const int32_t *idx, int Bcap, int L,
@@ -135,13 +135,13 @@ int32_t launch_forward(const ss_tables *tb, const int32_t *idx, int Bcap, int L,
         return fail(SS_ERR_UNSUPPORTED, "ss_embbag_forward: grid too large");
     ProfScope prof("forward_kernel", s);
     if (L == 1) {
-        SS_DISPATCH_G(g, launch(forward_onehot_kernel<G>,
+        SS_DISPATCH_G(g, launch(SS_BOTH(forward_onehot_kernel, G),
                                             dim3((unsigned)blocks), dim3(kWG), s,
                                             tb->weights, idx, Bcap, n_valid, out,
                                             D4, tiles, (tb->num_tables / 8) * 8 * tiles));
     } else {
 #define SS_FWD(F_)                                                                \
-    SS_DISPATCH_G(g, launch((forward_kernel<G, F_>), dim3((unsigned)blocks),       \
+    SS_DISPATCH_G(g, launch(SS_BOTH(forward_kernel, G, F_), dim3((unsigned)blocks),       \
                             dim3(kWG), s, tb->weights, idx, Bcap, L, n_valid, out,  \
                             D4, tiles, (tb->num_tables / 8) * 8 * tiles))
         if (D4 == g) { SS_FWD(true); } else { SS_FWD(false); }
