@@ -484,7 +484,11 @@ int32_t ss_stream_wait_event(void *stream, void *event);
  *                              the batch's ss_step_backward has been called.  If
  *                              idx is still being produced on some stream, pass
  *                              the event recorded after its producer (a
- *                              hipEvent_t as void *), else NULL
+ *                              hipEvent_t as void *), else NULL.  The wait for it
+ *                              may be enqueued later than this call (by an issue
+ *                              thread, or after a detect pass): the event must
+ *                              not be destroyed or recorded again before the
+ *                              batch's ss_step_forward has returned
  *     ss_step_forward          pooled lookup of the oldest submitted batch into
  *                              `pooled` on the training stream; *set_used (may be
  *                              NULL) = the buffer set that holds this batch's

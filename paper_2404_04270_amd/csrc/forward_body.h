@@ -26,21 +26,28 @@ __device__ __forceinline__ void forward_onehot_body(
     constexpr int GROUPS = THREADS / G, BPG = kOneHotBags;
     int t, tile;
     block_to_table_tile(b, tiles_per_table, t, tile);
-    const int n = clamp_valid(n_valid, Bcap);
     const int g = threadIdx.x / G, c = threadIdx.x % G;
     const int j0 = tile * GROUPS * BPG + g;      // bags j0 + k * GROUPS
-    if (j0 >= n) return;
+    if (j0 >= Bcap) return;
     const auto W = as_global(reinterpret_cast<const f4 *>(weights[t]));
     const int32_t *__restrict__ ip = idx + (int64_t)t * Bcap;
     f4 *__restrict__ o = reinterpret_cast<f4 *>(out) + (int64_t)t * Bcap * D4;
 
-    // bags past n_valid re-read bag j0 (always valid) and store nothing
+    // The index words are requested before the number of valid bags is looked at (it
+    // sits in device memory, one more round trip away): every position below Bcap can
+    // be read, and what lies past n_valid is replaced by bag j0's index before it is
+    // used as a row number.  Those bags store nothing.
     int32_t r[BPG];
 #pragma unroll
     for (int k = 0; k < BPG; ++k) {
         const int j = j0 + k * GROUPS;
-        r[k] = ip[j < n ? j : j0];
+        r[k] = ip[j < Bcap ? j : j0];
     }
+    const int n = clamp_valid(n_valid, Bcap);
+    if (j0 >= n) return;
+#pragma unroll
+    for (int k = 0; k < BPG; ++k)
+        if (j0 + k * GROUPS >= n) r[k] = r[0];
     for (int col = c; col < D4; col += G) {
         f4 v[BPG];
 #pragma unroll

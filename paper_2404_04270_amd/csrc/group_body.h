@@ -96,7 +96,9 @@ __device__ __forceinline__ void class_sort_body(
 #pragma unroll
     for (int r = 0; r < ITEMS; ++r) {
         const int pos = wave * ITEMS * 64 + r * 64 + lane;
-        key[r] = pos < n ? (uint32_t)ip[pos] : kNoRow;
+        // requested before n is known (it comes from device memory); used only below n
+        const uint32_t word = (uint32_t)ip[pos < Bcap * L ? pos : 0];
+        key[r] = pos < n ? word : kNoRow;
     }
     drop_stale(bt, key);
 

@@ -168,6 +168,7 @@ class PipelinedStep:
             self.ws_backward = torch.empty(
                 B.ss_backward_workspace_bytes(T, batch, bag, D), dtype=torch.uint8, device=dev)
             self.idx = None                        # keeps the index tensor alive
+            self.ready = None                      # ... and the event it was handed over with
 
     @staticmethod
     def auto_every(T: int, batch: int, bag: int, n_side: int) -> int:
@@ -265,7 +266,11 @@ class PipelinedStep:
         if self.room() <= 0:
             raise RuntimeError("PipelinedStep: too far ahead (see room())")
         B.ss_step_submit(self._step, idx, ready)
-        self.sets[self.submitted % len(self.sets)].idx = idx
+        # the wait for `ready` may be enqueued later than this call (issue thread, or a
+        # batch held back behind a detect pass): the event lives as long as the set
+        # holds this batch
+        st = self.sets[self.submitted % len(self.sets)]
+        st.idx, st.ready = idx, ready
         self.submitted += 1
 
     def forward(self) -> torch.Tensor:
