@@ -105,6 +105,15 @@ ProfScope::~ProfScope()
     t_prof_kernel = nullptr;
 }
 
+static thread_local hipEvent_t t_stop_event = nullptr;
+void stop_event_for_next_launch(hipEvent_t ev) { t_stop_event = ev; }
+hipEvent_t take_stop_event()
+{
+    const hipEvent_t ev = t_stop_event;
+    t_stop_event = nullptr;
+    return ev;
+}
+
 bool prof_events(hipEvent_t *start, hipEvent_t *stop)
 {
     if (t_prof_slot < 0) return false;

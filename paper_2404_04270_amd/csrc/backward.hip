@@ -733,7 +733,7 @@ int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bca
 }
 
 int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float *grad,
-                              float lr, void *ws, hipStream_t s)
+                              float lr, void *ws, hipStream_t s, hipEvent_t record_after)
 {
     const int T = tb->num_tables, D4 = tb->dim / 4;
     const Layout y = make_layout(T, Bcap, L, tb->dim);
@@ -775,6 +775,7 @@ int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float 
     // apply workgroups looked at per workgroup of this launch
     const int per_chunk = (int64_t)wgs * T <= 2048 ? 1 : kWG / g;
     const int chunks = (wgs + per_chunk - 1) / per_chunk;
+    if (record_after) stop_event_for_next_launch(record_after);     // the last launch of the update
     SS_DISPATCH_G(g, launch(SS_BOTH(fixup_kernel, G), dim3((unsigned)(chunks * T)),
                                         dim3(kWG), s, tb->weights, D4, lr, wgs,
                                         chunks, per_chunk, trail_row, lead_state,

@@ -107,15 +107,33 @@ __device__ __forceinline__ void trace_end(TraceSlot ts, unsigned long long t0)
 // k<..., NoTrace>, k<..., TraceSlot>: the two variants of a kernel template, for launch()
 #define SS_BOTH(kernel, ...) (kernel<__VA_ARGS__, NoTrace>), (kernel<__VA_ARGS__, TraceSlot>)
 
+// The next launch of the calling thread also records `ev` when its kernel has
+// ended: the event rides on the dispatch's own completion signal, and the stream
+// gets no separate command for it (between two dependent kernels such a command
+// costs the stream several microseconds).
+void stop_event_for_next_launch(hipEvent_t ev);
+hipEvent_t take_stop_event();
+
+template <typename K, typename... Args>
+inline void launch_with_events(K kernel, dim3 grid, dim3 block, hipStream_t s, Args... args)
+{
+    hipEvent_t e0, e1;
+    const hipEvent_t stop = take_stop_event();
+    if (prof_events(&e0, &e1)) {
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, s, e0, e1, 0, args...);
+        if (stop) (void)hipEventRecord(stop, s);
+    } else if (stop) {
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, s, nullptr, stop, 0, args...);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, 0, s, args...);
+    }
+}
+
 template <typename... KArgs, typename... Args>
 inline void launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t s,
                    Args... args)
 {
-    hipEvent_t e0, e1;
-    if (prof_events(&e0, &e1))
-        hipExtLaunchKernelGGL(kernel, grid, block, 0, s, e0, e1, 0, args...);
-    else
-        hipLaunchKernelGGL(kernel, grid, block, 0, s, args...);
+    launch_with_events(kernel, grid, block, s, args...);
 }
 
 // A kernel with a traced variant: `plain` takes a NoTrace after args, `traced` a TraceSlot.
@@ -126,15 +144,8 @@ inline void launch(void (*plain)(PArgs...), void (*traced)(TArgs...), dim3 grid,
     static_assert(sizeof...(PArgs) == sizeof...(Args) + 1 && sizeof...(TArgs) == sizeof...(Args) + 1,
                   "both variants take the arguments plus the trace parameter");
     const TraceSlot ts = next_trace_slot();
-    hipEvent_t e0, e1;
-    const bool pairs = prof_events(&e0, &e1);
-    if (ts.p) {
-        if (pairs) hipExtLaunchKernelGGL(traced, grid, block, 0, s, e0, e1, 0, args..., ts);
-        else hipLaunchKernelGGL(traced, grid, block, 0, s, args..., ts);
-    } else {
-        if (pairs) hipExtLaunchKernelGGL(plain, grid, block, 0, s, e0, e1, 0, args..., NoTrace{});
-        else hipLaunchKernelGGL(plain, grid, block, 0, s, args..., NoTrace{});
-    }
+    if (ts.p) launch_with_events(traced, grid, block, s, args..., ts);
+    else launch_with_events(plain, grid, block, s, args..., NoTrace{});
 }
 
 // Lanes that cooperate on one row: one f4 per lane, a power of two <= 64.
@@ -254,8 +265,10 @@ int32_t launch_detect(const ss_tables *tb, int32_t *const *hot_ids, int H,
 int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bcap,
                                 int L, const int32_t *n_valid, void *ws,
                                 hipStream_t s);
+// record_after (may be null): an event to record when the update is complete
 int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float *grad,
-                              float lr, void *ws, hipStream_t s);
+                              float lr, void *ws, hipStream_t s,
+                              hipEvent_t record_after = nullptr);
 size_t backward_ws_bytes(int T, int Bcap, int L, int dim);
 // Where stage 1 of the backward pass leaves a table's grouped lookups when it
 // takes the one-launch path (buffer 0 of the workspace), and the padded length.

@@ -51,7 +51,9 @@ struct StepOps {
                             uint64_t *ticket) = 0;
     // on the training stream
     virtual int32_t lookup(int set) = 0;
-    virtual int32_t update(int set, const float *grad) = 0;
+    // record_after (may be null): an event of the training stream to record once the
+    // update is complete, as record_now would right after it
+    virtual int32_t update(int set, const float *grad, void *record_after) = 0;
     virtual int32_t detect(float threshold) = 0;
     // events; stream kMainStream is the training stream
     virtual int32_t new_event(void **ev) = 0;
@@ -107,6 +109,15 @@ struct ss_step {
     bool boundary_in(int64_t lo, int64_t hi) const { return (lo / K + 1) * K - 1 < hi; }
     int room() const { return (int)(2 * (int64_t)every * n_side - (submitted - it)); }
 
+    void keep(Marks &m, int64_t covers, void *ev, uint64_t ticket)
+    {
+        m.recorded.push_back(Mark{covers, ev, ticket});
+        if (m.recorded.size() > ss::kMarksKept) {     // that far back: issued and waited for long ago
+            m.spare.push_back(m.recorded.front().ev);
+            m.recorded.pop_front();
+        }
+    }
+
     int32_t record(Marks &m, int64_t covers)
     {
         if (m.spare.empty())
@@ -117,11 +128,7 @@ struct ss_step {
         const int32_t rc = (n_queues && m.by_queue) ? ops->q_record(m.queue, ev, m.stream, &ticket)
                                                     : ops->record_now(ev, m.stream);
         if (rc) return rc;
-        m.recorded.push_back(Mark{covers, ev, ticket});
-        if (m.recorded.size() > ss::kMarksKept) {     // that far back: issued and waited for long ago
-            m.spare.push_back(m.recorded.front().ev);
-            m.recorded.pop_front();
-        }
+        keep(m, covers, ev, ticket);
         return SS_OK;
     }
 
@@ -281,9 +288,11 @@ struct GpuOps final : StepOps {
         const ss_step_set &b = sets[set];
         return launch_forward(&tables, b.idx_c, B, L, b.n_kept, pooled, main);
     }
-    int32_t update(int set, const float *grad) override
+    int32_t update(int set, const float *grad, void *record_after) override
     {
-        return launch_backward_apply(&tables, B, L, grad, lr, sets[set].ws_backward, main);
+        // the event rides on the update's last launch: no command of its own on the stream
+        return launch_backward_apply(&tables, B, L, grad, lr, sets[set].ws_backward, main,
+                                     static_cast<hipEvent_t>(record_after));
     }
     int32_t detect(float threshold) override
     {
@@ -297,7 +306,17 @@ struct GpuOps final : StepOps {
         return rc;
     }
     int32_t record_now(void *ev, int s) override { return ss_event_record(ev, stream(s)); }
-    int32_t wait_now(int s, void *ev) override { return ss_stream_wait_event(stream(s), ev); }
+    int32_t wait_now(int s, void *ev) override
+    {
+        // An event that has already happened needs no wait command on the stream (a
+        // command that the stream would spend microseconds on between two kernels).
+        // Every event that comes here has been recorded before: ss_step records its
+        // own before it waits for them, through an issue queue only after the record
+        // has been issued, and a caller's ready event is recorded before ss_step_submit.
+        if (hipEventQuery(static_cast<hipEvent_t>(ev)) == hipSuccess) return SS_OK;
+        (void)hipGetLastError();        // "not ready" is not an error to keep
+        return ss_stream_wait_event(stream(s), ev);
+    }
     int32_t q_record(int q, void *ev, int s, uint64_t *t) override
     {
         return ss_issue_record_event(queues[q], ev, stream(s), t);
@@ -337,7 +356,12 @@ struct TracedOps final : StepOps {
         return cb.q_index(cb.user, q, s, set, t);
     }
     int32_t lookup(int set) override { return cb.lookup(cb.user, set); }
-    int32_t update(int set, const float *) override { return cb.update(cb.user, set); }
+    int32_t update(int set, const float *, void *record_after) override
+    {
+        const int32_t rc = cb.update(cb.user, set);
+        if (rc || !record_after) return rc;
+        return cb.record_now(cb.user, id(record_after), kMainStream);
+    }
     int32_t detect(float thr) override { return cb.detect(cb.user, thr > 0.f ? 1 : 0); }
     int32_t new_event(void **ev) override
     {
@@ -585,8 +609,21 @@ int32_t ss_step_backward(ss_step *st, const float *grad, int32_t *detected)
     if (reinterpret_cast<uintptr_t>(grad) % 16 != 0)
         return fail(SS_ERR_INVALID_ARG, "%s: grad is not 16-byte aligned", who);
     const int64_t k = st->it;
-    int32_t rc = st->ops->update((int)(k % st->n_sets), grad);
-    if (rc) return rc;
+    // Every `every`-th batch the training stream leaves an event for the index streams
+    // (a buffer set is free again once its batch has been trained on).  Without a
+    // detect pass behind it the update's last launch carries the event.
+    const bool mark = (k + 1) % st->every == 0;
+    void *rides = nullptr;
+    if (mark && !st->boundary(k) && !st->trained.spare.empty()) {
+        rides = st->trained.spare.back();
+        st->trained.spare.pop_back();
+    }
+    int32_t rc = st->ops->update((int)(k % st->n_sets), grad, rides);
+    if (rc) {
+        if (rides) st->trained.spare.push_back(rides);
+        return rc;
+    }
+    if (rides) st->keep(st->trained, k, rides, 0);
     int32_t det = 0;
     if (st->boundary(k)) {
         // the first period is the warm-up: its end captures the first snapshot
@@ -597,7 +634,7 @@ int32_t ss_step_backward(ss_step *st, const float *grad, int32_t *detected)
         st->last_detect = k;
     }
     ++st->it;
-    if (st->it % st->every == 0) {
+    if (mark && !rides) {
         rc = st->record(st->trained, k);
         if (rc) return rc;
     }
