@@ -222,6 +222,9 @@ class Measurement:
         # as long as twenty to forty steps of the default workload.
         gc_was_on = gc.isenabled()
         gc.disable()
+        # torch creates an event's HIP object at its first record: not inside the region
+        e0.record()
+        e1.record()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         e0.record()
