@@ -540,10 +540,14 @@ __global__ __launch_bounds__(kWG) void fixup_kernel(
         const uint32_t lrow = s_long_row[i];
         if (tid == 0) s_end = 0x7fffffff;
         __syncthreads();
-        // first among the states already in LDS ...
+        // first among the states already in LDS ...  (One LDS atomic per wavefront:
+        // its first lane that sees the run end, found with a ballot.  An atomic per
+        // lane on the one address took 2 us, a third of this kernel's duration.)
         {
             const int k = w0g - wg_first + tid;
-            if (k < kWG && s_state[k] != 2) atomicMin(&s_end, w0g + 1 + tid);
+            const unsigned long long hits = __ballot(k < kWG && s_state[k] != 2);
+            if (hits && (tid & 63) == 0)
+                atomicMin(&s_end, w0g + 1 + tid + (int)__builtin_ctzll(hits));
         }
         __syncthreads();
         int end = s_end;
@@ -553,7 +557,8 @@ __global__ __launch_bounds__(kWG) void fixup_kernel(
              b0 += kWG) {
             const int q = b0 + tid;
             const uint8_t s2 = q < wgs_per_table ? ls[q] : (uint8_t)2;
-            if (q < wgs_per_table && s2 != 2) atomicMin(&s_end, q);
+            const unsigned long long hits = __ballot(q < wgs_per_table && s2 != 2);
+            if (hits && (tid & 63) == 0) atomicMin(&s_end, q + (int)__builtin_ctzll(hits));
             __syncthreads();
             end = s_end;
             __syncthreads();
