@@ -577,8 +577,7 @@ __global__ __launch_bounds__(kWG) void fixup_kernel(
             if (active) {
                 const f4 *pt = PT + (int64_t)w0g * D4 + col;
                 const f4 *pl = PL + (int64_t)w0g * D4 + col;
-                if (npieces <= 8 * NG) sum = sum_pieces<8, NG>(pt, pl, D4, g, npieces);
-                else sum = sum_pieces<16, NG>(pt, pl, D4, g, npieces);
+                sum = sum_pieces<8, NG>(pt, pl, D4, g, npieces);
             }
             s_part[tid] = sum;
             __syncthreads();
