@@ -672,7 +672,7 @@ static int sorted_buffer(const Layout &y, int64_t rows)
 
 int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bcap,
                                 int L, const int32_t *n_valid, void *ws,
-                                hipStream_t s)
+                                hipStream_t s, hipEvent_t record_after)
 {
     const int T = tb->num_tables;
     const Layout y = make_layout(T, Bcap, L, tb->dim);
@@ -687,6 +687,7 @@ int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bca
         const ClassSortPlan cp = plan_class_sort(y.NP, Bcap, key_bits);
         const dim3 grid(1 << cp.class_bits, T);
         ProfScope prof("class_sort_kernel", s);
+        if (record_after) stop_event_for_next_launch(record_after);     // the only launch
 #define SS_LDS_SORT(I, P)                                                          \
     launch(SS_BOTH(class_sort_kernel, I, P), grid, dim3(1024), s, idx, Bcap, L, n_valid,     \
            tb->stale_bits, key_bits, cp.class_bits, cp.val_bits, ent[0],            \
@@ -725,6 +726,7 @@ int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bca
                            y.tiles);
             }
             ProfScope prof("rs_scatter_kernel", s);
+            if (record_after && pass == npass - 1) stop_event_for_next_launch(record_after);
             launch(rs_scatter_kernel<NoTrace>, rs_scatter_kernel<TraceSlot>, grid, dim3(kRsThreads), s, ent[in], ent[out], y.NP,
                    shift, nb, hist, y.tiles);
             cur = out;

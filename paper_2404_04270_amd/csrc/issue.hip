@@ -87,7 +87,7 @@ void run_job(ss_issue_queue *q, const Job &j)
                            j.n_kept, j.idx_c, j.ws_filter, j.stream);
         if (rc == SS_OK)
             rc = launch_backward_prepare(&j.tables, j.idx_c, j.B, j.L, j.n_kept,
-                                         j.ws_backward, j.stream);
+                                         j.ws_backward, j.stream, j.event);
         break;
     }
     std::lock_guard<std::mutex> lk(q->mu);
@@ -170,6 +170,20 @@ int32_t ss_issue_index_batch(ss_issue_queue *q, const ss_tables *tables,
                              void *ws_backward, size_t ws_backward_bytes, void *stream,
                              uint64_t *ticket)
 {
+    return ss::issue_index_batch(q, tables, idx, B, L, alpha, skip_mask, kept_ids, n_kept, idx_c,
+                                 ws_filter, ws_filter_bytes, ws_backward, ws_backward_bytes,
+                                 stream, nullptr, ticket);
+}
+
+}  // extern "C"
+
+int32_t ss::issue_index_batch(ss_issue_queue *q, const ss_tables *tables, const int32_t *idx,
+                              int32_t B, int32_t L, int32_t alpha, uint8_t *skip_mask,
+                              int32_t *kept_ids, int32_t *n_kept, int32_t *idx_c,
+                              void *ws_filter, size_t ws_filter_bytes, void *ws_backward,
+                              size_t ws_backward_bytes, void *stream, void *record_after,
+                              uint64_t *ticket)
+{
     const char *who = "ss_issue_index_batch";
     if (!q) return fail(SS_ERR_INVALID_ARG, "%s: queue is NULL", who);
     int32_t rc = check_filter(who, tables, idx, B, L, skip_mask, kept_ids, n_kept, idx_c,
@@ -191,8 +205,11 @@ int32_t ss_issue_index_batch(ss_issue_queue *q, const ss_tables *tables,
     j.idx_c = idx_c;
     j.ws_filter = ws_filter;
     j.ws_backward = ws_backward;
+    j.event = static_cast<hipEvent_t>(record_after);
     return push(q, j, ticket);
 }
+
+extern "C" {
 
 int32_t ss_issue_wait_event(ss_issue_queue *q, void *event, void *stream, uint64_t *ticket)
 {

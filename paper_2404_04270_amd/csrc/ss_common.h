@@ -262,9 +262,17 @@ int32_t launch_detect(const ss_tables *tb, int32_t *const *hot_ids, int H,
                       float **snapshot, float threshold, int refresh,
                       uint8_t **stale_hot, double **drift,
                       uint32_t *stale_count, hipStream_t s);
+// record_after (may be null): an event to record when the grouped lists are complete
 int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bcap,
                                 int L, const int32_t *n_valid, void *ws,
-                                hipStream_t s);
+                                hipStream_t s, hipEvent_t record_after = nullptr);
+// ss_issue_index_batch with an event (may be null) that the job records behind its
+// last launch
+int32_t issue_index_batch(::ss_issue_queue *q, const ss_tables *tables, const int32_t *idx,
+                          int32_t B, int32_t L, int32_t alpha, uint8_t *skip_mask,
+                          int32_t *kept_ids, int32_t *n_kept, int32_t *idx_c, void *ws_filter,
+                          size_t ws_filter_bytes, void *ws_backward, size_t ws_backward_bytes,
+                          void *stream, void *record_after, uint64_t *ticket);
 // record_after (may be null): an event to record when the update is complete
 int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float *grad,
                               float lr, void *ws, hipStream_t s,

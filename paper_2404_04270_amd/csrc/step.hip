@@ -45,9 +45,11 @@ constexpr size_t kRingBytes = 96u << 20;
 struct StepOps {
     virtual ~StepOps() {}
     // ss_filter_batch + ss_embbag_backward_prepare of a batch into buffer set `set`,
-    // on index stream `stream`: at once, or as a job of issue queue `queue`
-    virtual int32_t index_now(int stream, int set, const int32_t *idx) = 0;
-    virtual int32_t q_index(int queue, int stream, int set, const int32_t *idx,
+    // on index stream `stream`: at once, or as a job of issue queue `queue`; then
+    // event `done` is recorded on that stream as record_now / q_record would
+    // (*ticket: the job after which the record has been issued)
+    virtual int32_t index_now(int stream, int set, const int32_t *idx, void *done) = 0;
+    virtual int32_t q_index(int queue, int stream, int set, const int32_t *idx, void *done,
                             uint64_t *ticket) = 0;
     // on the training stream
     virtual int32_t lookup(int set) = 0;
@@ -59,6 +61,8 @@ struct StepOps {
     virtual int32_t new_event(void **ev) = 0;
     virtual int32_t record_now(void *ev, int stream) = 0;
     virtual int32_t wait_now(int stream, void *ev) = 0;
+    // has the event, recorded (issued) earlier, happened already?  "no" is always a safe answer
+    virtual bool done_now(void *ev) = 0;
     virtual int32_t q_record(int queue, void *ev, int stream, uint64_t *ticket) = 0;
     virtual int32_t q_wait(int queue, void *ev, int stream, uint64_t *ticket) = 0;
     virtual int32_t q_wait_issued(int queue, uint64_t ticket) = 0;
@@ -159,6 +163,58 @@ struct ss_step {
         return SS_OK;
     }
 
+    // The training stream is about to look up batch k, whose index work ran on index
+    // stream j.  Every batch has an event of its own there.  If the calling thread can see
+    // that the index stream is past k already, nothing is enqueued, and all batches up to
+    // the newest finished one count as known.  Otherwise the training stream gets a wait
+    // command, which costs it a few microseconds between two kernels whether it has to wait
+    // or not: it is made to cover `ahead` further batches of that stream, as many as the
+    // index streams can be expected to have regained of their lead since the last detect
+    // pass (behind which they start with none and gain only the difference between the
+    // two paces per batch; an event that covered a whole ring there kept the training
+    // stream waiting 130-180 us once per pass).
+    int32_t cover_indexed(int j, int64_t k)
+    {
+        Marks &m = indexed[j];
+        if (k <= m.known[0]) return SS_OK;
+        const auto at = [&](int64_t batch) -> const Mark * {
+            for (const Mark &mk : m.recorded)
+                if (mk.covers == batch) return &mk;
+            return nullptr;
+        };
+        const int64_t last = issued - 1 - (issued - 1 - j) % n_side;     // newest batch of stream j
+        const Mark *mine = at(k);
+        if (!mine) return ss::fail(SS_ERR_HIP, "ss_step: internal: batch %lld has no event", (long long)k);
+        if (!n_queues) {
+            // events of a stream happen in order: the newest finished one, by bisection
+            if (ops->done_now(mine->ev)) {
+                int64_t lo = k, hi = last;           // lo is done
+                while (lo < hi) {
+                    const int64_t mid = lo + ((hi - lo) / n_side + 1) / 2 * n_side;
+                    const Mark *mk = at(mid);
+                    if (mk && ops->done_now(mk->ev)) lo = mid;
+                    else hi = mid - n_side;
+                }
+                m.known[0] = lo;
+                return SS_OK;
+            }
+        }
+        const int64_t since = k - last_detect - 1;                       // last_detect = -1 at the start
+        const int64_t ahead = std::min<int64_t>(every - 1, since / (8 * n_side));
+        const Mark *target = at(std::min(last, k + ahead * n_side));
+        if (!target) target = mine;
+        int32_t rc = SS_OK;
+        if (n_queues) {
+            // a wait for an event whose record has not been issued yet is a no-op
+            rc = ops->q_wait_issued(m.queue, target->ticket);
+            if (rc) return rc;
+        }
+        rc = ops->wait_now(ss::kMainStream, target->ev);
+        if (rc) return rc;
+        m.known[0] = target->covers;
+        return SS_OK;
+    }
+
     int32_t issue(int64_t k, const int32_t *idx, void *ready)
     {
         const int set = (int)(k % n_sets), j = (int)(k % n_side);
@@ -183,18 +239,28 @@ struct ss_step {
                                          (long long)need);
             }
         }
-        if (n_queues)
-            rc = ops->q_index(queue_of(j), j, set, idx, &last_ticket[queue_of(j)]);
-        else
-            rc = ops->index_now(j, set, idx);
-        if (rc) return rc;
+        // Every batch's index work carries an event of its own, on its last launch.  The
+        // training stream then never waits for more index work than the batch it is about
+        // to look up needs (an event that covered several batches kept it waiting 130-180 us
+        // once behind every detect pass, while the index streams had not regained their
+        // lead), and as long as the index streams are ahead it does not wait at all.
+        Marks &m = indexed[j];
+        if (m.spare.empty()) return ss::fail(SS_ERR_HIP, "ss_step: event pool exhausted");
+        void *ev = m.spare.back();
+        m.spare.pop_back();
+        uint64_t ticket = 0;
+        if (n_queues) {
+            rc = ops->q_index(queue_of(j), j, set, idx, ev, &ticket);
+            last_ticket[queue_of(j)] = ticket;
+        } else {
+            rc = ops->index_now(j, set, idx, ev);
+        }
+        if (rc) {
+            m.spare.push_back(ev);
+            return rc;
+        }
         ++issued;
-        // every `every`-th batch of this stream, and a batch the training stream is about
-        // to ask for (right after a detect pass, or a caller that submits just in time):
-        // an event recorded later, on demand, would also cover, and so wait for, whatever
-        // index work has been enqueued behind this batch by then
-        if ((k / n_side + 1) % every == 0 || k - it < (int64_t)every * n_side)
-            rc = record(indexed[j], k);
+        keep(m, k, ev, ticket);
         return rc;
     }
 
@@ -268,20 +334,23 @@ struct GpuOps final : StepOps {
 
     hipStream_t stream(int s) const { return s == kMainStream ? main : sides[s]; }
 
-    int32_t index_now(int s, int set, const int32_t *idx) override
+    // the event rides on the last launch of the index work: no command of its own
+    int32_t index_now(int s, int set, const int32_t *idx, void *done) override
     {
         const ss_step_set &b = sets[set];
         int32_t rc = launch_filter(&tables, idx, B, L, alpha, b.skip_mask, b.kept_ids, b.n_kept,
                                    b.idx_c, b.ws_filter, stream(s));
         if (rc) return rc;
-        return launch_backward_prepare(&tables, b.idx_c, B, L, b.n_kept, b.ws_backward, stream(s));
+        return launch_backward_prepare(&tables, b.idx_c, B, L, b.n_kept, b.ws_backward, stream(s),
+                                       static_cast<hipEvent_t>(done));
     }
-    int32_t q_index(int q, int s, int set, const int32_t *idx, uint64_t *ticket) override
+    int32_t q_index(int q, int s, int set, const int32_t *idx, void *done,
+                    uint64_t *ticket) override
     {
         const ss_step_set &b = sets[set];
-        return ss_issue_index_batch(queues[q], &tables, idx, B, L, alpha, b.skip_mask, b.kept_ids,
-                                    b.n_kept, b.idx_c, b.ws_filter, b.ws_filter_bytes,
-                                    b.ws_backward, b.ws_backward_bytes, stream(s), ticket);
+        return issue_index_batch(queues[q], &tables, idx, B, L, alpha, b.skip_mask, b.kept_ids,
+                                 b.n_kept, b.idx_c, b.ws_filter, b.ws_filter_bytes, b.ws_backward,
+                                 b.ws_backward_bytes, stream(s), done, ticket);
     }
     int32_t lookup(int set) override
     {
@@ -306,6 +375,12 @@ struct GpuOps final : StepOps {
         return rc;
     }
     int32_t record_now(void *ev, int s) override { return ss_event_record(ev, stream(s)); }
+    bool done_now(void *ev) override
+    {
+        if (hipEventQuery(static_cast<hipEvent_t>(ev)) == hipSuccess) return true;
+        (void)hipGetLastError();        // "not ready" is not an error to keep
+        return false;
+    }
     int32_t wait_now(int s, void *ev) override
     {
         // An event that has already happened needs no wait command on the stream (a
@@ -313,8 +388,7 @@ struct GpuOps final : StepOps {
         // Every event that comes here has been recorded before: ss_step records its
         // own before it waits for them, through an issue queue only after the record
         // has been issued, and a caller's ready event is recorded before ss_step_submit.
-        if (hipEventQuery(static_cast<hipEvent_t>(ev)) == hipSuccess) return SS_OK;
-        (void)hipGetLastError();        // "not ready" is not an error to keep
+        if (done_now(ev)) return SS_OK;
         return ss_stream_wait_event(stream(s), ev);
     }
     int32_t q_record(int q, void *ev, int s, uint64_t *t) override
@@ -350,10 +424,17 @@ struct GpuOps final : StepOps {
 struct TracedOps final : StepOps {
     ss_step_trace_ops cb;
     int next_event = 0;
-    int32_t index_now(int s, int set, const int32_t *) override { return cb.index_now(cb.user, s, set); }
-    int32_t q_index(int q, int s, int set, const int32_t *, uint64_t *t) override
+    int32_t index_now(int s, int set, const int32_t *, void *done) override
     {
-        return cb.q_index(cb.user, q, s, set, t);
+        const int32_t rc = cb.index_now(cb.user, s, set);
+        if (rc || !done) return rc;
+        return cb.record_now(cb.user, id(done), s);
+    }
+    int32_t q_index(int q, int s, int set, const int32_t *, void *done, uint64_t *t) override
+    {
+        const int32_t rc = cb.q_index(cb.user, q, s, set, t);
+        if (rc || !done) return rc;
+        return cb.q_record(cb.user, q, id(done), s, t);
     }
     int32_t lookup(int set) override { return cb.lookup(cb.user, set); }
     int32_t update(int set, const float *, void *record_after) override
@@ -371,6 +452,7 @@ struct TracedOps final : StepOps {
     static int id(void *ev) { return (int)reinterpret_cast<uintptr_t>(ev); }
     int32_t record_now(void *ev, int s) override { return cb.record_now(cb.user, id(ev), s); }
     int32_t wait_now(int s, void *ev) override { return cb.wait_now(cb.user, s, id(ev)); }
+    bool done_now(void *) override { return false; }
     int32_t q_record(int q, void *ev, int s, uint64_t *t) override
     {
         return cb.q_record(cb.user, q, id(ev), s, t);
@@ -582,18 +664,8 @@ int32_t ss_step_forward(ss_step *st, int32_t *set_used)
         return fail(SS_ERR_INVALID_ARG,
                     "%s: needs a submitted batch and the previous batch finished", who);
     const int set = (int)(k % st->n_sets), j = (int)(k % st->n_side);
-    bool ok = false;
-    int32_t rc = st->cover(st->indexed[j], 0, kMainStream, k, &ok);
+    int32_t rc = st->cover_indexed(j, k);
     if (rc) return rc;
-    if (!ok) {
-        // on demand: this stream's last issued batch is the last one congruent to j
-        const int64_t last = st->issued - 1 - (st->issued - 1 - j) % st->n_side;
-        rc = st->record(st->indexed[j], last);
-        if (rc) return rc;
-        rc = st->cover(st->indexed[j], 0, kMainStream, k, &ok);
-        if (rc) return rc;
-        if (!ok) return fail(SS_ERR_HIP, "%s: internal: batch %lld not covered", who, (long long)k);
-    }
     ++st->forwarded;
     if (set_used) *set_used = set;
     return st->ops->lookup(set);
