@@ -7,11 +7,16 @@
 // ss_embbag_backward_prepare) need the indices and the stale bitmaps only, not the
 // weights: they run for the coming batches on index streams of their own, into a
 // ring of buffer sets, while the current batch is in its lookup and update kernels
-// on the training stream.  An event recorded on one stream and waited for on
-// another costs about ten microseconds of GPU time on this platform, so the streams
-// do not meet once per batch: each records an event only every `every` batches
-// ("everything up to batch k is done"), and a stream waits only when the batch it
-// needs is not covered by an event it has waited for already.  The ring holds
+// on the training stream.  An event recorded on a stream, or a wait for one, as a
+// command of its own between two dependent kernels costs that stream several
+// microseconds on this platform, so there are as few such commands as possible.
+// Events ride on launches that happen anyway (the dispatch's own completion signal):
+// every batch's index work carries one on its last launch, and every `every`-th
+// update of the training stream carries one ("everything up to batch k is done").
+// A stream is made to wait only for a batch that is not covered by an event it has
+// waited for already, the training stream only if the calling thread cannot see that
+// the event has happened, and then for as many further batches as the index streams
+// can be expected to be ahead (cover_indexed).  The ring holds
 // 3 * every sets per index stream, of which two thirds may be in use ahead of the
 // batch being trained on: the set a new batch takes over was then last used at
 // least `every` batches ago, which an event of the training stream already covers.
