@@ -204,8 +204,11 @@ struct ss_step {
                 return SS_OK;
             }
         }
+        // ... and never more than half of what has been issued beyond k: a caller that
+        // starts again after a synchronisation has no lead either
         const int64_t since = k - last_detect - 1;                       // last_detect = -1 at the start
-        const int64_t ahead = std::min<int64_t>(every - 1, since / (8 * n_side));
+        const int64_t ahead = std::min<int64_t>(
+            {(int64_t)every - 1, since / (8 * n_side), (last - k) / (2 * n_side)});
         const Mark *target = at(std::min(last, k + ahead * n_side));
         if (!target) target = mine;
         int32_t rc = SS_OK;
