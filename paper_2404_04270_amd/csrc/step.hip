@@ -104,6 +104,7 @@ struct ss_step {
     Marks trained;                        // training stream: update done up to batch ...
 
     int64_t submitted = 0, issued = 0, forwarded = 0, it = 0, last_detect = -1;
+    int64_t lead_lost = -1;               // last batch before which the index streams had no lead
     bool have_snapshot = false;
     struct Held {
         const int32_t *idx;
@@ -204,11 +205,12 @@ struct ss_step {
                 return SS_OK;
             }
         }
-        // ... and never more than half of what has been issued beyond k: a caller that
-        // starts again after a synchronisation has no lead either
-        const int64_t since = k - last_detect - 1;                       // last_detect = -1 at the start
+        // A caller that submits just in time (at the start, or when it starts again after
+        // a synchronisation) has no lead either: that moment counts like a detect pass.
+        if (issued - 1 - k <= 1) lead_lost = k - 1;
+        const int64_t since = k - std::max(last_detect, lead_lost) - 1;
         const int64_t ahead = std::min<int64_t>(
-            {(int64_t)every - 1, since / (8 * n_side), (last - k) / (2 * n_side)});
+            {(int64_t)every - 1, since / (8 * n_side), (last - k) / n_side});
         const Mark *target = at(std::min(last, k + ahead * n_side));
         if (!target) target = mine;
         int32_t rc = SS_OK;
