@@ -66,6 +66,11 @@ def parse():
                          "(EmbeddingStep).  Default: PipelinedStep, which classifies and groups "
                          "the coming batches on a second stream while the current one is in its "
                          "forward and update kernels")
+    ap.add_argument("--start-empty", action="store_true",
+                    help="pipelined step: submit no index work beyond the last batch of a timed "
+                         "region, so that every region starts from an empty pipeline (default: "
+                         "the pipeline keeps its lead across regions, and a region holds the "
+                         "index work of as many batches as it trains on, the ones further on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prime", action="store_true",
                     help="diagnostic: leave out the untimed priming batches that precede the "
@@ -177,6 +182,8 @@ class Measurement:
         torch.cuda.synchronize()
         self.setup_s = time.time() - t0
         self.done = 0              # batches run so far (the next batch's number)
+        self.submitted = 0         # batches whose index work has been submitted
+        self.index_submitted_in_run = 0     # ... of them, by the last call of run()
 
     def run(self, n, stamps=None):
         """Exactly n more batches.  stamps: list that receives the host clock after
@@ -184,15 +191,23 @@ class Measurement:
         step, ring, grads, n_grads = self.step, self.args.ring, self.grads, self.n_grads
         idx_d, start = self.idx_d, self.done
         if self.pipelined:
-            # Index work is submitted ahead of the batch being trained on, never past the
-            # n-th, and at most two new batches per step: the lead grows to what the ring
-            # takes (room()) within a few steps, and a run that starts with an empty
-            # pipeline does not spend its first quarter millisecond enqueueing index
-            # work while the training stream has nothing to do.
-            nxt, end = start, start + n
+            # Index work is submitted ahead of the batch being trained on, at most two new
+            # batches per step: the lead grows to what the ring takes (room()) within a few
+            # steps, and a run that starts with an empty pipeline does not spend its first
+            # quarter millisecond enqueueing index work while the training stream has
+            # nothing to do.  By default the pipeline keeps running across calls: a region
+            # of n batches holds the lookup and update of those n batches and the index
+            # work of the n batches that lie `lead` further on, as any stretch of a training
+            # run does.  With --start-empty no index work is submitted beyond the region's
+            # last batch, so every region begins with an empty pipeline and holds the index
+            # work of exactly its own batches.
+            end = start + n
+            limit = end if self.args.start_empty else None
+            nxt = max(self.submitted, start)
             for it in range(start, end):
                 fresh = 0
-                while nxt < end and step.room() > 0 and (fresh < 2 or nxt <= it):
+                while (limit is None or nxt < limit) and step.room() > 0 and \
+                        (fresh < 2 or nxt <= it):
                     step.submit(idx_d[nxt % ring])
                     nxt += 1
                     fresh += 1
@@ -200,6 +215,8 @@ class Measurement:
                 step.backward(grads[it % n_grads])
                 if stamps is not None:
                     stamps.append(time.perf_counter())
+            self.index_submitted_in_run = nxt - max(self.submitted, start)
+            self.submitted = nxt
             step.flush()
         else:
             for it in range(start, start + n):
@@ -207,6 +224,7 @@ class Measurement:
                 step.backward(grads[it % n_grads])
                 if stamps is not None:
                     stamps.append(time.perf_counter())
+            self.index_submitted_in_run = n
         self.done += n
 
     def timed(self, n):
@@ -286,9 +304,15 @@ class Measurement:
         n_prime = 0 if args.no_prime else prime_batches(step, self.pipelined,
                                                         cfg.snapshot_every)
         self.run(n_prime)
-        self.run(warmup)
+        # A full collection before the warm-up batches, none between them and the
+        # region: the collector walks every object of the process, and the first
+        # batch after it pays for the caches it has emptied (measured: 140-190 us of
+        # host time for that batch instead of 35-45).
         gc.collect()
+        gc.disable()
+        self.run(warmup)
         elapsed, gpu_ms, t1, stamps = self.timed(steps)
+        gc.enable()
         ms_per_step = 1e3 * elapsed / steps
         value = Bn * steps / elapsed
         per = np.diff(np.array([t1] + stamps)) * 1e6       # host time per batch, us
@@ -298,12 +322,20 @@ class Measurement:
             "argmax": int(per.argmax()), "median_us": float(np.median(per)),
             "host_enqueue_done_ms": 1e3 * (stamps[-1] - t1),
             "note": "host clock after each batch was enqueued (no synchronisation): "
-                    "what the calling thread spent per batch, not GPU time"}
+                    "what the calling thread spent per batch, not GPU time",
+            "index_batches_submitted": self.index_submitted_in_run,
+            "pipeline": ("started empty: the region holds the index work of its own batches "
+                         "and no other") if (not self.pipelined or self.args.start_empty) else
+                        ("running: the training stream is drained by the synchronisation before "
+                         "the region, the index work done ahead of it is kept; the region holds "
+                         "the lookup and update of its %d batches and the index work of the %d "
+                         "batches that lie %d further on" % (steps, self.index_submitted_in_run,
+                                                            self.submitted - self.done))}
         stale_rows = int(sum(int(torch.count_nonzero(b).item()) for b in step.bits))
         kept_frac = self.kept_fraction()
 
         # spread of the step time: further pieces, each timed on its own (each starts
-        # with an empty pipeline), outside the timed region
+        # from a synchronisation), outside the timed region
         piece = max(1, min(200, steps))
         spread = sorted(1e6 * self.timed(piece)[0] / piece for _ in range(pieces))
 
