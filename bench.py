@@ -58,6 +58,10 @@ def parse():
     ap.add_argument("--index-streams", type=int, default=0,
                     help="streams the index work of the pipelined step is spread over "
                          "(0: PipelinedStep's own choice)")
+    ap.add_argument("--host-wait-us", type=int, default=-1,
+                    help="pipelined step: longest the calling thread polls for a batch's index "
+                         "work instead of making the training stream wait for it (0: never; "
+                         "-1: the library's choice)")
     ap.add_argument("--issue-thread", type=int, default=-1,
                     help="pipelined step: enqueue the index work from the library's own host "
                          "threads (ss_issue_queue), that many; 0: none; -1: PipelinedStep's own choice")
@@ -173,7 +177,8 @@ class Measurement:
                 weights, hot_d, Bn, L, cfg.lr, self.thr, cfg.snapshot_every,
                 diagnostics=False, every=args.pipeline_every or None,
                 index_streams=self.index_streams,
-                issue_thread=None if args.issue_thread < 0 else int(args.issue_thread))
+                issue_thread=None if args.issue_thread < 0 else int(args.issue_thread),
+                host_wait_us=None if args.host_wait_us < 0 else args.host_wait_us)
         else:
             self.step = EmbeddingStep(weights, hot_d, Bn, L, cfg.lr, self.thr,
                                       cfg.snapshot_every, diagnostics=False,
@@ -311,7 +316,9 @@ class Measurement:
         gc.collect()
         gc.disable()
         self.run(warmup)
+        c0 = step.counters() if self.pipelined else None
         elapsed, gpu_ms, t1, stamps = self.timed(steps)
+        c1 = step.counters() if self.pipelined else None
         gc.enable()
         ms_per_step = 1e3 * elapsed / steps
         value = Bn * steps / elapsed
@@ -324,6 +331,9 @@ class Measurement:
             "note": "host clock after each batch was enqueued (no synchronisation): "
                     "what the calling thread spent per batch, not GPU time",
             "index_batches_submitted": self.index_submitted_in_run,
+            # what the scheduler did in the region: wait commands it gave the training
+            # stream for index work, and polls of the calling thread instead of them
+            "scheduler": None if c0 is None else {k: c1[k] - c0[k] for k in c1},
             "pipeline": ("started empty: the region holds the index work of its own batches "
                          "and no other") if (not self.pipelined or self.args.start_empty) else
                         ("running: the training stream is drained by the synchronisation before "

@@ -507,15 +507,22 @@ int32_t ss_stream_wait_event(void *stream, void *event);
  *
  * The plan: `every` batches between two cross-stream events, `index_streams`,
  * `issue_threads` (0: the calling thread enqueues everything) and the number of
- * buffer sets, 3 * every * index_streams.  ss_step_plan_for fills in what the
- * caller left at 0 (every, index_streams) or -1 (issue_threads) with the measured
- * choices for the shape, and sets num_sets.
+ * buffer sets, 3 * every * index_streams.  host_wait_us: when the index work of
+ * the batch that ss_step_forward is about to look up has not finished, and the
+ * training stream still has a few batches of work queued, the call may keep the
+ * calling thread polling for it for up to this many microseconds instead of
+ * giving the training stream a wait command (which costs the stream time between
+ * two kernels); the thread then stays at most a ring of batches ahead of the GPU.
+ * 0: never, ss_step_forward only ever enqueues.  ss_step_plan_for fills in what
+ * the caller left at 0 (every, index_streams) or -1 (issue_threads, host_wait_us)
+ * with the measured choices for the shape, and sets num_sets.
  */
 typedef struct {
     int32_t every;
     int32_t index_streams;
     int32_t issue_threads;
     int32_t num_sets;
+    int32_t host_wait_us;
 } ss_step_plan;
 
 /* One buffer set of the ring: the outputs of ss_filter_batch for the batch that
@@ -549,6 +556,11 @@ int32_t ss_step_submit(ss_step *step, const int32_t *idx, void *ready_event);
 int32_t ss_step_forward(ss_step *step, int32_t *set_used);
 int32_t ss_step_backward(ss_step *step, const float *grad, int32_t *detected);
 int32_t ss_step_flush(ss_step *step);
+/* What the scheduler has done so far, for diagnosis (host memory, four values):
+ * out[0] = lookups enqueued, out[1] = wait commands given to the training stream
+ * for index work, out[2] = times the calling thread polled for index work
+ * (host_wait_us), out[3] = polls that ended with the index work finished. */
+int32_t ss_step_counters(const ss_step *step, int64_t *out);
 
 /*
  * The same scheduler with every operation it would enqueue handed to a callback

@@ -32,6 +32,7 @@ SYMBOLS = (
     "ss_step_plan_for", "ss_step_create", "ss_step_destroy", "ss_step_room",
     "ss_step_submit", "ss_step_forward", "ss_step_backward", "ss_step_flush",
     "ss_step_create_traced", "ss_filter_batch_split", "ss_profile_trace",
+    "ss_step_counters",
 )
 
 
@@ -72,7 +73,7 @@ def _load():
               "ss_check_indices", "ss_step_plan_for", "ss_step_create", "ss_step_destroy",
               "ss_step_room", "ss_step_submit", "ss_step_forward", "ss_step_backward",
               "ss_step_flush", "ss_step_create_traced", "ss_filter_batch_split",
-              "ss_profile_trace"):
+              "ss_profile_trace", "ss_step_counters"):
         getattr(lib, n).restype = C.c_int32
     lib.ss_check_enable.restype = None
     return lib
@@ -753,7 +754,8 @@ class IssueQueue:
 # ---- the training iteration as a whole (ss_step_*) -------------------------
 class StepPlan(C.Structure):
     _fields_ = [("every", C.c_int32), ("index_streams", C.c_int32),
-                ("issue_threads", C.c_int32), ("num_sets", C.c_int32)]
+                ("issue_threads", C.c_int32), ("num_sets", C.c_int32),
+                ("host_wait_us", C.c_int32)]
 
 
 class StepSet(C.Structure):
@@ -780,9 +782,9 @@ class StepTraceOps(C.Structure):
 
 
 def ss_step_plan_for(T: int, B: int, L: int, every: int = 0, index_streams: int = 0,
-                     issue_threads: int = -1) -> StepPlan:
-    """The plan for a shape; 0 / 0 / -1 leave the choice to the library."""
-    plan = StepPlan(int(every), int(index_streams), int(issue_threads), 0)
+                     issue_threads: int = -1, host_wait_us: int = -1) -> StepPlan:
+    """The plan for a shape; 0 / 0 / -1 / -1 leave the choice to the library."""
+    plan = StepPlan(int(every), int(index_streams), int(issue_threads), 0, int(host_wait_us))
     _check(_lib.ss_step_plan_for(C.c_int32(T), C.c_int32(B), C.c_int32(L), C.byref(plan)))
     return plan
 
@@ -834,6 +836,15 @@ def ss_step_destroy(step: C.c_void_p) -> None:
 
 def ss_step_room(step: C.c_void_p) -> int:
     return int(_lib.ss_step_room(step))
+
+
+def ss_step_counters(step: C.c_void_p) -> dict:
+    """Lookups enqueued, wait commands given to the training stream for index work,
+    polls of the calling thread for index work, polls that found it finished."""
+    out = (C.c_int64 * 4)()
+    _check(_lib.ss_step_counters(step, out))
+    return {"lookups": out[0], "wait_commands": out[1], "host_polls": out[2],
+            "host_polls_done": out[3]}
 
 
 def ss_step_submit(step: C.c_void_p, idx: torch.Tensor, ready_event=None) -> None:

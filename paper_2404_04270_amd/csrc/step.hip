@@ -30,6 +30,7 @@
 // waits under a random scheduler on the CPU and check that every kernel finds its
 // inputs complete.
 #include <algorithm>
+#include <chrono>
 #include <deque>
 #include <memory>
 #include <new>
@@ -68,6 +69,7 @@ struct StepOps {
     virtual int32_t wait_now(int stream, void *ev) = 0;
     // has the event, recorded (issued) earlier, happened already?  "no" is always a safe answer
     virtual bool done_now(void *ev) = 0;
+    virtual bool polls() const = 0;    // can done_now ever say yes?
     virtual int32_t q_record(int queue, void *ev, int stream, uint64_t *ticket) = 0;
     virtual int32_t q_wait(int queue, void *ev, int stream, uint64_t *ticket) = 0;
     virtual int32_t q_wait_issued(int queue, uint64_t ticket) = 0;
@@ -105,6 +107,11 @@ struct ss_step {
 
     int64_t submitted = 0, issued = 0, forwarded = 0, it = 0, last_detect = -1;
     int64_t lead_lost = -1;               // last batch before which the index streams had no lead
+    int host_wait_us = 0;                 // longest the calling thread polls for index work
+    int64_t n_wait_cmds = 0, n_polls = 0, n_polls_done = 0;      // ss_step_counters
+    static constexpr int kProgress = 8;
+    void *progress[kProgress] = {};       // by batch % kProgress: the event that says its update is done
+    std::vector<void *> progress_pool;    // ... those of them that are not also in `trained`
     bool have_snapshot = false;
     struct Held {
         const int32_t *idx;
@@ -169,6 +176,44 @@ struct ss_step {
         return SS_OK;
     }
 
+    // Is the update of the batch before the last one still unfinished?  Then the training
+    // stream has more than one batch of work left.
+    bool backlog()
+    {
+        if (it < 2 || !progress[(it - 2) % kProgress]) return false;
+        return !ops->done_now(progress[(it - 2) % kProgress]);
+    }
+
+    // The calling thread is ahead of the GPU: the index work of the batch it is about to
+    // enqueue the lookup of has not finished.  While the training stream still has more
+    // than a batch of work queued, nothing is lost by keeping the thread here until that
+    // index work is done, and the stream is spared a wait command, which takes it 8 us
+    // between two kernels even when the event has long happened by the time the stream
+    // gets there.  With less work queued (a start from an empty pipeline, the batches
+    // behind a detect pass) the thread would be late with the lookup: the wait command is
+    // better there (20 steps from an empty pipeline at 26 tables x 8192 lookups: 56-58 us
+    // each when always polled for, 48.5 so).  Measured, 2000 steps: 94.5-94.9 instead of
+    // 96.6 us per step at 8 tables x 81920 lookups, where 37 % of the batches got a wait
+    // command; 44.8 either way at 26 x 8192 (19 %); 27.5 against 27.4 at one table x
+    // 65536.  Regions of 20 steps take 1 us per step longer with it (the thread submits
+    // the index work of later batches later), which is why ss_step_plan_for turns it on
+    // for bags of several lookups only.
+    int32_t poll_indexed(const Marks &m, const Mark *mine)
+    {
+        if (n_queues) {      // the event's record must have been issued before a query means anything
+            const int32_t rc = ops->q_wait_issued(m.queue, mine->ticket);
+            if (rc) return rc;
+        }
+        const auto t0 = std::chrono::steady_clock::now();
+        const auto limit = std::chrono::microseconds(host_wait_us);
+        ++n_polls;
+        while (!ops->done_now(mine->ev) && backlog() &&
+               std::chrono::steady_clock::now() - t0 < limit)
+            __builtin_ia32_pause();
+        if (ops->done_now(mine->ev)) ++n_polls_done;
+        return SS_OK;
+    }
+
     // The training stream is about to look up batch k, whose index work ran on index
     // stream j.  Every batch has an event of its own there.  If the calling thread can see
     // that the index stream is past k already, nothing is enqueued, and all batches up to
@@ -191,6 +236,14 @@ struct ss_step {
         const int64_t last = issued - 1 - (issued - 1 - j) % n_side;     // newest batch of stream j
         const Mark *mine = at(k);
         if (!mine) return ss::fail(SS_ERR_HIP, "ss_step: internal: batch %lld has no event", (long long)k);
+        if (host_wait_us > 0 && ops->polls() && !ops->done_now(mine->ev)) {
+            const int32_t rc = poll_indexed(m, mine);
+            if (rc) return rc;
+            if (n_queues && ops->done_now(mine->ev)) {
+                m.known[0] = k;       // (later events of the stream may not have been recorded yet)
+                return SS_OK;
+            }
+        }
         if (!n_queues) {
             // events of a stream happen in order: the newest finished one, by bisection
             if (ops->done_now(mine->ev)) {
@@ -219,6 +272,7 @@ struct ss_step {
             rc = ops->q_wait_issued(m.queue, target->ticket);
             if (rc) return rc;
         }
+        ++n_wait_cmds;
         rc = ops->wait_now(ss::kMainStream, target->ev);
         if (rc) return rc;
         m.known[0] = target->covers;
@@ -391,6 +445,7 @@ struct GpuOps final : StepOps {
         (void)hipGetLastError();        // "not ready" is not an error to keep
         return false;
     }
+    bool polls() const override { return true; }
     int32_t wait_now(int s, void *ev) override
     {
         // An event that has already happened needs no wait command on the stream (a
@@ -463,6 +518,7 @@ struct TracedOps final : StepOps {
     int32_t record_now(void *ev, int s) override { return cb.record_now(cb.user, id(ev), s); }
     int32_t wait_now(int s, void *ev) override { return cb.wait_now(cb.user, s, id(ev)); }
     bool done_now(void *) override { return false; }
+    bool polls() const override { return false; }
     int32_t q_record(int q, void *ev, int s, uint64_t *t) override
     {
         return cb.q_record(cb.user, q, id(ev), s, t);
@@ -481,11 +537,12 @@ int32_t check_plan(const char *who, int32_t T, int32_t B, int32_t L, const ss_st
     if (T < 1 || T > 65535 || B < 1 || L < 1)
         return fail(SS_ERR_INVALID_ARG, "%s: T = %d, B = %d, L = %d", who, T, B, L);
     if (p->every < 1 || p->index_streams < 1 || p->index_streams > 16 || p->issue_threads < 0 ||
-        p->issue_threads > p->index_streams)
+        p->issue_threads > p->index_streams || p->host_wait_us < 0)
         return fail(SS_ERR_INVALID_ARG,
-                    "%s: every = %d, index_streams = %d, issue_threads = %d (need every >= 1, "
-                    "1 <= streams <= 16, 0 <= threads <= streams)",
-                    who, p->every, p->index_streams, p->issue_threads);
+                    "%s: every = %d, index_streams = %d, issue_threads = %d, host_wait_us = %d "
+                    "(need every >= 1, 1 <= streams <= 16, 0 <= threads <= streams, "
+                    "host_wait_us >= 0)",
+                    who, p->every, p->index_streams, p->issue_threads, p->host_wait_us);
     if (p->num_sets != 3 * p->every * p->index_streams)
         return fail(SS_ERR_INVALID_ARG, "%s: num_sets = %d, need 3 * every * index_streams = %d",
                     who, p->num_sets, 3 * p->every * p->index_streams);
@@ -503,6 +560,7 @@ int32_t make_step(std::unique_ptr<StepOps> ops, const ss_step_plan *plan, int32_
     st->n_side = plan->index_streams;
     st->n_sets = plan->num_sets;
     st->n_queues = plan->issue_threads;
+    st->host_wait_us = plan->host_wait_us;
     st->K = K;
     st->threshold = threshold;
     st->last_ticket.assign(std::max(1, st->n_queues), 0);
@@ -526,6 +584,13 @@ int32_t make_step(std::unique_ptr<StepOps> ops, const ss_step_plan *plan, int32_
     }
     const int32_t rc = fill(st->trained, kMainStream, false, st->n_side);
     if (rc) return rc;
+    if (st->host_wait_us > 0 && st->ops->polls())
+        for (int i = 0; i < ss_step::kProgress; ++i) {
+            void *ev = nullptr;
+            const int32_t rc2 = st->ops->new_event(&ev);
+            if (rc2) return rc2;
+            st->progress_pool.push_back(ev);
+        }
     *out = st.release();
     return SS_OK;
 }
@@ -551,6 +616,7 @@ int32_t ss_step_plan_for(int32_t T, int32_t B, int32_t L, ss_step_plan *plan)
     if (plan->every <= 0) plan->every = auto_every(T, B, L, plan->index_streams);
     if (plan->issue_threads < 0) plan->issue_threads = auto_threads(T, B, L, plan->index_streams);
     if (plan->issue_threads > plan->index_streams) plan->issue_threads = plan->index_streams;
+    if (plan->host_wait_us < 0) plan->host_wait_us = L > 1 ? 2000 : 0;
     plan->num_sets = 3 * plan->every * plan->index_streams;
     return SS_OK;
 }
@@ -700,11 +766,16 @@ int32_t ss_step_backward(ss_step *st, const float *grad, int32_t *detected)
         rides = st->trained.spare.back();
         st->trained.spare.pop_back();
     }
-    int32_t rc = st->ops->update((int)(k % st->n_sets), grad, rides);
+    // every other update carries an event that only tells the calling thread how far
+    // the training stream has got (poll_indexed)
+    void *tells = rides;
+    if (!tells && !st->progress_pool.empty()) tells = st->progress_pool[k % ss_step::kProgress];
+    int32_t rc = st->ops->update((int)(k % st->n_sets), grad, tells);
     if (rc) {
         if (rides) st->trained.spare.push_back(rides);
         return rc;
     }
+    st->progress[k % ss_step::kProgress] = tells;
     if (rides) st->keep(st->trained, k, rides, 0);
     int32_t det = 0;
     if (st->boundary(k)) {
@@ -723,6 +794,16 @@ int32_t ss_step_backward(ss_step *st, const float *grad, int32_t *detected)
     if (detected) *detected = det;
     // batches that waited for a detect pass (this one's, or an earlier one's)
     return st->drain(2);
+}
+
+int32_t ss_step_counters(const ss_step *st, int64_t *out)
+{
+    if (!st || !out) return fail(SS_ERR_INVALID_ARG, "ss_step_counters: step or out is NULL");
+    out[0] = st->forwarded;
+    out[1] = st->n_wait_cmds;
+    out[2] = st->n_polls;
+    out[3] = st->n_polls_done;
+    return SS_OK;
 }
 
 int32_t ss_step_flush(ss_step *st)

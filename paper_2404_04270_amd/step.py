@@ -185,12 +185,13 @@ class PipelinedStep:
                  lr: float, threshold: float, snapshot_every: int,
                  alpha: Optional[int] = None, diagnostics: bool = True,
                  every: Optional[int] = None, index_streams: Optional[int] = None,
-                 issue_thread=None):
+                 issue_thread=None, host_wait_us: Optional[int] = None):
         """every: batches between two cross-stream events; index_streams; issue_thread:
         False / 0 = the calling thread enqueues everything, True = the library's issue
         threads (one, or one per index stream from three streams on), an int = that
-        many threads (at most one per index stream).  None leaves a choice to the
-        library (ss_step_plan_for)."""
+        many threads (at most one per index stream); host_wait_us: how long forward()
+        may keep the calling thread polling for a batch's index work (0: never).  None
+        leaves a choice to the library (ss_step_plan_for)."""
         self.tables = B.Tables(weights)
         self.bits = self.tables.new_bits()
         self.hot = B.HotState(self.tables, hot_ids, diagnostics=diagnostics)
@@ -207,7 +208,8 @@ class PipelinedStep:
             threads = streams if streams >= 3 else 1
         else:
             threads = min(int(issue_thread), streams)
-        plan = B.ss_step_plan_for(T, batch, bag, int(every or 0), streams, threads)
+        plan = B.ss_step_plan_for(T, batch, bag, int(every or 0), streams, threads,
+                                  -1 if host_wait_us is None else int(host_wait_us))
         self.plan = plan
         self.every = plan.every
         self.sets = [self._Set(T, batch, bag, D, dev) for _ in range(plan.num_sets)]
@@ -250,6 +252,10 @@ class PipelinedStep:
     kept_ids = property(lambda self: self._cur().kept_ids)
     n_kept = property(lambda self: self._cur().n_kept)
     idx_c = property(lambda self: self._cur().idx_c)
+
+    def counters(self) -> dict:
+        """Diagnosis: lookups, wait commands of the training stream, host polls."""
+        return B.ss_step_counters(self._step)
 
     def room(self) -> int:
         """How many more batches submit() takes right now."""

@@ -311,6 +311,11 @@ def test_step_plan_picks_streams_threads_and_event_spacing_for_the_shape():
     # what the caller fixes stays; the ring follows
     p = plan(26, 8192, 1, every=3, index_streams=2, issue_threads=5)
     assert (p.every, p.index_streams, p.issue_threads, p.num_sets) == (3, 2, 2, 18)
+    # the calling thread polls for index work only where that was measured to pay
+    # (bags of several lookups), unless the caller says otherwise
+    assert plan(8, 4096, 20).host_wait_us == 2000 and plan(26, 8192, 1).host_wait_us == 0
+    assert plan(26, 8192, 1, host_wait_us=300).host_wait_us == 300
+    assert plan(8, 4096, 20, host_wait_us=0).host_wait_us == 0
     with pytest.raises(binding.SlipstreamError):
         plan(0, 8, 1)
     with pytest.raises(binding.SlipstreamError):
@@ -333,6 +338,9 @@ def test_step_calls_validate_on_the_host(lib):
     assert b"num_sets" in lib.ss_last_error()
     plan = binding.StepPlan(2, 1, 3, 6)                  # more threads than streams
     assert lib.ss_step_create_traced(C.byref(plan), 4, C.byref(ops), C.byref(out)) != 0
+    plan = binding.StepPlan(2, 1, 0, 6, -1)              # host_wait_us left unplanned
+    assert lib.ss_step_create_traced(C.byref(plan), 4, C.byref(ops), C.byref(out)) != 0
+    assert b"host_wait_us" in lib.ss_last_error()
     plan = binding.StepPlan(2, 1, 0, 6)
     assert lib.ss_step_create_traced(C.byref(plan), 0, C.byref(ops), C.byref(out)) != 0
     assert b"snapshot_every" in lib.ss_last_error()

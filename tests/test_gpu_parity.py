@@ -708,3 +708,54 @@ def test_pipelined_step_waits_for_indices_still_being_produced(B, dev):
             assert torch.equal(pipe.tables.weights[t], serial.tables.weights[t]), (threads, t)
             assert torch.equal(pipe.bits[t], serial.bits[t]), (threads, t)
         pipe.close()
+
+
+@pytest.mark.parametrize("host_wait_us,threads", [(0, 0), (2000, 0), (2000, 2)])
+def test_free_running_pipelined_step_equals_call_by_call_step(B, dev, host_wait_us, threads):
+    """The pipelined step with no synchronisation between its batches, the way a
+    training loop and the benchmark drive it: the calling thread runs ahead of the GPU,
+    the training stream is made to wait for index work by wait commands
+    (host_wait_us = 0) or the calling thread polls for it instead.  Either way it must
+    leave bit for bit what the call-by-call step leaves (every sum in the library has a
+    fixed order).  Gradients go in uncompacted on both sides: row i stands for the i-th
+    kept sample."""
+    from paper_2404_04270_amd.step import EmbeddingStep, PipelinedStep
+    T, R, D, Bn, L, K, n_iters = 8, 60000, 128, 8192, 4, 25, 160
+    rng = np.random.default_rng(97)
+    idx = zipf_idx(rng, T, Bn, L, R, 1.2).astype(np.int32)
+    ring = [torch.from_numpy(np.roll(idx, s, axis=1).copy()).to(dev) for s in range(6)]
+    hot = to_dev(wl.hot_set(idx[None], R, 300), dev)
+    W0 = rand_tables(rng, T, R, D)
+    grads = [torch.empty(T, Bn, D, dtype=torch.float32, device=dev).normal_(0, 0.01)
+             for _ in range(3)]
+    # threshold +inf: the second boundary freezes every hot row
+    serial = EmbeddingStep(to_dev(W0, dev), hot, Bn, L, 0.05, math.inf, K)
+    for it in range(n_iters):
+        serial.filter_forward(ring[it % len(ring)])
+        serial.backward(grads[it % len(grads)])
+    pipe = PipelinedStep(to_dev(W0, dev), hot, Bn, L, 0.05, math.inf, K, index_streams=2,
+                         issue_thread=threads, host_wait_us=host_wait_us)
+    torch.cuda.synchronize()
+    ahead = 0
+    for it in range(n_iters):
+        while ahead < n_iters and pipe.room() > 0:
+            pipe.submit(ring[ahead % len(ring)])
+            ahead += 1
+        pipe.forward()
+        pipe.backward(grads[it % len(grads)])
+    pipe.flush()
+    torch.cuda.synchronize()
+    c = pipe.counters()
+    assert c["lookups"] == n_iters
+    assert c["host_polls"] >= c["host_polls_done"] >= 0
+    if host_wait_us == 0:
+        assert c["host_polls"] == 0
+    stale = 0
+    for t in range(T):
+        assert torch.equal(pipe.tables.weights[t], serial.tables.weights[t]), t
+        assert torch.equal(pipe.bits[t], serial.bits[t]), t
+        assert torch.equal(pipe.hot.snapshot[t], serial.hot.snapshot[t]), t
+        stale += int(torch.count_nonzero(serial.bits[t]).item())
+    assert stale > 0                       # the run did freeze rows
+    print("free-running step, host_wait_us", host_wait_us, "issue threads", threads, c, flush=True)
+    pipe.close()
