@@ -353,6 +353,18 @@ class Measurement:
         # inside): what the calling thread needs to enqueue a batch
         host_us = float(np.median(np.diff(np.array(self.timed(piece)[3])))) * 1e6
 
+        # The same number of steps from an empty pipeline: the batches submitted ahead
+        # are trained on without submitting more, then a region submits its own index
+        # work and no other (what --start-empty times in the main region).
+        from_empty = None
+        if self.pipelined and not self.args.start_empty:
+            self.args.start_empty = True
+            self.run(self.submitted - self.done)
+            e_elapsed = self.timed(steps)[0]
+            self.args.start_empty = False
+            from_empty = {"steps": steps, "ms_per_step": 1e3 * e_elapsed / steps,
+                          "value": Bn * steps / e_elapsed}
+
         # per-kernel durations: the same steps again, each launch bracketed by events
         n_prof = max(steps, 200)
         B.ss_profile_enable(True)
@@ -425,6 +437,7 @@ class Measurement:
             "step_us_spread": {"pieces": pieces, "steps_per_piece": piece, "median": med,
                                "min": spread[0], "max": spread[-1]},
             "host_us_per_batch": host_us,
+            "from_empty_pipeline": from_empty,
             "kernels": kern, "setup_s": self.setup_s,
         }
 
