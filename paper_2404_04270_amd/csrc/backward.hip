@@ -56,6 +56,10 @@ constexpr int kRsItems = 4;            // steps per thread is what it waits for:
                                        // against 12.4 us with 256 x 8 at one table x 65536)
 constexpr int kRsMaxBits = 10;         // ... widest digit
 constexpr int kRsMaxDig = 1 << kRsMaxBits;
+constexpr int kBucketThreads = 256;    // bucket sort: a workgroup no larger than those of the
+constexpr int kBucketItems = 16;       // training kernels it runs beside; keys per thread
+constexpr int kBucketCap = kBucketThreads * kBucketItems;
+constexpr int kBsStride = kRsMaxDig + 4;   // per table: where each bucket starts
 constexpr int kApplyWG = 256;           // apply stage: threads per workgroup (512 and
                                         // 1024 were measured slower: 22 and 38 us vs 18)
 
@@ -81,6 +85,13 @@ __global__ __launch_bounds__(1024) void class_sort_kernel(
 // What the histogram kernel reads at position `pos` of a table: in the first pass
 // the index tensor itself (the sample number is the position divided by the bag
 // length), afterwards the row id of the pair the previous pass left there.
+// Digit of a key in one pass.  sent (0 or 1, first pass only): the sentinel key gets a
+// digit of its own behind all others, so that every other bucket holds real rows only.
+__device__ __forceinline__ uint32_t rs_digit(uint32_t key, int shift, uint32_t dmask, int sent)
+{
+    return sent && key == kNoRow ? dmask + 1u : (key >> shift) & dmask;
+}
+
 template <bool FIRST>
 __device__ __forceinline__ void rs_load(const int32_t *__restrict__ ip, int L, int n,
                                         const uint2 *__restrict__ in_ent, int pos,
@@ -100,14 +111,14 @@ __global__ __launch_bounds__(kRsHistThreads) void rs_hist_kernel(
     const int32_t *__restrict__ idx, int Bcap, int L,
     const int32_t *__restrict__ n_valid, const uint32_t *const *__restrict__ bits,
     const uint2 *__restrict__ in_ent, uint2 *__restrict__ first_ent, int NP, int shift,
-    int nb, uint32_t *__restrict__ hist, int tiles, TS ts)
+    int nb, int sent, uint32_t *__restrict__ hist, int tiles, TS ts)
 {
     __shared__ uint32_t s_hist[kRsMaxDig];
     const unsigned long long trace_t0 = trace_begin<TS>();
     const int t = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
     const int n = clamp_valid(n_valid, Bcap) * L;
-    const int ndig = 1 << nb;
-    const uint32_t dmask = ndig - 1;
+    const int ndig = (1 << nb) + sent;
+    const uint32_t dmask = (1u << nb) - 1;
     const int32_t *__restrict__ ip = idx + (int64_t)t * Bcap * L;
     const auto bt = as_global((FIRST && bits) ? bits[t] : nullptr);
     const uint2 *__restrict__ ein = FIRST ? nullptr : in_ent + (int64_t)t * NP;
@@ -128,7 +139,8 @@ __global__ __launch_bounds__(kRsHistThreads) void rs_hist_kernel(
             eo[tile * kPad + r * kRsHistThreads + tid] = make_uint2(key[r], val[r]);
     }
 #pragma unroll
-    for (int r = 0; r < kRsHistItems; ++r) atomicAdd(&s_hist[(key[r] >> shift) & dmask], 1u);
+    for (int r = 0; r < kRsHistItems; ++r)
+        atomicAdd(&s_hist[rs_digit(key[r], shift, dmask, sent)], 1u);
     __syncthreads();
     for (int i = tid; i < ndig; i += kRsHistThreads)
         hist[((int64_t)t * tiles + tile) * kRsMaxDig + i] = s_hist[i];
@@ -141,7 +153,8 @@ __global__ __launch_bounds__(kRsHistThreads) void rs_hist_kernel(
 template <typename TS>
 __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
     const uint2 *__restrict__ in_ent, uint2 *__restrict__ out_ent, int NP, int shift,
-    int nb, const uint32_t *__restrict__ hist, int tiles, TS ts)
+    int nb, int sent, uint32_t *__restrict__ bucket_out, const uint32_t *__restrict__ hist,
+    int tiles, TS ts)
 {
     constexpr int NW = kRsThreads / 64;
     const unsigned long long trace_t0 = trace_begin<TS>();
@@ -150,8 +163,9 @@ __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
     __shared__ uint32_t s_wsum[NW];
     const int t = blockIdx.y, tile = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int ndig = 1 << nb;
-    const uint32_t dmask = ndig - 1;
+    const int ndig = (1 << nb) + sent;
+    const int nbits = nb + sent;                 // bits that tell the digits apart
+    const uint32_t dmask = (1u << nb) - 1;
     const uint2 *__restrict__ ein = in_ent + (int64_t)t * NP;
 
     uint32_t key[kRsItems], val[kRsItems], rank[kRsItems];
@@ -233,10 +247,16 @@ __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
 
 #pragma unroll
     for (int r = 0; r < kRsItems; ++r) {
-        const uint32_t d = (key[r] >> shift) & dmask;
-        rank[r] = wave_rank(s_cnt + wave * ndig, d, nb, lane);
+        const uint32_t d = rs_digit(key[r], shift, dmask, sent);
+        rank[r] = wave_rank(s_cnt + wave * ndig, d, nbits, lane);
     }
     __syncthreads();
+    if (bucket_out && tile == 0) {
+        // The pass ahead of a bucket sort: where each bucket starts (for tile 0 the
+        // digit offsets are just that; the last digit is the sentinels').
+        uint32_t *__restrict__ bo = bucket_out + t * kBsStride;
+        for (int d = tid; d < ndig; d += kRsThreads) bo[d] = s_base[d];
+    }
     for (int d = tid; d < ndig; d += kRsThreads) {
         uint32_t acc = s_base[d];
         for (int w = 0; w < NW; ++w) {
@@ -248,9 +268,282 @@ __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < kRsItems; ++r) {
-        const uint32_t d = (key[r] >> shift) & dmask;
+        const uint32_t d = rs_digit(key[r], shift, dmask, sent);
         const int64_t p = (int64_t)t * NP + s_cnt[wave * ndig + d] + rank[r];
         out_ent[p] = make_uint2(key[r], val[r]);      // one 8-byte store, not two of 4
+    }
+    trace_end(ts, trace_t0);
+}
+
+// Stage 1c: after one global pass on the low nb0 bits a table lies in 2^nb0 buckets
+// (plus the sentinels behind them).  The apply stage needs equal rows adjacent, not
+// ascending, so all that is left to do is to sort every bucket by the remaining bits,
+// in place, and a bucket fits the LDS of a workgroup: one launch instead of two or three
+// more global passes of two launches each.  The workgroups are as small as those of the
+// training kernels this runs beside (a workgroup that needs a whole compute unit waits
+// there until those have all but left it).  Remaining row bits and sample number are
+// packed into one word where they fit one, as in the class sort.
+// A bucket of more than kBucketCap lookups nearly always owes its size to one row (the
+// hottest row of a Zipf table holds a fifth of all lookups): that row is found by a
+// vote among 64 samples and its lookups are moved to the end of the bucket while the
+// others are collected in LDS and sorted.  The bucket is read from its end, so that the
+// heavy row's lookups land on places that have been read already.  Others that LDS has
+// no room for are parked in the spare buffer; with those the workgroup falls back on
+// an LSD sort of its own through global memory (slow, and rare: it takes several rows
+// of thousands of lookups each with the same low bits).
+
+// n pairs from `from` to `to` (which do not overlap), by all NT threads, eight loads
+// in flight per thread.
+template <int NT>
+__device__ __forceinline__ void copy_pairs(const uint2 *__restrict__ from,
+                                           uint2 *__restrict__ to, uint32_t n, int tid)
+{
+    for (uint32_t i0 = 0; i0 < n; i0 += NT * 8) {
+        uint2 e[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const uint32_t i = i0 + u * NT + tid;
+            e[u] = from[i < n ? i : n - 1];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const uint32_t i = i0 + u * NT + tid;
+            if (i < n) to[i] = e[u];
+        }
+    }
+}
+
+// LSD sort of the n pairs at a (global memory) by key bits [shift, shift + bits), by one
+// workgroup of NT threads; b is scratch of the same size; the result is left in a.
+// s_cnt: NW * 64 words, s_run: 64 words.  1024 pairs at a time.
+template <int NT>
+__device__ __forceinline__ void wg_lsd_global(uint2 *a, uint2 *b, uint32_t n, int shift,
+                                              int bits, uint32_t *s_cnt, uint32_t *s_run)
+{
+    constexpr int NW = NT / 64, V = 1024 / NT;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int npass = (bits + 5) / 6;
+    uint2 *cur = a, *oth = b;
+    for (int pass = 0; pass < npass; ++pass) {
+        const int nb = pass_bits(bits, npass, pass);
+        const uint32_t dmask = (1u << nb) - 1u;
+        // digit totals, then where each digit starts
+        if (tid < 64) s_run[tid] = 0;
+        __syncthreads();
+        for (uint32_t i = tid; i < n; i += NT) atomicAdd(&s_run[(cur[i].x >> shift) & dmask], 1u);
+        __syncthreads();
+        if (wave == 0) {
+            const uint32_t c = s_run[lane];
+            uint32_t incl = c;
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t up = __shfl_up(incl, off);
+                if (lane >= off) incl += up;
+            }
+            s_run[lane] = incl - c;
+        }
+        __syncthreads();
+        for (uint32_t c0 = 0; c0 < n; c0 += NT * V) {
+            for (int i = tid; i < NW * 64; i += NT) s_cnt[i] = 0;
+            __syncthreads();
+            uint2 e[V];
+            uint32_t rank[V];
+#pragma unroll
+            for (int u = 0; u < V; ++u) {
+                const uint32_t pos = c0 + wave * (64 * V) + u * 64 + lane;
+                e[u] = cur[pos < n ? pos : n - 1];
+            }
+#pragma unroll
+            for (int u = 0; u < V; ++u) {
+                const uint32_t pos = c0 + wave * (64 * V) + u * 64 + lane;
+                const bool valid = pos < n;
+                const uint32_t d = (e[u].x >> shift) & dmask;
+                const uint64_t mm = match_digit(d, nb) & __ballot(valid);
+                const uint32_t before = __popcll(mm & lanes_below(lane));
+                uint32_t base = 0;
+                if (valid && before == 0) base = atomicAdd(&s_cnt[wave * 64 + d], (uint32_t)__popcll(mm));
+                base = __shfl(base, mm ? __ffsll((long long)mm) - 1 : 0);
+                rank[u] = base + before;
+            }
+            __syncthreads();
+            if (wave == 0) {
+                uint32_t acc = s_run[lane];
+                for (int w = 0; w < NW; ++w) {
+                    const uint32_t c = s_cnt[w * 64 + lane];
+                    s_cnt[w * 64 + lane] = acc;
+                    acc += c;
+                }
+                s_run[lane] = acc;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < V; ++u) {
+                const uint32_t pos = c0 + wave * (64 * V) + u * 64 + lane;
+                if (pos < n) {
+                    const uint32_t d = (e[u].x >> shift) & dmask;
+                    const uint32_t p = s_cnt[wave * 64 + d] + rank[u];
+                    if (p < n) oth[p] = e[u];
+                }
+            }
+            __syncthreads();
+        }
+        // what this workgroup wrote is read by all of it in the next pass
+        __threadfence_block();
+        __syncthreads();
+        uint2 *x = cur;
+        cur = oth;
+        oth = x;
+        shift += nb;
+    }
+    if (cur != a) {
+        copy_pairs<NT>(cur, a, n, tid);
+        __threadfence_block();
+        __syncthreads();
+    }
+}
+
+template <bool PACKED, typename TS>
+__global__ __launch_bounds__(kBucketThreads) void bucket_sort_kernel(
+    uint2 *ent, uint2 *spare, int NP, const uint32_t *__restrict__ bucket, int nb0,
+    int rem_bits, int val_bits, TS ts)
+{
+    constexpr int NT = kBucketThreads, NW = NT / 64, CAP = kBucketCap, U = 8, V = 16;
+    __shared__ uint32_t s_keys[CAP];
+    __shared__ uint32_t s_vals[PACKED ? 1 : CAP];
+    __shared__ uint32_t s_cnt[2 * NW * 64];
+    __shared__ uint32_t s_dig[64];
+    __shared__ uint32_t s_w[2][NW];      // per wavefront: the heavy row's / other lookups of a chunk
+    __shared__ uint32_t s_heavy;
+    const unsigned long long trace_t0 = trace_begin<TS>();
+    const int d = blockIdx.x, t = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t *__restrict__ bo = bucket + t * kBsStride;
+    const uint32_t b0 = bo[d], b1 = bo[d + 1];
+    if (b0 >= b1 || b1 > (uint32_t)NP) {         // empty (b0 > b1, b1 > NP: cannot happen)
+        trace_end(ts, trace_t0);
+        return;
+    }
+    const uint32_t m = b1 - b0;
+    uint2 *io = ent + (int64_t)t * NP + b0;
+    // in LDS: (row bits above the bucket's, sample) in one word, or the pair as it is
+    const uint32_t vmask = PACKED ? (1u << val_bits) - 1u : 0u;
+    const int lds_shift = PACKED ? val_bits : nb0;
+    const auto put = [&](uint32_t i, uint2 e) {
+        if (PACKED) {
+            s_keys[i] = ((e.x >> nb0) << val_bits) | e.y;
+        } else {
+            s_keys[i] = e.x;
+            s_vals[i] = e.y;
+        }
+    };
+    const auto get = [&](uint32_t i) {
+        const uint32_t w = s_keys[i];
+        return PACKED ? make_uint2(((w >> val_bits) << nb0) | (uint32_t)d, w & vmask)
+                      : make_uint2(w, s_vals[i]);
+    };
+
+    if (m <= (uint32_t)CAP) {
+        for (uint32_t i0 = 0; i0 < m; i0 += NT * U) {
+            uint2 e[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t i = i0 + u * NT + tid;
+                e[u] = io[i < m ? i : m - 1];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t i = i0 + u * NT + tid;
+                if (i < m) put(i, e[u]);
+            }
+        }
+        __syncthreads();
+        lds_lsd_sort<NT, kBucketItems, PACKED>(s_keys, s_vals, s_cnt, s_dig, m, rem_bits,
+                                               lds_shift);
+        for (uint32_t i = tid; i < m; i += NT) io[i] = get(i);
+        trace_end(ts, trace_t0);
+        return;
+    }
+
+    // the row most of 64 evenly spaced lookups hit (the lowest lane among equals)
+    if (wave == 0) {
+        const uint32_t mine = io[(uint32_t)(((uint64_t)lane * m) >> 6)].x;
+        uint32_t votes = 0;
+        for (int i = 0; i < 64; ++i) votes += __shfl(mine, i) == mine ? 1u : 0u;
+        uint32_t best = (votes << 6) | (uint32_t)(63 - lane);
+        for (int off = 32; off; off >>= 1) {
+            const uint32_t o = __shfl_xor(best, off);
+            best = o > best ? o : best;
+        }
+        const uint32_t heavy = __shfl(mine, 63 - (int)(best & 63u));
+        if (lane == 0) s_heavy = heavy;
+    }
+    __syncthreads();
+    const uint32_t heavy = s_heavy;
+    // The split, 4096 lookups at a time, from the end of the bucket to its start: by the
+    // time n_eq lookups of the heavy row have been found, at least n_eq places at the end
+    // have been read.  Others: the first CAP into LDS (packed), the rest into the spare buffer.
+    uint2 *park = spare + (int64_t)t * NP + b0;
+    uint32_t n_eq = 0, n_ne = 0;
+    const uint32_t nchunks = (m + NT * V - 1) / (NT * V);
+    for (uint32_t c = 0; c < nchunks; ++c) {
+        const uint32_t c0 = (nchunks - 1 - c) * (NT * V);
+        uint2 e[V];
+        uint32_t rank[V];
+#pragma unroll
+        for (int u = 0; u < V; ++u) {
+            const uint32_t pos = c0 + wave * (64 * V) + u * 64 + lane;
+            e[u] = io[pos < m ? pos : m - 1];
+        }
+        uint32_t w_eq = 0, w_ne = 0;
+#pragma unroll
+        for (int u = 0; u < V; ++u) {
+            const uint32_t pos = c0 + wave * (64 * V) + u * 64 + lane;
+            const bool eq = pos < m && e[u].x == heavy, ne = pos < m && e[u].x != heavy;
+            const unsigned long long beq = __ballot(eq), bne = __ballot(ne);
+            rank[u] = eq ? w_eq + __popcll(beq & lanes_below(lane))
+                         : w_ne + __popcll(bne & lanes_below(lane));
+            w_eq += __popcll(beq);
+            w_ne += __popcll(bne);
+        }
+        if (lane == 0) {
+            s_w[0][wave] = w_eq;
+            s_w[1][wave] = w_ne;
+        }
+        __syncthreads();        // every wavefront has its part of the chunk in registers
+        uint32_t off_eq = n_eq, off_ne = n_ne;
+        for (int w = 0; w < NW; ++w) {
+            if (w < wave) {
+                off_eq += s_w[0][w];
+                off_ne += s_w[1][w];
+            }
+            n_eq += s_w[0][w];
+            n_ne += s_w[1][w];
+        }
+#pragma unroll
+        for (int u = 0; u < V; ++u) {
+            const uint32_t pos = c0 + wave * (64 * V) + u * 64 + lane;
+            if (pos < m) {
+                const uint32_t k = (e[u].x == heavy ? off_eq : off_ne) + rank[u];
+                if (e[u].x == heavy) io[m - 1 - k] = e[u];
+                else if (k < (uint32_t)CAP) put(k, e[u]);
+                else park[k - CAP] = e[u];
+            }
+        }
+        __syncthreads();
+    }
+    if (n_ne <= (uint32_t)CAP) {
+        lds_lsd_sort<NT, kBucketItems, PACKED>(s_keys, s_vals, s_cnt, s_dig, n_ne, rem_bits,
+                                               lds_shift);
+        for (uint32_t i = tid; i < n_ne; i += NT) io[i] = get(i);
+    } else {
+        // all others back in front of the heavy row's lookups, then sorted through
+        // global memory (what this workgroup wrote is read by all of it)
+        for (uint32_t i = tid; i < (uint32_t)CAP; i += NT) io[i] = get(i);
+        __threadfence_block();
+        __syncthreads();
+        copy_pairs<NT>(park, io + CAP, n_ne - CAP, tid);
+        __threadfence_block();
+        __syncthreads();
+        wg_lsd_global<NT>(io, park, n_ne, nb0, rem_bits, s_cnt, s_dig);
     }
     trace_end(ts, trace_t0);
 }
@@ -595,7 +888,7 @@ __global__ __launch_bounds__(kWG) void fixup_kernel(
 
 struct Layout {
     int NP, tiles, max_wgs;
-    size_t ent0, ent1, hist, trail_row, lead_state, part_lead,
+    size_t ent0, ent1, hist, bucket, trail_row, lead_state, part_lead,
         part_trail, total;
 };
 
@@ -618,6 +911,7 @@ Layout make_layout(int T, int Bcap, int L, int dim)
     y.ent0 = take(arr);
     y.ent1 = take(arr);
     y.hist = take((size_t)T * kRsMaxDig * y.tiles * sizeof(uint32_t));
+    y.bucket = take((size_t)T * kBsStride * sizeof(uint32_t));
     y.trail_row = take((size_t)T * y.max_wgs * sizeof(uint32_t));
     y.lead_state = take((size_t)T * y.max_wgs);
     y.part_lead = take((size_t)T * y.max_wgs * dim * sizeof(float));
@@ -663,11 +957,51 @@ void backward_first_buffers(int T, int Bcap, int L, int dim, void *ws, uint2 **e
 }
 
 // Which of the two pair buffers holds the sorted lists after stage 1.
-static int sorted_buffer(const Layout &y, int64_t rows)
+// How the lists of a table that is too large for the one-launch sort get sorted.
+struct RadixPlan {
+    int npass;          // global passes (histogram + scatter each)
+    int nb[4];          // digit bits of each
+    bool buckets;       // one global pass, then every bucket sorted by its own workgroup
+                        // (bucket_sort_kernel)
+    int rem_bits;       // ... row bits left to sort there
+    int val_bits;       // ... bits of a sample number
+    bool packed;        // ... the two fit one word
+    int sorted;         // buffer that holds the sorted lists
+};
+
+static RadixPlan plan_radix(const Layout &y, int T, int Bcap, int64_t rows)
 {
-    if (y.NP <= kLdsSortMax) return 0;
-    const int npass = (radix_bits_for(rows) + kRsMaxBits - 1) / kRsMaxBits;
-    return (npass - 1) & 1;      // pass 0 writes buffer 0, then they alternate
+    RadixPlan p = {};
+    const int sort_bits = radix_bits_for(rows);
+    p.npass = (sort_bits + kRsMaxBits - 1) / kRsMaxBits;
+    for (int i = 0; i < p.npass; ++i) p.nb[i] = pass_bits(sort_bits, p.npass, i);
+    // Three global passes or more: one pass instead, into buckets of 2048 to 4096
+    // lookups on average (at 8 tables x 81920 lookups, us per training step: 87.4 with 32
+    // buckets per table, 88.8 with 64, 90.8 with 128, 92.9 with 256; 95.1 with the three
+    // global passes), more where the tables are so few that this would leave compute
+    // units without a bucket.
+    if (p.npass >= 3) {
+        int nb0 = 4;
+        while (nb0 < 9 && (4096 << nb0) < y.NP) ++nb0;
+        while (nb0 < 9 && ((int64_t)T << nb0) < 256 && (64 << nb0) < y.NP) ++nb0;
+        int vb = 1;
+        while ((1 << vb) < Bcap) ++vb;
+        if (sort_bits - nb0 > 0) {
+            p.buckets = true;
+            p.rem_bits = sort_bits - nb0;
+            p.val_bits = vb;
+            p.packed = p.rem_bits + vb <= 31;
+            p.npass = 1;
+            p.nb[0] = nb0;
+        }
+    }
+    p.sorted = (p.npass - 1) & 1;      // pass 0 writes buffer 0, then they alternate
+    return p;
+}
+
+static int sorted_buffer(const Layout &y, int T, int Bcap, int64_t rows)
+{
+    return y.NP <= kLdsSortMax ? 0 : plan_radix(y, T, Bcap, rows).sorted;
 }
 
 int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bcap,
@@ -705,12 +1039,13 @@ int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bca
         }
 #undef SS_LDS_SORT
     } else {
-        const int sort_bits = radix_bits_for(tb->rows);
-        const int npass = (sort_bits + kRsMaxBits - 1) / kRsMaxBits;
+        const RadixPlan rp = plan_radix(y, T, Bcap, tb->rows);
+        uint32_t *bucket = reinterpret_cast<uint32_t *>(w8 + y.bucket);
         const dim3 grid(y.tiles, T);
+        const int sent = rp.buckets ? 1 : 0;
         int shift = 0;
-        for (int pass = 0; pass < npass; ++pass) {
-            const int nb = pass_bits(sort_bits, npass, pass);
+        for (int pass = 0; pass < rp.npass; ++pass) {
+            const int nb = rp.nb[pass];
             // the first pass reads the index tensor, leaves its (row, sample) pairs in
             // buffer 1 and scatters them into buffer 0; then the buffers alternate
             const int in = pass == 0 ? 1 : cur, out = pass == 0 ? 0 : 1 - cur;
@@ -718,22 +1053,37 @@ int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bca
                 ProfScope prof("rs_hist_kernel", s);
                 if (pass == 0)
                     launch(SS_BOTH(rs_hist_kernel, true), grid, dim3(kRsHistThreads), s, idx, Bcap, L,
-                           n_valid, tb->stale_bits, nullptr, ent[1], y.NP, shift, nb, hist,
+                           n_valid, tb->stale_bits, nullptr, ent[1], y.NP, shift, nb, sent, hist,
                            y.tiles);
                 else
                     launch(SS_BOTH(rs_hist_kernel, false), grid, dim3(kRsHistThreads), s, idx, Bcap, L,
-                           n_valid, nullptr, ent[in], nullptr, y.NP, shift, nb, hist,
-                           y.tiles);
+                           n_valid, nullptr, ent[in], nullptr, y.NP, shift, nb, 0, hist, y.tiles);
             }
-            ProfScope prof("rs_scatter_kernel", s);
-            if (record_after && pass == npass - 1) stop_event_for_next_launch(record_after);
-            launch(rs_scatter_kernel<NoTrace>, rs_scatter_kernel<TraceSlot>, grid, dim3(kRsThreads), s, ent[in], ent[out], y.NP,
-                   shift, nb, hist, y.tiles);
+            {
+                ProfScope prof("rs_scatter_kernel", s);
+                if (record_after && pass == rp.npass - 1 && !rp.buckets)
+                    stop_event_for_next_launch(record_after);
+                launch(rs_scatter_kernel<NoTrace>, rs_scatter_kernel<TraceSlot>, grid, dim3(kRsThreads), s, ent[in], ent[out], y.NP,
+                       shift, nb, sent, rp.buckets ? bucket : nullptr, hist, y.tiles);
+            }
+            if (rp.buckets) {
+                // buffer 0 in place; buffer 1 (the pairs as the first pass read them) is spare
+                ProfScope prof("bucket_sort_kernel", s);
+                if (record_after) stop_event_for_next_launch(record_after);
+                if (rp.packed)
+                    launch(SS_BOTH(bucket_sort_kernel, true), dim3(1u << nb, T),
+                           dim3(kBucketThreads), s, ent[0], ent[1], y.NP,
+                           (const uint32_t *)bucket, nb, rp.rem_bits, rp.val_bits);
+                else
+                    launch(SS_BOTH(bucket_sort_kernel, false), dim3(1u << nb, T),
+                           dim3(kBucketThreads), s, ent[0], ent[1], y.NP,
+                           (const uint32_t *)bucket, nb, rp.rem_bits, rp.val_bits);
+            }
             cur = out;
             shift += nb;
         }
     }
-    if (cur != sorted_buffer(y, tb->rows))
+    if (cur != sorted_buffer(y, T, Bcap, tb->rows))
         return fail(SS_ERR_HIP, "ss_embbag_backward_prepare: internal buffer mismatch");
     return check_launch("ss_embbag_backward_prepare");
 }
@@ -746,7 +1096,7 @@ int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float 
     char *w8 = static_cast<char *>(ws);
     uint2 *ent[2] = {reinterpret_cast<uint2 *>(w8 + y.ent0),
                      reinterpret_cast<uint2 *>(w8 + y.ent1)};
-    const int cur = sorted_buffer(y, tb->rows);
+    const int cur = sorted_buffer(y, T, Bcap, tb->rows);
 
     const int g = lanes_per_row(tb->dim);
     const int ng = kApplyWG / g;

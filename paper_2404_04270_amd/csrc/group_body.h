@@ -59,6 +59,78 @@ __host__ __device__ inline int pass_bits(int key_bits, int npass, int pass)
     return key_bits / npass + (pass < key_bits % npass ? 1 : 0);
 }
 
+// LSD radix sort, by a workgroup of NT threads, of m <= NT * ITEMS keys that lie in LDS,
+// on `bits` key bits from bit `shift` up; stable.  PACKED: s_keys alone is permuted,
+// else s_vals with it.  s_cnt: 2 * (NT / 64) * 64 words, s_dig: 64 words.  All threads
+// call; on return the sorted keys are visible to all of them.
+// Digits of at most 6 bits: one wavefront can then turn the per-wavefront counters into
+// offsets with shuffles alone, which leaves three barriers per pass.
+template <int NT, int ITEMS, bool PACKED>
+__device__ __forceinline__ void lds_lsd_sort(uint32_t *s_keys, uint32_t *s_vals,
+                                             uint32_t *s_cnt, uint32_t *s_dig, uint32_t m,
+                                             int bits, int shift)
+{
+    constexpr int NW = NT / 64;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t key[ITEMS], val[PACKED ? 1 : ITEMS], rank[ITEMS];
+    const int rounds = ((int)m + NT - 1) / NT;       // keys per thread, <= ITEMS
+    const int npass = (bits + 5) / 6;
+    for (int i = tid; i < 2 * NW * 64; i += NT) s_cnt[i] = 0;
+    __syncthreads();
+    for (int pass = 0; pass < npass; ++pass) {
+        uint32_t *cnt = s_cnt + (pass & 1) * (NW * 64);       // this pass
+        uint32_t *cnt_next = s_cnt + ((pass + 1) & 1) * (NW * 64);
+#pragma unroll
+        for (int r = 0; r < ITEMS; ++r)
+            if (r < rounds) {
+                const uint32_t pos = wave * rounds * 64 + r * 64 + lane;
+                key[r] = pos < m ? s_keys[pos] : kNoRow;
+                if (!PACKED) val[r] = pos < m ? s_vals[pos] : 0u;
+            }
+        const int nb = pass_bits(bits, npass, pass);
+        const uint32_t dmask = (1u << nb) - 1u;
+#pragma unroll
+        for (int r = 0; r < ITEMS; ++r)
+            if (r < rounds) {
+                const uint32_t d = (key[r] >> shift) & dmask;
+                rank[r] = wave_rank(cnt + wave * 64, d, nb, lane);
+            }
+        __syncthreads();
+        if (wave == 0) {
+            // lane d: offsets of the wavefronts for digit d, then digit starts
+            uint32_t run = 0;
+            if (lane <= (int)dmask)
+                for (int w = 0; w < NW; ++w) {
+                    const uint32_t c = cnt[w * 64 + lane];
+                    cnt[w * 64 + lane] = run;
+                    run += c;
+                }
+            uint32_t incl = run;
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t up = __shfl_up(incl, off);
+                if (lane >= off) incl += up;
+            }
+            s_dig[lane] = incl - run;
+        }
+        if (NW == 1 || wave != 0)
+            for (int i = NW == 1 ? tid : tid - 64; i < NW * 64; i += NW == 1 ? NT : NT - 64)
+                cnt_next[i] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < ITEMS; ++r)
+            if (r < rounds) {
+                const uint32_t d = (key[r] >> shift) & dmask;
+                const uint32_t p = s_dig[d] + cnt[wave * 64 + d] + rank[r];
+                if (p < m) {            // padding keys rank behind every real key
+                    s_keys[p] = key[r];
+                    if (!PACKED) s_vals[p] = val[r];
+                }
+            }
+        __syncthreads();
+        shift += nb;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // The apply stage needs equal rows to be neighbours, not ascending rows, so a
 // table is cut into P classes by the low bits of the row id and each class is
@@ -92,7 +164,7 @@ __device__ __forceinline__ void class_sort_body(
     const auto bt = as_global(bits ? bits[t] : nullptr);
     const uint32_t cmask = (1u << class_bits) - 1u;
 
-    uint32_t key[ITEMS], val[PACKED ? 1 : ITEMS], rank[ITEMS];
+    uint32_t key[ITEMS];
 #pragma unroll
     for (int r = 0; r < ITEMS; ++r) {
         const int pos = wave * ITEMS * 64 + r * 64 + lane;
@@ -141,66 +213,8 @@ __device__ __forceinline__ void class_sort_body(
         }
     __syncthreads();
 
-    // LSD radix sort of the m kept lookups on the row bits above the class bits.
-    // Digits of at most 6 bits: one wavefront can then turn the 16 x 64 counters
-    // into offsets with shuffles alone, which leaves three barriers per pass.
-    const int rounds = ((int)m + 1023) >> 10;       // keys per thread, <= ITEMS
-    const int rem_bits = key_bits - class_bits;
-    const int npass = (rem_bits + 5) / 6;
-    int shift = PACKED ? val_bits : class_bits;
-    for (int i = tid; i < 2 * NW * 64; i += 1024) s_cnt[i] = 0;
-    __syncthreads();
-    for (int pass = 0; pass < npass; ++pass) {
-        uint32_t *cnt = s_cnt + (pass & 1) * (NW * 64);       // this pass
-        uint32_t *cnt_next = s_cnt + ((pass + 1) & 1) * (NW * 64);
-#pragma unroll
-        for (int r = 0; r < ITEMS; ++r)
-            if (r < rounds) {
-                const uint32_t pos = wave * rounds * 64 + r * 64 + lane;
-                key[r] = pos < m ? s_keys[pos] : kNoRow;
-                if (!PACKED) val[r] = pos < m ? s_vals[pos] : 0u;
-            }
-        const int nb = pass_bits(rem_bits, npass, pass);
-        const uint32_t dmask = (1u << nb) - 1u;
-#pragma unroll
-        for (int r = 0; r < ITEMS; ++r)
-            if (r < rounds) {
-                const uint32_t d = (key[r] >> shift) & dmask;
-                rank[r] = wave_rank(cnt + wave * 64, d, nb, lane);
-            }
-        __syncthreads();
-        if (wave == 0) {
-            // lane d: offsets of the 16 wavefronts for digit d, then digit starts
-            uint32_t run = 0;
-            if (lane <= (int)dmask)
-                for (int w = 0; w < NW; ++w) {
-                    const uint32_t c = cnt[w * 64 + lane];
-                    cnt[w * 64 + lane] = run;
-                    run += c;
-                }
-            uint32_t incl = run;
-            for (int off = 1; off < 64; off <<= 1) {
-                const uint32_t up = __shfl_up(incl, off);
-                if (lane >= off) incl += up;
-            }
-            s_dig[lane] = incl - run;
-        } else {
-            for (int i = tid - 64; i < NW * 64; i += 1024 - 64) cnt_next[i] = 0;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int r = 0; r < ITEMS; ++r)
-            if (r < rounds) {
-                const uint32_t d = (key[r] >> shift) & dmask;
-                const uint32_t p = s_dig[d] + cnt[wave * 64 + d] + rank[r];
-                if (p < m) {            // sentinels rank behind every real key
-                    s_keys[p] = key[r];
-                    if (!PACKED) s_vals[p] = val[r];
-                }
-            }
-        __syncthreads();
-        shift += nb;
-    }
+    lds_lsd_sort<1024, ITEMS, PACKED>(s_keys, s_vals, s_cnt, s_dig, m, key_bits - class_bits,
+                                      PACKED ? val_bits : class_bits);
     uint2 *__restrict__ oe = out_ent + (int64_t)t * NP;
     const uint32_t vmask = PACKED ? (1u << val_bits) - 1u : 0u;
     for (uint32_t i = tid; i < m; i += 1024) {

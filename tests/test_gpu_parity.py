@@ -257,6 +257,15 @@ BACKWARD_CASES = [
     (11, 5000, 32, 500, 4, None, 0.1, 1.2),     # ... eight pinned, three spread
     (2, 100000, 8, 250000, 4, 249000, 0.05, 1.1),   # a million lookups per table: 489 sort
     (1, 2000000, 4, 1 << 20, 1, None, 0.0, 1.05),   # tiles; one lane per row, three passes
+    # one global pass, then every bucket sorted in LDS (more than a million rows, and the
+    # row bits left + the sample number fit one word): 32, 64 and 128 buckets per table
+    (3, 3000000, 16, 4096, 6, None, 0.1, 1.2),
+    (2, 1500000, 8, 30000, 2, 29000, 0.3, 1.05),
+    (2, 10000000, 16, 4096, 20, None, 0.02, 1.2),   # its hottest row alone has 15 000 lookups
+    (2, 4194303, 8, 20000, 1, None, 0.5, 1.1),      # the last row id is all ones below bit 22
+    (1, 100000000, 4, 512, 40, None, 0.0, 3.0),     # 27 row bits, 22 of them left to the
+                                                    # bucket sort; one row has four fifths
+                                                    # of the lookups
 ]
 
 
@@ -759,3 +768,47 @@ def test_free_running_pipelined_step_equals_call_by_call_step(B, dev, host_wait_
     assert stale > 0                       # the run did freeze rows
     print("free-running step, host_wait_us", host_wait_us, "issue threads", threads, c, flush=True)
     pipe.close()
+
+
+def test_backward_bucket_sort_with_oversized_buckets(B, dev):
+    """Tables of more than a million rows: after one global pass each bucket is sorted
+    by a workgroup in LDS.  A bucket that is too large for that has its most frequent
+    row taken out first; if the rest still does not fit, the workgroup sorts it through
+    global memory.  Table 0: every lookup hits one row; table 1: Zipf (its hottest row
+    stale); table 2: six rows that share their low bits, 6 800 lookups each (the rest
+    does not fit); table 3: as table 0 with that row stale (everything is a dropped
+    lookup); table 4: one row with 35 000 lookups and 6 000 lookups of 2 000 other rows
+    in the same bucket (they do not fit either: 2 048 do)."""
+    T, R, D, Bc, L = 5, 3000000, 8, 4096, 10
+    rng = np.random.default_rng(4242)
+    idx = zipf_idx(rng, T, Bc, L, R, 1.2)
+    idx[0] = 777
+    idx[2] = (5 + 64 * rng.integers(0, 6, (Bc, L))).astype(np.int32)
+    idx[3] = 123456
+    flat = idx[4].reshape(-1)
+    flat[:] = 9 + 64 * 7
+    where = rng.choice(flat.size, 6000, replace=False)
+    flat[where] = (9 + 64 * rng.integers(100, 2100, 6000)).astype(np.int32)
+    bits = random_bits(rng, T, R, 0.0)
+    bits[3][123456 >> 5] |= np.uint32(1 << (123456 & 31))
+    bits[1][0] |= np.uint32(1)
+    W = rand_tables(rng, T, R, D)
+    grad = rng.normal(0, 0.01, (T, Bc, D)).astype(np.float32)
+    ref = [w.copy() for w in W]
+    oracle.embbag_backward_update(ref, bits, idx, grad, 0.01, None)
+    tb = B.Tables(to_dev(W, dev), bits_to_dev(bits, dev))
+    ws = torch.empty(B.ss_backward_workspace_bytes(T, Bc, L, D), dtype=torch.uint8, device=dev)
+    ws.fill_(0xCD)
+    idx_d, grad_d = torch.from_numpy(idx).to(dev), torch.from_numpy(grad).to(dev)
+    B.ss_embbag_backward_update(tb, idx_d, None, grad_d, 0.01, ws)
+    got = [w.cpu().numpy() for w in tb.weights]
+    for t in range(T):
+        np.testing.assert_allclose(got[t], ref[t], rtol=RTOL, atol=ATOL)
+    assert np.array_equal(got[3], W[3])            # nothing moved in table 3
+    assert not np.array_equal(got[0][777], W[0][777])
+    # again on fresh tables: bit-identical (every sum has a fixed order)
+    tb2 = B.Tables(to_dev(W, dev), bits_to_dev(bits, dev))
+    ws.fill_(0x3C)
+    B.ss_embbag_backward_update(tb2, idx_d, None, grad_d, 0.01, ws)
+    for t in range(T):
+        assert torch.equal(tb2.weights[t], tb.weights[t])
