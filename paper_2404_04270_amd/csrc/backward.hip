@@ -3,19 +3,24 @@
 //
 // Three stages, all tables in every launch:
 //
-//  1. SORT the lookups of each table by row id (stable, so equal rows keep the
-//     order "ascending sample, then position in bag").  The lists hold
-//     (row, sample) pairs: the sample number is all the gradient gather needs.
+//  1. GROUP the lookups of each table by row id (the apply stage needs equal rows
+//     adjacent, not ascending; the order inside a group is the same from run to
+//     run).  The lists hold (row, sample) pairs: the sample number is all the
+//     gradient gather needs.
 //       - up to 16384 lookups per table: one launch; the table is cut into
 //         classes by the low bits of the row id and a 1024-thread workgroup per
 //         class runs an LSD radix sort on the remaining bits with keys and
-//         sample numbers in registers and the exchange buffers in LDS (the apply
-//         stage needs equal rows adjacent, not ascending);
-//       - more: a global LSD radix sort, up to 10 bits per pass, two launches
-//         per pass: per-tile digit histograms, then a stable scatter whose
-//         workgroups each derive their own offsets from the histograms.  The
-//         first histogram launch also writes the (row, sample) pairs, so every
-//         scatter reads pairs and the bitmap is probed once per lookup.
+//         sample numbers in registers and the exchange buffers in LDS;
+//       - more: one pass of a global LSD radix sort on the low bits (two
+//         launches: per-tile digit histograms, then a stable scatter whose
+//         workgroups each derive their own offsets from the histograms; the
+//         histogram launch also writes the (row, sample) pairs, so the scatter
+//         reads pairs and the bitmap is probed once per lookup), which leaves
+//         the table in buckets; then one launch in which a 256-thread workgroup
+//         per bucket sorts it by the remaining bits in LDS, in place;
+//       - row ids of 10 bits or fewer with that many lookups: the one global
+//         pass is all it takes (further passes of the same kind exist for row
+//         ids whose remaining bits would not leave a bucket anything to sort).
 //     A lookup whose row is stale is given the sentinel key when the keys are
 //     first read, so it sorts behind all real lookups and costs nothing later.
 //     Ranking inside a wavefront uses ballots: the lanes that hold the same
@@ -79,39 +84,26 @@ __global__ __launch_bounds__(1024) void class_sort_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// Stage 1b: global LSD radix sort, one pass = histogram, scan, scatter.
-// Tile = 2048 keys; hist layout [table][tile][digit].
+// Stage 1b: one global radix pass on the low nb bits of the row id = histogram, then
+// scatter.  Tile = 2048 keys; hist layout [table][tile][digit].
 // ---------------------------------------------------------------------------
-// What the histogram kernel reads at position `pos` of a table: in the first pass
-// the index tensor itself (the sample number is the position divided by the bag
-// length), afterwards the row id of the pair the previous pass left there.
-// Digit of a key in one pass.  sent (0 or 1, first pass only): the sentinel key gets a
-// digit of its own behind all others, so that every other bucket holds real rows only.
-__device__ __forceinline__ uint32_t rs_digit(uint32_t key, int shift, uint32_t dmask, int sent)
+// Digit of a key.  sent (0 or 1): the sentinel key gets a digit of its own behind all
+// others, so that every other bucket holds real rows only.
+__device__ __forceinline__ uint32_t rs_digit(uint32_t key, uint32_t dmask, int sent)
 {
-    return sent && key == kNoRow ? dmask + 1u : (key >> shift) & dmask;
+    return sent && key == kNoRow ? dmask + 1u : key & dmask;
 }
 
-template <bool FIRST>
-__device__ __forceinline__ void rs_load(const int32_t *__restrict__ ip, int L, int n,
-                                        const uint2 *__restrict__ in_ent, int pos,
-                                        uint32_t &key, uint32_t &val)
-{
-    if (FIRST) {
-        key = pos < n ? (uint32_t)ip[pos] : kNoRow;
-        val = pos < n ? (uint32_t)(L == 1 ? pos : pos / L) : 0u;
-    } else {
-        key = in_ent[pos].x;
-        val = 0u;
-    }
-}
-
-template <bool FIRST, typename TS>
+// Reads the index tensor, turns it into (row, sample) pairs with the sentinel for stale
+// rows and padding (the sample number is the position divided by the bag length), leaves
+// them for the scatter, which then needs neither the bitmap probes nor the division, and
+// counts the digits of its tile.
+template <typename TS>
 __global__ __launch_bounds__(kRsHistThreads) void rs_hist_kernel(
     const int32_t *__restrict__ idx, int Bcap, int L,
     const int32_t *__restrict__ n_valid, const uint32_t *const *__restrict__ bits,
-    const uint2 *__restrict__ in_ent, uint2 *__restrict__ first_ent, int NP, int shift,
-    int nb, int sent, uint32_t *__restrict__ hist, int tiles, TS ts)
+    uint2 *__restrict__ pairs, int NP, int nb, int sent, uint32_t *__restrict__ hist,
+    int tiles, TS ts)
 {
     __shared__ uint32_t s_hist[kRsMaxDig];
     const unsigned long long trace_t0 = trace_begin<TS>();
@@ -120,27 +112,24 @@ __global__ __launch_bounds__(kRsHistThreads) void rs_hist_kernel(
     const int ndig = (1 << nb) + sent;
     const uint32_t dmask = (1u << nb) - 1;
     const int32_t *__restrict__ ip = idx + (int64_t)t * Bcap * L;
-    const auto bt = as_global((FIRST && bits) ? bits[t] : nullptr);
-    const uint2 *__restrict__ ein = FIRST ? nullptr : in_ent + (int64_t)t * NP;
+    const auto bt = as_global(bits ? bits[t] : nullptr);
     for (int i = tid; i < ndig; i += kRsHistThreads) s_hist[i] = 0;
     __syncthreads();
     uint32_t key[kRsHistItems], val[kRsHistItems];
 #pragma unroll
-    for (int r = 0; r < kRsHistItems; ++r)
-        rs_load<FIRST>(ip, L, n, ein, tile * kPad + r * kRsHistThreads + tid, key[r], val[r]);
-    if (FIRST) {
-        // The first pass turns the index tensor into (row, sample) pairs, with the
-        // sentinel for stale rows and padding, and leaves them for its scatter, which
-        // then needs neither the bitmap probes nor the division by the bag length.
-        drop_stale(bt, key);
-        uint2 *__restrict__ eo = first_ent + (int64_t)t * NP;
-#pragma unroll
-        for (int r = 0; r < kRsHistItems; ++r)
-            eo[tile * kPad + r * kRsHistThreads + tid] = make_uint2(key[r], val[r]);
+    for (int r = 0; r < kRsHistItems; ++r) {
+        const int pos = tile * kPad + r * kRsHistThreads + tid;
+        key[r] = pos < n ? (uint32_t)ip[pos] : kNoRow;
+        val[r] = pos < n ? (uint32_t)(L == 1 ? pos : pos / L) : 0u;
     }
+    drop_stale(bt, key);
+    uint2 *__restrict__ eo = pairs + (int64_t)t * NP;
 #pragma unroll
     for (int r = 0; r < kRsHistItems; ++r)
-        atomicAdd(&s_hist[rs_digit(key[r], shift, dmask, sent)], 1u);
+        eo[tile * kPad + r * kRsHistThreads + tid] = make_uint2(key[r], val[r]);
+#pragma unroll
+    for (int r = 0; r < kRsHistItems; ++r)
+        atomicAdd(&s_hist[rs_digit(key[r], dmask, sent)], 1u);
     __syncthreads();
     for (int i = tid; i < ndig; i += kRsHistThreads)
         hist[((int64_t)t * tiles + tile) * kRsMaxDig + i] = s_hist[i];
@@ -152,9 +141,8 @@ __global__ __launch_bounds__(kRsHistThreads) void rs_hist_kernel(
 // the whole table) + (keys with this digit in earlier tiles).
 template <typename TS>
 __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
-    const uint2 *__restrict__ in_ent, uint2 *__restrict__ out_ent, int NP, int shift,
-    int nb, int sent, uint32_t *__restrict__ bucket_out, const uint32_t *__restrict__ hist,
-    int tiles, TS ts)
+    const uint2 *__restrict__ in_ent, uint2 *__restrict__ out_ent, int NP, int nb, int sent,
+    uint32_t *__restrict__ bucket_out, const uint32_t *__restrict__ hist, int tiles, TS ts)
 {
     constexpr int NW = kRsThreads / 64;
     const unsigned long long trace_t0 = trace_begin<TS>();
@@ -247,7 +235,7 @@ __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
 
 #pragma unroll
     for (int r = 0; r < kRsItems; ++r) {
-        const uint32_t d = rs_digit(key[r], shift, dmask, sent);
+        const uint32_t d = rs_digit(key[r], dmask, sent);
         rank[r] = wave_rank(s_cnt + wave * ndig, d, nbits, lane);
     }
     __syncthreads();
@@ -268,7 +256,7 @@ __global__ __launch_bounds__(kRsThreads) void rs_scatter_kernel(
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < kRsItems; ++r) {
-        const uint32_t d = rs_digit(key[r], shift, dmask, sent);
+        const uint32_t d = rs_digit(key[r], dmask, sent);
         const int64_t p = (int64_t)t * NP + s_cnt[wave * ndig + d] + rank[r];
         out_ent[p] = make_uint2(key[r], val[r]);      // one 8-byte store, not two of 4
     }
@@ -957,53 +945,41 @@ void backward_first_buffers(int T, int Bcap, int L, int dim, void *ws, uint2 **e
 }
 
 // Which of the two pair buffers holds the sorted lists after stage 1.
-// How the lists of a table that is too large for the one-launch sort get sorted.
+// How the lists of a table that is too large for the one-launch sort get grouped: one
+// global pass on the low nb0 bits of the row id, and, if the row id has more bits than
+// that, a sort of every bucket by the remaining bits (bucket_sort_kernel).
 struct RadixPlan {
-    int npass;          // global passes (histogram + scatter each)
-    int nb[4];          // digit bits of each
-    bool buckets;       // one global pass, then every bucket sorted by its own workgroup
-                        // (bucket_sort_kernel)
-    int rem_bits;       // ... row bits left to sort there
-    int val_bits;       // ... bits of a sample number
-    bool packed;        // ... the two fit one word
-    int sorted;         // buffer that holds the sorted lists
+    int nb0;            // digit bits of the global pass (at most kRsMaxBits; 9 with buckets)
+    bool buckets;
+    int rem_bits;       // row bits left to sort in the buckets
+    int val_bits;       // bits of a sample number
+    bool packed;        // the two fit one word
 };
 
 static RadixPlan plan_radix(const Layout &y, int T, int Bcap, int64_t rows)
 {
     RadixPlan p = {};
     const int sort_bits = radix_bits_for(rows);
-    p.npass = (sort_bits + kRsMaxBits - 1) / kRsMaxBits;
-    for (int i = 0; i < p.npass; ++i) p.nb[i] = pass_bits(sort_bits, p.npass, i);
-    // Two global passes or more: one pass instead, into buckets of 2048 to 4096 lookups
-    // on average (at 8 tables x 81920 lookups, us per training step: 87.4 with 32
-    // buckets per table, 88.8 with 64, 90.8 with 128, 92.9 with 256; 95.1 with the three
-    // global passes; two passes replaced: 52.6 instead of 54.0 at 8 tables x 32768
-    // lookups of 500 000 rows, 20.6 instead of 24.1 at one table x 65536 of 800 000),
-    // more buckets where the tables are so few that this would leave compute units
-    // without one.
-    if (p.npass >= 2) {
-        int nb0 = 4;
-        while (nb0 < 9 && (4096 << nb0) < y.NP) ++nb0;
-        while (nb0 < 9 && ((int64_t)T << nb0) < 256 && (64 << nb0) < y.NP) ++nb0;
-        int vb = 1;
-        while ((1 << vb) < Bcap) ++vb;
-        if (sort_bits - nb0 > 0) {
-            p.buckets = true;
-            p.rem_bits = sort_bits - nb0;
-            p.val_bits = vb;
-            p.packed = p.rem_bits + vb <= 31;
-            p.npass = 1;
-            p.nb[0] = nb0;
-        }
+    if (sort_bits <= kRsMaxBits) {
+        p.nb0 = sort_bits;
+        return p;
     }
-    p.sorted = (p.npass - 1) & 1;      // pass 0 writes buffer 0, then they alternate
+    // Buckets of 2048 to 4096 lookups on average (at 8 tables x 81920 lookups, us per
+    // training step: 87.4 with 32 buckets per table, 88.8 with 64, 90.8 with 128, 92.9
+    // with 256; 95.1 with three global passes instead of the buckets.  In place of two
+    // global passes: 52.6 instead of 54.0 at 8 tables x 32768 lookups of 500 000 rows,
+    // 20.6 instead of 24.1 at one table x 65536 of 800 000), more buckets where the
+    // tables are so few that this would leave compute units without one.
+    int nb0 = 4;
+    while (nb0 < 9 && (4096 << nb0) < y.NP) ++nb0;
+    while (nb0 < 9 && ((int64_t)T << nb0) < 256 && (64 << nb0) < y.NP) ++nb0;
+    p.nb0 = nb0;
+    p.buckets = true;
+    p.rem_bits = sort_bits - nb0;
+    p.val_bits = 1;
+    while ((1 << p.val_bits) < Bcap) ++p.val_bits;
+    p.packed = p.rem_bits + p.val_bits <= 31;
     return p;
-}
-
-static int sorted_buffer(const Layout &y, int T, int Bcap, int64_t rows)
-{
-    return y.NP <= kLdsSortMax ? 0 : plan_radix(y, T, Bcap, rows).sorted;
 }
 
 int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bcap,
@@ -1017,7 +993,6 @@ int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bca
                      reinterpret_cast<uint2 *>(w8 + y.ent1)};
     uint32_t *hist = reinterpret_cast<uint32_t *>(w8 + y.hist);
     const int key_bits = key_bits_for(tb->rows);
-    int cur = 0;   // buffer that holds the sorted lists
 
     if (y.NP <= kLdsSortMax) {
         const ClassSortPlan cp = plan_class_sort(y.NP, Bcap, key_bits);
@@ -1041,52 +1016,38 @@ int32_t launch_backward_prepare(const ss_tables *tb, const int32_t *idx, int Bca
         }
 #undef SS_LDS_SORT
     } else {
+        // the (row, sample) pairs go to buffer 1 and are scattered into buffer 0, where
+        // the buckets are then sorted in place (buffer 1 is their spare)
         const RadixPlan rp = plan_radix(y, T, Bcap, tb->rows);
         uint32_t *bucket = reinterpret_cast<uint32_t *>(w8 + y.bucket);
         const dim3 grid(y.tiles, T);
         const int sent = rp.buckets ? 1 : 0;
-        int shift = 0;
-        for (int pass = 0; pass < rp.npass; ++pass) {
-            const int nb = rp.nb[pass];
-            // the first pass reads the index tensor, leaves its (row, sample) pairs in
-            // buffer 1 and scatters them into buffer 0; then the buffers alternate
-            const int in = pass == 0 ? 1 : cur, out = pass == 0 ? 0 : 1 - cur;
-            {
-                ProfScope prof("rs_hist_kernel", s);
-                if (pass == 0)
-                    launch(SS_BOTH(rs_hist_kernel, true), grid, dim3(kRsHistThreads), s, idx, Bcap, L,
-                           n_valid, tb->stale_bits, nullptr, ent[1], y.NP, shift, nb, sent, hist,
-                           y.tiles);
-                else
-                    launch(SS_BOTH(rs_hist_kernel, false), grid, dim3(kRsHistThreads), s, idx, Bcap, L,
-                           n_valid, nullptr, ent[in], nullptr, y.NP, shift, nb, 0, hist, y.tiles);
-            }
-            {
-                ProfScope prof("rs_scatter_kernel", s);
-                if (record_after && pass == rp.npass - 1 && !rp.buckets)
-                    stop_event_for_next_launch(record_after);
-                launch(rs_scatter_kernel<NoTrace>, rs_scatter_kernel<TraceSlot>, grid, dim3(kRsThreads), s, ent[in], ent[out], y.NP,
-                       shift, nb, sent, rp.buckets ? bucket : nullptr, hist, y.tiles);
-            }
-            if (rp.buckets) {
-                // buffer 0 in place; buffer 1 (the pairs as the first pass read them) is spare
-                ProfScope prof("bucket_sort_kernel", s);
-                if (record_after) stop_event_for_next_launch(record_after);
-                if (rp.packed)
-                    launch(SS_BOTH(bucket_sort_kernel, true), dim3(1u << nb, T),
-                           dim3(kBucketThreads), s, ent[0], ent[1], y.NP,
-                           (const uint32_t *)bucket, nb, rp.rem_bits, rp.val_bits);
-                else
-                    launch(SS_BOTH(bucket_sort_kernel, false), dim3(1u << nb, T),
-                           dim3(kBucketThreads), s, ent[0], ent[1], y.NP,
-                           (const uint32_t *)bucket, nb, rp.rem_bits, rp.val_bits);
-            }
-            cur = out;
-            shift += nb;
+        {
+            ProfScope prof("rs_hist_kernel", s);
+            launch(rs_hist_kernel<NoTrace>, rs_hist_kernel<TraceSlot>, grid, dim3(kRsHistThreads),
+                   s, idx, Bcap, L, n_valid, tb->stale_bits, ent[1], y.NP, rp.nb0, sent, hist,
+                   y.tiles);
+        }
+        {
+            ProfScope prof("rs_scatter_kernel", s);
+            if (record_after && !rp.buckets) stop_event_for_next_launch(record_after);
+            launch(rs_scatter_kernel<NoTrace>, rs_scatter_kernel<TraceSlot>, grid,
+                   dim3(kRsThreads), s, (const uint2 *)ent[1], ent[0], y.NP, rp.nb0, sent,
+                   rp.buckets ? bucket : nullptr, (const uint32_t *)hist, y.tiles);
+        }
+        if (rp.buckets) {
+            ProfScope prof("bucket_sort_kernel", s);
+            if (record_after) stop_event_for_next_launch(record_after);
+            if (rp.packed)
+                launch(SS_BOTH(bucket_sort_kernel, true), dim3(1u << rp.nb0, T),
+                       dim3(kBucketThreads), s, ent[0], ent[1], y.NP,
+                       (const uint32_t *)bucket, rp.nb0, rp.rem_bits, rp.val_bits);
+            else
+                launch(SS_BOTH(bucket_sort_kernel, false), dim3(1u << rp.nb0, T),
+                       dim3(kBucketThreads), s, ent[0], ent[1], y.NP,
+                       (const uint32_t *)bucket, rp.nb0, rp.rem_bits, rp.val_bits);
         }
     }
-    if (cur != sorted_buffer(y, T, Bcap, tb->rows))
-        return fail(SS_ERR_HIP, "ss_embbag_backward_prepare: internal buffer mismatch");
     return check_launch("ss_embbag_backward_prepare");
 }
 
@@ -1096,9 +1057,7 @@ int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float 
     const int T = tb->num_tables, D4 = tb->dim / 4;
     const Layout y = make_layout(T, Bcap, L, tb->dim);
     char *w8 = static_cast<char *>(ws);
-    uint2 *ent[2] = {reinterpret_cast<uint2 *>(w8 + y.ent0),
-                     reinterpret_cast<uint2 *>(w8 + y.ent1)};
-    const int cur = sorted_buffer(y, T, Bcap, tb->rows);
+    const uint2 *ent = reinterpret_cast<const uint2 *>(w8 + y.ent0);      // the grouped lists
 
     const int g = lanes_per_row(tb->dim);
     const int ng = kApplyWG / g;
@@ -1115,7 +1074,7 @@ int32_t launch_backward_apply(const ss_tables *tb, int Bcap, int L, const float 
     const int pinned = L > 1 ? (T / 8) * 8 * wgs : 0;
 #define SS_APPLY(S_, F_)                                                          \
     SS_DISPATCH_G(g, launch(SS_BOTH(apply_kernel, G, S_, F_), dim3((unsigned)blocks),    \
-                            dim3(kApplyWG), s, tb->weights, ent[cur], y.NP, grad, \
+                            dim3(kApplyWG), s, tb->weights, ent, y.NP, grad,    \
                             Bcap, D4, lr, wgs, pinned, L == 1, trail_row,         \
                             lead_state, part_lead, part_trail))
     {
