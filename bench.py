@@ -171,7 +171,7 @@ class Measurement:
         hot_d = [torch.from_numpy(h).to(dev) for h in self.hot]
         self.pipelined = bool(args.pipeline)
         self.index_streams = args.index_streams if args.index_streams > 0 else \
-            PipelinedStep.auto_streams(Bn, L, T)
+            PipelinedStep.auto_streams(Bn, L, T, cfg.dim)
         if self.pipelined:
             self.step = PipelinedStep(
                 weights, hot_d, Bn, L, cfg.lr, self.thr, cfg.snapshot_every,

@@ -513,9 +513,12 @@ int32_t ss_stream_wait_event(void *stream, void *event);
  * calling thread polling for it for up to this many microseconds instead of
  * giving the training stream a wait command (which costs the stream time between
  * two kernels); the thread then stays at most a ring of batches ahead of the GPU.
- * 0: never, ss_step_forward only ever enqueues.  ss_step_plan_for fills in what
- * the caller left at 0 (every, index_streams) or -1 (issue_threads, host_wait_us)
- * with the measured choices for the shape, and sets num_sets.
+ * 0: never, ss_step_forward only ever enqueues.  dim: floats per row, an input
+ * of ss_step_plan_for only (0: unknown; with it the choice of index_streams can
+ * weigh the training kernels of a batch against its index work).
+ * ss_step_plan_for fills in what the caller left at 0 (every, index_streams) or
+ * -1 (issue_threads, host_wait_us) with the measured choices for the shape, and
+ * sets num_sets.
  */
 typedef struct {
     int32_t every;
@@ -523,6 +526,7 @@ typedef struct {
     int32_t issue_threads;
     int32_t num_sets;
     int32_t host_wait_us;
+    int32_t dim;
 } ss_step_plan;
 
 /* One buffer set of the ring: the outputs of ss_filter_batch for the batch that

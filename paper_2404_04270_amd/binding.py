@@ -755,7 +755,7 @@ class IssueQueue:
 class StepPlan(C.Structure):
     _fields_ = [("every", C.c_int32), ("index_streams", C.c_int32),
                 ("issue_threads", C.c_int32), ("num_sets", C.c_int32),
-                ("host_wait_us", C.c_int32)]
+                ("host_wait_us", C.c_int32), ("dim", C.c_int32)]
 
 
 class StepSet(C.Structure):
@@ -782,9 +782,11 @@ class StepTraceOps(C.Structure):
 
 
 def ss_step_plan_for(T: int, B: int, L: int, every: int = 0, index_streams: int = 0,
-                     issue_threads: int = -1, host_wait_us: int = -1) -> StepPlan:
-    """The plan for a shape; 0 / 0 / -1 / -1 leave the choice to the library."""
-    plan = StepPlan(int(every), int(index_streams), int(issue_threads), 0, int(host_wait_us))
+                     issue_threads: int = -1, host_wait_us: int = -1, dim: int = 0) -> StepPlan:
+    """The plan for a shape; 0 / 0 / -1 / -1 leave the choice to the library (dim = 0:
+    the row length is not known)."""
+    plan = StepPlan(int(every), int(index_streams), int(issue_threads), 0, int(host_wait_us),
+                    int(dim))
     _check(_lib.ss_step_plan_for(C.c_int32(T), C.c_int32(B), C.c_int32(L), C.byref(plan)))
     return plan
 

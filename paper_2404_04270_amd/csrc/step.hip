@@ -361,14 +361,21 @@ int auto_every(int T, int B, int L, int n_side)
 }
 
 // Index streams: one while a table has at most 16384 lookups per batch; beyond that
-// the grouping is a chain of six small launches per batch that lasts about as long
-// as the training kernels, and two chains side by side keep the index work ahead;
-// three when those launches are tiny (fewer than 128 workgroups over all tables).
-int auto_streams(int T, int B, int L)
+// the grouping is a chain of three launches per batch behind the two of the classifier
+// that lasts 50-70 us beside the training kernels, longer than those do at most shapes,
+// and two chains side by side keep the index work ahead (52.7 against 63.7 us per step
+// at 8 tables x 32768 lookups of 64 floats, 38.9 against 52.8 at 2 x 80000 x 64); three
+// when those launches are tiny (fewer than 128 workgroups over all tables: 24.4 / 28.4 /
+// 50.1 us with 3 / 2 / 1 at one table x 65536).  Where the training kernels of a batch
+// move so much that they outlast the chain (more than 256 MB of looked-up rows: 335 MB
+// and 85 us at 8 tables x 81920 lookups of 128 floats), one stream is enough and a second
+// only puts more index kernels beside them (84.7 against 87.4 us per step).
+int auto_streams(int T, int B, int L, int dim)
 {
     const int64_t lookups = (int64_t)B * L;
     if (lookups <= 16384) return 1;
-    return T * ((lookups + 2047) / 2048) < 128 ? 3 : 2;
+    if (T * ((lookups + 2047) / 2048) < 128) return 3;
+    return (int64_t)T * lookups * dim * 4 > (256LL << 20) ? 1 : 2;
 }
 
 // Issue threads: where a batch is a string of launches at their latency floor, so
@@ -609,7 +616,8 @@ int32_t ss_step_plan_for(int32_t T, int32_t B, int32_t L, ss_step_plan *plan)
     if (!plan) return fail(SS_ERR_INVALID_ARG, "%s: plan is NULL", who);
     if (T < 1 || T > 65535 || B < 1 || L < 1 || (int64_t)B * L >= (1LL << 31))
         return fail(SS_ERR_INVALID_ARG, "%s: T = %d, B = %d, L = %d", who, T, B, L);
-    if (plan->index_streams <= 0) plan->index_streams = auto_streams(T, B, L);
+    if (plan->dim < 0) return fail(SS_ERR_INVALID_ARG, "%s: dim = %d", who, plan->dim);
+    if (plan->index_streams <= 0) plan->index_streams = auto_streams(T, B, L, plan->dim);
     if (plan->index_streams > 16)
         return fail(SS_ERR_INVALID_ARG, "%s: index_streams = %d (at most 16)", who,
                     plan->index_streams);

@@ -176,9 +176,9 @@ class PipelinedStep:
         return B.ss_step_plan_for(T, batch, bag, 0, n_side, 0).every
 
     @staticmethod
-    def auto_streams(batch: int, bag: int, num_tables: int = 8) -> int:
+    def auto_streams(batch: int, bag: int, num_tables: int = 8, dim: int = 0) -> int:
         """Index streams, as the library chooses them for the shape."""
-        return B.ss_step_plan_for(num_tables, batch, bag, 1, 0, 0).index_streams
+        return B.ss_step_plan_for(num_tables, batch, bag, 1, 0, 0, dim=dim).index_streams
 
     def __init__(self, weights: Sequence[torch.Tensor],
                  hot_ids: Sequence[torch.Tensor], batch: int, bag: int,
@@ -201,7 +201,8 @@ class PipelinedStep:
         self.lr, self.threshold, self.K = float(lr), float(threshold), int(snapshot_every)
         self.alpha = T * bag if alpha is None else int(alpha)
         self.pooled = torch.zeros(T, batch, D, dtype=torch.float32, device=dev)
-        streams = B.ss_step_plan_for(T, batch, bag, 1, int(index_streams or 0), 0).index_streams
+        streams = B.ss_step_plan_for(T, batch, bag, 1, int(index_streams or 0), 0,
+                                     dim=D).index_streams
         if issue_thread is None:
             threads = -1
         elif issue_thread is True:
@@ -209,7 +210,7 @@ class PipelinedStep:
         else:
             threads = min(int(issue_thread), streams)
         plan = B.ss_step_plan_for(T, batch, bag, int(every or 0), streams, threads,
-                                  -1 if host_wait_us is None else int(host_wait_us))
+                                  -1 if host_wait_us is None else int(host_wait_us), dim=D)
         self.plan = plan
         self.every = plan.every
         self.sets = [self._Set(T, batch, bag, D, dev) for _ in range(plan.num_sets)]

@@ -296,6 +296,9 @@ def test_step_plan_picks_streams_threads_and_event_spacing_for_the_shape():
     assert P.auto_streams(8192, 1) == 1 and P.auto_streams(16384, 1) == 1
     assert P.auto_streams(65536, 1, 1) == 3 and P.auto_streams(4096, 20, 8) == 2
     assert P.auto_streams(65536, 1, 8) == 2 and P.auto_streams(20000, 1, 1) == 3
+    # ... and one again where the training kernels of a batch outlast its index work
+    assert P.auto_streams(4096, 20, 8, 128) == 1 and P.auto_streams(4096, 20, 8, 64) == 2
+    assert P.auto_streams(32768, 1, 8, 64) == 2 and P.auto_streams(65536, 1, 1, 1024) == 3
     assert plan(26, 2048, 1).issue_threads == 1 and plan(1, 65536, 1).issue_threads == 3
     assert plan(26, 8192, 1).issue_threads == 0 and plan(8, 4096, 20).issue_threads == 0
     assert P.auto_every(26, 8192, 1, 1) == 8         # 3.4 MB of lists per batch

@@ -242,9 +242,10 @@ def test_config5_full_shape_sampled_with_skips_and_detect(B, dev):
 
 @pytest.mark.parametrize("config", [4, 5])
 def test_pipelined_step_equals_call_by_call_step_at_full_shape(B, dev, config):
-    """The benchmark times PipelinedStep with its automatic settings (several index
-    streams at these shapes, the issue thread at config 5).  Every sum in the library
-    has a fixed order, so that step must leave bit for bit what the call-by-call
+    """The benchmark times PipelinedStep with its automatic settings (the global pass
+    and bucket sort at these shapes; several index streams and issue threads at config
+    5).  Every sum in the library has a fixed order, so that step must leave bit for bit
+    what the call-by-call
     step leaves, whose calls the tests above hold against the oracle at this shape:
     a property that can be checked at any size, on the device.  Threshold +inf and a
     short period make the second boundary freeze every hot row, so the runs cover
@@ -261,7 +262,8 @@ def test_pipelined_step_equals_call_by_call_step_at_full_shape(B, dev, config):
     wb = [x.clone() for x in wa]
     serial = EmbeddingStep(wa, hot, Bn, L, cfg.lr, math.inf, period)
     pipe = PipelinedStep(wb, hot, Bn, L, cfg.lr, math.inf, period)
-    assert len(pipe.sides) >= 2                       # what bench.py runs at these shapes
+    # what bench.py runs at these shapes: one index stream at config 4, three at config 5
+    assert len(pipe.sides) == PipelinedStep.auto_streams(Bn, L, T, cfg.dim) == (1 if config == 4 else 3)
     torch.cuda.synchronize()
     ahead = skipped = detects = 0
     for it in range(n_iters):
