@@ -1,6 +1,8 @@
 // Grouping of one table's lookups by row, for tables of up to 16384 lookups
 // (stage 1 of the backward pass), as a device function so that it can run as a
-// kernel of its own or as one role of the fused forward + grouping launch.
+// kernel of its own or as one role of the fused forward + grouping launch; and the
+// pieces it shares with the grouping of larger tables: ranking inside a wavefront,
+// the sentinel for stale rows, the LDS radix sort of one workgroup.
 #pragma once
 #include "ss_common.h"
 
